@@ -1,0 +1,278 @@
+"""Pins for the oracle's network pieces, cache rule, solver and VC.  CPU only.
+Each piece is checked against a library routine, a closed form or an invariant
+of its definition, never against the oracle's own formula."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import dit, sampler, quant
+from synthetic import dit_inputs as I
+
+TINY = I.ModelDesc(depth=2, hidden=32, heads=2, mlp_dim=64, patch=2, latent_c=4, latent_h=8, latent_w=8,
+                   num_classes=10)
+
+
+def _tiny_setup(seed=0, std=0.2):
+    w = I.make_weights(TINY, seed, std=std)
+    lat = I.make_latents(3, TINY, seed + 1)
+    lab = I.make_labels(3, TINY, seed + 2)
+    return w, lat, lab
+
+
+# ------------------------------------------------------- library routines
+def test_layer_norm_vs_torch():
+    x = np.random.default_rng(0).standard_normal((2, 5, 32)) * 3 + 1
+    want = F.layer_norm(torch.from_numpy(x), (32,), eps=1e-6).numpy()
+    assert np.allclose(dit.layer_norm(x), want, rtol=1e-12, atol=1e-12)
+    out = dit.layer_norm(x)
+    assert np.allclose(out.mean(-1), 0, atol=1e-12) and np.allclose(out.var(-1), 1, atol=1e-5)
+
+
+def test_gelu_silu_vs_torch():
+    x = np.linspace(-6, 6, 1001)
+    assert np.allclose(dit.gelu_tanh(x), F.gelu(torch.from_numpy(x), approximate="tanh").numpy(), atol=1e-14)
+    assert np.allclose(dit.silu(x), F.silu(torch.from_numpy(x)).numpy(), atol=1e-14)
+
+
+def test_attention_vs_torch_sdpa():
+    rng = np.random.default_rng(1)
+    B, T, H, d = 2, 7, 3, 8
+    D = H * d
+    qkv = rng.standard_normal((B, T, 3 * D))
+    got = dit.attention(qkv, H)
+    t = torch.from_numpy(qkv).reshape(B, T, 3, H, d).permute(2, 0, 3, 1, 4)
+    want = F.scaled_dot_product_attention(t[0], t[1], t[2]).permute(0, 2, 1, 3).reshape(B, T, D).numpy()
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-12)
+
+
+def test_attention_uniform_when_keys_equal():
+    # identical keys -> uniform weights -> output is the mean of V
+    B, T, H, d = 1, 6, 2, 4
+    D = H * d
+    rng = np.random.default_rng(2)
+    qkv = rng.standard_normal((B, T, 3 * D))
+    qkv[:, :, D:2 * D] = qkv[:, :1, D:2 * D]
+    out = dit.attention(qkv, H)
+    assert np.allclose(out, np.broadcast_to(qkv[:, :, 2 * D:].mean(axis=1, keepdims=True), out.shape))
+
+
+def test_timestep_embedding_closed_forms():
+    e = dit.timestep_embedding([0, 500], 256)
+    assert e.shape == (2, 256)
+    assert np.all(e[0, :128] == 1.0) and np.all(e[0, 128:] == 0.0)
+    assert math.isclose(e[1, 0], math.cos(500.0)) and math.isclose(e[1, 128], math.sin(500.0))
+    j = 64                                        # f_64 = 10^-2
+    assert math.isclose(e[1, j], math.cos(5.0), rel_tol=1e-12)
+    assert math.isclose(e[1, 128 + j], math.sin(5.0), rel_tol=1e-12)
+    assert np.allclose(e[:, :128] ** 2 + e[:, 128:] ** 2, 1.0)
+
+
+def test_patchify_vs_torch_unfold_and_unpatchify_inverse():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((2, 4, 8, 6))
+    got = dit.patchify(x, 2)
+    want = F.unfold(torch.from_numpy(x), kernel_size=2, stride=2).transpose(1, 2).numpy()
+    assert np.array_equal(got, want)
+    # unpatchify places feature (ph, pw, c) of token (i, j) at pixel (c, i*p+ph, j*p+pw)
+    tok = rng.standard_normal((2, 12, 2 * 2 * 8))
+    img = dit.unpatchify(tok, 2, 8, 8, 6)
+    for (b, i, j, ph, pw, c) in [(0, 0, 0, 0, 0, 0), (1, 3, 2, 1, 0, 5), (0, 2, 1, 1, 1, 7)]:
+        assert img[b, c, i * 2 + ph, j * 2 + pw] == tok[b, i * 3 + j, (ph * 2 + pw) * 8 + c]
+
+
+# ------------------------------------------------ the block, un-quantised
+class _TorchBlock:
+    """The adaLN-Zero block written with torch library ops only."""
+
+    def __init__(self, bw, heads):
+        self.w = {k: torch.from_numpy(v.astype(np.float64)) for k, v in bw.items()}
+        self.h = heads
+
+    def __call__(self, x, c):
+        w = self.w
+        x = torch.from_numpy(x); c = torch.from_numpy(c)
+        B, T, D = x.shape
+        mod = F.linear(F.silu(c), w["ada_w"], w["ada_b"])
+        sm, cm, gm, sl, cl, gl = mod.chunk(6, dim=1)
+        h = F.layer_norm(x, (D,), eps=1e-6) * (1 + cm.unsqueeze(1)) + sm.unsqueeze(1)
+        qkv = F.linear(h, w["qkv_w"], w["qkv_b"]).reshape(B, T, 3, self.h, D // self.h).permute(2, 0, 3, 1, 4)
+        o = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2]).transpose(1, 2).reshape(B, T, D)
+        x = x + gm.unsqueeze(1) * F.linear(o, w["proj_w"], w["proj_b"])
+        h2 = F.layer_norm(x, (D,), eps=1e-6) * (1 + cl.unsqueeze(1)) + sl.unsqueeze(1)
+        m = F.linear(F.gelu(F.linear(h2, w["fc1_w"], w["fc1_b"]), approximate="tanh"), w["fc2_w"], w["fc2_b"])
+        return (x + gl.unsqueeze(1) * m).numpy()
+
+
+def test_fp_block_vs_torch_library_block():
+    w, _, _ = _tiny_setup()
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((2, TINY.tokens, TINY.hidden))
+    c = rng.standard_normal((2, TINY.hidden))
+    got = dit.block_full(x, c, 1, TINY.heads, dit.FPLinears(w))
+    want = _TorchBlock(w["blocks"][1], TINY.heads)(x, c)
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-12)
+
+
+def _qparams_for(w, x_lat, lab, t):
+    qp, ranges = sampler.calibrate(TINY, w, x_lat, lab, t)
+    return qp, ranges
+
+
+def test_quantised_block_close_to_fp_and_converges_with_bits():
+    w, lat, lab = _tiny_setup()
+    t = np.array([500, 500, 500])
+    qp8, ranges = _qparams_for(w, lat, lab, t)
+    assert set(ranges) == {(b, s) for b in range(TINY.depth) for s in dit.SITES}
+    fp = dit.denoiser(lat, t, lab, TINY, w, dit.FPLinears(w), {}, True)
+    e8 = dit.denoiser(lat, t, lab, TINY, w, dit.QLinears(w, qp8, 8, 8), {}, True)
+    qp16 = {k: quant.act_qparams(lo, hi, 16) for k, (lo, hi) in ranges.items()}
+
+    class Fine(dit.QLinears):
+        def __init__(self, weights, qparams):
+            self.qparams = qparams; self.act_bits = 16; self.taps = None
+            self.lin = []
+            for b in weights["blocks"]:
+                d = {}
+                for s in dit.SITES:
+                    lin = quant.QLinear.__new__(quant.QLinear)
+                    W = b[s + "_w"]; qmax = 2 ** 15 - 1
+                    lin.bits = 16
+                    lin.scale = (np.abs(W).max(axis=1) / np.float32(qmax)).astype(np.float32)
+                    lin.q = np.clip(np.rint(W / lin.scale[:, None]), -qmax, qmax).astype(np.int64)
+                    lin.wsum = lin.q.sum(axis=1); lin.bias = b[s + "_b"]
+                    d[s] = lin
+                self.lin.append(d)
+
+    e16 = dit.denoiser(lat, t, lab, TINY, w, Fine(w, qp16), {}, True)
+    r8 = np.sqrt(np.mean((e8 - fp) ** 2)) / np.sqrt(np.mean(fp ** 2))
+    r16 = np.sqrt(np.mean((e16 - fp) ** 2)) / np.sqrt(np.mean(fp ** 2))
+    assert r8 < 5e-2 and r16 < r8 / 50
+
+
+def test_block_is_identity_when_gates_are_zero():
+    w, _, _ = _tiny_setup()
+    D = TINY.hidden
+    bw = w["blocks"][0]
+    bw["ada_w"][2 * D:3 * D] = 0; bw["ada_b"][2 * D:3 * D] = 0      # gate_msa
+    bw["ada_w"][5 * D:6 * D] = 0; bw["ada_b"][5 * D:6 * D] = 0      # gate_mlp
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((2, TINY.tokens, D)); c = rng.standard_normal((2, D))
+    qp = {(0, s): quant.act_qparams(-4, 4) for s in dit.SITES}
+    out = dit.block_full(x, c, 0, TINY.heads, dit.QLinears(w, qp))
+    assert np.array_equal(out, x)
+
+
+# ---------------------------------------------------------------- cache
+def test_cached_step_equals_full_step_on_fresh_cache_bitwise():
+    w, lat, lab = _tiny_setup()
+    t = np.array([500, 500, 500])
+    qp, _ = _qparams_for(w, lat, lab, t)
+    lin = dit.QLinears(w, qp)
+    cache = {}
+    full = dit.denoiser(lat, t, lab, TINY, w, lin, cache, True)
+    assert set(cache) == {(b, k) for b in range(TINY.depth) for k in ("attn", "mlp")}
+    again = dit.denoiser(lat, t, lab, TINY, w, lin, cache, False)
+    assert np.array_equal(full, again)
+    # at another timestep only the gates change: the result differs from both
+    other = dit.denoiser(lat, t - 20, lab, TINY, w, lin, cache, False)
+    assert not np.array_equal(other, full)
+
+
+@pytest.mark.parametrize("St,N", [(50, 2), (100, 3), (250, 5), (7, 3), (5, 1)])
+def test_refresh_count(St, N):
+    n = sum(sampler.is_refresh_step(i, N) for i in range(St))
+    assert n == -(-St // N) and sampler.is_refresh_step(0, N)
+
+
+def test_interval_one_is_no_cache():
+    w, lat, lab = _tiny_setup()
+    t = np.array([500, 500, 500])
+    qp, _ = _qparams_for(w, lat, lab, t)
+    a = sampler.sample(lat, lab, 5, 1, TINY, w, dit.QLinears(w, qp))
+    # reference run: every step forced full with a throw-away cache
+    tt, at, ap = sampler.ddim_schedule(5)
+    x = lat.astype(np.float64)
+    for i in range(5):
+        x, _ = sampler.sample_step(x, lab, i, int(tt[i]), at[i], ap[i], TINY, w, dit.QLinears(w, qp), {}, 1,
+                                   force_full=True)
+    assert np.array_equal(a, x)
+
+
+def test_cached_run_differs_but_tracks_uncached_run():
+    w, lat, lab = _tiny_setup()
+    qp, _ = _qparams_for(w, lat, lab, np.array([500, 500, 500]))
+    a = sampler.sample(lat, lab, 6, 1, TINY, w, dit.QLinears(w, qp))
+    b = sampler.sample(lat, lab, 6, 2, TINY, w, dit.QLinears(w, qp))
+    assert not np.array_equal(a, b)
+    assert np.sqrt(np.mean((a - b) ** 2)) < 0.2 * np.sqrt(np.mean(a ** 2))
+
+
+# --------------------------------------------------------------- solver
+def test_abar_table_and_schedule():
+    ab = sampler.abar_table()
+    want = torch.cumprod(1 - torch.linspace(1e-4, 2e-2, 1000, dtype=torch.float64), 0).numpy()
+    assert np.allclose(ab, want, rtol=1e-13)
+    assert math.isclose(ab[0], 1 - 1e-4) and np.all(np.diff(ab) < 0) and 3.9e-5 < ab[-1] < 4.2e-5
+    t, at, ap = sampler.ddim_schedule(50)
+    assert list(t[:3]) == [980, 960, 940] and t[-1] == 0 and len(t) == 50
+    assert ap[-1] == 1.0 and np.array_equal(ap[:-1], at[1:]) and np.array_equal(at, ab[t])
+
+
+def test_ddim_identity_and_exact_denoise_and_hand_case():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((2, 4, 8, 8))
+    assert np.allclose(sampler.ddim_update(x, np.zeros_like(x), 0.3, 0.3), x, rtol=1e-15)
+    # if eps is the true noise, a jump to abar_prev = 1 returns x0 exactly
+    x0 = rng.standard_normal(x.shape); eps = rng.standard_normal(x.shape); ab = 0.37
+    xt = math.sqrt(ab) * x0 + math.sqrt(1 - ab) * eps
+    assert np.allclose(sampler.ddim_update(xt, eps, ab, 1.0), x0, atol=1e-13)
+    # and a jump to another noise level lands on the same (x0, eps) line
+    assert np.allclose(sampler.ddim_update(xt, eps, ab, 0.81), 0.9 * x0 + math.sqrt(0.19) * eps, atol=1e-13)
+    # hand case: x=1, eps=0.5, abar_t=0.25, abar_prev=0.64: x0=(1-sqrt(.75)/2)/0.5, out=0.8 x0+0.6*0.5
+    x0h = (1 - math.sqrt(0.75) * 0.5) / 0.5
+    assert math.isclose(float(sampler.ddim_update(np.array(1.0), np.array(0.5), 0.25, 0.64)), 0.8 * x0h + 0.3)
+
+
+def test_cfg_combine_special_cases():
+    a = np.array([1.0, 2.0]); b = np.array([0.5, -1.0])
+    assert np.array_equal(sampler.cfg_combine(a, b, 1.0), a)
+    assert np.array_equal(sampler.cfg_combine(a, b, 0.0), b)
+    assert np.allclose(sampler.cfg_combine(a, b, 1.5), 1.5 * a - 0.5 * b)
+
+
+# -------------------------------------------------------------------- VC
+def test_vc_identity_mean_variance_and_collapse():
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((3, 4, 8, 8)) * 2 + 0.7
+    assert np.array_equal(sampler.vc_correct(x, np.ones(4)), x)          # K = 1: bitwise identity
+    K = np.array([0.9, 1.0, 1.1, 0.5])
+    y = sampler.vc_correct(x, K)
+    assert np.allclose(y.mean(axis=(2, 3)), x.mean(axis=(2, 3)), atol=1e-14)      # Eq. 9: mean kept
+    assert np.allclose(y.var(axis=(2, 3)), x.var(axis=(2, 3)) * K[None, :] ** 2)   # variance times K^2
+    z = sampler.vc_correct(x, np.zeros(4))
+    assert np.allclose(z, np.broadcast_to(x.mean(axis=(2, 3), keepdims=True), x.shape))
+    # caller-supplied mu reading: mu + K (x - mu)
+    mu = np.array([0.1, 0.2, 0.3, 0.4])
+    y2 = sampler.vc_correct(x, K, mu)
+    assert np.allclose(y2, mu.reshape(1, 4, 1, 1) + K.reshape(1, 4, 1, 1) * (x - mu.reshape(1, 4, 1, 1)))
+
+
+def test_vc_matches_gaussian_rescale_statistically():
+    # Eq. 9: f ~ N(mu, sigma^2) rescaled with sigma_new/sigma has std sigma_new
+    rng = np.random.default_rng(8)
+    f = rng.normal(1.5, 2.0, size=(1, 1, 400, 400))
+    y = sampler.vc_correct(f, np.array([0.25]))
+    assert abs(y.std() - 0.5) < 5e-3 and abs(y.mean() - 1.5) < 2e-2
+
+
+def test_guidance_step_uses_null_label_for_second_half():
+    w, lat, lab = _tiny_setup()
+    qp, _ = _qparams_for(w, lat, lab, np.array([500, 500, 500]))
+    lin = dit.QLinears(w, qp)
+    x1, eps = sampler.sample_step(lat.astype(np.float64), lab, 0, 500, 0.3, 0.4, TINY, w, lin, {}, 2, cfg_scale=1.5)
+    ec = dit.denoiser(lat, np.full(3, 500), lab, TINY, w, lin, {}, True)
+    eu = dit.denoiser(lat, np.full(3, 500), np.full(3, TINY.num_classes), TINY, w, lin, {}, True)
+    assert np.allclose(eps, eu + 1.5 * (ec - eu), atol=1e-14)

@@ -1,0 +1,208 @@
+/*
+ * qc.h - C ABI of the MI355X (gfx950) implementation of the quantised + cached
+ * DiT sampler step of "Q&C: When Quantization Meets Cache in Efficient Image
+ * Generation" (arXiv 2503.02508).
+ *
+ * Conventions (all entry points)
+ *   - return value: QC_OK (0) or a negative qc_status; qc_last_error() gives a
+ *     thread-local text for the last failure.  No exceptions, no aborts.
+ *   - "dev" pointers are device (HBM) pointers owned by the caller and only
+ *     borrowed for the call; "host" pointers are ordinary host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Unless stated otherwise a call only enqueues work on that stream.
+ *   - tensors are row-major and dense.  Activation codes are int8 holding the
+ *     paper's unsigned code minus 128 (Eq. 1: q in [0, 255]); a zero point is
+ *     passed in the paper's unsigned convention (0..255) and shifted inside.
+ *   - weight matrices are [N, K] (one row per output channel).  4-bit weights
+ *     are packed two per byte along K: element 2j in bits 0-3, element 2j+1 in
+ *     bits 4-7, two's complement.
+ *   - the library never allocates device memory: everything a context needs
+ *     lives in one caller-provided arena.
+ *   - argument checks run before any device call.
+ */
+#ifndef QC_H_
+#define QC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum qc_status {
+  QC_OK = 0,
+  QC_ERR_NULL = -1,        /* a required pointer is NULL                      */
+  QC_ERR_SHAPE = -2,       /* zero / negative / inconsistent dimension         */
+  QC_ERR_ALIGN = -3,       /* pointer or leading dimension not 16-byte aligned */
+  QC_ERR_RANGE = -4,       /* scale <= 0 or not finite, zero point outside 0..255, index out of range */
+  QC_ERR_STATE = -5,       /* e.g. cached block before anything was stored     */
+  QC_ERR_WORKSPACE = -6,   /* arena too small                                  */
+  QC_ERR_UNSUPPORTED = -7, /* shape the kernels do not cover                   */
+  QC_ERR_HIP = -8          /* a HIP runtime call failed                        */
+} qc_status;
+
+enum { QC_FULL = 0, QC_CACHED = 1 };                 /* block / step mode          */
+enum { QC_CACHE_ATTN = 0, QC_CACHE_MLP = 1 };        /* which cached module output */
+enum { QC_SITE_ADA = 0, QC_SITE_QKV = 1, QC_SITE_PROJ = 2, QC_SITE_FC1 = 3, QC_SITE_FC2 = 4, QC_NUM_SITES = 5 };
+enum {                                               /* qc_workspace_ptr selectors */
+  QC_WS_TOKENS = 0,   /* float  [B, T, D]  residual stream of the last denoiser call      */
+  QC_WS_QACT_LN = 1,  /* int8   [B*T, D]   codes produced by the last LN+modulate+quantise */
+  QC_WS_QACT_ATTN = 2,/* int8   [B*T, D]   codes of the last attention output              */
+  QC_WS_QACT_MLP = 3, /* int8   [B*T, R]   codes of the last GELU output                    */
+  QC_WS_QKV = 4,      /* float  [B*T, 3D]  last QKV projection                              */
+  QC_WS_MOD = 5,      /* float  [L, B, 6D] adaLN modulation of every block                  */
+  QC_WS_COND = 6,     /* float  [B, D]     conditioning vector c                            */
+  QC_WS_EPS = 7       /* float  [B, C, H, W] last noise estimate                            */
+};
+
+/* The network: a class-conditional DiT (the architecture the paper evaluates,
+ * Experimental Settings) with `depth` adaLN-Zero blocks. */
+typedef struct qc_model_desc {
+  int32_t depth, hidden, heads, mlp_dim;
+  int32_t patch, latent_c, latent_h, latent_w;
+  int32_t num_classes;     /* label table has num_classes + 1 rows; the last is the null label */
+  int32_t freq_dim;        /* width of the sinusoidal timestep embedding (256)                 */
+  int32_t weight_bits;     /* 8 or 4 (Tables 1 and 2: W8A8, W4A8)                              */
+  int32_t cache_interval;  /* N of the cache rule: step i is recomputed iff i mod N == 0       */
+} qc_model_desc;
+
+typedef struct qc_block_weights_f32 {   /* dev pointers, fp32, [N, K] / [N] */
+  const float *ada_w, *ada_b;     /* [6D, D], [6D]  adaLN projection */
+  const float *qkv_w, *qkv_b;     /* [3D, D], [3D]                   */
+  const float *proj_w, *proj_b;   /* [D, D],  [D]                    */
+  const float *fc1_w, *fc1_b;     /* [R, D],  [R]                    */
+  const float *fc2_w, *fc2_b;     /* [D, R],  [D]                    */
+} qc_block_weights_f32;
+
+typedef struct qc_weights_f32 {
+  const float *patch_w, *patch_b;   /* dev [D, C*p*p] (features ordered c, ph, pw), [D] */
+  const float *pos;                 /* dev [T, D]                                      */
+  const float *t_w1, *t_b1;         /* dev [D, freq_dim], [D]                           */
+  const float *t_w2, *t_b2;         /* dev [D, D], [D]                                  */
+  const float *label_table;         /* dev [num_classes + 1, D]                         */
+  const float *fada_w, *fada_b;     /* dev [2D, D], [2D]  final-layer adaLN (shift, scale) */
+  const float *flin_w, *flin_b;     /* dev [p*p*2C, D], [p*p*2C] (features ordered ph, pw, c) */
+  const qc_block_weights_f32 *blocks; /* HOST array of `depth` entries holding dev pointers */
+} qc_weights_f32;
+
+typedef struct qc_ctx qc_ctx;
+
+const char *qc_last_error(void);
+
+/* ---------------------------------------------------------------- context */
+
+/* Bytes of device arena a context needs for effective batches up to max_batch
+ * (the effective batch is twice the number of latents under guidance). */
+int qc_arena_bytes(const qc_model_desc *desc, int max_batch, size_t *bytes_out);
+
+/* Creates a context inside `arena` (dev, 256-byte aligned, arena_bytes >=
+ * qc_arena_bytes).  The arena stays owned by the caller and must outlive the
+ * context.  Holds: quantised weights, per-site activation parameters, the
+ * attention / MLP output cache (two fp32 [B, T, D] tensors per block) and
+ * workspace. */
+int qc_create(const qc_model_desc *desc, void *arena, size_t arena_bytes, int max_batch, qc_ctx **out);
+int qc_destroy(qc_ctx *ctx);
+
+/* Quantises the five linears of every block on the device ("channel-wise"
+ * weights, Comparison on Performance section: one symmetric scale per output
+ * row, s_w = max|row| / qmax, codes clip(round(w / s_w), -qmax, qmax), qmax =
+ * 127 or 7; an all-zero row gets s_w = 1), stores row sums of the codes, and
+ * copies the floating-point embedders / final layer into the arena. */
+int qc_load_weights_f32(qc_ctx *ctx, const qc_weights_f32 *w, void *stream);
+
+/* Static activation quantiser parameters of one site (Eq. 1-3; "tensor-wise"
+ * activations).  scale > 0 finite, zero_point in 0..255.  Synchronous. */
+int qc_set_act_qparams(qc_ctx *ctx, int block, int site, float scale, int zero_point);
+int qc_get_act_qparams(const qc_ctx *ctx, int block, int site, float *scale, int *zero_point);
+
+/* Derives every site's (s, z) from calibration data (Eq. 2-3): runs the
+ * un-quantised fp32 network (weights w, the same structure that was given to
+ * qc_load_weights_f32) on n inputs, one at a time, takes the global min l and
+ * max u of each site's input, widens [l, u] to contain 0, s = (u - l) / 255,
+ * z = round(-l / s), and installs them as with qc_set_act_qparams.
+ * x: dev [n, C, H, W]; t, y: HOST [n].  Synchronous. */
+int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, const int32_t *t, const int32_t *y, int n,
+                        void *stream);
+
+/* ------------------------------------------------------- single operations */
+
+/* Eq. 1 with b = 8: q[i] = clip(round(x[i] / scale) + zero_point, 0, 255) - 128,
+ * round-half-to-even, x / scale an IEEE fp32 division.  x, q: dev, n elements. */
+int qc_quantize_act(const float *x, int8_t *q, size_t n, float scale, int zero_point, void *stream);
+
+/* Channel-wise weight quantiser (as in qc_load_weights_f32) for one matrix.
+ * w: dev fp32 [N, K]; qw: dev int8 [N, K] or packed [N, K/2] for bits = 4;
+ * w_scale: dev [N]; wsum: dev [N] (sum over k of the codes).  K % 16 == 0. */
+int qc_quantize_weight(const float *w, int N, int K, int bits, void *qw, float *w_scale, int32_t *wsum, void *stream);
+
+/* Quantised linear layer on codes (Eq. 1 applied to both operands, weights
+ * channel-wise, activations tensor-wise):
+ *   acc[m, n] = sum_k qx[m, k] * qw[n, k]                       (int32, exact)
+ *   y[m, n]   = x_scale * w_scale[n] * (acc[m, n] - (x_zp - 128) * wsum[n]) + bias[n]
+ * qx: dev int8 [M, K]; qw: dev [N, K] int8 (weight_bits 8) or [N, K/2] packed
+ * (weight_bits 4); wsum, w_scale, bias: dev [N] (bias may be NULL); y: dev fp32
+ * [M, N]; acc_or_null: dev int32 [M, N] receiving the raw accumulators, or
+ * NULL.  K % 16 == 0; pointers 16-byte aligned. */
+int qc_w8a8_linear(const int8_t *qx, const void *qw, const int32_t *wsum, const float *w_scale, const float *bias,
+                   float x_scale, int x_zp, int M, int N, int K, int weight_bits,
+                   float *y, int32_t *acc_or_null, void *stream);
+
+/* Variance compensation, Eq. 10, channel-wise: x <- mu + K_t * (x - mu) on
+ * x: dev [B, C, H, W] in place; K_t: dev [C]; mu_or_null: dev [C], or NULL to
+ * use the spatial mean of each (sample, channel) plane (then the plane mean is
+ * preserved and its variance scales by K_t^2, Eq. 9). */
+int qc_vc_correct(float *x, const float *K_t, const float *mu_or_null, int B, int C, int H, int W, void *stream);
+
+/* Deterministic DDIM schedule on the 1000-step linear-beta (1e-4..2e-2)
+ * training schedule: t[i] = (steps-1-i) * floor(1000/steps), abar_t[i],
+ * abar_prev[i] (= 1 on the last step).  HOST arrays of `steps` entries. */
+int qc_ddim_schedule(int steps, int32_t *t, double *abar_t, double *abar_prev);
+
+/* ------------------------------------------------------------- DiT pieces */
+
+/* One adaLN-Zero block on x: dev [B, T, D] in place, conditioning c: dev
+ * [B, D].  QC_FULL: adaLN projection, LN+modulate+quantise, QKV, attention,
+ * projection, MLP, all five linears quantised; stores the attention and MLP
+ * module outputs (before the gate) in the cache.  QC_CACHED ("reuse for the
+ * following N-1 steps", Quantization and Cache section): recomputes only the
+ * two gates from c and adds gate * cached output twice.  QC_ERR_STATE when
+ * nothing was stored for this block at this batch size. */
+int qc_dit_block(qc_ctx *ctx, int block, int mode, float *x, const float *c, int B, void *stream);
+
+/* Copy a module output into / add a gated cached module output from the cache.
+ * src, x: dev [B, T, D]; gate: dev [B, ld_gate] rows, first D entries used. */
+int qc_cache_store(qc_ctx *ctx, int block, int which, const float *src, int B, void *stream);
+int qc_cache_reuse(qc_ctx *ctx, int block, int which, float *x, const float *gate, int ld_gate, int B, void *stream);
+/* Device address of a cached tensor (fp32 [max_batch, T, D], first B rows valid). */
+int qc_cache_ptr(qc_ctx *ctx, int block, int which, float **ptr_out);
+/* Device address of an internal buffer, see QC_WS_*; for inspection by tests. */
+int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out);
+
+/* Noise estimate of the whole network at timestep t.  x: dev [n_labels, C, H, W],
+ * labels: dev int32 [n_labels].  The effective batch B is n_labels, or
+ * 2 * n_labels for guidance: then sample b + n_labels is latent b again with
+ * the null label.  eps_out: dev [B, C, H, W] (first C of the 2C output
+ * channels).  mode QC_FULL recomputes all blocks and refreshes the cache,
+ * QC_CACHED reuses it (QC_ERR_STATE unless the cache holds this batch size). */
+int qc_denoise(qc_ctx *ctx, const float *x, int t, const int32_t *labels, int n_labels, int B, int mode,
+               float *eps_out, void *stream);
+
+/* One sampler step on x: dev [B, C, H, W] in place: denoiser (full iff
+ * step_index mod N == 0 unless force_mode is QC_FULL / QC_CACHED; pass -1 for
+ * the rule), guidance when cfg_scale > 0 (the library runs the 2B batch
+ * [labels ; null] and combines eps_u + w (eps_c - eps_u)), DDIM (eta = 0)
+ * update with the given abar values, then VC (Eq. 10) with K_t: dev [C] unless
+ * K_t is NULL. */
+int qc_sample_step(qc_ctx *ctx, float *x, const int32_t *labels, int B, int step_index, int t,
+                   double abar_t, double abar_prev, float cfg_scale, const float *K_t, int force_mode, void *stream);
+
+/* The whole sampling loop: `steps` calls of qc_sample_step with the schedule
+ * of qc_ddim_schedule; K: dev [steps, C] or NULL. */
+int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, float cfg_scale, const float *K,
+              void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QC_H_ */

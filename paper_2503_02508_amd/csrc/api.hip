@@ -1,0 +1,690 @@
+// Host layer of the C ABI: argument checks, arena layout, and the sequence of
+// kernel launches that makes up a DiT block, a denoiser call and a sampler step.
+// Every check runs before the first device call, so error paths work without a GPU.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "qc_internal.h"
+
+namespace qc {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+#define QC_FAIL(code, ...)      \
+  do {                          \
+    qc::set_error(__VA_ARGS__); \
+    return (code);              \
+  } while (0)
+
+#define QC_HIP(expr)                                                                          \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess) QC_FAIL(QC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));        \
+  } while (0)
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// bump allocator over the arena (base may be null when only sizing)
+struct Bump {
+  char *base;
+  size_t off = 0;
+  explicit Bump(char *b) : base(b) {}
+  template <typename T>
+  T *take(size_t count) {
+    off = (off + 255) & ~size_t(255);
+    T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+struct BlockQ {
+  LinearQ lin[QC_NUM_SITES];
+};
+
+}  // namespace qc
+
+using namespace qc;
+
+struct qc_ctx {
+  qc_model_desc d;
+  int max_batch;
+  int T, D, R, H, hd, L, C, F;   // F = patch feature count
+  char *arena;
+  size_t arena_bytes;
+  std::vector<BlockQ> blk;
+  // adaLN weights of all blocks are contiguous so that one batched launch covers them
+  size_t ada_w_stride_bytes;
+  float *patch_w, *patch_b, *pos, *t_w1, *t_b1, *t_w2, *t_b2, *label_table, *fada_w, *fada_b, *flin_w, *flin_b;
+  std::vector<QParam> host_qp;
+  std::vector<char> qp_set;
+  QParam *dev_qp;   // [L][5]
+  float *cache;     // [L][2][max_batch*T*D]
+  std::vector<int> cache_batch;   // [L][2]: batch size held, 0 = nothing stored
+  // workspace
+  float *emb, *h1, *te, *cond, *mod, *fmod, *tokens, *qkv, *eps;
+  int8_t *silu_q, *qa_ln, *qa_attn, *qa_mlp;
+  // calibration scratch (one sample)
+  float *cal_h, *cal_o, *cal_a, *cal_u, *cal_mod;
+  int *cal_slots, *cal_label;
+  bool weights_loaded;
+};
+
+static size_t weight_bytes(const qc_model_desc &d, size_t N, size_t K) { return d.weight_bits == 4 ? N * K / 2 : N * K; }
+
+static int check_desc(const qc_model_desc *d) {
+  if (!d) QC_FAIL(QC_ERR_NULL, "model description is NULL");
+  if (d->depth < 1 || d->hidden < 1 || d->heads < 1 || d->mlp_dim < 1 || d->patch < 1 || d->latent_c < 1 ||
+      d->latent_h < 1 || d->latent_w < 1 || d->num_classes < 1 || d->freq_dim < 2)
+    QC_FAIL(QC_ERR_SHAPE, "model description has a non-positive dimension");
+  if (d->hidden % d->heads) QC_FAIL(QC_ERR_SHAPE, "hidden (%d) is not a multiple of heads (%d)", d->hidden, d->heads);
+  if (d->latent_h % d->patch || d->latent_w % d->patch)
+    QC_FAIL(QC_ERR_SHAPE, "latent %dx%d is not a multiple of the patch size %d", d->latent_h, d->latent_w, d->patch);
+  if (d->freq_dim % 2) QC_FAIL(QC_ERR_SHAPE, "freq_dim must be even");
+  if (d->weight_bits != 8 && d->weight_bits != 4) QC_FAIL(QC_ERR_UNSUPPORTED, "weight_bits must be 8 or 4");
+  if (d->cache_interval < 1) QC_FAIL(QC_ERR_RANGE, "cache_interval must be >= 1");
+  const int hd = d->hidden / d->heads;
+  if (d->hidden % 16 || d->mlp_dim % 16) QC_FAIL(QC_ERR_UNSUPPORTED, "hidden and mlp_dim must be multiples of 16");
+  if (d->hidden > 2048) QC_FAIL(QC_ERR_UNSUPPORTED, "hidden > 2048 is not covered by the row kernels");
+  if (hd % 4 || hd > 96) QC_FAIL(QC_ERR_UNSUPPORTED, "head dim must be a multiple of 4 and at most 96");
+  if (d->latent_c * d->patch * d->patch > 256) QC_FAIL(QC_ERR_UNSUPPORTED, "patch feature count above 256");
+  return QC_OK;
+}
+
+// Lays the context out in the arena; with ctx == nullptr only measures.
+static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *c) {
+  Bump a(base);
+  const size_t D = d.hidden, R = d.mlp_dim, L = d.depth, C = d.latent_c;
+  const size_t T = (size_t)(d.latent_h / d.patch) * (d.latent_w / d.patch);
+  const size_t F = C * d.patch * d.patch, O = (size_t)d.patch * d.patch * 2 * C;
+  const size_t B = max_batch, M = B * T;
+  // batched adaLN weights
+  const size_t ada_bytes = (weight_bytes(d, 6 * D, D) + 255) & ~size_t(255);
+  char *ada_q = a.take<char>(ada_bytes * L);
+  float *ada_scale = a.take<float>(6 * D * L);
+  int32_t *ada_wsum = a.take<int32_t>(6 * D * L);
+  float *ada_bias = a.take<float>(6 * D * L);
+  if (c) {
+    c->ada_w_stride_bytes = ada_bytes;
+    c->blk.resize(L);
+  }
+  const size_t Ns[QC_NUM_SITES] = {6 * D, 3 * D, D, R, D};
+  const size_t Ks[QC_NUM_SITES] = {D, D, D, D, R};
+  for (size_t l = 0; l < L; ++l) {
+    for (int s = 0; s < QC_NUM_SITES; ++s) {
+      LinearQ q;
+      q.N = (int)Ns[s];
+      q.K = (int)Ks[s];
+      if (s == QC_SITE_ADA) {
+        q.q = ada_q ? ada_q + l * ada_bytes : nullptr;
+        q.scale = ada_scale ? ada_scale + l * 6 * D : nullptr;
+        q.wsum = ada_wsum ? ada_wsum + l * 6 * D : nullptr;
+        q.bias = ada_bias ? ada_bias + l * 6 * D : nullptr;
+      } else {
+        q.q = a.take<char>(weight_bytes(d, Ns[s], Ks[s]));
+        q.scale = a.take<float>(Ns[s]);
+        q.wsum = a.take<int32_t>(Ns[s]);
+        q.bias = a.take<float>(Ns[s]);
+      }
+      if (c) c->blk[l].lin[s] = q;
+    }
+  }
+  float *patch_w = a.take<float>(D * F), *patch_b = a.take<float>(D), *pos = a.take<float>(T * D);
+  float *t_w1 = a.take<float>(D * d.freq_dim), *t_b1 = a.take<float>(D), *t_w2 = a.take<float>(D * D), *t_b2 = a.take<float>(D);
+  float *label_table = a.take<float>((size_t)(d.num_classes + 1) * D);
+  float *fada_w = a.take<float>(2 * D * D), *fada_b = a.take<float>(2 * D);
+  float *flin_w = a.take<float>(O * D), *flin_b = a.take<float>(O);
+  QParam *dev_qp = a.take<QParam>(L * QC_NUM_SITES);
+  float *cache = a.take<float>(L * 2 * M * D);
+  float *emb = a.take<float>(d.freq_dim), *h1 = a.take<float>(D), *te = a.take<float>(D);
+  float *cond = a.take<float>(B * D), *mod = a.take<float>(L * B * 6 * D), *fmod = a.take<float>(B * 2 * D);
+  float *tokens = a.take<float>(M * D), *qkv = a.take<float>(M * 3 * D), *eps = a.take<float>(B * C * d.latent_h * d.latent_w);
+  int8_t *silu_q = a.take<int8_t>(L * B * D), *qa_ln = a.take<int8_t>(M * D), *qa_attn = a.take<int8_t>(M * D);
+  int8_t *qa_mlp = a.take<int8_t>(M * R);
+  float *cal_h = a.take<float>(T * D), *cal_o = a.take<float>(T * D), *cal_a = a.take<float>(T * D);
+  float *cal_u = a.take<float>(T * R), *cal_mod = a.take<float>(6 * D);
+  int *cal_slots = a.take<int>(L * QC_NUM_SITES * 2), *cal_label = a.take<int>(4);
+  if (c) {
+    c->patch_w = patch_w; c->patch_b = patch_b; c->pos = pos; c->t_w1 = t_w1; c->t_b1 = t_b1; c->t_w2 = t_w2; c->t_b2 = t_b2;
+    c->label_table = label_table; c->fada_w = fada_w; c->fada_b = fada_b; c->flin_w = flin_w; c->flin_b = flin_b;
+    c->dev_qp = dev_qp; c->cache = cache; c->emb = emb; c->h1 = h1; c->te = te; c->cond = cond; c->mod = mod; c->fmod = fmod;
+    c->tokens = tokens; c->qkv = qkv; c->eps = eps; c->silu_q = silu_q; c->qa_ln = qa_ln; c->qa_attn = qa_attn;
+    c->qa_mlp = qa_mlp; c->cal_h = cal_h; c->cal_o = cal_o; c->cal_a = cal_a; c->cal_u = cal_u; c->cal_mod = cal_mod;
+    c->cal_slots = cal_slots; c->cal_label = cal_label;
+  }
+  return (a.off + 255) & ~size_t(255);
+}
+
+extern "C" {
+
+const char *qc_last_error(void) { return g_err; }
+
+int qc_arena_bytes(const qc_model_desc *desc, int max_batch, size_t *bytes_out) {
+  if (!bytes_out) QC_FAIL(QC_ERR_NULL, "bytes_out is NULL");
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (max_batch < 1) QC_FAIL(QC_ERR_SHAPE, "max_batch must be >= 1");
+  *bytes_out = layout(*desc, max_batch, nullptr, nullptr);
+  return QC_OK;
+}
+
+int qc_create(const qc_model_desc *desc, void *arena, size_t arena_bytes, int max_batch, qc_ctx **out) {
+  if (!out) QC_FAIL(QC_ERR_NULL, "out is NULL");
+  *out = nullptr;
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!arena) QC_FAIL(QC_ERR_NULL, "arena is NULL");
+  if (max_batch < 1) QC_FAIL(QC_ERR_SHAPE, "max_batch must be >= 1");
+  if (reinterpret_cast<uintptr_t>(arena) & 255u) QC_FAIL(QC_ERR_ALIGN, "arena must be 256-byte aligned");
+  const size_t need = layout(*desc, max_batch, nullptr, nullptr);
+  if (arena_bytes < need) QC_FAIL(QC_ERR_WORKSPACE, "arena holds %zu bytes, %zu needed", arena_bytes, need);
+  qc_ctx *c = new (std::nothrow) qc_ctx();
+  if (!c) QC_FAIL(QC_ERR_WORKSPACE, "out of host memory");
+  c->d = *desc;
+  c->max_batch = max_batch;
+  c->D = desc->hidden; c->R = desc->mlp_dim; c->H = desc->heads; c->hd = desc->hidden / desc->heads; c->L = desc->depth;
+  c->C = desc->latent_c; c->F = desc->latent_c * desc->patch * desc->patch;
+  c->T = (desc->latent_h / desc->patch) * (desc->latent_w / desc->patch);
+  c->arena = static_cast<char *>(arena);
+  c->arena_bytes = arena_bytes;
+  layout(*desc, max_batch, c->arena, c);
+  c->host_qp.assign((size_t)c->L * QC_NUM_SITES, QParam{1.0f, 0});
+  c->qp_set.assign((size_t)c->L * QC_NUM_SITES, 0);
+  c->cache_batch.assign((size_t)c->L * 2, 0);
+  c->weights_loaded = false;
+  *out = c;
+  return QC_OK;
+}
+
+int qc_destroy(qc_ctx *ctx) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  delete ctx;
+  return QC_OK;
+}
+
+static int check_weights(const qc_ctx *ctx, const qc_weights_f32 *w) {
+  if (!w) QC_FAIL(QC_ERR_NULL, "weights are NULL");
+  const void *g[] = {w->patch_w, w->patch_b, w->pos, w->t_w1, w->t_b1, w->t_w2, w->t_b2, w->label_table,
+                     w->fada_w, w->fada_b, w->flin_w, w->flin_b, w->blocks};
+  for (const void *p : g)
+    if (!p) QC_FAIL(QC_ERR_NULL, "a weight pointer is NULL");
+  for (int l = 0; l < ctx->L; ++l) {
+    const qc_block_weights_f32 &b = w->blocks[l];
+    const void *q[] = {b.ada_w, b.ada_b, b.qkv_w, b.qkv_b, b.proj_w, b.proj_b, b.fc1_w, b.fc1_b, b.fc2_w, b.fc2_b};
+    for (const void *p : q) {
+      if (!p) QC_FAIL(QC_ERR_NULL, "a weight pointer of block %d is NULL", l);
+      if (!aligned16(p)) QC_FAIL(QC_ERR_ALIGN, "a weight pointer of block %d is not 16-byte aligned", l);
+    }
+  }
+  return QC_OK;
+}
+
+int qc_load_weights_f32(qc_ctx *ctx, const qc_weights_f32 *w, void *stream) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  int rc = check_weights(ctx, w);
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t D = ctx->D, T = ctx->T, O = (size_t)ctx->d.patch * ctx->d.patch * 2 * ctx->C;
+  struct { float *dst; const float *src; size_t n; } cp[] = {
+      {ctx->patch_w, w->patch_w, D * ctx->F}, {ctx->patch_b, w->patch_b, D}, {ctx->pos, w->pos, T * D},
+      {ctx->t_w1, w->t_w1, D * ctx->d.freq_dim}, {ctx->t_b1, w->t_b1, D}, {ctx->t_w2, w->t_w2, D * D}, {ctx->t_b2, w->t_b2, D},
+      {ctx->label_table, w->label_table, (size_t)(ctx->d.num_classes + 1) * D}, {ctx->fada_w, w->fada_w, 2 * D * D},
+      {ctx->fada_b, w->fada_b, 2 * D}, {ctx->flin_w, w->flin_w, O * D}, {ctx->flin_b, w->flin_b, O}};
+  for (auto &c : cp) QC_HIP(hipMemcpyAsync(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToDevice, st));
+  for (int l = 0; l < ctx->L; ++l) {
+    const qc_block_weights_f32 &b = w->blocks[l];
+    const float *ws[QC_NUM_SITES] = {b.ada_w, b.qkv_w, b.proj_w, b.fc1_w, b.fc2_w};
+    const float *bs[QC_NUM_SITES] = {b.ada_b, b.qkv_b, b.proj_b, b.fc1_b, b.fc2_b};
+    for (int s = 0; s < QC_NUM_SITES; ++s) {
+      LinearQ &q = ctx->blk[l].lin[s];
+      QC_HIP(launch_quantize_weight(ws[s], q.N, q.K, ctx->d.weight_bits, q.q, q.scale, q.wsum, st));
+      QC_HIP(hipMemcpyAsync(q.bias, bs[s], (size_t)q.N * sizeof(float), hipMemcpyDeviceToDevice, st));
+    }
+  }
+  ctx->weights_loaded = true;
+  return QC_OK;
+}
+
+static int check_site(const qc_ctx *ctx, int block, int site) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  if (block < 0 || block >= ctx->L) QC_FAIL(QC_ERR_RANGE, "block %d outside 0..%d", block, ctx->L - 1);
+  if (site < 0 || site >= QC_NUM_SITES) QC_FAIL(QC_ERR_RANGE, "site %d outside 0..%d", site, QC_NUM_SITES - 1);
+  return QC_OK;
+}
+
+static int check_qparam(float scale, int zp) {
+  if (!(scale > 0.0f) || !std::isfinite(scale)) QC_FAIL(QC_ERR_RANGE, "scale must be positive and finite");
+  if (zp < 0 || zp > 255) QC_FAIL(QC_ERR_RANGE, "zero point %d outside 0..255", zp);
+  return QC_OK;
+}
+
+int qc_set_act_qparams(qc_ctx *ctx, int block, int site, float scale, int zero_point) {
+  int rc = check_site(ctx, block, site);
+  if (rc) return rc;
+  rc = check_qparam(scale, zero_point);
+  if (rc) return rc;
+  const size_t i = (size_t)block * QC_NUM_SITES + site;
+  ctx->host_qp[i] = QParam{scale, zero_point - 128};
+  ctx->qp_set[i] = 1;
+  QC_HIP(hipMemcpy(ctx->dev_qp + i, &ctx->host_qp[i], sizeof(QParam), hipMemcpyHostToDevice));
+  return QC_OK;
+}
+
+int qc_get_act_qparams(const qc_ctx *ctx, int block, int site, float *scale, int *zero_point) {
+  int rc = check_site(ctx, block, site);
+  if (rc) return rc;
+  if (!scale || !zero_point) QC_FAIL(QC_ERR_NULL, "output pointer is NULL");
+  const size_t i = (size_t)block * QC_NUM_SITES + site;
+  if (!ctx->qp_set[i]) QC_FAIL(QC_ERR_STATE, "activation parameters of block %d site %d were never set", block, site);
+  *scale = ctx->host_qp[i].s;
+  *zero_point = ctx->host_qp[i].z + 128;
+  return QC_OK;
+}
+
+// ------------------------------------------------------------ single ops
+int qc_quantize_act(const float *x, int8_t *q, size_t n, float scale, int zero_point, void *stream) {
+  int rc = check_qparam(scale, zero_point);
+  if (rc) return rc;
+  if (n == 0) return QC_OK;   // an empty tensor may come with a null pointer
+  if (!x || !q) QC_FAIL(QC_ERR_NULL, "x or q is NULL");
+  if (!aligned16(x) || (reinterpret_cast<uintptr_t>(q) & 3u)) QC_FAIL(QC_ERR_ALIGN, "x must be 16-byte and q 4-byte aligned");
+  QC_HIP(launch_quantize_act(x, q, n, scale, zero_point - 128, static_cast<hipStream_t>(stream)));
+  return QC_OK;
+}
+
+int qc_quantize_weight(const float *w, int N, int K, int bits, void *qw, float *w_scale, int32_t *wsum, void *stream) {
+  if (!w || !qw || !w_scale || !wsum) QC_FAIL(QC_ERR_NULL, "a pointer is NULL");
+  if (N < 1 || K < 1) QC_FAIL(QC_ERR_SHAPE, "N and K must be positive");
+  if (K % 16) QC_FAIL(QC_ERR_SHAPE, "K (%d) must be a multiple of 16", K);
+  if (bits != 8 && bits != 4) QC_FAIL(QC_ERR_UNSUPPORTED, "bits must be 8 or 4");
+  if (!aligned16(w) || !aligned16(qw)) QC_FAIL(QC_ERR_ALIGN, "w and qw must be 16-byte aligned");
+  QC_HIP(launch_quantize_weight(w, N, K, bits, qw, w_scale, wsum, static_cast<hipStream_t>(stream)));
+  return QC_OK;
+}
+
+int qc_w8a8_linear(const int8_t *qx, const void *qw, const int32_t *wsum, const float *w_scale, const float *bias,
+                   float x_scale, int x_zp, int M, int N, int K, int weight_bits, float *y, int32_t *acc_or_null,
+                   void *stream) {
+  if (!qx || !qw || !wsum || !w_scale || !y) QC_FAIL(QC_ERR_NULL, "a required pointer is NULL");
+  if (M < 0 || N < 0 || K < 1) QC_FAIL(QC_ERR_SHAPE, "M, N must be non-negative and K positive");
+  if (K % 16) QC_FAIL(QC_ERR_SHAPE, "K (%d) must be a multiple of 16", K);
+  if (weight_bits != 8 && weight_bits != 4) QC_FAIL(QC_ERR_UNSUPPORTED, "weight_bits must be 8 or 4");
+  int rc = check_qparam(x_scale, x_zp);
+  if (rc) return rc;
+  if (!aligned16(qx) || !aligned16(qw)) QC_FAIL(QC_ERR_ALIGN, "qx and qw must be 16-byte aligned");
+  if (M == 0 || N == 0) return QC_OK;
+  GemmArgs a{};
+  a.A = qx; a.W = qw; a.w_scale = w_scale; a.wsum = wsum; a.bias = bias;
+  a.M = M; a.N = N; a.K = K; a.lda = K; a.w4 = weight_bits == 4;
+  a.a_scale = x_scale; a.a_zp = x_zp - 128;
+  a.y = y; a.ldy = N; a.acc_out = acc_or_null;
+  QC_HIP(launch_gemm(a, EPI_F32, 1, static_cast<hipStream_t>(stream)));
+  return QC_OK;
+}
+
+int qc_vc_correct(float *x, const float *K_t, const float *mu_or_null, int B, int C, int H, int W, void *stream) {
+  if (!x || !K_t) QC_FAIL(QC_ERR_NULL, "x or K_t is NULL");
+  if (B < 0 || C < 1 || H < 1 || W < 1) QC_FAIL(QC_ERR_SHAPE, "bad shape");
+  if (B == 0) return QC_OK;
+  QC_HIP(launch_vc(x, K_t, mu_or_null, B, C, H * W, static_cast<hipStream_t>(stream)));
+  return QC_OK;
+}
+
+int qc_ddim_schedule(int steps, int32_t *t, double *abar_t, double *abar_prev) {
+  if (!t || !abar_t || !abar_prev) QC_FAIL(QC_ERR_NULL, "an output array is NULL");
+  if (steps < 1 || steps > 1000) QC_FAIL(QC_ERR_RANGE, "steps must be in 1..1000");
+  double abar[1000];
+  double prod = 1.0;
+  for (int i = 0; i < 1000; ++i) {
+    const double beta = 1e-4 + (2e-2 - 1e-4) * (double)i / 999.0;
+    prod *= 1.0 - beta;
+    abar[i] = prod;
+  }
+  const int stride = 1000 / steps;
+  for (int i = 0; i < steps; ++i) {
+    t[i] = (steps - 1 - i) * stride;
+    abar_t[i] = abar[t[i]];
+  }
+  for (int i = 0; i < steps; ++i) abar_prev[i] = i + 1 < steps ? abar_t[i + 1] : 1.0;
+  return QC_OK;
+}
+
+// ------------------------------------------------------------- DiT pieces
+static int check_ready(const qc_ctx *ctx, int B) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  if (B < 1 || B > ctx->max_batch) QC_FAIL(QC_ERR_SHAPE, "batch %d outside 1..%d", B, ctx->max_batch);
+  if (!ctx->weights_loaded) QC_FAIL(QC_ERR_STATE, "weights were not loaded");
+  for (char s : ctx->qp_set)
+    if (!s) QC_FAIL(QC_ERR_STATE, "activation parameters are not set for every site");
+  return QC_OK;
+}
+
+static float *cache_slot(const qc_ctx *ctx, int block, int which) {
+  return ctx->cache + ((size_t)block * 2 + which) * (size_t)ctx->max_batch * ctx->T * ctx->D;
+}
+
+// adaLN projection of blocks [l0, l0+nl): mod[l, b, :] = Lin_q(codes of SiLU(c)); gates only on request.
+static int run_adaln(qc_ctx *ctx, int l0, int nl, int B, bool gates_only, hipStream_t st) {
+  const size_t D = ctx->D;
+  GemmArgs a{};
+  const LinearQ &q = ctx->blk[l0].lin[QC_SITE_ADA];
+  a.A = ctx->silu_q + (size_t)l0 * ctx->max_batch * D;
+  a.W = q.q; a.w_scale = q.scale; a.wsum = q.wsum; a.bias = q.bias;
+  a.M = B; a.N = (int)(6 * D); a.K = (int)D; a.lda = (int)D; a.w4 = ctx->d.weight_bits == 4;
+  a.a_qp = ctx->dev_qp + (size_t)l0 * QC_NUM_SITES + QC_SITE_ADA;
+  a.zs_A = (long long)ctx->max_batch * D; a.zs_W = (long long)ctx->ada_w_stride_bytes; a.zs_vecN = (long long)(6 * D);
+  a.zs_out = (long long)ctx->max_batch * 6 * D; a.zs_qp = QC_NUM_SITES;
+  a.sel_D = (gates_only && D % 128 == 0) ? (int)D : 0;
+  a.y = ctx->mod + (size_t)l0 * ctx->max_batch * 6 * D; a.ldy = (int)(6 * D);
+  QC_HIP(launch_gemm(a, EPI_F32, nl, st));
+  return QC_OK;
+}
+
+static int run_block_full(qc_ctx *ctx, int l, float *x, int B, hipStream_t st) {
+  const int D = ctx->D, R = ctx->R, T = ctx->T, M = B * T;
+  const float *mod = ctx->mod + (size_t)l * ctx->max_batch * 6 * D;
+  const QParam *qp = ctx->dev_qp + (size_t)l * QC_NUM_SITES;
+  const bool w4 = ctx->d.weight_bits == 4;
+  const BlockQ &bq = ctx->blk[l];
+  auto base = [&](const LinearQ &q, const int8_t *A, int K, int site) {
+    GemmArgs a{};
+    a.A = A; a.W = q.q; a.w_scale = q.scale; a.wsum = q.wsum; a.bias = q.bias;
+    a.M = M; a.N = q.N; a.K = K; a.lda = K; a.w4 = w4; a.a_qp = qp + site;
+    return a;
+  };
+  QC_HIP(launch_ln_mod_quant(x, mod, mod + D, 6 * D, M, D, T, qp + QC_SITE_QKV, ctx->qa_ln, nullptr, st));
+  {
+    GemmArgs a = base(bq.lin[QC_SITE_QKV], ctx->qa_ln, D, QC_SITE_QKV);
+    a.y = ctx->qkv; a.ldy = 3 * D;
+    QC_HIP(launch_gemm(a, EPI_F32, 1, st));
+  }
+  QC_HIP(launch_attention(ctx->qkv, B, T, ctx->H, ctx->hd, qp + QC_SITE_PROJ, ctx->qa_attn, nullptr, st));
+  {
+    GemmArgs a = base(bq.lin[QC_SITE_PROJ], ctx->qa_attn, D, QC_SITE_PROJ);
+    a.cache_out = cache_slot(ctx, l, QC_CACHE_ATTN); a.x = x; a.gate = mod + 2 * D; a.ld_gate = 6 * D; a.rows_per_batch = T;
+    QC_HIP(launch_gemm(a, EPI_RESID, 1, st));
+  }
+  QC_HIP(launch_ln_mod_quant(x, mod + 3 * D, mod + 4 * D, 6 * D, M, D, T, qp + QC_SITE_FC1, ctx->qa_ln, nullptr, st));
+  {
+    GemmArgs a = base(bq.lin[QC_SITE_FC1], ctx->qa_ln, D, QC_SITE_FC1);
+    a.q_out = ctx->qa_mlp; a.ldq = R; a.o_qp = qp + QC_SITE_FC2;
+    QC_HIP(launch_gemm(a, EPI_GELU_Q, 1, st));
+  }
+  {
+    GemmArgs a = base(bq.lin[QC_SITE_FC2], ctx->qa_mlp, R, QC_SITE_FC2);
+    a.cache_out = cache_slot(ctx, l, QC_CACHE_MLP); a.x = x; a.gate = mod + 5 * D; a.ld_gate = 6 * D; a.rows_per_batch = T;
+    QC_HIP(launch_gemm(a, EPI_RESID, 1, st));
+  }
+  ctx->cache_batch[(size_t)l * 2] = B;
+  ctx->cache_batch[(size_t)l * 2 + 1] = B;
+  return QC_OK;
+}
+
+int qc_dit_block(qc_ctx *ctx, int block, int mode, float *x, const float *c, int B, void *stream) {
+  int rc = check_ready(ctx, B);
+  if (rc) return rc;
+  if (block < 0 || block >= ctx->L) QC_FAIL(QC_ERR_RANGE, "block %d outside 0..%d", block, ctx->L - 1);
+  if (mode != QC_FULL && mode != QC_CACHED) QC_FAIL(QC_ERR_RANGE, "mode must be QC_FULL or QC_CACHED");
+  if (!x || !c) QC_FAIL(QC_ERR_NULL, "x or c is NULL");
+  if (!aligned16(x) || !aligned16(c)) QC_FAIL(QC_ERR_ALIGN, "x and c must be 16-byte aligned");
+  if (mode == QC_CACHED && (ctx->cache_batch[(size_t)block * 2] != B || ctx->cache_batch[(size_t)block * 2 + 1] != B))
+    QC_FAIL(QC_ERR_STATE, "block %d has no cached outputs for batch %d", block, B);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const size_t D = ctx->D;
+  QC_HIP(launch_silu_quant(c, B, (int)D, 1, ctx->dev_qp + (size_t)block * QC_NUM_SITES + QC_SITE_ADA, QC_NUM_SITES,
+                           ctx->silu_q + (size_t)block * ctx->max_batch * D, (size_t)ctx->max_batch * D, st));
+  rc = run_adaln(ctx, block, 1, B, mode == QC_CACHED, st);
+  if (rc) return rc;
+  if (mode == QC_FULL) return run_block_full(ctx, block, x, B, st);
+  const float *mod = ctx->mod + (size_t)block * ctx->max_batch * 6 * D;
+  QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, QC_CACHE_ATTN), mod + 2 * D, (int)(6 * D), B, ctx->T, (int)D, st));
+  QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, QC_CACHE_MLP), mod + 5 * D, (int)(6 * D), B, ctx->T, (int)D, st));
+  return QC_OK;
+}
+
+static int check_cache_args(const qc_ctx *ctx, int block, int which, int B) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  if (block < 0 || block >= ctx->L) QC_FAIL(QC_ERR_RANGE, "block %d outside 0..%d", block, ctx->L - 1);
+  if (which != QC_CACHE_ATTN && which != QC_CACHE_MLP) QC_FAIL(QC_ERR_RANGE, "which must be QC_CACHE_ATTN or QC_CACHE_MLP");
+  if (B < 1 || B > ctx->max_batch) QC_FAIL(QC_ERR_SHAPE, "batch %d outside 1..%d", B, ctx->max_batch);
+  return QC_OK;
+}
+
+int qc_cache_store(qc_ctx *ctx, int block, int which, const float *src, int B, void *stream) {
+  int rc = check_cache_args(ctx, block, which, B);
+  if (rc) return rc;
+  if (!src) QC_FAIL(QC_ERR_NULL, "src is NULL");
+  if (!aligned16(src)) QC_FAIL(QC_ERR_ALIGN, "src must be 16-byte aligned");
+  QC_HIP(launch_cache_store(src, cache_slot(ctx, block, which), (size_t)B * ctx->T * ctx->D, static_cast<hipStream_t>(stream)));
+  ctx->cache_batch[(size_t)block * 2 + which] = B;
+  return QC_OK;
+}
+
+int qc_cache_reuse(qc_ctx *ctx, int block, int which, float *x, const float *gate, int ld_gate, int B, void *stream) {
+  int rc = check_cache_args(ctx, block, which, B);
+  if (rc) return rc;
+  if (!x || !gate) QC_FAIL(QC_ERR_NULL, "x or gate is NULL");
+  if (ld_gate < ctx->D || ld_gate % 4) QC_FAIL(QC_ERR_SHAPE, "ld_gate must be >= hidden and a multiple of 4");
+  if (!aligned16(x) || !aligned16(gate)) QC_FAIL(QC_ERR_ALIGN, "x and gate must be 16-byte aligned");
+  if (ctx->cache_batch[(size_t)block * 2 + which] != B)
+    QC_FAIL(QC_ERR_STATE, "block %d holds no cached tensor %d for batch %d", block, which, B);
+  QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, which), gate, ld_gate, B, ctx->T, ctx->D, static_cast<hipStream_t>(stream)));
+  return QC_OK;
+}
+
+int qc_cache_ptr(qc_ctx *ctx, int block, int which, float **ptr_out) {
+  int rc = check_cache_args(ctx, block, which, 1);
+  if (rc) return rc;
+  if (!ptr_out) QC_FAIL(QC_ERR_NULL, "ptr_out is NULL");
+  *ptr_out = cache_slot(ctx, block, which);
+  return QC_OK;
+}
+
+int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out) {
+  if (!ctx || !ptr_out) QC_FAIL(QC_ERR_NULL, "ctx or ptr_out is NULL");
+  const size_t B = ctx->max_batch, M = B * ctx->T, D = ctx->D;
+  void *p = nullptr;
+  size_t n = 0;
+  switch (which) {
+    case QC_WS_TOKENS: p = ctx->tokens; n = M * D * 4; break;
+    case QC_WS_QACT_LN: p = ctx->qa_ln; n = M * D; break;
+    case QC_WS_QACT_ATTN: p = ctx->qa_attn; n = M * D; break;
+    case QC_WS_QACT_MLP: p = ctx->qa_mlp; n = M * ctx->R; break;
+    case QC_WS_QKV: p = ctx->qkv; n = M * 3 * D * 4; break;
+    case QC_WS_MOD: p = ctx->mod; n = (size_t)ctx->L * B * 6 * D * 4; break;
+    case QC_WS_COND: p = ctx->cond; n = B * D * 4; break;
+    case QC_WS_EPS: p = ctx->eps; n = B * ctx->C * ctx->d.latent_h * ctx->d.latent_w * 4; break;
+    default: QC_FAIL(QC_ERR_RANGE, "unknown workspace selector %d", which);
+  }
+  *ptr_out = p;
+  if (bytes_out) *bytes_out = n;
+  return QC_OK;
+}
+
+// conditioning vector c[B, D] for timestep t and the labels (null label for b >= n_labels)
+static int run_conditioning(qc_ctx *ctx, int t, const int32_t *labels, int n_labels, int B, hipStream_t st) {
+  const int D = ctx->D, fd = ctx->d.freq_dim;
+  QC_HIP(launch_time_embed(t, nullptr, 1, fd, ctx->emb, st));
+  QC_HIP(launch_small_linear(ctx->emb, fd, ctx->t_w1, ctx->t_b1, ctx->h1, D, 1, D, fd, 0, 1, st));
+  QC_HIP(launch_small_linear(ctx->h1, D, ctx->t_w2, ctx->t_b2, ctx->te, D, 1, D, D, 0, 0, st));
+  QC_HIP(launch_cond_finish(ctx->te, ctx->label_table, labels, n_labels, ctx->d.num_classes, B, D, ctx->cond, st));
+  return QC_OK;
+}
+
+static int denoise_impl(qc_ctx *ctx, const float *x, int t, const int32_t *labels, int n_labels, int B, int mode,
+                        float *eps_out, hipStream_t st) {
+  const int D = ctx->D, L = ctx->L;
+  int rc = run_conditioning(ctx, t, labels, n_labels, B, st);
+  if (rc) return rc;
+  QC_HIP(launch_silu_quant(ctx->cond, B, D, L, ctx->dev_qp + QC_SITE_ADA, QC_NUM_SITES, ctx->silu_q,
+                           (size_t)ctx->max_batch * D, st));
+  QC_HIP(launch_small_linear(ctx->cond, D, ctx->fada_w, ctx->fada_b, ctx->fmod, 2 * D, B, 2 * D, D, 1, 0, st));
+  rc = run_adaln(ctx, 0, L, B, mode == QC_CACHED, st);
+  if (rc) return rc;
+  QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, B, n_labels, ctx->C, ctx->d.latent_h,
+                      ctx->d.latent_w, ctx->d.patch, D, st));
+  if (mode == QC_FULL) {
+    for (int l = 0; l < L; ++l) {
+      rc = run_block_full(ctx, l, ctx->tokens, B, st);
+      if (rc) return rc;
+    }
+  } else {
+    const size_t slot = (size_t)ctx->max_batch * ctx->T * D;
+    QC_HIP(launch_cached_blocks(ctx->tokens, ctx->cache, 2 * slot, slot, ctx->mod, (size_t)ctx->max_batch * 6 * D, 6 * D, L, B,
+                                ctx->T, D, st));
+  }
+  QC_HIP(launch_final(ctx->tokens, ctx->fmod, ctx->flin_w, ctx->flin_b, eps_out, B, ctx->C, ctx->d.latent_h, ctx->d.latent_w,
+                      ctx->d.patch, D, st));
+  return QC_OK;
+}
+
+static int check_denoise(qc_ctx *ctx, const float *x, const int32_t *labels, int n_labels, int B, int mode) {
+  int rc = check_ready(ctx, B);
+  if (rc) return rc;
+  if (!x || !labels) QC_FAIL(QC_ERR_NULL, "x or labels is NULL");
+  if (n_labels < 1 || (B != n_labels && B != 2 * n_labels))
+    QC_FAIL(QC_ERR_SHAPE, "effective batch %d must be n_labels (%d) or twice that", B, n_labels);
+  if (mode != QC_FULL && mode != QC_CACHED) QC_FAIL(QC_ERR_RANGE, "mode must be QC_FULL or QC_CACHED");
+  if (mode == QC_CACHED)
+    for (int v : ctx->cache_batch)
+      if (v != B) QC_FAIL(QC_ERR_STATE, "cached step requested but the cache does not hold batch %d", B);
+  return QC_OK;
+}
+
+int qc_denoise(qc_ctx *ctx, const float *x, int t, const int32_t *labels, int n_labels, int B, int mode, float *eps_out,
+               void *stream) {
+  int rc = check_denoise(ctx, x, labels, n_labels, B, mode);
+  if (rc) return rc;
+  if (!eps_out) QC_FAIL(QC_ERR_NULL, "eps_out is NULL");
+  if (t < 0) QC_FAIL(QC_ERR_RANGE, "timestep must be non-negative");
+  return denoise_impl(ctx, x, t, labels, n_labels, B, mode, eps_out, static_cast<hipStream_t>(stream));
+}
+
+static int sample_step_impl(qc_ctx *ctx, float *x, const int32_t *labels, int B, int step_index, int t, double abar_t,
+                            double abar_prev, float cfg_scale, const float *K_t, int force_mode, hipStream_t st) {
+  const int Beff = cfg_scale > 0.0f ? 2 * B : B;
+  int mode = force_mode;
+  if (mode < 0) mode = (step_index % ctx->d.cache_interval == 0) ? QC_FULL : QC_CACHED;
+  int rc = check_denoise(ctx, x, labels, B, Beff, mode);
+  if (rc) return rc;
+  rc = denoise_impl(ctx, x, t, labels, B, Beff, mode, ctx->eps, st);
+  if (rc) return rc;
+  const double cx = std::sqrt(abar_prev / abar_t);
+  const double ce = std::sqrt(1.0 - abar_prev) - cx * std::sqrt(1.0 - abar_t);
+  QC_HIP(launch_ddim_vc(x, ctx->eps, B, ctx->C, ctx->d.latent_h * ctx->d.latent_w, (float)cx, (float)ce, cfg_scale, K_t, st));
+  return QC_OK;
+}
+
+int qc_sample_step(qc_ctx *ctx, float *x, const int32_t *labels, int B, int step_index, int t, double abar_t,
+                   double abar_prev, float cfg_scale, const float *K_t, int force_mode, void *stream) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  if (step_index < 0 || t < 0) QC_FAIL(QC_ERR_RANGE, "step index and timestep must be non-negative");
+  if (!(abar_t > 0.0 && abar_t <= 1.0) || !(abar_prev > 0.0 && abar_prev <= 1.0)) QC_FAIL(QC_ERR_RANGE, "abar values must be in (0, 1]");
+  if (force_mode != -1 && force_mode != QC_FULL && force_mode != QC_CACHED) QC_FAIL(QC_ERR_RANGE, "force_mode must be -1, QC_FULL or QC_CACHED");
+  return sample_step_impl(ctx, x, labels, B, step_index, t, abar_t, abar_prev, cfg_scale, K_t, force_mode,
+                          static_cast<hipStream_t>(stream));
+}
+
+int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, float cfg_scale, const float *K, void *stream) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  std::vector<int32_t> t(steps > 0 ? steps : 1);
+  std::vector<double> at(t.size()), ap(t.size());
+  int rc = qc_ddim_schedule(steps, t.data(), at.data(), ap.data());
+  if (rc) return rc;
+  for (int i = 0; i < steps; ++i) {
+    rc = sample_step_impl(ctx, x, labels, B, i, t[i], at[i], ap[i], cfg_scale, K ? K + (size_t)i * ctx->C : nullptr, -1,
+                          static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+  }
+  return QC_OK;
+}
+
+// ------------------------------------------------------------ calibration
+static inline float ord2f(int i) {
+  i ^= (i >> 31) & 0x7FFFFFFF;
+  float f;
+  std::memcpy(&f, &i, 4);
+  return f;
+}
+
+int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, const int32_t *t, const int32_t *y, int n,
+                        void *stream) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  int rc = check_weights(ctx, w);
+  if (rc) return rc;
+  if (!x || !t || !y) QC_FAIL(QC_ERR_NULL, "x, t or y is NULL");
+  if (n < 1) QC_FAIL(QC_ERR_SHAPE, "n must be >= 1");
+  if (!ctx->weights_loaded) QC_FAIL(QC_ERR_STATE, "weights were not loaded");
+  for (int i = 0; i < n; ++i) {
+    if (t[i] < 0) QC_FAIL(QC_ERR_RANGE, "timestep must be non-negative");
+    if (y[i] < 0 || y[i] > ctx->d.num_classes) QC_FAIL(QC_ERR_RANGE, "label %d outside 0..%d", y[i], ctx->d.num_classes);
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int D = ctx->D, R = ctx->R, T = ctx->T, L = ctx->L;
+  const size_t nslots = (size_t)L * QC_NUM_SITES;
+  std::vector<int> init(nslots * 2);
+  for (size_t i = 0; i < nslots; ++i) {
+    init[2 * i] = 0x7FFFFFFF;
+    init[2 * i + 1] = (int)0x80000000;
+  }
+  QC_HIP(hipMemcpyAsync(ctx->cal_slots, init.data(), init.size() * sizeof(int), hipMemcpyHostToDevice, st));
+  QC_HIP(hipStreamSynchronize(st));
+  const size_t lat = (size_t)ctx->C * ctx->d.latent_h * ctx->d.latent_w;
+  for (int i = 0; i < n; ++i) {
+    QC_HIP(hipMemcpyAsync(ctx->cal_label, &y[i], sizeof(int), hipMemcpyHostToDevice, st));
+    QC_HIP(hipStreamSynchronize(st));
+    rc = run_conditioning(ctx, t[i], ctx->cal_label, 1, 1, st);
+    if (rc) return rc;
+    QC_HIP(launch_embed(x + i * lat, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 1, 1, ctx->C, ctx->d.latent_h,
+                        ctx->d.latent_w, ctx->d.patch, D, st));
+    for (int l = 0; l < L; ++l) {
+      const qc_block_weights_f32 &b = w->blocks[l];
+      int *slot = ctx->cal_slots + (size_t)l * QC_NUM_SITES * 2;
+      float *mod = ctx->cal_mod;
+      QC_HIP(launch_minmax_silu(ctx->cond, D, slot + 2 * QC_SITE_ADA, st));
+      QC_HIP(launch_small_linear(ctx->cond, D, b.ada_w, b.ada_b, mod, 6 * D, 1, 6 * D, D, 1, 0, st));
+      QC_HIP(launch_ln_mod_quant(ctx->tokens, mod, mod + D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
+      QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_QKV, st));
+      QC_HIP(launch_linear_f32(ctx->cal_h, b.qkv_w, b.qkv_b, ctx->qkv, T, 3 * D, D, 0, st));
+      QC_HIP(launch_attention(ctx->qkv, 1, T, ctx->H, ctx->hd, nullptr, nullptr, ctx->cal_o, st));
+      QC_HIP(launch_minmax(ctx->cal_o, (size_t)T * D, slot + 2 * QC_SITE_PROJ, st));
+      QC_HIP(launch_linear_f32(ctx->cal_o, b.proj_w, b.proj_b, ctx->cal_a, T, D, D, 0, st));
+      QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 2 * D, 6 * D, 1, T, D, st));
+      QC_HIP(launch_ln_mod_quant(ctx->tokens, mod + 3 * D, mod + 4 * D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
+      QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_FC1, st));
+      QC_HIP(launch_linear_f32(ctx->cal_h, b.fc1_w, b.fc1_b, ctx->cal_u, T, R, D, 2, st));
+      QC_HIP(launch_minmax(ctx->cal_u, (size_t)T * R, slot + 2 * QC_SITE_FC2, st));
+      QC_HIP(launch_linear_f32(ctx->cal_u, b.fc2_w, b.fc2_b, ctx->cal_a, T, D, R, 0, st));
+      QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 5 * D, 6 * D, 1, T, D, st));
+    }
+  }
+  std::vector<int> got(nslots * 2);
+  QC_HIP(hipMemcpyAsync(got.data(), ctx->cal_slots, got.size() * sizeof(int), hipMemcpyDeviceToHost, st));
+  QC_HIP(hipStreamSynchronize(st));
+  for (size_t i = 0; i < nslots; ++i) {
+    // Eq. 2-3 in fp32: range widened to contain 0, s = (u - l) / 255, z = round(-l / s)
+    float lo = std::fmin(ord2f(got[2 * i]), 0.0f), hi = std::fmax(ord2f(got[2 * i + 1]), 0.0f);
+    float s = 1.0f;
+    int z = 0;
+    if (hi > lo) {
+      s = (hi - lo) / 255.0f;
+      float zf = std::nearbyintf(-lo / s);
+      z = (int)std::fmin(std::fmax(zf, 0.0f), 255.0f);
+    }
+    rc = qc_set_act_qparams(ctx, (int)(i / QC_NUM_SITES), (int)(i % QC_NUM_SITES), s, z);
+    if (rc) return rc;
+  }
+  return QC_OK;
+}
+
+}  // extern "C"

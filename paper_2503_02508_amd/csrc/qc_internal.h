@@ -1,0 +1,104 @@
+// Internal declarations shared by the host layer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <vector>
+#include "qc.h"
+
+namespace qc {
+
+// Activation quantiser parameters as the kernels use them: zero point already
+// shifted to the signed code range (paper's z minus 128).
+struct QParam {
+  float s;
+  int z;
+};
+
+// One quantised weight matrix in the arena.
+struct LinearQ {
+  void *q = nullptr;         // int8 [N, K] or packed nibbles [N, K/2]
+  float *scale = nullptr;    // [N]
+  int32_t *wsum = nullptr;   // [N]
+  float *bias = nullptr;     // [N]
+  int N = 0, K = 0;
+};
+
+void set_error(const char *fmt, ...);
+
+// ---- epilogues of the int8 GEMM
+enum Epi { EPI_F32 = 0, EPI_GELU_Q = 1, EPI_RESID = 2 };
+
+struct GemmArgs {
+  const int8_t *A;           // [M, lda] signed codes
+  const void *W;             // [N, K] int8 or [N, K/2] packed
+  const float *w_scale;
+  const int32_t *wsum;
+  const float *bias;         // may be null
+  int M, N, K, lda;
+  int w4;                    // weights are packed nibbles
+  // activation parameters of the input: either by value or from device memory
+  float a_scale;
+  int a_zp;                  // signed
+  const QParam *a_qp;        // if non-null overrides a_scale / a_zp
+  // batching over blockIdx.z (element strides; 0 = shared)
+  long long zs_A, zs_W, zs_vecN, zs_out;   // zs_W in bytes, the others in elements
+  int zs_qp;
+  // subset of output rows: when sel_D > 0 the launch covers 2*sel_D outputs,
+  // logical column j maps to j + 2*sel_D for j < sel_D and j + 4*sel_D otherwise
+  // (the two gate chunks of an adaLN projection).
+  int sel_D;
+  // EPI_F32
+  float *y;
+  int ldy;
+  int32_t *acc_out;          // optional raw accumulators [M, N]
+  // EPI_GELU_Q
+  int8_t *q_out;
+  int ldq;
+  const QParam *o_qp;        // output quantiser
+  // EPI_RESID
+  float *cache_out;          // [M, N]
+  float *x;                  // [M, N] residual stream, updated in place
+  const float *gate;         // [B, ld_gate]
+  int ld_gate;
+  int rows_per_batch;        // T
+};
+
+hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st);
+
+// ---- elementwise / row kernels
+hipError_t launch_quantize_act(const float *x, int8_t *q, size_t n, float s, int z_signed, hipStream_t st);
+hipError_t launch_quantize_weight(const float *w, int N, int K, int bits, void *qw, float *scale, int32_t *wsum,
+                                  hipStream_t st);
+hipError_t launch_ln_mod_quant(const float *x, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
+                               const QParam *qp, int8_t *q, float *f32_out, hipStream_t st);
+hipError_t launch_small_linear(const float *x, int ldx, const float *W, const float *b, float *y, int ldy, int B, int N,
+                               int K, int act_in, int act_out, hipStream_t st);
+hipError_t launch_time_embed(int t, const int32_t *t_arr, int B, int dim, float *out, hipStream_t st);
+hipError_t launch_cond_finish(const float *te, const float *table, const int32_t *labels, int n_labels, int null_label,
+                              int B, int D, float *c, hipStream_t st);
+hipError_t launch_silu_quant(const float *c, int B, int D, int L, const QParam *qp, int qp_stride, int8_t *q,
+                             size_t l_stride, hipStream_t st);
+hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, float *tok, int B, int n_src,
+                        int C, int H, int W, int p, int D, hipStream_t st);
+hipError_t launch_final(const float *tok, const float *fmod, const float *fw, const float *fb, float *eps, int B, int C,
+                        int H, int W, int p, int D, hipStream_t st);
+hipError_t launch_cache_store(const float *src, float *dst, size_t n, hipStream_t st);
+hipError_t launch_cache_reuse(float *x, const float *cached, const float *gate, int ld_gate, int B, int T, int D,
+                              hipStream_t st);
+hipError_t launch_cached_blocks(float *x, const float *cache, size_t cache_block_stride, size_t cache_which_stride,
+                                const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D,
+                                hipStream_t st);
+hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, float cx, float ce, float cfg_scale,
+                          const float *K_t, hipStream_t st);
+hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, int HW, hipStream_t st);
+hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const QParam *qp, int8_t *q_out, float *f32_out,
+                            hipStream_t st);
+// calibration helpers
+hipError_t launch_linear_f32(const float *x, const float *W, const float *b, float *y, int M, int N, int K, int act_out,
+                             hipStream_t st);
+hipError_t launch_minmax(const float *x, size_t n, int *slot, hipStream_t st);
+hipError_t launch_minmax_silu(const float *x, size_t n, int *slot, hipStream_t st);
+hipError_t launch_fill_i32(int *p, size_t n, int v, hipStream_t st);
+
+}  // namespace qc

@@ -1,0 +1,598 @@
+// Bandwidth-bound kernels of the sampler step: activation / weight quantisers,
+// LayerNorm + adaLN modulation + quantise, conditioning, patch embedding, final
+// layer, cache store / reuse, DDIM update + variance compensation.
+// One wavefront is 64 lanes; row reductions use cross-lane shuffles only.
+#include "qc_internal.h"
+
+namespace qc {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
+__device__ __forceinline__ float gelu_f(float v) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  return 0.5f * v * (1.0f + tanhf(k0 * (v + k1 * v * v * v)));
+}
+// Eq. 1 on signed codes: clip(round(v / s) + z, -128, 127), z already shifted.
+__device__ __forceinline__ int quant_code(float v, float s, int z) {
+  float r = rintf(v / s) + (float)z;
+  return (int)fminf(fmaxf(r, -128.0f), 127.0f);
+}
+__device__ __forceinline__ unsigned pack4(int a, int b, int c, int d) {
+  return (unsigned)(a & 0xFF) | ((unsigned)(b & 0xFF) << 8) | ((unsigned)(c & 0xFF) << 16) | ((unsigned)(d & 0xFF) << 24);
+}
+
+// ------------------------------------------------------------ quantize_act
+__global__ __launch_bounds__(256) void quantize_act_kernel(const float *__restrict__ x, int8_t *__restrict__ q, size_t n,
+                                                           float s, int z) {
+  const size_t n4 = n >> 2;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    float4 v = ((const float4 *)x)[i];
+    ((unsigned *)q)[i] = pack4(quant_code(v.x, s, z), quant_code(v.y, s, z), quant_code(v.z, s, z), quant_code(v.w, s, z));
+  }
+  if (blockIdx.x == 0) {
+    size_t i = (n4 << 2) + threadIdx.x;
+    if (i < n) q[i] = (int8_t)quant_code(x[i], s, z);
+  }
+}
+
+hipError_t launch_quantize_act(const float *x, int8_t *q, size_t n, float s, int z, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  size_t blocks = ((n >> 2) + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(quantize_act_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, q, n, s, z);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------- quantize_weight
+// One wavefront per output row: max |w|, scale, codes, row sum.
+__global__ __launch_bounds__(256) void quantize_weight_kernel(const float *__restrict__ w, int N, int K, int bits,
+                                                              unsigned char *__restrict__ qw, float *__restrict__ scale,
+                                                              int32_t *__restrict__ wsum) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  const float *row = w + (size_t)n * K;
+  float amax = 0.0f;
+  for (int k = lane; k < K; k += 64) amax = fmaxf(amax, fabsf(row[k]));
+  amax = wave_max(amax);
+  const float qmax = (float)((1 << (bits - 1)) - 1);
+  const float s = amax > 0.0f ? amax / qmax : 1.0f;
+  int sum = 0;
+  for (int k = 2 * lane; k < K; k += 128) {
+    float2 v = *(const float2 *)(row + k);
+    int q0 = (int)fminf(fmaxf(rintf(v.x / s), -qmax), qmax);
+    int q1 = (int)fminf(fmaxf(rintf(v.y / s), -qmax), qmax);
+    sum += q0 + q1;
+    if (bits == 4) {
+      qw[(size_t)n * (K >> 1) + (k >> 1)] = (unsigned char)((q0 & 0xF) | ((q1 & 0xF) << 4));
+    } else {
+      *(unsigned short *)(qw + (size_t)n * K + k) = (unsigned short)((q0 & 0xFF) | ((q1 & 0xFF) << 8));
+    }
+  }
+  sum = wave_sum_i(sum);
+  if (lane == 0) {
+    scale[n] = s;
+    wsum[n] = sum;
+  }
+}
+
+hipError_t launch_quantize_weight(const float *w, int N, int K, int bits, void *qw, float *scale, int32_t *wsum,
+                                  hipStream_t st) {
+  hipLaunchKernelGGL(quantize_weight_kernel, dim3((N + 3) / 4), dim3(256), 0, st, w, N, K, bits, (unsigned char *)qw, scale,
+                     wsum);
+  return hipGetLastError();
+}
+
+// ------------------------------------------- LayerNorm + modulate + quantise
+// One wavefront per token row; the row lives in registers (D <= 2048).
+constexpr int LN_MAX_IT = 8;
+
+__global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restrict__ x, const float *__restrict__ shift,
+                                                           const float *__restrict__ scale, int ld_mod, int M, int D, int T,
+                                                           const QParam *qp, int8_t *__restrict__ q,
+                                                           float *__restrict__ f32_out) {
+  const int lane = threadIdx.x & 63;
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= M) return;
+  const float *row = x + (size_t)m * D;
+  float4 v[LN_MAX_IT];
+  float sum = 0.0f;
+#pragma unroll
+  for (int it = 0; it < LN_MAX_IT; ++it) {
+    const int k = (lane + 64 * it) * 4;
+    if (k < D) {
+      v[it] = *(const float4 *)(row + k);
+      sum += (v[it].x + v[it].y) + (v[it].z + v[it].w);
+    }
+  }
+  const float mean = wave_sum(sum) / (float)D;
+  float sq = 0.0f;
+#pragma unroll
+  for (int it = 0; it < LN_MAX_IT; ++it) {
+    const int k = (lane + 64 * it) * 4;
+    if (k < D) {
+      float a = v[it].x - mean, b = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
+      sq += (a * a + b * b) + (c * c + d * d);
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + 1e-6f);
+  const int b = m / T;
+  const float *sh = shift + (size_t)b * ld_mod, *sc = scale + (size_t)b * ld_mod;
+  float qs = 1.0f;
+  int qz = 0;
+  if (qp) {
+    QParam t = *qp;
+    qs = t.s;
+    qz = t.z;
+  }
+#pragma unroll
+  for (int it = 0; it < LN_MAX_IT; ++it) {
+    const int k = (lane + 64 * it) * 4;
+    if (k < D) {
+      float4 s4 = *(const float4 *)(sh + k), c4 = *(const float4 *)(sc + k);
+      float h0 = (v[it].x - mean) * rstd * (1.0f + c4.x) + s4.x;
+      float h1 = (v[it].y - mean) * rstd * (1.0f + c4.y) + s4.y;
+      float h2 = (v[it].z - mean) * rstd * (1.0f + c4.z) + s4.z;
+      float h3 = (v[it].w - mean) * rstd * (1.0f + c4.w) + s4.w;
+      if (q)
+        *(unsigned *)(q + (size_t)m * D + k) =
+            pack4(quant_code(h0, qs, qz), quant_code(h1, qs, qz), quant_code(h2, qs, qz), quant_code(h3, qs, qz));
+      if (f32_out) *(float4 *)(f32_out + (size_t)m * D + k) = make_float4(h0, h1, h2, h3);
+    }
+  }
+}
+
+hipError_t launch_ln_mod_quant(const float *x, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
+                               const QParam *qp, int8_t *q, float *f32_out, hipStream_t st) {
+  hipLaunchKernelGGL(ln_mod_quant_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q,
+                     f32_out);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------- small fp32 linear (M = B)
+// y[b, n] = act_out(W[n, :] . act_in(x[b, :]) + bias[n]); one wavefront per n.
+__global__ __launch_bounds__(256) void small_linear_kernel(const float *__restrict__ x, int ldx, const float *__restrict__ W,
+                                                           const float *__restrict__ bias, float *__restrict__ y, int ldy,
+                                                           int B, int N, int K, int act_in, int act_out) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  const float *wr = W + (size_t)n * K;
+  for (int b0 = 0; b0 < B; b0 += 8) {
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+    for (int k = lane; k < K; k += 64) {
+      const float wv = wr[k];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (b0 + i < B) {
+          float xv = x[(size_t)(b0 + i) * ldx + k];
+          if (act_in == 1) xv = silu_f(xv);
+          acc[i] = fmaf(wv, xv, acc[i]);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (b0 + i < B) {
+        float r = wave_sum(acc[i]) + (bias ? bias[n] : 0.0f);
+        if (act_out == 1) r = silu_f(r);
+        if (lane == 0) y[(size_t)(b0 + i) * ldy + n] = r;
+      }
+    }
+  }
+}
+
+hipError_t launch_small_linear(const float *x, int ldx, const float *W, const float *b, float *y, int ldy, int B, int N,
+                               int K, int act_in, int act_out, hipStream_t st) {
+  hipLaunchKernelGGL(small_linear_kernel, dim3((N + 3) / 4), dim3(256), 0, st, x, ldx, W, b, y, ldy, B, N, K, act_in,
+                     act_out);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------- conditioning
+// Sinusoidal timestep embedding [cos | sin], frequencies exp(-ln(1e4) j / half),
+// evaluated in double so that the fp32 result is correctly rounded.
+__global__ void time_embed_kernel(int t, int B, int dim, float *__restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * dim) return;
+  const int j = i % dim, half = dim / 2;
+  const int f = j < half ? j : j - half;
+  const double a = (double)t * exp(-log(10000.0) * (double)f / (double)half);
+  out[i] = (float)(j < half ? cos(a) : sin(a));
+}
+
+hipError_t launch_time_embed(int t, const int32_t *, int B, int dim, float *out, hipStream_t st) {
+  hipLaunchKernelGGL(time_embed_kernel, dim3((B * dim + 255) / 256), dim3(256), 0, st, t, B, dim, out);
+  return hipGetLastError();
+}
+
+__global__ void cond_finish_kernel(const float *__restrict__ te, const float *__restrict__ table,
+                                   const int32_t *__restrict__ labels, int n_labels, int null_label, int B, int D,
+                                   float *__restrict__ c) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * D) return;
+  const int b = i / D, n = i % D;
+  const int y = b < n_labels ? labels[b] : null_label;
+  c[i] = te[n] + table[(size_t)y * D + n];   // one timestep per call: te is a single row
+}
+
+hipError_t launch_cond_finish(const float *te, const float *table, const int32_t *labels, int n_labels, int null_label,
+                              int B, int D, float *c, hipStream_t st) {
+  hipLaunchKernelGGL(cond_finish_kernel, dim3((B * D + 255) / 256), dim3(256), 0, st, te, table, labels, n_labels,
+                     null_label, B, D, c);
+  return hipGetLastError();
+}
+
+// codes of SiLU(c) for the adaLN site of every block: q[l, b, n]
+__global__ void silu_quant_kernel(const float *__restrict__ c, int BD, int L, const QParam *qp, int qp_stride,
+                                  int8_t *__restrict__ q, size_t l_stride) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= BD) return;
+  const float v = silu_f(c[i]);
+  for (int l = 0; l < L; ++l) {
+    QParam t = qp[(size_t)l * qp_stride];
+    q[(size_t)l * l_stride + i] = (int8_t)quant_code(v, t.s, t.z);
+  }
+}
+
+hipError_t launch_silu_quant(const float *c, int B, int D, int L, const QParam *qp, int qp_stride, int8_t *q,
+                             size_t l_stride, hipStream_t st) {
+  hipLaunchKernelGGL(silu_quant_kernel, dim3((B * D + 255) / 256), dim3(256), 0, st, c, B * D, L, qp, qp_stride, q,
+                     l_stride);
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------- patch embedding
+// tok[b, t, n] = sum_f pw[n, f] * patch(b, t)[f] + pb[n] + pos[t, n], features f = (c, ph, pw).
+__global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x, const float *__restrict__ pw,
+                                                    const float *__restrict__ pb, const float *__restrict__ pos,
+                                                    float *__restrict__ tok, int n_src, int C, int H, int W, int p, int D) {
+  __shared__ float patch[256];
+  const int gw = W / p, T = (H / p) * gw;
+  const int bt = blockIdx.x, b = bt / T, t = bt % T;
+  const int F = C * p * p;
+  const int ty = t / gw, tx = t % gw;
+  const float *src = x + (size_t)(b % n_src) * C * H * W;
+  for (int f = threadIdx.x; f < F; f += blockDim.x) {
+    const int c = f / (p * p), ph = (f / p) % p, pq = f % p;
+    patch[f] = src[((size_t)c * H + ty * p + ph) * W + tx * p + pq];
+  }
+  __syncthreads();
+  for (int n = threadIdx.x; n < D; n += blockDim.x) {
+    float acc = 0.0f;
+    for (int f = 0; f < F; ++f) acc = fmaf(pw[(size_t)n * F + f], patch[f], acc);
+    tok[(size_t)bt * D + n] = acc + pb[n] + pos[(size_t)t * D + n];
+  }
+}
+
+hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, float *tok, int B, int n_src,
+                        int C, int H, int W, int p, int D, hipStream_t st) {
+  const int T = (H / p) * (W / p);
+  hipLaunchKernelGGL(embed_kernel, dim3(B * T), dim3(256), 0, st, x, pw, pb, pos, tok, n_src, C, H, W, p, D);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- final layer
+// Per token: LayerNorm, modulate with (shift, scale) = fmod[b, 0:D], fmod[b, D:2D],
+// dot with the rows of the output linear that belong to the first C of the 2C
+// channels, and scatter to eps[b, c, ty*p+ph, tx*p+pw] (output features (ph, pw, c)).
+__global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ tok, const float *__restrict__ fmod,
+                                                    const float *__restrict__ fw, const float *__restrict__ fb,
+                                                    float *__restrict__ eps, int M, int C, int H, int W, int p, int D) {
+  const int lane = threadIdx.x & 63;
+  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= M) return;
+  const int gw = W / p, T = (H / p) * gw;
+  const int b = m / T, t = m % T, ty = t / gw, tx = t % gw;
+  const float *row = tok + (size_t)m * D;
+  float4 v[LN_MAX_IT];
+  float sum = 0.0f;
+#pragma unroll
+  for (int it = 0; it < LN_MAX_IT; ++it) {
+    const int k = (lane + 64 * it) * 4;
+    if (k < D) {
+      v[it] = *(const float4 *)(row + k);
+      sum += (v[it].x + v[it].y) + (v[it].z + v[it].w);
+    }
+  }
+  const float mean = wave_sum(sum) / (float)D;
+  float sq = 0.0f;
+#pragma unroll
+  for (int it = 0; it < LN_MAX_IT; ++it) {
+    const int k = (lane + 64 * it) * 4;
+    if (k < D) {
+      float a = v[it].x - mean, bq = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
+      sq += (a * a + bq * bq) + (c * c + d * d);
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + 1e-6f);
+  const float *sh = fmod + (size_t)b * 2 * D, *sc = sh + D;
+#pragma unroll
+  for (int it = 0; it < LN_MAX_IT; ++it) {
+    const int k = (lane + 64 * it) * 4;
+    if (k < D) {
+      float4 s4 = *(const float4 *)(sh + k), c4 = *(const float4 *)(sc + k);
+      v[it].x = (v[it].x - mean) * rstd * (1.0f + c4.x) + s4.x;
+      v[it].y = (v[it].y - mean) * rstd * (1.0f + c4.y) + s4.y;
+      v[it].z = (v[it].z - mean) * rstd * (1.0f + c4.z) + s4.z;
+      v[it].w = (v[it].w - mean) * rstd * (1.0f + c4.w) + s4.w;
+    }
+  }
+  for (int pp = 0; pp < p * p; ++pp) {
+    for (int c = 0; c < C; ++c) {
+      const int o = pp * 2 * C + c;
+      const float *wr = fw + (size_t)o * D;
+      float acc = 0.0f;
+#pragma unroll
+      for (int it = 0; it < LN_MAX_IT; ++it) {
+        const int k = (lane + 64 * it) * 4;
+        if (k < D) {
+          float4 w4 = *(const float4 *)(wr + k);
+          acc += (v[it].x * w4.x + v[it].y * w4.y) + (v[it].z * w4.z + v[it].w * w4.w);
+        }
+      }
+      acc = wave_sum(acc) + fb[o];
+      if (lane == 0) eps[(((size_t)b * C + c) * H + ty * p + pp / p) * W + tx * p + pp % p] = acc;
+    }
+  }
+}
+
+hipError_t launch_final(const float *tok, const float *fmod, const float *fw, const float *fb, float *eps, int B, int C,
+                        int H, int W, int p, int D, hipStream_t st) {
+  const int M = B * (H / p) * (W / p);
+  hipLaunchKernelGGL(final_kernel, dim3((M + 3) / 4), dim3(256), 0, st, tok, fmod, fw, fb, eps, M, C, H, W, p, D);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- cache ops
+__global__ __launch_bounds__(256) void copy_kernel(const float4 *__restrict__ s, float4 *__restrict__ d, size_t n4) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) d[i] = s[i];
+}
+
+hipError_t launch_cache_store(const float *src, float *dst, size_t n, hipStream_t st) {
+  size_t n4 = n / 4, blocks = (n4 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float4 *)src, (float4 *)dst, n4);
+  return hipGetLastError();
+}
+
+// x[b, t, :] += gate[b, :] * cached[b, t, :]
+__global__ __launch_bounds__(256) void cache_reuse_kernel(float *__restrict__ x, const float *__restrict__ cached,
+                                                          const float *__restrict__ gate, int ld_gate, size_t n4, int TD4,
+                                                          int D4) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  const int b = (int)(i / TD4), n = (int)(i % D4) * 4;
+  float4 xv = ((float4 *)x)[i], cv = ((const float4 *)cached)[i];
+  float4 g = *(const float4 *)(gate + (size_t)b * ld_gate + n);
+  xv.x = xv.x + g.x * cv.x;
+  xv.y = xv.y + g.y * cv.y;
+  xv.z = xv.z + g.z * cv.z;
+  xv.w = xv.w + g.w * cv.w;
+  ((float4 *)x)[i] = xv;
+}
+
+hipError_t launch_cache_reuse(float *x, const float *cached, const float *gate, int ld_gate, int B, int T, int D,
+                              hipStream_t st) {
+  const size_t n4 = (size_t)B * T * D / 4;
+  hipLaunchKernelGGL(cache_reuse_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, x, cached, gate, ld_gate, n4,
+                     T * D / 4, D / 4);
+  return hipGetLastError();
+}
+
+// All blocks of a cached step in one pass over x: for every block in order,
+// x += gate_msa * attn_cached; x += gate_mlp * mlp_cached (same association
+// as block after block).  mod[l, b, 6D] holds the gates in chunks 2 and 5.
+__global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ x, const float *__restrict__ cache,
+                                                            size_t cache_block_stride, size_t cache_which_stride,
+                                                            const float *__restrict__ mod, size_t mod_block_stride,
+                                                            int ld_mod, int L, size_t n4, int TD4, int D4, int D) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  const int b = (int)(i / TD4), n = (int)(i % D4) * 4;
+  float4 xv = ((float4 *)x)[i];
+  for (int l = 0; l < L; ++l) {
+    const float *mrow = mod + (size_t)l * mod_block_stride + (size_t)b * ld_mod + n;
+    const float4 g1 = *(const float4 *)(mrow + 2 * D), g2 = *(const float4 *)(mrow + 5 * D);
+    const float4 a = ((const float4 *)(cache + (size_t)l * cache_block_stride))[i];
+    const float4 mo = ((const float4 *)(cache + (size_t)l * cache_block_stride + cache_which_stride))[i];
+    xv.x = xv.x + g1.x * a.x; xv.y = xv.y + g1.y * a.y; xv.z = xv.z + g1.z * a.z; xv.w = xv.w + g1.w * a.w;
+    xv.x = xv.x + g2.x * mo.x; xv.y = xv.y + g2.y * mo.y; xv.z = xv.z + g2.z * mo.z; xv.w = xv.w + g2.w * mo.w;
+  }
+  ((float4 *)x)[i] = xv;
+}
+
+hipError_t launch_cached_blocks(float *x, const float *cache, size_t cache_block_stride, size_t cache_which_stride,
+                                const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D,
+                                hipStream_t st) {
+  const size_t n4 = (size_t)B * T * D / 4;
+  hipLaunchKernelGGL(cached_blocks_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, x, cache,
+                     cache_block_stride, cache_which_stride, mod, mod_block_stride, ld_mod, L, n4, T * D / 4, D / 4, D);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------- DDIM update + guidance + VC
+__device__ __forceinline__ float block_sum_256(float v, float *red) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[w] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// One workgroup per (latent, channel) plane.  xhat = cx*x + ce*eps is DDIM with
+// eta = 0 (cx = sqrt(abar_prev/abar_t), ce = sqrt(1-abar_prev) - cx*sqrt(1-abar_t));
+// then Eq. 10 with mu = plane mean: x~ = xhat + (K-1)(xhat - mu).
+__global__ __launch_bounds__(256) void ddim_vc_kernel(float *__restrict__ x, const float *__restrict__ eps, int B, int C,
+                                                      int HW, float cx, float ce, float cfg, const float *__restrict__ K_t) {
+  __shared__ float red[4];
+  const int plane = blockIdx.x, c = plane % C;
+  float *xp = x + (size_t)plane * HW;
+  const float *ec = eps + (size_t)plane * HW;
+  const float *eu = eps + ((size_t)B * C + plane) * HW;
+  float sum = 0.0f;
+  for (int i = threadIdx.x; i < HW; i += 256) {
+    float e = ec[i];
+    if (cfg > 0.0f) {
+      const float u = eu[i];
+      e = u + cfg * (e - u);
+    }
+    const float xh = cx * xp[i] + ce * e;
+    xp[i] = xh;
+    sum += xh;
+  }
+  if (!K_t) return;
+  const float mu = block_sum_256(sum, red) / (float)HW;
+  const float km1 = K_t[c] - 1.0f;
+  for (int i = threadIdx.x; i < HW; i += 256) {
+    const float xh = xp[i];
+    xp[i] = xh + km1 * (xh - mu);
+  }
+}
+
+hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, float cx, float ce, float cfg_scale,
+                          const float *K_t, hipStream_t st) {
+  hipLaunchKernelGGL(ddim_vc_kernel, dim3(B * C), dim3(256), 0, st, x, eps, B, C, HW, cx, ce, cfg_scale, K_t);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void vc_kernel(float *__restrict__ x, const float *__restrict__ K_t,
+                                                 const float *__restrict__ mu_in, int C, int HW) {
+  __shared__ float red[4];
+  const int plane = blockIdx.x, c = plane % C;
+  float *xp = x + (size_t)plane * HW;
+  float mu;
+  if (mu_in) {
+    mu = mu_in[c];
+  } else {
+    float sum = 0.0f;
+    for (int i = threadIdx.x; i < HW; i += 256) sum += xp[i];
+    mu = block_sum_256(sum, red) / (float)HW;
+  }
+  const float km1 = K_t[c] - 1.0f;
+  for (int i = threadIdx.x; i < HW; i += 256) {
+    const float v = xp[i];
+    xp[i] = v + km1 * (v - mu);
+  }
+}
+
+hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, int HW, hipStream_t st) {
+  hipLaunchKernelGGL(vc_kernel, dim3(B * C), dim3(256), 0, st, x, K_t, mu, C, HW);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------ calibration helpers
+// Plain fp32 tiled linear y = act(x W^T + b): 64x64 tile, 16-deep slabs, 4x4 per thread.
+__global__ __launch_bounds__(256) void linear_f32_kernel(const float *__restrict__ x, const float *__restrict__ W,
+                                                         const float *__restrict__ bias, float *__restrict__ y, int M, int N,
+                                                         int K, int act_out) {
+  __shared__ float sx[16][65], sw[16][65];
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+      const int r = i / 16, k = i % 16;
+      sx[k][r] = (m0 + r < M && k0 + k < K) ? x[(size_t)(m0 + r) * K + k0 + k] : 0.0f;
+      sw[k][r] = (n0 + r < N && k0 + k < K) ? W[(size_t)(n0 + r) * K + k0 + k] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = sx[k][ty * 4 + i], b[i] = sw[k][tx * 4 + i];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j) {
+      const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < M && n < N) {
+        float v = acc[i][j] + (bias ? bias[n] : 0.0f);
+        if (act_out == 2) v = gelu_f(v);
+        y[(size_t)m * N + n] = v;
+      }
+    }
+}
+
+hipError_t launch_linear_f32(const float *x, const float *W, const float *b, float *y, int M, int N, int K, int act_out,
+                             hipStream_t st) {
+  hipLaunchKernelGGL(linear_f32_kernel, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), 0, st, x, W, b, y, M, N, K, act_out);
+  return hipGetLastError();
+}
+
+// Running min / max of a tensor kept as order-preserving integers:
+// slot[0] = min, slot[1] = max; act = 1 takes SiLU of the values first.
+__device__ __forceinline__ int f2ord(float f) {
+  int i = __float_as_int(f);
+  return i ^ ((i >> 31) & 0x7FFFFFFF);
+}
+__global__ __launch_bounds__(256) void minmax_kernel(const float *__restrict__ x, size_t n, int act, int *slot) {
+  float lo = INFINITY, hi = -INFINITY;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    float v = x[i];
+    if (act == 1) v = silu_f(v);
+    lo = fminf(lo, v);
+    hi = fmaxf(hi, v);
+  }
+  hi = wave_max(hi);
+  lo = -wave_max(-lo);
+  if ((threadIdx.x & 63) == 0 && lo <= hi) {
+    atomicMin(slot, f2ord(lo));
+    atomicMax(slot + 1, f2ord(hi));
+  }
+}
+
+hipError_t launch_minmax(const float *x, size_t n, int *slot, hipStream_t st) {
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 1024) blocks = 1024;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(minmax_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, n, 0, slot);
+  return hipGetLastError();
+}
+hipError_t launch_minmax_silu(const float *x, size_t n, int *slot, hipStream_t st) {
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 1024) blocks = 1024;
+  if (blocks == 0) return hipSuccess;
+  hipLaunchKernelGGL(minmax_kernel, dim3((unsigned)blocks), dim3(256), 0, st, x, n, 1, slot);
+  return hipGetLastError();
+}
+
+__global__ void fill_i32_kernel(int *p, size_t n, int v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+hipError_t launch_fill_i32(int *p, size_t n, int v, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
+  return hipGetLastError();
+}
+
+}  // namespace qc

@@ -1,0 +1,124 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before touching a
+device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import sampler as OS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def qc():
+    import paper_2503_02508_amd as m
+    return m
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "qc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(qc):
+    names = _declared()
+    assert len(names) >= 20 and "qc_sample_step" in names and "qc_w8a8_linear" in names
+    for n in names:
+        assert hasattr(qc.lib, n), n
+
+
+def _desc(qc, **kw):
+    d = dict(depth=2, hidden=64, heads=4, mlp_dim=128, patch=2, latent_c=4, latent_h=8, latent_w=8, num_classes=10,
+             freq_dim=256, weight_bits=8, cache_interval=2)
+    d.update(kw)
+    return qc.ModelDesc(**d)
+
+
+def test_arena_bytes_and_bad_descriptions(qc):
+    n = C.c_size_t()
+    assert qc.lib.qc_arena_bytes(C.byref(_desc(qc)), 4, C.byref(n)) == 0 and n.value > 0
+    small = n.value
+    assert qc.lib.qc_arena_bytes(C.byref(_desc(qc)), 8, C.byref(n)) == 0 and n.value > small
+    for kw, code in [(dict(hidden=62), -2), (dict(hidden=72), -7), (dict(depth=0), -2), (dict(latent_h=7), -2), (dict(weight_bits=3), -7),
+                     (dict(cache_interval=0), -4), (dict(hidden=4096, heads=64), -7), (dict(heads=1, hidden=128), -7),
+                     (dict(freq_dim=255), -2)]:
+        assert qc.lib.qc_arena_bytes(C.byref(_desc(qc, **kw)), 4, C.byref(n)) == code, kw
+        assert qc.last_error()
+    assert qc.lib.qc_arena_bytes(C.byref(_desc(qc)), 0, C.byref(n)) == -2
+    assert qc.lib.qc_arena_bytes(None, 4, C.byref(n)) == -1
+    assert qc.lib.qc_arena_bytes(C.byref(_desc(qc)), 4, None) == -1
+
+
+def test_create_rejects_bad_arenas_without_a_device(qc):
+    h = C.c_void_p()
+    d = _desc(qc)
+    assert qc.lib.qc_create(C.byref(d), None, 1 << 30, 4, C.byref(h)) == -1
+    assert qc.lib.qc_create(C.byref(d), C.c_void_p(0x1000 + 8), 1 << 30, 4, C.byref(h)) == -3
+    assert qc.lib.qc_create(C.byref(d), C.c_void_p(0x1000), 1024, 4, C.byref(h)) == -6
+    assert "needed" in qc.last_error()
+    assert qc.lib.qc_create(C.byref(d), C.c_void_p(0x1000), 1 << 30, 4, None) == -1
+    assert qc.lib.qc_destroy(None) == -1
+
+
+def test_context_state_checks_without_a_device(qc):
+    """A context over a fake (never dereferenced) arena: every call must fail on its checks."""
+    d = _desc(qc)
+    n = C.c_size_t()
+    qc.lib.qc_arena_bytes(C.byref(d), 2, C.byref(n))
+    h = C.c_void_p()
+    assert qc.lib.qc_create(C.byref(d), C.c_void_p(0x100000), n.value, 2, C.byref(h)) == 0
+    fake = C.c_void_p(0x200000)
+    assert qc.lib.qc_set_act_qparams(h, 5, 0, 1.0, 0) == -4
+    assert qc.lib.qc_set_act_qparams(h, 0, 7, 1.0, 0) == -4
+    assert qc.lib.qc_set_act_qparams(h, 0, 0, 0.0, 0) == -4
+    assert qc.lib.qc_set_act_qparams(h, 0, 0, 1.0, 300) == -4
+    s, z = C.c_float(), C.c_int()
+    assert qc.lib.qc_get_act_qparams(h, 0, 0, C.byref(s), C.byref(z)) == -5
+    # weights not loaded / parameters not set -> state error before any launch
+    assert qc.lib.qc_dit_block(h, 0, 0, fake, fake, 1, None) == -5
+    assert qc.lib.qc_dit_block(h, 0, 0, fake, fake, 3, None) == -2          # batch above max_batch
+    assert qc.lib.qc_denoise(h, fake, 10, fake, 1, 1, 0, fake, None) == -5
+    assert qc.lib.qc_sample_step(h, fake, fake, 1, 0, 10, 0.5, 0.6, 0.0, None, -1, None) == -5
+    assert qc.lib.qc_sample_step(h, fake, fake, 1, 0, 10, 0.0, 0.6, 0.0, None, -1, None) == -4
+    assert qc.lib.qc_sample_step(h, fake, fake, 1, -1, 10, 0.5, 0.6, 0.0, None, -1, None) == -4
+    assert qc.lib.qc_sample_step(h, fake, fake, 1, 0, 10, 0.5, 0.6, 0.0, None, 3, None) == -4
+    assert qc.lib.qc_cache_store(h, 0, 2, fake, 1, None) == -4
+    assert qc.lib.qc_cache_store(h, 9, 0, fake, 1, None) == -4
+    assert qc.lib.qc_cache_reuse(h, 0, 0, fake, fake, 64, 1, None) == -5        # nothing stored
+    assert qc.lib.qc_cache_reuse(h, 0, 0, fake, fake, 10, 1, None) == -2
+    p = C.c_void_p()
+    assert qc.lib.qc_cache_ptr(h, 1, 1, C.byref(p)) == 0 and p.value >= 0x100000
+    assert qc.lib.qc_workspace_ptr(h, 99, C.byref(p), None) == -4
+    assert qc.lib.qc_destroy(h) == 0
+
+
+def test_single_op_argument_checks_without_a_device(qc):
+    f = C.c_void_p(0x1000)
+    assert qc.lib.qc_quantize_act(None, f, 4, 1.0, 0, None) == -1
+    assert qc.lib.qc_quantize_act(C.c_void_p(0x1004), f, 4, 1.0, 0, None) == -3
+    assert qc.lib.qc_quantize_act(f, f, 4, -1.0, 0, None) == -4
+    assert qc.lib.qc_quantize_act(f, f, 0, 1.0, 0, None) == 0                   # empty input: nothing to do
+    assert qc.lib.qc_w8a8_linear(f, f, f, f, None, 1.0, 0, 4, 4, 24, 8, f, None, None) == -2
+    assert qc.lib.qc_w8a8_linear(f, f, f, f, None, 1.0, 0, 0, 4, 32, 8, f, None, None) == 0   # M = 0
+    assert qc.lib.qc_w8a8_linear(f, f, f, f, None, 1.0, 0, -1, 4, 32, 8, f, None, None) == -2
+    assert qc.lib.qc_w8a8_linear(f, C.c_void_p(0x1001), f, f, None, 1.0, 0, 4, 4, 32, 8, f, None, None) == -3
+    assert qc.lib.qc_quantize_weight(f, 4, 20, 8, f, f, f, None) == -2
+    assert qc.lib.qc_quantize_weight(f, 4, 32, 2, f, f, f, None) == -7
+    assert qc.lib.qc_vc_correct(None, f, None, 1, 4, 8, 8, None) == -1
+    assert qc.lib.qc_vc_correct(f, f, None, 0, 4, 8, 8, None) == 0
+    assert qc.lib.qc_vc_correct(f, f, None, 1, 0, 8, 8, None) == -2
+
+
+@pytest.mark.parametrize("steps", [50, 100, 250, 7, 1])
+def test_ddim_schedule_matches_oracle(qc, steps):
+    t, a, b = qc.qc_ddim_schedule(steps)
+    tt, at, ap = OS.ddim_schedule(steps)
+    assert t == list(tt)
+    assert np.allclose(a, at, rtol=1e-13) and np.allclose(b, ap, rtol=1e-13)
+    with pytest.raises(qc.QCError):
+        qc.qc_ddim_schedule(0)

@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the W8A8 + step-cache + VC DiT sampler on one MI355X.
+
+One benchmark "step" is one pass of the whole hot path over one batch: the
+complete DDIM sampling loop of the workload (for the default workload: 8
+latents, 50 sampler steps, cache refreshed every 2nd step, VC every step), all
+inputs resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak (published), TOP/s
+FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X fp32 matrix peak (published), TFLOP/s
+
+
+def int8_ops_per_full_step(m, B):
+    """int8 multiply-accumulate work (2 ops per MAC) of the five quantised linears of all blocks."""
+    M = B * m.tokens
+    D, R = m.hidden, m.mlp_dim
+    per_block = M * (3 * D * D + D * D + 2 * R * D) + B * 6 * D * D
+    return 2 * per_block * m.depth
+
+
+def cpu_baseline(wl):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload:
+    one latent, one refresh step and one cached step of the full-depth network;
+    scaled to the workload's (refresh, cached) step counts."""
+    import numpy as np
+    from oracle import dit, sampler
+    from synthetic import dit_inputs as I
+    m = wl.model
+    w = I.make_weights(m, wl.seed_weights)
+    clat, clab, idx = I.calibration_inputs(wl, n=1)
+    tt, at, ap = sampler.ddim_schedule(wl.steps)
+    qp, _ = sampler.calibrate(m, w, clat, clab, tt[idx])
+    lin = dit.QLinears(w, qp, m.weight_bits)
+    lat = I.make_latents(1, m, wl.seed_latents)
+    lab = I.make_labels(1, m, wl.seed_labels)
+    K = I.make_vc_factors(wl.steps, m.latent_c, wl.seed_k)
+    cache = {}
+    x = lat.astype(np.float64)
+    times = []
+    for i in range(2):
+        t0 = time.perf_counter()
+        x, _ = sampler.sample_step(x, lab, i, int(tt[i]), at[i], ap[i], m, w, lin, cache, 2, wl.cfg_scale, K[i])
+        times.append(time.perf_counter() - t0)
+    n_full = -(-wl.steps // wl.cache_interval)
+    per_latent = n_full * times[0] + (wl.steps - n_full) * times[1]
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": 1.0 / per_latent, "unit": "latents/sec", "cores": int(cores), "kind": "oracle",
+            "sample": "1 latent, 1 refresh step (%.2f s) + 1 cached step (%.2f s) of the full-depth network, "
+                      "scaled to %d refresh + %d cached steps" % (times[0], times[1], n_full, wl.steps - n_full)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (latents are independent, so more GPUs would each run "
+              "this same program on their share of the batch); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2503_02508_amd as qc
+    from synthetic import dit_inputs as I
+
+    wl = I.WORKLOADS[args.workload]
+    m = wl.model
+    B = wl.batch
+    Beff = 2 * B if wl.cfg_scale > 0 else B
+    torch.cuda.set_device(0)
+
+    # ---- setup (untimed): weights, on-device weight quantisation, on-device calibration
+    w = I.make_weights(m, wl.seed_weights)
+    ctx = qc.Context(m, Beff, wl.cache_interval)
+    ctx.load_weights(w, keep_fp32=True)
+    clat, clab, idx = I.calibration_inputs(wl)
+    tt, _, _ = qc.qc_ddim_schedule(wl.steps)
+    ctx.calibrate(torch.from_numpy(clat).cuda(), [tt[i] for i in idx], clab)
+    ctx.drop_fp32()
+    del w
+    lat = torch.from_numpy(I.make_latents(B, m, wl.seed_latents)).cuda()
+    lab = torch.from_numpy(I.make_labels(B, m, wl.seed_labels).astype(np.int32)).cuda()
+    K = torch.from_numpy(I.make_vc_factors(wl.steps, m.latent_c, wl.seed_k)).cuda()
+    x = torch.empty_like(lat)
+
+    def run_once():
+        x.copy_(lat)
+        ctx.sample(x, lab, wl.steps, wl.cfg_scale, K)
+
+    for _ in range(args.warmup):
+        run_once()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_once()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert torch.isfinite(x).all()
+    ms_per_step = dt / args.steps * 1e3
+    value = B * args.steps / dt
+
+    # ---- dominant kernel: instrumented repeat of the same pass with HIP events around its launches
+    prof = ctx.profile_pass(run_once)
+    n_full = -(-wl.steps // wl.cache_interval)
+    roofline = None
+    if prof:
+        dom = max(prof.values(), key=lambda p: p["total_ms"])
+        for p in prof.values():
+            p["avg_us"] = p["total_ms"] * 1e3 / max(p["launches"], 1)
+        MT, D, R = Beff * m.tokens, m.hidden, m.mlp_dim
+        ops = {"gemm_qkv": 2.0 * MT * 3 * D * D, "gemm_proj": 2.0 * MT * D * D,
+               "gemm_fc1": 2.0 * MT * R * D, "gemm_fc2": 2.0 * MT * D * R}
+        for k, v in ops.items():
+            if k in prof:
+                prof[k]["tops"] = v / (prof[k]["avg_us"] * 1e-6) / 1e12
+        if dom["name"] in ops:
+            ach = ops[dom["name"]] / (dom["avg_us"] * 1e-6) / 1e12
+            roofline = {"bound": "mfma", "kernel": dom["name"], "achieved": ach, "peak": INT8_MFMA_PEAK_TOPS,
+                        "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                        "avg_launch_us": dom["avg_us"], "launches": dom["launches"]}
+        elif dom["name"] == "attention":
+            fl = 4.0 * Beff * m.heads * m.tokens * m.tokens * m.head_dim
+            ach = fl / (dom["avg_us"] * 1e-6) / 1e12
+            roofline = {"bound": "mfma", "kernel": "attention", "achieved": ach, "peak": FP32_MFMA_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": ach / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
+                        "avg_launch_us": dom["avg_us"], "launches": dom["launches"]}
+    total_int8 = int8_ops_per_full_step(m, Beff) * n_full
+    out = {
+        "metric": "latents/sec, DiT-XL/2 W8A8+cache 256^2 at 50 steps; int8 GEMM % of MFMA peak",
+        "value": value, "unit": "latents/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": wl.name, "latents": B, "effective_batch": Beff, "sampler_steps": wl.steps,
+                   "cache_interval": wl.cache_interval, "refresh_steps": n_full, "cfg_scale": wl.cfg_scale,
+                   "weight_bits": m.weight_bits, "vc": True},
+        "int8_tops_end_to_end": total_int8 / (ms_per_step * 1e-3) / 1e12,
+        "roofline": roofline,
+        "kernels": prof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

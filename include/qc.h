@@ -202,6 +202,30 @@ int qc_sample_step(qc_ctx *ctx, float *x, const int32_t *labels, int B, int step
 int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, float cfg_scale, const float *K,
               void *stream);
 
+/* ------------------------------------------------------------- profiling */
+
+/* Kernel classes of the per-launch timing below. */
+enum {
+  QC_K_ADALN = 0,          /* batched adaLN projection GEMM (all blocks, M = batch)      */
+  QC_K_LN_QUANT = 1,       /* LayerNorm + modulate + quantise (two per block)            */
+  QC_K_GEMM_QKV = 2,       /* QKV GEMM + dequantise                                       */
+  QC_K_ATTENTION = 3,      /* softmax(QK^T)V + quantise                                   */
+  QC_K_GEMM_PROJ = 4,      /* projection GEMM + cache store + gated residual             */
+  QC_K_GEMM_FC1 = 5,       /* fc1 GEMM + GELU + requantise                                */
+  QC_K_GEMM_FC2 = 6,       /* fc2 GEMM + cache store + gated residual                    */
+  QC_K_CACHED_BLOCKS = 7,  /* all blocks of a cached step                                 */
+  QC_K_COUNT = 8
+};
+
+/* Between qc_profile_begin and qc_profile_end every launch of the classes above
+ * on this context is bracketed by two HIP events on the launch stream.
+ * qc_profile_end synchronises the stream and returns, per class, the number of
+ * launches and the sum of their durations in milliseconds (HOST arrays of
+ * n_classes >= QC_K_COUNT entries).  The events serialise nothing but add a
+ * little launch overhead: time whole-job throughput with profiling off. */
+int qc_profile_begin(qc_ctx *ctx);
+int qc_profile_end(qc_ctx *ctx, int n_classes, int32_t *launches, float *total_ms, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

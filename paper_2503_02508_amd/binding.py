@@ -11,7 +11,7 @@ import os
 __all__ = [
     "lib", "QCError", "ModelDesc", "Context", "QC_FULL", "QC_CACHED", "QC_CACHE_ATTN", "QC_CACHE_MLP", "SITES",
     "qc_quantize_act", "qc_quantize_weight", "qc_w8a8_linear", "qc_vc_correct", "qc_ddim_schedule", "last_error",
-    "LIB_PATH", "WS",
+    "LIB_PATH", "WS", "KERNEL_CLASSES",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqc.so")
@@ -65,7 +65,11 @@ _SIGS = {
     "qc_denoise": (i32, [vp, vp, i32, vp, i32, i32, i32, vp, vp]),
     "qc_sample_step": (i32, [vp, vp, vp, i32, i32, i32, f64, f64, f32, vp, i32, vp]),
     "qc_sample": (i32, [vp, vp, vp, i32, i32, f32, vp, vp]),
+    "qc_profile_begin": (i32, [vp]),
+    "qc_profile_end": (i32, [vp, i32, C.POINTER(C.c_int32), C.POINTER(f32), vp]),
 }
+KERNEL_CLASSES = ("gemm_adaln", "ln_mod_quant", "gemm_qkv", "attention", "gemm_proj", "gemm_fc1", "gemm_fc2",
+                  "cached_blocks")
 for _n, (_r, _a) in _SIGS.items():
     _f = getattr(lib, _n)
     _f.restype, _f.argtypes = _r, _a
@@ -236,6 +240,18 @@ class Context:
     def sample_step(self, x, labels, step_index, t, abar_t, abar_prev, cfg_scale=0.0, K_t=None, force_mode=-1):
         _chk(lib.qc_sample_step(self.h, _p(x), _p(labels), x.shape[0], step_index, int(t), abar_t, abar_prev,
                                 cfg_scale, _p(K_t), force_mode, _stream()))
+
+    def profile_pass(self, fn):
+        """Runs fn() with per-launch event timing on; returns {class: {name, launches, total_ms}}."""
+        n = len(KERNEL_CLASSES)
+        cnt, ms = (C.c_int32 * n)(), (f32 * n)()
+        _chk(lib.qc_profile_begin(self.h))
+        try:
+            fn()
+        finally:
+            _chk(lib.qc_profile_end(self.h, n, cnt, ms, _stream()))
+        return {k: {"name": k, "launches": int(cnt[i]), "total_ms": float(ms[i])}
+                for i, k in enumerate(KERNEL_CLASSES) if cnt[i]}
 
     def sample(self, x, labels, steps, cfg_scale=0.0, K=None):
         _chk(lib.qc_sample(self.h, _p(x), _p(labels), x.shape[0], steps, cfg_scale, _p(K), _stream()))

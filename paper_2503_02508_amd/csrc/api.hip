@@ -78,7 +78,35 @@ struct qc_ctx {
   float *cal_h, *cal_o, *cal_a, *cal_u, *cal_mod;
   int *cal_slots, *cal_label;
   bool weights_loaded;
+  // optional per-kernel-class timing with HIP events (qc_profile_begin / qc_profile_end)
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_pool;
+  size_t prof_used = 0;
+  std::vector<int> prof_cls;
 };
+
+// Brackets one launch with two events while profiling is on.
+struct ProfScope {
+  qc_ctx *c;
+  hipStream_t st;
+  bool on;
+  ProfScope(qc_ctx *ctx, int cls, hipStream_t s) : c(ctx), st(s), on(ctx->prof_on) {
+    if (!on) return;
+    while (c->prof_pool.size() < c->prof_used + 2) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+      c->prof_pool.push_back(e);
+    }
+    c->prof_cls.push_back(cls);
+    (void)hipEventRecord(c->prof_pool[c->prof_used], st);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(c->prof_pool[c->prof_used + 1], st);
+    c->prof_used += 2;
+  }
+};
+#define QC_PROF(cls) ProfScope prof_scope_(ctx, (cls), st)
 
 static size_t weight_bytes(const qc_model_desc &d, size_t N, size_t K) { return d.weight_bits == 4 ? N * K / 2 : N * K; }
 
@@ -208,6 +236,7 @@ int qc_create(const qc_model_desc *desc, void *arena, size_t arena_bytes, int ma
 
 int qc_destroy(qc_ctx *ctx) {
   if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
   delete ctx;
   return QC_OK;
 }
@@ -386,6 +415,7 @@ static int run_adaln(qc_ctx *ctx, int l0, int nl, int B, bool gates_only, hipStr
   a.zs_out = (long long)ctx->max_batch * 6 * D; a.zs_qp = QC_NUM_SITES;
   a.sel_D = (gates_only && D % 128 == 0) ? (int)D : 0;
   a.y = ctx->mod + (size_t)l0 * ctx->max_batch * 6 * D; a.ldy = (int)(6 * D);
+  QC_PROF(QC_K_ADALN);
   QC_HIP(launch_gemm(a, EPI_F32, nl, st));
   return QC_OK;
 }
@@ -402,27 +432,40 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, int B, hipStream_t st) {
     a.M = M; a.N = q.N; a.K = K; a.lda = K; a.w4 = w4; a.a_qp = qp + site;
     return a;
   };
-  QC_HIP(launch_ln_mod_quant(x, mod, mod + D, 6 * D, M, D, T, qp + QC_SITE_QKV, ctx->qa_ln, nullptr, st));
+  {
+    QC_PROF(QC_K_LN_QUANT);
+    QC_HIP(launch_ln_mod_quant(x, mod, mod + D, 6 * D, M, D, T, qp + QC_SITE_QKV, ctx->qa_ln, nullptr, st));
+  }
   {
     GemmArgs a = base(bq.lin[QC_SITE_QKV], ctx->qa_ln, D, QC_SITE_QKV);
     a.y = ctx->qkv; a.ldy = 3 * D;
+    QC_PROF(QC_K_GEMM_QKV);
     QC_HIP(launch_gemm(a, EPI_F32, 1, st));
   }
-  QC_HIP(launch_attention(ctx->qkv, B, T, ctx->H, ctx->hd, qp + QC_SITE_PROJ, ctx->qa_attn, nullptr, st));
+  {
+    QC_PROF(QC_K_ATTENTION);
+    QC_HIP(launch_attention(ctx->qkv, B, T, ctx->H, ctx->hd, qp + QC_SITE_PROJ, ctx->qa_attn, nullptr, st));
+  }
   {
     GemmArgs a = base(bq.lin[QC_SITE_PROJ], ctx->qa_attn, D, QC_SITE_PROJ);
     a.cache_out = cache_slot(ctx, l, QC_CACHE_ATTN); a.x = x; a.gate = mod + 2 * D; a.ld_gate = 6 * D; a.rows_per_batch = T;
+    QC_PROF(QC_K_GEMM_PROJ);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st));
   }
-  QC_HIP(launch_ln_mod_quant(x, mod + 3 * D, mod + 4 * D, 6 * D, M, D, T, qp + QC_SITE_FC1, ctx->qa_ln, nullptr, st));
+  {
+    QC_PROF(QC_K_LN_QUANT);
+    QC_HIP(launch_ln_mod_quant(x, mod + 3 * D, mod + 4 * D, 6 * D, M, D, T, qp + QC_SITE_FC1, ctx->qa_ln, nullptr, st));
+  }
   {
     GemmArgs a = base(bq.lin[QC_SITE_FC1], ctx->qa_ln, D, QC_SITE_FC1);
     a.q_out = ctx->qa_mlp; a.ldq = R; a.o_qp = qp + QC_SITE_FC2;
+    QC_PROF(QC_K_GEMM_FC1);
     QC_HIP(launch_gemm(a, EPI_GELU_Q, 1, st));
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_FC2], ctx->qa_mlp, R, QC_SITE_FC2);
     a.cache_out = cache_slot(ctx, l, QC_CACHE_MLP); a.x = x; a.gate = mod + 5 * D; a.ld_gate = 6 * D; a.rows_per_batch = T;
+    QC_PROF(QC_K_GEMM_FC2);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st));
   }
   ctx->cache_batch[(size_t)l * 2] = B;
@@ -540,6 +583,7 @@ static int denoise_impl(qc_ctx *ctx, const float *x, int t, const int32_t *label
     }
   } else {
     const size_t slot = (size_t)ctx->max_batch * ctx->T * D;
+    QC_PROF(QC_K_CACHED_BLOCKS);
     QC_HIP(launch_cached_blocks(ctx->tokens, ctx->cache, 2 * slot, slot, ctx->mod, (size_t)ctx->max_batch * 6 * D, 6 * D, L, B,
                                 ctx->T, D, st));
   }
@@ -606,6 +650,32 @@ int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, fl
                           static_cast<hipStream_t>(stream));
     if (rc) return rc;
   }
+  return QC_OK;
+}
+
+// ---------------------------------------------------------------- profiling
+int qc_profile_begin(qc_ctx *ctx) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  ctx->prof_on = true;
+  ctx->prof_used = 0;
+  ctx->prof_cls.clear();
+  return QC_OK;
+}
+
+int qc_profile_end(qc_ctx *ctx, int n_classes, int32_t *launches, float *total_ms, void *stream) {
+  if (!ctx || !launches || !total_ms) QC_FAIL(QC_ERR_NULL, "a pointer is NULL");
+  if (n_classes < QC_K_COUNT) QC_FAIL(QC_ERR_SHAPE, "n_classes must be at least %d", QC_K_COUNT);
+  ctx->prof_on = false;
+  QC_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  for (int i = 0; i < n_classes; ++i) { launches[i] = 0; total_ms[i] = 0.0f; }
+  for (size_t i = 0; i < ctx->prof_cls.size(); ++i) {
+    float ms = 0.0f;
+    QC_HIP(hipEventElapsedTime(&ms, ctx->prof_pool[2 * i], ctx->prof_pool[2 * i + 1]));
+    launches[ctx->prof_cls[i]] += 1;
+    total_ms[ctx->prof_cls[i]] += ms;
+  }
+  ctx->prof_used = 0;
+  ctx->prof_cls.clear();
   return QC_OK;
 }
 

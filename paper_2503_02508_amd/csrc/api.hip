@@ -357,7 +357,7 @@ int qc_w8a8_linear(const int8_t *qx, const void *qw, const int32_t *wsum, const 
   a.M = M; a.N = N; a.K = K; a.lda = K; a.w4 = weight_bits == 4;
   a.a_scale = x_scale; a.a_zp = x_zp - 128;
   a.y = y; a.ldy = N; a.acc_out = acc_or_null;
-  QC_HIP(launch_gemm(a, EPI_F32, 1, static_cast<hipStream_t>(stream)));
+  QC_HIP(launch_gemm(a, EPI_F32, 1, static_cast<hipStream_t>(stream), QC_SITE_QKV));
   return QC_OK;
 }
 
@@ -416,7 +416,7 @@ static int run_adaln(qc_ctx *ctx, int l0, int nl, int B, bool gates_only, hipStr
   a.sel_D = (gates_only && D % 128 == 0) ? (int)D : 0;
   a.y = ctx->mod + (size_t)l0 * ctx->max_batch * 6 * D; a.ldy = (int)(6 * D);
   QC_PROF(QC_K_ADALN);
-  QC_HIP(launch_gemm(a, EPI_F32, nl, st));
+  QC_HIP(launch_gemm(a, EPI_F32, nl, st, QC_SITE_ADA));
   return QC_OK;
 }
 
@@ -440,7 +440,7 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, int B, hipStream_t st) {
     GemmArgs a = base(bq.lin[QC_SITE_QKV], ctx->qa_ln, D, QC_SITE_QKV);
     a.y = ctx->qkv; a.ldy = 3 * D;
     QC_PROF(QC_K_GEMM_QKV);
-    QC_HIP(launch_gemm(a, EPI_F32, 1, st));
+    QC_HIP(launch_gemm(a, EPI_F32, 1, st, QC_SITE_QKV));
   }
   {
     QC_PROF(QC_K_ATTENTION);
@@ -450,7 +450,7 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, int B, hipStream_t st) {
     GemmArgs a = base(bq.lin[QC_SITE_PROJ], ctx->qa_attn, D, QC_SITE_PROJ);
     a.cache_out = cache_slot(ctx, l, QC_CACHE_ATTN); a.x = x; a.gate = mod + 2 * D; a.ld_gate = 6 * D; a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_PROJ);
-    QC_HIP(launch_gemm(a, EPI_RESID, 1, st));
+    QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_PROJ));
   }
   {
     QC_PROF(QC_K_LN_QUANT);
@@ -460,13 +460,13 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, int B, hipStream_t st) {
     GemmArgs a = base(bq.lin[QC_SITE_FC1], ctx->qa_ln, D, QC_SITE_FC1);
     a.q_out = ctx->qa_mlp; a.ldq = R; a.o_qp = qp + QC_SITE_FC2;
     QC_PROF(QC_K_GEMM_FC1);
-    QC_HIP(launch_gemm(a, EPI_GELU_Q, 1, st));
+    QC_HIP(launch_gemm(a, EPI_GELU_Q, 1, st, QC_SITE_FC1));
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_FC2], ctx->qa_mlp, R, QC_SITE_FC2);
     a.cache_out = cache_slot(ctx, l, QC_CACHE_MLP); a.x = x; a.gate = mod + 5 * D; a.ld_gate = 6 * D; a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_FC2);
-    QC_HIP(launch_gemm(a, EPI_RESID, 1, st));
+    QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_FC2));
   }
   ctx->cache_batch[(size_t)l * 2] = B;
   ctx->cache_batch[(size_t)l * 2 + 1] = B;

@@ -48,6 +48,7 @@ struct GemmArgs {
   // logical column j maps to j + 2*sel_D for j < sel_D and j + 4*sel_D otherwise
   // (the two gate chunks of an adaLN projection).
   int sel_D;
+  int xcd_m;                 // XCD grid rows (set by the launcher)
   // EPI_F32
   float *y;
   int ldy;
@@ -64,7 +65,7 @@ struct GemmArgs {
   int rows_per_batch;        // T
 };
 
-hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st);
+hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st, int site);
 
 // ---- elementwise / row kernels
 hipError_t launch_quantize_act(const float *x, int8_t *q, size_t n, float s, int z_signed, hipStream_t st);

@@ -50,7 +50,7 @@ enum {                                               /* qc_workspace_ptr selecto
   QC_WS_QACT_LN = 1,  /* int8   [B*T, D]   codes produced by the last LN+modulate+quantise */
   QC_WS_QACT_ATTN = 2,/* int8   [B*T, D]   codes of the last attention output              */
   QC_WS_QACT_MLP = 3, /* int8   [B*T, R]   codes of the last GELU output                    */
-  QC_WS_QKV = 4,      /* float  [B*T, 3D]  last QKV projection                              */
+  QC_WS_QKV = 4,      /* float  [B*T, 3D]  last QKV projection (only with qc_keep_qkv_f32)          */
   QC_WS_MOD = 5,      /* float  [L, B, 6D] adaLN modulation of every block                  */
   QC_WS_COND = 6,     /* float  [B, D]     conditioning vector c                            */
   QC_WS_EPS = 7       /* float  [B, C, H, W] last noise estimate                            */
@@ -178,6 +178,10 @@ int qc_cache_reuse(qc_ctx *ctx, int block, int which, float *x, const float *gat
 int qc_cache_ptr(qc_ctx *ctx, int block, int which, float **ptr_out);
 /* Device address of an internal buffer, see QC_WS_*; for inspection by tests. */
 int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out);
+
+/* Inspection aid: when on, full blocks also write the QKV projection as fp32 into the
+ * QC_WS_QKV buffer (the attention kernel itself reads an fp16 high/low split of it). */
+int qc_keep_qkv_f32(qc_ctx *ctx, int on);
 
 /* Noise estimate of the whole network at timestep t.  x: dev [n_labels, C, H, W],
  * labels: dev int32 [n_labels].  The effective batch B is n_labels, or

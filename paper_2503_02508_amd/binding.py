@@ -65,6 +65,7 @@ _SIGS = {
     "qc_denoise": (i32, [vp, vp, i32, vp, i32, i32, i32, vp, vp]),
     "qc_sample_step": (i32, [vp, vp, vp, i32, i32, i32, f64, f64, f32, vp, i32, vp]),
     "qc_sample": (i32, [vp, vp, vp, i32, i32, f32, vp, vp]),
+    "qc_keep_qkv_f32": (i32, [vp, i32]),
     "qc_profile_begin": (i32, [vp]),
     "qc_profile_end": (i32, [vp, i32, C.POINTER(C.c_int32), C.POINTER(f32), vp]),
 }
@@ -202,6 +203,9 @@ class Context:
         s, z = f32(), i32()
         _chk(lib.qc_get_act_qparams(self.h, block, site, C.byref(s), C.byref(z)))
         return s.value, z.value
+
+    def keep_qkv_f32(self, on=True):
+        _chk(lib.qc_keep_qkv_f32(self.h, int(on)))
 
     def dit_block(self, block, mode, x, c):
         _chk(lib.qc_dit_block(self.h, block, mode, _p(x), _p(c), x.shape[0], _stream()))

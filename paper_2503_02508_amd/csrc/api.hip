@@ -74,6 +74,11 @@ struct qc_ctx {
   // workspace
   float *emb, *h1, *te, *cond, *mod, *fmod, *tokens, *qkv, *eps;
   int8_t *silu_q, *qa_ln, *qa_attn, *qa_mlp;
+  _Float16 *qkv16;            // fp16 (high, low) Q, K [B,H,T,DP] and V^T [B,H,DP,Tp] for the attention kernel
+  long long qkv_part_stride, qkv_v_stride;
+  size_t qkv16_bytes;
+  int DP, Tp;
+  bool keep_qkv_f32 = false;
   // calibration scratch (one sample)
   float *cal_h, *cal_o, *cal_a, *cal_u, *cal_mod;
   int *cal_slots, *cal_label;
@@ -179,6 +184,9 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
   float *tokens = a.take<float>(M * D), *qkv = a.take<float>(M * 3 * D), *eps = a.take<float>(B * C * d.latent_h * d.latent_w);
   int8_t *silu_q = a.take<int8_t>(L * B * D), *qa_ln = a.take<int8_t>(M * D), *qa_attn = a.take<int8_t>(M * D);
   int8_t *qa_mlp = a.take<int8_t>(M * R);
+  const size_t hd = D / d.heads, DP = (hd + 31) / 32 * 32, Tp = (T + 63) / 64 * 64;
+  const size_t part = B * d.heads * T * DP, vpart = B * d.heads * DP * Tp;
+  _Float16 *qkv16 = a.take<_Float16>(4 * part + 2 * vpart);
   float *cal_h = a.take<float>(T * D), *cal_o = a.take<float>(T * D), *cal_a = a.take<float>(T * D);
   float *cal_u = a.take<float>(T * R), *cal_mod = a.take<float>(6 * D);
   int *cal_slots = a.take<int>(L * QC_NUM_SITES * 2), *cal_label = a.take<int>(4);
@@ -189,6 +197,8 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
     c->tokens = tokens; c->qkv = qkv; c->eps = eps; c->silu_q = silu_q; c->qa_ln = qa_ln; c->qa_attn = qa_attn;
     c->qa_mlp = qa_mlp; c->cal_h = cal_h; c->cal_o = cal_o; c->cal_a = cal_a; c->cal_u = cal_u; c->cal_mod = cal_mod;
     c->cal_slots = cal_slots; c->cal_label = cal_label;
+    c->qkv16 = qkv16; c->qkv_part_stride = (long long)part; c->qkv_v_stride = (long long)vpart;
+    c->qkv16_bytes = (4 * part + 2 * vpart) * sizeof(_Float16); c->DP = (int)DP; c->Tp = (int)Tp;
   }
   return (a.off + 255) & ~size_t(255);
 }
@@ -270,6 +280,8 @@ int qc_load_weights_f32(qc_ctx *ctx, const qc_weights_f32 *w, void *stream) {
       {ctx->label_table, w->label_table, (size_t)(ctx->d.num_classes + 1) * D}, {ctx->fada_w, w->fada_w, 2 * D * D},
       {ctx->fada_b, w->fada_b, 2 * D}, {ctx->flin_w, w->flin_w, O * D}, {ctx->flin_b, w->flin_b, O}};
   for (auto &c : cp) QC_HIP(hipMemcpyAsync(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToDevice, st));
+  // padding features / keys of the fp16 attention operands are never written afterwards and must read as zero
+  QC_HIP(hipMemsetAsync(ctx->qkv16, 0, ctx->qkv16_bytes, st));
   for (int l = 0; l < ctx->L; ++l) {
     const qc_block_weights_f32 &b = w->blocks[l];
     const float *ws[QC_NUM_SITES] = {b.ada_w, b.qkv_w, b.proj_w, b.fc1_w, b.fc2_w};
@@ -438,13 +450,17 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, int B, hipStream_t st) {
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_QKV], ctx->qa_ln, D, QC_SITE_QKV);
-    a.y = ctx->qkv; a.ldy = 3 * D;
+    a.qkv16 = ctx->qkv16; a.part_stride = ctx->qkv_part_stride; a.v_stride = ctx->qkv_v_stride;
+    a.heads = ctx->H; a.hd = ctx->hd; a.DP = ctx->DP; a.Tp = ctx->Tp; a.rows_per_batch = T;
+    a.q_scale = 1.4426950408889634f / std::sqrt((float)ctx->hd);     // log2(e) / sqrt(d): the softmax runs in base 2
+    a.y = ctx->keep_qkv_f32 ? ctx->qkv : nullptr; a.ldy = 3 * D;
     QC_PROF(QC_K_GEMM_QKV);
-    QC_HIP(launch_gemm(a, EPI_F32, 1, st, QC_SITE_QKV));
+    QC_HIP(launch_gemm(a, EPI_QKV, 1, st, QC_SITE_QKV));
   }
   {
     QC_PROF(QC_K_ATTENTION);
-    QC_HIP(launch_attention(ctx->qkv, B, T, ctx->H, ctx->hd, qp + QC_SITE_PROJ, ctx->qa_attn, nullptr, st));
+    QC_HIP(launch_attention_f16(ctx->qkv16, ctx->qkv_part_stride, ctx->qkv_v_stride, B, T, ctx->Tp, ctx->H, ctx->hd, ctx->DP,
+                                qp + QC_SITE_PROJ, ctx->qa_attn, st));
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_PROJ], ctx->qa_attn, D, QC_SITE_PROJ);
@@ -551,6 +567,12 @@ int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out) 
   }
   *ptr_out = p;
   if (bytes_out) *bytes_out = n;
+  return QC_OK;
+}
+
+int qc_keep_qkv_f32(qc_ctx *ctx, int on) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  ctx->keep_qkv_f32 = on != 0;
   return QC_OK;
 }
 

@@ -293,6 +293,69 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     return;
   }
 
+  if (EPI == EPI_QKV) {
+    // split every value into fp16 high and low parts (hi + lo carries ~22 bits) and scatter to the
+    // head-major layouts of the attention kernel
+    const int T = p.rows_per_batch, D = p.N / 3;
+    _Float16 *vh = p.qkv16 + 4 * p.part_stride, *vl = vh + p.v_stride;
+    const bool fast_t = (T % 4) == 0;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn0 + j * 32 + (lane & 31);
+      if (n >= p.N) continue;
+      const float sc = a_s * w_scale[n];
+      const int zw = a_z * wsum[n];
+      const float bs = bias ? bias[n] : 0.0f;
+      const int part = n / D, nn = n - part * D, h = nn / p.hd, e = nn - h * p.hd;
+      const float mul = part == 0 ? p.q_scale : 1.0f;
+      _Float16 *dh = p.qkv16 + (long long)(2 * part) * p.part_stride, *dl = dh + p.part_stride;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const int mb = m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4;   // 4 consecutive rows mb .. mb+3
+          if (mb >= p.M) continue;
+          _Float16 hi[4], lo[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float v = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs) * mul;
+            hi[q] = (_Float16)v;
+            lo[q] = (_Float16)(v - (float)hi[q]);
+          }
+          if (part == 2 && fast_t && mb + 3 < p.M) {
+            const int b = mb / T, t = mb - b * T;
+            const long long o = ((long long)(b * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t);
+            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+            *(h4 *)(vh + o) = (h4){hi[0], hi[1], hi[2], hi[3]};
+            *(h4 *)(vl + o) = (h4){lo[0], lo[1], lo[2], lo[3]};
+          } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int m = mb + q;
+              if (m >= p.M) continue;
+              const int b = m / T, t = m - b * T;
+              if (part == 2) {
+                const long long o = ((long long)(b * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t);
+                vh[o] = hi[q];
+                vl[o] = lo[q];
+              } else {
+                const long long o = ((long long)(b * p.heads + h) * T + t) * p.DP + e;
+                dh[o] = hi[q];
+                dl[o] = lo[q];
+              }
+            }
+          }
+          if (p.y) {   // optional fp32 copy for inspection
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              if (mb + q < p.M) p.y[(long long)(mb + q) * p.ldy + n] = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs);
+          }
+        }
+      }
+    }
+    return;
+  }
+
   const bool uniform_batch = (EPI == EPI_RESID) && (p.rows_per_batch % BM == 0);
   const int b_uniform = (EPI == EPI_RESID) ? m0 / p.rows_per_batch : 0;
 #pragma unroll
@@ -409,6 +472,7 @@ hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st, int s
   if (epi == EPI_GELU_Q) return launch_epi<EPI_GELU_Q, QC_SITE_FC1>(a, nz, st);
   if (epi == EPI_RESID)
     return site == QC_SITE_FC2 ? launch_epi<EPI_RESID, QC_SITE_FC2>(a, nz, st) : launch_epi<EPI_RESID, QC_SITE_PROJ>(a, nz, st);
+  if (epi == EPI_QKV) return launch_epi<EPI_QKV, QC_SITE_QKV>(a, nz, st);
   return site == QC_SITE_ADA ? launch_epi<EPI_F32, QC_SITE_ADA>(a, nz, st) : launch_epi<EPI_F32, QC_SITE_QKV>(a, nz, st);
 }
 

@@ -27,7 +27,7 @@ struct LinearQ {
 void set_error(const char *fmt, ...);
 
 // ---- epilogues of the int8 GEMM
-enum Epi { EPI_F32 = 0, EPI_GELU_Q = 1, EPI_RESID = 2 };
+enum Epi { EPI_F32 = 0, EPI_GELU_Q = 1, EPI_RESID = 2, EPI_QKV = 3 };
 
 struct GemmArgs {
   const int8_t *A;           // [M, lda] signed codes
@@ -63,7 +63,20 @@ struct GemmArgs {
   const float *gate;         // [B, ld_gate]
   int ld_gate;
   int rows_per_batch;        // T
+  // EPI_QKV: Q | K | V columns go out as fp16 (high part, low part) for the attention kernel:
+  // Q (pre-scaled by q_scale) and K as [B, H, T, DP], V transposed and key-permuted as [B, H, DP, Tp]
+  _Float16 *qkv16;           // 6 arrays back to back: Qh Ql Kh Kl (part_stride each) Vh Vl (v_stride each)
+  long long part_stride, v_stride;
+  int heads, hd, DP, Tp;
+  float q_scale;
 };
+
+// position of key t inside V^T rows: within each group of 32 keys the units of 4 keys are interleaved so that
+// the 8 keys a lane of the P^T operand owns (4g..4g+3 and 16+4g..16+4g+3) are contiguous
+__host__ __device__ inline int vt_pos(int t) {
+  const int u = (t >> 2) & 7;
+  return (t & ~31) | ((((u & 3) << 1) | (u >> 2)) << 2) | (t & 3);
+}
 
 hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st, int site);
 
@@ -95,6 +108,8 @@ hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, floa
 hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, int HW, hipStream_t st);
 hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const QParam *qp, int8_t *q_out, float *f32_out,
                             hipStream_t st);
+hipError_t launch_attention_f16(const _Float16 *qkv16, long long part_stride, long long v_stride, int B, int T, int Tp, int H,
+                                int hd, int DP, const QParam *qp, int8_t *q_out, hipStream_t st);
 // calibration helpers
 hipError_t launch_linear_f32(const float *x, const float *W, const float *b, float *y, int M, int N, int K, int act_out,
                              hipStream_t st);

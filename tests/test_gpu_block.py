@@ -48,6 +48,7 @@ def _block_case(model, seed, B, std=0.02, wb=8):
     cond = I.make_cond(B, model, seed + 2, std=0.5)
     qp, _ = sampler.calibrate_block(model, w, I.make_tokens(4, model, seed + 3), I.make_cond(4, model, seed + 4, std=0.5))
     lin, ctx = make_pair(model, w, qp, B)
+    ctx.keep_qkv_f32(True)
     lin.taps = {}
     cache, tap = {}, {}
     want = dit.block_full(tok.astype(np.float64), cond.astype(np.float64), 0, model.heads, lin, cache, tap)

@@ -103,6 +103,15 @@ hipError_t launch_quantize_weight(const float *w, int N, int K, int bits, void *
 // One wavefront per token row; the row lives in registers (D <= 2048).
 constexpr int LN_MAX_IT = 8;
 
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// The value that gets quantised is formed in fp64 and rounded to fp32 once: the codes then differ from
+// exact arithmetic only where the fp32 residual stream itself does, which keeps code flips (and the
+// error they seed in every later layer) at the floor.
 __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restrict__ x, const float *__restrict__ shift,
                                                            const float *__restrict__ scale, int ld_mod, int M, int D, int T,
                                                            const QParam *qp, int8_t *__restrict__ q,
@@ -111,29 +120,35 @@ __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restri
   const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (m >= M) return;
   const float *row = x + (size_t)m * D;
-  float4 v[LN_MAX_IT];
-  float sum = 0.0f;
+  const int b = m / T;
+  const float *sh = shift + (size_t)b * ld_mod, *sc = scale + (size_t)b * ld_mod;
+  float4 v[LN_MAX_IT], s4[LN_MAX_IT], c4[LN_MAX_IT];
+  double sum = 0.0;
 #pragma unroll
   for (int it = 0; it < LN_MAX_IT; ++it) {
     const int k = (lane + 64 * it) * 4;
     if (k < D) {
       v[it] = *(const float4 *)(row + k);
-      sum += (v[it].x + v[it].y) + (v[it].z + v[it].w);
+      s4[it] = *(const float4 *)(sh + k);      // issued together with the row: one memory round trip
+      c4[it] = *(const float4 *)(sc + k);
     }
   }
-  const float mean = wave_sum(sum) / (float)D;
-  float sq = 0.0f;
+#pragma unroll
+  for (int it = 0; it < LN_MAX_IT; ++it) {
+    const int k = (lane + 64 * it) * 4;
+    if (k < D) sum += ((double)v[it].x + (double)v[it].y) + ((double)v[it].z + (double)v[it].w);
+  }
+  const double mean = wave_sum_d(sum) / (double)D;
+  double sq = 0.0;
 #pragma unroll
   for (int it = 0; it < LN_MAX_IT; ++it) {
     const int k = (lane + 64 * it) * 4;
     if (k < D) {
-      float a = v[it].x - mean, b = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
-      sq += (a * a + b * b) + (c * c + d * d);
+      const double a = v[it].x - mean, bq = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
+      sq += (a * a + bq * bq) + (c * c + d * d);
     }
   }
-  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + 1e-6f);
-  const int b = m / T;
-  const float *sh = shift + (size_t)b * ld_mod, *sc = scale + (size_t)b * ld_mod;
+  const double rstd = 1.0 / sqrt(wave_sum_d(sq) / (double)D + 1e-6);
   float qs = 1.0f;
   int qz = 0;
   if (qp) {
@@ -145,11 +160,10 @@ __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restri
   for (int it = 0; it < LN_MAX_IT; ++it) {
     const int k = (lane + 64 * it) * 4;
     if (k < D) {
-      float4 s4 = *(const float4 *)(sh + k), c4 = *(const float4 *)(sc + k);
-      float h0 = (v[it].x - mean) * rstd * (1.0f + c4.x) + s4.x;
-      float h1 = (v[it].y - mean) * rstd * (1.0f + c4.y) + s4.y;
-      float h2 = (v[it].z - mean) * rstd * (1.0f + c4.z) + s4.z;
-      float h3 = (v[it].w - mean) * rstd * (1.0f + c4.w) + s4.w;
+      const float h0 = (float)((v[it].x - mean) * rstd * (1.0 + (double)c4[it].x) + (double)s4[it].x);
+      const float h1 = (float)((v[it].y - mean) * rstd * (1.0 + (double)c4[it].y) + (double)s4[it].y);
+      const float h2 = (float)((v[it].z - mean) * rstd * (1.0 + (double)c4[it].z) + (double)s4[it].z);
+      const float h3 = (float)((v[it].w - mean) * rstd * (1.0 + (double)c4[it].w) + (double)s4[it].w);
       if (q)
         *(unsigned *)(q + (size_t)m * D + k) =
             pack4(quant_code(h0, qs, qz), quant_code(h1, qs, qz), quant_code(h2, qs, qz), quant_code(h3, qs, qz));

@@ -74,7 +74,7 @@ struct qc_ctx {
   // workspace
   float *emb, *h1, *te, *cond, *mod, *fmod, *tokens, *qkv, *eps;
   int8_t *silu_q, *qa_ln, *qa_attn, *qa_mlp;
-  _Float16 *qkv16;            // fp16 (high, low) Q, K [B,H,T,DP] and V^T [B,H,DP,Tp] for the attention kernel
+  _Float16 *qkv16;            // fp16 (high, low) Q, K words [B,H,T,hd] and V^T halves [B,H,DP,Tp] for the attention kernel
   long long qkv_part_stride, qkv_v_stride;
   size_t qkv16_bytes;
   int DP, Tp;
@@ -129,7 +129,7 @@ static int check_desc(const qc_model_desc *d) {
   const int hd = d->hidden / d->heads;
   if (d->hidden % 16 || d->mlp_dim % 16) QC_FAIL(QC_ERR_UNSUPPORTED, "hidden and mlp_dim must be multiples of 16");
   if (d->hidden > 2048) QC_FAIL(QC_ERR_UNSUPPORTED, "hidden > 2048 is not covered by the row kernels");
-  if (hd % 4 || hd > 96) QC_FAIL(QC_ERR_UNSUPPORTED, "head dim must be a multiple of 4 and at most 96");
+  if (hd % 4 || hd > 80) QC_FAIL(QC_ERR_UNSUPPORTED, "head dim must be a multiple of 4 and at most 80");
   if (d->latent_c * d->patch * d->patch > 256) QC_FAIL(QC_ERR_UNSUPPORTED, "patch feature count above 256");
   return QC_OK;
 }
@@ -184,8 +184,8 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
   float *tokens = a.take<float>(M * D), *qkv = a.take<float>(M * 3 * D), *eps = a.take<float>(B * C * d.latent_h * d.latent_w);
   int8_t *silu_q = a.take<int8_t>(L * B * D), *qa_ln = a.take<int8_t>(M * D), *qa_attn = a.take<int8_t>(M * D);
   int8_t *qa_mlp = a.take<int8_t>(M * R);
-  const size_t hd = D / d.heads, DP = (hd + 31) / 32 * 32, Tp = (T + 63) / 64 * 64;
-  const size_t part = B * d.heads * T * DP, vpart = B * d.heads * DP * Tp;
+  const size_t hd = D / d.heads, DP = (hd + 15) / 16 * 16, Tp = (T + 63) / 64 * 64;
+  const size_t part = B * d.heads * T * hd, vpart = B * d.heads * DP * Tp;   // part: 32-bit words = 2 halves each
   _Float16 *qkv16 = a.take<_Float16>(4 * part + 2 * vpart);
   float *cal_h = a.take<float>(T * D), *cal_o = a.take<float>(T * D), *cal_a = a.take<float>(T * D);
   float *cal_u = a.take<float>(T * R), *cal_mod = a.take<float>(6 * D);

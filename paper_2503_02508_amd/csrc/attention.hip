@@ -177,159 +177,241 @@ hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const
 // codes quantised from it stay the oracle's.  The probabilities are split the
 // same way after the exponential.
 //
+// Global layouts: Q and K as one 32-bit (hi | lo << 16) word per element,
+// [B, H, T, d]; V transposed, separate hi and lo arrays [B, H, DPv, Tp] with the
+// keys of each group of 32 interleaved in units of 4 (vt_pos).
+//
 // Layout facts used (16x16x32 f16): lane l supplies A[row l%16][k 8(l/16)..+7]
 // and B[k 8(l/16)..+7][col l%16] as 8 halves; result register r of lane l is
 // row 4(l/16)+r, column l%16.  With S^T = K Q^T a lane owns one query and the
 // keys 4g..4g+3 of each block of 16; two such blocks give the 8 k-values of the
 // P^T operand of O^T = V^T P^T, whose key order (4g..4g+3, 16+4g..16+4g+3) is
 // the order V^T was stored in.
+//
+// One workgroup = 128 queries of one (batch, head); each of the 4 wavefronts
+// owns two blocks of 16 queries, so every K / V^T fragment read from LDS feeds
+// two MFMAs.  The next key tile is loaded into registers while the current one
+// is being used.
 namespace qc {
 
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+// four (hi | lo << 16) words -> four hi halves, four lo halves
+__device__ __forceinline__ void unpack_pairs(v4u p, v2u &hi, v2u &lo) {
+  hi.x = __builtin_amdgcn_perm(p.y, p.x, 0x05040100u);
+  hi.y = __builtin_amdgcn_perm(p.w, p.z, 0x05040100u);
+  lo.x = __builtin_amdgcn_perm(p.y, p.x, 0x07060302u);
+  lo.y = __builtin_amdgcn_perm(p.w, p.z, 0x07060302u);
+}
 
 template <int NCH, int NEB>   // feature chunks of 32 (operand width), feature blocks of 16 that hold real features
 __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__restrict__ qkv16, long long ps, long long vs, int T,
-                                                            int Tp, int H, int hd, const QParam *qp,
+                                                            int Tp, int H, int hd, int DPv, const QParam *qp,
                                                             int8_t *__restrict__ q_out) {
   constexpr int DP = 32 * NCH;
   constexpr int KROW = DP + 8;    // halves per K row in LDS (16 bytes of padding)
   constexpr int VROW = 64 + 8;    // halves per V^T row in LDS
+  constexpr int KCH = 5;          // 16-byte chunks of K pairs per thread per tile: 64 keys * d/4 <= 256 * KCH for d <= 80
+  constexpr int VCH = (NEB * 16 * 8 + 255) / 256;
   __shared__ __align__(16) _Float16 Ksh[2][64 * KROW];
-  __shared__ __align__(16) _Float16 Vsh[2][DP * VROW];
+  __shared__ __align__(16) _Float16 Vsh[2][NEB * 16 * VROW];
 
   const int D = H * hd;
   const int bh = blockIdx.y, b = bh / H, h = bh % H;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ql = lane & 15, g = lane >> 4;
-  const int q_row = blockIdx.x * 64 + wave * 16 + ql;
-  const _Float16 *Qh = qkv16, *Ql = qkv16 + ps, *Kh = qkv16 + 2 * ps, *Kl = qkv16 + 3 * ps;
+  const unsigned *Qp = (const unsigned *)qkv16, *Kp = Qp + ps;
   const _Float16 *Vh = qkv16 + 4 * ps, *Vl = Vh + vs;
-  const long long tok_base = (long long)bh * T * DP;
-  const long long vt_base = (long long)bh * DP * Tp;
+  const long long tok_base = (long long)bh * T * hd;
+  const long long vt_base = (long long)bh * DPv * Tp;
+  const int kchunks = 64 * (hd / 4);            // 16-byte chunks of one K tile
 
-  v8h qh[NCH], qlo[NCH];
+  // feature padding of the K tile is never written below: clear it once
+  for (int i = tid; i < 2 * 64 * KROW / 8; i += 256) ((v8h *)&Ksh[0][0])[i] = (v8h){0, 0, 0, 0, 0, 0, 0, 0};
+
+  int q_row[2];
+  v8h qh[2][NCH], qlo[2][NCH];
 #pragma unroll
-  for (int c = 0; c < NCH; ++c) {
-    v8h zh = {0, 0, 0, 0, 0, 0, 0, 0};
-    qh[c] = zh;
-    qlo[c] = zh;
-    if (q_row < T) {
-      qh[c] = *(const v8h *)(Qh + tok_base + (long long)q_row * DP + 32 * c + 8 * g);
-      qlo[c] = *(const v8h *)(Ql + tok_base + (long long)q_row * DP + 32 * c + 8 * g);
+  for (int j = 0; j < 2; ++j) {
+    q_row[j] = blockIdx.x * 128 + wave * 32 + j * 16 + ql;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      v2u h0 = {0, 0}, l0 = {0, 0}, h1 = {0, 0}, l1 = {0, 0};
+      const int f = 32 * c + 8 * g;
+      if (q_row[j] < T) {
+        const unsigned *src = Qp + tok_base + (long long)q_row[j] * hd + f;
+        if (f < hd) unpack_pairs(*(const v4u *)src, h0, l0);
+        if (f + 4 < hd) unpack_pairs(*(const v4u *)(src + 4), h1, l1);
+      }
+      v4u hh = {h0.x, h0.y, h1.x, h1.y}, ll = {l0.x, l0.y, l1.x, l1.y};
+      qh[j][c] = *(v8h *)&hh;
+      qlo[j][c] = *(v8h *)&ll;
     }
   }
-  v4f o[NEB];
+  v4f o[2][NEB];
 #pragma unroll
-  for (int e = 0; e < NEB; ++e) o[e] = (v4f){0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.0f;
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int e = 0; e < NEB; ++e) o[j][e] = (v4f){0.f, 0.f, 0.f, 0.f};
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
 
-  for (int k0 = 0; k0 < T; k0 += 64) {
-    __syncthreads();
-    // stage K (token-major rows) and V^T (feature-major rows) tiles, high and low parts
-    for (int i = tid; i < 64 * (DP / 8); i += 256) {
-      const int r = i / (DP / 8), c8 = (i % (DP / 8)) * 8;
-      v8h a = {0, 0, 0, 0, 0, 0, 0, 0}, bq = a;
-      if (k0 + r < T) {
-        a = *(const v8h *)(Kh + tok_base + (long long)(k0 + r) * DP + c8);
-        bq = *(const v8h *)(Kl + tok_base + (long long)(k0 + r) * DP + c8);
-      }
-      *(v8h *)(Ksh[0] + r * KROW + c8) = a;
-      *(v8h *)(Ksh[1] + r * KROW + c8) = bq;
+  v4u kreg[KCH];
+  v4u vreg[2][VCH];
+  auto load_tile = [&](int k0) {
+#pragma unroll
+    for (int u = 0; u < KCH; ++u) {
+      const int i = tid + 256 * u;
+      const int r = i / (hd / 4), c4 = (i % (hd / 4)) * 4;
+      v4u v = {0, 0, 0, 0};
+      if (i < kchunks && k0 + r < T) v = *(const v4u *)(Kp + tok_base + (long long)(k0 + r) * hd + c4);
+      kreg[u] = v;
     }
-    for (int i = tid; i < NEB * 16 * 8; i += 256) {
+#pragma unroll
+    for (int u = 0; u < VCH; ++u) {
+      const int i = tid + 256 * u;
       const int e = i >> 3, c8 = (i & 7) * 8;
-      *(v8h *)(Vsh[0] + e * VROW + c8) = *(const v8h *)(Vh + vt_base + (long long)e * Tp + k0 + c8);
-      *(v8h *)(Vsh[1] + e * VROW + c8) = *(const v8h *)(Vl + vt_base + (long long)e * Tp + k0 + c8);
+      v4u a = {0, 0, 0, 0}, bq = a;
+      if (i < NEB * 16 * 8) {
+        a = *(const v4u *)(Vh + vt_base + (long long)e * Tp + k0 + c8);
+        bq = *(const v4u *)(Vl + vt_base + (long long)e * Tp + k0 + c8);
+      }
+      vreg[0][u] = a;
+      vreg[1][u] = bq;
     }
-    __syncthreads();
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int u = 0; u < KCH; ++u) {
+      const int i = tid + 256 * u;
+      if (i < kchunks) {
+        const int r = i / (hd / 4), c4 = (i % (hd / 4)) * 4;
+        v2u hi, lo;
+        unpack_pairs(kreg[u], hi, lo);
+        *(v2u *)(Ksh[0] + r * KROW + c4) = hi;
+        *(v2u *)(Ksh[1] + r * KROW + c4) = lo;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < VCH; ++u) {
+      const int i = tid + 256 * u;
+      if (i < NEB * 16 * 8) {
+        const int e = i >> 3, c8 = (i & 7) * 8;
+        *(v4u *)(Vsh[0] + e * VROW + c8) = vreg[0][u];
+        *(v4u *)(Vsh[1] + e * VROW + c8) = vreg[1][u];
+      }
+    }
+  };
 
-    v4f s[4];
+  load_tile(0);
+  for (int k0 = 0; k0 < T; k0 += 64) {
+    __syncthreads();                       // everyone is done with the previous tile
+    store_tile();
+    __syncthreads();
+    if (k0 + 64 < T) load_tile(k0 + 64);   // in flight during the MFMAs below
+
+    v4f s[2][4];
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
-      v4f acc = {0.f, 0.f, 0.f, 0.f};
+      v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
         const v8h kh = *(const v8h *)(Ksh[0] + (kt * 16 + ql) * KROW + 32 * c + 8 * g);
         const v8h kl = *(const v8h *)(Ksh[1] + (kt * 16 + ql) * KROW + 32 * c + 8 * g);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[c], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[c], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[c], acc, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[0][c], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[1][c], acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[0][c], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[1][c], acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[0][c], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[1][c], acc1, 0, 0, 0);
       }
-      s[kt] = acc;
+      s[0][kt] = acc0;
+      s[1][kt] = acc1;
     }
-    float mx = -INFINITY;
+    v8h ph[2][2], pl[2][2];
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+    for (int j = 0; j < 2; ++j) {
+      float mx = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (k0 + kt * 16 + 4 * g + r >= T) s[kt][r] = -INFINITY;
-        mx = fmaxf(mx, s[kt][r]);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    l_run *= alpha;
+      for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-    for (int e = 0; e < NEB; ++e) o[e] *= alpha;
-    v8h ph[2], pl[2];
+        for (int r = 0; r < 4; ++r) {
+          if (k0 + kt * 16 + 4 * g + r >= T) s[j][kt][r] = -INFINITY;
+          mx = fmaxf(mx, s[j][kt][r]);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[j], mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[j] - m_new);
+      m_run[j] = m_new;
+      l_run[j] *= alpha;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+      for (int e = 0; e < NEB; ++e) o[j][e] *= alpha;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float pv = __builtin_amdgcn_exp2f(s[kt][r] - m_new);
-        l_run += pv;
-        const _Float16 hi = (_Float16)pv;
-        ph[kt >> 1][(kt & 1) * 4 + r] = hi;
-        pl[kt >> 1][(kt & 1) * 4 + r] = (_Float16)(pv - (float)hi);
-      }
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float pv = __builtin_amdgcn_exp2f(s[j][kt][r] - m_new);
+          l_run[j] += pv;
+          const _Float16 hi = (_Float16)pv;
+          ph[j][kt >> 1][(kt & 1) * 4 + r] = hi;
+          pl[j][kt >> 1][(kt & 1) * 4 + r] = (_Float16)(pv - (float)hi);
+        }
+    }
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int e = 0; e < NEB; ++e) {
         const v8h vh = *(const v8h *)(Vsh[0] + (e * 16 + ql) * VROW + 32 * a + 8 * g);
         const v8h vl = *(const v8h *)(Vsh[1] + (e * 16 + ql) * VROW + 32 * a + 8 * g);
-        o[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, ph[a], o[e], 0, 0, 0);
-        o[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[a], o[e], 0, 0, 0);
-        o[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[a], o[e], 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, ph[j][a], o[j][e], 0, 0, 0);
+          o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[j][a], o[j][e], 0, 0, 0);
+          o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[j][a], o[j][e], 0, 0, 0);
+        }
       }
   }
 
-  l_run += __shfl_xor(l_run, 16, 64);
-  l_run += __shfl_xor(l_run, 32, 64);
-  if (q_row >= T) return;
-  const float inv = 1.0f / l_run;
   const QParam t = *qp;
   const float qs = t.s, qz = (float)t.z;
-  const size_t out_row = ((size_t)b * T + q_row) * D + (size_t)h * hd;
 #pragma unroll
-  for (int e = 0; e < NEB; ++e) {
-    const int f = 16 * e + 4 * g;
-    if (f >= hd) continue;
-    const v4f v = o[e] * inv;
-    int c[4];
+  for (int j = 0; j < 2; ++j) {
+    float l = l_run[j];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (q_row[j] >= T) continue;
+    const float inv = 1.0f / l;
+    const size_t out_row = ((size_t)b * T + q_row[j]) * D + (size_t)h * hd;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) c[r] = (int)fminf(fmaxf(rintf(v[r] / qs) + qz, -128.f), 127.f);
-    *(unsigned *)(q_out + out_row + f) = (unsigned)(c[0] & 0xFF) | ((unsigned)(c[1] & 0xFF) << 8) |
-                                         ((unsigned)(c[2] & 0xFF) << 16) | ((unsigned)(c[3] & 0xFF) << 24);
+    for (int e = 0; e < NEB; ++e) {
+      const int f = 16 * e + 4 * g;
+      if (f >= hd) continue;
+      const v4f v = o[j][e] * inv;
+      int c[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) c[r] = (int)fminf(fmaxf(rintf(v[r] / qs) + qz, -128.f), 127.f);
+      *(unsigned *)(q_out + out_row + f) = (unsigned)(c[0] & 0xFF) | ((unsigned)(c[1] & 0xFF) << 8) |
+                                           ((unsigned)(c[2] & 0xFF) << 16) | ((unsigned)(c[3] & 0xFF) << 24);
+    }
   }
 }
 
 hipError_t launch_attention_f16(const _Float16 *qkv16, long long part_stride, long long v_stride, int B, int T, int Tp, int H,
-                                int hd, int DP, const QParam *qp, int8_t *q_out, hipStream_t st) {
-  dim3 grid((T + 63) / 64, B * H);
-  const int neb = (hd + 15) / 16;
+                                int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st) {
+  dim3 grid((T + 127) / 128, B * H);
+  const int neb = (hd + 15) / 16, nch = (hd + 31) / 32;
+  if (hd > 80 || hd % 4) return hipErrorInvalidValue;      // K prefetch registers are sized for d <= 80
 #define QC_ATT(NCH, NEB)                                                                                               \
   hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB>), grid, dim3(256), 0, st, qkv16, part_stride, v_stride, T, Tp, H, hd, \
-                     qp, q_out)
-  if (DP == 32 && neb == 1) QC_ATT(1, 1);
-  else if (DP == 32) QC_ATT(1, 2);
-  else if (DP == 64 && neb == 3) QC_ATT(2, 3);
-  else if (DP == 64) QC_ATT(2, 4);
-  else if (DP == 96 && neb == 5) QC_ATT(3, 5);
-  else if (DP == 96) QC_ATT(3, 6);
+                     DPv, qp, q_out)
+  if (nch == 1 && neb == 1) QC_ATT(1, 1);
+  else if (nch == 1) QC_ATT(1, 2);
+  else if (nch == 2 && neb == 3) QC_ATT(2, 3);
+  else if (nch == 2) QC_ATT(2, 4);
+  else if (nch == 3 && neb == 5) QC_ATT(3, 5);
   else return hipErrorInvalidValue;
 #undef QC_ATT
   return hipGetLastError();

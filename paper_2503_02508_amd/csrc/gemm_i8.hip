@@ -308,7 +308,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
       const float bs = bias ? bias[n] : 0.0f;
       const int part = n / D, nn = n - part * D, h = nn / p.hd, e = nn - h * p.hd;
       const float mul = part == 0 ? p.q_scale : 1.0f;
-      _Float16 *dh = p.qkv16 + (long long)(2 * part) * p.part_stride, *dl = dh + p.part_stride;
+      unsigned *dpair = (unsigned *)p.qkv16 + (long long)part * p.part_stride;   // Q / K: one (hi | lo << 16) word per element
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -322,8 +322,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
             hi[q] = (_Float16)v;
             lo[q] = (_Float16)(v - (float)hi[q]);
           }
+          const int b0 = mb / T, t0 = mb - b0 * T;
           if (part == 2 && fast_t && mb + 3 < p.M) {
-            const int b = mb / T, t = mb - b * T;
+            const int b = b0, t = t0;
             const long long o = ((long long)(b * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t);
             typedef _Float16 h4 __attribute__((ext_vector_type(4)));
             *(h4 *)(vh + o) = (h4){hi[0], hi[1], hi[2], hi[3]};
@@ -333,15 +334,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
             for (int q = 0; q < 4; ++q) {
               const int m = mb + q;
               if (m >= p.M) continue;
-              const int b = m / T, t = m - b * T;
+              int b = b0, t = t0 + q;
+              while (t >= T) { t -= T; ++b; }
               if (part == 2) {
                 const long long o = ((long long)(b * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t);
                 vh[o] = hi[q];
                 vl[o] = lo[q];
               } else {
-                const long long o = ((long long)(b * p.heads + h) * T + t) * p.DP + e;
-                dh[o] = hi[q];
-                dl[o] = lo[q];
+                const unsigned short uh = __builtin_bit_cast(unsigned short, hi[q]), ul = __builtin_bit_cast(unsigned short, lo[q]);
+                dpair[((long long)(b * p.heads + h) * T + t) * p.hd + e] = (unsigned)uh | ((unsigned)ul << 16);
               }
             }
           }
@@ -454,6 +455,10 @@ static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
     case 1: return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
     case 2: return launch_cfg<256, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
     case 3: return launch_cfg<256, 256, 2, 4, EPI, TAG, W4, 2>(a, nz, st);
+    case 4: return launch_cfg<64, 128, 2, 2, EPI, TAG, W4, 4>(a, nz, st);
+    case 5: return launch_cfg<64, 64, 2, 2, EPI, TAG, W4, 4>(a, nz, st);
+    case 6: return launch_cfg<128, 64, 2, 2, EPI, TAG, W4, 4>(a, nz, st);
+    case 7: return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 4>(a, nz, st);
     default: break;
   }
   // Large problems: 256x256 tiles on 8 wavefronts (256 ops per byte fetched from L2, the

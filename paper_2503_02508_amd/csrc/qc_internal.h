@@ -64,8 +64,9 @@ struct GemmArgs {
   int ld_gate;
   int rows_per_batch;        // T
   // EPI_QKV: Q | K | V columns go out as fp16 (high part, low part) for the attention kernel:
-  // Q (pre-scaled by q_scale) and K as [B, H, T, DP], V transposed and key-permuted as [B, H, DP, Tp]
-  _Float16 *qkv16;           // 6 arrays back to back: Qh Ql Kh Kl (part_stride each) Vh Vl (v_stride each)
+  // Q (pre-scaled by q_scale) and K as one (hi | lo << 16) word per element, [B, H, T, hd];
+  // V transposed and key-permuted, separate hi and lo arrays [B, H, DP, Tp] (DP = hd rounded up to 16)
+  _Float16 *qkv16;           // Q words, K words (part_stride words each), then Vh, Vl (v_stride halves each)
   long long part_stride, v_stride;
   int heads, hd, DP, Tp;
   float q_scale;
@@ -109,7 +110,7 @@ hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, 
 hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const QParam *qp, int8_t *q_out, float *f32_out,
                             hipStream_t st);
 hipError_t launch_attention_f16(const _Float16 *qkv16, long long part_stride, long long v_stride, int B, int T, int Tp, int H,
-                                int hd, int DP, const QParam *qp, int8_t *q_out, hipStream_t st);
+                                int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st);
 // calibration helpers
 hipError_t launch_linear_f32(const float *x, const float *W, const float *b, float *y, int M, int N, int K, int act_out,
                              hipStream_t st);

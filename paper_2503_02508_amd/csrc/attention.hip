@@ -260,13 +260,19 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
 
   v4u kreg[KCH];
   v4u vreg[2][VCH];
+  // key row and feature offset of this thread's K chunks (the same for every tile: no divisions in the loop)
+  int kr[KCH], kc[KCH];
+#pragma unroll
+  for (int u = 0; u < KCH; ++u) {
+    const int i = tid + 256 * u;
+    kr[u] = i < kchunks ? i / (hd / 4) : -1;
+    kc[u] = (i % (hd / 4)) * 4;
+  }
   auto load_tile = [&](int k0) {
 #pragma unroll
     for (int u = 0; u < KCH; ++u) {
-      const int i = tid + 256 * u;
-      const int r = i / (hd / 4), c4 = (i % (hd / 4)) * 4;
       v4u v = {0, 0, 0, 0};
-      if (i < kchunks && k0 + r < T) v = *(const v4u *)(Kp + tok_base + (long long)(k0 + r) * hd + c4);
+      if (kr[u] >= 0 && k0 + kr[u] < T) v = *(const v4u *)(Kp + tok_base + (long long)(k0 + kr[u]) * hd + kc[u]);
       kreg[u] = v;
     }
 #pragma unroll
@@ -285,13 +291,11 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
   auto store_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < KCH; ++u) {
-      const int i = tid + 256 * u;
-      if (i < kchunks) {
-        const int r = i / (hd / 4), c4 = (i % (hd / 4)) * 4;
+      if (kr[u] >= 0) {
         v2u hi, lo;
         unpack_pairs(kreg[u], hi, lo);
-        *(v2u *)(Ksh[0] + r * KROW + c4) = hi;
-        *(v2u *)(Ksh[1] + r * KROW + c4) = lo;
+        *(v2u *)(Ksh[0] + kr[u] * KROW + kc[u]) = hi;
+        *(v2u *)(Ksh[1] + kr[u] * KROW + kc[u]) = lo;
       }
     }
 #pragma unroll
@@ -331,6 +335,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
       s[1][kt] = acc1;
     }
     v8h ph[2][2], pl[2][2];
+    const bool ragged_tile = k0 + 64 > T;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       float mx = -INFINITY;
@@ -338,7 +343,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
       for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          if (k0 + kt * 16 + 4 * g + r >= T) s[j][kt][r] = -INFINITY;
+          if (ragged_tile && k0 + kt * 16 + 4 * g + r >= T) s[j][kt][r] = -INFINITY;
           mx = fmaxf(mx, s[j][kt][r]);
         }
       mx = fmaxf(mx, __shfl_xor(mx, 16, 64));

@@ -38,10 +38,10 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int BK = 128;
-constexpr int LDS_ROW = BK + 16;
 
 constexpr int NUM_XCD = 8;
+long long *g_trace = nullptr;
+int g_trace_epi = -1, g_trace_tag = -1;
 
 __device__ __forceinline__ int map_col(int j, int sel_D) {
   return sel_D ? (j < sel_D ? j + 2 * sel_D : j + 4 * sel_D) : j;
@@ -83,12 +83,14 @@ __device__ __forceinline__ int quant_code(float v, float s, float inv_s, float z
   return (int)r;
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF>
+template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int NT = 64 * WM * WN;            // threads per workgroup
-  constexpr int RP = NT / 8;                  // slab rows covered by one pass of the workgroup
+  constexpr int LDS_ROW = BK + 16;            // padded slab row in LDS
+  constexpr int CPR = BK / 16;                // 16-byte chunks per slab row
+  constexpr int RP = NT / CPR;                // slab rows covered by one pass of the workgroup
   constexpr int PA = BM / RP, PB = BN / RP;   // 16-byte chunks per thread per slab
   static_assert(TM >= 1 && TN >= 1 && PA >= 1 && PB >= 1, "tile too small for the workgroup");
   extern __shared__ __align__(16) unsigned char smem[];
@@ -97,6 +99,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int z = blockIdx.z;
+  long long *trace = p.trace ? p.trace + 4 * (long long)blockIdx.x : nullptr;
+  if (trace && tid == 0) trace[0] = wall_clock64();
   const int ncover = p.sel_D ? 2 * p.sel_D : p.N;
   const int tiles_m = (p.M + BM - 1) / BM;
   // XCD-aware order: workgroup b runs on XCD b % 8.  The 8 XCDs form an xm x xn
@@ -119,7 +123,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
   // Loads never branch: rows outside the matrix are clamped to the last row
   // (their products land in accumulators that are never stored) and the
   // chunks of a ragged last slab are clamped in k and zeroed by a select.
-  const int lr = tid >> 3, lc = tid & 7;   // slab row (per pass of 32) and chunk of this thread
+  const int lr = tid / CPR, lc = tid % CPR;   // slab row (per pass of RP rows) and chunk of this thread
   unsigned oa[PA], ob[PB];                  // byte offsets of this thread's chunk rows
 #pragma unroll
   for (int i = 0; i < PA; ++i) oa[i] = (unsigned)min(m0 + lr + RP * i, p.M - 1) * (unsigned)p.lda;
@@ -153,6 +157,35 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
       else v = *(v4i *)&rb[s][i];
       *(v4i *)(sB + (buf * BN + lr + RP * i) * LDS_ROW + lc * 16) = zero ? (v4i){0, 0, 0, 0} : v;
     }
+  };
+
+  // the same, one quarter at a time (chunk c of the PA + PB chunks belongs to part c % NPART): lets the
+  // steady-state step spread its memory instructions between the MFMA groups
+  constexpr int NPART = BK / 32;
+  auto load_part = [&](int s, int k0, int part) {
+    const int k = k0 + lc * 16;
+#pragma unroll
+    for (int i = 0; i < PA; ++i)
+      if (i % NPART == part) ra[s][i] = *(const v4i *)(A + oa[i] + k);
+#pragma unroll
+    for (int i = 0; i < PB; ++i)
+      if ((PA + i) % NPART == part) {
+        if (W4) *(v2i *)&rb[s][i] = *(const v2i *)(W + ob[i] + (k >> 1));
+        else *(v4i *)&rb[s][i] = *(const v4i *)(W + ob[i] + k);
+      }
+  };
+  auto store_part = [&](int s, int buf, int part) {
+#pragma unroll
+    for (int i = 0; i < PA; ++i)
+      if (i % NPART == part) *(v4i *)(sA + (buf * BM + lr + RP * i) * LDS_ROW + lc * 16) = ra[s][i];
+#pragma unroll
+    for (int i = 0; i < PB; ++i)
+      if ((PA + i) % NPART == part) {
+        v4i v;
+        if (W4) v = unpack_w4(*(v2i *)&rb[s][i]);
+        else v = *(v4i *)&rb[s][i];
+        *(v4i *)(sB + (buf * BN + lr + RP * i) * LDS_ROW + lc * 16) = v;
+      }
   };
 
   v16i acc[TM][TN];
@@ -189,25 +222,63 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     }
   };
 
+  // One steady-state step, software-pipelined inside the wavefront: the fragments of k-group kk+1 are
+  // read from LDS before the MFMAs of group kk issue, and a quarter of the next slab's LDS stores and of
+  // the global loads PF slabs ahead is issued behind each MFMA group, so that LDS and memory instructions
+  // execute under the matrix-core time instead of in front of it.
+  auto step = [&](int s, int kt) {
+    const int cur = kt & 1;
+    const unsigned char *a_base = sA + (cur * BM + wm0 + frow) * LDS_ROW + fk;
+    const unsigned char *b_base = sB + (cur * BN + wn0 + frow) * LDS_ROW + fk;
+    v4i fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = *(const v4i *)(a_base + i * 32 * LDS_ROW);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = *(const v4i *)(b_base + j * 32 * LDS_ROW);
+#pragma unroll
+    for (int kk = 0; kk < NPART; ++kk) {
+      if (kk + 1 < NPART) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = *(const v4i *)(a_base + i * 32 * LDS_ROW + (kk + 1) * 32);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = *(const v4i *)(b_base + j * 32 * LDS_ROW + (kk + 1) * 32);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if (EPI == EPI_GELU_Q)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+          else
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+        }
+      __builtin_amdgcn_sched_barrier(0);
+      store_part((s + 1) % PF, cur ^ 1, kk);
+      load_part(s, (kt + PF) * BK, kk);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   // prologue: PF slabs in flight, slab 0 into LDS
 #pragma unroll
   for (int s = 0; s < PF; ++s)
     if (s < nk) load_slab(s, s * BK, k_ragged && s == nk - 1);
   store_slab(0, 0, k_ragged && nk == 1 && lc * 16 >= p.K);
   __syncthreads();
+  if (trace && tid == 0) trace[1] = wall_clock64();
   // main loop, unrolled by PF so that the register sets rotate with static indices:
   // at step kt LDS[kt & 1] holds slab kt, registers hold slabs kt+1 .. kt+PF-1.
   // Steady state is straight-line code (every step loads, computes, stores) so
   // that the wait before a store only covers the one slab it needs; the last
   // few steps run in a conditional tail.
   int kb = 0;
-  for (; kb + 2 * PF - 1 < nk; kb += PF) {
+  const int nk_steady = k_ragged ? nk - 1 : nk;      // the ragged last slab is loaded by the tail (clamped, zero-filled)
+  for (; kb + 2 * PF - 1 < nk_steady; kb += PF) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) {
       const int kt = kb + s;
-      load_slab(s, (kt + PF) * BK, k_ragged && kt + PF == nk - 1);     // set s is free: slab kt is in LDS
-      store_slab((s + 1) % PF, (kt + 1) & 1, false);                   // loaded PF-1 steps ago: no wait, overlaps the MFMAs
-      compute(kt & 1);
+      step(s, kt);
       __syncthreads();
     }
   }
@@ -224,6 +295,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     }
   }
 
+  if (trace && tid == 0) trace[2] = wall_clock64();
   // ------------------------------------------------------------ epilogue
   float a_s = p.a_scale;
   int a_z = p.a_zp;
@@ -290,6 +362,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
         for (int e = 0; n + e < p.N; ++e) dst[e] = (int8_t)stage[r * SROW + cc + e];
       }
     }
+    if (trace && tid == 0) trace[3] = wall_clock64();
     return;
   }
 
@@ -299,6 +372,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     const int T = p.rows_per_batch, D = p.N / 3;
     _Float16 *vh = p.qkv16 + 4 * p.part_stride, *vl = vh + p.v_stride;
     const bool fast_t = (T % 4) == 0;
+    const bool tile_one_batch = (T % BM) == 0;      // then every row of the tile belongs to batch element m0 / T
+    const int b_tile = m0 / T;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int n = n0 + wn0 + j * 32 + (lane & 31);
@@ -309,6 +384,44 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
       const int part = n / D, nn = n - part * D, h = nn / p.hd, e = nn - h * p.hd;
       const float mul = part == 0 ? p.q_scale : 1.0f;
       unsigned *dpair = (unsigned *)p.qkv16 + (long long)part * p.part_stride;   // Q / K: one (hi | lo << 16) word per element
+      if (tile_one_batch && fast_t && m0 + BM <= p.M && !p.y) {
+        // interior tile inside one batch element: 32-bit offsets advanced row by row, no per-element index arithmetic
+        const int tb = m0 - b_tile * T + wm0 + (lane >> 5) * 4;            // token of this lane's first row
+        const unsigned head = (unsigned)(b_tile * p.heads + h);
+        if (part == 2) {
+          const unsigned base = (head * (unsigned)p.DP + (unsigned)e) * (unsigned)p.Tp;
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+              typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+              h4 hi, lo;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const float v = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs);
+                hi[q] = (_Float16)v;
+                lo[q] = (_Float16)(v - (float)hi[q]);
+              }
+              const unsigned o = base + (unsigned)vt_pos(tb + i * 32 + rg * 8);
+              *(h4 *)(vh + o) = hi;
+              *(h4 *)(vl + o) = lo;
+            }
+        } else {
+          unsigned *dst = dpair + (head * (unsigned)T + (unsigned)tb) * (unsigned)p.hd + (unsigned)e;
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const float v = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs) * mul;
+                const _Float16 hi = (_Float16)v, lo = (_Float16)(v - (float)hi);
+                dst[(unsigned)(i * 32 + rg * 8 + q) * (unsigned)p.hd] =
+                    (unsigned)__builtin_bit_cast(unsigned short, hi) | ((unsigned)__builtin_bit_cast(unsigned short, lo) << 16);
+              }
+        }
+        continue;
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -322,7 +435,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
             hi[q] = (_Float16)v;
             lo[q] = (_Float16)(v - (float)hi[q]);
           }
-          const int b0 = mb / T, t0 = mb - b0 * T;
+          const int b0 = tile_one_batch ? b_tile : mb / T, t0 = mb - b0 * T;
           if (part == 2 && fast_t && mb + 3 < p.M) {
             const int b = b0, t = t0;
             const long long o = ((long long)(b * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t);
@@ -354,11 +467,71 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
         }
       }
     }
+    if (trace && tid == 0) trace[3] = wall_clock64();
     return;
   }
 
-  const bool uniform_batch = (EPI == EPI_RESID) && (p.rows_per_batch % BM == 0);
-  const int b_uniform = (EPI == EPI_RESID) ? m0 / p.rows_per_batch : 0;
+  if (EPI == EPI_RESID) {
+    // read-modify-write of the residual stream: every load of the tile is issued before the first use, so
+    // the epilogue pays one memory round trip instead of one per register group
+    const bool uniform_batch = (p.rows_per_batch % BM) == 0;
+    const int b_uniform = m0 / p.rows_per_batch;
+    float xv[TN][TM][16], gv[TN], scv[TN], bsv[TN];
+    int zwv[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = min(n0 + wn0 + j * 32 + (lane & 31), p.N - 1);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = min(m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), p.M - 1);
+          xv[j][i][r] = p.x[(long long)m * p.N + n];
+        }
+      scv[j] = a_s * w_scale[n];
+      zwv[j] = a_z * wsum[n];
+      bsv[j] = bias ? bias[n] : 0.0f;
+      gv[j] = p.gate[(long long)b_uniform * p.ld_gate + n];
+    }
+    if (uniform_batch && m0 + BM <= p.M && n0 + BN <= p.N) {
+      // interior tile inside one batch element: no bounds checks, one gate per column
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const long long n = n0 + wn0 + j * 32 + (lane & 31);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            const float v = fmaf(scv[j], (float)(acc[i][j][r] - zwv[j]), bsv[j]);
+            const long long o = (long long)m * p.N + n;
+            p.cache_out[o] = v;
+            p.x[o] = xv[j][i][r] + gv[j] * v;
+          }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn0 + j * 32 + (lane & 31);
+        if (n >= p.N) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            if (m >= p.M) continue;
+            const float v = fmaf(scv[j], (float)(acc[i][j][r] - zwv[j]), bsv[j]);
+            const long long o = (long long)m * p.N + n;
+            p.cache_out[o] = v;
+            const float g = p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
+            p.x[o] = xv[j][i][r] + g * v;
+          }
+      }
+    }
+    if (trace && tid == 0) trace[3] = wall_clock64();
+    return;
+  }
+
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int jl = n0 + wn0 + j * 32 + (lane & 31);
@@ -367,50 +540,28 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     const float sc = a_s * w_scale[n];
     const int zw = a_z * wsum[n];
     const float bs = bias ? bias[n] : 0.0f;
-    float g_uniform = 0.0f;
-    if (EPI == EPI_RESID && uniform_batch) g_uniform = p.gate[(long long)b_uniform * p.ld_gate + n];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      if (EPI == EPI_RESID) {
-        // read-modify-write of the residual stream: issue the 16 loads first
-        float xv[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-          xv[r] = m < p.M ? p.x[(long long)m * p.N + n] : 0.0f;
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-          if (m >= p.M) continue;
-          const float v = fmaf(sc, (float)(acc[i][j][r] - zw), bs);
-          const long long o = (long long)m * p.N + n;
-          p.cache_out[o] = v;
-          const float g = uniform_batch ? g_uniform : p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
-          p.x[o] = xv[r] + g * v;
-        }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-          if (m >= p.M) continue;
-          const int a = acc[i][j][r];
-          float *y = p.y + (long long)z * p.zs_out;
-          y[(long long)m * p.ldy + n] = fmaf(sc, (float)(a - zw), bs);
-          if (p.acc_out) p.acc_out[(long long)m * p.N + n] = a;
-        }
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (m >= p.M) continue;
+        const int a = acc[i][j][r];
+        float *y = p.y + (long long)z * p.zs_out;
+        y[(long long)m * p.ldy + n] = fmaf(sc, (float)(a - zw), bs);
+        if (p.acc_out) p.acc_out[(long long)m * p.N + n] = a;
       }
     }
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF>
+template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK = 128>
 static hipError_t launch_cfg(const GemmArgs &a, int nz, hipStream_t st) {
-  constexpr int smem_loop = 2 * (BM + BN) * LDS_ROW;
+  constexpr int smem_loop = 2 * (BM + BN) * (BK + 16);
   constexpr int smem_epi = BN * 12 + BM * (BN + 16);
   constexpr int smem = smem_loop > smem_epi ? smem_loop : smem_epi;
   static bool attr_set = false;
-  auto kern = gemm_i8_kernel<BM, BN, WM, WN, EPI, TAG, W4, PF>;
+  auto kern = gemm_i8_kernel<BM, BN, WM, WN, EPI, TAG, W4, PF, BK>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -430,6 +581,7 @@ static hipError_t launch_cfg(const GemmArgs &a, int nz, hipStream_t st) {
   }
   GemmArgs b = a;
   b.xcd_m = best_xm;
+  b.trace = (EPI == g_trace_epi && TAG == g_trace_tag) ? g_trace : nullptr;
   const int cm = (tiles_m + best_xm - 1) / best_xm, cn = (tiles_n + NUM_XCD / best_xm - 1) / (NUM_XCD / best_xm);
   const int grid = NUM_XCD * cm * cn;
   hipLaunchKernelGGL(kern, dim3(grid, 1, nz), dim3(64 * WM * WN), smem, st, b);
@@ -455,10 +607,6 @@ static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
     case 1: return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
     case 2: return launch_cfg<256, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
     case 3: return launch_cfg<256, 256, 2, 4, EPI, TAG, W4, 2>(a, nz, st);
-    case 4: return launch_cfg<64, 128, 2, 2, EPI, TAG, W4, 4>(a, nz, st);
-    case 5: return launch_cfg<64, 64, 2, 2, EPI, TAG, W4, 4>(a, nz, st);
-    case 6: return launch_cfg<128, 64, 2, 2, EPI, TAG, W4, 4>(a, nz, st);
-    case 7: return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 4>(a, nz, st);
     default: break;
   }
   // Large problems: 256x256 tiles on 8 wavefronts (256 ops per byte fetched from L2, the
@@ -482,3 +630,5 @@ hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st, int s
 }
 
 }  // namespace qc
+extern "C" void qc_debug_trace(long long *p, int epi, int tag) { qc::g_trace = p; qc::g_trace_epi = epi; qc::g_trace_tag = tag; }
+

@@ -132,16 +132,20 @@ def main():
         MT, D, R = Beff * m.tokens, m.hidden, m.mlp_dim
         ops = {"gemm_qkv": 2.0 * MT * 3 * D * D, "gemm_proj": 2.0 * MT * D * D,
                "gemm_fc1": 2.0 * MT * R * D, "gemm_fc2": 2.0 * MT * D * R}
-        for k, v in ops.items():
+        # work of one launch: the class's work in one pass over its launches (a pass may cut the batch
+        # into sub-batches that are launched separately)
+        per_pass = n_full * m.depth
+        for k in ops:
             if k in prof:
-                prof[k]["tops"] = v / (prof[k]["avg_us"] * 1e-6) / 1e12
+                ops[k] *= per_pass / prof[k]["launches"]
+                prof[k]["tops"] = ops[k] / (prof[k]["avg_us"] * 1e-6) / 1e12
         if dom["name"] in ops:
             ach = ops[dom["name"]] / (dom["avg_us"] * 1e-6) / 1e12
             roofline = {"bound": "mfma", "kernel": dom["name"], "achieved": ach, "peak": INT8_MFMA_PEAK_TOPS,
                         "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS, "traffic": None,
                         "avg_launch_us": dom["avg_us"], "launches": dom["launches"]}
         elif dom["name"] == "attention":
-            fl = 4.0 * Beff * m.heads * m.tokens * m.tokens * m.head_dim
+            fl = 4.0 * Beff * m.heads * m.tokens * m.tokens * m.head_dim * n_full * m.depth / dom["launches"]
             ach = fl / (dom["avg_us"] * 1e-6) / 1e12
             roofline = {"bound": "mfma", "kernel": "attention", "achieved": ach, "peak": FP32_MFMA_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": ach / FP32_MFMA_PEAK_TFLOPS, "traffic": None,

@@ -4,12 +4,20 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
 #include "qc_internal.h"
 
 namespace qc {
+
+constexpr int MAX_LANES = 4;
+
+// a contiguous range of the (effective) batch handled by one stream; `lane` picks its private scratch
+struct Sub {
+  int b0, nb, lane;
+};
 
 static thread_local char g_err[512] = "";
 
@@ -75,7 +83,7 @@ struct qc_ctx {
   float *emb, *h1, *te, *cond, *mod, *fmod, *tokens, *qkv, *eps;
   int8_t *silu_q, *qa_ln, *qa_attn, *qa_mlp;
   _Float16 *qkv16;            // fp16 (high, low) Q, K words [B,H,T,hd] and V^T halves [B,H,DP,Tp] for the attention kernel
-  long long qkv_part_stride, qkv_v_stride;
+  long long qkv_part_stride, qkv_v_stride;   // words per Q / K array, halves per V^T array
   size_t qkv16_bytes;
   int DP, Tp;
   bool keep_qkv_f32 = false;
@@ -83,6 +91,10 @@ struct qc_ctx {
   float *cal_h, *cal_o, *cal_a, *cal_u, *cal_mod;
   int *cal_slots, *cal_label;
   bool weights_loaded;
+  // a denoiser call may run its batch as up to MAX_LANES independent sub-batches on internal streams
+  hipStream_t lane_stream[4] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev_fork = nullptr, ev_join[4] = {nullptr, nullptr, nullptr, nullptr};
+  int forced_lanes = -1;
   // optional per-kernel-class timing with HIP events (qc_profile_begin / qc_profile_end)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_pool;
@@ -179,7 +191,7 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
   float *flin_w = a.take<float>(O * D), *flin_b = a.take<float>(O);
   QParam *dev_qp = a.take<QParam>(L * QC_NUM_SITES);
   float *cache = a.take<float>(L * 2 * M * D);
-  float *emb = a.take<float>(d.freq_dim), *h1 = a.take<float>(D), *te = a.take<float>(D);
+  float *emb = a.take<float>(MAX_LANES * d.freq_dim), *h1 = a.take<float>(MAX_LANES * D), *te = a.take<float>(MAX_LANES * D);
   float *cond = a.take<float>(B * D), *mod = a.take<float>(L * B * 6 * D), *fmod = a.take<float>(B * 2 * D);
   float *tokens = a.take<float>(M * D), *qkv = a.take<float>(M * 3 * D), *eps = a.take<float>(B * C * d.latent_h * d.latent_w);
   int8_t *silu_q = a.take<int8_t>(L * B * D), *qa_ln = a.take<int8_t>(M * D), *qa_attn = a.take<int8_t>(M * D);
@@ -247,6 +259,11 @@ int qc_create(const qc_model_desc *desc, void *arena, size_t arena_bytes, int ma
 int qc_destroy(qc_ctx *ctx) {
   if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
   for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
+  for (int i = 0; i < MAX_LANES; ++i) {
+    if (ctx->lane_stream[i]) (void)hipStreamDestroy(ctx->lane_stream[i]);
+    if (ctx->ev_join[i]) (void)hipEventDestroy(ctx->ev_join[i]);
+  }
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
   delete ctx;
   return QC_OK;
 }
@@ -415,29 +432,36 @@ static float *cache_slot(const qc_ctx *ctx, int block, int which) {
 }
 
 // adaLN projection of blocks [l0, l0+nl): mod[l, b, :] = Lin_q(codes of SiLU(c)); gates only on request.
-static int run_adaln(qc_ctx *ctx, int l0, int nl, int B, bool gates_only, hipStream_t st) {
+static int run_adaln(qc_ctx *ctx, int l0, int nl, const Sub &sb, bool gates_only, hipStream_t st) {
   const size_t D = ctx->D;
   GemmArgs a{};
   const LinearQ &q = ctx->blk[l0].lin[QC_SITE_ADA];
-  a.A = ctx->silu_q + (size_t)l0 * ctx->max_batch * D;
+  a.A = ctx->silu_q + ((size_t)l0 * ctx->max_batch + sb.b0) * D;
   a.W = q.q; a.w_scale = q.scale; a.wsum = q.wsum; a.bias = q.bias;
-  a.M = B; a.N = (int)(6 * D); a.K = (int)D; a.lda = (int)D; a.w4 = ctx->d.weight_bits == 4;
+  a.M = sb.nb; a.N = (int)(6 * D); a.K = (int)D; a.lda = (int)D; a.w4 = ctx->d.weight_bits == 4;
   a.a_qp = ctx->dev_qp + (size_t)l0 * QC_NUM_SITES + QC_SITE_ADA;
   a.zs_A = (long long)ctx->max_batch * D; a.zs_W = (long long)ctx->ada_w_stride_bytes; a.zs_vecN = (long long)(6 * D);
   a.zs_out = (long long)ctx->max_batch * 6 * D; a.zs_qp = QC_NUM_SITES;
   a.sel_D = (gates_only && D % 128 == 0) ? (int)D : 0;
-  a.y = ctx->mod + (size_t)l0 * ctx->max_batch * 6 * D; a.ldy = (int)(6 * D);
+  a.y = ctx->mod + ((size_t)l0 * ctx->max_batch + sb.b0) * 6 * D; a.ldy = (int)(6 * D);
   QC_PROF(QC_K_ADALN);
   QC_HIP(launch_gemm(a, EPI_F32, nl, st, QC_SITE_ADA));
   return QC_OK;
 }
 
-static int run_block_full(qc_ctx *ctx, int l, float *x, int B, hipStream_t st) {
-  const int D = ctx->D, R = ctx->R, T = ctx->T, M = B * T;
-  const float *mod = ctx->mod + (size_t)l * ctx->max_batch * 6 * D;
+// One full block on the rows of sub-batch sb; x points at the first of those rows.
+static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream_t st) {
+  const int D = ctx->D, R = ctx->R, T = ctx->T, B = sb.nb, M = B * T;
+  const size_t row0 = (size_t)sb.b0 * T;
+  const float *mod = ctx->mod + ((size_t)l * ctx->max_batch + sb.b0) * 6 * D;
   const QParam *qp = ctx->dev_qp + (size_t)l * QC_NUM_SITES;
   const bool w4 = ctx->d.weight_bits == 4;
   const BlockQ &bq = ctx->blk[l];
+  int8_t *qa_ln = ctx->qa_ln + row0 * D, *qa_attn = ctx->qa_attn + row0 * D, *qa_mlp = ctx->qa_mlp + row0 * R;
+  unsigned *q_words = (unsigned *)ctx->qkv16 + (size_t)sb.b0 * ctx->H * T * ctx->hd;
+  unsigned *k_words = q_words + ctx->qkv_part_stride;
+  _Float16 *vt_hi = ctx->qkv16 + 4 * ctx->qkv_part_stride + (size_t)sb.b0 * ctx->H * ctx->DP * ctx->Tp;
+  _Float16 *vt_lo = vt_hi + ctx->qkv_v_stride;
   auto base = [&](const LinearQ &q, const int8_t *A, int K, int site) {
     GemmArgs a{};
     a.A = A; a.W = q.q; a.w_scale = q.scale; a.wsum = q.wsum; a.bias = q.bias;
@@ -446,46 +470,46 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, int B, hipStream_t st) {
   };
   {
     QC_PROF(QC_K_LN_QUANT);
-    QC_HIP(launch_ln_mod_quant(x, mod, mod + D, 6 * D, M, D, T, qp + QC_SITE_QKV, ctx->qa_ln, nullptr, st));
+    QC_HIP(launch_ln_mod_quant(x, mod, mod + D, 6 * D, M, D, T, qp + QC_SITE_QKV, qa_ln, nullptr, st));
   }
   {
-    GemmArgs a = base(bq.lin[QC_SITE_QKV], ctx->qa_ln, D, QC_SITE_QKV);
-    a.qkv16 = ctx->qkv16; a.part_stride = ctx->qkv_part_stride; a.v_stride = ctx->qkv_v_stride;
+    GemmArgs a = base(bq.lin[QC_SITE_QKV], qa_ln, D, QC_SITE_QKV);
+    a.q_words = q_words; a.k_words = k_words; a.vt_hi = vt_hi; a.vt_lo = vt_lo;
     a.heads = ctx->H; a.hd = ctx->hd; a.DP = ctx->DP; a.Tp = ctx->Tp; a.rows_per_batch = T;
     a.q_scale = 1.4426950408889634f / std::sqrt((float)ctx->hd);     // log2(e) / sqrt(d): the softmax runs in base 2
-    a.y = ctx->keep_qkv_f32 ? ctx->qkv : nullptr; a.ldy = 3 * D;
+    a.y = ctx->keep_qkv_f32 ? ctx->qkv + row0 * 3 * D : nullptr; a.ldy = 3 * D;
     QC_PROF(QC_K_GEMM_QKV);
     QC_HIP(launch_gemm(a, EPI_QKV, 1, st, QC_SITE_QKV));
   }
   {
     QC_PROF(QC_K_ATTENTION);
-    QC_HIP(launch_attention_f16(ctx->qkv16, ctx->qkv_part_stride, ctx->qkv_v_stride, B, T, ctx->Tp, ctx->H, ctx->hd, ctx->DP,
-                                qp + QC_SITE_PROJ, ctx->qa_attn, st));
+    QC_HIP(launch_attention_f16(q_words, k_words, vt_hi, vt_lo, B, T, ctx->Tp, ctx->H, ctx->hd, ctx->DP, qp + QC_SITE_PROJ,
+                                qa_attn, st));
   }
   {
-    GemmArgs a = base(bq.lin[QC_SITE_PROJ], ctx->qa_attn, D, QC_SITE_PROJ);
-    a.cache_out = cache_slot(ctx, l, QC_CACHE_ATTN); a.x = x; a.gate = mod + 2 * D; a.ld_gate = 6 * D; a.rows_per_batch = T;
+    GemmArgs a = base(bq.lin[QC_SITE_PROJ], qa_attn, D, QC_SITE_PROJ);
+    a.cache_out = cache_slot(ctx, l, QC_CACHE_ATTN) + row0 * D; a.x = x; a.gate = mod + 2 * D; a.ld_gate = 6 * D;
+    a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_PROJ);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_PROJ));
   }
   {
     QC_PROF(QC_K_LN_QUANT);
-    QC_HIP(launch_ln_mod_quant(x, mod + 3 * D, mod + 4 * D, 6 * D, M, D, T, qp + QC_SITE_FC1, ctx->qa_ln, nullptr, st));
+    QC_HIP(launch_ln_mod_quant(x, mod + 3 * D, mod + 4 * D, 6 * D, M, D, T, qp + QC_SITE_FC1, qa_ln, nullptr, st));
   }
   {
-    GemmArgs a = base(bq.lin[QC_SITE_FC1], ctx->qa_ln, D, QC_SITE_FC1);
-    a.q_out = ctx->qa_mlp; a.ldq = R; a.o_qp = qp + QC_SITE_FC2;
+    GemmArgs a = base(bq.lin[QC_SITE_FC1], qa_ln, D, QC_SITE_FC1);
+    a.q_out = qa_mlp; a.ldq = R; a.o_qp = qp + QC_SITE_FC2;
     QC_PROF(QC_K_GEMM_FC1);
     QC_HIP(launch_gemm(a, EPI_GELU_Q, 1, st, QC_SITE_FC1));
   }
   {
-    GemmArgs a = base(bq.lin[QC_SITE_FC2], ctx->qa_mlp, R, QC_SITE_FC2);
-    a.cache_out = cache_slot(ctx, l, QC_CACHE_MLP); a.x = x; a.gate = mod + 5 * D; a.ld_gate = 6 * D; a.rows_per_batch = T;
+    GemmArgs a = base(bq.lin[QC_SITE_FC2], qa_mlp, R, QC_SITE_FC2);
+    a.cache_out = cache_slot(ctx, l, QC_CACHE_MLP) + row0 * D; a.x = x; a.gate = mod + 5 * D; a.ld_gate = 6 * D;
+    a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_FC2);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_FC2));
   }
-  ctx->cache_batch[(size_t)l * 2] = B;
-  ctx->cache_batch[(size_t)l * 2 + 1] = B;
   return QC_OK;
 }
 
@@ -502,9 +526,14 @@ int qc_dit_block(qc_ctx *ctx, int block, int mode, float *x, const float *c, int
   const size_t D = ctx->D;
   QC_HIP(launch_silu_quant(c, B, (int)D, 1, ctx->dev_qp + (size_t)block * QC_NUM_SITES + QC_SITE_ADA, QC_NUM_SITES,
                            ctx->silu_q + (size_t)block * ctx->max_batch * D, (size_t)ctx->max_batch * D, st));
-  rc = run_adaln(ctx, block, 1, B, mode == QC_CACHED, st);
+  const Sub whole{0, B, 0};
+  rc = run_adaln(ctx, block, 1, whole, mode == QC_CACHED, st);
   if (rc) return rc;
-  if (mode == QC_FULL) return run_block_full(ctx, block, x, B, st);
+  if (mode == QC_FULL) {
+    rc = run_block_full(ctx, block, x, whole, st);
+    ctx->cache_batch[(size_t)block * 2] = ctx->cache_batch[(size_t)block * 2 + 1] = B;
+    return rc;
+  }
   const float *mod = ctx->mod + (size_t)block * ctx->max_batch * 6 * D;
   QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, QC_CACHE_ATTN), mod + 2 * D, (int)(6 * D), B, ctx->T, (int)D, st));
   QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, QC_CACHE_MLP), mod + 5 * D, (int)(6 * D), B, ctx->T, (int)D, st));
@@ -577,41 +606,102 @@ int qc_keep_qkv_f32(qc_ctx *ctx, int on) {
 }
 
 // conditioning vector c[B, D] for timestep t and the labels (null label for b >= n_labels)
-static int run_conditioning(qc_ctx *ctx, int t, const int32_t *labels, int n_labels, int B, hipStream_t st) {
+static int run_conditioning(qc_ctx *ctx, int t, const int32_t *labels, int n_labels, const Sub &sb, hipStream_t st) {
   const int D = ctx->D, fd = ctx->d.freq_dim;
-  QC_HIP(launch_time_embed(t, nullptr, 1, fd, ctx->emb, st));
-  QC_HIP(launch_small_linear(ctx->emb, fd, ctx->t_w1, ctx->t_b1, ctx->h1, D, 1, D, fd, 0, 1, st));
-  QC_HIP(launch_small_linear(ctx->h1, D, ctx->t_w2, ctx->t_b2, ctx->te, D, 1, D, D, 0, 0, st));
-  QC_HIP(launch_cond_finish(ctx->te, ctx->label_table, labels, n_labels, ctx->d.num_classes, B, D, ctx->cond, st));
+  float *emb = ctx->emb + (size_t)sb.lane * fd, *h1 = ctx->h1 + (size_t)sb.lane * D, *te = ctx->te + (size_t)sb.lane * D;
+  QC_HIP(launch_time_embed(t, nullptr, 1, fd, emb, st));
+  QC_HIP(launch_small_linear(emb, fd, ctx->t_w1, ctx->t_b1, h1, D, 1, D, fd, 0, 1, st));
+  QC_HIP(launch_small_linear(h1, D, ctx->t_w2, ctx->t_b2, te, D, 1, D, D, 0, 0, st));
+  QC_HIP(launch_cond_finish(te, ctx->label_table, labels, n_labels, ctx->d.num_classes, sb.nb, D,
+                            ctx->cond + (size_t)sb.b0 * D, sb.b0, st));
   return QC_OK;
+}
+
+// The network on one sub-batch (rows b0 .. b0+nb of the effective batch) in three parts, so that the
+// caller can interleave the launches of several sub-batches: everything before the blocks ...
+static int denoise_head(qc_ctx *ctx, const float *x, int t, const int32_t *labels, int n_labels, const Sub &sb, int mode,
+                        hipStream_t st) {
+  const int D = ctx->D, L = ctx->L, B = sb.nb;
+  float *cond = ctx->cond + (size_t)sb.b0 * D, *fmod = ctx->fmod + (size_t)sb.b0 * 2 * D;
+  int rc = run_conditioning(ctx, t, labels, n_labels, sb, st);
+  if (rc) return rc;
+  QC_HIP(launch_silu_quant(cond, B, D, L, ctx->dev_qp + QC_SITE_ADA, QC_NUM_SITES, ctx->silu_q + (size_t)sb.b0 * D,
+                           (size_t)ctx->max_batch * D, st));
+  QC_HIP(launch_small_linear(cond, D, ctx->fada_w, ctx->fada_b, fmod, 2 * D, B, 2 * D, D, 1, 0, st));
+  rc = run_adaln(ctx, 0, L, sb, mode == QC_CACHED, st);
+  if (rc) return rc;
+  QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens + (size_t)sb.b0 * ctx->T * D, B, n_labels, ctx->C,
+                      ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, sb.b0, st));
+  return QC_OK;
+}
+
+// ... all blocks of a cached step in one launch, and the final layer.
+static int denoise_tail(qc_ctx *ctx, const Sub &sb, int mode, float *eps_out, hipStream_t st) {
+  const int D = ctx->D, L = ctx->L, B = sb.nb;
+  const size_t lat = (size_t)ctx->C * ctx->d.latent_h * ctx->d.latent_w;
+  float *tokens = ctx->tokens + (size_t)sb.b0 * ctx->T * D;
+  if (mode == QC_CACHED) {
+    const size_t slot = (size_t)ctx->max_batch * ctx->T * D;
+    QC_PROF(QC_K_CACHED_BLOCKS);
+    QC_HIP(launch_cached_blocks(tokens, ctx->cache + (size_t)sb.b0 * ctx->T * D, 2 * slot, slot, ctx->mod + (size_t)sb.b0 * 6 * D,
+                                (size_t)ctx->max_batch * 6 * D, 6 * D, L, B, ctx->T, D, st));
+  }
+  QC_HIP(launch_final(tokens, ctx->fmod + (size_t)sb.b0 * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + (size_t)sb.b0 * lat, B,
+                      ctx->C, ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, st));
+  return QC_OK;
+}
+
+// Small batches leave most of the chip idle inside every kernel (a launch has fewer workgroups than
+// compute units, and every dependent kernel pays a few microseconds of dispatch latency), and latents
+// are independent, so the batch may be cut into sub-batches that run the network concurrently: the first
+// on the caller's stream, the others on internal streams, their launches interleaved block by block.
+// QC_LANES (environment) forces the number of sub-batches.
+static int choose_lanes(qc_ctx *ctx, int B) {
+  if (ctx->forced_lanes < 0) {
+    const char *e = getenv("QC_LANES");
+    ctx->forced_lanes = e ? atoi(e) : 0;
+  }
+  int n = ctx->forced_lanes > 0 ? ctx->forced_lanes : ((long long)B * ctx->T <= 4096 ? 2 : 1);
+  if (n > MAX_LANES) n = MAX_LANES;
+  if (n > B) n = B;
+  return n < 1 ? 1 : n;
 }
 
 static int denoise_impl(qc_ctx *ctx, const float *x, int t, const int32_t *labels, int n_labels, int B, int mode,
                         float *eps_out, hipStream_t st) {
-  const int D = ctx->D, L = ctx->L;
-  int rc = run_conditioning(ctx, t, labels, n_labels, B, st);
-  if (rc) return rc;
-  QC_HIP(launch_silu_quant(ctx->cond, B, D, L, ctx->dev_qp + QC_SITE_ADA, QC_NUM_SITES, ctx->silu_q,
-                           (size_t)ctx->max_batch * D, st));
-  QC_HIP(launch_small_linear(ctx->cond, D, ctx->fada_w, ctx->fada_b, ctx->fmod, 2 * D, B, 2 * D, D, 1, 0, st));
-  rc = run_adaln(ctx, 0, L, B, mode == QC_CACHED, st);
-  if (rc) return rc;
-  QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, B, n_labels, ctx->C, ctx->d.latent_h,
-                      ctx->d.latent_w, ctx->d.patch, D, st));
-  if (mode == QC_FULL) {
-    for (int l = 0; l < L; ++l) {
-      rc = run_block_full(ctx, l, ctx->tokens, B, st);
-      if (rc) return rc;
-    }
-  } else {
-    const size_t slot = (size_t)ctx->max_batch * ctx->T * D;
-    QC_PROF(QC_K_CACHED_BLOCKS);
-    QC_HIP(launch_cached_blocks(ctx->tokens, ctx->cache, 2 * slot, slot, ctx->mod, (size_t)ctx->max_batch * 6 * D, 6 * D, L, B,
-                                ctx->T, D, st));
+  const int lanes = choose_lanes(ctx, B);
+  Sub sub[MAX_LANES];
+  hipStream_t ls[MAX_LANES];
+  for (int i = 0, b0 = 0; i < lanes; ++i) {
+    sub[i] = Sub{b0, B / lanes + (i < B % lanes ? 1 : 0), i};
+    b0 += sub[i].nb;
   }
-  QC_HIP(launch_final(ctx->tokens, ctx->fmod, ctx->flin_w, ctx->flin_b, eps_out, B, ctx->C, ctx->d.latent_h, ctx->d.latent_w,
-                      ctx->d.patch, D, st));
-  return QC_OK;
+  ls[0] = st;
+  if (lanes > 1) {
+    if (!ctx->ev_fork) QC_HIP(hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
+    QC_HIP(hipEventRecord(ctx->ev_fork, st));
+    for (int i = 1; i < lanes; ++i) {
+      if (!ctx->lane_stream[i]) QC_HIP(hipStreamCreateWithFlags(&ctx->lane_stream[i], hipStreamNonBlocking));
+      if (!ctx->ev_join[i]) QC_HIP(hipEventCreateWithFlags(&ctx->ev_join[i], hipEventDisableTiming));
+      ls[i] = ctx->lane_stream[i];
+      QC_HIP(hipStreamWaitEvent(ls[i], ctx->ev_fork, 0));
+    }
+  }
+  int rc = QC_OK;
+  for (int i = 0; i < lanes && !rc; ++i) rc = denoise_head(ctx, x, t, labels, n_labels, sub[i], mode, ls[i]);
+  if (mode == QC_FULL)
+    for (int l = 0; l < ctx->L && !rc; ++l)
+      for (int i = 0; i < lanes && !rc; ++i)
+        rc = run_block_full(ctx, l, ctx->tokens + (size_t)sub[i].b0 * ctx->T * ctx->D, sub[i], ls[i]);
+  for (int i = 0; i < lanes && !rc; ++i) rc = denoise_tail(ctx, sub[i], mode, eps_out, ls[i]);
+  // join even after an error so that the internal streams never run past the caller's stream unobserved
+  for (int i = 1; i < lanes; ++i) {
+    QC_HIP(hipEventRecord(ctx->ev_join[i], ls[i]));
+    QC_HIP(hipStreamWaitEvent(st, ctx->ev_join[i], 0));
+  }
+  if (rc == QC_OK && mode == QC_FULL)
+    for (int &v : ctx->cache_batch) v = B;
+  return rc;
 }
 
 static int check_denoise(qc_ctx *ctx, const float *x, const int32_t *labels, int n_labels, int B, int mode) {
@@ -735,10 +825,10 @@ int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, co
   for (int i = 0; i < n; ++i) {
     QC_HIP(hipMemcpyAsync(ctx->cal_label, &y[i], sizeof(int), hipMemcpyHostToDevice, st));
     QC_HIP(hipStreamSynchronize(st));
-    rc = run_conditioning(ctx, t[i], ctx->cal_label, 1, 1, st);
+    rc = run_conditioning(ctx, t[i], ctx->cal_label, 1, Sub{0, 1, 0}, st);
     if (rc) return rc;
     QC_HIP(launch_embed(x + i * lat, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 1, 1, ctx->C, ctx->d.latent_h,
-                        ctx->d.latent_w, ctx->d.patch, D, st));
+                        ctx->d.latent_w, ctx->d.patch, D, 0, st));
     for (int l = 0; l < L; ++l) {
       const qc_block_weights_f32 &b = w->blocks[l];
       int *slot = ctx->cal_slots + (size_t)l * QC_NUM_SITES * 2;

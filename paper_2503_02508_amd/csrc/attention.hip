@@ -208,9 +208,10 @@ __device__ __forceinline__ void unpack_pairs(v4u p, v2u &hi, v2u &lo) {
 }
 
 template <int NCH, int NEB>   // feature chunks of 32 (operand width), feature blocks of 16 that hold real features
-__global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__restrict__ qkv16, long long ps, long long vs, int T,
+__global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__restrict__ Qp, const unsigned *__restrict__ Kp,
+                                                            const _Float16 *__restrict__ Vh, const _Float16 *__restrict__ Vl, int T,
                                                             int Tp, int H, int hd, int DPv, const QParam *qp,
-                                                            int8_t *__restrict__ q_out) {
+                                                            int8_t *__restrict__ q_out, long long *trace) {
   constexpr int DP = 32 * NCH;
   constexpr int KROW = DP + 8;    // halves per K row in LDS (16 bytes of padding)
   constexpr int VROW = 64 + 8;    // halves per V^T row in LDS
@@ -223,8 +224,9 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
   const int bh = blockIdx.y, b = bh / H, h = bh % H;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ql = lane & 15, g = lane >> 4;
-  const unsigned *Qp = (const unsigned *)qkv16, *Kp = Qp + ps;
-  const _Float16 *Vh = qkv16 + 4 * ps, *Vl = Vh + vs;
+  long long tr[6] = {0, 0, 0, 0, 0, 0}, tl = 0;
+  if (trace) { tr[0] = wall_clock64(); tl = tr[0]; }
+#define QC_TR(k) if (trace) { long long now_ = wall_clock64(); tr[k] += now_ - tl; tl = now_; }
   const long long tok_base = (long long)bh * T * hd;
   const long long vt_base = (long long)bh * DPv * Tp;
   const int kchunks = 64 * (hd / 4);            // 16-byte chunks of one K tile
@@ -232,25 +234,6 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
   // feature padding of the K tile is never written below: clear it once
   for (int i = tid; i < 2 * 64 * KROW / 8; i += 256) ((v8h *)&Ksh[0][0])[i] = (v8h){0, 0, 0, 0, 0, 0, 0, 0};
 
-  int q_row[2];
-  v8h qh[2][NCH], qlo[2][NCH];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    q_row[j] = blockIdx.x * 128 + wave * 32 + j * 16 + ql;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-      v2u h0 = {0, 0}, l0 = {0, 0}, h1 = {0, 0}, l1 = {0, 0};
-      const int f = 32 * c + 8 * g;
-      if (q_row[j] < T) {
-        const unsigned *src = Qp + tok_base + (long long)q_row[j] * hd + f;
-        if (f < hd) unpack_pairs(*(const v4u *)src, h0, l0);
-        if (f + 4 < hd) unpack_pairs(*(const v4u *)(src + 4), h1, l1);
-      }
-      v4u hh = {h0.x, h0.y, h1.x, h1.y}, ll = {l0.x, l0.y, l1.x, l1.y};
-      qh[j][c] = *(v8h *)&hh;
-      qlo[j][c] = *(v8h *)&ll;
-    }
-  }
   v4f o[2][NEB];
 #pragma unroll
   for (int j = 0; j < 2; ++j)
@@ -309,12 +292,33 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
     }
   };
 
-  load_tile(0);
+  load_tile(0);                            // first key tile and the queries are in flight together
+  int q_row[2];
+  v8h qh[2][NCH], qlo[2][NCH];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    q_row[j] = blockIdx.x * 128 + wave * 32 + j * 16 + ql;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      v2u h0 = {0, 0}, l0 = {0, 0}, h1 = {0, 0}, l1 = {0, 0};
+      const int f = 32 * c + 8 * g;
+      if (q_row[j] < T) {
+        const unsigned *src = Qp + tok_base + (long long)q_row[j] * hd + f;
+        if (f < hd) unpack_pairs(*(const v4u *)src, h0, l0);
+        if (f + 4 < hd) unpack_pairs(*(const v4u *)(src + 4), h1, l1);
+      }
+      v4u hh = {h0.x, h0.y, h1.x, h1.y}, ll = {l0.x, l0.y, l1.x, l1.y};
+      qh[j][c] = *(v8h *)&hh;
+      qlo[j][c] = *(v8h *)&ll;
+    }
+  }
+  QC_TR(1)
   for (int k0 = 0; k0 < T; k0 += 64) {
     __syncthreads();                       // everyone is done with the previous tile
     store_tile();
     __syncthreads();
     if (k0 + 64 < T) load_tile(k0 + 64);   // in flight during the MFMAs below
+    QC_TR(2)
 
     v4f s[2][4];
 #pragma unroll
@@ -334,6 +338,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
       s[0][kt] = acc0;
       s[1][kt] = acc1;
     }
+    QC_TR(3)
     v8h ph[2][2], pl[2][2];
     const bool ragged_tile = k0 + 64 > T;
 #pragma unroll
@@ -365,6 +370,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
           pl[j][kt >> 1][(kt & 1) * 4 + r] = (_Float16)(pv - (float)hi);
         }
     }
+    QC_TR(4)
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -378,6 +384,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
           o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[j][a], o[j][e], 0, 0, 0);
         }
       }
+    QC_TR(5)
   }
 
   const QParam t = *qp;
@@ -402,16 +409,24 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const _Float16 *__re
                                            ((unsigned)(c[2] & 0xFF) << 16) | ((unsigned)(c[3] & 0xFF) << 24);
     }
   }
+  if (trace && tid == 0) {
+    long long *o_ = trace + 8 * (long long)(blockIdx.y * gridDim.x + blockIdx.x);
+    o_[0] = tr[0]; o_[1] = tr[1]; o_[2] = tr[2]; o_[3] = tr[3]; o_[4] = tr[4]; o_[5] = tr[5]; o_[6] = wall_clock64();
+  }
+#undef QC_TR
 }
 
-hipError_t launch_attention_f16(const _Float16 *qkv16, long long part_stride, long long v_stride, int B, int T, int Tp, int H,
-                                int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st) {
+extern long long *g_trace;
+extern int g_trace_epi;
+
+hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
+                                int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st) {
   dim3 grid((T + 127) / 128, B * H);
   const int neb = (hd + 15) / 16, nch = (hd + 31) / 32;
   if (hd > 80 || hd % 4) return hipErrorInvalidValue;      // K prefetch registers are sized for d <= 80
 #define QC_ATT(NCH, NEB)                                                                                               \
-  hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB>), grid, dim3(256), 0, st, qkv16, part_stride, v_stride, T, Tp, H, hd, \
-                     DPv, qp, q_out)
+  hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, H, hd, \
+                     DPv, qp, q_out, g_trace_epi == 100 ? g_trace : nullptr)
   if (nch == 1 && neb == 1) QC_ATT(1, 1);
   else if (nch == 1) QC_ATT(1, 2);
   else if (nch == 2 && neb == 3) QC_ATT(2, 3);

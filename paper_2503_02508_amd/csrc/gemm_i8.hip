@@ -370,7 +370,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     // split every value into fp16 high and low parts (hi + lo carries ~22 bits) and scatter to the
     // head-major layouts of the attention kernel
     const int T = p.rows_per_batch, D = p.N / 3;
-    _Float16 *vh = p.qkv16 + 4 * p.part_stride, *vl = vh + p.v_stride;
+    _Float16 *vh = p.vt_hi, *vl = p.vt_lo;
     const bool fast_t = (T % 4) == 0;
     const bool tile_one_batch = (T % BM) == 0;      // then every row of the tile belongs to batch element m0 / T
     const int b_tile = m0 / T;
@@ -383,7 +383,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
       const float bs = bias ? bias[n] : 0.0f;
       const int part = n / D, nn = n - part * D, h = nn / p.hd, e = nn - h * p.hd;
       const float mul = part == 0 ? p.q_scale : 1.0f;
-      unsigned *dpair = (unsigned *)p.qkv16 + (long long)part * p.part_stride;   // Q / K: one (hi | lo << 16) word per element
+      unsigned *dpair = part == 0 ? p.q_words : p.k_words;   // Q / K: one (hi | lo << 16) word per element
       if (tile_one_batch && fast_t && m0 + BM <= p.M && !p.y) {
         // interior tile inside one batch element: 32-bit offsets advanced row by row, no per-element index arithmetic
         const int tb = m0 - b_tile * T + wm0 + (lane >> 5) * 4;            // token of this lane's first row

@@ -67,8 +67,8 @@ struct GemmArgs {
   // EPI_QKV: Q | K | V columns go out as fp16 (high part, low part) for the attention kernel:
   // Q (pre-scaled by q_scale) and K as one (hi | lo << 16) word per element, [B, H, T, hd];
   // V transposed and key-permuted, separate hi and lo arrays [B, H, DP, Tp] (DP = hd rounded up to 16)
-  _Float16 *qkv16;           // Q words, K words (part_stride words each), then Vh, Vl (v_stride halves each)
-  long long part_stride, v_stride;
+  unsigned *q_words, *k_words;
+  _Float16 *vt_hi, *vt_lo;
   int heads, hd, DP, Tp;
   float q_scale;
 };
@@ -92,11 +92,11 @@ hipError_t launch_small_linear(const float *x, int ldx, const float *W, const fl
                                int K, int act_in, int act_out, hipStream_t st);
 hipError_t launch_time_embed(int t, const int32_t *t_arr, int B, int dim, float *out, hipStream_t st);
 hipError_t launch_cond_finish(const float *te, const float *table, const int32_t *labels, int n_labels, int null_label,
-                              int B, int D, float *c, hipStream_t st);
+                              int B, int D, float *c, int b_off, hipStream_t st);
 hipError_t launch_silu_quant(const float *c, int B, int D, int L, const QParam *qp, int qp_stride, int8_t *q,
                              size_t l_stride, hipStream_t st);
 hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, float *tok, int B, int n_src,
-                        int C, int H, int W, int p, int D, hipStream_t st);
+                        int C, int H, int W, int p, int D, int b_off, hipStream_t st);
 hipError_t launch_final(const float *tok, const float *fmod, const float *fw, const float *fb, float *eps, int B, int C,
                         int H, int W, int p, int D, hipStream_t st);
 hipError_t launch_cache_store(const float *src, float *dst, size_t n, hipStream_t st);
@@ -110,8 +110,8 @@ hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, floa
 hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, int HW, hipStream_t st);
 hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const QParam *qp, int8_t *q_out, float *f32_out,
                             hipStream_t st);
-hipError_t launch_attention_f16(const _Float16 *qkv16, long long part_stride, long long v_stride, int B, int T, int Tp, int H,
-                                int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st);
+hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
+                                int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st);
 // calibration helpers
 hipError_t launch_linear_f32(const float *x, const float *W, const float *b, float *y, int M, int N, int K, int act_out,
                              hipStream_t st);

@@ -112,21 +112,30 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // The value that gets quantised is formed in fp64 and rounded to fp32 once: the codes then differ from
 // exact arithmetic only where the fp32 residual stream itself does, which keeps code flips (and the
 // error they seed in every later layer) at the floor.
+// One workgroup (4 wavefronts) per token row: short per-thread work and 8 wavefronts per SIMD keep the
+// two memory round trips (row in, codes out) and the fp64 arithmetic of different rows overlapped.
+__device__ __forceinline__ double block_sum_d(double v, double *red, int slot) {
+  v = wave_sum_d(v);
+  if ((threadIdx.x & 63) == 0) red[slot * 4 + (threadIdx.x >> 6)] = v;
+  __syncthreads();
+  return (red[slot * 4] + red[slot * 4 + 1]) + (red[slot * 4 + 2] + red[slot * 4 + 3]);
+}
+
 __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restrict__ x, const float *__restrict__ shift,
                                                            const float *__restrict__ scale, int ld_mod, int M, int D, int T,
                                                            const QParam *qp, int8_t *__restrict__ q,
                                                            float *__restrict__ f32_out) {
-  const int lane = threadIdx.x & 63;
-  const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (m >= M) return;
+  constexpr int IT = 2;                      // D <= 2048: at most two float4 per thread
+  __shared__ double red[8];
+  const int m = blockIdx.x;
   const float *row = x + (size_t)m * D;
   const int b = m / T;
   const float *sh = shift + (size_t)b * ld_mod, *sc = scale + (size_t)b * ld_mod;
-  float4 v[LN_MAX_IT], s4[LN_MAX_IT], c4[LN_MAX_IT];
+  float4 v[IT], s4[IT], c4[IT];
   double sum = 0.0;
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it) {
-    const int k = (lane + 64 * it) * 4;
+  for (int it = 0; it < IT; ++it) {
+    const int k = (threadIdx.x + 256 * it) * 4;
     if (k < D) {
       v[it] = *(const float4 *)(row + k);
       s4[it] = *(const float4 *)(sh + k);      // issued together with the row: one memory round trip
@@ -134,21 +143,21 @@ __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restri
     }
   }
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it) {
-    const int k = (lane + 64 * it) * 4;
+  for (int it = 0; it < IT; ++it) {
+    const int k = (threadIdx.x + 256 * it) * 4;
     if (k < D) sum += ((double)v[it].x + (double)v[it].y) + ((double)v[it].z + (double)v[it].w);
   }
-  const double mean = wave_sum_d(sum) / (double)D;
+  const double mean = block_sum_d(sum, red, 0) / (double)D;
   double sq = 0.0;
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it) {
-    const int k = (lane + 64 * it) * 4;
+  for (int it = 0; it < IT; ++it) {
+    const int k = (threadIdx.x + 256 * it) * 4;
     if (k < D) {
       const double a = v[it].x - mean, bq = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
       sq += (a * a + bq * bq) + (c * c + d * d);
     }
   }
-  const double rstd = 1.0 / sqrt(wave_sum_d(sq) / (double)D + 1e-6);
+  const double rstd = 1.0 / sqrt(block_sum_d(sq, red, 1) / (double)D + 1e-6);
   float qs = 1.0f;
   int qz = 0;
   if (qp) {
@@ -157,8 +166,8 @@ __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restri
     qz = t.z;
   }
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it) {
-    const int k = (lane + 64 * it) * 4;
+  for (int it = 0; it < IT; ++it) {
+    const int k = (threadIdx.x + 256 * it) * 4;
     if (k < D) {
       const float h0 = (float)((v[it].x - mean) * rstd * (1.0 + (double)c4[it].x) + (double)s4[it].x);
       const float h1 = (float)((v[it].y - mean) * rstd * (1.0 + (double)c4[it].y) + (double)s4[it].y);
@@ -174,8 +183,7 @@ __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restri
 
 hipError_t launch_ln_mod_quant(const float *x, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
                                const QParam *qp, int8_t *q, float *f32_out, hipStream_t st) {
-  hipLaunchKernelGGL(ln_mod_quant_kernel, dim3((M + 3) / 4), dim3(256), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q,
-                     f32_out);
+  hipLaunchKernelGGL(ln_mod_quant_kernel, dim3(M), dim3(256), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q, f32_out);
   return hipGetLastError();
 }
 
@@ -240,18 +248,18 @@ hipError_t launch_time_embed(int t, const int32_t *, int B, int dim, float *out,
 
 __global__ void cond_finish_kernel(const float *__restrict__ te, const float *__restrict__ table,
                                    const int32_t *__restrict__ labels, int n_labels, int null_label, int B, int D,
-                                   float *__restrict__ c) {
+                                   float *__restrict__ c, int b_off) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B * D) return;
   const int b = i / D, n = i % D;
-  const int y = b < n_labels ? labels[b] : null_label;
+  const int y = b + b_off < n_labels ? labels[b + b_off] : null_label;   // b_off: position of this sub-batch in the batch
   c[i] = te[n] + table[(size_t)y * D + n];   // one timestep per call: te is a single row
 }
 
 hipError_t launch_cond_finish(const float *te, const float *table, const int32_t *labels, int n_labels, int null_label,
-                              int B, int D, float *c, hipStream_t st) {
+                              int B, int D, float *c, int b_off, hipStream_t st) {
   hipLaunchKernelGGL(cond_finish_kernel, dim3((B * D + 255) / 256), dim3(256), 0, st, te, table, labels, n_labels,
-                     null_label, B, D, c);
+                     null_label, B, D, c, b_off);
   return hipGetLastError();
 }
 
@@ -278,13 +286,13 @@ hipError_t launch_silu_quant(const float *c, int B, int D, int L, const QParam *
 // tok[b, t, n] = sum_f pw[n, f] * patch(b, t)[f] + pb[n] + pos[t, n], features f = (c, ph, pw).
 __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x, const float *__restrict__ pw,
                                                     const float *__restrict__ pb, const float *__restrict__ pos,
-                                                    float *__restrict__ tok, int n_src, int C, int H, int W, int p, int D) {
+                                                    float *__restrict__ tok, int n_src, int C, int H, int W, int p, int D, int b_off) {
   __shared__ float patch[256];
   const int gw = W / p, T = (H / p) * gw;
   const int bt = blockIdx.x, b = bt / T, t = bt % T;
   const int F = C * p * p;
   const int ty = t / gw, tx = t % gw;
-  const float *src = x + (size_t)(b % n_src) * C * H * W;
+  const float *src = x + (size_t)((b + b_off) % n_src) * C * H * W;
   for (int f = threadIdx.x; f < F; f += blockDim.x) {
     const int c = f / (p * p), ph = (f / p) % p, pq = f % p;
     patch[f] = src[((size_t)c * H + ty * p + ph) * W + tx * p + pq];
@@ -298,9 +306,9 @@ __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x,
 }
 
 hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, float *tok, int B, int n_src,
-                        int C, int H, int W, int p, int D, hipStream_t st) {
+                        int C, int H, int W, int p, int D, int b_off, hipStream_t st) {
   const int T = (H / p) * (W / p);
-  hipLaunchKernelGGL(embed_kernel, dim3(B * T), dim3(256), 0, st, x, pw, pb, pos, tok, n_src, C, H, W, p, D);
+  hipLaunchKernelGGL(embed_kernel, dim3(B * T), dim3(256), 0, st, x, pw, pb, pos, tok, n_src, C, H, W, p, D, b_off);
   return hipGetLastError();
 }
 

@@ -21,7 +21,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak (published), TOP/s
-FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X fp32 matrix peak (published), TFLOP/s
+FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak (published), TFLOP/s
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak (published), GB/s
+
+# HBM bytes per launch of a kernel class from the hardware counters (two rocprofv3 --pmc runs, FETCH_SIZE and
+# WRITE_SIZE, scaled by what the same counters read for a copy of known size); filled in from the summaries
+# under profiles/, keyed by (workload, kernel class).  None where no counter run covers the pair.
+TRAFFIC = {}
 
 
 def int8_ops_per_full_step(m, B):
@@ -121,6 +127,31 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = B * args.steps / dt
 
+    # ---- full-step and cached-step latency (same batch, forced modes)
+    tt_, at_, ap_ = qc.qc_ddim_schedule(wl.steps)
+    def step_us(mode, reps=6):
+        x.copy_(lat)
+        ctx.sample_step(x, lab, 0, tt_[0], at_[0], ap_[0], wl.cfg_scale, K[0], qc.QC_FULL)   # fills the cache
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ctx.sample_step(x, lab, 1, tt_[1], at_[1], ap_[1], wl.cfg_scale, K[1], mode)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e6
+    full_us, cached_us = step_us(qc.QC_FULL), step_us(qc.QC_CACHED)
+
+    # ---- what an event pair around a launch adds to the kernel's own duration (dispatch latency):
+    # the same bracketing around a one-workgroup kernel
+    tiny_in = torch.zeros(64, device="cuda")
+    tiny_out = torch.empty(64, dtype=torch.int8, device="cuda")
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+    for e0, e1 in evs:
+        e0.record()
+        qc.qc_quantize_act(tiny_in, tiny_out, 1.0, 0)
+        e1.record()
+    torch.cuda.synchronize()
+    event_floor_us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)[len(evs) // 2]
+
     # ---- dominant kernel: instrumented repeat of the same pass with HIP events around its launches
     prof = ctx.profile_pass(run_once)
     n_full = -(-wl.steps // wl.cache_interval)
@@ -130,26 +161,38 @@ def main():
         for p in prof.values():
             p["avg_us"] = p["total_ms"] * 1e3 / max(p["launches"], 1)
         MT, D, R = Beff * m.tokens, m.hidden, m.mlp_dim
-        ops = {"gemm_qkv": 2.0 * MT * 3 * D * D, "gemm_proj": 2.0 * MT * D * D,
-               "gemm_fc1": 2.0 * MT * R * D, "gemm_fc2": 2.0 * MT * D * R}
-        # work of one launch: the class's work in one pass over its launches (a pass may cut the batch
-        # into sub-batches that are launched separately)
-        per_pass = n_full * m.depth
-        for k in ops:
-            if k in prof:
-                ops[k] *= per_pass / prof[k]["launches"]
-                prof[k]["tops"] = ops[k] / (prof[k]["avg_us"] * 1e-6) / 1e12
-        if dom["name"] in ops:
-            ach = ops[dom["name"]] / (dom["avg_us"] * 1e-6) / 1e12
-            roofline = {"bound": "mfma", "kernel": dom["name"], "achieved": ach, "peak": INT8_MFMA_PEAK_TOPS,
-                        "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                        "avg_launch_us": dom["avg_us"], "launches": dom["launches"]}
-        elif dom["name"] == "attention":
-            fl = 4.0 * Beff * m.heads * m.tokens * m.tokens * m.head_dim * n_full * m.depth / dom["launches"]
-            ach = fl / (dom["avg_us"] * 1e-6) / 1e12
-            roofline = {"bound": "mfma", "kernel": "attention", "achieved": ach, "peak": FP32_MFMA_PEAK_TFLOPS,
-                        "unit": "TFLOP/s", "frac": ach / FP32_MFMA_PEAK_TFLOPS, "traffic": None,
-                        "avg_launch_us": dom["avg_us"], "launches": dom["launches"]}
+        per_pass = n_full * m.depth        # full blocks in one pass
+        # algorithmic work of each class in one pass; a pass may cut the batch into sub-batches that are
+        # launched separately, so the work of one launch is the class's work over its launches
+        work = {
+            "gemm_qkv": ("mfma", 2.0 * MT * 3 * D * D * per_pass),
+            "gemm_proj": ("mfma", 2.0 * MT * D * D * per_pass),
+            "gemm_fc1": ("mfma", 2.0 * MT * R * D * per_pass),
+            "gemm_fc2": ("mfma", 2.0 * MT * D * R * per_pass),
+            "attention": ("mfma16", 4.0 * Beff * m.heads * m.tokens * m.tokens * m.head_dim * per_pass),
+            # fp32 row in, int8 codes out
+            "ln_mod_quant": ("hbm", 5.0 * MT * D * 2 * per_pass),
+            # both cached tensors of every block read once, the residual stream read and written once
+            "cached_blocks": ("hbm", (2.0 * m.depth + 2.0) * MT * D * 4 * (wl.steps - n_full)),
+            # int8 weights of the gate projections (cached steps) or all six chunks (refresh steps), read once
+            "gemm_adaln": ("hbm", m.depth * D * D * (6.0 * n_full + 2.0 * (wl.steps - n_full))
+                           * (0.5 if m.weight_bits == 4 else 1.0)),
+        }
+        peaks = {"mfma": (INT8_MFMA_PEAK_TOPS, "TOP/s"), "mfma16": (FP16_MFMA_PEAK_TFLOPS, "TFLOP/s"),
+                 "hbm": (HBM_PEAK_GBS, "GB/s")}
+        for k, (bound, wk) in work.items():
+            if k not in prof:
+                continue
+            peak, unit = peaks[bound]
+            per_launch = wk / prof[k]["launches"]
+            ach = per_launch / (prof[k]["avg_us"] * 1e-6) / (1e9 if bound == "hbm" else 1e12)
+            prof[k].update({"bound": "mfma" if bound != "hbm" else "hbm", "achieved": ach, "peak": peak, "unit": unit,
+                            "frac": ach / peak})
+        if "achieved" in dom:
+            roofline = {"bound": dom["bound"], "kernel": dom["name"], "achieved": dom["achieved"], "peak": dom["peak"],
+                        "unit": dom["unit"], "frac": dom["frac"], "traffic": TRAFFIC.get((wl.name, dom["name"])),
+                        "avg_launch_us": dom["avg_us"], "launches": dom["launches"],
+                        "event_pair_floor_us": event_floor_us}
     total_int8 = int8_ops_per_full_step(m, Beff) * n_full
     out = {
         "metric": "latents/sec, DiT-XL/2 W8A8+cache 256^2 at 50 steps; int8 GEMM % of MFMA peak",
@@ -160,6 +203,7 @@ def main():
                    "cache_interval": wl.cache_interval, "refresh_steps": n_full, "cfg_scale": wl.cfg_scale,
                    "weight_bits": m.weight_bits, "vc": True},
         "int8_tops_end_to_end": total_int8 / (ms_per_step * 1e-3) / 1e12,
+        "full_step_us": full_us, "cached_step_us": cached_us,
         "roofline": roofline,
         "kernels": prof,
     }

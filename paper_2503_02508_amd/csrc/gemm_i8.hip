@@ -222,26 +222,76 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     }
   };
 
-  // One steady-state step, software-pipelined inside the wavefront: the fragments of k-group kk+1 are
-  // read from LDS before the MFMAs of group kk issue, and a quarter of the next slab's LDS stores and of
-  // the global loads PF slabs ahead is issued behind each MFMA group, so that LDS and memory instructions
-  // execute under the matrix-core time instead of in front of it.
+  // One steady-state step, software-pipelined inside the wavefront.  LDS reads have a latency of a few
+  // hundred cycles and a wavefront is alone on its SIMD when the launch has few workgroups, so a whole
+  // slab of fragments (all NPART k-groups) is in flight at once: the reads of the next slab are issued
+  // right after the barrier that publishes it, in front of the last MFMA group of the current slab, and a
+  // quarter of the next slab's LDS stores and of the global loads PF slabs ahead is issued behind each
+  // MFMA group, so that LDS and memory instructions execute under the matrix-core time.
+  constexpr bool DEEP = TM * TN <= 4;          // a slab of fragments fits beside the accumulators
+  v4i fa[DEEP ? NPART : 1][TM], fb[DEEP ? NPART : 1][TN];
+  auto read_group = [&](int buf, int kk) {
+    const unsigned char *a_base = sA + (buf * BM + wm0 + frow) * LDS_ROW + fk + kk * 32;
+    const unsigned char *b_base = sB + (buf * BN + wn0 + frow) * LDS_ROW + fk + kk * 32;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[DEEP ? kk : 0][i] = *(const v4i *)(a_base + i * 32 * LDS_ROW);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[DEEP ? kk : 0][j] = *(const v4i *)(b_base + j * 32 * LDS_ROW);
+  };
+  auto mfma_group = [&](int kk) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int g = DEEP ? kk : 0;
+        if (EPI == EPI_GELU_Q)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[g][j], fa[g][i], acc[i][j], 0, 0, 0);
+        else
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[g][i], fb[g][j], acc[i][j], 0, 0, 0);
+      }
+  };
+  // precondition: the fragment reads of slab kt (buffer kt & 1) have been issued
   auto step = [&](int s, int kt) {
+    const int cur = kt & 1;
+#pragma unroll
+    for (int kk = 0; kk < NPART; ++kk) {
+      if (kk + 1 < NPART) {
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_group(kk);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      store_part((s + 1) % PF, cur ^ 1, kk);
+      load_part(s, (kt + PF) * BK, kk);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk + 1 < NPART; ++kk) read_group(cur ^ 1, kk);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(NPART - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_group(cur ^ 1, NPART - 1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // Shallow variant for tiles whose accumulators leave no room for a slab of fragments: the fragments of
+  // k-group kk+1 are read while the MFMAs of group kk run.
+  auto step_shallow = [&](int s, int kt) {
     const int cur = kt & 1;
     const unsigned char *a_base = sA + (cur * BM + wm0 + frow) * LDS_ROW + fk;
     const unsigned char *b_base = sB + (cur * BN + wn0 + frow) * LDS_ROW + fk;
-    v4i fa[2][TM], fb[2][TN];
+    v4i ga[2][TM], gb[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = *(const v4i *)(a_base + i * 32 * LDS_ROW);
+    for (int i = 0; i < TM; ++i) ga[0][i] = *(const v4i *)(a_base + i * 32 * LDS_ROW);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = *(const v4i *)(b_base + j * 32 * LDS_ROW);
+    for (int j = 0; j < TN; ++j) gb[0][j] = *(const v4i *)(b_base + j * 32 * LDS_ROW);
 #pragma unroll
     for (int kk = 0; kk < NPART; ++kk) {
       if (kk + 1 < NPART) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = *(const v4i *)(a_base + i * 32 * LDS_ROW + (kk + 1) * 32);
+        for (int i = 0; i < TM; ++i) ga[(kk + 1) & 1][i] = *(const v4i *)(a_base + i * 32 * LDS_ROW + (kk + 1) * 32);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = *(const v4i *)(b_base + j * 32 * LDS_ROW + (kk + 1) * 32);
+        for (int j = 0; j < TN; ++j) gb[(kk + 1) & 1][j] = *(const v4i *)(b_base + j * 32 * LDS_ROW + (kk + 1) * 32);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -249,15 +299,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           if (EPI == EPI_GELU_Q)
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(gb[kk & 1][j], ga[kk & 1][i], acc[i][j], 0, 0, 0);
           else
-            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ga[kk & 1][i], gb[kk & 1][j], acc[i][j], 0, 0, 0);
         }
       __builtin_amdgcn_sched_barrier(0);
       store_part((s + 1) % PF, cur ^ 1, kk);
       load_part(s, (kt + PF) * BK, kk);
       __builtin_amdgcn_sched_barrier(0);
     }
+    __syncthreads();
   };
 
   // prologue: PF slabs in flight, slab 0 into LDS
@@ -274,12 +325,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
   // few steps run in a conditional tail.
   int kb = 0;
   const int nk_steady = k_ragged ? nk - 1 : nk;      // the ragged last slab is loaded by the tail (clamped, zero-filled)
+  if (DEEP && 2 * PF - 1 < nk_steady) {
+#pragma unroll
+    for (int kk = 0; kk < NPART; ++kk) read_group(0, kk);
+  }
   for (; kb + 2 * PF - 1 < nk_steady; kb += PF) {
 #pragma unroll
     for (int s = 0; s < PF; ++s) {
-      const int kt = kb + s;
-      step(s, kt);
-      __syncthreads();
+      if (DEEP) step(s, kb + s);
+      else step_shallow(s, kb + s);
     }
   }
   for (; kb < nk; kb += PF) {
@@ -472,62 +526,69 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
   }
 
   if (EPI == EPI_RESID) {
-    // read-modify-write of the residual stream: every load of the tile is issued before the first use, so
-    // the epilogue pays one memory round trip instead of one per register group
+    // read-modify-write of the residual stream: the loads of a batch of column blocks are all issued
+    // before the first use, so the epilogue pays one memory round trip per batch instead of one per
+    // register group; a batch is the whole tile when its values fit in registers beside the accumulators
+    constexpr int JB = TM * TN <= 4 ? TN : 1, IB = TM * TN <= 4 ? TM : (TM % 2 == 0 ? 2 : 1);
     const bool uniform_batch = (p.rows_per_batch % BM) == 0;
     const int b_uniform = m0 / p.rows_per_batch;
-    float xv[TN][TM][16], gv[TN], scv[TN], bsv[TN];
-    int zwv[TN];
+    const bool interior = uniform_batch && m0 + BM <= p.M && n0 + BN <= p.N;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = min(n0 + wn0 + j * 32 + (lane & 31), p.N - 1);
+    for (int j0 = 0; j0 < TN; j0 += JB)
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int i0 = 0; i0 < TM; i0 += IB) {
+        float xv[JB][IB][16], gv[JB], scv[JB], bsv[JB];
+        int zwv[JB];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = min(m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), p.M - 1);
-          xv[j][i][r] = p.x[(long long)m * p.N + n];
+        for (int jj = 0; jj < JB; ++jj) {
+          const int n = min(n0 + wn0 + (j0 + jj) * 32 + (lane & 31), p.N - 1);
+#pragma unroll
+          for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int m = min(m0 + wm0 + (i0 + ii) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), p.M - 1);
+              xv[jj][ii][r] = p.x[(long long)m * p.N + n];
+            }
+          scv[jj] = a_s * w_scale[n];
+          zwv[jj] = a_z * wsum[n];
+          bsv[jj] = bias ? bias[n] : 0.0f;
+          gv[jj] = p.gate[(long long)b_uniform * p.ld_gate + n];
         }
-      scv[j] = a_s * w_scale[n];
-      zwv[j] = a_z * wsum[n];
-      bsv[j] = bias ? bias[n] : 0.0f;
-      gv[j] = p.gate[(long long)b_uniform * p.ld_gate + n];
-    }
-    if (uniform_batch && m0 + BM <= p.M && n0 + BN <= p.N) {
-      // interior tile inside one batch element: no bounds checks, one gate per column
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const long long n = n0 + wn0 + j * 32 + (lane & 31);
+        for (int jj = 0; jj < JB; ++jj) {
+          const int j = j0 + jj;
+          const int n = n0 + wn0 + j * 32 + (lane & 31);
+          if (interior) {
+            // interior tile inside one batch element: no bounds checks, one gate per column
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int ii = 0; ii < IB; ++ii)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-            const float v = fmaf(scv[j], (float)(acc[i][j][r] - zwv[j]), bsv[j]);
-            const long long o = (long long)m * p.N + n;
-            p.cache_out[o] = v;
-            p.x[o] = xv[j][i][r] + gv[j] * v;
+              for (int r = 0; r < 16; ++r) {
+                const int i = i0 + ii;
+                const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const float v = fmaf(scv[jj], (float)(acc[i][j][r] - zwv[jj]), bsv[jj]);
+                const long long o = (long long)m * p.N + n;
+                p.cache_out[o] = v;
+                p.x[o] = xv[jj][ii][r] + gv[jj] * v;
+              }
+          } else {
+            if (n >= p.N) continue;
+#pragma unroll
+            for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int i = i0 + ii;
+                const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                if (m >= p.M) continue;
+                const float v = fmaf(scv[jj], (float)(acc[i][j][r] - zwv[jj]), bsv[jj]);
+                const long long o = (long long)m * p.N + n;
+                p.cache_out[o] = v;
+                const float g = p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
+                p.x[o] = xv[jj][ii][r] + g * v;
+              }
           }
+        }
       }
-    } else {
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn0 + j * 32 + (lane & 31);
-        if (n >= p.N) continue;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-            if (m >= p.M) continue;
-            const float v = fmaf(scv[j], (float)(acc[i][j][r] - zwv[j]), bsv[j]);
-            const long long o = (long long)m * p.N + n;
-            p.cache_out[o] = v;
-            const float g = p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
-            p.x[o] = xv[j][i][r] + g * v;
-          }
-      }
-    }
     if (trace && tid == 0) trace[3] = wall_clock64();
     return;
   }
@@ -589,7 +650,7 @@ static hipError_t launch_cfg(const GemmArgs &a, int nz, hipStream_t st) {
 }
 
 // Tile choice.  QC_GEMM_TILE (environment, read once) forces one for tuning runs:
-// 1 = 128x128 and 2 = 256x128 on 4 wavefronts, 3 = 256x256 on 8 wavefronts.
+// 1 = 128x128 and 2 = 256x128 on 4 wavefronts, 3 = 256x256 and 4 = 128x128 on 8 wavefronts.
 static int forced_tile() {
   static int v = -1;
   if (v < 0) {
@@ -607,11 +668,15 @@ static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
     case 1: return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
     case 2: return launch_cfg<256, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
     case 3: return launch_cfg<256, 256, 2, 4, EPI, TAG, W4, 2>(a, nz, st);
+    case 4: return launch_cfg<128, 128, 2, 4, EPI, TAG, W4, 3>(a, nz, st);
     default: break;
   }
   // Large problems: 256x256 tiles on 8 wavefronts (256 ops per byte fetched from L2, the
   // bandwidth that bounds this kernel); small ones: 128x128 tiles, more workgroups in flight.
   if ((long long)a.M * a.N >= (long long)8192 * 1152) return launch_cfg<256, 256, 2, 4, EPI, TAG, W4, 2>(a, nz, st);
+  // Fewer tiles than compute units: a workgroup is alone on its CU and a single wavefront per SIMD cannot
+  // keep the LDS and memory pipes busy (they are issue-bound per wavefront), so the tile is shared by 8.
+  if (((a.M + 127) / 128) * ((a.N + 127) / 128) <= 256) return launch_cfg<128, 128, 2, 4, EPI, TAG, W4, 3>(a, nz, st);
   return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
 }
 

@@ -140,18 +140,6 @@ def main():
         return (time.perf_counter() - t0) / reps * 1e6
     full_us, cached_us = step_us(qc.QC_FULL), step_us(qc.QC_CACHED)
 
-    # ---- what an event pair around a launch adds to the kernel's own duration (dispatch latency):
-    # the same bracketing around a one-workgroup kernel
-    tiny_in = torch.zeros(64, device="cuda")
-    tiny_out = torch.empty(64, dtype=torch.int8, device="cuda")
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
-    for e0, e1 in evs:
-        e0.record()
-        qc.qc_quantize_act(tiny_in, tiny_out, 1.0, 0)
-        e1.record()
-    torch.cuda.synchronize()
-    event_floor_us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)[len(evs) // 2]
-
     # ---- dominant kernel: instrumented repeat of the same pass with HIP events around its launches
     prof = ctx.profile_pass(run_once)
     n_full = -(-wl.steps // wl.cache_interval)
@@ -191,8 +179,7 @@ def main():
         if "achieved" in dom:
             roofline = {"bound": dom["bound"], "kernel": dom["name"], "achieved": dom["achieved"], "peak": dom["peak"],
                         "unit": dom["unit"], "frac": dom["frac"], "traffic": TRAFFIC.get((wl.name, dom["name"])),
-                        "avg_launch_us": dom["avg_us"], "launches": dom["launches"],
-                        "event_pair_floor_us": event_floor_us}
+                        "avg_launch_us": dom["avg_us"], "launches": dom["launches"]}
     total_int8 = int8_ops_per_full_step(m, Beff) * n_full
     out = {
         "metric": "latents/sec, DiT-XL/2 W8A8+cache 256^2 at 50 steps; int8 GEMM % of MFMA peak",

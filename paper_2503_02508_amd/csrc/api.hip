@@ -1,6 +1,7 @@
 // Host layer of the C ABI: argument checks, arena layout, and the sequence of
 // kernel launches that makes up a DiT block, a denoiser call and a sampler step.
 // Every check runs before the first device call, so error paths work without a GPU.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -13,10 +14,13 @@
 namespace qc {
 
 constexpr int MAX_LANES = 4;
+// rows of the conditioning tables: the conditioning of several sampler steps is prepared in one go
+constexpr int WINDOW_ROWS = 512;
 
 // a contiguous range of the (effective) batch handled by one stream; `lane` picks its private scratch
 struct Sub {
   int b0, nb, lane;
+  int r0;   // first row of this range in the conditioning tables (cond, fmod, mod, silu_q): step slot * batch + b0
 };
 
 static thread_local char g_err[512] = "";
@@ -86,6 +90,7 @@ struct qc_ctx {
   long long qkv_part_stride, qkv_v_stride;   // words per Q / K array, halves per V^T array
   size_t qkv16_bytes;
   int DP, Tp;
+  int win_rows;               // row capacity of cond / fmod / mod / silu_q (per block for the last two)
   bool keep_qkv_f32 = false;
   // calibration scratch (one sample)
   float *cal_h, *cal_o, *cal_a, *cal_u, *cal_mod;
@@ -191,10 +196,11 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
   float *flin_w = a.take<float>(O * D), *flin_b = a.take<float>(O);
   QParam *dev_qp = a.take<QParam>(L * QC_NUM_SITES);
   float *cache = a.take<float>(L * 2 * M * D);
-  float *emb = a.take<float>(MAX_LANES * d.freq_dim), *h1 = a.take<float>(MAX_LANES * D), *te = a.take<float>(MAX_LANES * D);
-  float *cond = a.take<float>(B * D), *mod = a.take<float>(L * B * 6 * D), *fmod = a.take<float>(B * 2 * D);
+  const size_t WR = B > (size_t)WINDOW_ROWS ? B : (size_t)WINDOW_ROWS;
+  float *emb = a.take<float>(WR * d.freq_dim), *h1 = a.take<float>(WR * D), *te = a.take<float>(WR * D);
+  float *cond = a.take<float>(WR * D), *mod = a.take<float>(L * WR * 6 * D), *fmod = a.take<float>(WR * 2 * D);
   float *tokens = a.take<float>(M * D), *qkv = a.take<float>(M * 3 * D), *eps = a.take<float>(B * C * d.latent_h * d.latent_w);
-  int8_t *silu_q = a.take<int8_t>(L * B * D), *qa_ln = a.take<int8_t>(M * D), *qa_attn = a.take<int8_t>(M * D);
+  int8_t *silu_q = a.take<int8_t>(L * WR * D), *qa_ln = a.take<int8_t>(M * D), *qa_attn = a.take<int8_t>(M * D);
   int8_t *qa_mlp = a.take<int8_t>(M * R);
   const size_t hd = D / d.heads, DP = (hd + 15) / 16 * 16, Tp = (T + 63) / 64 * 64;
   const size_t part = B * d.heads * T * hd, vpart = B * d.heads * DP * Tp;   // part: 32-bit words = 2 halves each
@@ -211,6 +217,7 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
     c->cal_slots = cal_slots; c->cal_label = cal_label;
     c->qkv16 = qkv16; c->qkv_part_stride = (long long)part; c->qkv_v_stride = (long long)vpart;
     c->qkv16_bytes = (4 * part + 2 * vpart) * sizeof(_Float16); c->DP = (int)DP; c->Tp = (int)Tp;
+    c->win_rows = (int)WR;
   }
   return (a.off + 255) & ~size_t(255);
 }
@@ -431,19 +438,20 @@ static float *cache_slot(const qc_ctx *ctx, int block, int which) {
   return ctx->cache + ((size_t)block * 2 + which) * (size_t)ctx->max_batch * ctx->T * ctx->D;
 }
 
-// adaLN projection of blocks [l0, l0+nl): mod[l, b, :] = Lin_q(codes of SiLU(c)); gates only on request.
-static int run_adaln(qc_ctx *ctx, int l0, int nl, const Sub &sb, bool gates_only, hipStream_t st) {
-  const size_t D = ctx->D;
+// adaLN projection of blocks [l0, l0+nl) for `rows` rows of the conditioning tables starting at row r0:
+// mod[l, r, :] = Lin_q(codes of SiLU(c[r])); gates only on request.
+static int run_adaln(qc_ctx *ctx, int l0, int nl, int r0, int rows, bool gates_only, hipStream_t st) {
+  const size_t D = ctx->D, WR = ctx->win_rows;
   GemmArgs a{};
   const LinearQ &q = ctx->blk[l0].lin[QC_SITE_ADA];
-  a.A = ctx->silu_q + ((size_t)l0 * ctx->max_batch + sb.b0) * D;
+  a.A = ctx->silu_q + ((size_t)l0 * WR + r0) * D;
   a.W = q.q; a.w_scale = q.scale; a.wsum = q.wsum; a.bias = q.bias;
-  a.M = sb.nb; a.N = (int)(6 * D); a.K = (int)D; a.lda = (int)D; a.w4 = ctx->d.weight_bits == 4;
+  a.M = rows; a.N = (int)(6 * D); a.K = (int)D; a.lda = (int)D; a.w4 = ctx->d.weight_bits == 4;
   a.a_qp = ctx->dev_qp + (size_t)l0 * QC_NUM_SITES + QC_SITE_ADA;
-  a.zs_A = (long long)ctx->max_batch * D; a.zs_W = (long long)ctx->ada_w_stride_bytes; a.zs_vecN = (long long)(6 * D);
-  a.zs_out = (long long)ctx->max_batch * 6 * D; a.zs_qp = QC_NUM_SITES;
+  a.zs_A = (long long)(WR * D); a.zs_W = (long long)ctx->ada_w_stride_bytes; a.zs_vecN = (long long)(6 * D);
+  a.zs_out = (long long)(WR * 6 * D); a.zs_qp = QC_NUM_SITES;
   a.sel_D = (gates_only && D % 128 == 0) ? (int)D : 0;
-  a.y = ctx->mod + ((size_t)l0 * ctx->max_batch + sb.b0) * 6 * D; a.ldy = (int)(6 * D);
+  a.y = ctx->mod + ((size_t)l0 * WR + r0) * 6 * D; a.ldy = (int)(6 * D);
   QC_PROF(QC_K_ADALN);
   QC_HIP(launch_gemm(a, EPI_F32, nl, st, QC_SITE_ADA));
   return QC_OK;
@@ -453,7 +461,7 @@ static int run_adaln(qc_ctx *ctx, int l0, int nl, const Sub &sb, bool gates_only
 static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream_t st) {
   const int D = ctx->D, R = ctx->R, T = ctx->T, B = sb.nb, M = B * T;
   const size_t row0 = (size_t)sb.b0 * T;
-  const float *mod = ctx->mod + ((size_t)l * ctx->max_batch + sb.b0) * 6 * D;
+  const float *mod = ctx->mod + ((size_t)l * ctx->win_rows + sb.r0) * 6 * D;
   const QParam *qp = ctx->dev_qp + (size_t)l * QC_NUM_SITES;
   const bool w4 = ctx->d.weight_bits == 4;
   const BlockQ &bq = ctx->blk[l];
@@ -525,16 +533,16 @@ int qc_dit_block(qc_ctx *ctx, int block, int mode, float *x, const float *c, int
   hipStream_t st = static_cast<hipStream_t>(stream);
   const size_t D = ctx->D;
   QC_HIP(launch_silu_quant(c, B, (int)D, 1, ctx->dev_qp + (size_t)block * QC_NUM_SITES + QC_SITE_ADA, QC_NUM_SITES,
-                           ctx->silu_q + (size_t)block * ctx->max_batch * D, (size_t)ctx->max_batch * D, st));
-  const Sub whole{0, B, 0};
-  rc = run_adaln(ctx, block, 1, whole, mode == QC_CACHED, st);
+                           ctx->silu_q + (size_t)block * ctx->win_rows * D, (size_t)ctx->win_rows * D, st));
+  const Sub whole{0, B, 0, 0};
+  rc = run_adaln(ctx, block, 1, 0, B, mode == QC_CACHED, st);
   if (rc) return rc;
   if (mode == QC_FULL) {
     rc = run_block_full(ctx, block, x, whole, st);
     ctx->cache_batch[(size_t)block * 2] = ctx->cache_batch[(size_t)block * 2 + 1] = B;
     return rc;
   }
-  const float *mod = ctx->mod + (size_t)block * ctx->max_batch * 6 * D;
+  const float *mod = ctx->mod + (size_t)block * ctx->win_rows * 6 * D;
   QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, QC_CACHE_ATTN), mod + 2 * D, (int)(6 * D), B, ctx->T, (int)D, st));
   QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, QC_CACHE_MLP), mod + 5 * D, (int)(6 * D), B, ctx->T, (int)D, st));
   return QC_OK;
@@ -589,8 +597,8 @@ int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out) 
     case QC_WS_QACT_ATTN: p = ctx->qa_attn; n = M * D; break;
     case QC_WS_QACT_MLP: p = ctx->qa_mlp; n = M * ctx->R; break;
     case QC_WS_QKV: p = ctx->qkv; n = M * 3 * D * 4; break;
-    case QC_WS_MOD: p = ctx->mod; n = (size_t)ctx->L * B * 6 * D * 4; break;
-    case QC_WS_COND: p = ctx->cond; n = B * D * 4; break;
+    case QC_WS_MOD: p = ctx->mod; n = (size_t)ctx->L * ctx->win_rows * 6 * D * 4; break;
+    case QC_WS_COND: p = ctx->cond; n = (size_t)ctx->win_rows * D * 4; break;
     case QC_WS_EPS: p = ctx->eps; n = B * ctx->C * ctx->d.latent_h * ctx->d.latent_w * 4; break;
     default: QC_FAIL(QC_ERR_RANGE, "unknown workspace selector %d", which);
   }
@@ -605,32 +613,44 @@ int qc_keep_qkv_f32(qc_ctx *ctx, int on) {
   return QC_OK;
 }
 
-// conditioning vector c[B, D] for timestep t and the labels (null label for b >= n_labels)
-static int run_conditioning(qc_ctx *ctx, int t, const int32_t *labels, int n_labels, const Sub &sb, hipStream_t st) {
+// Conditioning vectors for nw timesteps and one set of labels: c[w * B + b, :] = tMLP(sinusoid(t[w])) + E[y_b]
+// (null label for b >= n_labels), rows 0 .. nw*B of the table.
+static int run_cond(qc_ctx *ctx, const int32_t *t, int nw, const int32_t *labels, int n_labels, int B, hipStream_t st) {
   const int D = ctx->D, fd = ctx->d.freq_dim;
-  float *emb = ctx->emb + (size_t)sb.lane * fd, *h1 = ctx->h1 + (size_t)sb.lane * D, *te = ctx->te + (size_t)sb.lane * D;
-  QC_HIP(launch_time_embed(t, nullptr, 1, fd, emb, st));
-  QC_HIP(launch_small_linear(emb, fd, ctx->t_w1, ctx->t_b1, h1, D, 1, D, fd, 0, 1, st));
-  QC_HIP(launch_small_linear(h1, D, ctx->t_w2, ctx->t_b2, te, D, 1, D, D, 0, 0, st));
-  QC_HIP(launch_cond_finish(te, ctx->label_table, labels, n_labels, ctx->d.num_classes, sb.nb, D,
-                            ctx->cond + (size_t)sb.b0 * D, sb.b0, st));
+  bool affine = true;
+  for (int w = 2; w < nw; ++w) affine = affine && (t[w] - t[w - 1] == t[1] - t[0]);
+  if (affine) {
+    QC_HIP(launch_time_embed(t[0], nw > 1 ? t[1] - t[0] : 0, nw, fd, ctx->emb, st));
+  } else {
+    for (int w = 0; w < nw; ++w) QC_HIP(launch_time_embed(t[w], 0, 1, fd, ctx->emb + (size_t)w * fd, st));
+  }
+  QC_HIP(launch_small_linear(ctx->emb, fd, ctx->t_w1, ctx->t_b1, ctx->h1, D, nw, D, fd, 0, 1, st));
+  QC_HIP(launch_small_linear(ctx->h1, D, ctx->t_w2, ctx->t_b2, ctx->te, D, nw, D, D, 0, 0, st));
+  QC_HIP(launch_cond_finish(ctx->te, ctx->label_table, labels, n_labels, ctx->d.num_classes, nw * B, B, D, ctx->cond, st));
   return QC_OK;
 }
 
-// The network on one sub-batch (rows b0 .. b0+nb of the effective batch) in three parts, so that the
-// caller can interleave the launches of several sub-batches: everything before the blocks ...
-static int denoise_head(qc_ctx *ctx, const float *x, int t, const int32_t *labels, int n_labels, const Sub &sb, int mode,
-                        hipStream_t st) {
-  const int D = ctx->D, L = ctx->L, B = sb.nb;
-  float *cond = ctx->cond + (size_t)sb.b0 * D, *fmod = ctx->fmod + (size_t)sb.b0 * 2 * D;
-  int rc = run_conditioning(ctx, t, labels, n_labels, sb, st);
+// Everything of the network that depends only on (timestep, label), for nw sampler steps at once: the
+// conditioning vectors, the final layer's modulation and the adaLN projections of every block.  One
+// int8 GEMM with nw * B rows replaces nw weight-bandwidth-bound launches with B rows each, and the
+// steps themselves start at the patch embedding.  Step w of the window owns rows w*B .. (w+1)*B.
+static int prepare_window(qc_ctx *ctx, const int32_t *t, int nw, const int32_t *labels, int n_labels, int B, bool gates_only,
+                          hipStream_t st) {
+  const int D = ctx->D, L = ctx->L, rows = nw * B;
+  if (rows > ctx->win_rows) QC_FAIL(QC_ERR_WORKSPACE, "conditioning window of %d rows exceeds %d", rows, ctx->win_rows);
+  int rc = run_cond(ctx, t, nw, labels, n_labels, B, st);
   if (rc) return rc;
-  QC_HIP(launch_silu_quant(cond, B, D, L, ctx->dev_qp + QC_SITE_ADA, QC_NUM_SITES, ctx->silu_q + (size_t)sb.b0 * D,
-                           (size_t)ctx->max_batch * D, st));
-  QC_HIP(launch_small_linear(cond, D, ctx->fada_w, ctx->fada_b, fmod, 2 * D, B, 2 * D, D, 1, 0, st));
-  rc = run_adaln(ctx, 0, L, sb, mode == QC_CACHED, st);
-  if (rc) return rc;
-  QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens + (size_t)sb.b0 * ctx->T * D, B, n_labels, ctx->C,
+  QC_HIP(launch_silu_quant(ctx->cond, rows, D, L, ctx->dev_qp + QC_SITE_ADA, QC_NUM_SITES, ctx->silu_q,
+                           (size_t)ctx->win_rows * D, st));
+  QC_HIP(launch_small_linear(ctx->cond, D, ctx->fada_w, ctx->fada_b, ctx->fmod, 2 * D, rows, 2 * D, D, 1, 0, st));
+  return run_adaln(ctx, 0, L, 0, rows, gates_only, st);
+}
+
+// The x-dependent part of the network on one sub-batch (rows b0 .. b0+nb of the effective batch) in three
+// pieces, so that the caller can interleave the launches of several sub-batches: the patch embedding ...
+static int denoise_head(qc_ctx *ctx, const float *x, int n_labels, const Sub &sb, hipStream_t st) {
+  const int D = ctx->D;
+  QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens + (size_t)sb.b0 * ctx->T * D, sb.nb, n_labels, ctx->C,
                       ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, sb.b0, st));
   return QC_OK;
 }
@@ -643,10 +663,10 @@ static int denoise_tail(qc_ctx *ctx, const Sub &sb, int mode, float *eps_out, hi
   if (mode == QC_CACHED) {
     const size_t slot = (size_t)ctx->max_batch * ctx->T * D;
     QC_PROF(QC_K_CACHED_BLOCKS);
-    QC_HIP(launch_cached_blocks(tokens, ctx->cache + (size_t)sb.b0 * ctx->T * D, 2 * slot, slot, ctx->mod + (size_t)sb.b0 * 6 * D,
-                                (size_t)ctx->max_batch * 6 * D, 6 * D, L, B, ctx->T, D, st));
+    QC_HIP(launch_cached_blocks(tokens, ctx->cache + (size_t)sb.b0 * ctx->T * D, 2 * slot, slot, ctx->mod + (size_t)sb.r0 * 6 * D,
+                                (size_t)ctx->win_rows * 6 * D, 6 * D, L, B, ctx->T, D, st));
   }
-  QC_HIP(launch_final(tokens, ctx->fmod + (size_t)sb.b0 * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + (size_t)sb.b0 * lat, B,
+  QC_HIP(launch_final(tokens, ctx->fmod + (size_t)sb.r0 * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + (size_t)sb.b0 * lat, B,
                       ctx->C, ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, st));
   return QC_OK;
 }
@@ -667,13 +687,13 @@ static int choose_lanes(qc_ctx *ctx, int B) {
   return n < 1 ? 1 : n;
 }
 
-static int denoise_impl(qc_ctx *ctx, const float *x, int t, const int32_t *labels, int n_labels, int B, int mode,
-                        float *eps_out, hipStream_t st) {
+// One denoiser evaluation whose conditioning sits in slot `w` of the prepared window.
+static int denoise_impl(qc_ctx *ctx, const float *x, int n_labels, int B, int mode, int w, float *eps_out, hipStream_t st) {
   const int lanes = choose_lanes(ctx, B);
   Sub sub[MAX_LANES];
   hipStream_t ls[MAX_LANES];
   for (int i = 0, b0 = 0; i < lanes; ++i) {
-    sub[i] = Sub{b0, B / lanes + (i < B % lanes ? 1 : 0), i};
+    sub[i] = Sub{b0, B / lanes + (i < B % lanes ? 1 : 0), i, w * B + b0};
     b0 += sub[i].nb;
   }
   ls[0] = st;
@@ -688,7 +708,7 @@ static int denoise_impl(qc_ctx *ctx, const float *x, int t, const int32_t *label
     }
   }
   int rc = QC_OK;
-  for (int i = 0; i < lanes && !rc; ++i) rc = denoise_head(ctx, x, t, labels, n_labels, sub[i], mode, ls[i]);
+  for (int i = 0; i < lanes && !rc; ++i) rc = denoise_head(ctx, x, n_labels, sub[i], ls[i]);
   if (mode == QC_FULL)
     for (int l = 0; l < ctx->L && !rc; ++l)
       for (int i = 0; i < lanes && !rc; ++i)
@@ -723,17 +743,22 @@ int qc_denoise(qc_ctx *ctx, const float *x, int t, const int32_t *labels, int n_
   if (rc) return rc;
   if (!eps_out) QC_FAIL(QC_ERR_NULL, "eps_out is NULL");
   if (t < 0) QC_FAIL(QC_ERR_RANGE, "timestep must be non-negative");
-  return denoise_impl(ctx, x, t, labels, n_labels, B, mode, eps_out, static_cast<hipStream_t>(stream));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int32_t t32 = t;
+  rc = prepare_window(ctx, &t32, 1, labels, n_labels, B, mode == QC_CACHED, st);
+  if (rc) return rc;
+  return denoise_impl(ctx, x, n_labels, B, mode, 0, eps_out, st);
 }
 
-static int sample_step_impl(qc_ctx *ctx, float *x, const int32_t *labels, int B, int step_index, int t, double abar_t,
-                            double abar_prev, float cfg_scale, const float *K_t, int force_mode, hipStream_t st) {
+static int step_mode(const qc_ctx *ctx, int step_index, int force_mode) {
+  return force_mode >= 0 ? force_mode : (step_index % ctx->d.cache_interval == 0 ? QC_FULL : QC_CACHED);
+}
+
+// One sampler step whose conditioning sits in slot w of the prepared window: denoiser, CFG, DDIM update, VC.
+static int sample_step_prepared(qc_ctx *ctx, float *x, int B, int mode, int w, double abar_t, double abar_prev, float cfg_scale,
+                                const float *K_t, hipStream_t st) {
   const int Beff = cfg_scale > 0.0f ? 2 * B : B;
-  int mode = force_mode;
-  if (mode < 0) mode = (step_index % ctx->d.cache_interval == 0) ? QC_FULL : QC_CACHED;
-  int rc = check_denoise(ctx, x, labels, B, Beff, mode);
-  if (rc) return rc;
-  rc = denoise_impl(ctx, x, t, labels, B, Beff, mode, ctx->eps, st);
+  int rc = denoise_impl(ctx, x, B, Beff, mode, w, ctx->eps, st);
   if (rc) return rc;
   const double cx = std::sqrt(abar_prev / abar_t);
   const double ce = std::sqrt(1.0 - abar_prev) - cx * std::sqrt(1.0 - abar_t);
@@ -747,8 +772,15 @@ int qc_sample_step(qc_ctx *ctx, float *x, const int32_t *labels, int B, int step
   if (step_index < 0 || t < 0) QC_FAIL(QC_ERR_RANGE, "step index and timestep must be non-negative");
   if (!(abar_t > 0.0 && abar_t <= 1.0) || !(abar_prev > 0.0 && abar_prev <= 1.0)) QC_FAIL(QC_ERR_RANGE, "abar values must be in (0, 1]");
   if (force_mode != -1 && force_mode != QC_FULL && force_mode != QC_CACHED) QC_FAIL(QC_ERR_RANGE, "force_mode must be -1, QC_FULL or QC_CACHED");
-  return sample_step_impl(ctx, x, labels, B, step_index, t, abar_t, abar_prev, cfg_scale, K_t, force_mode,
-                          static_cast<hipStream_t>(stream));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int Beff = cfg_scale > 0.0f ? 2 * B : B;
+  const int mode = step_mode(ctx, step_index, force_mode);
+  int rc = check_denoise(ctx, x, labels, B, Beff, mode);
+  if (rc) return rc;
+  const int32_t t32 = t;
+  rc = prepare_window(ctx, &t32, 1, labels, B, Beff, mode == QC_CACHED, st);
+  if (rc) return rc;
+  return sample_step_prepared(ctx, x, B, mode, 0, abar_t, abar_prev, cfg_scale, K_t, st);
 }
 
 int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, float cfg_scale, const float *K, void *stream) {
@@ -757,10 +789,21 @@ int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, fl
   std::vector<double> at(t.size()), ap(t.size());
   int rc = qc_ddim_schedule(steps, t.data(), at.data(), ap.data());
   if (rc) return rc;
-  for (int i = 0; i < steps; ++i) {
-    rc = sample_step_impl(ctx, x, labels, B, i, t[i], at[i], ap[i], cfg_scale, K ? K + (size_t)i * ctx->C : nullptr, -1,
-                          static_cast<hipStream_t>(stream));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int Beff = cfg_scale > 0.0f ? 2 * B : B;
+  rc = check_denoise(ctx, x, labels, B, Beff, QC_FULL);
+  if (rc) return rc;
+  // the whole schedule is known: conditioning and adaLN projections are prepared a window of steps at a time
+  const int W = std::max(1, std::min(steps, ctx->win_rows / Beff));
+  for (int i0 = 0; i0 < steps; i0 += W) {
+    const int nw = std::min(W, steps - i0);
+    rc = prepare_window(ctx, t.data() + i0, nw, labels, B, Beff, false, st);
     if (rc) return rc;
+    for (int i = i0; i < i0 + nw; ++i) {
+      rc = sample_step_prepared(ctx, x, B, step_mode(ctx, i, -1), i - i0, at[i], ap[i], cfg_scale,
+                                K ? K + (size_t)i * ctx->C : nullptr, st);
+      if (rc) return rc;
+    }
   }
   return QC_OK;
 }
@@ -825,7 +868,7 @@ int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, co
   for (int i = 0; i < n; ++i) {
     QC_HIP(hipMemcpyAsync(ctx->cal_label, &y[i], sizeof(int), hipMemcpyHostToDevice, st));
     QC_HIP(hipStreamSynchronize(st));
-    rc = run_conditioning(ctx, t[i], ctx->cal_label, 1, Sub{0, 1, 0}, st);
+    rc = run_cond(ctx, &t[i], 1, ctx->cal_label, 1, 1, st);
     if (rc) return rc;
     QC_HIP(launch_embed(x + i * lat, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 1, 1, ctx->C, ctx->d.latent_h,
                         ctx->d.latent_w, ctx->d.patch, D, 0, st));

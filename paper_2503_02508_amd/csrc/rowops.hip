@@ -232,34 +232,36 @@ hipError_t launch_small_linear(const float *x, int ldx, const float *W, const fl
 // ----------------------------------------------------------- conditioning
 // Sinusoidal timestep embedding [cos | sin], frequencies exp(-ln(1e4) j / half),
 // evaluated in double so that the fp32 result is correctly rounded.
-__global__ void time_embed_kernel(int t, int B, int dim, float *__restrict__ out) {
+// Row w is the embedding of timestep t_first + w * t_step.
+__global__ void time_embed_kernel(int t_first, int t_step, int W, int dim, float *__restrict__ out) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= B * dim) return;
-  const int j = i % dim, half = dim / 2;
+  if (i >= W * dim) return;
+  const int j = i % dim, half = dim / 2, t = t_first + (i / dim) * t_step;
   const int f = j < half ? j : j - half;
   const double a = (double)t * exp(-log(10000.0) * (double)f / (double)half);
   out[i] = (float)(j < half ? cos(a) : sin(a));
 }
 
-hipError_t launch_time_embed(int t, const int32_t *, int B, int dim, float *out, hipStream_t st) {
-  hipLaunchKernelGGL(time_embed_kernel, dim3((B * dim + 255) / 256), dim3(256), 0, st, t, B, dim, out);
+hipError_t launch_time_embed(int t_first, int t_step, int W, int dim, float *out, hipStream_t st) {
+  hipLaunchKernelGGL(time_embed_kernel, dim3((W * dim + 255) / 256), dim3(256), 0, st, t_first, t_step, W, dim, out);
   return hipGetLastError();
 }
 
+// c[r, :] = te[r / B, :] + table[label of batch element r % B]: rows are (timestep slot, batch element)
 __global__ void cond_finish_kernel(const float *__restrict__ te, const float *__restrict__ table,
-                                   const int32_t *__restrict__ labels, int n_labels, int null_label, int B, int D,
-                                   float *__restrict__ c, int b_off) {
+                                   const int32_t *__restrict__ labels, int n_labels, int null_label, int rows, int B, int D,
+                                   float *__restrict__ c) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= B * D) return;
-  const int b = i / D, n = i % D;
-  const int y = b + b_off < n_labels ? labels[b + b_off] : null_label;   // b_off: position of this sub-batch in the batch
-  c[i] = te[n] + table[(size_t)y * D + n];   // one timestep per call: te is a single row
+  if (i >= rows * D) return;
+  const int r = i / D, n = i % D, w = r / B, b = r % B;
+  const int y = b < n_labels ? labels[b] : null_label;
+  c[i] = te[(size_t)w * D + n] + table[(size_t)y * D + n];
 }
 
 hipError_t launch_cond_finish(const float *te, const float *table, const int32_t *labels, int n_labels, int null_label,
-                              int B, int D, float *c, int b_off, hipStream_t st) {
-  hipLaunchKernelGGL(cond_finish_kernel, dim3((B * D + 255) / 256), dim3(256), 0, st, te, table, labels, n_labels,
-                     null_label, B, D, c, b_off);
+                              int rows, int B, int D, float *c, hipStream_t st) {
+  hipLaunchKernelGGL(cond_finish_kernel, dim3((rows * D + 255) / 256), dim3(256), 0, st, te, table, labels, n_labels,
+                     null_label, rows, B, D, c);
   return hipGetLastError();
 }
 

@@ -5,9 +5,10 @@ workload plus a plain copy of known size, for hardware-counter collection.
 Counter collection serialises kernels and slows every dispatch, so the full
 benchmark is too long for it; the kernels of one refresh step and one cached
 step are the same ones the benchmark launches (same shapes, same launch
-configuration).  The copy (the cache-store kernel on a [B, T, D] fp32 tensor:
-reads and writes exactly B*T*D*4 bytes) is the yardstick that converts the
-FETCH_SIZE / WRITE_SIZE counter readings into bytes.
+configuration).  The copies at the end are the yardstick that converts the
+FETCH_SIZE / WRITE_SIZE counter readings into bytes: a plain device-to-device
+copy of 512 MiB (far larger than the L2s and the memory-side cache, so every
+byte is fetched from and written to HBM once).
 
     rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <out> -- python3 paper_2503_02508_amd/profile_driver.py
     rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <out> -- python3 paper_2503_02508_amd/profile_driver.py
@@ -27,7 +28,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--sampler-steps", type=int, default=2, help="sampler steps to run (from step 0)")
-    ap.add_argument("--copies", type=int, default=4)
+    ap.add_argument("--copies", type=int, default=3)
+    ap.add_argument("--copy-mib", type=int, default=512)
     args = ap.parse_args()
 
     import numpy as np
@@ -55,12 +57,15 @@ def main():
     for i in range(args.sampler_steps):
         ctx.sample_step(x, lab, i, tt[i], at[i], ap_[i], wl.cfg_scale, K[i])
     torch.cuda.synchronize()
-    src = torch.randn(Beff, m.tokens, m.hidden, device="cuda")
-    for _ in range(args.copies):
-        ctx.cache_store(0, qc.QC_CACHE_ATTN, src)
+    n = args.copy_mib * (1 << 20) // 4
+    src = torch.ones(n, device="cuda")
+    dst = torch.empty_like(src)
     torch.cuda.synchronize()
-    print("profile_driver: copy yardstick = %d bytes read and %d bytes written per cache_store launch"
-          % (src.numel() * 4, src.numel() * 4), flush=True)
+    for _ in range(args.copies):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print("profile_driver: copy yardstick = %d bytes read and %d bytes written per copy kernel launch"
+          % (n * 4, n * 4), flush=True)
 
 
 if __name__ == "__main__":

@@ -285,6 +285,32 @@ def test_sampler_free_running_whole_loop_via_qc_sample():
     ctx.close()
 
 
+@pytest.mark.parametrize("B,steps,interval,cfg", [(3, 10, 2, 0.0), (8, 150, 3, 0.0), (5, 120, 4, 1.5)])
+def test_qc_sample_equals_step_by_step_calls(B, steps, interval, cfg):
+    """The whole-loop entry point prepares the conditioning and the adaLN projections of many steps with
+    one launch each (several windows at the larger step counts); its samples must be bit-identical to
+    the ones the per-step entry point produces."""
+    import torch
+    import paper_2503_02508_amd as qc
+    model = TINY
+    w = I.make_weights(model, 61, std=0.15)
+    tt, at, ap = sampler.ddim_schedule(steps)
+    clat = np.concatenate([I.make_latents(1, model, 4000 + i) for i in range(4)])
+    qp, _, _ = oracle_calibration(model, w, lat=clat, lab=I.make_labels(4, model, 62), t=tt[[0, steps // 3, 2 * steps // 3, steps - 1]])
+    Beff = 2 * B if cfg > 0 else B
+    _, ctx = make_pair(model, w, qp, Beff, interval)
+    lat, lab = I.make_latents(B, model, 63), _cuda(I.make_labels(B, model, 64).astype(np.int32))
+    K = _cuda(I.make_vc_factors(steps, model.latent_c, 65))
+    xa, xb = _cuda(lat), _cuda(lat)
+    ctx.sample(xa, lab, steps, cfg, K)
+    for i in range(steps):
+        ctx.sample_step(xb, lab, i, int(tt[i]), float(at[i]), float(ap[i]), cfg, K[i])
+    torch.cuda.synchronize()
+    assert torch.isfinite(xa).all()
+    assert torch.equal(xa, xb)
+    ctx.close()
+
+
 def test_calibration_matches_oracle():
     """qc_calibrate_minmax (fp32 un-quantised forward on the device) against the oracle's calibration."""
     import torch

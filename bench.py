@@ -27,7 +27,14 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak (published), GB/s
 # HBM bytes per launch of a kernel class from the hardware counters (two rocprofv3 --pmc runs, FETCH_SIZE and
 # WRITE_SIZE, scaled by what the same counters read for a copy of known size); filled in from the summaries
 # under profiles/, keyed by (workload, kernel class).  None where no counter run covers the pair.
-TRAFFIC = {}
+TRAFFIC = {
+    # profiles/sampler_cfg1_dit_xl2_b8_hbm_traffic.txt: (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB per dispatch
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc2"): (17407.9 * 2.0 + 9216.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_qkv"): (6322.9 * 2.0 + 13827.8) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc1"): (7678.0 * 2.0 + 4608.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_proj"): (6170.6 * 2.0 + 9216.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "attention"): (12175.0 * 2.0 + 1536.0) * 1024,
+}
 
 
 def int8_ops_per_full_step(m, B):

@@ -221,7 +221,9 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
   __shared__ __align__(16) _Float16 Vsh[2][NEB * 16 * VROW];
 
   const int D = H * hd;
-  const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  // blockIdx.x = (batch, head): the query blocks of one head are B*H workgroups apart and land on the same XCD
+  // (workgroups go round-robin over the 8 XCDs), so its K and V are fetched into one L2 only
+  const int bh = blockIdx.x, b = bh / H, h = bh % H;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ql = lane & 15, g = lane >> 4;
   long long tr[6] = {0, 0, 0, 0, 0, 0}, tl = 0;
@@ -297,7 +299,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
   v8h qh[2][NCH], qlo[2][NCH];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    q_row[j] = blockIdx.x * 128 + wave * 32 + j * 16 + ql;
+    q_row[j] = blockIdx.y * 128 + wave * 32 + j * 16 + ql;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
       v2u h0 = {0, 0}, l0 = {0, 0}, h1 = {0, 0}, l1 = {0, 0};
@@ -421,7 +423,7 @@ extern int g_trace_epi;
 
 hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
                                 int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st) {
-  dim3 grid((T + 127) / 128, B * H);
+  dim3 grid(B * H, (T + 127) / 128);
   const int neb = (hd + 15) / 16, nch = (hd + 31) / 32;
   if (hd > 80 || hd % 4) return hipErrorInvalidValue;      // K prefetch registers are sized for d <= 80
 #define QC_ATT(NCH, NEB)                                                                                               \

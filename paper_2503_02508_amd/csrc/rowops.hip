@@ -114,13 +114,6 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // error they seed in every later layer) at the floor.
 // One workgroup (4 wavefronts) per token row: short per-thread work and 8 wavefronts per SIMD keep the
 // two memory round trips (row in, codes out) and the fp64 arithmetic of different rows overlapped.
-__device__ __forceinline__ double block_sum_d(double v, double *red, int slot) {
-  v = wave_sum_d(v);
-  if ((threadIdx.x & 63) == 0) red[slot * 4 + (threadIdx.x >> 6)] = v;
-  __syncthreads();
-  return (red[slot * 4] + red[slot * 4 + 1]) + (red[slot * 4 + 2] + red[slot * 4 + 3]);
-}
-
 __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restrict__ x, const float *__restrict__ shift,
                                                            const float *__restrict__ scale, int ld_mod, int M, int D, int T,
                                                            const QParam *qp, int8_t *__restrict__ q,
@@ -147,17 +140,27 @@ __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restri
     const int k = (threadIdx.x + 256 * it) * 4;
     if (k < D) sum += ((double)v[it].x + (double)v[it].y) + ((double)v[it].z + (double)v[it].w);
   }
-  const double mean = block_sum_d(sum, red, 0) / (double)D;
+  // mean and variance from one reduction of (sum, sum of squares): in fp64 the cancellation in
+  // E[x^2] - mean^2 costs ~1e-13 relative for rows of O(1) values, far below the fp32 rounding of the result
   double sq = 0.0;
 #pragma unroll
   for (int it = 0; it < IT; ++it) {
     const int k = (threadIdx.x + 256 * it) * 4;
     if (k < D) {
-      const double a = v[it].x - mean, bq = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
+      const double a = v[it].x, bq = v[it].y, c = v[it].z, d = v[it].w;
       sq += (a * a + bq * bq) + (c * c + d * d);
     }
   }
-  const double rstd = 1.0 / sqrt(block_sum_d(sq, red, 1) / (double)D + 1e-6);
+  sum = wave_sum_d(sum);
+  sq = wave_sum_d(sq);
+  if ((threadIdx.x & 63) == 0) {
+    red[threadIdx.x >> 6] = sum;
+    red[4 + (threadIdx.x >> 6)] = sq;
+  }
+  __syncthreads();
+  const double mean = ((red[0] + red[1]) + (red[2] + red[3])) / (double)D;
+  const double var = ((red[4] + red[5]) + (red[6] + red[7])) / (double)D - mean * mean;
+  const double rstd = 1.0 / sqrt(fmax(var, 0.0) + 1e-6);
   float qs = 1.0f;
   int qz = 0;
   if (qp) {
@@ -360,21 +363,48 @@ __global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ to
       v[it].w = (v[it].w - mean) * rstd * (1.0f + c4.w) + s4.w;
     }
   }
-  for (int pp = 0; pp < p * p; ++pp) {
-    for (int c = 0; c < C; ++c) {
-      const int o = pp * 2 * C + c;
-      const float *wr = fw + (size_t)o * D;
-      float acc = 0.0f;
+  // the p*p*C dot products of this row, 16 at a time: per-lane partial sums, then a butterfly that halves
+  // the number of live values with every exchange (17 shuffles for 16 sums instead of 6 each)
+  const int n_out = p * p * C;
+  for (int o0 = 0; o0 < n_out; o0 += 16) {
+    float part[16];
 #pragma unroll
-      for (int it = 0; it < LN_MAX_IT; ++it) {
-        const int k = (lane + 64 * it) * 4;
-        if (k < D) {
-          float4 w4 = *(const float4 *)(wr + k);
-          acc += (v[it].x * w4.x + v[it].y * w4.y) + (v[it].z * w4.z + v[it].w * w4.w);
+    for (int u = 0; u < 16; ++u) {
+      part[u] = 0.0f;
+      const int oi = o0 + u;
+      if (oi < n_out) {
+        const float *wr = fw + (size_t)((oi / C) * 2 * C + oi % C) * D;
+#pragma unroll
+        for (int it = 0; it < LN_MAX_IT; ++it) {
+          const int k = (lane + 64 * it) * 4;
+          if (k < D) {
+            float4 w4 = *(const float4 *)(wr + k);
+            part[u] += (v[it].x * w4.x + v[it].y * w4.y) + (v[it].z * w4.z + v[it].w * w4.w);
+          }
         }
       }
-      acc = wave_sum(acc) + fb[o];
-      if (lane == 0) eps[(((size_t)b * C + c) * H + ty * p + pp / p) * W + tx * p + pp % p] = acc;
+    }
+    // after the exchange over distance 32 >> s a lane keeps the values whose index has bit (3 - s) equal to
+    // its own lane bit (5 - s); after 4 exchanges lane l holds value (l >> 2) & 15 summed over 16 lanes
+#pragma unroll
+    for (int s2 = 0; s2 < 4; ++s2) {
+      const int dist = 32 >> s2, half = 8 >> s2;
+      const bool upper = (lane & dist) != 0;
+#pragma unroll
+      for (int u = 0; u < half; ++u) {
+        const float keep = upper ? part[u + half] : part[u];
+        const float send = upper ? part[u] : part[u + half];
+        part[u] = keep + __shfl_xor(send, dist, 64);
+      }
+    }
+    float r = part[0];
+    r += __shfl_xor(r, 2, 64);
+    r += __shfl_xor(r, 1, 64);
+    const int u_mine = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
+    const int oi = o0 + u_mine;
+    if ((lane & 3) == 0 && oi < n_out) {
+      const int pp = oi / C, c = oi % C;
+      eps[(((size_t)b * C + c) * H + ty * p + pp / p) * W + tx * p + pp % p] = r + fb[pp * 2 * C + c];
     }
   }
 }

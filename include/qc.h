@@ -154,6 +154,21 @@ int qc_w8a8_linear(const int8_t *qx, const void *qw, const int32_t *wsum, const 
  * preserved and its variance scales by K_t^2, Eq. 9). */
 int qc_vc_correct(float *x, const float *K_t, const float *mu_or_null, int B, int C, int H, int W, void *stream);
 
+/* VC factors of one timestep ("Variance Align for Exposure Bias" section, the
+ * argmin objective that follows Eq. 10): for every channel c the K that
+ * minimises  sum ((x~ - x') / x')^2 + sum (x~ - x')^2,  x~ = mu + K (x^ - mu),
+ * over all elements of channel c in the batch; mu is the spatial mean of the
+ * x^ plane the element lies in.  The exact minimiser is computed,
+ * K = sum d (x' - mu) w / sum d^2 w,  d = x^ - mu,  w = 1 + 1 / (x'^2 + eps)
+ * (the closed form printed after the objective is this one for mu = 0, eps = 0);
+ * a channel with d == 0 everywhere gets K = 1.  fp64 accumulation.
+ * x_hat (accelerated sampler's sample, before VC), x_ref (full-precision
+ * sampler's sample at the same step): dev fp32 [B, C, H, W], read only;
+ * work: dev, B*C*2 doubles of scratch owned by the caller; K_t: dev fp32 [C],
+ * written.  eps >= 0. */
+int qc_vc_fit(const float *x_hat, const float *x_ref, int B, int C, int H, int W, float eps, double *work, float *K_t,
+              void *stream);
+
 /* Deterministic DDIM schedule on the 1000-step linear-beta (1e-4..2e-2)
  * training schedule: t[i] = (steps-1-i) * floor(1000/steps), abar_t[i],
  * abar_prev[i] (= 1 on the last step).  HOST arrays of `steps` entries. */
@@ -207,6 +222,30 @@ int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, fl
               void *stream);
 
 /* ------------------------------------------------------------- profiling */
+
+/* Noise prediction of the UN-quantised network (fp32 weights and activations,
+ * no cache): the reference that the VC factors are fitted against and the
+ * network the activation ranges are calibrated on.  Set-up-grade kernels, one
+ * sample at a time.  w: the fp32 weights (device pointers, as for
+ * qc_load_weights_f32, which must have run: the embedders and the final layer
+ * are taken from the context); x: dev [n_labels, C, H, W]; labels: dev
+ * [n_labels]; B = n_labels, or 2*n_labels for [labels ; null label] on the
+ * same latents; eps_out: dev [B, C, H, W]. */
+int qc_denoise_f32(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, int t, const int32_t *labels, int n_labels, int B,
+                   float *eps_out, void *stream);
+
+/* Fits K[steps, C] along a sampling trajectory ("Variance Align for Exposure
+ * Bias" section): the un-quantised, un-cached sampler (x_ref) and the
+ * quantised sampler under the cache rule (x_hat) run side by side from the
+ * same initial latents and labels on the schedule of qc_ddim_schedule; at
+ * every step the accelerated sample before VC is fitted against the reference
+ * sample (qc_vc_fit with vc_eps), the fitted K_i is applied to it (Eq. 10) and
+ * both go on.  x_hat, x_ref: dev [B, C, H, W], both holding the initial
+ * latents on entry (distinct buffers), the two final samples on return;
+ * labels: dev [B]; cfg_scale as in qc_sample_step; K_out: dev fp32
+ * [steps, C], written.  Requires activation parameters for every site. */
+int qc_vc_fit_sampler(qc_ctx *ctx, const qc_weights_f32 *w, float *x_hat, float *x_ref, const int32_t *labels, int B, int steps,
+                      float cfg_scale, float vc_eps, float *K_out, void *stream);
 
 /* Kernel classes of the per-launch timing below. */
 enum {

@@ -10,7 +10,7 @@ import os
 
 __all__ = [
     "lib", "QCError", "ModelDesc", "Context", "QC_FULL", "QC_CACHED", "QC_CACHE_ATTN", "QC_CACHE_MLP", "SITES",
-    "qc_quantize_act", "qc_quantize_weight", "qc_w8a8_linear", "qc_vc_correct", "qc_ddim_schedule", "last_error",
+    "qc_quantize_act", "qc_quantize_weight", "qc_w8a8_linear", "qc_vc_correct", "qc_vc_fit", "qc_ddim_schedule", "last_error",
     "LIB_PATH", "WS", "KERNEL_CLASSES",
 ]
 
@@ -56,6 +56,9 @@ _SIGS = {
     "qc_quantize_weight": (i32, [vp, i32, i32, i32, vp, vp, vp, vp]),
     "qc_w8a8_linear": (i32, [vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, vp, vp, vp]),
     "qc_vc_correct": (i32, [vp, vp, vp, i32, i32, i32, i32, vp]),
+    "qc_vc_fit": (i32, [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp]),
+    "qc_denoise_f32": (i32, [vp, C.POINTER(Weights), vp, i32, vp, i32, i32, vp, vp]),
+    "qc_vc_fit_sampler": (i32, [vp, C.POINTER(Weights), vp, vp, vp, i32, i32, f32, f32, vp, vp]),
     "qc_ddim_schedule": (i32, [i32, C.POINTER(C.c_int32), C.POINTER(f64), C.POINTER(f64)]),
     "qc_dit_block": (i32, [vp, i32, i32, vp, vp, i32, vp]),
     "qc_cache_store": (i32, [vp, i32, i32, vp, i32, vp]),
@@ -115,6 +118,11 @@ def qc_w8a8_linear(qx, qw, wsum, w_scale, bias, x_scale, x_zp, weight_bits, y, a
     N = qw.shape[0]
     _chk(lib.qc_w8a8_linear(_p(qx), _p(qw), _p(wsum), _p(w_scale), _p(bias), x_scale, x_zp, M, N, K, weight_bits,
                             _p(y), _p(acc), _stream()))
+
+
+def qc_vc_fit(x_hat, x_ref, eps, work, K_t):
+    B, Cc, H, W = x_hat.shape
+    _chk(lib.qc_vc_fit(_p(x_hat), _p(x_ref), B, Cc, H, W, float(eps), _p(work), _p(K_t), _stream()))
 
 
 def qc_vc_correct(x, K_t, mu=None):
@@ -192,6 +200,18 @@ class Context:
         ta = (C.c_int32 * n)(*[int(v) for v in t])
         ya = (C.c_int32 * n)(*[int(v) for v in y])
         _chk(lib.qc_calibrate_minmax(self.h, C.byref(self._keep[0]), _p(x), ta, ya, n, _stream()))
+
+    def denoise_f32(self, x, t, labels, B, eps_out):
+        if self._keep is None:
+            raise QCError(-5, "load_weights(..., keep_fp32=True) is needed before denoise_f32")
+        _chk(lib.qc_denoise_f32(self.h, C.byref(self._keep[0]), _p(x), int(t), _p(labels), labels.numel(), B, _p(eps_out),
+                                _stream()))
+
+    def vc_fit_sampler(self, x_hat, x_ref, labels, steps, cfg_scale, vc_eps, K_out):
+        if self._keep is None:
+            raise QCError(-5, "load_weights(..., keep_fp32=True) is needed before vc_fit_sampler")
+        _chk(lib.qc_vc_fit_sampler(self.h, C.byref(self._keep[0]), _p(x_hat), _p(x_ref), _p(labels), x_hat.shape[0], steps,
+                                   float(cfg_scale), float(vc_eps), _p(K_out), _stream()))
 
     def drop_fp32(self):
         self._keep = None

@@ -85,6 +85,8 @@ struct qc_ctx {
   std::vector<int> cache_batch;   // [L][2]: batch size held, 0 = nothing stored
   // workspace
   float *emb, *h1, *te, *cond, *mod, *fmod, *tokens, *qkv, *eps;
+  float *eps_ref;      // noise prediction of the un-quantised reference forward (VC fitting)
+  double *vcfit_work;  // per-plane partial sums of the VC fit [max_batch * C][2]
   int8_t *silu_q, *qa_ln, *qa_attn, *qa_mlp;
   _Float16 *qkv16;            // fp16 (high, low) Q, K words [B,H,T,hd] and V^T halves [B,H,DP,Tp] for the attention kernel
   long long qkv_part_stride, qkv_v_stride;   // words per Q / K array, halves per V^T array
@@ -208,13 +210,15 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
   float *cal_h = a.take<float>(T * D), *cal_o = a.take<float>(T * D), *cal_a = a.take<float>(T * D);
   float *cal_u = a.take<float>(T * R), *cal_mod = a.take<float>(6 * D);
   int *cal_slots = a.take<int>(L * QC_NUM_SITES * 2), *cal_label = a.take<int>(4);
+  float *eps_ref = a.take<float>(B * C * d.latent_h * d.latent_w);
+  double *vcfit_work = a.take<double>(B * C * 2);
   if (c) {
     c->patch_w = patch_w; c->patch_b = patch_b; c->pos = pos; c->t_w1 = t_w1; c->t_b1 = t_b1; c->t_w2 = t_w2; c->t_b2 = t_b2;
     c->label_table = label_table; c->fada_w = fada_w; c->fada_b = fada_b; c->flin_w = flin_w; c->flin_b = flin_b;
     c->dev_qp = dev_qp; c->cache = cache; c->emb = emb; c->h1 = h1; c->te = te; c->cond = cond; c->mod = mod; c->fmod = fmod;
     c->tokens = tokens; c->qkv = qkv; c->eps = eps; c->silu_q = silu_q; c->qa_ln = qa_ln; c->qa_attn = qa_attn;
     c->qa_mlp = qa_mlp; c->cal_h = cal_h; c->cal_o = cal_o; c->cal_a = cal_a; c->cal_u = cal_u; c->cal_mod = cal_mod;
-    c->cal_slots = cal_slots; c->cal_label = cal_label;
+    c->cal_slots = cal_slots; c->cal_label = cal_label; c->eps_ref = eps_ref; c->vcfit_work = vcfit_work;
     c->qkv16 = qkv16; c->qkv_part_stride = (long long)part; c->qkv_v_stride = (long long)vpart;
     c->qkv16_bytes = (4 * part + 2 * vpart) * sizeof(_Float16); c->DP = (int)DP; c->Tp = (int)Tp;
     c->win_rows = (int)WR;
@@ -842,6 +846,60 @@ static inline float ord2f(int i) {
   return f;
 }
 
+}  // extern "C"
+
+// Un-quantised fp32 forward of one sample through all blocks (the network the quantiser parameters are
+// calibrated on and the reference the VC factors are fitted against): tokens must hold the embedded sample,
+// cond the sample's conditioning vector.  With slots != null the min / max of the five quantiser sites of
+// every block are folded into slots[l][site][2].
+static int fp32_blocks_one(qc_ctx *ctx, const qc_weights_f32 *w, const float *cond, int *slots, hipStream_t st) {
+  const int D = ctx->D, R = ctx->R, T = ctx->T, L = ctx->L;
+  for (int l = 0; l < L; ++l) {
+    const qc_block_weights_f32 &b = w->blocks[l];
+    int *slot = slots ? slots + (size_t)l * QC_NUM_SITES * 2 : nullptr;
+    float *mod = ctx->cal_mod;
+    if (slot) QC_HIP(launch_minmax_silu(cond, D, slot + 2 * QC_SITE_ADA, st));
+    QC_HIP(launch_small_linear(cond, D, b.ada_w, b.ada_b, mod, 6 * D, 1, 6 * D, D, 1, 0, st));
+    QC_HIP(launch_ln_mod_quant(ctx->tokens, mod, mod + D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
+    if (slot) QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_QKV, st));
+    QC_HIP(launch_linear_f32(ctx->cal_h, b.qkv_w, b.qkv_b, ctx->qkv, T, 3 * D, D, 0, st));
+    QC_HIP(launch_attention(ctx->qkv, 1, T, ctx->H, ctx->hd, nullptr, nullptr, ctx->cal_o, st));
+    if (slot) QC_HIP(launch_minmax(ctx->cal_o, (size_t)T * D, slot + 2 * QC_SITE_PROJ, st));
+    QC_HIP(launch_linear_f32(ctx->cal_o, b.proj_w, b.proj_b, ctx->cal_a, T, D, D, 0, st));
+    QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 2 * D, 6 * D, 1, T, D, st));
+    QC_HIP(launch_ln_mod_quant(ctx->tokens, mod + 3 * D, mod + 4 * D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
+    if (slot) QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_FC1, st));
+    QC_HIP(launch_linear_f32(ctx->cal_h, b.fc1_w, b.fc1_b, ctx->cal_u, T, R, D, 2, st));
+    if (slot) QC_HIP(launch_minmax(ctx->cal_u, (size_t)T * R, slot + 2 * QC_SITE_FC2, st));
+    QC_HIP(launch_linear_f32(ctx->cal_u, b.fc2_w, b.fc2_b, ctx->cal_a, T, D, R, 0, st));
+    QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 5 * D, 6 * D, 1, T, D, st));
+  }
+  return QC_OK;
+}
+
+// eps[B] of the un-quantised network; x holds n_src latents, batch element b reads latent b % n_src
+// (guidance runs the same latents with the labels and with the null label).
+static int denoise_f32_impl(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, int n_src, int t, const int32_t *labels,
+                            int n_labels, int B, float *eps_out, hipStream_t st) {
+  const int D = ctx->D;
+  const size_t lat = (size_t)ctx->C * ctx->d.latent_h * ctx->d.latent_w;
+  const int32_t t32 = t;
+  int rc = run_cond(ctx, &t32, 1, labels, n_labels, B, st);
+  if (rc) return rc;
+  QC_HIP(launch_small_linear(ctx->cond, D, ctx->fada_w, ctx->fada_b, ctx->fmod, 2 * D, B, 2 * D, D, 1, 0, st));
+  for (int b = 0; b < B; ++b) {
+    QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 1, n_src, ctx->C, ctx->d.latent_h, ctx->d.latent_w,
+                        ctx->d.patch, D, b, st));
+    rc = fp32_blocks_one(ctx, w, ctx->cond + (size_t)b * D, nullptr, st);
+    if (rc) return rc;
+    QC_HIP(launch_final(ctx->tokens, ctx->fmod + (size_t)b * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + b * lat, 1, ctx->C,
+                        ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, st));
+  }
+  return QC_OK;
+}
+
+extern "C" {
+
 int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, const int32_t *t, const int32_t *y, int n,
                         void *stream) {
   if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
@@ -855,7 +913,7 @@ int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, co
     if (y[i] < 0 || y[i] > ctx->d.num_classes) QC_FAIL(QC_ERR_RANGE, "label %d outside 0..%d", y[i], ctx->d.num_classes);
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int D = ctx->D, R = ctx->R, T = ctx->T, L = ctx->L;
+  const int D = ctx->D, L = ctx->L;
   const size_t nslots = (size_t)L * QC_NUM_SITES;
   std::vector<int> init(nslots * 2);
   for (size_t i = 0; i < nslots; ++i) {
@@ -872,26 +930,8 @@ int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, co
     if (rc) return rc;
     QC_HIP(launch_embed(x + i * lat, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 1, 1, ctx->C, ctx->d.latent_h,
                         ctx->d.latent_w, ctx->d.patch, D, 0, st));
-    for (int l = 0; l < L; ++l) {
-      const qc_block_weights_f32 &b = w->blocks[l];
-      int *slot = ctx->cal_slots + (size_t)l * QC_NUM_SITES * 2;
-      float *mod = ctx->cal_mod;
-      QC_HIP(launch_minmax_silu(ctx->cond, D, slot + 2 * QC_SITE_ADA, st));
-      QC_HIP(launch_small_linear(ctx->cond, D, b.ada_w, b.ada_b, mod, 6 * D, 1, 6 * D, D, 1, 0, st));
-      QC_HIP(launch_ln_mod_quant(ctx->tokens, mod, mod + D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
-      QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_QKV, st));
-      QC_HIP(launch_linear_f32(ctx->cal_h, b.qkv_w, b.qkv_b, ctx->qkv, T, 3 * D, D, 0, st));
-      QC_HIP(launch_attention(ctx->qkv, 1, T, ctx->H, ctx->hd, nullptr, nullptr, ctx->cal_o, st));
-      QC_HIP(launch_minmax(ctx->cal_o, (size_t)T * D, slot + 2 * QC_SITE_PROJ, st));
-      QC_HIP(launch_linear_f32(ctx->cal_o, b.proj_w, b.proj_b, ctx->cal_a, T, D, D, 0, st));
-      QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 2 * D, 6 * D, 1, T, D, st));
-      QC_HIP(launch_ln_mod_quant(ctx->tokens, mod + 3 * D, mod + 4 * D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
-      QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_FC1, st));
-      QC_HIP(launch_linear_f32(ctx->cal_h, b.fc1_w, b.fc1_b, ctx->cal_u, T, R, D, 2, st));
-      QC_HIP(launch_minmax(ctx->cal_u, (size_t)T * R, slot + 2 * QC_SITE_FC2, st));
-      QC_HIP(launch_linear_f32(ctx->cal_u, b.fc2_w, b.fc2_b, ctx->cal_a, T, D, R, 0, st));
-      QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 5 * D, 6 * D, 1, T, D, st));
-    }
+    rc = fp32_blocks_one(ctx, w, ctx->cond, ctx->cal_slots, st);
+    if (rc) return rc;
   }
   std::vector<int> got(nslots * 2);
   QC_HIP(hipMemcpyAsync(got.data(), ctx->cal_slots, got.size() * sizeof(int), hipMemcpyDeviceToHost, st));
@@ -908,6 +948,68 @@ int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, co
     }
     rc = qc_set_act_qparams(ctx, (int)(i / QC_NUM_SITES), (int)(i % QC_NUM_SITES), s, z);
     if (rc) return rc;
+  }
+  return QC_OK;
+}
+
+int qc_vc_fit(const float *x_hat, const float *x_ref, int B, int C, int H, int W, float eps, double *work, float *K_t, void *stream) {
+  if (!x_hat || !x_ref || !work || !K_t) QC_FAIL(QC_ERR_NULL, "a pointer is NULL");
+  if (B < 1 || C < 1 || H < 1 || W < 1) QC_FAIL(QC_ERR_SHAPE, "B, C, H, W must be positive");
+  if (!(eps >= 0.0f)) QC_FAIL(QC_ERR_RANGE, "eps must be >= 0");
+  if (reinterpret_cast<uintptr_t>(work) & 7u) QC_FAIL(QC_ERR_ALIGN, "work must be 8-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  QC_HIP(launch_vc_fit(x_hat, x_ref, B, C, H * W, eps, work, K_t, st));
+  return QC_OK;
+}
+
+int qc_denoise_f32(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, int t, const int32_t *labels, int n_labels, int B,
+                   float *eps_out, void *stream) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  int rc = check_weights(ctx, w);
+  if (rc) return rc;
+  if (!x || !labels || !eps_out) QC_FAIL(QC_ERR_NULL, "x, labels or eps_out is NULL");
+  if (!ctx->weights_loaded) QC_FAIL(QC_ERR_STATE, "weights were not loaded");
+  if (B < 1 || B > ctx->max_batch) QC_FAIL(QC_ERR_SHAPE, "batch %d outside 1..%d", B, ctx->max_batch);
+  if (n_labels < 1 || (B != n_labels && B != 2 * n_labels))
+    QC_FAIL(QC_ERR_SHAPE, "effective batch %d must be n_labels (%d) or twice that", B, n_labels);
+  if (t < 0) QC_FAIL(QC_ERR_RANGE, "timestep must be non-negative");
+  return denoise_f32_impl(ctx, w, x, n_labels, t, labels, n_labels, B, eps_out, static_cast<hipStream_t>(stream));
+}
+
+int qc_vc_fit_sampler(qc_ctx *ctx, const qc_weights_f32 *w, float *x_hat, float *x_ref, const int32_t *labels, int B, int steps,
+                      float cfg_scale, float vc_eps, float *K_out, void *stream) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  int rc = check_weights(ctx, w);
+  if (rc) return rc;
+  if (!x_hat || !x_ref || !K_out) QC_FAIL(QC_ERR_NULL, "x_hat, x_ref or K_out is NULL");
+  if (x_hat == x_ref) QC_FAIL(QC_ERR_SHAPE, "x_hat and x_ref must be different buffers");
+  if (!(vc_eps >= 0.0f)) QC_FAIL(QC_ERR_RANGE, "vc_eps must be >= 0");
+  std::vector<int32_t> t(steps > 0 ? steps : 1);
+  std::vector<double> at(t.size()), ap(t.size());
+  rc = qc_ddim_schedule(steps, t.data(), at.data(), ap.data());
+  if (rc) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int Beff = cfg_scale > 0.0f ? 2 * B : B;
+  rc = check_denoise(ctx, x_hat, labels, B, Beff, QC_FULL);
+  if (rc) return rc;
+  const int HW = ctx->d.latent_h * ctx->d.latent_w, C = ctx->C;
+  for (int i = 0; i < steps; ++i) {
+    const double cx = std::sqrt(ap[i] / at[i]);
+    const double ce = std::sqrt(1.0 - ap[i]) - cx * std::sqrt(1.0 - at[i]);
+    // reference: un-quantised network, every step in full, no VC
+    rc = denoise_f32_impl(ctx, w, x_ref, B, t[i], labels, B, Beff, ctx->eps_ref, st);
+    if (rc) return rc;
+    QC_HIP(launch_ddim_vc(x_ref, ctx->eps_ref, B, C, HW, (float)cx, (float)ce, cfg_scale, nullptr, st));
+    // accelerated: quantised network under the cache rule, VC with the factor fitted at this very step
+    const int mode = step_mode(ctx, i, -1);
+    rc = prepare_window(ctx, &t[i], 1, labels, B, Beff, mode == QC_CACHED, st);
+    if (rc) return rc;
+    rc = denoise_impl(ctx, x_hat, B, Beff, mode, 0, ctx->eps, st);
+    if (rc) return rc;
+    QC_HIP(launch_ddim_vc(x_hat, ctx->eps, B, C, HW, (float)cx, (float)ce, cfg_scale, nullptr, st));
+    float *K_i = K_out + (size_t)i * C;
+    QC_HIP(launch_vc_fit(x_hat, x_ref, B, C, HW, vc_eps, ctx->vcfit_work, K_i, st));
+    QC_HIP(launch_vc(x_hat, K_i, nullptr, B, C, HW, st));
   }
   return QC_OK;
 }

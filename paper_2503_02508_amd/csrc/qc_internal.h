@@ -108,6 +108,8 @@ hipError_t launch_cached_blocks(float *x, const float *cache, size_t cache_block
 hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, float cx, float ce, float cfg_scale,
                           const float *K_t, hipStream_t st);
 hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, int HW, hipStream_t st);
+hipError_t launch_vc_fit(const float *x_hat, const float *x_ref, int B, int C, int HW, float eps, double *work, float *K_t,
+                         hipStream_t st);
 hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const QParam *qp, int8_t *q_out, float *f32_out,
                             hipStream_t st);
 hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,

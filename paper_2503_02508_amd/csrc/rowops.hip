@@ -556,6 +556,65 @@ hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, 
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ VC fit
+// Factors of one timestep: the exact minimiser, channel by channel, of
+//   sum ((x~ - x') / x')^2 + sum (x~ - x')^2,   x~ = mu + K (x^ - mu)     (objective after Eq. 10)
+// over the elements of the channel in the whole batch: K = S1 / S2 with S1 = sum d (x' - mu) w,
+// S2 = sum d^2 w, d = x^ - mu, w = 1 + 1 / (x'^2 + eps), mu = spatial mean of the x^ plane.
+// One workgroup per (sample, channel) plane writes its two partial sums (fp64); a second, tiny kernel adds the
+// planes of a channel in a fixed order, so the result does not depend on scheduling.
+__device__ __forceinline__ double block_sum_256d(double v, double *red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();                       // red may still be read from the previous use
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(256) void vc_fit_sums_kernel(const float *__restrict__ x_hat, const float *__restrict__ x_ref,
+                                                          int HW, double eps, double *__restrict__ part) {
+  __shared__ double red[4];
+  const int plane = blockIdx.x;
+  const float *xh = x_hat + (size_t)plane * HW, *xr = x_ref + (size_t)plane * HW;
+  double sum = 0.0;
+  for (int i = threadIdx.x; i < HW; i += 256) sum += (double)xh[i];
+  const double mu = block_sum_256d(sum, red) / (double)HW;
+  double s1 = 0.0, s2 = 0.0;
+  for (int i = threadIdx.x; i < HW; i += 256) {
+    const double d = (double)xh[i] - mu, r = (double)xr[i];
+    const double w = 1.0 + 1.0 / (r * r + eps);
+    s1 += d * (r - mu) * w;
+    s2 += d * d * w;
+  }
+  s1 = block_sum_256d(s1, red);
+  s2 = block_sum_256d(s2, red);
+  if (threadIdx.x == 0) {
+    part[2 * plane] = s1;
+    part[2 * plane + 1] = s2;
+  }
+}
+
+__global__ void vc_fit_solve_kernel(const double *__restrict__ part, int B, int C, float *__restrict__ K_t) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  double s1 = 0.0, s2 = 0.0;
+  for (int b = 0; b < B; ++b) {
+    s1 += part[2 * ((size_t)b * C + c)];
+    s2 += part[2 * ((size_t)b * C + c) + 1];
+  }
+  K_t[c] = s2 > 0.0 ? (float)(s1 / s2) : 1.0f;
+}
+
+hipError_t launch_vc_fit(const float *x_hat, const float *x_ref, int B, int C, int HW, float eps, double *work, float *K_t,
+                         hipStream_t st) {
+  hipLaunchKernelGGL(vc_fit_sums_kernel, dim3(B * C), dim3(256), 0, st, x_hat, x_ref, HW, (double)eps, work);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(vc_fit_solve_kernel, dim3((C + 63) / 64), dim3(64), 0, st, work, B, C, K_t);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------ calibration helpers
 // Plain fp32 tiled linear y = act(x W^T + b): 64x64 tile, 16-deep slabs, 4x4 per thread.
 __global__ __launch_bounds__(256) void linear_f32_kernel(const float *__restrict__ x, const float *__restrict__ W,

@@ -140,6 +140,32 @@ def block_cached(x, c, blk: int, linear, cache: dict):
     return x
 
 
+def block_mixed(x, c, blk: int, heads: int, linear, cache: dict, attn_full: bool, mlp_full: bool):
+    """A block under a per-module cache schedule (the cache rule of the
+    "Quantization and Cache" section applied module by module, as a learned
+    layer-caching policy would): each of the two modules is either recomputed,
+    which also refreshes its stored output, or replaced by its stored output;
+    gates always come from the current conditioning."""
+    B, T, D = x.shape
+    shift_msa, scale_msa, gate_msa, shift_mlp, scale_mlp, gate_mlp = block_mod(c, blk, linear)
+    if attn_full:
+        h = modulate(layer_norm(x), shift_msa, scale_msa)
+        qkv = linear(blk, "qkv", h.reshape(B * T, D)).reshape(B, T, 3 * D)
+        A = linear(blk, "proj", attention(qkv, heads).reshape(B * T, D)).reshape(B, T, D)
+        cache[(blk, "attn")] = A
+    else:
+        A = cache[(blk, "attn")]
+    x = x + gate_msa[:, None, :] * A
+    if mlp_full:
+        h2 = modulate(layer_norm(x), shift_mlp, scale_mlp)
+        Mo = linear(blk, "fc2", gelu_tanh(linear(blk, "fc1", h2.reshape(B * T, D)))).reshape(B, T, D)
+        cache[(blk, "mlp")] = Mo
+    else:
+        Mo = cache[(blk, "mlp")]
+    x = x + gate_mlp[:, None, :] * Mo
+    return x
+
+
 # ------------------------------------------------- embedders and final layer
 def timestep_embedding(t, dim: int = 256):
     t = np.asarray(t, dtype=F64).reshape(-1)
@@ -191,10 +217,16 @@ def final_layer(x, c, w: dict, p: int, C: int, H: int, W: int):
 
 def denoiser(x_lat, t, y, desc, w: dict, linear, cache: dict, full: bool, taps: list | None = None):
     """Noise estimate of the network for latents x_lat[B, C, H, W] at timesteps
-    t[B] with labels y[B].  `full` recomputes every block and refreshes the
-    cache; otherwise every block reuses it."""
+    t[B] with labels y[B].  `full` = True recomputes every block and refreshes
+    the cache, False reuses it in every block; an array [depth, 2] of booleans
+    decides per (block, module) with module 0 = attention, 1 = MLP."""
     c = conditioning(t, y, w)
     x = embed(x_lat, w, desc.patch)
+    if not isinstance(full, (bool, np.bool_)):
+        sched = np.asarray(full, dtype=bool).reshape(desc.depth, 2)
+        for blk in range(desc.depth):
+            x = block_mixed(x, c, blk, desc.heads, linear, cache, bool(sched[blk, 0]), bool(sched[blk, 1]))
+        return final_layer(x, c, w, desc.patch, desc.latent_c, desc.latent_h, desc.latent_w)
     for blk in range(desc.depth):
         if full:
             tap = None

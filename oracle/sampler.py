@@ -71,8 +71,14 @@ def vc_correct(x, K_t, mu=None):
 def sample_step(x, labels, i, t, abar_t, abar_prev, desc, w, linear, cache, interval,
                 cfg_scale=0.0, K_t=None, force_full=None, taps=None):
     """One sampler step: denoiser (full or cached by the cache rule), guidance,
-    solver update, VC."""
-    full = is_refresh_step(i, interval) if force_full is None else bool(force_full)
+    solver update, VC.  force_full: None = the rule, a boolean = that mode, an
+    array [depth, 2] = a per-(block, module) schedule for this step."""
+    if force_full is None:
+        full = is_refresh_step(i, interval)
+    elif isinstance(force_full, (bool, np.bool_, int)):
+        full = bool(force_full)
+    else:
+        full = np.asarray(force_full, dtype=bool)
     B = x.shape[0]
     if cfg_scale > 0:
         xin = np.concatenate([x, x], axis=0)
@@ -90,8 +96,9 @@ def sample_step(x, labels, i, t, abar_t, abar_prev, desc, w, linear, cache, inte
 
 
 def sample(x, labels, steps, interval, desc, w, linear, cfg_scale=0.0, K=None,
-           max_steps=None, trace=None):
-    """Run the sampler for `steps` steps (or only the first `max_steps`)."""
+           max_steps=None, trace=None, mask=None):
+    """Run the sampler for `steps` steps (or only the first `max_steps`).
+    mask[steps, depth, 2] (1 = recompute) replaces the interval rule."""
     t, abar_t, abar_prev = ddim_schedule(steps)
     cache: dict = {}
     x = np.asarray(x, dtype=F64)
@@ -99,7 +106,7 @@ def sample(x, labels, steps, interval, desc, w, linear, cfg_scale=0.0, K=None,
     for i in range(n):
         K_t = None if K is None else K[i]
         x, eps = sample_step(x, labels, i, int(t[i]), abar_t[i], abar_prev[i], desc, w, linear,
-                             cache, interval, cfg_scale, K_t)
+                             cache, interval, cfg_scale, K_t, None if mask is None else np.asarray(mask)[i])
         if trace is not None:
             trace.append((x.copy(), eps.copy()))
     return x

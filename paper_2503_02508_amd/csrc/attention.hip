@@ -211,7 +211,7 @@ template <int NCH, int NEB>   // feature chunks of 32 (operand width), feature b
 __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__restrict__ Qp, const unsigned *__restrict__ Kp,
                                                             const _Float16 *__restrict__ Vh, const _Float16 *__restrict__ Vl, int T,
                                                             int Tp, int H, int hd, int DPv, const QParam *qp,
-                                                            int8_t *__restrict__ q_out, long long *trace) {
+                                                            int8_t *__restrict__ q_out) {
   constexpr int DP = 32 * NCH;
   constexpr int KROW = DP + 8;    // halves per K row in LDS (16 bytes of padding)
   constexpr int VROW = 64 + 8;    // halves per V^T row in LDS
@@ -226,9 +226,6 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
   const int bh = blockIdx.x, b = bh / H, h = bh % H;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ql = lane & 15, g = lane >> 4;
-  long long tr[6] = {0, 0, 0, 0, 0, 0}, tl = 0;
-  if (trace) { tr[0] = wall_clock64(); tl = tr[0]; }
-#define QC_TR(k) if (trace) { long long now_ = wall_clock64(); tr[k] += now_ - tl; tl = now_; }
   const long long tok_base = (long long)bh * T * hd;
   const long long vt_base = (long long)bh * DPv * Tp;
   const int kchunks = 64 * (hd / 4);            // 16-byte chunks of one K tile
@@ -314,13 +311,11 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
       qlo[j][c] = *(v8h *)&ll;
     }
   }
-  QC_TR(1)
   for (int k0 = 0; k0 < T; k0 += 64) {
     __syncthreads();                       // everyone is done with the previous tile
     store_tile();
     __syncthreads();
     if (k0 + 64 < T) load_tile(k0 + 64);   // in flight during the MFMAs below
-    QC_TR(2)
 
     v4f s[2][4];
 #pragma unroll
@@ -340,7 +335,6 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
       s[0][kt] = acc0;
       s[1][kt] = acc1;
     }
-    QC_TR(3)
     v8h ph[2][2], pl[2][2];
     const bool ragged_tile = k0 + 64 > T;
 #pragma unroll
@@ -372,7 +366,6 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
           pl[j][kt >> 1][(kt & 1) * 4 + r] = (_Float16)(pv - (float)hi);
         }
     }
-    QC_TR(4)
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -386,7 +379,6 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
           o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[j][a], o[j][e], 0, 0, 0);
         }
       }
-    QC_TR(5)
   }
 
   const QParam t = *qp;
@@ -411,15 +403,7 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
                                            ((unsigned)(c[2] & 0xFF) << 16) | ((unsigned)(c[3] & 0xFF) << 24);
     }
   }
-  if (trace && tid == 0) {
-    long long *o_ = trace + 8 * (long long)(blockIdx.y * gridDim.x + blockIdx.x);
-    o_[0] = tr[0]; o_[1] = tr[1]; o_[2] = tr[2]; o_[3] = tr[3]; o_[4] = tr[4]; o_[5] = tr[5]; o_[6] = wall_clock64();
-  }
-#undef QC_TR
 }
-
-extern long long *g_trace;
-extern int g_trace_epi;
 
 hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
                                 int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st) {
@@ -428,7 +412,7 @@ hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words
   if (hd > 80 || hd % 4) return hipErrorInvalidValue;      // K prefetch registers are sized for d <= 80
 #define QC_ATT(NCH, NEB)                                                                                               \
   hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, H, hd, \
-                     DPv, qp, q_out, g_trace_epi == 100 ? g_trace : nullptr)
+                     DPv, qp, q_out)
   if (nch == 1 && neb == 1) QC_ATT(1, 1);
   else if (nch == 1) QC_ATT(1, 2);
   else if (nch == 2 && neb == 3) QC_ATT(2, 3);

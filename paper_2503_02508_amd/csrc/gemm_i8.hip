@@ -40,8 +40,6 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 
 constexpr int NUM_XCD = 8;
-long long *g_trace = nullptr;
-int g_trace_epi = -1, g_trace_tag = -1;
 
 __device__ __forceinline__ int map_col(int j, int sel_D) {
   return sel_D ? (j < sel_D ? j + 2 * sel_D : j + 4 * sel_D) : j;
@@ -99,8 +97,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int z = blockIdx.z;
-  long long *trace = p.trace ? p.trace + 4 * (long long)blockIdx.x : nullptr;
-  if (trace && tid == 0) trace[0] = wall_clock64();
   const int ncover = p.sel_D ? 2 * p.sel_D : p.N;
   const int tiles_m = (p.M + BM - 1) / BM;
   // XCD-aware order: workgroup b runs on XCD b % 8.  The 8 XCDs form an xm x xn
@@ -317,7 +313,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     if (s < nk) load_slab(s, s * BK, k_ragged && s == nk - 1);
   store_slab(0, 0, k_ragged && nk == 1 && lc * 16 >= p.K);
   __syncthreads();
-  if (trace && tid == 0) trace[1] = wall_clock64();
   // main loop, unrolled by PF so that the register sets rotate with static indices:
   // at step kt LDS[kt & 1] holds slab kt, registers hold slabs kt+1 .. kt+PF-1.
   // Steady state is straight-line code (every step loads, computes, stores) so
@@ -349,7 +344,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     }
   }
 
-  if (trace && tid == 0) trace[2] = wall_clock64();
   // ------------------------------------------------------------ epilogue
   float a_s = p.a_scale;
   int a_z = p.a_zp;
@@ -416,7 +410,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
         for (int e = 0; n + e < p.N; ++e) dst[e] = (int8_t)stage[r * SROW + cc + e];
       }
     }
-    if (trace && tid == 0) trace[3] = wall_clock64();
     return;
   }
 
@@ -521,7 +514,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
         }
       }
     }
-    if (trace && tid == 0) trace[3] = wall_clock64();
     return;
   }
 
@@ -589,7 +581,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
           }
         }
       }
-    if (trace && tid == 0) trace[3] = wall_clock64();
     return;
   }
 
@@ -642,7 +633,6 @@ static hipError_t launch_cfg(const GemmArgs &a, int nz, hipStream_t st) {
   }
   GemmArgs b = a;
   b.xcd_m = best_xm;
-  b.trace = (EPI == g_trace_epi && TAG == g_trace_tag) ? g_trace : nullptr;
   const int cm = (tiles_m + best_xm - 1) / best_xm, cn = (tiles_n + NUM_XCD / best_xm - 1) / (NUM_XCD / best_xm);
   const int grid = NUM_XCD * cm * cn;
   hipLaunchKernelGGL(kern, dim3(grid, 1, nz), dim3(64 * WM * WN), smem, st, b);
@@ -695,5 +685,4 @@ hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st, int s
 }
 
 }  // namespace qc
-extern "C" void qc_debug_trace(long long *p, int epi, int tag) { qc::g_trace = p; qc::g_trace_epi = epi; qc::g_trace_tag = tag; }
 

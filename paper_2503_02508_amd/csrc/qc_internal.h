@@ -49,7 +49,6 @@ struct GemmArgs {
   // (the two gate chunks of an adaLN projection).
   int sel_D;
   int xcd_m;                 // XCD grid rows (set by the launcher)
-  long long *trace;          // optional: 4 timestamps per workgroup (tuning aid)
   // EPI_F32
   float *y;
   int ldy;

@@ -91,6 +91,11 @@ def test_context_state_checks_without_a_device(qc):
     assert qc.lib.qc_cache_store(h, 9, 0, fake, 1, None) == -4
     assert qc.lib.qc_cache_reuse(h, 0, 0, fake, fake, 64, 1, None) == -5        # nothing stored
     assert qc.lib.qc_cache_reuse(h, 0, 0, fake, fake, 10, 1, None) == -2
+    # the fitting entry points check the weight table and the context state first
+    assert qc.lib.qc_denoise_f32(h, None, fake, 10, fake, 1, 1, fake, None) != 0
+    assert qc.lib.qc_vc_fit_sampler(h, None, fake, C.c_void_p(0x300000), fake, 1, 4, 0.0, 1e-3, fake, None) != 0
+    assert qc.lib.qc_denoise_f32(None, None, fake, 10, fake, 1, 1, fake, None) == -1
+    assert qc.lib.qc_vc_fit_sampler(None, None, fake, fake, fake, 1, 4, 0.0, 1e-3, fake, None) == -1
     p = C.c_void_p()
     assert qc.lib.qc_cache_ptr(h, 1, 1, C.byref(p)) == 0 and p.value >= 0x100000
     assert qc.lib.qc_workspace_ptr(h, 99, C.byref(p), None) == -4
@@ -112,6 +117,12 @@ def test_single_op_argument_checks_without_a_device(qc):
     assert qc.lib.qc_vc_correct(None, f, None, 1, 4, 8, 8, None) == -1
     assert qc.lib.qc_vc_correct(f, f, None, 0, 4, 8, 8, None) == 0
     assert qc.lib.qc_vc_correct(f, f, None, 1, 0, 8, 8, None) == -2
+    assert qc.lib.qc_vc_fit(None, f, 1, 4, 8, 8, 1e-3, f, f, None) == -1
+    assert qc.lib.qc_vc_fit(f, f, 1, 4, 8, 8, 1e-3, None, f, None) == -1
+    assert qc.lib.qc_vc_fit(f, f, 0, 4, 8, 8, 1e-3, f, f, None) == -2
+    assert qc.lib.qc_vc_fit(f, f, 1, 4, 8, 8, -1.0, f, f, None) == -4
+    assert qc.lib.qc_vc_fit(f, f, 1, 4, 8, 8, float("nan"), f, f, None) == -4
+    assert qc.lib.qc_vc_fit(f, f, 1, 4, 8, 8, 1e-3, C.c_void_p(0x1004), f, None) == -3
 
 
 @pytest.mark.parametrize("steps", [50, 100, 250, 7, 1])

@@ -201,6 +201,40 @@ def test_interval_one_is_no_cache():
     assert np.array_equal(a, x)
 
 
+def test_per_module_schedule_special_cases():
+    """The per-(block, module) schedule: all ones is the full step, all zeros the cached step, the schedule
+    built from the interval rule is the interval sampler, and recomputing one module on an unchanged input
+    reproduces its stored output (so a mixed step on a fresh cache equals the full step) - all bitwise."""
+    w, lat, lab = _tiny_setup()
+    t = np.array([500, 500, 500])
+    qp, _ = _qparams_for(w, lat, lab, t)
+    lin = dit.QLinears(w, qp)
+    L = TINY.depth
+    cache = {}
+    full = dit.denoiser(lat, t, lab, TINY, w, lin, cache, True)
+    ones, zeros = np.ones((L, 2), bool), np.zeros((L, 2), bool)
+    assert np.array_equal(dit.denoiser(lat, t, lab, TINY, w, lin, {}, ones), full)
+    assert np.array_equal(dit.denoiser(lat, t, lab, TINY, w, lin, dict(cache), zeros), full)
+    for sched in ([[1, 0]] * L, [[0, 1]] * L, [[1, 0], [0, 1]][:L] + [[0, 0]] * (L - 2)):
+        c2 = {k: v.copy() for k, v in cache.items()}
+        assert np.array_equal(dit.denoiser(lat, t, lab, TINY, w, lin, c2, np.array(sched, bool)), full)
+    # at another timestep a recomputed module differs from its stored output, and is stored again
+    c3 = {k: v.copy() for k, v in cache.items()}
+    sched = np.zeros((L, 2), bool)
+    sched[0, 1] = True
+    mixed = dit.denoiser(lat, t - 40, lab, TINY, w, lin, c3, sched)
+    cached = dit.denoiser(lat, t - 40, lab, TINY, w, lin, dict(cache), False)
+    assert not np.array_equal(mixed, cached)
+    assert not np.array_equal(c3[(0, "mlp")], cache[(0, "mlp")]) and np.array_equal(c3[(0, "attn")], cache[(0, "attn")])
+    # the interval rule written as a mask
+    steps, N = 7, 3
+    mask = np.zeros((steps, L, 2), bool)
+    mask[::N] = True
+    a = sampler.sample(lat, lab, steps, N, TINY, w, lin)
+    b = sampler.sample(lat, lab, steps, 1, TINY, w, lin, mask=mask)
+    assert np.array_equal(a, b)
+
+
 def test_cached_run_differs_but_tracks_uncached_run():
     w, lat, lab = _tiny_setup()
     qp, _ = _qparams_for(w, lat, lab, np.array([500, 500, 500]))

@@ -194,6 +194,17 @@ int qc_cache_ptr(qc_ctx *ctx, int block, int which, float **ptr_out);
 /* Device address of an internal buffer, see QC_WS_*; for inspection by tests. */
 int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out);
 
+/* Per-(step, block, module) cache schedule, a generalisation of the interval
+ * rule of the "Quantization and Cache" section to learned layer-caching
+ * policies (the kind the ablation compares against): mask is a HOST array
+ * [steps][depth][2] of 0/1, module 0 = attention, 1 = MLP; 1 recomputes the
+ * module at that step and stores its output, 0 reuses the stored output (gates
+ * always follow the current conditioning).  Row 0 must be all ones.  It
+ * replaces `step_index mod N` in qc_sample_step (force_mode -1), qc_sample and
+ * qc_vc_fit_sampler, which then accept at most `steps` steps; the array is
+ * copied.  mask = NULL restores the interval rule. */
+int qc_set_cache_mask(qc_ctx *ctx, const unsigned char *mask, int steps);
+
 /* Inspection aid: when on, full blocks also write the QKV projection as fp32 into the
  * QC_WS_QKV buffer (the attention kernel itself reads an fp16 high/low split of it). */
 int qc_keep_qkv_f32(qc_ctx *ctx, int on);

@@ -56,6 +56,7 @@ _SIGS = {
     "qc_quantize_weight": (i32, [vp, i32, i32, i32, vp, vp, vp, vp]),
     "qc_w8a8_linear": (i32, [vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, vp, vp, vp]),
     "qc_vc_correct": (i32, [vp, vp, vp, i32, i32, i32, i32, vp]),
+    "qc_set_cache_mask": (i32, [vp, vp, i32]),
     "qc_vc_fit": (i32, [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp]),
     "qc_denoise_f32": (i32, [vp, C.POINTER(Weights), vp, i32, vp, i32, i32, vp, vp]),
     "qc_vc_fit_sampler": (i32, [vp, C.POINTER(Weights), vp, vp, vp, i32, i32, f32, f32, vp, vp]),
@@ -223,6 +224,15 @@ class Context:
         s, z = f32(), i32()
         _chk(lib.qc_get_act_qparams(self.h, block, site, C.byref(s), C.byref(z)))
         return s.value, z.value
+
+    def set_cache_mask(self, mask):
+        """mask: numpy array [steps, depth, 2] of 0/1 (1 = recompute), or None for the interval rule."""
+        if mask is None:
+            _chk(lib.qc_set_cache_mask(self.h, None, 0))
+            return
+        import numpy as np
+        m = np.ascontiguousarray(np.asarray(mask, dtype=np.uint8))
+        _chk(lib.qc_set_cache_mask(self.h, m.ctypes.data_as(vp), m.shape[0]))
 
     def keep_qkv_f32(self, on=True):
         _chk(lib.qc_keep_qkv_f32(self.h, int(on)))

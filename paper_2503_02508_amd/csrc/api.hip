@@ -83,6 +83,8 @@ struct qc_ctx {
   QParam *dev_qp;   // [L][5]
   float *cache;     // [L][2][max_batch*T*D]
   std::vector<int> cache_batch;   // [L][2]: batch size held, 0 = nothing stored
+  std::vector<unsigned char> cache_mask;   // optional [steps][L][2] schedule (1 = recompute); empty = interval rule
+  int mask_steps = 0;
   // workspace
   float *emb, *h1, *te, *cond, *mod, *fmod, *tokens, *qkv, *eps;
   float *eps_ref;      // noise prediction of the un-quantised reference forward (VC fitting)
@@ -462,7 +464,8 @@ static int run_adaln(qc_ctx *ctx, int l0, int nl, int r0, int rows, bool gates_o
 }
 
 // One full block on the rows of sub-batch sb; x points at the first of those rows.
-static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream_t st) {
+static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream_t st, bool attn_full = true,
+                          bool mlp_full = true) {
   const int D = ctx->D, R = ctx->R, T = ctx->T, B = sb.nb, M = B * T;
   const size_t row0 = (size_t)sb.b0 * T;
   const float *mod = ctx->mod + ((size_t)l * ctx->win_rows + sb.r0) * 6 * D;
@@ -480,6 +483,9 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
     a.M = M; a.N = q.N; a.K = K; a.lda = K; a.w4 = w4; a.a_qp = qp + site;
     return a;
   };
+  if (!attn_full) {
+    QC_HIP(launch_cache_reuse(x, cache_slot(ctx, l, QC_CACHE_ATTN) + row0 * D, mod + 2 * D, 6 * D, B, T, D, st));
+  } else {
   {
     QC_PROF(QC_K_LN_QUANT);
     QC_HIP(launch_ln_mod_quant(x, mod, mod + D, 6 * D, M, D, T, qp + QC_SITE_QKV, qa_ln, nullptr, st));
@@ -504,6 +510,11 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
     a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_PROJ);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_PROJ));
+  }
+  }
+  if (!mlp_full) {
+    QC_HIP(launch_cache_reuse(x, cache_slot(ctx, l, QC_CACHE_MLP) + row0 * D, mod + 5 * D, 6 * D, B, T, D, st));
+    return QC_OK;
   }
   {
     QC_PROF(QC_K_LN_QUANT);
@@ -611,6 +622,24 @@ int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out) 
   return QC_OK;
 }
 
+int qc_set_cache_mask(qc_ctx *ctx, const unsigned char *mask, int steps) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  if (!mask) {
+    ctx->cache_mask.clear();
+    ctx->mask_steps = 0;
+    return QC_OK;
+  }
+  if (steps < 1) QC_FAIL(QC_ERR_SHAPE, "steps must be >= 1");
+  const size_t row = (size_t)ctx->L * 2;
+  for (size_t i = 0; i < row; ++i)
+    if (!mask[i]) QC_FAIL(QC_ERR_RANGE, "step 0 must recompute every module (block %zu, module %zu is marked as reused)", i / 2, i % 2);
+  for (size_t i = 0; i < row * steps; ++i)
+    if (mask[i] > 1) QC_FAIL(QC_ERR_RANGE, "schedule entries must be 0 or 1");
+  ctx->cache_mask.assign(mask, mask + row * steps);
+  ctx->mask_steps = steps;
+  return QC_OK;
+}
+
 int qc_keep_qkv_f32(qc_ctx *ctx, int on) {
   if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
   ctx->keep_qkv_f32 = on != 0;
@@ -691,8 +720,21 @@ static int choose_lanes(qc_ctx *ctx, int B) {
   return n < 1 ? 1 : n;
 }
 
-// One denoiser evaluation whose conditioning sits in slot `w` of the prepared window.
-static int denoise_impl(qc_ctx *ctx, const float *x, int n_labels, int B, int mode, int w, float *eps_out, hipStream_t st) {
+// One denoiser evaluation whose conditioning sits in slot `w` of the prepared window.  sched (optional,
+// [L][2], 1 = recompute) decides per (block, module) instead of `mode`.
+static int denoise_impl(qc_ctx *ctx, const float *x, int n_labels, int B, int mode, int w, float *eps_out, hipStream_t st,
+                        const unsigned char *sched = nullptr) {
+  bool mixed = false;
+  if (sched) {
+    int n_full = 0;
+    for (int i = 0; i < 2 * ctx->L; ++i) n_full += sched[i] ? 1 : 0;
+    for (int i = 0; i < 2 * ctx->L; ++i)
+      if (!sched[i] && ctx->cache_batch[i] != B)
+        QC_FAIL(QC_ERR_STATE, "block %d reuses cached tensor %d but the cache does not hold batch %d", i / 2, i % 2, B);
+    if (n_full == 2 * ctx->L) mode = QC_FULL;
+    else if (n_full == 0) mode = QC_CACHED;
+    else mixed = true;
+  }
   const int lanes = choose_lanes(ctx, B);
   Sub sub[MAX_LANES];
   hipStream_t ls[MAX_LANES];
@@ -713,18 +755,23 @@ static int denoise_impl(qc_ctx *ctx, const float *x, int n_labels, int B, int mo
   }
   int rc = QC_OK;
   for (int i = 0; i < lanes && !rc; ++i) rc = denoise_head(ctx, x, n_labels, sub[i], ls[i]);
-  if (mode == QC_FULL)
+  if (mode == QC_FULL || mixed)
     for (int l = 0; l < ctx->L && !rc; ++l)
       for (int i = 0; i < lanes && !rc; ++i)
-        rc = run_block_full(ctx, l, ctx->tokens + (size_t)sub[i].b0 * ctx->T * ctx->D, sub[i], ls[i]);
-  for (int i = 0; i < lanes && !rc; ++i) rc = denoise_tail(ctx, sub[i], mode, eps_out, ls[i]);
+        rc = run_block_full(ctx, l, ctx->tokens + (size_t)sub[i].b0 * ctx->T * ctx->D, sub[i], ls[i],
+                            mixed ? sched[2 * l] != 0 : true, mixed ? sched[2 * l + 1] != 0 : true);
+  for (int i = 0; i < lanes && !rc; ++i) rc = denoise_tail(ctx, sub[i], mixed ? QC_FULL : mode, eps_out, ls[i]);
   // join even after an error so that the internal streams never run past the caller's stream unobserved
   for (int i = 1; i < lanes; ++i) {
     QC_HIP(hipEventRecord(ctx->ev_join[i], ls[i]));
     QC_HIP(hipStreamWaitEvent(st, ctx->ev_join[i], 0));
   }
-  if (rc == QC_OK && mode == QC_FULL)
+  if (rc == QC_OK && mixed) {
+    for (int i = 0; i < 2 * ctx->L; ++i)
+      if (sched[i]) ctx->cache_batch[i] = B;
+  } else if (rc == QC_OK && mode == QC_FULL) {
     for (int &v : ctx->cache_batch) v = B;
+  }
   return rc;
 }
 
@@ -758,11 +805,18 @@ static int step_mode(const qc_ctx *ctx, int step_index, int force_mode) {
   return force_mode >= 0 ? force_mode : (step_index % ctx->d.cache_interval == 0 ? QC_FULL : QC_CACHED);
 }
 
+// Row of the installed per-(step, block, module) schedule for this step, or null when the interval rule (or a
+// forced mode) decides.
+static const unsigned char *step_sched(const qc_ctx *ctx, int step_index, int force_mode) {
+  if (force_mode >= 0 || ctx->cache_mask.empty()) return nullptr;
+  return ctx->cache_mask.data() + (size_t)step_index * ctx->L * 2;
+}
+
 // One sampler step whose conditioning sits in slot w of the prepared window: denoiser, CFG, DDIM update, VC.
 static int sample_step_prepared(qc_ctx *ctx, float *x, int B, int mode, int w, double abar_t, double abar_prev, float cfg_scale,
-                                const float *K_t, hipStream_t st) {
+                                const float *K_t, hipStream_t st, const unsigned char *sched = nullptr) {
   const int Beff = cfg_scale > 0.0f ? 2 * B : B;
-  int rc = denoise_impl(ctx, x, B, Beff, mode, w, ctx->eps, st);
+  int rc = denoise_impl(ctx, x, B, Beff, mode, w, ctx->eps, st, sched);
   if (rc) return rc;
   const double cx = std::sqrt(abar_prev / abar_t);
   const double ce = std::sqrt(1.0 - abar_prev) - cx * std::sqrt(1.0 - abar_t);
@@ -778,13 +832,16 @@ int qc_sample_step(qc_ctx *ctx, float *x, const int32_t *labels, int B, int step
   if (force_mode != -1 && force_mode != QC_FULL && force_mode != QC_CACHED) QC_FAIL(QC_ERR_RANGE, "force_mode must be -1, QC_FULL or QC_CACHED");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int Beff = cfg_scale > 0.0f ? 2 * B : B;
-  const int mode = step_mode(ctx, step_index, force_mode);
+  if (force_mode < 0 && !ctx->cache_mask.empty() && step_index >= ctx->mask_steps)
+    QC_FAIL(QC_ERR_RANGE, "step %d is outside the installed cache schedule of %d steps", step_index, ctx->mask_steps);
+  const unsigned char *sched = step_sched(ctx, step_index, force_mode);
+  const int mode = sched ? QC_FULL : step_mode(ctx, step_index, force_mode);   // with a schedule the per-module check is in the denoiser
   int rc = check_denoise(ctx, x, labels, B, Beff, mode);
   if (rc) return rc;
   const int32_t t32 = t;
-  rc = prepare_window(ctx, &t32, 1, labels, B, Beff, mode == QC_CACHED, st);
+  rc = prepare_window(ctx, &t32, 1, labels, B, Beff, !sched && mode == QC_CACHED, st);
   if (rc) return rc;
-  return sample_step_prepared(ctx, x, B, mode, 0, abar_t, abar_prev, cfg_scale, K_t, st);
+  return sample_step_prepared(ctx, x, B, mode, 0, abar_t, abar_prev, cfg_scale, K_t, st, sched);
 }
 
 int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, float cfg_scale, const float *K, void *stream) {
@@ -797,6 +854,8 @@ int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, fl
   const int Beff = cfg_scale > 0.0f ? 2 * B : B;
   rc = check_denoise(ctx, x, labels, B, Beff, QC_FULL);
   if (rc) return rc;
+  if (!ctx->cache_mask.empty() && steps > ctx->mask_steps)
+    QC_FAIL(QC_ERR_RANGE, "%d steps requested but the installed cache schedule has %d", steps, ctx->mask_steps);
   // the whole schedule is known: conditioning and adaLN projections are prepared a window of steps at a time
   const int W = std::max(1, std::min(steps, ctx->win_rows / Beff));
   for (int i0 = 0; i0 < steps; i0 += W) {
@@ -805,7 +864,7 @@ int qc_sample(qc_ctx *ctx, float *x, const int32_t *labels, int B, int steps, fl
     if (rc) return rc;
     for (int i = i0; i < i0 + nw; ++i) {
       rc = sample_step_prepared(ctx, x, B, step_mode(ctx, i, -1), i - i0, at[i], ap[i], cfg_scale,
-                                K ? K + (size_t)i * ctx->C : nullptr, st);
+                                K ? K + (size_t)i * ctx->C : nullptr, st, step_sched(ctx, i, -1));
       if (rc) return rc;
     }
   }
@@ -992,6 +1051,8 @@ int qc_vc_fit_sampler(qc_ctx *ctx, const qc_weights_f32 *w, float *x_hat, float 
   const int Beff = cfg_scale > 0.0f ? 2 * B : B;
   rc = check_denoise(ctx, x_hat, labels, B, Beff, QC_FULL);
   if (rc) return rc;
+  if (!ctx->cache_mask.empty() && steps > ctx->mask_steps)
+    QC_FAIL(QC_ERR_RANGE, "%d steps requested but the installed cache schedule has %d", steps, ctx->mask_steps);
   const int HW = ctx->d.latent_h * ctx->d.latent_w, C = ctx->C;
   for (int i = 0; i < steps; ++i) {
     const double cx = std::sqrt(ap[i] / at[i]);
@@ -1002,9 +1063,10 @@ int qc_vc_fit_sampler(qc_ctx *ctx, const qc_weights_f32 *w, float *x_hat, float 
     QC_HIP(launch_ddim_vc(x_ref, ctx->eps_ref, B, C, HW, (float)cx, (float)ce, cfg_scale, nullptr, st));
     // accelerated: quantised network under the cache rule, VC with the factor fitted at this very step
     const int mode = step_mode(ctx, i, -1);
-    rc = prepare_window(ctx, &t[i], 1, labels, B, Beff, mode == QC_CACHED, st);
+    const unsigned char *sched = step_sched(ctx, i, -1);
+    rc = prepare_window(ctx, &t[i], 1, labels, B, Beff, !sched && mode == QC_CACHED, st);
     if (rc) return rc;
-    rc = denoise_impl(ctx, x_hat, B, Beff, mode, 0, ctx->eps, st);
+    rc = denoise_impl(ctx, x_hat, B, Beff, mode, 0, ctx->eps, st, sched);
     if (rc) return rc;
     QC_HIP(launch_ddim_vc(x_hat, ctx->eps, B, C, HW, (float)cx, (float)ce, cfg_scale, nullptr, st));
     float *K_i = K_out + (size_t)i * C;

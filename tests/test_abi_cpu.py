@@ -91,6 +91,18 @@ def test_context_state_checks_without_a_device(qc):
     assert qc.lib.qc_cache_store(h, 9, 0, fake, 1, None) == -4
     assert qc.lib.qc_cache_reuse(h, 0, 0, fake, fake, 64, 1, None) == -5        # nothing stored
     assert qc.lib.qc_cache_reuse(h, 0, 0, fake, fake, 10, 1, None) == -2
+    # cache schedule: host array [steps][depth][2]; row 0 must be all ones, entries 0/1
+    L = d.depth
+    ok = (C.c_ubyte * (3 * L * 2))(*([1] * (L * 2) + [0, 1] * L + [0] * (L * 2)))
+    assert qc.lib.qc_set_cache_mask(h, ok, 3) == 0
+    assert qc.lib.qc_sample_step(h, fake, fake, 1, 3, 10, 0.5, 0.6, 0.0, None, -1, None) == -4     # step beyond the schedule
+    bad0 = (C.c_ubyte * (L * 2))(*([1] * (L * 2 - 1) + [0]))
+    assert qc.lib.qc_set_cache_mask(h, bad0, 1) == -4
+    bad2 = (C.c_ubyte * (2 * L * 2))(*([1] * (L * 2) + [2] * (L * 2)))
+    assert qc.lib.qc_set_cache_mask(h, bad2, 2) == -4
+    assert qc.lib.qc_set_cache_mask(h, ok, 0) == -2
+    assert qc.lib.qc_set_cache_mask(None, ok, 3) == -1
+    assert qc.lib.qc_set_cache_mask(h, None, 0) == 0                                               # back to the interval rule
     # the fitting entry points check the weight table and the context state first
     assert qc.lib.qc_denoise_f32(h, None, fake, 10, fake, 1, 1, fake, None) != 0
     assert qc.lib.qc_vc_fit_sampler(h, None, fake, C.c_void_p(0x300000), fake, 1, 4, 0.0, 1e-3, fake, None) != 0

@@ -311,6 +311,80 @@ def test_qc_sample_equals_step_by_step_calls(B, steps, interval, cfg):
     ctx.close()
 
 
+def _random_mask(steps, depth, seed, p_full=0.5):
+    rng = np.random.default_rng(seed)
+    m = (rng.random((steps, depth, 2)) < p_full).astype(np.uint8)
+    m[0] = 1
+    return m
+
+
+@pytest.mark.parametrize("name,model,B,steps,cfg", [("tiny", TINY, 3, 9, 0.0), ("tiny_cfg", TINY, 2, 8, 1.5),
+                                                    ("ragged", RAGGED, 2, 7, 0.0),
+                                                    ("xl_256_depth2", I.shrink(I.DIT_XL2_256, 2), 2, 6, 0.0)])
+def test_sampler_with_per_module_cache_schedule(name, model, B, steps, cfg):
+    """A random per-(step, block, module) schedule: mixed steps recompute some modules and reuse others.
+    Teacher-forced against the oracle step by step, then the whole loop through qc_sample."""
+    import torch
+    std = 0.02 if model.hidden > 256 else 0.15
+    w = I.make_weights(model, 71, std=std)
+    tt, at, ap = sampler.ddim_schedule(steps)
+    clat = np.concatenate([I.make_latents(1, model, 4000 + i) for i in range(4)])
+    qp, _, _ = oracle_calibration(model, w, lat=clat, lab=I.make_labels(4, model, 72), t=tt[[0, steps // 3, 2 * steps // 3, steps - 1]])
+    Beff = 2 * B if cfg > 0 else B
+    lin, ctx = make_pair(model, w, qp, Beff, 2)
+    mask = _random_mask(steps, model.depth, 73)
+    assert 0 < mask[1:].mean() < 1
+    ctx.set_cache_mask(mask)
+    lat, lab = I.make_latents(B, model, 74), I.make_labels(B, model, 75)
+    K = I.make_vc_factors(steps, model.latent_c, 76)
+    Kd, ld = _cuda(K), _cuda(lab.astype(np.int32))
+    x_or, cache = lat.astype(np.float64), {}
+    worst = (0.0, 0.0)
+    for i in range(steps):
+        xd = _cuda(x_or.astype(np.float32))
+        x_start = xd.cpu().numpy().astype(np.float64)
+        x_or, _ = sampler.sample_step(x_start, lab, i, int(tt[i]), at[i], ap[i], model, w, lin, cache, 2, cfg, K[i], mask[i])
+        ctx.sample_step(xd, ld, i, int(tt[i]), float(at[i]), float(ap[i]), cfg, Kd[i])
+        got = xd.cpu().numpy()
+        ma, rr = max_abs(got, x_or), rel_rms(got, x_or)
+        assert ma <= 1e-2 and rr <= 1e-3, "%s step %d: max-abs %.2e rel-RMS %.2e" % (name, i, ma, rr)
+        worst = (max(worst[0], ma), max(worst[1], rr))
+    print(name, "per-module schedule, teacher-forced: worst max-abs %.2e rel-RMS %.2e" % worst)
+    # whole loop: qc_sample under the schedule equals the per-step calls bit for bit
+    xa, xb = _cuda(lat), _cuda(lat)
+    ctx.sample(xa, ld, steps, cfg, Kd)
+    for i in range(steps):
+        ctx.sample_step(xb, ld, i, int(tt[i]), float(at[i]), float(ap[i]), cfg, Kd[i])
+    torch.cuda.synchronize()
+    assert torch.equal(xa, xb)
+    # more steps than the schedule holds is an error, and so is reusing a module that was never stored
+    with pytest.raises(Exception):
+        ctx.sample(xa, ld, steps + 1, cfg, Kd)
+    ctx.close()
+
+
+def test_schedule_written_from_the_interval_rule_is_the_interval_sampler():
+    import torch
+    model, B, steps, N = TINY, 3, 10, 3
+    w = I.make_weights(model, 81, std=0.15)
+    tt, _, _ = sampler.ddim_schedule(steps)
+    clat = np.concatenate([I.make_latents(1, model, 4000 + i) for i in range(4)])
+    qp, _, _ = oracle_calibration(model, w, lat=clat, lab=I.make_labels(4, model, 82), t=tt[[0, 3, 6, 9]])
+    _, ctx = make_pair(model, w, qp, B, N)
+    lat, lab = _cuda(I.make_latents(B, model, 83)), _cuda(I.make_labels(B, model, 84).astype(np.int32))
+    K = _cuda(I.make_vc_factors(steps, model.latent_c, 85))
+    xa, xb = lat.clone(), lat.clone()
+    ctx.sample(xa, lab, steps, 0.0, K)
+    mask = np.zeros((steps, model.depth, 2), np.uint8)
+    mask[::N] = 1
+    ctx.set_cache_mask(mask)
+    ctx.sample(xb, lab, steps, 0.0, K)
+    torch.cuda.synchronize()
+    assert torch.equal(xa, xb)
+    ctx.set_cache_mask(None)
+    ctx.close()
+
+
 def test_calibration_matches_oracle():
     """qc_calibrate_minmax (fp32 un-quantised forward on the device) against the oracle's calibration."""
     import torch

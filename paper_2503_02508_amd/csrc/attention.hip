@@ -208,7 +208,7 @@ __device__ __forceinline__ void unpack_pairs(v4u p, v2u &hi, v2u &lo) {
 }
 
 template <int NCH, int NEB>   // feature chunks of 32 (operand width), feature blocks of 16 that hold real features
-__global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__restrict__ Qp, const unsigned *__restrict__ Kp,
+__global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *__restrict__ Qp, const unsigned *__restrict__ Kp,
                                                             const _Float16 *__restrict__ Vh, const _Float16 *__restrict__ Vl, int T,
                                                             int Tp, int H, int hd, int DPv, const QParam *qp,
                                                             int8_t *__restrict__ q_out) {
@@ -242,38 +242,36 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
 
   v4u kreg[KCH];
   v4u vreg[2][VCH];
-  // key row and feature offset of this thread's K chunks (the same for every tile: no divisions in the loop)
+  // key row and feature offset of this thread's K chunks (the same for every tile: no divisions in the loop).
+  // Loads never branch: a chunk index beyond the tile is clamped to the last chunk and a key beyond T to key
+  // T-1 (finite values that the ragged-tile mask or the store predicate discards), so that all loads of a tile
+  // are issued back to back and nothing waits in between.
   int kr[KCH], kc[KCH];
+  bool kvalid[KCH];
 #pragma unroll
   for (int u = 0; u < KCH; ++u) {
     const int i = tid + 256 * u;
-    kr[u] = i < kchunks ? i / (hd / 4) : -1;
-    kc[u] = (i % (hd / 4)) * 4;
+    kvalid[u] = i < kchunks;
+    const int ic = min(i, kchunks - 1);
+    kr[u] = ic / (hd / 4);
+    kc[u] = (ic % (hd / 4)) * 4;
   }
   auto load_tile = [&](int k0) {
 #pragma unroll
-    for (int u = 0; u < KCH; ++u) {
-      v4u v = {0, 0, 0, 0};
-      if (kr[u] >= 0 && k0 + kr[u] < T) v = *(const v4u *)(Kp + tok_base + (long long)(k0 + kr[u]) * hd + kc[u]);
-      kreg[u] = v;
-    }
+    for (int u = 0; u < KCH; ++u)
+      kreg[u] = *(const v4u *)(Kp + tok_base + (long long)min(k0 + kr[u], T - 1) * hd + kc[u]);
 #pragma unroll
     for (int u = 0; u < VCH; ++u) {
-      const int i = tid + 256 * u;
+      const int i = min(tid + 256 * u, NEB * 16 * 8 - 1);
       const int e = i >> 3, c8 = (i & 7) * 8;
-      v4u a = {0, 0, 0, 0}, bq = a;
-      if (i < NEB * 16 * 8) {
-        a = *(const v4u *)(Vh + vt_base + (long long)e * Tp + k0 + c8);
-        bq = *(const v4u *)(Vl + vt_base + (long long)e * Tp + k0 + c8);
-      }
-      vreg[0][u] = a;
-      vreg[1][u] = bq;
+      vreg[0][u] = *(const v4u *)(Vh + vt_base + (long long)e * Tp + k0 + c8);
+      vreg[1][u] = *(const v4u *)(Vl + vt_base + (long long)e * Tp + k0 + c8);
     }
   };
   auto store_tile = [&]() {
 #pragma unroll
     for (int u = 0; u < KCH; ++u) {
-      if (kr[u] >= 0) {
+      if (kvalid[u]) {
         v2u hi, lo;
         unpack_pairs(kreg[u], hi, lo);
         *(v2u *)(Ksh[0] + kr[u] * KROW + kc[u]) = hi;
@@ -294,22 +292,35 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
   load_tile(0);                            // first key tile and the queries are in flight together
   int q_row[2];
   v8h qh[2][NCH], qlo[2][NCH];
+  {
+    // all query loads are issued before any is used; rows beyond T read row T-1 (their results are never
+    // stored), features beyond d read the last chunk and are zeroed below
+    v4u qraw[2][NCH][2];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    q_row[j] = blockIdx.y * 128 + wave * 32 + j * 16 + ql;
+    for (int j = 0; j < 2; ++j) {
+      q_row[j] = blockIdx.y * 128 + wave * 32 + j * 16 + ql;
+      const unsigned *src = Qp + tok_base + (long long)min(q_row[j], T - 1) * hd;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-      v2u h0 = {0, 0}, l0 = {0, 0}, h1 = {0, 0}, l1 = {0, 0};
-      const int f = 32 * c + 8 * g;
-      if (q_row[j] < T) {
-        const unsigned *src = Qp + tok_base + (long long)q_row[j] * hd + f;
-        if (f < hd) unpack_pairs(*(const v4u *)src, h0, l0);
-        if (f + 4 < hd) unpack_pairs(*(const v4u *)(src + 4), h1, l1);
+      for (int c = 0; c < NCH; ++c) {
+        const int f = 32 * c + 8 * g;
+        qraw[j][c][0] = *(const v4u *)(src + min(f, hd - 4));
+        qraw[j][c][1] = *(const v4u *)(src + min(f + 4, hd - 4));
       }
-      v4u hh = {h0.x, h0.y, h1.x, h1.y}, ll = {l0.x, l0.y, l1.x, l1.y};
-      qh[j][c] = *(v8h *)&hh;
-      qlo[j][c] = *(v8h *)&ll;
     }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int f = 32 * c + 8 * g;
+        v2u h0, l0, h1, l1;
+        unpack_pairs(qraw[j][c][0], h0, l0);
+        unpack_pairs(qraw[j][c][1], h1, l1);
+        if (f >= hd) { h0 = (v2u){0, 0}; l0 = h0; }
+        if (f + 4 >= hd) { h1 = (v2u){0, 0}; l1 = h1; }
+        v4u hh = {h0.x, h0.y, h1.x, h1.y}, ll = {l0.x, l0.y, l1.x, l1.y};
+        qh[j][c] = *(v8h *)&hh;
+        qlo[j][c] = *(v8h *)&ll;
+      }
   }
   for (int k0 = 0; k0 < T; k0 += 64) {
     __syncthreads();                       // everyone is done with the previous tile
@@ -317,24 +328,49 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
     __syncthreads();
     if (k0 + 64 < T) load_tile(k0 + 64);   // in flight during the MFMAs below
 
+    // S^T = K Q^T: the K fragments run two iterations ahead of the MFMAs that use them (LDS latency is
+    // several MFMA groups long and a wavefront is alone on its SIMD)
     v4f s[2][4];
+    constexpr int NS = 4 * NCH;
+    v8h kfh[3], kfl[3];
+    auto load_k = [&](int it, int slot) {
+      const int kt = it / NCH, c = it % NCH;
+      kfh[slot] = *(const v8h *)(Ksh[0] + (kt * 16 + ql) * KROW + 32 * c + 8 * g);
+      kfl[slot] = *(const v8h *)(Ksh[1] + (kt * 16 + ql) * KROW + 32 * c + 8 * g);
+    };
+    load_k(0, 0);
+    load_k(1, 1);
+    v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
-      v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
-#pragma unroll
-      for (int c = 0; c < NCH; ++c) {
-        const v8h kh = *(const v8h *)(Ksh[0] + (kt * 16 + ql) * KROW + 32 * c + 8 * g);
-        const v8h kl = *(const v8h *)(Ksh[1] + (kt * 16 + ql) * KROW + 32 * c + 8 * g);
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[0][c], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[1][c], acc1, 0, 0, 0);
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[0][c], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[1][c], acc1, 0, 0, 0);
-        acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[0][c], acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[1][c], acc1, 0, 0, 0);
+    for (int it = 0; it < NS; ++it) {
+      const int kt = it / NCH, c = it % NCH, slot = it % 3;
+      if (it + 2 < NS) load_k(it + 2, (it + 2) % 3);
+      __builtin_amdgcn_sched_barrier(0);
+      const v8h kh = kfh[slot], kl = kfl[slot];
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[0][c], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[1][c], acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[0][c], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[1][c], acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[0][c], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[1][c], acc1, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (c == NCH - 1) {
+        s[0][kt] = acc0;
+        s[1][kt] = acc1;
+        acc0 = (v4f){0.f, 0.f, 0.f, 0.f};
+        acc1 = acc0;
       }
-      s[0][kt] = acc0;
-      s[1][kt] = acc1;
     }
+    // the first V^T fragments are requested before the softmax arithmetic, which hides their latency
+    constexpr int NP = 2 * NEB;
+    v8h vfh[3], vfl[3];
+    auto load_v = [&](int it, int slot) {
+      const int a = it / NEB, e = it % NEB;
+      vfh[slot] = *(const v8h *)(Vsh[0] + (e * 16 + ql) * VROW + 32 * a + 8 * g);
+      vfl[slot] = *(const v8h *)(Vsh[1] + (e * 16 + ql) * VROW + 32 * a + 8 * g);
+    };
+    load_v(0, 0);
+    load_v(1, 1);
     v8h ph[2][2], pl[2][2];
     const bool ragged_tile = k0 + 64 > T;
 #pragma unroll
@@ -367,18 +403,20 @@ __global__ __launch_bounds__(256) void attention_f16_kernel(const unsigned *__re
         }
     }
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int e = 0; e < NEB; ++e) {
-        const v8h vh = *(const v8h *)(Vsh[0] + (e * 16 + ql) * VROW + 32 * a + 8 * g);
-        const v8h vl = *(const v8h *)(Vsh[1] + (e * 16 + ql) * VROW + 32 * a + 8 * g);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, ph[j][a], o[j][e], 0, 0, 0);
-          o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[j][a], o[j][e], 0, 0, 0);
-          o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[j][a], o[j][e], 0, 0, 0);
-        }
-      }
+    for (int it = 0; it < NP; ++it) {
+      const int a = it / NEB, e = it % NEB, slot = it % 3;
+      if (it + 2 < NP) load_v(it + 2, (it + 2) % 3);
+      __builtin_amdgcn_sched_barrier(0);
+      const v8h vh = vfh[slot], vl = vfl[slot];
+      // the two query blocks alternate so that consecutive MFMAs never wait on each other's result
+      o[0][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, ph[0][a], o[0][e], 0, 0, 0);
+      o[1][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, ph[1][a], o[1][e], 0, 0, 0);
+      o[0][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[0][a], o[0][e], 0, 0, 0);
+      o[1][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[1][a], o[1][e], 0, 0, 0);
+      o[0][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[0][a], o[0][e], 0, 0, 0);
+      o[1][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[1][a], o[1][e], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
 
   const QParam t = *qp;

@@ -114,52 +114,44 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // error they seed in every later layer) at the floor.
 // One workgroup (4 wavefronts) per token row: short per-thread work and 8 wavefronts per SIMD keep the
 // two memory round trips (row in, codes out) and the fp64 arithmetic of different rows overlapped.
-__global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restrict__ x, const float *__restrict__ shift,
+__global__ __launch_bounds__(512) void ln_mod_quant_kernel(const float *__restrict__ x, const float *__restrict__ shift,
                                                            const float *__restrict__ scale, int ld_mod, int M, int D, int T,
                                                            const QParam *qp, int8_t *__restrict__ q,
                                                            float *__restrict__ f32_out) {
-  constexpr int IT = 2;                      // D <= 2048: at most two float4 per thread
-  __shared__ double red[8];
+  // one float4 per thread (the launch sizes the workgroup to D / 4 rounded up to whole wavefronts, D <= 2048):
+  // every load of the row and of its modulation vectors is issued at once, one memory round trip
+  __shared__ double red[16];
   const int m = blockIdx.x;
-  const float *row = x + (size_t)m * D;
   const int b = m / T;
-  const float *sh = shift + (size_t)b * ld_mod, *sc = scale + (size_t)b * ld_mod;
-  float4 v[IT], s4[IT], c4[IT];
-  double sum = 0.0;
-#pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int k = (threadIdx.x + 256 * it) * 4;
-    if (k < D) {
-      v[it] = *(const float4 *)(row + k);
-      s4[it] = *(const float4 *)(sh + k);      // issued together with the row: one memory round trip
-      c4[it] = *(const float4 *)(sc + k);
-    }
-  }
-#pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int k = (threadIdx.x + 256 * it) * 4;
-    if (k < D) sum += ((double)v[it].x + (double)v[it].y) + ((double)v[it].z + (double)v[it].w);
+  const int k = threadIdx.x * 4;
+  const bool live = k < D;
+  const int kc = live ? k : 0;
+  const float4 v = *(const float4 *)(x + (size_t)m * D + kc);
+  const float4 s4 = *(const float4 *)(shift + (size_t)b * ld_mod + kc);
+  const float4 c4 = *(const float4 *)(scale + (size_t)b * ld_mod + kc);
+  double sum = 0.0, sq = 0.0;
+  if (live) {
+    const double a = v.x, bq = v.y, c = v.z, d = v.w;
+    sum = (a + bq) + (c + d);
+    sq = (a * a + bq * bq) + (c * c + d * d);
   }
   // mean and variance from one reduction of (sum, sum of squares): in fp64 the cancellation in
   // E[x^2] - mean^2 costs ~1e-13 relative for rows of O(1) values, far below the fp32 rounding of the result
-  double sq = 0.0;
-#pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int k = (threadIdx.x + 256 * it) * 4;
-    if (k < D) {
-      const double a = v[it].x, bq = v[it].y, c = v[it].z, d = v[it].w;
-      sq += (a * a + bq * bq) + (c * c + d * d);
-    }
-  }
   sum = wave_sum_d(sum);
   sq = wave_sum_d(sq);
+  const int nw = blockDim.x >> 6;
   if ((threadIdx.x & 63) == 0) {
     red[threadIdx.x >> 6] = sum;
-    red[4 + (threadIdx.x >> 6)] = sq;
+    red[8 + (threadIdx.x >> 6)] = sq;
   }
   __syncthreads();
-  const double mean = ((red[0] + red[1]) + (red[2] + red[3])) / (double)D;
-  const double var = ((red[4] + red[5]) + (red[6] + red[7])) / (double)D - mean * mean;
+  double tot = 0.0, tot2 = 0.0;
+  for (int w = 0; w < nw; ++w) {
+    tot += red[w];
+    tot2 += red[8 + w];
+  }
+  const double mean = tot / (double)D;
+  const double var = tot2 / (double)D - mean * mean;
   const double rstd = 1.0 / sqrt(fmax(var, 0.0) + 1e-6);
   float qs = 1.0f;
   int qz = 0;
@@ -168,25 +160,22 @@ __global__ __launch_bounds__(256) void ln_mod_quant_kernel(const float *__restri
     qs = t.s;
     qz = t.z;
   }
-#pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int k = (threadIdx.x + 256 * it) * 4;
-    if (k < D) {
-      const float h0 = (float)((v[it].x - mean) * rstd * (1.0 + (double)c4[it].x) + (double)s4[it].x);
-      const float h1 = (float)((v[it].y - mean) * rstd * (1.0 + (double)c4[it].y) + (double)s4[it].y);
-      const float h2 = (float)((v[it].z - mean) * rstd * (1.0 + (double)c4[it].z) + (double)s4[it].z);
-      const float h3 = (float)((v[it].w - mean) * rstd * (1.0 + (double)c4[it].w) + (double)s4[it].w);
-      if (q)
-        *(unsigned *)(q + (size_t)m * D + k) =
-            pack4(quant_code(h0, qs, qz), quant_code(h1, qs, qz), quant_code(h2, qs, qz), quant_code(h3, qs, qz));
-      if (f32_out) *(float4 *)(f32_out + (size_t)m * D + k) = make_float4(h0, h1, h2, h3);
-    }
-  }
+  if (!live) return;
+  const float h0 = (float)((v.x - mean) * rstd * (1.0 + (double)c4.x) + (double)s4.x);
+  const float h1 = (float)((v.y - mean) * rstd * (1.0 + (double)c4.y) + (double)s4.y);
+  const float h2 = (float)((v.z - mean) * rstd * (1.0 + (double)c4.z) + (double)s4.z);
+  const float h3 = (float)((v.w - mean) * rstd * (1.0 + (double)c4.w) + (double)s4.w);
+  if (q)
+    *(unsigned *)(q + (size_t)m * D + k) =
+        pack4(quant_code(h0, qs, qz), quant_code(h1, qs, qz), quant_code(h2, qs, qz), quant_code(h3, qs, qz));
+  if (f32_out) *(float4 *)(f32_out + (size_t)m * D + k) = make_float4(h0, h1, h2, h3);
 }
 
 hipError_t launch_ln_mod_quant(const float *x, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
                                const QParam *qp, int8_t *q, float *f32_out, hipStream_t st) {
-  hipLaunchKernelGGL(ln_mod_quant_kernel, dim3(M), dim3(256), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q, f32_out);
+  const int threads = ((D / 4 + 63) / 64) * 64;
+  if (D % 4 || threads > 512) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(ln_mod_quant_kernel, dim3(M), dim3(threads), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q, f32_out);
   return hipGetLastError();
 }
 
@@ -305,8 +294,29 @@ __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x,
   __syncthreads();
   for (int n = threadIdx.x; n < D; n += blockDim.x) {
     float acc = 0.0f;
-    for (int f = 0; f < F; ++f) acc = fmaf(pw[(size_t)n * F + f], patch[f], acc);
-    tok[(size_t)bt * D + n] = acc + pb[n] + pos[(size_t)t * D + n];
+    const float bias = pb[n], pe = pos[(size_t)t * D + n];
+    if (F % 4 == 0) {
+      // sixteen weights per round trip; the sum keeps the feature order
+      const float *wr = pw + (size_t)n * F;
+      for (int f0 = 0; f0 < F; f0 += 16) {
+        float4 w4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) w4[u] = *(const float4 *)(wr + min(f0 + 4 * u, F - 4));
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int f = f0 + 4 * u;
+          if (f < F) {
+            acc = fmaf(w4[u].x, patch[f], acc);
+            acc = fmaf(w4[u].y, patch[f + 1], acc);
+            acc = fmaf(w4[u].z, patch[f + 2], acc);
+            acc = fmaf(w4[u].w, patch[f + 3], acc);
+          }
+        }
+      }
+    } else {
+      for (int f = 0; f < F; ++f) acc = fmaf(pw[(size_t)n * F + f], patch[f], acc);
+    }
+    tok[(size_t)bt * D + n] = acc + bias + pe;
   }
 }
 
@@ -330,37 +340,40 @@ __global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ to
   const int gw = W / p, T = (H / p) * gw;
   const int b = m / T, t = m % T, ty = t / gw, tx = t % gw;
   const float *row = tok + (size_t)m * D;
-  float4 v[LN_MAX_IT];
-  float sum = 0.0f;
+  const float *sh = fmod + (size_t)b * 2 * D, *sc = sh + D;
+  // loads never branch (chunks beyond D re-read the last chunk and are zeroed): the row and its modulation
+  // vectors arrive in one memory round trip
+  float4 v[LN_MAX_IT], s4[LN_MAX_IT], c4[LN_MAX_IT];
+  int kk[LN_MAX_IT];
 #pragma unroll
   for (int it = 0; it < LN_MAX_IT; ++it) {
-    const int k = (lane + 64 * it) * 4;
-    if (k < D) {
-      v[it] = *(const float4 *)(row + k);
-      sum += (v[it].x + v[it].y) + (v[it].z + v[it].w);
-    }
+    kk[it] = min((lane + 64 * it) * 4, D - 4);
+    v[it] = *(const float4 *)(row + kk[it]);
+    s4[it] = *(const float4 *)(sh + kk[it]);
+    c4[it] = *(const float4 *)(sc + kk[it]);
   }
+  float sum = 0.0f;
+#pragma unroll
+  for (int it = 0; it < LN_MAX_IT; ++it)
+    if ((lane + 64 * it) * 4 < D) sum += (v[it].x + v[it].y) + (v[it].z + v[it].w);
   const float mean = wave_sum(sum) / (float)D;
   float sq = 0.0f;
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it) {
-    const int k = (lane + 64 * it) * 4;
-    if (k < D) {
+  for (int it = 0; it < LN_MAX_IT; ++it)
+    if ((lane + 64 * it) * 4 < D) {
       float a = v[it].x - mean, bq = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
       sq += (a * a + bq * bq) + (c * c + d * d);
     }
-  }
   const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + 1e-6f);
-  const float *sh = fmod + (size_t)b * 2 * D, *sc = sh + D;
 #pragma unroll
   for (int it = 0; it < LN_MAX_IT; ++it) {
-    const int k = (lane + 64 * it) * 4;
-    if (k < D) {
-      float4 s4 = *(const float4 *)(sh + k), c4 = *(const float4 *)(sc + k);
-      v[it].x = (v[it].x - mean) * rstd * (1.0f + c4.x) + s4.x;
-      v[it].y = (v[it].y - mean) * rstd * (1.0f + c4.y) + s4.y;
-      v[it].z = (v[it].z - mean) * rstd * (1.0f + c4.z) + s4.z;
-      v[it].w = (v[it].w - mean) * rstd * (1.0f + c4.w) + s4.w;
+    if ((lane + 64 * it) * 4 < D) {
+      v[it].x = (v[it].x - mean) * rstd * (1.0f + c4[it].x) + s4[it].x;
+      v[it].y = (v[it].y - mean) * rstd * (1.0f + c4[it].y) + s4[it].y;
+      v[it].z = (v[it].z - mean) * rstd * (1.0f + c4[it].z) + s4[it].z;
+      v[it].w = (v[it].w - mean) * rstd * (1.0f + c4[it].w) + s4[it].w;
+    } else {
+      v[it] = make_float4(0.f, 0.f, 0.f, 0.f);      // contributes nothing to the dot products below
     }
   }
   // the p*p*C dot products of this row, 16 at a time: per-lane partial sums, then a butterfly that halves
@@ -376,11 +389,8 @@ __global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ to
         const float *wr = fw + (size_t)((oi / C) * 2 * C + oi % C) * D;
 #pragma unroll
         for (int it = 0; it < LN_MAX_IT; ++it) {
-          const int k = (lane + 64 * it) * 4;
-          if (k < D) {
-            float4 w4 = *(const float4 *)(wr + k);
-            part[u] += (v[it].x * w4.x + v[it].y * w4.y) + (v[it].z * w4.z + v[it].w * w4.w);
-          }
+          const float4 w4 = *(const float4 *)(wr + kk[it]);
+          part[u] += (v[it].x * w4.x + v[it].y * w4.y) + (v[it].z * w4.z + v[it].w * w4.w);
         }
       }
     }
@@ -465,13 +475,32 @@ __global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ 
   if (i >= n4) return;
   const int b = (int)(i / TD4), n = (int)(i % D4) * 4;
   float4 xv = ((float4 *)x)[i];
-  for (int l = 0; l < L; ++l) {
+  auto apply = [&](const float4 &g1, const float4 &a, const float4 &g2, const float4 &mo) {
+    xv.x = xv.x + g1.x * a.x; xv.y = xv.y + g1.y * a.y; xv.z = xv.z + g1.z * a.z; xv.w = xv.w + g1.w * a.w;
+    xv.x = xv.x + g2.x * mo.x; xv.y = xv.y + g2.y * mo.y; xv.z = xv.z + g2.z * mo.z; xv.w = xv.w + g2.w * mo.w;
+  };
+  // the loads of four blocks are in flight together; the additions keep the block order
+  constexpr int U = 4;
+  int l = 0;
+  for (; l + U <= L; l += U) {
+    float4 g1[U], g2[U], a[U], mo[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float *mrow = mod + (size_t)(l + u) * mod_block_stride + (size_t)b * ld_mod + n;
+      g1[u] = *(const float4 *)(mrow + 2 * D);
+      g2[u] = *(const float4 *)(mrow + 5 * D);
+      a[u] = ((const float4 *)(cache + (size_t)(l + u) * cache_block_stride))[i];
+      mo[u] = ((const float4 *)(cache + (size_t)(l + u) * cache_block_stride + cache_which_stride))[i];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) apply(g1[u], a[u], g2[u], mo[u]);
+  }
+  for (; l < L; ++l) {
     const float *mrow = mod + (size_t)l * mod_block_stride + (size_t)b * ld_mod + n;
     const float4 g1 = *(const float4 *)(mrow + 2 * D), g2 = *(const float4 *)(mrow + 5 * D);
     const float4 a = ((const float4 *)(cache + (size_t)l * cache_block_stride))[i];
     const float4 mo = ((const float4 *)(cache + (size_t)l * cache_block_stride + cache_which_stride))[i];
-    xv.x = xv.x + g1.x * a.x; xv.y = xv.y + g1.y * a.y; xv.z = xv.z + g1.z * a.z; xv.w = xv.w + g1.w * a.w;
-    xv.x = xv.x + g2.x * mo.x; xv.y = xv.y + g2.y * mo.y; xv.z = xv.z + g2.z * mo.z; xv.w = xv.w + g2.w * mo.w;
+    apply(g1, a, g2, mo);
   }
   ((float4 *)x)[i] = xv;
 }

@@ -661,12 +661,15 @@ static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
     case 4: return launch_cfg<128, 128, 2, 4, EPI, TAG, W4, 3>(a, nz, st);
     default: break;
   }
-  // Large problems: 256x256 tiles on 8 wavefronts (256 ops per byte fetched from L2, the
-  // bandwidth that bounds this kernel); small ones: 128x128 tiles, more workgroups in flight.
-  if ((long long)a.M * a.N >= (long long)8192 * 1152) return launch_cfg<256, 256, 2, 4, EPI, TAG, W4, 2>(a, nz, st);
   // Fewer tiles than compute units: a workgroup is alone on its CU and a single wavefront per SIMD cannot
   // keep the LDS and memory pipes busy (they are issue-bound per wavefront), so the tile is shared by 8.
-  if (((a.M + 127) / 128) * ((a.N + 127) / 128) <= 256) return launch_cfg<128, 128, 2, 4, EPI, TAG, W4, 3>(a, nz, st);
+  // The residual epilogue keeps a tile of x in registers, which would leave the 4-wavefront variant one
+  // workgroup per CU: it always runs on 8.
+  if (EPI == EPI_RESID || ((a.M + 127) / 128) * ((a.N + 127) / 128) <= 256)
+    return launch_cfg<128, 128, 2, 4, EPI, TAG, W4, 3>(a, nz, st);
+  // Otherwise 4 wavefronts per tile and two workgroups per compute unit.  (256x256 tiles on 8 wavefronts halve
+  // the L2 traffic per operation but measured no faster at M = 32768 and slower below, and their QKV
+  // epilogue does not fit the register file: they stay selectable for tuning only.)
   return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
 }
 

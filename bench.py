@@ -29,11 +29,11 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak (published), GB/s
 # under profiles/, keyed by (workload, kernel class).  None where no counter run covers the pair.
 TRAFFIC = {
     # profiles/sampler_cfg1_dit_xl2_b8_hbm_traffic.txt: (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB per dispatch
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc2"): (17407.9 * 2.0 + 9216.0) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_qkv"): (6322.9 * 2.0 + 13827.8) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc1"): (7678.0 * 2.0 + 4608.0) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_proj"): (6170.6 * 2.0 + 9216.0) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "attention"): (12175.0 * 2.0 + 1536.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc2"): (17403.1 * 2.0 + 9216.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_qkv"): (6324.8 * 2.0 + 13831.1) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc1"): (7676.6 * 2.0 + 4608.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_proj"): (6164.1 * 2.0 + 9216.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "attention"): (7283.5 * 2.0 + 1536.0) * 1024,
 }
 
 
@@ -169,9 +169,8 @@ def main():
             "ln_mod_quant": ("hbm", 5.0 * MT * D * 2 * per_pass),
             # both cached tensors of every block read once, the residual stream read and written once
             "cached_blocks": ("hbm", (2.0 * m.depth + 2.0) * MT * D * 4 * (wl.steps - n_full)),
-            # int8 weights of the gate projections (cached steps) or all six chunks (refresh steps), read once
-            "gemm_adaln": ("hbm", m.depth * D * D * (6.0 * n_full + 2.0 * (wl.steps - n_full))
-                           * (0.5 if m.weight_bits == 4 else 1.0)),
+            # all steps' adaLN projections of every block in one launch per window of steps
+            "gemm_adaln": ("mfma", 2.0 * wl.steps * Beff * 6 * D * D * m.depth),
         }
         peaks = {"mfma": (INT8_MFMA_PEAK_TOPS, "TOP/s"), "mfma16": (FP16_MFMA_PEAK_TFLOPS, "TFLOP/s"),
                  "hbm": (HBM_PEAK_GBS, "GB/s")}

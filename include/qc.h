@@ -19,6 +19,12 @@
  *   - the library never allocates device memory: everything a context needs
  *     lives in one caller-provided arena.
  *   - argument checks run before any device call.
+ *   - a context is not thread-safe: calls on one context must not overlap, and
+ *     work enqueued through one context on different streams must be ordered by
+ *     the caller (the context owns one workspace).  The denoiser entry points
+ *     may run parts of a call on internal streams of the context; these fork
+ *     from and join back into `stream`, so the caller only ever orders against
+ *     `stream`.  Different contexts are independent.
  */
 #ifndef QC_H_
 #define QC_H_
@@ -51,8 +57,9 @@ enum {                                               /* qc_workspace_ptr selecto
   QC_WS_QACT_ATTN = 2,/* int8   [B*T, D]   codes of the last attention output              */
   QC_WS_QACT_MLP = 3, /* int8   [B*T, R]   codes of the last GELU output                    */
   QC_WS_QKV = 4,      /* float  [B*T, 3D]  last QKV projection (only with qc_keep_qkv_f32)          */
-  QC_WS_MOD = 5,      /* float  [L, B, 6D] adaLN modulation of every block                  */
-  QC_WS_COND = 6,     /* float  [B, D]     conditioning vector c                            */
+  QC_WS_MOD = 5,      /* float  [L, R, 6D] adaLN modulation of every block; R = max(512, max_batch) rows,
+                         row = step slot of the prepared window * batch + batch element           */
+  QC_WS_COND = 6,     /* float  [R, D]     conditioning vectors c, same rows                        */
   QC_WS_EPS = 7       /* float  [B, C, H, W] last noise estimate                            */
 };
 

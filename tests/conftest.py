@@ -10,6 +10,15 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; only when there is none do they build it (hipcc cross-compiles
+    # without a GPU)
+    lib = os.path.join(ROOT, "paper_2503_02508_amd", "libqc.so")
+    if not os.path.exists(lib):
+        import importlib.util
+        spec = importlib.util.spec_from_file_location("qc_build", os.path.join(ROOT, "paper_2503_02508_amd", "build.py"))
+        b = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(b)
+        b.build()
 
 
 def _have_gpu():

@@ -169,6 +169,8 @@ def main():
             "ln_mod_quant": ("hbm", 5.0 * MT * D * 2 * per_pass),
             # both cached tensors of every block read once, the residual stream read and written once
             "cached_blocks": ("hbm", (2.0 * m.depth + 2.0) * MT * D * 4 * (wl.steps - n_full)),
+            # sample and noise estimate(s) read, sample written; one launch per step
+            "ddim_vc": ("hbm", (4.0 * (B + Beff) + 4.0 * B) * m.latent_c * m.latent_h * m.latent_w * wl.steps),
             # all steps' adaLN projections of every block in one launch per window of steps
             "gemm_adaln": ("mfma", 2.0 * wl.steps * Beff * 6 * D * D * m.depth),
         }

@@ -275,7 +275,8 @@ enum {
   QC_K_GEMM_FC1 = 5,       /* fc1 GEMM + GELU + requantise                                */
   QC_K_GEMM_FC2 = 6,       /* fc2 GEMM + cache store + gated residual                    */
   QC_K_CACHED_BLOCKS = 7,  /* all blocks of a cached step                                 */
-  QC_K_COUNT = 8
+  QC_K_DDIM_VC = 8,        /* guidance + solver update + VC                               */
+  QC_K_COUNT = 9
 };
 
 /* Between qc_profile_begin and qc_profile_end every launch of the classes above

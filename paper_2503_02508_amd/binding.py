@@ -74,7 +74,7 @@ _SIGS = {
     "qc_profile_end": (i32, [vp, i32, C.POINTER(C.c_int32), C.POINTER(f32), vp]),
 }
 KERNEL_CLASSES = ("gemm_adaln", "ln_mod_quant", "gemm_qkv", "attention", "gemm_proj", "gemm_fc1", "gemm_fc2",
-                  "cached_blocks")
+                  "cached_blocks", "ddim_vc")
 for _n, (_r, _a) in _SIGS.items():
     _f = getattr(lib, _n)
     _f.restype, _f.argtypes = _r, _a

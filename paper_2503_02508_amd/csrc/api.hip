@@ -820,6 +820,7 @@ static int sample_step_prepared(qc_ctx *ctx, float *x, int B, int mode, int w, d
   if (rc) return rc;
   const double cx = std::sqrt(abar_prev / abar_t);
   const double ce = std::sqrt(1.0 - abar_prev) - cx * std::sqrt(1.0 - abar_t);
+  QC_PROF(QC_K_DDIM_VC);
   QC_HIP(launch_ddim_vc(x, ctx->eps, B, ctx->C, ctx->d.latent_h * ctx->d.latent_w, (float)cx, (float)ce, cfg_scale, K_t, st));
   return QC_OK;
 }

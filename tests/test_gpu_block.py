@@ -20,6 +20,11 @@ TINY = I.ModelDesc(depth=2, hidden=32, heads=2, mlp_dim=64, patch=2, latent_c=4,
 # ragged everywhere: 35 tokens (not a multiple of the 64-key tile), head dim 20, hidden 80
 RAGGED = I.ModelDesc(depth=2, hidden=80, heads=4, mlp_dim=176, patch=1, latent_c=3, latent_h=5, latent_w=7,
                      num_classes=7)
+# the limits of the kernels: widest hidden size the row kernels cover (2048) and largest head dimension (80)
+WIDEST = I.ModelDesc(depth=1, hidden=2048, heads=32, mlp_dim=2304, patch=1, latent_c=4, latent_h=6, latent_w=7,
+                     num_classes=5)
+HEAD80 = I.ModelDesc(depth=1, hidden=320, heads=4, mlp_dim=640, patch=2, latent_c=4, latent_h=12, latent_w=10,
+                     num_classes=5)
 MAX_FLIP_FRACTION = 1e-2
 # Module outputs inside a block (the cached tensors) sit behind one or two more
 # quantisers than the block input; a flipped code upstream shifts a whole row of
@@ -88,6 +93,8 @@ def _block_case(model, seed, B, std=0.02, wb=8):
     ("tiny", TINY, 2, 8),
     ("ragged", RAGGED, 3, 8),
     ("ragged_w4", RAGGED, 3, 4),
+    ("widest_hidden_2048", WIDEST, 2, 8),
+    ("head_dim_80", HEAD80, 2, 8),
 ])
 def test_block_full_and_cached_parity(name, model, B, wb):
     std = 0.02 if model.hidden >= 384 else 0.15

@@ -24,7 +24,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from .quant import QLinear, lin_q
+from .quant import QLinear, lin_q, bf16_round
 
 SITES = ("ada", "qkv", "proj", "fc1", "fc2")
 F64 = np.float64
@@ -108,9 +108,11 @@ def block_mod(c, blk: int, linear):
     return np.split(mod, 6, axis=1)
 
 
-def block_full(x, c, blk: int, heads: int, linear, cache: dict | None = None, tap: dict | None = None):
+def block_full(x, c, blk: int, heads: int, linear, cache: dict | None = None, tap: dict | None = None,
+               cache_bf16: bool = False):
     """One adaLN-Zero DiT block, fully computed; stores the attention and MLP
-    module outputs into `cache` when given."""
+    module outputs into `cache` when given (rounded to bfloat16 storage with
+    cache_bf16; the block itself always uses the exact module outputs)."""
     B, T, D = x.shape
     shift_msa, scale_msa, gate_msa, shift_mlp, scale_mlp, gate_mlp = block_mod(c, blk, linear)
     h = modulate(layer_norm(x), shift_msa, scale_msa)
@@ -124,8 +126,8 @@ def block_full(x, c, blk: int, heads: int, linear, cache: dict | None = None, ta
     Mo = linear(blk, "fc2", g).reshape(B, T, D)
     x = x + gate_mlp[:, None, :] * Mo
     if cache is not None:
-        cache[(blk, "attn")] = A
-        cache[(blk, "mlp")] = Mo
+        cache[(blk, "attn")] = bf16_round(A) if cache_bf16 else A
+        cache[(blk, "mlp")] = bf16_round(Mo) if cache_bf16 else Mo
     if tap is not None:
         tap.update(h=h, qkv=qkv, o=o, A=A, h2=h2, u=u, g=g, Mo=Mo)
     return x
@@ -140,7 +142,8 @@ def block_cached(x, c, blk: int, linear, cache: dict):
     return x
 
 
-def block_mixed(x, c, blk: int, heads: int, linear, cache: dict, attn_full: bool, mlp_full: bool):
+def block_mixed(x, c, blk: int, heads: int, linear, cache: dict, attn_full: bool, mlp_full: bool,
+                cache_bf16: bool = False):
     """A block under a per-module cache schedule (the cache rule of the
     "Quantization and Cache" section applied module by module, as a learned
     layer-caching policy would): each of the two modules is either recomputed,
@@ -152,14 +155,14 @@ def block_mixed(x, c, blk: int, heads: int, linear, cache: dict, attn_full: bool
         h = modulate(layer_norm(x), shift_msa, scale_msa)
         qkv = linear(blk, "qkv", h.reshape(B * T, D)).reshape(B, T, 3 * D)
         A = linear(blk, "proj", attention(qkv, heads).reshape(B * T, D)).reshape(B, T, D)
-        cache[(blk, "attn")] = A
+        cache[(blk, "attn")] = bf16_round(A) if cache_bf16 else A
     else:
         A = cache[(blk, "attn")]
     x = x + gate_msa[:, None, :] * A
     if mlp_full:
         h2 = modulate(layer_norm(x), shift_mlp, scale_mlp)
         Mo = linear(blk, "fc2", gelu_tanh(linear(blk, "fc1", h2.reshape(B * T, D)))).reshape(B, T, D)
-        cache[(blk, "mlp")] = Mo
+        cache[(blk, "mlp")] = bf16_round(Mo) if cache_bf16 else Mo
     else:
         Mo = cache[(blk, "mlp")]
     x = x + gate_mlp[:, None, :] * Mo
@@ -215,7 +218,8 @@ def final_layer(x, c, w: dict, p: int, C: int, H: int, W: int):
     return img[:, :C]
 
 
-def denoiser(x_lat, t, y, desc, w: dict, linear, cache: dict, full: bool, taps: list | None = None):
+def denoiser(x_lat, t, y, desc, w: dict, linear, cache: dict, full: bool, taps: list | None = None,
+             cache_bf16: bool = False):
     """Noise estimate of the network for latents x_lat[B, C, H, W] at timesteps
     t[B] with labels y[B].  `full` = True recomputes every block and refreshes
     the cache, False reuses it in every block; an array [depth, 2] of booleans
@@ -225,7 +229,7 @@ def denoiser(x_lat, t, y, desc, w: dict, linear, cache: dict, full: bool, taps: 
     if not isinstance(full, (bool, np.bool_)):
         sched = np.asarray(full, dtype=bool).reshape(desc.depth, 2)
         for blk in range(desc.depth):
-            x = block_mixed(x, c, blk, desc.heads, linear, cache, bool(sched[blk, 0]), bool(sched[blk, 1]))
+            x = block_mixed(x, c, blk, desc.heads, linear, cache, bool(sched[blk, 0]), bool(sched[blk, 1]), cache_bf16)
         return final_layer(x, c, w, desc.patch, desc.latent_c, desc.latent_h, desc.latent_w)
     for blk in range(desc.depth):
         if full:
@@ -233,7 +237,7 @@ def denoiser(x_lat, t, y, desc, w: dict, linear, cache: dict, full: bool, taps: 
             if taps is not None:
                 tap = {}
                 taps.append(tap)
-            x = block_full(x, c, blk, desc.heads, linear, cache, tap)
+            x = block_full(x, c, blk, desc.heads, linear, cache, tap, cache_bf16)
         else:
             x = block_cached(x, c, blk, linear, cache)
     return final_layer(x, c, w, desc.patch, desc.latent_c, desc.latent_h, desc.latent_w)

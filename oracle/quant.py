@@ -126,3 +126,14 @@ def lin_q(a, lin: QLinear, s_a, z_a: int, act_bits: int = 8, tap: dict | None = 
         tap["codes"] = qs.astype(np.int8) if act_bits == 8 else qs
         tap["acc"] = acc
     return y
+
+
+def bf16_round(x):
+    """Value of x after storage as bfloat16 (8 exponent bits, 7 fraction bits):
+    x is first rounded to float32, then to the nearest bfloat16 with ties to
+    even, and returned as float64.  Used by the reduced-precision cache variant
+    (not in the paper: it halves the bytes a cached step streams)."""
+    x32 = np.ascontiguousarray(np.asarray(x, dtype=np.float32))
+    bits = x32.view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).astype(np.float64).reshape(x32.shape)

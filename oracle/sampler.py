@@ -69,7 +69,7 @@ def vc_correct(x, K_t, mu=None):
 
 
 def sample_step(x, labels, i, t, abar_t, abar_prev, desc, w, linear, cache, interval,
-                cfg_scale=0.0, K_t=None, force_full=None, taps=None):
+                cfg_scale=0.0, K_t=None, force_full=None, taps=None, cache_bf16=False):
     """One sampler step: denoiser (full or cached by the cache rule), guidance,
     solver update, VC.  force_full: None = the rule, a boolean = that mode, an
     array [depth, 2] = a per-(block, module) schedule for this step."""
@@ -86,7 +86,7 @@ def sample_step(x, labels, i, t, abar_t, abar_prev, desc, w, linear, cache, inte
     else:
         xin, yin = x, np.asarray(labels)
     tt = np.full((xin.shape[0],), t)
-    eps = denoiser(xin, tt, yin, desc, w, linear, cache, full, taps)
+    eps = denoiser(xin, tt, yin, desc, w, linear, cache, full, taps, cache_bf16)
     if cfg_scale > 0:
         eps = cfg_combine(eps[:B], eps[B:], cfg_scale)
     xn = ddim_update(np.asarray(x, dtype=F64), eps, abar_t, abar_prev)
@@ -96,7 +96,7 @@ def sample_step(x, labels, i, t, abar_t, abar_prev, desc, w, linear, cache, inte
 
 
 def sample(x, labels, steps, interval, desc, w, linear, cfg_scale=0.0, K=None,
-           max_steps=None, trace=None, mask=None):
+           max_steps=None, trace=None, mask=None, cache_bf16=False):
     """Run the sampler for `steps` steps (or only the first `max_steps`).
     mask[steps, depth, 2] (1 = recompute) replaces the interval rule."""
     t, abar_t, abar_prev = ddim_schedule(steps)
@@ -106,7 +106,8 @@ def sample(x, labels, steps, interval, desc, w, linear, cfg_scale=0.0, K=None,
     for i in range(n):
         K_t = None if K is None else K[i]
         x, eps = sample_step(x, labels, i, int(t[i]), abar_t[i], abar_prev[i], desc, w, linear,
-                             cache, interval, cfg_scale, K_t, None if mask is None else np.asarray(mask)[i])
+                             cache, interval, cfg_scale, K_t, None if mask is None else np.asarray(mask)[i],
+                             cache_bf16=cache_bf16)
         if trace is not None:
             trace.append((x.copy(), eps.copy()))
     return x

@@ -235,6 +235,31 @@ def test_per_module_schedule_special_cases():
     assert np.array_equal(a, b)
 
 
+def test_bf16_cache_variant():
+    """Reduced-precision cache: the refresh step itself is unchanged (it uses the exact module outputs), what it
+    stores is the bfloat16 rounding of what the fp32 cache stores, and a cached step differs from the fp32-cache
+    one by at most the rounding of the stored tensors times the gates."""
+    w, lat, lab = _tiny_setup()
+    t = np.array([500, 500, 500])
+    qp, _ = _qparams_for(w, lat, lab, t)
+    lin = dit.QLinears(w, qp)
+    c32, c16 = {}, {}
+    f32 = dit.denoiser(lat, t, lab, TINY, w, lin, c32, True)
+    f16 = dit.denoiser(lat, t, lab, TINY, w, lin, c16, True, cache_bf16=True)
+    assert np.array_equal(f32, f16)
+    for k in c32:
+        assert np.array_equal(c16[k], quant.bf16_round(c32[k]))
+        assert not np.array_equal(c16[k], c32[k])
+    a = dit.denoiser(lat, t - 20, lab, TINY, w, lin, c32, False)
+    b = dit.denoiser(lat, t - 20, lab, TINY, w, lin, c16, False, cache_bf16=True)
+    assert not np.array_equal(a, b)
+    assert np.sqrt(np.mean((a - b) ** 2)) <= 2.0 ** -8 * np.sqrt(np.mean(a ** 2)) * 4
+    # the sampler threads the option through
+    s32 = sampler.sample(lat, lab, 6, 2, TINY, w, lin)
+    s16 = sampler.sample(lat, lab, 6, 2, TINY, w, lin, cache_bf16=True)
+    assert not np.array_equal(s32, s16) and np.sqrt(np.mean((s32 - s16) ** 2)) < 2e-2 * np.sqrt(np.mean(s32 ** 2))
+
+
 def test_cached_run_differs_but_tracks_uncached_run():
     w, lat, lab = _tiny_setup()
     qp, _ = _qparams_for(w, lat, lab, np.array([500, 500, 500]))

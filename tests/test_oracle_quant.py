@@ -197,3 +197,19 @@ def test_lin_q_converges_to_fp_linear_with_fine_codes():
         y = Q.lin_q(a, lin, s, z, act_bits=bits)
         errs.append(np.abs(y - exact).max())
     assert errs[0] < 2e-2 and errs[1] < errs[0] / 100
+
+
+def test_bf16_round_matches_library_conversion_and_ties_to_even():
+    import torch
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.normal(size=4000) * 10.0 ** rng.integers(-6, 6, size=4000), [0.0, -0.0, 1.0, -1.0, 3.0e38, 1e-30]])
+    want = torch.tensor(x, dtype=torch.float32).to(torch.bfloat16).to(torch.float32).numpy().astype(np.float64)
+    got = Q.bf16_round(x)
+    assert np.array_equal(got, want)
+    # exact halfway cases: 1 + 2^-8 lies between 1 and 1 + 2^-7 -> even (1); 1 + 3 * 2^-8 -> 1 + 2^-6
+    assert Q.bf16_round(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert Q.bf16_round(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    # idempotent, relative error at most 2^-9
+    assert np.array_equal(Q.bf16_round(got), got)
+    nz = x != 0
+    assert np.max(np.abs(got[nz] - np.float32(x[nz]).astype(np.float64)) / np.abs(x[nz])) <= 2.0 ** -8

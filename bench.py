@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cache-format", choices=["fp32", "bf16"], default="fp32",
+                    help="storage of the cached module outputs (fp32 is the headline configuration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (latents are independent, so more GPUs would each run "
@@ -112,6 +114,7 @@ def main():
     tt, _, _ = qc.qc_ddim_schedule(wl.steps)
     ctx.calibrate(torch.from_numpy(clat).cuda(), [tt[i] for i in idx], clab)
     ctx.drop_fp32()
+    ctx.set_cache_format(args.cache_format)
     del w
     lat = torch.from_numpy(I.make_latents(B, m, wl.seed_latents)).cuda()
     lab = torch.from_numpy(I.make_labels(B, m, wl.seed_labels).astype(np.int32)).cuda()
@@ -168,7 +171,8 @@ def main():
             # fp32 row in, int8 codes out
             "ln_mod_quant": ("hbm", 5.0 * MT * D * 2 * per_pass),
             # both cached tensors of every block read once, the residual stream read and written once
-            "cached_blocks": ("hbm", (2.0 * m.depth + 2.0) * MT * D * 4 * (wl.steps - n_full)),
+            "cached_blocks": ("hbm", (2.0 * m.depth * (2 if args.cache_format == "bf16" else 4) + 2.0 * 4) * MT * D
+                              * (wl.steps - n_full)),
             # sample and noise estimate(s) read, sample written; one launch per step
             "ddim_vc": ("hbm", (4.0 * (B + Beff) + 4.0 * B) * m.latent_c * m.latent_h * m.latent_w * wl.steps),
             # all steps' adaLN projections of every block in one launch per window of steps
@@ -196,7 +200,8 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": wl.name, "latents": B, "effective_batch": Beff, "sampler_steps": wl.steps,
                    "cache_interval": wl.cache_interval, "refresh_steps": n_full, "cfg_scale": wl.cfg_scale,
-                   "weight_bits": m.weight_bits, "vc": True},
+                   "weight_bits": m.weight_bits, "vc": True,
+                   "cache_format": args.cache_format},
         "int8_tops_end_to_end": total_int8 / (ms_per_step * 1e-3) / 1e12,
         "full_step_us": full_us, "cached_step_us": cached_us,
         "roofline": roofline,

@@ -196,8 +196,19 @@ int qc_dit_block(qc_ctx *ctx, int block, int mode, float *x, const float *c, int
  * src, x: dev [B, T, D]; gate: dev [B, ld_gate] rows, first D entries used. */
 int qc_cache_store(qc_ctx *ctx, int block, int which, const float *src, int B, void *stream);
 int qc_cache_reuse(qc_ctx *ctx, int block, int which, float *x, const float *gate, int ld_gate, int B, void *stream);
-/* Device address of a cached tensor (fp32 [max_batch, T, D], first B rows valid). */
-int qc_cache_ptr(qc_ctx *ctx, int block, int which, float **ptr_out);
+/* Device address of a cached tensor ([max_batch, T, D], first B rows valid), in
+ * the format set by qc_set_cache_format: fp32 or bfloat16. */
+int qc_cache_ptr(qc_ctx *ctx, int block, int which, void **ptr_out);
+
+/* Storage format of the cached module outputs.  QC_CACHE_FP32 (default) keeps
+ * them as the refresh step computed them.  QC_CACHE_BF16 stores the bfloat16
+ * rounding (nearest even) of those fp32 values: a cached step then streams
+ * half the bytes and adds gate * (rounded output); the refresh step itself is
+ * unchanged, it uses the exact outputs.  Not in the paper: a precision choice
+ * of this implementation, off by default.  Switching format discards what the
+ * cache holds. */
+enum { QC_CACHE_FP32 = 0, QC_CACHE_BF16 = 1 };
+int qc_set_cache_format(qc_ctx *ctx, int format);
 /* Device address of an internal buffer, see QC_WS_*; for inspection by tests. */
 int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out);
 

@@ -57,6 +57,7 @@ _SIGS = {
     "qc_w8a8_linear": (i32, [vp, vp, vp, vp, vp, f32, i32, i32, i32, i32, i32, vp, vp, vp]),
     "qc_vc_correct": (i32, [vp, vp, vp, i32, i32, i32, i32, vp]),
     "qc_set_cache_mask": (i32, [vp, vp, i32]),
+    "qc_set_cache_format": (i32, [vp, i32]),
     "qc_vc_fit": (i32, [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp]),
     "qc_denoise_f32": (i32, [vp, C.POINTER(Weights), vp, i32, vp, i32, i32, vp, vp]),
     "qc_vc_fit_sampler": (i32, [vp, C.POINTER(Weights), vp, vp, vp, i32, i32, f32, f32, vp, vp]),
@@ -157,6 +158,7 @@ class Context:
         self.h = vp()
         _chk(lib.qc_create(C.byref(self.desc), vp(base), n.value, max_batch, C.byref(self.h)))
         self._keep = None
+        self._cache_bf16 = False
 
     def close(self):
         if self.h:
@@ -261,7 +263,13 @@ class Context:
         p = vp()
         _chk(lib.qc_cache_ptr(self.h, block, which, C.byref(p)))
         m = self.model
-        return self._view(p.value, (B, m.tokens, m.hidden), torch.float32)
+        return self._view(p.value, (B, m.tokens, m.hidden), torch.bfloat16 if self._cache_bf16 else torch.float32)
+
+    def set_cache_format(self, fmt):
+        """fmt: "fp32" (default) or "bf16"."""
+        code = {"fp32": 0, "bf16": 1}[fmt]
+        _chk(lib.qc_set_cache_format(self.h, code))
+        self._cache_bf16 = code == 1
 
     def workspace(self, name, shape, dtype):
         p, n = vp(), sz()

@@ -83,6 +83,7 @@ struct qc_ctx {
   QParam *dev_qp;   // [L][5]
   float *cache;     // [L][2][max_batch*T*D]
   std::vector<int> cache_batch;   // [L][2]: batch size held, 0 = nothing stored
+  bool cache_bf16 = false;        // cached tensors stored as bfloat16 instead of fp32 (qc_set_cache_format)
   std::vector<unsigned char> cache_mask;   // optional [steps][L][2] schedule (1 = recompute); empty = interval rule
   int mask_steps = 0;
   // workspace
@@ -440,8 +441,10 @@ static int check_ready(const qc_ctx *ctx, int B) {
   return QC_OK;
 }
 
-static float *cache_slot(const qc_ctx *ctx, int block, int which) {
-  return ctx->cache + ((size_t)block * 2 + which) * (size_t)ctx->max_batch * ctx->T * ctx->D;
+// element `elem` of the cached tensor (block, which); the arena region is sized for fp32 and holds either format
+static void *cache_at(const qc_ctx *ctx, int block, int which, size_t elem = 0) {
+  const size_t e = ((size_t)block * 2 + which) * (size_t)ctx->max_batch * ctx->T * ctx->D + elem;
+  return reinterpret_cast<char *>(ctx->cache) + e * (ctx->cache_bf16 ? 2 : 4);
 }
 
 // adaLN projection of blocks [l0, l0+nl) for `rows` rows of the conditioning tables starting at row r0:
@@ -484,7 +487,7 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
     return a;
   };
   if (!attn_full) {
-    QC_HIP(launch_cache_reuse(x, cache_slot(ctx, l, QC_CACHE_ATTN) + row0 * D, mod + 2 * D, 6 * D, B, T, D, st));
+    QC_HIP(launch_cache_reuse(x, cache_at(ctx, l, QC_CACHE_ATTN, row0 * D), mod + 2 * D, 6 * D, B, T, D, ctx->cache_bf16, st));
   } else {
   {
     QC_PROF(QC_K_LN_QUANT);
@@ -506,14 +509,14 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_PROJ], qa_attn, D, QC_SITE_PROJ);
-    a.cache_out = cache_slot(ctx, l, QC_CACHE_ATTN) + row0 * D; a.x = x; a.gate = mod + 2 * D; a.ld_gate = 6 * D;
+    a.cache_out = cache_at(ctx, l, QC_CACHE_ATTN, row0 * D); a.cache_bf16 = ctx->cache_bf16; a.x = x; a.gate = mod + 2 * D; a.ld_gate = 6 * D;
     a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_PROJ);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_PROJ));
   }
   }
   if (!mlp_full) {
-    QC_HIP(launch_cache_reuse(x, cache_slot(ctx, l, QC_CACHE_MLP) + row0 * D, mod + 5 * D, 6 * D, B, T, D, st));
+    QC_HIP(launch_cache_reuse(x, cache_at(ctx, l, QC_CACHE_MLP, row0 * D), mod + 5 * D, 6 * D, B, T, D, ctx->cache_bf16, st));
     return QC_OK;
   }
   {
@@ -528,7 +531,7 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_FC2], qa_mlp, R, QC_SITE_FC2);
-    a.cache_out = cache_slot(ctx, l, QC_CACHE_MLP) + row0 * D; a.x = x; a.gate = mod + 5 * D; a.ld_gate = 6 * D;
+    a.cache_out = cache_at(ctx, l, QC_CACHE_MLP, row0 * D); a.cache_bf16 = ctx->cache_bf16; a.x = x; a.gate = mod + 5 * D; a.ld_gate = 6 * D;
     a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_FC2);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_FC2));
@@ -558,8 +561,8 @@ int qc_dit_block(qc_ctx *ctx, int block, int mode, float *x, const float *c, int
     return rc;
   }
   const float *mod = ctx->mod + (size_t)block * ctx->win_rows * 6 * D;
-  QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, QC_CACHE_ATTN), mod + 2 * D, (int)(6 * D), B, ctx->T, (int)D, st));
-  QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, QC_CACHE_MLP), mod + 5 * D, (int)(6 * D), B, ctx->T, (int)D, st));
+  QC_HIP(launch_cache_reuse(x, cache_at(ctx, block, QC_CACHE_ATTN), mod + 2 * D, (int)(6 * D), B, ctx->T, (int)D, ctx->cache_bf16, st));
+  QC_HIP(launch_cache_reuse(x, cache_at(ctx, block, QC_CACHE_MLP), mod + 5 * D, (int)(6 * D), B, ctx->T, (int)D, ctx->cache_bf16, st));
   return QC_OK;
 }
 
@@ -576,7 +579,7 @@ int qc_cache_store(qc_ctx *ctx, int block, int which, const float *src, int B, v
   if (rc) return rc;
   if (!src) QC_FAIL(QC_ERR_NULL, "src is NULL");
   if (!aligned16(src)) QC_FAIL(QC_ERR_ALIGN, "src must be 16-byte aligned");
-  QC_HIP(launch_cache_store(src, cache_slot(ctx, block, which), (size_t)B * ctx->T * ctx->D, static_cast<hipStream_t>(stream)));
+  QC_HIP(launch_cache_store(src, cache_at(ctx, block, which), (size_t)B * ctx->T * ctx->D, ctx->cache_bf16, static_cast<hipStream_t>(stream)));
   ctx->cache_batch[(size_t)block * 2 + which] = B;
   return QC_OK;
 }
@@ -589,15 +592,15 @@ int qc_cache_reuse(qc_ctx *ctx, int block, int which, float *x, const float *gat
   if (!aligned16(x) || !aligned16(gate)) QC_FAIL(QC_ERR_ALIGN, "x and gate must be 16-byte aligned");
   if (ctx->cache_batch[(size_t)block * 2 + which] != B)
     QC_FAIL(QC_ERR_STATE, "block %d holds no cached tensor %d for batch %d", block, which, B);
-  QC_HIP(launch_cache_reuse(x, cache_slot(ctx, block, which), gate, ld_gate, B, ctx->T, ctx->D, static_cast<hipStream_t>(stream)));
+  QC_HIP(launch_cache_reuse(x, cache_at(ctx, block, which), gate, ld_gate, B, ctx->T, ctx->D, ctx->cache_bf16, static_cast<hipStream_t>(stream)));
   return QC_OK;
 }
 
-int qc_cache_ptr(qc_ctx *ctx, int block, int which, float **ptr_out) {
+int qc_cache_ptr(qc_ctx *ctx, int block, int which, void **ptr_out) {
   int rc = check_cache_args(ctx, block, which, 1);
   if (rc) return rc;
   if (!ptr_out) QC_FAIL(QC_ERR_NULL, "ptr_out is NULL");
-  *ptr_out = cache_slot(ctx, block, which);
+  *ptr_out = cache_at(ctx, block, which);
   return QC_OK;
 }
 
@@ -619,6 +622,14 @@ int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out) 
   }
   *ptr_out = p;
   if (bytes_out) *bytes_out = n;
+  return QC_OK;
+}
+
+int qc_set_cache_format(qc_ctx *ctx, int format) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  if (format != QC_CACHE_FP32 && format != QC_CACHE_BF16) QC_FAIL(QC_ERR_RANGE, "format must be QC_CACHE_FP32 or QC_CACHE_BF16");
+  ctx->cache_bf16 = format == QC_CACHE_BF16;
+  for (int &v : ctx->cache_batch) v = 0;      // what the cache holds is in the other format: nothing is stored
   return QC_OK;
 }
 
@@ -696,8 +707,8 @@ static int denoise_tail(qc_ctx *ctx, const Sub &sb, int mode, float *eps_out, hi
   if (mode == QC_CACHED) {
     const size_t slot = (size_t)ctx->max_batch * ctx->T * D;
     QC_PROF(QC_K_CACHED_BLOCKS);
-    QC_HIP(launch_cached_blocks(tokens, ctx->cache + (size_t)sb.b0 * ctx->T * D, 2 * slot, slot, ctx->mod + (size_t)sb.r0 * 6 * D,
-                                (size_t)ctx->win_rows * 6 * D, 6 * D, L, B, ctx->T, D, st));
+    QC_HIP(launch_cached_blocks(tokens, cache_at(ctx, 0, 0, (size_t)sb.b0 * ctx->T * D), 2 * slot, slot, ctx->mod + (size_t)sb.r0 * 6 * D,
+                                (size_t)ctx->win_rows * 6 * D, 6 * D, L, B, ctx->T, D, ctx->cache_bf16, st));
   }
   QC_HIP(launch_final(tokens, ctx->fmod + (size_t)sb.r0 * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + (size_t)sb.b0 * lat, B,
                       ctx->C, ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, st));
@@ -926,13 +937,13 @@ static int fp32_blocks_one(qc_ctx *ctx, const qc_weights_f32 *w, const float *co
     QC_HIP(launch_attention(ctx->qkv, 1, T, ctx->H, ctx->hd, nullptr, nullptr, ctx->cal_o, st));
     if (slot) QC_HIP(launch_minmax(ctx->cal_o, (size_t)T * D, slot + 2 * QC_SITE_PROJ, st));
     QC_HIP(launch_linear_f32(ctx->cal_o, b.proj_w, b.proj_b, ctx->cal_a, T, D, D, 0, st));
-    QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 2 * D, 6 * D, 1, T, D, st));
+    QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 2 * D, 6 * D, 1, T, D, false, st));
     QC_HIP(launch_ln_mod_quant(ctx->tokens, mod + 3 * D, mod + 4 * D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
     if (slot) QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_FC1, st));
     QC_HIP(launch_linear_f32(ctx->cal_h, b.fc1_w, b.fc1_b, ctx->cal_u, T, R, D, 2, st));
     if (slot) QC_HIP(launch_minmax(ctx->cal_u, (size_t)T * R, slot + 2 * QC_SITE_FC2, st));
     QC_HIP(launch_linear_f32(ctx->cal_u, b.fc2_w, b.fc2_b, ctx->cal_a, T, D, R, 0, st));
-    QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 5 * D, 6 * D, 1, T, D, st));
+    QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 5 * D, 6 * D, 1, T, D, false, st));
   }
   return QC_OK;
 }

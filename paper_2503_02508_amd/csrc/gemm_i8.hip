@@ -71,6 +71,13 @@ __device__ __forceinline__ float gelu_tanh(float v) {
   return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
+// bfloat16 storage of an fp32 value, round to nearest even
+__device__ __forceinline__ unsigned short bf16_bits(float v) {
+  unsigned u = __builtin_bit_cast(unsigned, v);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+
 // Eq. 1 on signed codes with the quotient v / s refined to the correctly rounded
 // value by one Newton step on the reciprocal estimate.
 __device__ __forceinline__ int quant_code(float v, float s, float inv_s, float z) {
@@ -560,7 +567,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
                 const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 const float v = fmaf(scv[jj], (float)(acc[i][j][r] - zwv[jj]), bsv[jj]);
                 const long long o = (long long)m * p.N + n;
-                p.cache_out[o] = v;
+                if (p.cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
+                else ((float *)p.cache_out)[o] = v;
                 p.x[o] = xv[jj][ii][r] + gv[jj] * v;
               }
           } else {
@@ -574,7 +582,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
                 if (m >= p.M) continue;
                 const float v = fmaf(scv[jj], (float)(acc[i][j][r] - zwv[jj]), bsv[jj]);
                 const long long o = (long long)m * p.N + n;
-                p.cache_out[o] = v;
+                if (p.cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
+                else ((float *)p.cache_out)[o] = v;
                 const float g = p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
                 p.x[o] = xv[jj][ii][r] + g * v;
               }

@@ -58,7 +58,8 @@ struct GemmArgs {
   int ldq;
   const QParam *o_qp;        // output quantiser
   // EPI_RESID
-  float *cache_out;          // [M, N]
+  void *cache_out;           // [M, N] fp32, or bfloat16 when cache_bf16 is set
+  int cache_bf16;
   float *x;                  // [M, N] residual stream, updated in place
   const float *gate;         // [B, ld_gate]
   int ld_gate;
@@ -98,11 +99,11 @@ hipError_t launch_embed(const float *x, const float *pw, const float *pb, const 
                         int C, int H, int W, int p, int D, int b_off, hipStream_t st);
 hipError_t launch_final(const float *tok, const float *fmod, const float *fw, const float *fb, float *eps, int B, int C,
                         int H, int W, int p, int D, hipStream_t st);
-hipError_t launch_cache_store(const float *src, float *dst, size_t n, hipStream_t st);
-hipError_t launch_cache_reuse(float *x, const float *cached, const float *gate, int ld_gate, int B, int T, int D,
+hipError_t launch_cache_store(const float *src, void *dst, size_t n, bool bf16, hipStream_t st);
+hipError_t launch_cache_reuse(float *x, const void *cached, const float *gate, int ld_gate, int B, int T, int D, bool bf16,
                               hipStream_t st);
-hipError_t launch_cached_blocks(float *x, const float *cache, size_t cache_block_stride, size_t cache_which_stride,
-                                const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D,
+hipError_t launch_cached_blocks(float *x, const void *cache, size_t cache_block_stride, size_t cache_which_stride,
+                                const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D, bool bf16,
                                 hipStream_t st);
 hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, float cx, float ce, float cfg_scale,
                           const float *K_t, hipStream_t st);

@@ -427,27 +427,59 @@ hipError_t launch_final(const float *tok, const float *fmod, const float *fw, co
 }
 
 // ---------------------------------------------------------------- cache ops
-__global__ __launch_bounds__(256) void copy_kernel(const float4 *__restrict__ s, float4 *__restrict__ d, size_t n4) {
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) d[i] = s[i];
+// The cached tensors are stored as fp32 or, in the reduced-precision variant, as bfloat16 (round to nearest even
+// of the fp32 value); element i of a tensor sits at index i of either format.
+__device__ __forceinline__ unsigned short bf16_bits(float v) {
+  unsigned u = __builtin_bit_cast(unsigned, v);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
 }
 
-hipError_t launch_cache_store(const float *src, float *dst, size_t n, hipStream_t st) {
+template <bool BF16>
+__device__ __forceinline__ float4 load_cached4(const void *base, size_t i4) {
+  if (BF16) {
+    const uint2 r = ((const uint2 *)base)[i4];       // four bfloat16
+    return make_float4(__builtin_bit_cast(float, r.x << 16), __builtin_bit_cast(float, r.x & 0xFFFF0000u),
+                       __builtin_bit_cast(float, r.y << 16), __builtin_bit_cast(float, r.y & 0xFFFF0000u));
+  }
+  return ((const float4 *)base)[i4];
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void cache_store_kernel(const float4 *__restrict__ s, void *__restrict__ d, size_t n4) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    const float4 v = s[i];
+    if (BF16) {
+      uint2 r;
+      r.x = (unsigned)bf16_bits(v.x) | ((unsigned)bf16_bits(v.y) << 16);
+      r.y = (unsigned)bf16_bits(v.z) | ((unsigned)bf16_bits(v.w) << 16);
+      ((uint2 *)d)[i] = r;
+    } else {
+      ((float4 *)d)[i] = v;
+    }
+  }
+}
+
+hipError_t launch_cache_store(const float *src, void *dst, size_t n, bool bf16, hipStream_t st) {
   size_t n4 = n / 4, blocks = (n4 + 255) / 256;
   if (blocks > 16384) blocks = 16384;
   if (blocks == 0) return hipSuccess;
-  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float4 *)src, (float4 *)dst, n4);
+  if (bf16) hipLaunchKernelGGL(cache_store_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, (const float4 *)src, dst, n4);
+  else hipLaunchKernelGGL(cache_store_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, (const float4 *)src, dst, n4);
   return hipGetLastError();
 }
 
 // x[b, t, :] += gate[b, :] * cached[b, t, :]
-__global__ __launch_bounds__(256) void cache_reuse_kernel(float *__restrict__ x, const float *__restrict__ cached,
+template <bool BF16>
+__global__ __launch_bounds__(256) void cache_reuse_kernel(float *__restrict__ x, const void *__restrict__ cached,
                                                           const float *__restrict__ gate, int ld_gate, size_t n4, int TD4,
                                                           int D4) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n4) return;
   const int b = (int)(i / TD4), n = (int)(i % D4) * 4;
-  float4 xv = ((float4 *)x)[i], cv = ((const float4 *)cached)[i];
+  float4 xv = ((float4 *)x)[i];
+  const float4 cv = load_cached4<BF16>(cached, i);
   float4 g = *(const float4 *)(gate + (size_t)b * ld_gate + n);
   xv.x = xv.x + g.x * cv.x;
   xv.y = xv.y + g.y * cv.y;
@@ -456,24 +488,28 @@ __global__ __launch_bounds__(256) void cache_reuse_kernel(float *__restrict__ x,
   ((float4 *)x)[i] = xv;
 }
 
-hipError_t launch_cache_reuse(float *x, const float *cached, const float *gate, int ld_gate, int B, int T, int D,
+hipError_t launch_cache_reuse(float *x, const void *cached, const float *gate, int ld_gate, int B, int T, int D, bool bf16,
                               hipStream_t st) {
   const size_t n4 = (size_t)B * T * D / 4;
-  hipLaunchKernelGGL(cache_reuse_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, x, cached, gate, ld_gate, n4,
-                     T * D / 4, D / 4);
+  const dim3 grid((unsigned)((n4 + 255) / 256));
+  if (bf16) hipLaunchKernelGGL(cache_reuse_kernel<true>, grid, dim3(256), 0, st, x, cached, gate, ld_gate, n4, T * D / 4, D / 4);
+  else hipLaunchKernelGGL(cache_reuse_kernel<false>, grid, dim3(256), 0, st, x, cached, gate, ld_gate, n4, T * D / 4, D / 4);
   return hipGetLastError();
 }
 
 // All blocks of a cached step in one pass over x: for every block in order,
 // x += gate_msa * attn_cached; x += gate_mlp * mlp_cached (same association
-// as block after block).  mod[l, b, 6D] holds the gates in chunks 2 and 5.
-__global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ x, const float *__restrict__ cache,
+// as block after block).  mod[l, b, 6D] holds the gates in chunks 2 and 5.  Cache strides are in elements.
+template <bool BF16>
+__global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ x, const void *__restrict__ cache,
                                                             size_t cache_block_stride, size_t cache_which_stride,
                                                             const float *__restrict__ mod, size_t mod_block_stride,
                                                             int ld_mod, int L, size_t n4, int TD4, int D4, int D) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n4) return;
   const int b = (int)(i / TD4), n = (int)(i % D4) * 4;
+  constexpr size_t ES = BF16 ? 2 : 4;               // bytes per cached element
+  const char *cbase = (const char *)cache;
   float4 xv = ((float4 *)x)[i];
   auto apply = [&](const float4 &g1, const float4 &a, const float4 &g2, const float4 &mo) {
     xv.x = xv.x + g1.x * a.x; xv.y = xv.y + g1.y * a.y; xv.z = xv.z + g1.z * a.z; xv.w = xv.w + g1.w * a.w;
@@ -489,8 +525,8 @@ __global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ 
       const float *mrow = mod + (size_t)(l + u) * mod_block_stride + (size_t)b * ld_mod + n;
       g1[u] = *(const float4 *)(mrow + 2 * D);
       g2[u] = *(const float4 *)(mrow + 5 * D);
-      a[u] = ((const float4 *)(cache + (size_t)(l + u) * cache_block_stride))[i];
-      mo[u] = ((const float4 *)(cache + (size_t)(l + u) * cache_block_stride + cache_which_stride))[i];
+      a[u] = load_cached4<BF16>(cbase + (size_t)(l + u) * cache_block_stride * ES, i);
+      mo[u] = load_cached4<BF16>(cbase + ((size_t)(l + u) * cache_block_stride + cache_which_stride) * ES, i);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) apply(g1[u], a[u], g2[u], mo[u]);
@@ -498,19 +534,24 @@ __global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ 
   for (; l < L; ++l) {
     const float *mrow = mod + (size_t)l * mod_block_stride + (size_t)b * ld_mod + n;
     const float4 g1 = *(const float4 *)(mrow + 2 * D), g2 = *(const float4 *)(mrow + 5 * D);
-    const float4 a = ((const float4 *)(cache + (size_t)l * cache_block_stride))[i];
-    const float4 mo = ((const float4 *)(cache + (size_t)l * cache_block_stride + cache_which_stride))[i];
+    const float4 a = load_cached4<BF16>(cbase + (size_t)l * cache_block_stride * ES, i);
+    const float4 mo = load_cached4<BF16>(cbase + ((size_t)l * cache_block_stride + cache_which_stride) * ES, i);
     apply(g1, a, g2, mo);
   }
   ((float4 *)x)[i] = xv;
 }
 
-hipError_t launch_cached_blocks(float *x, const float *cache, size_t cache_block_stride, size_t cache_which_stride,
-                                const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D,
+hipError_t launch_cached_blocks(float *x, const void *cache, size_t cache_block_stride, size_t cache_which_stride,
+                                const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D, bool bf16,
                                 hipStream_t st) {
   const size_t n4 = (size_t)B * T * D / 4;
-  hipLaunchKernelGGL(cached_blocks_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, x, cache,
-                     cache_block_stride, cache_which_stride, mod, mod_block_stride, ld_mod, L, n4, T * D / 4, D / 4, D);
+  const dim3 grid((unsigned)((n4 + 255) / 256));
+  if (bf16)
+    hipLaunchKernelGGL(cached_blocks_kernel<true>, grid, dim3(256), 0, st, x, cache, cache_block_stride, cache_which_stride, mod,
+                       mod_block_stride, ld_mod, L, n4, T * D / 4, D / 4, D);
+  else
+    hipLaunchKernelGGL(cached_blocks_kernel<false>, grid, dim3(256), 0, st, x, cache, cache_block_stride, cache_which_stride, mod,
+                       mod_block_stride, ld_mod, L, n4, T * D / 4, D / 4, D);
   return hipGetLastError();
 }
 

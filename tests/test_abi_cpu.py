@@ -111,6 +111,10 @@ def test_context_state_checks_without_a_device(qc):
     p = C.c_void_p()
     assert qc.lib.qc_cache_ptr(h, 1, 1, C.byref(p)) == 0 and p.value >= 0x100000
     assert qc.lib.qc_workspace_ptr(h, 99, C.byref(p), None) == -4
+    # cache storage format: unknown formats refused, a switch leaves the context usable
+    assert qc.lib.qc_set_cache_format(None, 0) == -1
+    assert qc.lib.qc_set_cache_format(h, 2) == -4 and qc.lib.qc_set_cache_format(h, -1) == -4
+    assert qc.lib.qc_set_cache_format(h, 1) == 0 and qc.lib.qc_set_cache_format(h, 0) == 0
     assert qc.lib.qc_destroy(h) == 0
 
 

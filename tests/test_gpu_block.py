@@ -9,7 +9,7 @@ a differing code differs by exactly one step)."""
 import numpy as np
 import pytest
 
-from oracle import dit, sampler
+from oracle import dit, quant, sampler
 from synthetic import dit_inputs as I
 from qc_testlib import (assert_close, code_flip_stats, make_pair, oracle_calibration, rel_rms, max_abs)
 
@@ -389,6 +389,82 @@ def test_schedule_written_from_the_interval_rule_is_the_interval_sampler():
     torch.cuda.synchronize()
     assert torch.equal(xa, xb)
     ctx.set_cache_mask(None)
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,model,B,steps,interval,cfg", [
+    ("tiny_n2", TINY, 3, 8, 2, 0.0), ("ragged_n3_cfg", RAGGED, 2, 7, 3, 1.5),
+    ("xl_256_depth2_n2", I.shrink(I.DIT_XL2_256, 2), 2, 50, 2, 0.0)])
+def test_sampler_with_bf16_cache(name, model, B, steps, interval, cfg):
+    """Reduced-precision cache storage: the stored tensors are the bfloat16 rounding of the fp32 ones (bit for bit,
+    up to values the two sides computed differently within fp32 rounding), and the sampler stays inside the bar
+    against the oracle run with the same storage."""
+    import torch
+    n_run = min(steps, 2 * interval + 1)
+    std = 0.02 if model.hidden > 256 else 0.15
+    w = I.make_weights(model, 91, std=std)
+    tt, at, ap = sampler.ddim_schedule(steps)
+    clat = np.concatenate([I.make_latents(1, model, 4000 + i) for i in range(4)])
+    qp, _, _ = oracle_calibration(model, w, lat=clat, lab=I.make_labels(4, model, 92), t=tt[[0, steps // 3, 2 * steps // 3, steps - 1]])
+    Beff = 2 * B if cfg > 0 else B
+    lin, ctx = make_pair(model, w, qp, Beff, interval)
+    ctx.set_cache_format("bf16")
+    lat, lab = I.make_latents(B, model, 93), I.make_labels(B, model, 94)
+    K = I.make_vc_factors(steps, model.latent_c, 95)
+    Kd, ld = _cuda(K), _cuda(lab.astype(np.int32))
+    x_or, cache = lat.astype(np.float64), {}
+    worst = (0.0, 0.0)
+    for i in range(n_run):
+        xd = _cuda(x_or.astype(np.float32))
+        x_start = xd.cpu().numpy().astype(np.float64)
+        x_or, _ = sampler.sample_step(x_start, lab, i, int(tt[i]), at[i], ap[i], model, w, lin, cache, interval, cfg, K[i],
+                                      cache_bf16=True)
+        ctx.sample_step(xd, ld, i, int(tt[i]), float(at[i]), float(ap[i]), cfg, Kd[i])
+        got = xd.cpu().numpy()
+        ma, rr = max_abs(got, x_or), rel_rms(got, x_or)
+        assert ma <= 1e-2 and rr <= 1e-3, "%s step %d: max-abs %.2e rel-RMS %.2e" % (name, i, ma, rr)
+        worst = (max(worst[0], ma), max(worst[1], rr))
+        if i == 0:
+            # what the refresh step stored: bfloat16 values, equal to the oracle's rounding wherever the two
+            # fp32 values agree to well below a bfloat16 step
+            for which, key in ((0, "attn"), (1, "mlp")):
+                dev = ctx.cache_tensor(0, which, Beff).float().cpu().numpy().astype(np.float64)
+                ref = cache[(0, key)]
+                # the stored tensor against the oracle's: the floating-point bar (flipped activation codes move the
+                # fp32 value before rounding) plus one bfloat16 step; what is stored must be bfloat16 values.  The
+                # rounding itself is checked bit for bit in test_bf16_cache_store_and_reuse_calls.
+                excess = np.abs(dev - ref) - (np.abs(ref) * 2.0 ** -7 + 1e-2)
+                assert excess.max() <= 0, "%s cache %s differs by more than one bf16 step (%.2e)" % (name, key, excess.max())
+                assert rel_rms(dev, ref) <= 1e-3 + 2.0 ** -8
+                assert np.array_equal(quant.bf16_round(dev), dev), "%s cache %s holds values that are not bfloat16" % (name, key)
+    print(name, "bf16 cache: worst max-abs %.2e rel-RMS %.2e" % worst)
+    # switching the format discards the cache: a cached step must now be refused
+    ctx.set_cache_format("fp32")
+    with pytest.raises(Exception):
+        ctx.sample_step(xd, ld, 1, int(tt[1]), float(at[1]), float(ap[1]), cfg, Kd[1], 1)
+    ctx.close()
+
+
+def test_bf16_cache_store_and_reuse_calls():
+    import torch
+    import paper_2503_02508_amd as qc
+    from oracle import quant
+    model, B = TINY, 2
+    w = I.make_weights(model, 96, std=0.15)
+    qp = {(b, s): quant.act_qparams(-4, 4) for b in range(model.depth) for s in dit.SITES}
+    _, ctx = make_pair(model, w, qp, B, 2)
+    ctx.set_cache_format("bf16")
+    rng = np.random.default_rng(97)
+    src = rng.standard_normal((B, model.tokens, model.hidden)).astype(np.float32)
+    x = rng.standard_normal((B, model.tokens, model.hidden)).astype(np.float32)
+    gate = rng.standard_normal((B, model.hidden)).astype(np.float32)
+    ctx.cache_store(1, qc.QC_CACHE_MLP, _cuda(src))
+    stored = ctx.cache_tensor(1, qc.QC_CACHE_MLP, B).float().cpu().numpy()
+    assert np.array_equal(stored.astype(np.float64), quant.bf16_round(src))
+    xd = _cuda(x)
+    ctx.cache_reuse(1, qc.QC_CACHE_MLP, xd, _cuda(gate))
+    want = x.astype(np.float64) + gate[:, None, :].astype(np.float64) * quant.bf16_round(src)
+    assert max_abs(xd.cpu().numpy(), want) <= 1e-5
     ctx.close()
 
 

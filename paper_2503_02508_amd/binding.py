@@ -12,6 +12,8 @@ __all__ = [
     "lib", "QCError", "ModelDesc", "Context", "QC_FULL", "QC_CACHED", "QC_CACHE_ATTN", "QC_CACHE_MLP", "SITES",
     "qc_quantize_act", "qc_quantize_weight", "qc_w8a8_linear", "qc_vc_correct", "qc_vc_fit", "qc_ddim_schedule", "last_error",
     "LIB_PATH", "WS", "KERNEL_CLASSES",
+    "qc_tap_workspace_bytes", "qc_tap_similarity", "qc_tap_normalise", "qc_tap_embed", "qc_tap_kmeans",
+    "qc_tap_aggregate", "qc_tap_cluster",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqc.so")
@@ -71,6 +73,13 @@ _SIGS = {
     "qc_sample_step": (i32, [vp, vp, vp, i32, i32, i32, f64, f64, f32, vp, i32, vp]),
     "qc_sample": (i32, [vp, vp, vp, i32, i32, f32, vp, vp]),
     "qc_keep_qkv_f32": (i32, [vp, i32]),
+    "qc_tap_workspace_bytes": (i32, [i32, i32, i32, i32, i32, C.POINTER(sz)]),
+    "qc_tap_similarity": (i32, [vp, vp, i32, i32, vp, i32, f32, vp, vp, vp, vp, sz, vp]),
+    "qc_tap_normalise": (i32, [vp, vp, vp, i32, i32, vp, sz, vp]),
+    "qc_tap_embed": (i32, [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]),
+    "qc_tap_kmeans": (i32, [vp, i32, i32, i32, vp, i32, vp, vp, C.POINTER(i32), vp, sz, vp]),
+    "qc_tap_aggregate": (i32, [vp, i32, i32, i32, vp, vp, vp, sz, vp]),
+    "qc_tap_cluster": (i32, [vp, vp, i32, i32, vp, i32, i32, f32, i32, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]),
     "qc_profile_begin": (i32, [vp]),
     "qc_profile_end": (i32, [vp, i32, C.POINTER(C.c_int32), C.POINTER(f32), vp]),
 }
@@ -130,6 +139,53 @@ def qc_vc_fit(x_hat, x_ref, eps, work, K_t):
 def qc_vc_correct(x, K_t, mu=None):
     B, Cc, H, W = x.shape
     _chk(lib.qc_vc_correct(_p(x), _p(K_t), _p(mu), B, Cc, H, W, _stream()))
+
+
+# ------------------------------------------------ calibration-set clustering (include/qc_tap.h)
+def qc_tap_workspace_bytes(N, F, n, k, kb) -> int:
+    out = sz()
+    _chk(lib.qc_tap_workspace_bytes(N, F, n, k, kb, C.byref(out)))
+    return out.value
+
+
+def _wb(work):
+    return work.numel() * work.element_size()
+
+
+def qc_tap_similarity(X, t, idx, alpha, A, d_r, d_c, work):
+    N, F = X.shape
+    _chk(lib.qc_tap_similarity(_p(X), _p(t), N, F, _p(idx), idx.numel(), float(alpha), _p(A), _p(d_r), _p(d_c),
+                               _p(work), _wb(work), _stream()))
+
+
+def qc_tap_normalise(A, d_r, d_c, work):
+    N, n = A.shape
+    _chk(lib.qc_tap_normalise(_p(A), _p(d_r), _p(d_c), N, n, _p(work), _wb(work), _stream()))
+
+
+def qc_tap_embed(L, k, iters, q0, U, sigma, work):
+    N, n = L.shape
+    _chk(lib.qc_tap_embed(_p(L), N, n, k, q0.shape[0], iters, _p(q0), _p(U), _p(sigma), _p(work), _wb(work), _stream()))
+
+
+def qc_tap_kmeans(U, init_idx, max_iter, labels, centres, work) -> int:
+    N, d = U.shape
+    passes = i32(0)
+    _chk(lib.qc_tap_kmeans(_p(U), N, d, init_idx.numel(), _p(init_idx), max_iter, _p(labels), _p(centres),
+                           C.byref(passes), _p(work), _wb(work), _stream()))
+    return passes.value
+
+
+def qc_tap_aggregate(labels, k, out, work, perm_out=None):
+    m, N = labels.shape
+    _chk(lib.qc_tap_aggregate(_p(labels), m, N, k, _p(out), _p(perm_out), _p(work), _wb(work), _stream()))
+
+
+def qc_tap_cluster(X, t, subsamples, alpha, k, iters, q0, init_idx, max_iter, labels_out, per_labels, work):
+    N, F = X.shape
+    m, n = subsamples.shape
+    _chk(lib.qc_tap_cluster(_p(X), _p(t), N, F, _p(subsamples), m, n, float(alpha), k, q0.shape[0], iters, _p(q0),
+                            _p(init_idx), max_iter, _p(labels_out), _p(per_labels), _p(work), _wb(work), _stream()))
 
 
 def qc_ddim_schedule(steps: int):

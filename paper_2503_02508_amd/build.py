@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqc.so")
-SOURCES = ["api.hip", "gemm_i8.hip", "rowops.hip", "attention.hip"]
+SOURCES = ["api.hip", "gemm_i8.hip", "rowops.hip", "attention.hip", "tap.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-fhip-fp32-correctly-rounded-divide-sqrt", "-ffp-contract=on",
@@ -41,7 +41,7 @@ def build(verbose: bool = False) -> str:
     cc = _hipcc()
     objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
     cmds = [[cc, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=5) as ex:
         outs = list(ex.map(_run, cmds))
     outs.append(_run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]))
     if verbose:

@@ -1,0 +1,1047 @@
+// Calibration-set clustering (temporal-aware parallel clustering, TAP; the paper's section of that name and its
+// algorithm): similarity matrices on the fp32 matrix cores, degree normalisation, leading singular vectors by block
+// power iteration with Cholesky QR and a Jacobi Rayleigh-Ritz step, k-means, aggregation over subsamples.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <math.h>
+#include "qc_tap.h"
+#include "qc_internal.h"
+
+namespace {
+
+#define TAP_FAIL(code, ...)     \
+  do {                          \
+    qc::set_error(__VA_ARGS__); \
+    return (code);              \
+  } while (0)
+
+#define TAP_HIP(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) TAP_FAIL(QC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));     \
+  } while (0)
+
+#define TAP_RC(expr)       \
+  do {                     \
+    int rc_ = (expr);      \
+    if (rc_) return rc_;   \
+  } while (0)
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int NUM_XCD = 8;
+constexpr int KB_MAX = 128;
+constexpr int M_MAX = 8;
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------------ fp32 GEMM
+// C[m, n] = sum_k A(m, k) B(n, k) with A(m, k) = A[m * sam + k * sak], B(n, k) = B[n * sbn + k * sbk]; each operand
+// is contiguous either along k (KC) or along its own index.  128 x 128 tile per workgroup of four wavefronts (2 x 2,
+// each 64 x 64 = 2 x 2 blocks of v_mfma_f32_32x32x2_f32), K walked in slabs of 32 staged through LDS k-major, so that
+// an operand fetch is 32 consecutive floats per half wavefront.  The next slab's global loads are in flight while the
+// current one is multiplied.
+constexpr int TM = 128, TN = 128, TK = 32, LDT = 132;
+
+enum SgemmEpi { SE_PLAIN = 0, SE_SIM = 1, SE_COLSCALE = 2 };
+
+struct SgemmArgs {
+  const float *A, *B;
+  float *C;
+  long long sam, sak, sbn, sbk, ldc;
+  int M, N, K;
+  int a_kc, b_kc;     // operand contiguous along k (else along its own index)
+  int a_vec, b_vec;   // 16-byte loads are safe (alignment and extents are multiples of 4)
+  // SE_SIM: C = alpha * acc * rs[m] * cs[n] + (1 - alpha) * exp(-|tr[m] - tc[n]|);  SE_COLSCALE: C = acc * cs[n]
+  const float *rs, *cs, *tr, *tc;
+  float alpha;
+};
+
+// One operand's share of a slab for this thread: four units of four consecutive elements.
+//  KC: unit u -> (o = u / 8, k4 = (u % 8) * 4), elements along k
+//  else: unit u -> (k = u / 32, o4 = (u % 32) * 4), elements along o
+template <bool KC>
+__device__ __forceinline__ void load_units(const float *P, long long so, long long sk, int o0, int O, int k0, int K,
+                                           bool vec, int tid, float4 (&r)[4]) {
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int u = tid + 256 * p;
+    if (KC) {
+      const int o = o0 + (u >> 3), k = k0 + ((u & 7) << 2);
+      if (vec) {
+        const bool ok = o < O && k < K;
+        const float4 v = *reinterpret_cast<const float4 *>(P + (ok ? (long long)o * so + k : 0));
+        r[p] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+      } else {
+        float e[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool ok = o < O && k + i < K;
+          const float v = P[ok ? (long long)o * so + (long long)(k + i) * sk : 0];
+          e[i] = ok ? v : 0.f;
+        }
+        r[p] = make_float4(e[0], e[1], e[2], e[3]);
+      }
+    } else {
+      const int k = k0 + (u >> 5), o = o0 + ((u & 31) << 2);
+      if (vec) {
+        const bool ok = o < O && k < K;
+        const float4 v = *reinterpret_cast<const float4 *>(P + (ok ? (long long)k * sk + o : 0));
+        r[p] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+      } else {
+        float e[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool ok = o + i < O && k < K;
+          const float v = P[ok ? (long long)k * sk + (long long)(o + i) * so : 0];
+          e[i] = ok ? v : 0.f;
+        }
+        r[p] = make_float4(e[0], e[1], e[2], e[3]);
+      }
+    }
+  }
+}
+
+template <bool KC>
+__device__ __forceinline__ void store_units(float *T, int tid, const float4 (&r)[4]) {
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int u = tid + 256 * p;
+    if (KC) {
+      const int o = u >> 3, k = (u & 7) << 2;
+      T[(k + 0) * LDT + o] = r[p].x;
+      T[(k + 1) * LDT + o] = r[p].y;
+      T[(k + 2) * LDT + o] = r[p].z;
+      T[(k + 3) * LDT + o] = r[p].w;
+    } else {
+      const int k = u >> 5, o = (u & 31) << 2;
+      *reinterpret_cast<float4 *>(T + k * LDT + o) = r[p];
+    }
+  }
+}
+
+template <bool AKC, bool BKC, int EPI>
+__global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs p) {
+  __shared__ __align__(16) float As[TK * LDT];
+  __shared__ __align__(16) float Bs[TK * LDT];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tiles_m = (p.M + TM - 1) / TM, tiles_n = (p.N + TN - 1) / TN;
+  const int total = tiles_m * tiles_n;
+  // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of tiles (n fastest) so that the
+  // tiles sharing an A panel meet in one L2
+  const int per_xcd = (total + NUM_XCD - 1) / NUM_XCD;
+  const int tile = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
+  if (blockIdx.x / NUM_XCD >= per_xcd || tile >= total) return;
+  const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TN;
+  const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  float4 ra[4], rb[4];
+  const int nslab = (p.K + TK - 1) / TK;
+  load_units<AKC>(p.A, p.sam, p.sak, m0, p.M, 0, p.K, p.a_vec, tid, ra);
+  load_units<BKC>(p.B, p.sbn, p.sbk, n0, p.N, 0, p.K, p.b_vec, tid, rb);
+  for (int s = 0; s < nslab; ++s) {
+    __syncthreads();
+    store_units<AKC>(As, tid, ra);
+    store_units<BKC>(Bs, tid, rb);
+    __syncthreads();
+    if (s + 1 < nslab) {
+      load_units<AKC>(p.A, p.sam, p.sak, m0, p.M, (s + 1) * TK, p.K, p.a_vec, tid, ra);
+      load_units<BKC>(p.B, p.sbn, p.sbk, n0, p.N, (s + 1) * TK, p.K, p.b_vec, tid, rb);
+    }
+    const float *ap = As + (lane >> 5) * LDT + wm0 + (lane & 31);
+    const float *bp = Bs + (lane >> 5) * LDT + wn0 + (lane & 31);
+#pragma unroll
+    for (int kk = 0; kk < TK / 2; ++kk) {
+      const float a0 = ap[kk * 2 * LDT], a1 = ap[kk * 2 * LDT + 32];
+      const float b0 = bp[kk * 2 * LDT], b1 = bp[kk * 2 * LDT + 32];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+  }
+
+  // epilogue: register r of a 32 x 32 block is row 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int n = n0 + wn0 + j * 32 + (lane & 31);
+    const bool nok = n < p.N;
+    float csn = 1.f, tcn = 0.f;
+    if (EPI != SE_PLAIN) csn = p.cs[nok ? n : 0];
+    if (EPI == SE_SIM) tcn = p.tc[nok ? n : 0];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (!nok || m >= p.M) continue;
+        float v = acc[i][j][r];
+        if (EPI == SE_SIM) v = p.alpha * (v * p.rs[m] * csn) + (1.f - p.alpha) * expf(-fabsf(p.tr[m] - tcn));
+        if (EPI == SE_COLSCALE) v *= csn;
+        p.C[(long long)m * p.ldc + n] = v;
+      }
+  }
+}
+
+hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st) {
+  if (a.M <= 0 || a.N <= 0) return hipSuccess;
+  a.a_kc = a.sak == 1;
+  a.b_kc = a.sbk == 1;
+  if (!a.a_kc && a.sam != 1) return hipErrorInvalidValue;
+  if (!a.b_kc && a.sbn != 1) return hipErrorInvalidValue;
+  // 16-byte loads: base aligned, the strided dimension's stride and the contiguous extent multiples of 4
+  a.a_vec = aligned16(a.A) && (a.a_kc ? (a.sam % 4 == 0 && a.K % 4 == 0) : (a.sak % 4 == 0 && a.M % 4 == 0));
+  a.b_vec = aligned16(a.B) && (a.b_kc ? (a.sbn % 4 == 0 && a.K % 4 == 0) : (a.sbk % 4 == 0 && a.N % 4 == 0));
+  const int tiles = ((a.M + TM - 1) / TM) * ((a.N + TN - 1) / TN);
+  const int grid = ((tiles + NUM_XCD - 1) / NUM_XCD) * NUM_XCD;
+#define SG_LAUNCH(AK, BK, E) hipLaunchKernelGGL((sgemm_kernel<AK, BK, E>), dim3(grid), dim3(256), 0, st, a)
+  if (epi == SE_SIM) {
+    if (a.a_kc && a.b_kc) SG_LAUNCH(true, true, SE_SIM);
+    else return hipErrorInvalidValue;
+  } else if (epi == SE_COLSCALE) {
+    if (a.a_kc && a.b_kc) SG_LAUNCH(true, true, SE_COLSCALE);
+    else return hipErrorInvalidValue;
+  } else {
+    if (a.a_kc && a.b_kc) SG_LAUNCH(true, true, SE_PLAIN);
+    else if (a.a_kc && !a.b_kc) SG_LAUNCH(true, false, SE_PLAIN);
+    else if (!a.a_kc && !a.b_kc) SG_LAUNCH(false, false, SE_PLAIN);
+    else return hipErrorInvalidValue;
+  }
+#undef SG_LAUNCH
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------- similarity helpers
+// 1 / |x_r| of every pool row (fp64 sum of squares); 0 for a zero row
+__global__ __launch_bounds__(256) void rownorm_kernel(const float *X, int N, int F, float *rinv) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= N) return;
+  const float *x = X + (long long)row * F;
+  double s = 0.0;
+  for (int j = lane; j < F; j += 64) {
+    const double v = x[j];
+    s += v * v;
+  }
+  s = wave_sum(s);
+  if (lane == 0) rinv[row] = s > 0.0 ? (float)(1.0 / sqrt(s)) : 0.f;
+}
+
+// rows, inverse norms and timestamps of one subsample gathered into dense arrays; an index outside [0, N) raises
+// the flag and is replaced by 0
+__global__ __launch_bounds__(256) void gather_kernel(const float *X, const float *rinv, const float *t, const int *idx,
+                                                     int N, int F, float *Xs, float *cs, float *tc, int *flag) {
+  const int h = blockIdx.x;
+  int s = idx[h];
+  if (s < 0 || s >= N) {
+    if (threadIdx.x == 0) atomicOr(flag, 1);
+    s = 0;
+  }
+  const float *src = X + (long long)s * F;
+  float *dst = Xs + (long long)h * F;
+  for (int j = threadIdx.x; j < F; j += 256) dst[j] = src[j];
+  if (threadIdx.x == 0) {
+    cs[h] = rinv[s];
+    tc[h] = t[s];
+  }
+}
+
+// d_r: one wavefront per row, fp64 sum
+__global__ __launch_bounds__(256) void rowsum_kernel(const float *A, int N, int n, float *dr) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= N) return;
+  const float *a = A + (long long)row * n;
+  double s = 0.0;
+  for (int j = lane; j < n; j += 64) s += (double)a[j];
+  s = wave_sum(s);
+  if (lane == 0) dr[row] = (float)s;
+}
+
+// d_c in two deterministic stages: partial sums of COL_CHUNKS row ranges, then their sum in order
+constexpr int COL_CHUNKS = 64;
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const float *A, int N, int n, double *part) {
+  __shared__ double red[4][64];
+  const int c = threadIdx.x & 63, ph = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + c;
+  const int rows_per = (N + COL_CHUNKS - 1) / COL_CHUNKS;
+  const int r0 = blockIdx.y * rows_per, r1 = min(N, r0 + rows_per);
+  double s = 0.0;
+  if (col < n)
+    for (int r = r0 + ph; r < r1; r += 4) s += (double)A[(long long)r * n + col];
+  red[ph][c] = s;
+  __syncthreads();
+  if (ph == 0 && col < n) part[(long long)blockIdx.y * n + col] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
+}
+
+__global__ __launch_bounds__(256) void colsum_final_kernel(const double *part, int n, float *dc) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= n) return;
+  double s = 0.0;
+  for (int b = 0; b < COL_CHUNKS; ++b) s += part[(long long)b * n + col];
+  dc[col] = (float)s;
+}
+
+__global__ __launch_bounds__(256) void fill_int_kernel(int *p, int count, int v) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < count) p[i] = v;
+}
+
+__global__ __launch_bounds__(256) void degree_check_kernel(const float *d, int count, int *flag) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < count) {
+    const float v = d[i];
+    if (!(v > 0.f) || !isfinite(v)) atomicOr(flag, 1);
+  }
+}
+
+__global__ __launch_bounds__(256) void normalise_kernel(float *A, const float *dr, const float *dc, int N, int n) {
+  const int nblk = (n + 255) / 256;
+  const int r = blockIdx.x / nblk;
+  const int h = (blockIdx.x % nblk) * 256 + threadIdx.x;
+  if (h >= n) return;
+  const float s = (1.f / sqrtf(dr[r])) * (1.f / sqrtf(dc[h]));
+  A[(long long)r * n + h] *= s;
+}
+
+// -------------------------------------------------------------------------- orthonormalisation (Cholesky QR)
+// partial Gram matrices of the rows of Y[kb, n] over column ranges, fp64: part[b][a][c] = sum_j Y[a, j] Y[c, j]
+__global__ __launch_bounds__(256) void gram_partial_kernel(const float *Y, int kb, int n, int jchunk, double *part) {
+  __shared__ float ys[KB_MAX][33];
+  const int tid = threadIdx.x, ta = tid >> 4, tb = tid & 15;
+  double acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[i][c] = 0.0;
+  const int j0 = blockIdx.x * jchunk, j1 = min(n, j0 + jchunk);
+  for (int jb = j0; jb < j1; jb += 32) {
+    __syncthreads();
+    for (int u = tid; u < KB_MAX * 32; u += 256) {
+      const int a = u >> 5, j = u & 31;
+      const bool ok = a < kb && jb + j < j1;
+      const float v = Y[ok ? (long long)a * n + jb + j : 0];
+      ys[a][j] = ok ? v : 0.f;
+    }
+    __syncthreads();
+    for (int j = 0; j < 32; ++j) {
+      double av[8], bv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        av[i] = (double)ys[ta * 8 + i][j];
+        bv[i] = (double)ys[tb * 8 + i][j];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[i][c] = fma(av[i], bv[c], acc[i][c]);
+    }
+  }
+  double *out = part + (long long)blockIdx.x * kb * kb;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const int a = ta * 8 + i, b = tb * 8 + c;
+      if (a < kb && b < kb) out[a * kb + b] = acc[i][c];
+    }
+}
+
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const double *part, int nparts, int kk, double *W) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= kk) return;
+  double s = 0.0;
+  for (int b = 0; b < nparts; ++b) s += part[(long long)b * kk + i];
+  W[i] = s;
+}
+
+// Cholesky factor Lc of W + shift I (= Lc Lc^T, lower) and its inverse, one workgroup, the matrix in LDS (fp64).  The
+// shift, shift_rel times the largest diagonal entry, keeps the factorisation alive when the rows are numerically
+// dependent (shifted Cholesky QR: the rows come out better conditioned, not yet orthonormal, and the next pass
+// finishes).  The strict upper triangle, unused by the factorisation, receives the inverse (Linv[i][c] at [c][i],
+// i > c).  Out: Rinv[kb, kb] fp32 = Lc^-1 (lower triangular), so that Rinv Y has orthonormal rows when the shift is
+// negligible.  With `check` set (the last pass, whose input should already be near orthonormal) a pivot below 1/4
+// raises the flag: the block has no full rank.  A non-positive pivot always raises it.
+__global__ __launch_bounds__(256) void chol_inv_kernel(const double *W, int kb, double shift_rel, int check, float *Rinv,
+                                                        int *flag) {
+  extern __shared__ double Ws[];
+  __shared__ double dmax;
+  const int tid = threadIdx.x;
+  const int ld = kb + 1;
+  for (int u = tid; u < kb * kb; u += 256) Ws[(u / kb) * ld + (u % kb)] = W[u];
+  __syncthreads();
+  if (tid == 0) {
+    double m = 0.0;
+    for (int i = 0; i < kb; ++i) m = fmax(m, Ws[i * ld + i]);
+    dmax = m;
+  }
+  __syncthreads();
+  for (int i = tid; i < kb; i += 256) Ws[i * ld + i] += shift_rel * dmax;
+  __syncthreads();
+  for (int j = 0; j < kb; ++j) {
+    double piv = Ws[j * ld + j];
+    if (!(piv > 0.0) || !isfinite(piv)) {
+      if (tid == 0) atomicOr(flag, 2);
+      piv = 1.0;
+    } else if (check && piv < 0.25) {
+      if (tid == 0) atomicOr(flag, 2);
+    }
+    const double d = sqrt(piv);
+    __syncthreads();                      // everyone has read the pivot
+    if (tid == 0) Ws[j * ld + j] = d;
+    for (int i = j + 1 + tid; i < kb; i += 256) Ws[i * ld + j] /= d;
+    __syncthreads();
+    const int w = kb - j - 1;
+    for (int u = tid; u < w * w; u += 256) {
+      const int i = j + 1 + u / w, c = j + 1 + u % w;
+      if (c <= i) Ws[i * ld + c] -= Ws[i * ld + j] * Ws[c * ld + j];
+    }
+    __syncthreads();
+  }
+  // inverse, one column per thread: x_c = 1 / l_cc, x_i = -(sum_{p=c}^{i-1} l_ip x_p) / l_ii
+  for (int c = tid; c < kb; c += 256) {
+    const double xc = 1.0 / Ws[c * ld + c];
+    for (int i = c + 1; i < kb; ++i) {
+      double s = Ws[i * ld + c] * xc;
+      for (int q = c + 1; q < i; ++q) s = fma(Ws[i * ld + q], Ws[c * ld + q], s);
+      Ws[c * ld + i] = -s / Ws[i * ld + i];
+    }
+  }
+  __syncthreads();
+  for (int u = tid; u < kb * kb; u += 256) {
+    const int i = u / kb, c = u % kb;
+    double v = 0.0;
+    if (i == c) v = 1.0 / Ws[i * ld + i];
+    else if (i > c) v = Ws[c * ld + i];
+    Rinv[u] = (float)v;
+  }
+}
+
+// ------------------------------------------------------------------------------- Rayleigh-Ritz (Jacobi)
+// Eigenvectors of the symmetric positive semi-definite T[kb, kb] by one-sided Jacobi rotations on the rows of a copy
+// M of T (fp64, LDS): rotations from the left make the rows mutually orthogonal; then row j = lambda_j v_j^T.  Pairs
+// of a round are disjoint (round-robin schedule) and rotate concurrently, one pair per wavefront at a time.  Out: the
+// k eigenvectors of largest eigenvalue as rows of Wk[k, kb], eigenvalues lam[k] (descending), inv_sigma[k] =
+// lam^-1/2, sigma[k] = lam^1/2.
+__global__ __launch_bounds__(1024) void jacobi_kernel(const float *T, int kb, int k, int max_sweeps, float *Wk,
+                                                       float *lam, float *inv_sigma, float *sigma) {
+  extern __shared__ double Ms[];
+  __shared__ int rotated;
+  __shared__ double nrm[KB_MAX];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int u = tid; u < kb * kb; u += 1024) {
+    const int i = u / kb, j = u % kb;
+    Ms[u] = 0.5 * ((double)T[i * kb + j] + (double)T[j * kb + i]);
+  }
+  if (tid == 0) rotated = 0;
+  __syncthreads();
+  const int half = kb / 2, ring = kb - 1;
+  for (int sweep = 0; sweep < max_sweeps; ++sweep) {
+    for (int round = 0; round < ring; ++round) {
+      for (int pr = wave; pr < half; pr += 16) {
+        const int a = pr == 0 ? round : (round + pr) % ring;
+        const int b = pr == 0 ? ring : (round - pr + ring) % ring;
+        double *ra = Ms + a * kb, *rb = Ms + b * kb;
+        const bool has1 = lane + 64 < kb;
+        const double x0 = lane < kb ? ra[lane] : 0.0, x1 = has1 ? ra[lane + 64] : 0.0;
+        const double y0 = lane < kb ? rb[lane] : 0.0, y1 = has1 ? rb[lane + 64] : 0.0;
+        const double al = wave_sum(x0 * x0 + x1 * x1);
+        const double be = wave_sum(y0 * y0 + y1 * y1);
+        const double ga = wave_sum(x0 * y0 + x1 * y1);
+        if (al > 0.0 && be > 0.0 && fabs(ga) > 1e-13 * sqrt(al * be)) {
+          const double zeta = (be - al) / (2.0 * ga);
+          const double tt = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+          const double c = 1.0 / sqrt(1.0 + tt * tt), s = c * tt;
+          if (lane < kb) {
+            ra[lane] = c * x0 - s * y0;
+            rb[lane] = s * x0 + c * y0;
+          }
+          if (has1) {
+            ra[lane + 64] = c * x1 - s * y1;
+            rb[lane + 64] = s * x1 + c * y1;
+          }
+          if (lane == 0) rotated = 1;
+        }
+      }
+      __syncthreads();
+    }
+    const int any = rotated;
+    __syncthreads();
+    if (tid == 0) rotated = 0;
+    __syncthreads();
+    if (!any) break;
+  }
+  // eigenvalues = row norms; rank them (descending, ties to the lower row)
+  for (int j = wave; j < kb; j += 16) {
+    const double x0 = lane < kb ? Ms[j * kb + lane] : 0.0, x1 = lane + 64 < kb ? Ms[j * kb + lane + 64] : 0.0;
+    const double s = wave_sum(x0 * x0 + x1 * x1);
+    if (lane == 0) nrm[j] = sqrt(s);
+  }
+  __syncthreads();
+  for (int j = wave; j < kb; j += 16) {
+    int rank = 0;
+    const double mine = nrm[j];
+    for (int i = 0; i < kb; ++i) rank += (nrm[i] > mine || (nrm[i] == mine && i < j)) ? 1 : 0;
+    if (rank < k) {
+      const double inv = mine > 0.0 ? 1.0 / mine : 0.0;
+      for (int c = lane; c < kb; c += 64) Wk[rank * kb + c] = (float)(Ms[j * kb + c] * inv);
+      if (lane == 0) {
+        lam[rank] = (float)mine;
+        sigma[rank] = (float)sqrt(mine);
+        inv_sigma[rank] = mine > 0.0 ? (float)(1.0 / sqrt(mine)) : 0.f;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------- k-means
+__global__ __launch_bounds__(256) void kmeans_init_kernel(const float *U, int N, int d, int k, const int *init_idx,
+                                                          float *centres, int *flag) {
+  const int c = blockIdx.x;
+  int r = init_idx[c];
+  if (r < 0 || r >= N) {
+    if (threadIdx.x == 0) atomicOr(flag, 1);
+    r = 0;
+  }
+  for (int j = threadIdx.x; j < d; j += 256) centres[c * d + j] = U[(long long)r * d + j];
+}
+
+// assignment pass: 64 rows per workgroup staged in LDS beside the centres; thread (row, g) scans the centres
+// c = g, g + 4, ...; the four candidates of a row are merged with ties to the lowest centre
+__global__ __launch_bounds__(256) void kmeans_assign_kernel(const float *U, int N, int d, const float *centres, int k,
+                                                            int *labels, int *changed) {
+  extern __shared__ float sm[];
+  float *cs = sm;                       // [k][d]
+  float *us = sm + k * d;               // [64][d + 1]
+  __shared__ float bd[4][64];
+  __shared__ int bi[4][64];
+  const int tid = threadIdx.x, row = tid & 63, g = tid >> 6;
+  const int r0 = blockIdx.x * 64;
+  for (int u = tid; u < k * d; u += 256) cs[u] = centres[u];
+  for (int u = tid; u < 64 * d; u += 256) {
+    const int rr = u / d, j = u % d;
+    const bool ok = r0 + rr < N;
+    const float v = U[ok ? (long long)(r0 + rr) * d + j : 0];
+    us[rr * (d + 1) + j] = ok ? v : 0.f;
+  }
+  __syncthreads();
+  float best = INFINITY;
+  int besti = 0x7fffffff;
+  const float *u = us + row * (d + 1);
+  for (int c = g; c < k; c += 4) {
+    const float *cc = cs + c * d;
+    float s = 0.f;
+    for (int j = 0; j < d; ++j) {
+      const float df = u[j] - cc[j];
+      s = fmaf(df, df, s);
+    }
+    if (s < best) {
+      best = s;
+      besti = c;
+    }
+  }
+  bd[g][row] = best;
+  bi[g][row] = besti;
+  __syncthreads();
+  if (g == 0 && r0 + row < N) {
+    for (int q = 1; q < 4; ++q) {
+      const float s = bd[q][row];
+      const int c = bi[q][row];
+      if (s < best || (s == best && c < besti)) {
+        best = s;
+        besti = c;
+      }
+    }
+    if (labels[r0 + row] != besti) {
+      labels[r0 + row] = besti;
+      atomicAdd(changed, 1);
+    }
+  }
+}
+
+// update pass: workgroup (c, dimension chunk of 32); thread (phase, j) adds the member rows r = phase, phase + 8, ...
+// in ascending order in fp64, the eight phases are added in order; an empty cluster keeps its centre
+__global__ __launch_bounds__(256) void kmeans_update_kernel(const float *U, int N, int d, const int *labels,
+                                                            float *centres) {
+  __shared__ double red[8][32];
+  __shared__ int cnt[8];
+  const int c = blockIdx.x, j = blockIdx.y * 32 + (threadIdx.x & 31), ph = threadIdx.x >> 5;
+  double s = 0.0;
+  int m = 0;
+  for (int r = ph; r < N; r += 8)
+    if (labels[r] == c) {
+      ++m;
+      if (j < d) s += (double)U[(long long)r * d + j];
+    }
+  red[ph][threadIdx.x & 31] = s;
+  if ((threadIdx.x & 31) == 0) cnt[ph] = m;
+  __syncthreads();
+  if (ph == 0 && j < d) {
+    double tot = 0.0;
+    int mt = 0;
+    for (int q = 0; q < 8; ++q) {
+      tot += red[q][threadIdx.x & 31];
+      mt += cnt[q];
+    }
+    if (mt > 0) centres[c * d + j] = (float)(tot / (double)mt);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------- aggregation
+__device__ __forceinline__ int clamp_label(int v, int k) { return v < 0 ? 0 : (v >= k ? k - 1 : v); }
+
+__global__ __launch_bounds__(256) void contingency_kernel(const int *a, const int *b, int N, int k, int *T) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r < N) atomicAdd(&T[clamp_label(a[r], k) * k + clamp_label(b[r], k)], 1);
+}
+
+// greedy renaming, one workgroup: k times take the largest remaining count (ties to the lowest flat index), fix
+// perm[column] = row, retire the row and the column
+__global__ __launch_bounds__(256) void greedy_match_kernel(const int *T, int k, int *perm) {
+  __shared__ int rdone[KB_MAX], cdone[KB_MAX];
+  __shared__ int bv[256], bx[256];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < k; i += 256) rdone[i] = cdone[i] = 0;
+  __syncthreads();
+  for (int it = 0; it < k; ++it) {
+    int best = -1, besti = 0x7fffffff;
+    for (int u = tid; u < k * k; u += 256) {
+      const int p = u / k, q = u % k;
+      if (rdone[p] || cdone[q]) continue;
+      const int v = T[u];
+      if (v > best) {          // u ascends, so the first maximum of this thread is its lowest index
+        best = v;
+        besti = u;
+      }
+    }
+    bv[tid] = best;
+    bx[tid] = besti;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+      if (tid < o) {
+        const int v = bv[tid + o], x = bx[tid + o];
+        if (v > bv[tid] || (v == bv[tid] && x < bx[tid])) {
+          bv[tid] = v;
+          bx[tid] = x;
+        }
+      }
+      __syncthreads();
+    }
+    if (tid == 0) {
+      const int p = bx[0] / k, q = bx[0] % k;
+      perm[q] = p;
+      rdone[p] = 1;
+      cdone[q] = 1;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void identity_perm_kernel(int *perm, int k) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < k) perm[i] = i;
+}
+
+__global__ __launch_bounds__(256) void vote_kernel(const int *labels, const int *perm, int m, int N, int k, int *out) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= N) return;
+  int name[M_MAX];
+  for (int i = 0; i < m; ++i) name[i] = perm[i * k + clamp_label(labels[(long long)i * N + r], k)];
+  int best = 0, pick = name[0];
+  for (int i = 0; i < m; ++i) {
+    int votes = 0;
+    for (int q = 0; q < m; ++q) votes += name[q] == name[i] ? 1 : 0;
+    if (votes > best) {      // strict: the earliest vector among the most frequent names wins
+      best = votes;
+      pick = name[i];
+    }
+  }
+  out[r] = pick;
+}
+
+// ------------------------------------------------------------------------------------------- host side
+struct Carve {
+  char *base;
+  size_t off = 0;
+  explicit Carve(void *b) : base(static_cast<char *>(b)) {}
+  template <class T>
+  T *take(size_t count) {
+    off = (off + 255) & ~size_t(255);
+    T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+int gram_parts(int n) { return (n + 511) / 512; }
+
+struct SimWork {
+  float *rinv, *Xs, *cs, *tc;
+  double *colpart;
+  int *flag;
+  size_t bytes;
+  SimWork(void *w, int N, int F, int n) {
+    Carve c(w);
+    flag = c.take<int>(64);
+    rinv = c.take<float>(N);
+    Xs = c.take<float>((size_t)n * F);
+    cs = c.take<float>(n);
+    tc = c.take<float>(n);
+    colpart = c.take<double>((size_t)COL_CHUNKS * n);
+    bytes = c.off + 256;
+  }
+};
+
+struct EmbedWork {
+  float *G, *Q, *Y, *Z, *T, *Wk, *Qk, *lam, *isig, *Rinv;
+  double *part, *W;
+  int *flag;
+  size_t bytes;
+  EmbedWork(void *w, int n, int k, int kb) {
+    Carve c(w);
+    flag = c.take<int>(64);
+    G = c.take<float>((size_t)n * n);
+    Q = c.take<float>((size_t)kb * n);
+    Y = c.take<float>((size_t)kb * n);
+    Z = c.take<float>((size_t)kb * n);
+    T = c.take<float>((size_t)kb * kb);
+    Wk = c.take<float>((size_t)k * kb);
+    Qk = c.take<float>((size_t)k * n);
+    lam = c.take<float>(k);
+    isig = c.take<float>(k);
+    Rinv = c.take<float>((size_t)kb * kb);
+    part = c.take<double>((size_t)gram_parts(n) * kb * kb);
+    W = c.take<double>((size_t)kb * kb);
+    bytes = c.off + 256;
+  }
+};
+
+struct SmallWork {      // k-means, aggregation, normalisation
+  int *flag, *changed, *T, *perm;
+  size_t bytes;
+  SmallWork(void *w, int k) {
+    Carve c(w);
+    flag = c.take<int>(64);
+    changed = c.take<int>(64);
+    T = c.take<int>((size_t)k * k);
+    perm = c.take<int>((size_t)M_MAX * k);
+    bytes = c.off + 256;
+  }
+};
+
+struct ClusterWork {
+  float *A, *dr, *dc, *U, *sigma, *centres;
+  void *sub;            // region handed to the calls above
+  size_t sub_bytes, bytes;
+  ClusterWork(void *w, int N, int F, int n, int k, int kb) {
+    Carve c(w);
+    A = c.take<float>((size_t)N * n);
+    dr = c.take<float>(N);
+    dc = c.take<float>(n);
+    U = c.take<float>((size_t)N * k);
+    sigma = c.take<float>(k);
+    centres = c.take<float>((size_t)k * k);
+    size_t s1 = SimWork(nullptr, N, F, n).bytes, s2 = EmbedWork(nullptr, n, k, kb).bytes, s3 = SmallWork(nullptr, k).bytes;
+    sub_bytes = s1 > s2 ? s1 : s2;
+    if (s3 > sub_bytes) sub_bytes = s3;
+    sub = c.take<char>(sub_bytes);
+    bytes = c.off + 256;
+  }
+};
+
+int check_dims(int N, int F, int n, int k, int kb) {
+  if (N < 1 || F < 1 || n < 1 || k < 1 || kb < 1) TAP_FAIL(QC_ERR_SHAPE, "N, F, n, k, kb must be positive");
+  if (kb > KB_MAX || kb % 8) TAP_FAIL(QC_ERR_UNSUPPORTED, "kb must be a multiple of 8 and at most %d (got %d)", KB_MAX, kb);
+  if (k > kb) TAP_FAIL(QC_ERR_SHAPE, "k (%d) exceeds kb (%d)", k, kb);
+  if (kb > n) TAP_FAIL(QC_ERR_SHAPE, "kb (%d) exceeds the subsample size n (%d)", kb, n);
+  if (n > N) TAP_FAIL(QC_ERR_SHAPE, "n (%d) exceeds N (%d)", n, N);
+  if ((long long)N * (n > F ? n : F) >= (1ll << 31)) TAP_FAIL(QC_ERR_UNSUPPORTED, "N * max(n, F) must be below 2^31");
+  return QC_OK;
+}
+
+// reads a device flag word after waiting for the stream
+int read_flag(const int *flag, hipStream_t st, int *out) {
+  TAP_HIP(hipMemcpyAsync(out, flag, sizeof(int), hipMemcpyDeviceToHost, st));
+  TAP_HIP(hipStreamSynchronize(st));
+  return QC_OK;
+}
+
+int similarity_impl(const float *X, const float *t, int N, int F, const int *idx, int n, float alpha, float *A,
+                    float *d_r, float *d_c, void *work, hipStream_t st) {
+  SimWork w(work, N, F, n);
+  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
+  hipLaunchKernelGGL(rownorm_kernel, dim3((N + 3) / 4), dim3(256), 0, st, X, N, F, w.rinv);
+  hipLaunchKernelGGL(gather_kernel, dim3(n), dim3(256), 0, st, X, w.rinv, t, idx, N, F, w.Xs, w.cs, w.tc, w.flag);
+  TAP_HIP(hipGetLastError());
+  SgemmArgs g{};
+  g.A = X; g.sam = F; g.sak = 1;
+  g.B = w.Xs; g.sbn = F; g.sbk = 1;
+  g.C = A; g.ldc = n;
+  g.M = N; g.N = n; g.K = F;
+  g.rs = w.rinv; g.cs = w.cs; g.tr = t; g.tc = w.tc; g.alpha = alpha;
+  TAP_HIP(sgemm(g, SE_SIM, st));
+  hipLaunchKernelGGL(rowsum_kernel, dim3((N + 3) / 4), dim3(256), 0, st, A, N, n, d_r);
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3((n + 63) / 64, COL_CHUNKS), dim3(256), 0, st, A, N, n, w.colpart);
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((n + 255) / 256), dim3(256), 0, st, w.colpart, n, d_c);
+  TAP_HIP(hipGetLastError());
+  int flag = 0;
+  TAP_RC(read_flag(w.flag, st, &flag));
+  if (flag) TAP_FAIL(QC_ERR_RANGE, "a subsample index lies outside [0, %d)", N);
+  return QC_OK;
+}
+
+int normalise_impl(float *A, const float *d_r, const float *d_c, int N, int n, void *work, hipStream_t st) {
+  SmallWork w(work, 1);
+  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
+  hipLaunchKernelGGL(degree_check_kernel, dim3((N + 255) / 256), dim3(256), 0, st, d_r, N, w.flag);
+  hipLaunchKernelGGL(degree_check_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_c, n, w.flag);
+  TAP_HIP(hipGetLastError());
+  int flag = 0;
+  TAP_RC(read_flag(w.flag, st, &flag));
+  if (flag) TAP_FAIL(QC_ERR_RANGE, "a degree of the similarity matrix is not positive and finite");
+  hipLaunchKernelGGL(normalise_kernel, dim3(((n + 255) / 256) * N), dim3(256), 0, st, A, d_r, d_c, N, n);
+  TAP_HIP(hipGetLastError());
+  TAP_HIP(hipStreamSynchronize(st));
+  return QC_OK;
+}
+
+hipError_t set_lds(const void *kern, size_t bytes) {
+  return hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+// one pass of shifted Cholesky QR on the rows of `in` [kb, n] into `out` (`in` and `out` must differ)
+int cholqr_pass(const float *in, float *out, int kb, int n, int check, EmbedWork &w, hipStream_t st) {
+  const int parts = gram_parts(n);
+  hipLaunchKernelGGL(gram_partial_kernel, dim3(parts), dim3(256), 0, st, in, kb, n, 512, w.part);
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3((kb * kb + 255) / 256), dim3(256), 0, st, w.part, parts, kb * kb, w.W);
+  const size_t lds = (size_t)kb * (kb + 1) * sizeof(double);
+  TAP_HIP(set_lds((const void *)chol_inv_kernel, lds));
+  hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(256), lds, st, w.W, kb, 1e-12, check, w.Rinv, w.flag);
+  TAP_HIP(hipGetLastError());
+  SgemmArgs g{};
+  g.A = w.Rinv; g.sam = kb; g.sak = 1;
+  g.B = in; g.sbn = 1; g.sbk = n;
+  g.C = out; g.ldc = n;
+  g.M = kb; g.N = n; g.K = kb;
+  TAP_HIP(sgemm(g, SE_PLAIN, st));
+  return QC_OK;
+}
+
+// rows of `in` made orthonormal into w.Q: three passes, which is enough for a block whose condition number is as
+// large as 10^12 (the power iteration multiplies by L^T L, whose small eigenvalues are rounding noise in fp32); uses
+// w.Z and w.Y as intermediates (`in` may be w.Y)
+int orthonormalise(const float *in, EmbedWork &w, int kb, int n, hipStream_t st) {
+  TAP_RC(cholqr_pass(in, w.Z, kb, n, 0, w, st));
+  TAP_RC(cholqr_pass(w.Z, w.Y, kb, n, 0, w, st));
+  TAP_RC(cholqr_pass(w.Y, w.Q, kb, n, 1, w, st));
+  return QC_OK;
+}
+
+int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const float *q0, float *U, float *sigma,
+               void *work, hipStream_t st) {
+  EmbedWork w(work, n, k, kb);
+  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
+  TAP_HIP(hipGetLastError());
+  // G = L^T L
+  SgemmArgs g{};
+  g.A = L; g.sam = 1; g.sak = n;
+  g.B = L; g.sbn = 1; g.sbk = n;
+  g.C = w.G; g.ldc = n;
+  g.M = n; g.N = n; g.K = N;
+  TAP_HIP(sgemm(g, SE_PLAIN, st));
+  TAP_RC(orthonormalise(q0, w, kb, n, st));
+  SgemmArgs mul{};
+  mul.A = w.Q; mul.sam = n; mul.sak = 1;
+  mul.B = w.G; mul.sbn = n; mul.sbk = 1;      // G is symmetric
+  mul.C = w.Y; mul.ldc = n;
+  mul.M = kb; mul.N = n; mul.K = n;
+  for (int it = 0; it < iters; ++it) {
+    TAP_HIP(sgemm(mul, SE_PLAIN, st));
+    TAP_RC(orthonormalise(w.Y, w, kb, n, st));
+  }
+  // Rayleigh-Ritz: T = Q G Q^T, its k leading eigenvectors, Qk = Wk Q
+  TAP_HIP(sgemm(mul, SE_PLAIN, st));
+  SgemmArgs tt{};
+  tt.A = w.Y; tt.sam = n; tt.sak = 1;
+  tt.B = w.Q; tt.sbn = n; tt.sbk = 1;
+  tt.C = w.T; tt.ldc = kb;
+  tt.M = kb; tt.N = kb; tt.K = n;
+  TAP_HIP(sgemm(tt, SE_PLAIN, st));
+  const size_t lds = (size_t)kb * kb * sizeof(double);
+  TAP_HIP(set_lds((const void *)jacobi_kernel, lds));
+  hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(1024), lds, st, w.T, kb, k, 30, w.Wk, w.lam, w.isig, sigma);
+  TAP_HIP(hipGetLastError());
+  SgemmArgs qk{};
+  qk.A = w.Wk; qk.sam = kb; qk.sak = 1;
+  qk.B = w.Q; qk.sbn = 1; qk.sbk = n;
+  qk.C = w.Qk; qk.ldc = n;
+  qk.M = k; qk.N = n; qk.K = kb;
+  TAP_HIP(sgemm(qk, SE_PLAIN, st));
+  // U = L Qk^T diag(1 / sigma)
+  SgemmArgs u{};
+  u.A = L; u.sam = n; u.sak = 1;
+  u.B = w.Qk; u.sbn = n; u.sbk = 1;
+  u.C = U; u.ldc = k;
+  u.M = N; u.N = k; u.K = n;
+  u.cs = w.isig;
+  TAP_HIP(sgemm(u, SE_COLSCALE, st));
+  int flag = 0;
+  TAP_RC(read_flag(w.flag, st, &flag));
+  if (flag) TAP_FAIL(QC_ERR_RANGE, "the iteration block has no full rank (a zero start vector, or fewer than kb independent directions)");
+  return QC_OK;
+}
+
+int kmeans_impl(const float *U, int N, int d, int k, const int *init_idx, int max_iter, int *labels, float *centres,
+                int *passes_out, void *work, hipStream_t st) {
+  SmallWork w(work, k);
+  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
+  hipLaunchKernelGGL(fill_int_kernel, dim3((N + 255) / 256), dim3(256), 0, st, labels, N, -1);
+  hipLaunchKernelGGL(kmeans_init_kernel, dim3(k), dim3(256), 0, st, U, N, d, k, init_idx, centres, w.flag);
+  TAP_HIP(hipGetLastError());
+  int flag = 0;
+  TAP_RC(read_flag(w.flag, st, &flag));
+  if (flag) TAP_FAIL(QC_ERR_RANGE, "an initial-centre index lies outside [0, %d)", N);
+  const size_t lds = ((size_t)k * d + (size_t)64 * (d + 1)) * sizeof(float);
+  TAP_HIP(set_lds((const void *)kmeans_assign_kernel, lds));
+  int passes = 0;
+  for (int it = 0; it < max_iter; ++it) {
+    hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.changed, 64, 0);
+    hipLaunchKernelGGL(kmeans_assign_kernel, dim3((N + 63) / 64), dim3(256), lds, st, U, N, d, centres, k, labels,
+                       w.changed);
+    TAP_HIP(hipGetLastError());
+    ++passes;
+    int changed = 0;
+    TAP_RC(read_flag(w.changed, st, &changed));
+    if (changed == 0) break;
+    hipLaunchKernelGGL(kmeans_update_kernel, dim3(k, (d + 31) / 32), dim3(256), 0, st, U, N, d, labels, centres);
+    TAP_HIP(hipGetLastError());
+  }
+  TAP_HIP(hipStreamSynchronize(st));
+  if (passes_out) *passes_out = passes;
+  return QC_OK;
+}
+
+int aggregate_impl(const int *labels, int m, int N, int k, int *out, int *perm_out, void *work, hipStream_t st) {
+  SmallWork w(work, k);
+  hipLaunchKernelGGL(identity_perm_kernel, dim3((k + 255) / 256), dim3(256), 0, st, w.perm, k);
+  for (int i = 1; i < m; ++i) {
+    hipLaunchKernelGGL(fill_int_kernel, dim3((k * k + 255) / 256), dim3(256), 0, st, w.T, k * k, 0);
+    hipLaunchKernelGGL(contingency_kernel, dim3((N + 255) / 256), dim3(256), 0, st, labels, labels + (size_t)i * N, N, k, w.T);
+    hipLaunchKernelGGL(greedy_match_kernel, dim3(1), dim3(256), 0, st, w.T, k, w.perm + (size_t)i * k);
+  }
+  hipLaunchKernelGGL(vote_kernel, dim3((N + 255) / 256), dim3(256), 0, st, labels, w.perm, m, N, k, out);
+  TAP_HIP(hipGetLastError());
+  if (perm_out) TAP_HIP(hipMemcpyAsync(perm_out, w.perm, (size_t)m * k * sizeof(int), hipMemcpyDeviceToDevice, st));
+  return QC_OK;
+}
+
+int check_work(const void *work, size_t have, size_t need) {
+  if (!work) TAP_FAIL(QC_ERR_NULL, "work is NULL");
+  if (!aligned16(work)) TAP_FAIL(QC_ERR_ALIGN, "work must be 16-byte aligned");
+  if (have < need) TAP_FAIL(QC_ERR_WORKSPACE, "workspace of %zu bytes is too small (%zu needed)", have, need);
+  return QC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int qc_tap_workspace_bytes(int N, int F, int n, int k, int kb, size_t *bytes_out) {
+  if (!bytes_out) TAP_FAIL(QC_ERR_NULL, "bytes_out is NULL");
+  TAP_RC(check_dims(N, F, n, k, kb));
+  *bytes_out = ClusterWork(nullptr, N, F, n, k, kb).bytes;
+  return QC_OK;
+}
+
+int qc_tap_similarity(const float *X, const float *t, int N, int F, const int *idx, int n, float alpha, float *A,
+                      float *d_r, float *d_c, void *work, size_t work_bytes, void *stream) {
+  if (!X || !t || !idx || !A || !d_r || !d_c) TAP_FAIL(QC_ERR_NULL, "a required pointer is NULL");
+  if (N < 1 || F < 1 || n < 1) TAP_FAIL(QC_ERR_SHAPE, "N, F, n must be positive");
+  if (n > N) TAP_FAIL(QC_ERR_SHAPE, "n (%d) exceeds N (%d)", n, N);
+  if ((long long)N * (n > F ? n : F) >= (1ll << 31)) TAP_FAIL(QC_ERR_UNSUPPORTED, "N * max(n, F) must be below 2^31");
+  if (!(alpha >= 0.f && alpha <= 1.f)) TAP_FAIL(QC_ERR_RANGE, "alpha must lie in [0, 1]");
+  if (!aligned16(X) || !aligned16(A)) TAP_FAIL(QC_ERR_ALIGN, "X and A must be 16-byte aligned");
+  TAP_RC(check_work(work, work_bytes, SimWork(nullptr, N, F, n).bytes));
+  return similarity_impl(X, t, N, F, idx, n, alpha, A, d_r, d_c, work, static_cast<hipStream_t>(stream));
+}
+
+int qc_tap_normalise(float *A, const float *d_r, const float *d_c, int N, int n, void *work, size_t work_bytes,
+                     void *stream) {
+  if (!A || !d_r || !d_c) TAP_FAIL(QC_ERR_NULL, "a required pointer is NULL");
+  if (N < 1 || n < 1) TAP_FAIL(QC_ERR_SHAPE, "N and n must be positive");
+  if ((long long)N * n >= (1ll << 31)) TAP_FAIL(QC_ERR_UNSUPPORTED, "N * n must be below 2^31");
+  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, 1).bytes));
+  return normalise_impl(A, d_r, d_c, N, n, work, static_cast<hipStream_t>(stream));
+}
+
+int qc_tap_embed(const float *L, int N, int n, int k, int kb, int iters, const float *q0, float *U, float *sigma,
+                 void *work, size_t work_bytes, void *stream) {
+  if (!L || !q0 || !U || !sigma) TAP_FAIL(QC_ERR_NULL, "a required pointer is NULL");
+  TAP_RC(check_dims(N, 1, n, k, kb));
+  if (iters < 0 || iters > 1000) TAP_FAIL(QC_ERR_RANGE, "iters must lie in [0, 1000]");
+  if (!aligned16(L) || !aligned16(q0) || !aligned16(U)) TAP_FAIL(QC_ERR_ALIGN, "L, q0 and U must be 16-byte aligned");
+  TAP_RC(check_work(work, work_bytes, EmbedWork(nullptr, n, k, kb).bytes));
+  return embed_impl(L, N, n, k, kb, iters, q0, U, sigma, work, static_cast<hipStream_t>(stream));
+}
+
+int qc_tap_kmeans(const float *U, int N, int d, int k, const int *init_idx, int max_iter, int *labels, float *centres,
+                  int *passes_out, void *work, size_t work_bytes, void *stream) {
+  if (!U || !init_idx || !labels || !centres) TAP_FAIL(QC_ERR_NULL, "a required pointer is NULL");
+  if (N < 1 || d < 1 || k < 1) TAP_FAIL(QC_ERR_SHAPE, "N, d, k must be positive");
+  if (d > KB_MAX || k > KB_MAX) TAP_FAIL(QC_ERR_UNSUPPORTED, "d and k must be at most %d", KB_MAX);
+  if ((long long)N * d >= (1ll << 31)) TAP_FAIL(QC_ERR_UNSUPPORTED, "N * d must be below 2^31");
+  if (max_iter < 1) TAP_FAIL(QC_ERR_RANGE, "max_iter must be at least 1");
+  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, k).bytes));
+  return kmeans_impl(U, N, d, k, init_idx, max_iter, labels, centres, passes_out, work, static_cast<hipStream_t>(stream));
+}
+
+int qc_tap_aggregate(const int *labels, int m, int N, int k, int *out, int *perm_out, void *work, size_t work_bytes,
+                     void *stream) {
+  if (!labels || !out) TAP_FAIL(QC_ERR_NULL, "a required pointer is NULL");
+  if (m < 1 || N < 1 || k < 1) TAP_FAIL(QC_ERR_SHAPE, "m, N, k must be positive");
+  if (m > M_MAX) TAP_FAIL(QC_ERR_UNSUPPORTED, "at most %d label vectors", M_MAX);
+  if (k > KB_MAX) TAP_FAIL(QC_ERR_UNSUPPORTED, "k must be at most %d", KB_MAX);
+  if ((long long)m * N >= (1ll << 31)) TAP_FAIL(QC_ERR_UNSUPPORTED, "m * N must be below 2^31");
+  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, k).bytes));
+  return aggregate_impl(labels, m, N, k, out, perm_out, work, static_cast<hipStream_t>(stream));
+}
+
+int qc_tap_cluster(const float *X, const float *t, int N, int F, const int *subsamples, int m, int n, float alpha,
+                   int k, int kb, int iters, const float *q0, const int *init_idx, int max_iter, int *labels_out,
+                   int *per_labels, void *work, size_t work_bytes, void *stream) {
+  if (!X || !t || !subsamples || !q0 || !init_idx || !labels_out || !per_labels)
+    TAP_FAIL(QC_ERR_NULL, "a required pointer is NULL");
+  TAP_RC(check_dims(N, F, n, k, kb));
+  if (m < 1 || m > M_MAX) TAP_FAIL(QC_ERR_UNSUPPORTED, "m must lie in [1, %d]", M_MAX);
+  if (!(alpha >= 0.f && alpha <= 1.f)) TAP_FAIL(QC_ERR_RANGE, "alpha must lie in [0, 1]");
+  if (iters < 0 || iters > 1000) TAP_FAIL(QC_ERR_RANGE, "iters must lie in [0, 1000]");
+  if (max_iter < 1) TAP_FAIL(QC_ERR_RANGE, "max_iter must be at least 1");
+  if (!aligned16(X) || !aligned16(q0)) TAP_FAIL(QC_ERR_ALIGN, "X and q0 must be 16-byte aligned");
+  ClusterWork w(work, N, F, n, k, kb);
+  TAP_RC(check_work(work, work_bytes, w.bytes));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int i = 0; i < m; ++i) {
+    TAP_RC(similarity_impl(X, t, N, F, subsamples + (size_t)i * n, n, alpha, w.A, w.dr, w.dc, w.sub, st));
+    TAP_RC(normalise_impl(w.A, w.dr, w.dc, N, n, w.sub, st));
+    TAP_RC(embed_impl(w.A, N, n, k, kb, iters, q0, w.U, w.sigma, w.sub, st));
+    TAP_RC(kmeans_impl(w.U, N, k, k, init_idx + (size_t)i * k, max_iter, per_labels + (size_t)i * N, w.centres, nullptr,
+                       w.sub, st));
+  }
+  TAP_RC(aggregate_impl(per_labels, m, N, k, labels_out, nullptr, w.sub, st));
+  TAP_HIP(hipStreamSynchronize(st));
+  return QC_OK;
+}
+
+}  // extern "C"

@@ -20,14 +20,19 @@ def qc():
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "qc.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(qc_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for h in sorted(os.listdir(inc)):
+        if h.endswith(".h"):
+            text = open(os.path.join(inc, h)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(qc_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol(qc):
     names = _declared()
-    assert len(names) >= 20 and "qc_sample_step" in names and "qc_w8a8_linear" in names
+    assert len(names) >= 27 and "qc_sample_step" in names and "qc_w8a8_linear" in names and "qc_tap_cluster" in names
     for n in names:
         assert hasattr(qc.lib, n), n
 
@@ -139,6 +144,44 @@ def test_single_op_argument_checks_without_a_device(qc):
     assert qc.lib.qc_vc_fit(f, f, 1, 4, 8, 8, -1.0, f, f, None) == -4
     assert qc.lib.qc_vc_fit(f, f, 1, 4, 8, 8, float("nan"), f, f, None) == -4
     assert qc.lib.qc_vc_fit(f, f, 1, 4, 8, 8, 1e-3, C.c_void_p(0x1004), f, None) == -3
+
+
+def test_clustering_argument_checks_without_a_device(qc):
+    f, n = C.c_void_p(0x1000), C.c_size_t()
+    L = qc.lib
+    assert L.qc_tap_workspace_bytes(1024, 64, 128, 8, 16, C.byref(n)) == 0 and n.value > 1024 * 128 * 4
+    small = n.value
+    assert L.qc_tap_workspace_bytes(2048, 64, 128, 8, 16, C.byref(n)) == 0 and n.value > small
+    assert L.qc_tap_workspace_bytes(1024, 64, 128, 8, 16, None) == -1
+    for args, code in [((0, 64, 128, 8, 16), -2), ((1024, 64, 128, 8, 12), -7), ((1024, 64, 128, 8, 136), -7),
+                       ((1024, 64, 128, 24, 16), -2), ((1024, 64, 8, 8, 16), -2), ((100, 64, 128, 8, 16), -2),
+                       ((1 << 20, 4096, 128, 8, 16), -7)]:
+        assert L.qc_tap_workspace_bytes(*args, C.byref(n)) == code, args
+        assert qc.last_error()
+    big = C.c_size_t(1 << 40)
+    assert L.qc_tap_similarity(None, f, 64, 8, f, 16, 0.5, f, f, f, f, big, None) == -1
+    assert L.qc_tap_similarity(f, f, 64, 8, f, 16, 1.5, f, f, f, f, big, None) == -4
+    assert L.qc_tap_similarity(f, f, 64, 8, f, 16, float("nan"), f, f, f, f, big, None) == -4
+    assert L.qc_tap_similarity(f, f, 64, 8, f, 65, 0.5, f, f, f, f, big, None) == -2
+    assert L.qc_tap_similarity(C.c_void_p(0x1004), f, 64, 8, f, 16, 0.5, f, f, f, f, big, None) == -3
+    assert L.qc_tap_similarity(f, f, 64, 8, f, 16, 0.5, f, f, f, f, C.c_size_t(16), None) == -6
+    assert L.qc_tap_similarity(f, f, 64, 8, f, 16, 0.5, f, f, f, None, big, None) == -1
+    assert L.qc_tap_normalise(None, f, f, 64, 16, f, big, None) == -1
+    assert L.qc_tap_normalise(f, f, f, 0, 16, f, big, None) == -2
+    assert L.qc_tap_embed(f, 64, 16, 4, 8, 5, f, f, None, f, big, None) == -1
+    assert L.qc_tap_embed(f, 64, 16, 4, 12, 5, f, f, f, f, big, None) == -7
+    assert L.qc_tap_embed(f, 64, 16, 9, 8, 5, f, f, f, f, big, None) == -2
+    assert L.qc_tap_embed(f, 64, 16, 4, 8, -1, f, f, f, f, big, None) == -4
+    assert L.qc_tap_embed(f, 64, 16, 4, 8, 5, f, f, f, f, C.c_size_t(64), None) == -6
+    assert L.qc_tap_kmeans(f, 64, 200, 4, f, 10, f, f, None, f, big, None) == -7
+    assert L.qc_tap_kmeans(f, 64, 8, 4, f, 0, f, f, None, f, big, None) == -4
+    assert L.qc_tap_kmeans(f, 64, 8, 4, None, 10, f, f, None, f, big, None) == -1
+    assert L.qc_tap_aggregate(f, 9, 64, 4, f, None, f, big, None) == -7
+    assert L.qc_tap_aggregate(f, 0, 64, 4, f, None, f, big, None) == -2
+    assert L.qc_tap_aggregate(None, 3, 64, 4, f, None, f, big, None) == -1
+    assert L.qc_tap_cluster(f, f, 64, 8, f, 3, 16, 0.5, 4, 8, 5, f, f, 10, f, None, f, big, None) == -1
+    assert L.qc_tap_cluster(f, f, 64, 8, f, 9, 16, 0.5, 4, 8, 5, f, f, 10, f, f, f, big, None) == -7
+    assert L.qc_tap_cluster(f, f, 64, 8, f, 3, 16, 0.5, 4, 8, 5, f, f, 10, f, f, f, C.c_size_t(1000), None) == -6
 
 
 @pytest.mark.parametrize("steps", [50, 100, 250, 7, 1])

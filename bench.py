@@ -7,6 +7,9 @@ latents, 50 sampler steps, cache refreshed every 2nd step, VC every step), all
 inputs resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1] [--no-cpu-baseline]
+
+`--workload tap1` measures the calibration-set clustering instead (one "step" = the whole algorithm over the sample
+pool of the paper's setting); the default run and the headline metric are the sampler's.
 """
 from __future__ import annotations
 
@@ -23,6 +26,8 @@ if ROOT not in sys.path:
 INT8_MFMA_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix peak (published), TOP/s
 FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak (published), TFLOP/s
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak (published), GB/s
+FP32_MFMA_PEAK_TFLOPS = 157.3    # MI355X dense fp32 matrix peak (published), TFLOP/s
+TAP_ITERS, TAP_MAX_PASSES = 8, 100   # power-iteration rounds and k-means pass limit of the clustering workload
 
 # HBM bytes per launch of a kernel class from the hardware counters (two rocprofv3 --pmc runs, FETCH_SIZE and
 # WRITE_SIZE, scaled by what the same counters read for a copy of known size); filled in from the summaries
@@ -80,6 +85,91 @@ def cpu_baseline(wl):
                       "scaled to %d refresh + %d cached steps" % (times[0], times[1], n_full, wl.steps - n_full)}
 
 
+def tap_block(k):
+    """Size of the iteration block: k rounded up to a multiple of 8 plus 24 guard vectors, at most 128."""
+    return min(128, (k + 7) // 8 * 8 + 24)
+
+
+def tap_cpu_baseline(wl):
+    """The clustering oracle, as it stands, on the first 6144 samples of the same pool (subsamples of 1/20 of them,
+    the workload's k, alpha and number of subsamples)."""
+    import numpy as np
+    from oracle import tap
+    from synthetic import tap_inputs as TI
+    Ns = min(wl.N, 6144)
+    ns = max(wl.k, Ns // 20)
+    X, t, _, _ = TI.make_pool(wl.N, wl.F, wl.steps, wl.classes, wl.seed)
+    X, t = X[:Ns], t[:Ns]
+    subs = TI.make_subsamples(Ns, ns, wl.m, wl.seed + 1)
+    init = TI.make_init(Ns, wl.k, wl.m, wl.seed + 2)
+    t0 = time.perf_counter()
+    tap.tap(X, t, subs, wl.alpha, wl.k, init, TAP_MAX_PASSES)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": Ns / dt, "unit": "samples/sec", "cores": int(cores), "kind": "oracle",
+            "sample": "the first %d pool samples with subsamples of %d (%.1f s); the cost per sample grows with the "
+                      "pool (similarity and singular vectors are N x n with n = N / 20), so the full pool would be "
+                      "slower per sample" % (Ns, ns, dt)}
+
+
+def bench_tap(args):
+    import numpy as np
+    import torch
+    import paper_2503_02508_amd as qc
+    from synthetic import tap_inputs as TI
+    wl = TI.TAP_WORKLOADS[args.workload]
+    kb = tap_block(wl.k)
+    torch.cuda.set_device(0)
+    X, t, _, _ = TI.make_pool(wl.N, wl.F, wl.steps, wl.classes, wl.seed)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    Xd, td = dev(X), dev(t)
+    subs = dev(TI.make_subsamples(wl.N, wl.n, wl.m, wl.seed + 1))
+    init = dev(TI.make_init(wl.N, wl.k, wl.m, wl.seed + 2))
+    q0 = dev(TI.make_start_block(kb, wl.n, wl.seed + 3))
+    del X
+    work = torch.empty(qc.qc_tap_workspace_bytes(wl.N, wl.F, wl.n, wl.k, kb), dtype=torch.uint8, device="cuda")
+    final = torch.empty(wl.N, dtype=torch.int32, device="cuda")
+    per = torch.empty((wl.m, wl.N), dtype=torch.int32, device="cuda")
+
+    def run_once():
+        qc.qc_tap_cluster(Xd, td, subs, wl.alpha, wl.k, TAP_ITERS, q0, init, TAP_MAX_PASSES, final, per, work)
+
+    for _ in range(args.warmup):
+        run_once()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_once()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert int(final.min()) >= 0 and int(final.max()) < wl.k
+    # dominant kernel: the similarity contraction, events around its launches in one more pass
+    qc.qc_tap_profile_begin()
+    run_once()
+    sim_ms, launches = qc.qc_tap_profile_end()
+    flops = 2.0 * wl.N * wl.n * wl.F
+    ach = flops / (sim_ms / launches * 1e-3) / 1e12
+    out = {
+        "metric": "pool samples clustered/sec, calibration-set clustering (TAP)",
+        "value": wl.N * args.steps / dt, "unit": "samples/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "pool": wl.N, "features": wl.F, "subsample": wl.n, "subsamples": wl.m,
+                   "clusters": wl.k, "alpha": wl.alpha, "iteration_block": kb, "power_iterations": TAP_ITERS,
+                   "kmeans_pass_limit": TAP_MAX_PASSES},
+        "roofline": {"bound": "mfma", "kernel": "similarity (sgemm_kernel, cosine + temporal epilogue)", "achieved": ach,
+                     "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / FP32_MFMA_PEAK_TFLOPS,
+                     "traffic": None, "avg_launch_us": sim_ms / launches * 1e3, "launches": launches},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = tap_cpu_baseline(wl)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +184,9 @@ def main():
         print("bench.py: this build runs on one GPU only (latents are independent, so more GPUs would each run "
               "this same program on their share of the batch); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload.startswith("tap"):
+        return bench_tap(args)
 
     import numpy as np
     import torch

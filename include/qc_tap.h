@@ -112,6 +112,15 @@ int qc_tap_cluster(const float *X, const float *t, int N, int F, const int *subs
                    int k, int kb, int iters, const float *q0, const int *init_idx, int max_iter, int *labels_out,
                    int *per_labels, void *work, size_t work_bytes, void *stream);
 
+/* Measurement aid: between qc_tap_profile_begin and qc_tap_profile_end every
+ * launch of the similarity contraction (the dominant kernel of the algorithm)
+ * is bracketed by events on the stream it is launched on.  _end waits for
+ * them and returns the summed duration in milliseconds and the number of
+ * launches (host pointers); QC_ERR_STATE without a _begin.  Process-wide, not
+ * thread-safe. */
+int qc_tap_profile_begin(void);
+int qc_tap_profile_end(float *sim_ms_out, int *launches_out);
+
 #ifdef __cplusplus
 }
 #endif

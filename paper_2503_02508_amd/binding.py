@@ -13,7 +13,7 @@ __all__ = [
     "qc_quantize_act", "qc_quantize_weight", "qc_w8a8_linear", "qc_vc_correct", "qc_vc_fit", "qc_ddim_schedule", "last_error",
     "LIB_PATH", "WS", "KERNEL_CLASSES",
     "qc_tap_workspace_bytes", "qc_tap_similarity", "qc_tap_normalise", "qc_tap_embed", "qc_tap_kmeans",
-    "qc_tap_aggregate", "qc_tap_cluster",
+    "qc_tap_aggregate", "qc_tap_cluster", "qc_tap_profile_begin", "qc_tap_profile_end",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqc.so")
@@ -80,6 +80,8 @@ _SIGS = {
     "qc_tap_kmeans": (i32, [vp, i32, i32, i32, vp, i32, vp, vp, C.POINTER(i32), vp, sz, vp]),
     "qc_tap_aggregate": (i32, [vp, i32, i32, i32, vp, vp, vp, sz, vp]),
     "qc_tap_cluster": (i32, [vp, vp, i32, i32, vp, i32, i32, f32, i32, i32, i32, vp, vp, i32, vp, vp, vp, sz, vp]),
+    "qc_tap_profile_begin": (i32, []),
+    "qc_tap_profile_end": (i32, [C.POINTER(f32), C.POINTER(i32)]),
     "qc_profile_begin": (i32, [vp]),
     "qc_profile_end": (i32, [vp, i32, C.POINTER(C.c_int32), C.POINTER(f32), vp]),
 }
@@ -186,6 +188,17 @@ def qc_tap_cluster(X, t, subsamples, alpha, k, iters, q0, init_idx, max_iter, la
     m, n = subsamples.shape
     _chk(lib.qc_tap_cluster(_p(X), _p(t), N, F, _p(subsamples), m, n, float(alpha), k, q0.shape[0], iters, _p(q0),
                             _p(init_idx), max_iter, _p(labels_out), _p(per_labels), _p(work), _wb(work), _stream()))
+
+
+def qc_tap_profile_begin():
+    _chk(lib.qc_tap_profile_begin())
+
+
+def qc_tap_profile_end():
+    """(summed milliseconds, launches) of the similarity contraction since qc_tap_profile_begin."""
+    ms, n = f32(0), i32(0)
+    _chk(lib.qc_tap_profile_end(C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 def qc_ddim_schedule(steps: int):

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
+#include <utility>
+#include <vector>
 #include "qc_tap.h"
 #include "qc_internal.h"
 
@@ -61,6 +63,10 @@ struct SgemmArgs {
   // SE_SIM: C = alpha * acc * rs[m] * cs[n] + (1 - alpha) * exp(-|tr[m] - tc[n]|);  SE_COLSCALE: C = acc * cs[n]
   const float *rs, *cs, *tr, *tc;
   float alpha;
+  // split K (SE_PLAIN only): workgroup (tile, blockIdx.y = s) multiplies k in [s * kchunk, (s + 1) * kchunk) and writes
+  // its partial product to C + s * part_stride; a second kernel adds the partial products in order
+  int kchunk;
+  long long part_stride;
 };
 
 // One operand's share of a slab for this thread: four units of four consecutive elements.
@@ -95,11 +101,13 @@ __device__ __forceinline__ void load_units(const float *P, long long so, long lo
         const float4 v = *reinterpret_cast<const float4 *>(P + (ok ? (long long)k * sk + o : 0));
         r[p] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
       } else {
+        // element loads: lane l takes o = l % 32 + 32 i, so that every load covers 32 consecutive floats
+        const int ob = o0 + (u & 31);
         float e[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const bool ok = o + i < O && k < K;
-          const float v = P[ok ? (long long)k * sk + (long long)(o + i) * so : 0];
+          const bool ok = ob + 32 * i < O && k < K;
+          const float v = P[ok ? (long long)k * sk + (long long)(ob + 32 * i) * so : 0];
           e[i] = ok ? v : 0.f;
         }
         r[p] = make_float4(e[0], e[1], e[2], e[3]);
@@ -109,7 +117,7 @@ __device__ __forceinline__ void load_units(const float *P, long long so, long lo
 }
 
 template <bool KC>
-__device__ __forceinline__ void store_units(float *T, int tid, const float4 (&r)[4]) {
+__device__ __forceinline__ void store_units(float *T, int tid, bool vec, const float4 (&r)[4]) {
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int u = tid + 256 * p;
@@ -120,8 +128,16 @@ __device__ __forceinline__ void store_units(float *T, int tid, const float4 (&r)
       T[(k + 2) * LDT + o] = r[p].z;
       T[(k + 3) * LDT + o] = r[p].w;
     } else {
-      const int k = u >> 5, o = (u & 31) << 2;
-      *reinterpret_cast<float4 *>(T + k * LDT + o) = r[p];
+      const int k = u >> 5;
+      if (vec) {
+        *reinterpret_cast<float4 *>(T + k * LDT + ((u & 31) << 2)) = r[p];
+      } else {
+        float *d = T + k * LDT + (u & 31);
+        d[0] = r[p].x;
+        d[32] = r[p].y;
+        d[64] = r[p].z;
+        d[96] = r[p].w;
+      }
     }
   }
 }
@@ -150,17 +166,19 @@ __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs p) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   float4 ra[4], rb[4];
-  const int nslab = (p.K + TK - 1) / TK;
-  load_units<AKC>(p.A, p.sam, p.sak, m0, p.M, 0, p.K, p.a_vec, tid, ra);
-  load_units<BKC>(p.B, p.sbn, p.sbk, n0, p.N, 0, p.K, p.b_vec, tid, rb);
+  const int kbeg = blockIdx.y * p.kchunk, kend = min(p.K, kbeg + p.kchunk);
+  const int nslab = (kend - kbeg + TK - 1) / TK;
+  if (EPI == SE_PLAIN) p.C += (long long)blockIdx.y * p.part_stride;
+  load_units<AKC>(p.A, p.sam, p.sak, m0, p.M, kbeg, kend, p.a_vec, tid, ra);
+  load_units<BKC>(p.B, p.sbn, p.sbk, n0, p.N, kbeg, kend, p.b_vec, tid, rb);
   for (int s = 0; s < nslab; ++s) {
     __syncthreads();
-    store_units<AKC>(As, tid, ra);
-    store_units<BKC>(Bs, tid, rb);
+    store_units<AKC>(As, tid, p.a_vec, ra);
+    store_units<BKC>(Bs, tid, p.b_vec, rb);
     __syncthreads();
     if (s + 1 < nslab) {
-      load_units<AKC>(p.A, p.sam, p.sak, m0, p.M, (s + 1) * TK, p.K, p.a_vec, tid, ra);
-      load_units<BKC>(p.B, p.sbn, p.sbk, n0, p.N, (s + 1) * TK, p.K, p.b_vec, tid, rb);
+      load_units<AKC>(p.A, p.sam, p.sak, m0, p.M, kbeg + (s + 1) * TK, kend, p.a_vec, tid, ra);
+      load_units<BKC>(p.B, p.sbn, p.sbk, n0, p.N, kbeg + (s + 1) * TK, kend, p.b_vec, tid, rb);
     }
     const float *ap = As + (lane >> 5) * LDT + wm0 + (lane & 31);
     const float *bp = Bs + (lane >> 5) * LDT + wn0 + (lane & 31);
@@ -197,7 +215,17 @@ __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs p) {
   }
 }
 
-hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st) {
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *part, int splits, long long stride,
+                                                            long long count, float *out) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  float s = 0.f;
+  for (int q = 0; q < splits; ++q) s += part[q * stride + i];
+  out[i] = s;
+}
+
+// `part` (part_elems floats) allows a plain product with few tiles and a long K to be split along K
+hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st, float *part = nullptr, size_t part_elems = 0) {
   if (a.M <= 0 || a.N <= 0) return hipSuccess;
   a.a_kc = a.sak == 1;
   a.b_kc = a.sbk == 1;
@@ -208,7 +236,24 @@ hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st) {
   a.b_vec = aligned16(a.B) && (a.b_kc ? (a.sbn % 4 == 0 && a.K % 4 == 0) : (a.sbk % 4 == 0 && a.N % 4 == 0));
   const int tiles = ((a.M + TM - 1) / TM) * ((a.N + TN - 1) / TN);
   const int grid = ((tiles + NUM_XCD - 1) / NUM_XCD) * NUM_XCD;
-#define SG_LAUNCH(AK, BK, E) hipLaunchKernelGGL((sgemm_kernel<AK, BK, E>), dim3(grid), dim3(256), 0, st, a)
+  int splits = 1;
+  a.kchunk = a.K > 0 ? a.K : 1;
+  a.part_stride = 0;
+  float *out = a.C;
+  const long long out_elems = (long long)a.M * a.ldc;
+  if (epi == SE_PLAIN && part && tiles < 256 && a.K >= 8 * TK) {
+    long long want = (512 + tiles - 1) / tiles;
+    if (want > 16) want = 16;
+    if (want > a.K / (4 * TK)) want = a.K / (4 * TK);
+    if (want > (long long)(part_elems / (size_t)out_elems)) want = (long long)(part_elems / (size_t)out_elems);
+    if (want > 1) {
+      a.kchunk = (int)(((a.K + want - 1) / want + TK - 1) / TK * TK);
+      splits = (a.K + a.kchunk - 1) / a.kchunk;
+      a.part_stride = out_elems;
+      a.C = part;
+    }
+  }
+#define SG_LAUNCH(AK, BK, E) hipLaunchKernelGGL((sgemm_kernel<AK, BK, E>), dim3(grid, splits), dim3(256), 0, st, a)
   if (epi == SE_SIM) {
     if (a.a_kc && a.b_kc) SG_LAUNCH(true, true, SE_SIM);
     else return hipErrorInvalidValue;
@@ -222,6 +267,9 @@ hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st) {
     else return hipErrorInvalidValue;
   }
 #undef SG_LAUNCH
+  if (splits > 1)
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((out_elems + 255) / 256)), dim3(256), 0, st, part, splits,
+                       out_elems, out_elems, out);
   return hipGetLastError();
 }
 
@@ -317,8 +365,11 @@ __global__ __launch_bounds__(256) void normalise_kernel(float *A, const float *d
 }
 
 // -------------------------------------------------------------------------- orthonormalisation (Cholesky QR)
-// partial Gram matrices of the rows of Y[kb, n] over column ranges, fp64: part[b][a][c] = sum_j Y[a, j] Y[c, j]
-__global__ __launch_bounds__(256) void gram_partial_kernel(const float *Y, int kb, int n, int jchunk, double *part) {
+// partial Gram matrices of kb vectors of length n over ranges of their elements, fp64: part[b][a][c] = sum_j y_a[j]
+// y_c[j], vector a's element j at Y[a * sv + j * sj] (rows of a [kb, n] matrix: sv = n, sj = 1; columns of an
+// [n, kb] matrix: sv = 1, sj = kb)
+__global__ __launch_bounds__(256) void gram_partial_kernel(const float *Y, int kb, int n, long long sv, long long sj,
+                                                           int jchunk, double *part) {
   __shared__ float ys[KB_MAX][33];
   const int tid = threadIdx.x, ta = tid >> 4, tb = tid & 15;
   double acc[8][8];
@@ -330,9 +381,10 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const float *Y, int k
   for (int jb = j0; jb < j1; jb += 32) {
     __syncthreads();
     for (int u = tid; u < KB_MAX * 32; u += 256) {
-      const int a = u >> 5, j = u & 31;
+      // consecutive lanes along the contiguous direction
+      const int a = sj == 1 ? u >> 5 : u & (KB_MAX - 1), j = sj == 1 ? u & 31 : u >> 7;
       const bool ok = a < kb && jb + j < j1;
-      const float v = Y[ok ? (long long)a * n + jb + j : 0];
+      const float v = Y[ok ? (long long)a * sv + (long long)(jb + j) * sj : 0];
       ys[a][j] = ok ? v : 0.f;
     }
     __syncthreads();
@@ -367,20 +419,28 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double *part, in
   W[i] = s;
 }
 
-// Cholesky factor Lc of W + shift I (= Lc Lc^T, lower) and its inverse, one workgroup, the matrix in LDS (fp64).  The
-// shift, shift_rel times the largest diagonal entry, keeps the factorisation alive when the rows are numerically
-// dependent (shifted Cholesky QR: the rows come out better conditioned, not yet orthonormal, and the next pass
-// finishes).  The strict upper triangle, unused by the factorisation, receives the inverse (Linv[i][c] at [c][i],
-// i > c).  Out: Rinv[kb, kb] fp32 = Lc^-1 (lower triangular), so that Rinv Y has orthonormal rows when the shift is
-// negligible.  With `check` set (the last pass, whose input should already be near orthonormal) a pivot below 1/4
-// raises the flag: the block has no full rank.  A non-positive pivot always raises it.
-__global__ __launch_bounds__(256) void chol_inv_kernel(const double *W, int kb, double shift_rel, int check, float *Rinv,
-                                                        int *flag) {
+// Inverse Cholesky factor of W + shift I (= Lc Lc^T, Lc lower), one workgroup, the matrix in LDS (fp64).  The shift,
+// shift_rel times the largest diagonal entry, keeps the factorisation alive when the rows are numerically dependent
+// (shifted Cholesky QR: the rows come out better conditioned, not yet orthonormal, and the next pass finishes).
+// The sweep is the square-root-free form: at column j, with pivot p_j, every later row i takes
+//   trailing matrix  w_iq -= w_ij w_qj / p_j   (j < q <= i)
+//   inverse          r_iq -= w_ij r_jq / p_j   (q <= j; r starts as the identity)
+// which reads only column j and writes only columns beyond j, so one barrier per column suffices.  Then
+// Lc = w diag(p)^-1/2 and Lc^-1 = diag(p)^-1/2 r.  r's strict lower triangle lives in the strict upper triangle of the
+// LDS matrix (r_iq at [q][i]); its diagonal is 1.  Out: Rinv[kb, kb] fp32 = Lc^-1 (lower triangular), so that Rinv Y
+// has orthonormal rows when the shift is negligible.  With `check` set (the last pass, whose input should already be
+// near orthonormal) a pivot below 1/4 raises the flag: the block has no full rank.  A non-positive pivot always
+// raises it.  Thread (ty, tx) of the 8 x 128 workgroup handles rows i = j + 1 + ty, + 8, ... and column q = tx.
+__global__ __launch_bounds__(1024) void chol_inv_kernel(const double *W, int kb, double shift_rel, int check,
+                                                         float *Rinv, int *flag) {
   extern __shared__ double Ws[];
   __shared__ double dmax;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, tx = tid & 127, ty = tid >> 7;
   const int ld = kb + 1;
-  for (int u = tid; u < kb * kb; u += 256) Ws[(u / kb) * ld + (u % kb)] = W[u];
+  for (int u = tid; u < kb * kb; u += 1024) {
+    const int i = u / kb, c = u % kb;
+    Ws[i * ld + c] = c <= i ? W[u] : 0.0;
+  }
   __syncthreads();
   if (tid == 0) {
     double m = 0.0;
@@ -388,91 +448,152 @@ __global__ __launch_bounds__(256) void chol_inv_kernel(const double *W, int kb, 
     dmax = m;
   }
   __syncthreads();
-  for (int i = tid; i < kb; i += 256) Ws[i * ld + i] += shift_rel * dmax;
+  for (int i = tid; i < kb; i += 1024) Ws[i * ld + i] += shift_rel * dmax;
   __syncthreads();
   for (int j = 0; j < kb; ++j) {
     double piv = Ws[j * ld + j];
     if (!(piv > 0.0) || !isfinite(piv)) {
-      if (tid == 0) atomicOr(flag, 2);
+      if (tid == 0) {
+        atomicOr(flag, 2);
+        Ws[j * ld + j] = 1.0;             // nobody else writes the pivot; readers of this column use the local value
+      }
       piv = 1.0;
     } else if (check && piv < 0.25) {
       if (tid == 0) atomicOr(flag, 2);
     }
-    const double d = sqrt(piv);
-    __syncthreads();                      // everyone has read the pivot
-    if (tid == 0) Ws[j * ld + j] = d;
-    for (int i = j + 1 + tid; i < kb; i += 256) Ws[i * ld + j] /= d;
-    __syncthreads();
-    const int w = kb - j - 1;
-    for (int u = tid; u < w * w; u += 256) {
-      const int i = j + 1 + u / w, c = j + 1 + u % w;
-      if (c <= i) Ws[i * ld + c] -= Ws[i * ld + j] * Ws[c * ld + j];
+    if (tx < kb) {
+      // 1 / p: hardware estimate refined by two Newton steps
+      double inv_p = __builtin_amdgcn_rcp(piv);
+      inv_p = inv_p * (2.0 - piv * inv_p);
+      inv_p = inv_p * (2.0 - piv * inv_p);
+      // column j: rows below the diagonal hold w_qj, rows above it r_jq, the diagonal stands for r_jj = 1
+      const double colq = (tx == j ? 1.0 : Ws[tx * ld + j]) * inv_p;
+      // this thread's rows i = j + 1 + ty + 8 s: all loads first, then the updates, so that the LDS latencies overlap
+      const bool lower = tx > j;
+      double f[KB_MAX / 8], t[KB_MAX / 8];
+#pragma unroll
+      for (int q = 0; q < KB_MAX / 8; ++q) {
+        const int i = j + 1 + ty + 8 * q;
+        const bool on = i < kb && (!lower || tx <= i);
+        const int ii = i < kb ? i : j;                       // any valid row
+        f[q] = Ws[ii * ld + j];
+        t[q] = Ws[lower ? ii * ld + tx : tx * ld + ii];
+        if (!on) f[q] = 0.0;
+      }
+#pragma unroll
+      for (int q = 0; q < KB_MAX / 8; ++q) {
+        const int i = j + 1 + ty + 8 * q;
+        if (i < kb && (!lower || tx <= i)) Ws[lower ? i * ld + tx : tx * ld + i] = fma(-f[q], colq, t[q]);
+      }
     }
     __syncthreads();
   }
-  // inverse, one column per thread: x_c = 1 / l_cc, x_i = -(sum_{p=c}^{i-1} l_ip x_p) / l_ii
-  for (int c = tid; c < kb; c += 256) {
-    const double xc = 1.0 / Ws[c * ld + c];
-    for (int i = c + 1; i < kb; ++i) {
-      double s = Ws[i * ld + c] * xc;
-      for (int q = c + 1; q < i; ++q) s = fma(Ws[i * ld + q], Ws[c * ld + q], s);
-      Ws[c * ld + i] = -s / Ws[i * ld + i];
-    }
-  }
-  __syncthreads();
-  for (int u = tid; u < kb * kb; u += 256) {
+  for (int u = tid; u < kb * kb; u += 1024) {
     const int i = u / kb, c = u % kb;
+    const double sc = 1.0 / sqrt(Ws[i * ld + i]);
     double v = 0.0;
-    if (i == c) v = 1.0 / Ws[i * ld + i];
-    else if (i > c) v = Ws[c * ld + i];
+    if (i == c) v = sc;
+    else if (i > c) v = Ws[c * ld + i] * sc;
     Rinv[u] = (float)v;
   }
 }
 
 // ------------------------------------------------------------------------------- Rayleigh-Ritz (Jacobi)
-// Eigenvectors of the symmetric positive semi-definite T[kb, kb] by one-sided Jacobi rotations on the rows of a copy
-// M of T (fp64, LDS): rotations from the left make the rows mutually orthogonal; then row j = lambda_j v_j^T.  Pairs
-// of a round are disjoint (round-robin schedule) and rotate concurrently, one pair per wavefront at a time.  Out: the
-// k eigenvectors of largest eigenvalue as rows of Wk[k, kb], eigenvalues lam[k] (descending), inv_sigma[k] =
-// lam^-1/2, sigma[k] = lam^1/2.
-__global__ __launch_bounds__(1024) void jacobi_kernel(const float *T, int kb, int k, int max_sweeps, float *Wk,
-                                                       float *lam, float *inv_sigma, float *sigma) {
+// sum over each row of 16 lanes, every lane receiving it: four butterfly steps on the data-parallel-primitive paths
+// (quad permutes, mirror within 8, mirror within 16), no LDS traffic.  All lanes of a row add the same pairs in the
+// same tree, so they hold bitwise the same result.
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, true);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, true);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double row16_sum(double v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1, 0, 3, 2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2, 3, 0, 1]
+  v += dpp_move<0x141>(v);   // row_half_mirror
+  v += dpp_move<0x140>(v);   // row_mirror
+  return v;
+}
+
+// Eigenvectors of the symmetric positive semi-definite T[kb, kb] (fp64) by one-sided Jacobi rotations on the rows of
+// a copy M of T (LDS): rotations from the left make the rows mutually orthogonal; then row j = lambda_j v_j^T.  The
+// kb / 2 pairs of a round are disjoint (round-robin schedule) and rotate concurrently, one pair per row of 16 lanes
+// (64 rows in the workgroup), lane e holding elements e, e + 16, ....  The squared row norms are carried along (a
+// rotation by tangent t moves t * <x, y> from one to the other) and recomputed at the start of every sweep, so a pair
+// costs one reduction.  Rows whose norm is below 10^-11 of the largest are rounding noise and are left alone.  Out:
+// the k eigenvectors of largest eigenvalue as rows of Wk[k, kb], sigma[k] = lambda^1/2 (descending) and inv_sigma[k] =
+// lambda^-1/2 (0 where lambda = 0).
+__global__ __launch_bounds__(1024) void jacobi_kernel(const double *T, int kb, int k, int max_sweeps, float *Wk,
+                                                       float *inv_sigma, float *sigma) {
   extern __shared__ double Ms[];
   __shared__ int rotated;
-  __shared__ double nrm[KB_MAX];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ double nrm2[KB_MAX];
+  __shared__ double amax;
+  const int tid = threadIdx.x, e = tid & 15, grp = tid >> 4;   // grp: 0..63
+  const int ldm = kb + 2;
   for (int u = tid; u < kb * kb; u += 1024) {
     const int i = u / kb, j = u % kb;
-    Ms[u] = 0.5 * ((double)T[i * kb + j] + (double)T[j * kb + i]);
+    Ms[i * ldm + j] = 0.5 * (T[i * kb + j] + T[j * kb + i]);
   }
   if (tid == 0) rotated = 0;
   __syncthreads();
   const int half = kb / 2, ring = kb - 1;
-  for (int sweep = 0; sweep < max_sweeps; ++sweep) {
+  for (int sweep = 0; sweep <= max_sweeps; ++sweep) {
+    for (int j = grp; j < kb; j += 64) {
+      double s = 0.0;
+      for (int c = e; c < kb; c += 16) {
+        const double x = Ms[j * ldm + c];
+        s = fma(x, x, s);
+      }
+      s = row16_sum(s);
+      if (e == 0) nrm2[j] = s;
+    }
+    __syncthreads();
+    if (sweep == max_sweeps) break;       // the norms are exact again: ready for the ranking below
+    if (tid == 0) {
+      double m = 0.0;
+      for (int i = 0; i < kb; ++i) m = fmax(m, nrm2[i]);
+      amax = m;
+    }
+    __syncthreads();
+    const double floor2 = 1e-22 * amax;
     for (int round = 0; round < ring; ++round) {
-      for (int pr = wave; pr < half; pr += 16) {
-        const int a = pr == 0 ? round : (round + pr) % ring;
-        const int b = pr == 0 ? ring : (round - pr + ring) % ring;
-        double *ra = Ms + a * kb, *rb = Ms + b * kb;
-        const bool has1 = lane + 64 < kb;
-        const double x0 = lane < kb ? ra[lane] : 0.0, x1 = has1 ? ra[lane + 64] : 0.0;
-        const double y0 = lane < kb ? rb[lane] : 0.0, y1 = has1 ? rb[lane + 64] : 0.0;
-        const double al = wave_sum(x0 * x0 + x1 * x1);
-        const double be = wave_sum(y0 * y0 + y1 * y1);
-        const double ga = wave_sum(x0 * y0 + x1 * y1);
-        if (al > 0.0 && be > 0.0 && fabs(ga) > 1e-13 * sqrt(al * be)) {
-          const double zeta = (be - al) / (2.0 * ga);
-          const double tt = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-          const double c = 1.0 / sqrt(1.0 + tt * tt), s = c * tt;
-          if (lane < kb) {
-            ra[lane] = c * x0 - s * y0;
-            rb[lane] = s * x0 + c * y0;
+      // all 64 lanes of a wavefront run the reduction (the 16-lane groups without a pair add zeros)
+      const bool live = grp < half;
+      const int pr = live ? grp : 0;
+      const int a = pr == 0 ? round : (round + pr) % ring;
+      const int b = pr == 0 ? ring : (round - pr + ring) % ring;
+      double *ra = Ms + a * ldm, *rb = Ms + b * ldm;
+      double x[8], y[8];
+      double ga = 0.0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int c = e + 16 * i;
+        const bool ok = live && c < kb;
+        x[i] = ok ? ra[c] : 0.0;
+        y[i] = ok ? rb[c] : 0.0;
+        ga = fma(x[i], y[i], ga);
+      }
+      ga = row16_sum(ga);
+      const double al = nrm2[a], be = nrm2[b];
+      if (live && fmin(al, be) > floor2 && fabs(ga) > 1e-13 * sqrt(al * be)) {
+        const double zeta = (be - al) / (2.0 * ga);
+        const double tt = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
+        const double c_ = 1.0 / sqrt(1.0 + tt * tt), s_ = c_ * tt;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int c = e + 16 * i;
+          if (c < kb) {
+            ra[c] = c_ * x[i] - s_ * y[i];
+            rb[c] = s_ * x[i] + c_ * y[i];
           }
-          if (has1) {
-            ra[lane + 64] = c * x1 - s * y1;
-            rb[lane + 64] = s * x1 + c * y1;
-          }
-          if (lane == 0) rotated = 1;
+        }
+        if (e == 0) {
+          nrm2[a] = al - tt * ga;
+          nrm2[b] = be + tt * ga;
+          rotated = 1;
         }
       }
       __syncthreads();
@@ -481,32 +602,32 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const float *T, int kb, in
     __syncthreads();
     if (tid == 0) rotated = 0;
     __syncthreads();
-    if (!any) break;
-  }
-  // eigenvalues = row norms; rank them (descending, ties to the lower row)
-  for (int j = wave; j < kb; j += 16) {
-    const double x0 = lane < kb ? Ms[j * kb + lane] : 0.0, x1 = lane + 64 < kb ? Ms[j * kb + lane + 64] : 0.0;
-    const double s = wave_sum(x0 * x0 + x1 * x1);
-    if (lane == 0) nrm[j] = sqrt(s);
+    if (!any) break;                      // nothing moved in this sweep: the carried norms are the exact ones
   }
   __syncthreads();
-  for (int j = wave; j < kb; j += 16) {
+  // eigenvalues = row norms; rank them (descending, ties to the lower row)
+  for (int j = grp; j < kb; j += 64) {
     int rank = 0;
-    const double mine = nrm[j];
-    for (int i = 0; i < kb; ++i) rank += (nrm[i] > mine || (nrm[i] == mine && i < j)) ? 1 : 0;
+    const double mine = nrm2[j] > 0.0 ? nrm2[j] : 0.0;
+    for (int i = 0; i < kb; ++i) {
+      const double o = nrm2[i] > 0.0 ? nrm2[i] : 0.0;
+      rank += (o > mine || (o == mine && i < j)) ? 1 : 0;
+    }
     if (rank < k) {
-      const double inv = mine > 0.0 ? 1.0 / mine : 0.0;
-      for (int c = lane; c < kb; c += 64) Wk[rank * kb + c] = (float)(Ms[j * kb + c] * inv);
-      if (lane == 0) {
-        lam[rank] = (float)mine;
-        sigma[rank] = (float)sqrt(mine);
-        inv_sigma[rank] = mine > 0.0 ? (float)(1.0 / sqrt(mine)) : 0.f;
+      const double lam = sqrt(mine);
+      const double inv = lam > 0.0 ? 1.0 / lam : 0.0;
+      for (int c = e; c < kb; c += 16) Wk[rank * kb + c] = (float)(Ms[j * ldm + c] * inv);
+      if (e == 0) {
+        sigma[rank] = (float)sqrt(lam);
+        inv_sigma[rank] = lam > 0.0 ? (float)(1.0 / sqrt(lam)) : 0.f;
       }
     }
   }
 }
 
 // ------------------------------------------------------------------------------------------------- k-means
+__device__ __forceinline__ int clamp_label(int v, int k) { return v < 0 ? 0 : (v >= k ? k - 1 : v); }
+
 __global__ __launch_bounds__(256) void kmeans_init_kernel(const float *U, int N, int d, int k, const int *init_idx,
                                                           float *centres, int *flag) {
   const int c = blockIdx.x;
@@ -571,37 +692,60 @@ __global__ __launch_bounds__(256) void kmeans_assign_kernel(const float *U, int 
   }
 }
 
-// update pass: workgroup (c, dimension chunk of 32); thread (phase, j) adds the member rows r = phase, phase + 8, ...
-// in ascending order in fp64, the eight phases are added in order; an empty cluster keeps its centre
-__global__ __launch_bounds__(256) void kmeans_update_kernel(const float *U, int N, int d, const int *labels,
-                                                            float *centres) {
-  __shared__ double red[8][32];
-  __shared__ int cnt[8];
-  const int c = blockIdx.x, j = blockIdx.y * 32 + (threadIdx.x & 31), ph = threadIdx.x >> 5;
-  double s = 0.0;
-  int m = 0;
-  for (int r = ph; r < N; r += 8)
-    if (labels[r] == c) {
-      ++m;
-      if (j < d) s += (double)U[(long long)r * d + j];
-    }
-  red[ph][threadIdx.x & 31] = s;
-  if ((threadIdx.x & 31) == 0) cnt[ph] = m;
+// update pass, stage 1: workgroup b walks its range of rows in ascending order, thread j owning dimension j, and adds
+// each row to its cluster's fp64 sums in LDS; stage 2 adds the workgroups' sums in order.  An empty cluster keeps its
+// centre.
+__global__ __launch_bounds__(128) void kmeans_partial_kernel(const float *U, int N, int d, const int *labels, int k,
+                                                             int rows_per, double *psum, int *pcnt) {
+  extern __shared__ double accs[];      // [k][d]
+  __shared__ int cnt[KB_MAX];
+  const int j = threadIdx.x;
+  for (int u = j; u < k * d; u += 128) accs[u] = 0.0;
+  for (int u = j; u < k; u += 128) cnt[u] = 0;
   __syncthreads();
-  if (ph == 0 && j < d) {
-    double tot = 0.0;
-    int mt = 0;
-    for (int q = 0; q < 8; ++q) {
-      tot += red[q][threadIdx.x & 31];
-      mt += cnt[q];
+  const int r0 = blockIdx.x * rows_per, r1 = min(N, r0 + rows_per);
+  const int jj = j < d ? j : 0;
+  int r = r0;
+  for (; r + 4 <= r1; r += 4) {
+    int c[4];
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      c[i] = clamp_label(labels[r + i], k);
+      v[i] = U[(long long)(r + i) * d + jj];
     }
-    if (mt > 0) centres[c * d + j] = (float)(tot / (double)mt);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (j < d) accs[c[i] * d + j] += (double)v[i];
+      if (j == 0) cnt[c[i]] += 1;
+    }
   }
+  for (; r < r1; ++r) {
+    const int c = clamp_label(labels[r], k);
+    if (j < d) accs[c * d + j] += (double)U[(long long)r * d + j];
+    if (j == 0) cnt[c] += 1;
+  }
+  __syncthreads();
+  double *ps = psum + (long long)blockIdx.x * k * d;
+  for (int u = j; u < k * d; u += 128) ps[u] = accs[u];
+  for (int u = j; u < k; u += 128) pcnt[blockIdx.x * k + u] = cnt[u];
+}
+
+__global__ __launch_bounds__(256) void kmeans_finish_kernel(const double *psum, const int *pcnt, int nb, int k, int d,
+                                                            float *centres) {
+  const int u = blockIdx.x * 256 + threadIdx.x;
+  if (u >= k * d) return;
+  const int c = u / d;
+  double tot = 0.0;
+  int m = 0;
+  for (int b = 0; b < nb; ++b) {
+    tot += psum[(long long)b * k * d + u];
+    m += pcnt[b * k + c];
+  }
+  if (m > 0) centres[u] = (float)(tot / (double)m);
 }
 
 // ---------------------------------------------------------------------------------------------- aggregation
-__device__ __forceinline__ int clamp_label(int v, int k) { return v < 0 ? 0 : (v >= k ? k - 1 : v); }
-
 __global__ __launch_bounds__(256) void contingency_kernel(const int *a, const int *b, int N, int k, int *T) {
   const int r = blockIdx.x * 256 + threadIdx.x;
   if (r < N) atomicAdd(&T[clamp_label(a[r], k) * k + clamp_label(b[r], k)], 1);
@@ -685,7 +829,19 @@ struct Carve {
   }
 };
 
-int gram_parts(int n) { return (n + 511) / 512; }
+// element ranges of the partial Gram matrices: at most 128 of them, at least 128 elements each
+int gram_chunk(int len) {
+  const int c = (((len + 127) / 128) + 31) / 32 * 32;
+  return c < 128 ? 128 : c;
+}
+int gram_parts(int len) { return (len + gram_chunk(len) - 1) / gram_chunk(len); }
+
+// row ranges of the k-means partial sums: at most 256 of them, at least 256 rows each
+int kmeans_rows_per(int N) {
+  const int r = (N + 255) / 256;
+  return r < 256 ? 256 : r;
+}
+int kmeans_blocks(int N) { return (N + kmeans_rows_per(N) - 1) / kmeans_rows_per(N); }
 
 struct SimWork {
   float *rinv, *Xs, *cs, *tc;
@@ -705,38 +861,43 @@ struct SimWork {
 };
 
 struct EmbedWork {
-  float *G, *Q, *Y, *Z, *T, *Wk, *Qk, *lam, *isig, *Rinv;
+  float *G, *Q, *Y, *Z, *Bm, *Wk, *isig, *Rinv, *spart;
+  size_t spart_elems;
   double *part, *W;
   int *flag;
   size_t bytes;
-  EmbedWork(void *w, int n, int k, int kb) {
+  EmbedWork(void *w, int N, int n, int k, int kb) {
     Carve c(w);
     flag = c.take<int>(64);
     G = c.take<float>((size_t)n * n);
     Q = c.take<float>((size_t)kb * n);
     Y = c.take<float>((size_t)kb * n);
     Z = c.take<float>((size_t)kb * n);
-    T = c.take<float>((size_t)kb * kb);
+    Bm = c.take<float>((size_t)N * kb);
     Wk = c.take<float>((size_t)k * kb);
-    Qk = c.take<float>((size_t)k * n);
-    lam = c.take<float>(k);
     isig = c.take<float>(k);
     Rinv = c.take<float>((size_t)kb * kb);
-    part = c.take<double>((size_t)gram_parts(n) * kb * kb);
+    spart_elems = (size_t)4 * n * n;
+    spart = c.take<float>(spart_elems);
+    const int parts = gram_parts(n) > gram_parts(N) ? gram_parts(n) : gram_parts(N);
+    part = c.take<double>((size_t)parts * kb * kb);
     W = c.take<double>((size_t)kb * kb);
     bytes = c.off + 256;
   }
 };
 
-struct SmallWork {      // k-means, aggregation, normalisation
-  int *flag, *changed, *T, *perm;
+struct SmallWork {      // k-means (N rows of d dimensions), aggregation, normalisation
+  int *flag, *changed, *T, *perm, *pcnt;
+  double *psum;
   size_t bytes;
-  SmallWork(void *w, int k) {
+  SmallWork(void *w, int N, int d, int k) {
     Carve c(w);
     flag = c.take<int>(64);
     changed = c.take<int>(64);
     T = c.take<int>((size_t)k * k);
     perm = c.take<int>((size_t)M_MAX * k);
+    pcnt = c.take<int>((size_t)kmeans_blocks(N) * k);
+    psum = c.take<double>((size_t)kmeans_blocks(N) * k * d);
     bytes = c.off + 256;
   }
 };
@@ -753,7 +914,9 @@ struct ClusterWork {
     U = c.take<float>((size_t)N * k);
     sigma = c.take<float>(k);
     centres = c.take<float>((size_t)k * k);
-    size_t s1 = SimWork(nullptr, N, F, n).bytes, s2 = EmbedWork(nullptr, n, k, kb).bytes, s3 = SmallWork(nullptr, k).bytes;
+    // the k-means region is sized for rows of up to kb dimensions, so that the one size also covers qc_tap_kmeans
+    // on an embedding of the whole iteration block
+    size_t s1 = SimWork(nullptr, N, F, n).bytes, s2 = EmbedWork(nullptr, N, n, k, kb).bytes, s3 = SmallWork(nullptr, N, kb, kb).bytes;
     sub_bytes = s1 > s2 ? s1 : s2;
     if (s3 > sub_bytes) sub_bytes = s3;
     sub = c.take<char>(sub_bytes);
@@ -778,6 +941,14 @@ int read_flag(const int *flag, hipStream_t st, int *out) {
   return QC_OK;
 }
 
+// optional timing of the similarity contraction (the dominant kernel) with events on the caller's stream
+struct SimProfile {
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
+  size_t used = 0;
+};
+SimProfile g_prof;
+
 int similarity_impl(const float *X, const float *t, int N, int F, const int *idx, int n, float alpha, float *A,
                     float *d_r, float *d_c, void *work, hipStream_t st) {
   SimWork w(work, N, F, n);
@@ -791,7 +962,17 @@ int similarity_impl(const float *X, const float *t, int N, int F, const int *idx
   g.C = A; g.ldc = n;
   g.M = N; g.N = n; g.K = F;
   g.rs = w.rinv; g.cs = w.cs; g.tr = t; g.tc = w.tc; g.alpha = alpha;
+  if (g_prof.on) {
+    if (g_prof.used == g_prof.ev.size()) {
+      hipEvent_t a, b;
+      TAP_HIP(hipEventCreate(&a));
+      TAP_HIP(hipEventCreate(&b));
+      g_prof.ev.emplace_back(a, b);
+    }
+    TAP_HIP(hipEventRecord(g_prof.ev[g_prof.used].first, st));
+  }
   TAP_HIP(sgemm(g, SE_SIM, st));
+  if (g_prof.on) TAP_HIP(hipEventRecord(g_prof.ev[g_prof.used++].second, st));
   hipLaunchKernelGGL(rowsum_kernel, dim3((N + 3) / 4), dim3(256), 0, st, A, N, n, d_r);
   hipLaunchKernelGGL(colsum_partial_kernel, dim3((n + 63) / 64, COL_CHUNKS), dim3(256), 0, st, A, N, n, w.colpart);
   hipLaunchKernelGGL(colsum_final_kernel, dim3((n + 255) / 256), dim3(256), 0, st, w.colpart, n, d_c);
@@ -803,7 +984,7 @@ int similarity_impl(const float *X, const float *t, int N, int F, const int *idx
 }
 
 int normalise_impl(float *A, const float *d_r, const float *d_c, int N, int n, void *work, hipStream_t st) {
-  SmallWork w(work, 1);
+  SmallWork w(work, 1, 1, 1);
   hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
   hipLaunchKernelGGL(degree_check_kernel, dim3((N + 255) / 256), dim3(256), 0, st, d_r, N, w.flag);
   hipLaunchKernelGGL(degree_check_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_c, n, w.flag);
@@ -824,11 +1005,12 @@ hipError_t set_lds(const void *kern, size_t bytes) {
 // one pass of shifted Cholesky QR on the rows of `in` [kb, n] into `out` (`in` and `out` must differ)
 int cholqr_pass(const float *in, float *out, int kb, int n, int check, EmbedWork &w, hipStream_t st) {
   const int parts = gram_parts(n);
-  hipLaunchKernelGGL(gram_partial_kernel, dim3(parts), dim3(256), 0, st, in, kb, n, 512, w.part);
+  hipLaunchKernelGGL(gram_partial_kernel, dim3(parts), dim3(256), 0, st, in, kb, n, (long long)n, 1ll, gram_chunk(n),
+                     w.part);
   hipLaunchKernelGGL(gram_reduce_kernel, dim3((kb * kb + 255) / 256), dim3(256), 0, st, w.part, parts, kb * kb, w.W);
   const size_t lds = (size_t)kb * (kb + 1) * sizeof(double);
   TAP_HIP(set_lds((const void *)chol_inv_kernel, lds));
-  hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(256), lds, st, w.W, kb, 1e-12, check, w.Rinv, w.flag);
+  hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(1024), lds, st, w.W, kb, 1e-12, check, w.Rinv, w.flag);
   TAP_HIP(hipGetLastError());
   SgemmArgs g{};
   g.A = w.Rinv; g.sam = kb; g.sak = 1;
@@ -851,16 +1033,17 @@ int orthonormalise(const float *in, EmbedWork &w, int kb, int n, hipStream_t st)
 
 int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const float *q0, float *U, float *sigma,
                void *work, hipStream_t st) {
-  EmbedWork w(work, n, k, kb);
+  EmbedWork w(work, N, n, k, kb);
   hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
   TAP_HIP(hipGetLastError());
-  // G = L^T L
+  // G = L^T L drives the power iteration (its fp32 rounding only slows the convergence of directions whose singular
+  // values are below about 3e-4 of the largest; the Rayleigh-Ritz step below works on L itself)
   SgemmArgs g{};
   g.A = L; g.sam = 1; g.sak = n;
   g.B = L; g.sbn = 1; g.sbk = n;
   g.C = w.G; g.ldc = n;
   g.M = n; g.N = n; g.K = N;
-  TAP_HIP(sgemm(g, SE_PLAIN, st));
+  TAP_HIP(sgemm(g, SE_PLAIN, st, w.spart, w.spart_elems));
   TAP_RC(orthonormalise(q0, w, kb, n, st));
   SgemmArgs mul{};
   mul.A = w.Q; mul.sam = n; mul.sak = 1;
@@ -868,33 +1051,29 @@ int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const flo
   mul.C = w.Y; mul.ldc = n;
   mul.M = kb; mul.N = n; mul.K = n;
   for (int it = 0; it < iters; ++it) {
-    TAP_HIP(sgemm(mul, SE_PLAIN, st));
+    TAP_HIP(sgemm(mul, SE_PLAIN, st, w.spart, w.spart_elems));
     TAP_RC(orthonormalise(w.Y, w, kb, n, st));
   }
-  // Rayleigh-Ritz: T = Q G Q^T, its k leading eigenvectors, Qk = Wk Q
-  TAP_HIP(sgemm(mul, SE_PLAIN, st));
-  SgemmArgs tt{};
-  tt.A = w.Y; tt.sam = n; tt.sak = 1;
-  tt.B = w.Q; tt.sbn = n; tt.sbk = 1;
-  tt.C = w.T; tt.ldc = kb;
-  tt.M = kb; tt.N = kb; tt.K = n;
-  TAP_HIP(sgemm(tt, SE_PLAIN, st));
-  const size_t lds = (size_t)kb * kb * sizeof(double);
+  // Rayleigh-Ritz on B = L Q^T [N, kb]: T = B^T B (fp64), its k leading eigenvectors W, U = B W^T diag(1 / sigma)
+  SgemmArgs bm{};
+  bm.A = L; bm.sam = n; bm.sak = 1;
+  bm.B = w.Q; bm.sbn = n; bm.sbk = 1;
+  bm.C = w.Bm; bm.ldc = kb;
+  bm.M = N; bm.N = kb; bm.K = n;
+  TAP_HIP(sgemm(bm, SE_PLAIN, st));
+  const int parts = gram_parts(N);
+  hipLaunchKernelGGL(gram_partial_kernel, dim3(parts), dim3(256), 0, st, w.Bm, kb, N, 1ll, (long long)kb, gram_chunk(N),
+                     w.part);
+  hipLaunchKernelGGL(gram_reduce_kernel, dim3((kb * kb + 255) / 256), dim3(256), 0, st, w.part, parts, kb * kb, w.W);
+  const size_t lds = (size_t)kb * (kb + 2) * sizeof(double);
   TAP_HIP(set_lds((const void *)jacobi_kernel, lds));
-  hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(1024), lds, st, w.T, kb, k, 30, w.Wk, w.lam, w.isig, sigma);
+  hipLaunchKernelGGL(jacobi_kernel, dim3(1), dim3(1024), lds, st, w.W, kb, k, 30, w.Wk, w.isig, sigma);
   TAP_HIP(hipGetLastError());
-  SgemmArgs qk{};
-  qk.A = w.Wk; qk.sam = kb; qk.sak = 1;
-  qk.B = w.Q; qk.sbn = 1; qk.sbk = n;
-  qk.C = w.Qk; qk.ldc = n;
-  qk.M = k; qk.N = n; qk.K = kb;
-  TAP_HIP(sgemm(qk, SE_PLAIN, st));
-  // U = L Qk^T diag(1 / sigma)
   SgemmArgs u{};
-  u.A = L; u.sam = n; u.sak = 1;
-  u.B = w.Qk; u.sbn = n; u.sbk = 1;
+  u.A = w.Bm; u.sam = kb; u.sak = 1;
+  u.B = w.Wk; u.sbn = kb; u.sbk = 1;
   u.C = U; u.ldc = k;
-  u.M = N; u.N = k; u.K = n;
+  u.M = N; u.N = k; u.K = kb;
   u.cs = w.isig;
   TAP_HIP(sgemm(u, SE_COLSCALE, st));
   int flag = 0;
@@ -905,7 +1084,7 @@ int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const flo
 
 int kmeans_impl(const float *U, int N, int d, int k, const int *init_idx, int max_iter, int *labels, float *centres,
                 int *passes_out, void *work, hipStream_t st) {
-  SmallWork w(work, k);
+  SmallWork w(work, N, d, k);
   hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
   hipLaunchKernelGGL(fill_int_kernel, dim3((N + 255) / 256), dim3(256), 0, st, labels, N, -1);
   hipLaunchKernelGGL(kmeans_init_kernel, dim3(k), dim3(256), 0, st, U, N, d, k, init_idx, centres, w.flag);
@@ -915,6 +1094,9 @@ int kmeans_impl(const float *U, int N, int d, int k, const int *init_idx, int ma
   if (flag) TAP_FAIL(QC_ERR_RANGE, "an initial-centre index lies outside [0, %d)", N);
   const size_t lds = ((size_t)k * d + (size_t)64 * (d + 1)) * sizeof(float);
   TAP_HIP(set_lds((const void *)kmeans_assign_kernel, lds));
+  const size_t lds_acc = (size_t)k * d * sizeof(double);
+  TAP_HIP(set_lds((const void *)kmeans_partial_kernel, lds_acc));
+  const int nb = kmeans_blocks(N);
   int passes = 0;
   for (int it = 0; it < max_iter; ++it) {
     hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.changed, 64, 0);
@@ -925,7 +1107,10 @@ int kmeans_impl(const float *U, int N, int d, int k, const int *init_idx, int ma
     int changed = 0;
     TAP_RC(read_flag(w.changed, st, &changed));
     if (changed == 0) break;
-    hipLaunchKernelGGL(kmeans_update_kernel, dim3(k, (d + 31) / 32), dim3(256), 0, st, U, N, d, labels, centres);
+    hipLaunchKernelGGL(kmeans_partial_kernel, dim3(nb), dim3(128), lds_acc, st, U, N, d, labels, k, kmeans_rows_per(N),
+                       w.psum, w.pcnt);
+    hipLaunchKernelGGL(kmeans_finish_kernel, dim3((k * d + 255) / 256), dim3(256), 0, st, w.psum, w.pcnt, nb, k, d,
+                       centres);
     TAP_HIP(hipGetLastError());
   }
   TAP_HIP(hipStreamSynchronize(st));
@@ -934,7 +1119,7 @@ int kmeans_impl(const float *U, int N, int d, int k, const int *init_idx, int ma
 }
 
 int aggregate_impl(const int *labels, int m, int N, int k, int *out, int *perm_out, void *work, hipStream_t st) {
-  SmallWork w(work, k);
+  SmallWork w(work, 1, 1, k);
   hipLaunchKernelGGL(identity_perm_kernel, dim3((k + 255) / 256), dim3(256), 0, st, w.perm, k);
   for (int i = 1; i < m; ++i) {
     hipLaunchKernelGGL(fill_int_kernel, dim3((k * k + 255) / 256), dim3(256), 0, st, w.T, k * k, 0);
@@ -965,6 +1150,28 @@ int qc_tap_workspace_bytes(int N, int F, int n, int k, int kb, size_t *bytes_out
   return QC_OK;
 }
 
+int qc_tap_profile_begin(void) {
+  g_prof.on = true;
+  g_prof.used = 0;
+  return QC_OK;
+}
+
+int qc_tap_profile_end(float *sim_ms_out, int *launches_out) {
+  if (!sim_ms_out || !launches_out) TAP_FAIL(QC_ERR_NULL, "an output pointer is NULL");
+  if (!g_prof.on) TAP_FAIL(QC_ERR_STATE, "qc_tap_profile_begin was not called");
+  g_prof.on = false;
+  float total = 0.f;
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    TAP_HIP(hipEventSynchronize(g_prof.ev[i].second));
+    float ms = 0.f;
+    TAP_HIP(hipEventElapsedTime(&ms, g_prof.ev[i].first, g_prof.ev[i].second));
+    total += ms;
+  }
+  *sim_ms_out = total;
+  *launches_out = (int)g_prof.used;
+  return QC_OK;
+}
+
 int qc_tap_similarity(const float *X, const float *t, int N, int F, const int *idx, int n, float alpha, float *A,
                       float *d_r, float *d_c, void *work, size_t work_bytes, void *stream) {
   if (!X || !t || !idx || !A || !d_r || !d_c) TAP_FAIL(QC_ERR_NULL, "a required pointer is NULL");
@@ -982,7 +1189,7 @@ int qc_tap_normalise(float *A, const float *d_r, const float *d_c, int N, int n,
   if (!A || !d_r || !d_c) TAP_FAIL(QC_ERR_NULL, "a required pointer is NULL");
   if (N < 1 || n < 1) TAP_FAIL(QC_ERR_SHAPE, "N and n must be positive");
   if ((long long)N * n >= (1ll << 31)) TAP_FAIL(QC_ERR_UNSUPPORTED, "N * n must be below 2^31");
-  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, 1).bytes));
+  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, 1, 1, 1).bytes));
   return normalise_impl(A, d_r, d_c, N, n, work, static_cast<hipStream_t>(stream));
 }
 
@@ -992,7 +1199,7 @@ int qc_tap_embed(const float *L, int N, int n, int k, int kb, int iters, const f
   TAP_RC(check_dims(N, 1, n, k, kb));
   if (iters < 0 || iters > 1000) TAP_FAIL(QC_ERR_RANGE, "iters must lie in [0, 1000]");
   if (!aligned16(L) || !aligned16(q0) || !aligned16(U)) TAP_FAIL(QC_ERR_ALIGN, "L, q0 and U must be 16-byte aligned");
-  TAP_RC(check_work(work, work_bytes, EmbedWork(nullptr, n, k, kb).bytes));
+  TAP_RC(check_work(work, work_bytes, EmbedWork(nullptr, N, n, k, kb).bytes));
   return embed_impl(L, N, n, k, kb, iters, q0, U, sigma, work, static_cast<hipStream_t>(stream));
 }
 
@@ -1003,7 +1210,7 @@ int qc_tap_kmeans(const float *U, int N, int d, int k, const int *init_idx, int 
   if (d > KB_MAX || k > KB_MAX) TAP_FAIL(QC_ERR_UNSUPPORTED, "d and k must be at most %d", KB_MAX);
   if ((long long)N * d >= (1ll << 31)) TAP_FAIL(QC_ERR_UNSUPPORTED, "N * d must be below 2^31");
   if (max_iter < 1) TAP_FAIL(QC_ERR_RANGE, "max_iter must be at least 1");
-  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, k).bytes));
+  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, N, d, k).bytes));
   return kmeans_impl(U, N, d, k, init_idx, max_iter, labels, centres, passes_out, work, static_cast<hipStream_t>(stream));
 }
 
@@ -1014,7 +1221,7 @@ int qc_tap_aggregate(const int *labels, int m, int N, int k, int *out, int *perm
   if (m > M_MAX) TAP_FAIL(QC_ERR_UNSUPPORTED, "at most %d label vectors", M_MAX);
   if (k > KB_MAX) TAP_FAIL(QC_ERR_UNSUPPORTED, "k must be at most %d", KB_MAX);
   if ((long long)m * N >= (1ll << 31)) TAP_FAIL(QC_ERR_UNSUPPORTED, "m * N must be below 2^31");
-  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, k).bytes));
+  TAP_RC(check_work(work, work_bytes, SmallWork(nullptr, 1, 1, k).bytes));
   return aggregate_impl(labels, m, N, k, out, perm_out, work, static_cast<hipStream_t>(stream));
 }
 

@@ -168,7 +168,7 @@ def test_kmeans_matches_oracle(qc, N, d, k, spread):
     init = rng.choice(N, k, replace=False).astype(np.int32)
     labels = torch.empty(N, dtype=torch.int32, device="cuda")
     centres = torch.empty((k, d), device="cuda")
-    passes = qc.qc_tap_kmeans(_cuda(U), _cuda(init), 100, labels, centres, _work(qc, 256, 8, 128, k, 128))
+    passes = qc.qc_tap_kmeans(_cuda(U), _cuda(init), 100, labels, centres, _work(qc, max(N, 256), 8, 128, k, 128))
     wl, wc, wp = tap.kmeans(U, init, 100)
     nd = _check_labels(U, labels.cpu().numpy(), wl, wc)
     if nd == 0:
@@ -241,3 +241,84 @@ def test_cluster_recovers_planted_groups_like_the_oracle(qc, N, F, k, n, kb):
     assert np.array_equal(per.cpu().numpy(), wp)
     assert np.array_equal(final.cpu().numpy(), wf)
     assert np.array_equal(final.cpu().numpy(), truth)                # centre g starts inside planted group g
+
+
+# ------------------------------------------------------- the paper's sizes, in the configuration bench.py times
+def test_paper_sized_pool_sampled_outputs_and_properties(qc):
+    """N = 32768 samples of 4096 features, subsamples of N / 20, 100 clusters, iteration block 128, 8 power
+    iterations: entries, degrees and normalised entries on sampled rows and columns against the oracle one by one;
+    the embedding and the k-means result through properties that hold at any size."""
+    import torch
+    wl = TI.TAP_WORKLOADS["tap1"]
+    kb, iters = 128, 8
+    N, F, n, k = wl.N, wl.F, wl.n, wl.k
+    X, t, _, _ = TI.make_pool(N, F, wl.steps, wl.classes, wl.seed)
+    idx = TI.make_subsamples(N, n, wl.m, wl.seed + 1)[0]
+    rng = np.random.default_rng(77)
+    R = np.sort(rng.choice(N, 24, replace=False))
+    R[0], R[-1] = 0, N - 1                                           # first and last row tile
+    H = np.array([0, 1, 127, 128, n // 2, n - 1])                    # tile edges and the ragged last column tile
+    Xd, td = _cuda(X), _cuda(t)
+    A = torch.empty((N, n), device="cuda")
+    dr, dc = torch.empty(N, device="cuda"), torch.empty(n, device="cuda")
+    work = _work(qc, N, F, n, k, kb)
+    qc.qc_tap_similarity(Xd, td, _cuda(idx), wl.alpha, A, dr, dc, work)
+    # sampled rows against all subsample columns (gives their degrees too)
+    rows = tap.similarity(np.concatenate([X[R], X[idx]]), np.concatenate([t[R], t[idx]]), len(R) + np.arange(n), wl.alpha)[:len(R)]
+    assert np.abs(A[_cuda(R)].cpu().numpy() - rows).max() <= 2e-6
+    assert np.allclose(dr[_cuda(R)].cpu().numpy(), rows.sum(1), rtol=2e-6)
+    # sampled columns against all pool rows
+    cols = np.concatenate([tap.similarity(X, t, [int(idx[h])], wl.alpha) for h in H], axis=1)       # [N, len(H)]
+    assert np.abs(A[:, _cuda(H)].cpu().numpy() - cols).max() <= 2e-6
+    assert np.allclose(dc[_cuda(H)].cpu().numpy(), cols.sum(0), rtol=2e-6)
+    qc.qc_tap_normalise(A, dr, dc, work)
+    want = rows[:, H] / np.sqrt(rows.sum(1))[:, None] / np.sqrt(cols.sum(0))[None, :]
+    got = A[_cuda(R)][:, _cuda(H)].cpu().numpy()
+    assert np.allclose(got, want, rtol=5e-6)
+
+    U = torch.empty((N, k), device="cuda")
+    sig = torch.empty(k, device="cuda")
+    qc.qc_tap_embed(A, k, iters, _cuda(TI.make_start_block(kb, n, wl.seed + 3)), U, sig, work)
+    s = sig.cpu().numpy().astype(np.float64)
+    assert abs(s[0] - 1.0) <= 1e-5 and np.all(np.diff(s) <= 1e-7) and s[-1] > 0      # sigma_1 = 1, descending
+    Ud = U.double()
+    assert float((Ud.T @ Ud - torch.eye(k, device="cuda", dtype=torch.float64)).abs().max()) <= 1e-5
+    # the leading left singular vector of the normalised matrix is sqrt(d_r) up to scale
+    u1 = torch.sqrt(dr.double() / dr.double().sum())
+    assert abs(abs(float(u1 @ Ud[:, 0])) - 1.0) <= 1e-6
+    # singular pairs: L L^T u_j = sigma_j^2 u_j for the leading, well separated ones
+    Ld = A.double()
+    for j in range(5):
+        res = Ld @ (Ld.T @ Ud[:, j]) - s[j] ** 2 * Ud[:, j]
+        assert float(res.norm()) <= 1e-5 * s[0] ** 2, (j, float(res.norm()))
+    del Ld
+
+    labels = torch.empty(N, dtype=torch.int32, device="cuda")
+    centres = torch.empty((k, k), device="cuda")
+    init = TI.make_init(N, k, wl.m, wl.seed + 2)[0]
+    passes = qc.qc_tap_kmeans(U, _cuda(init), 100, labels, centres, work)
+    assert 2 <= passes <= 100
+    lab = labels.cpu().numpy()
+    assert lab.min() >= 0 and lab.max() < k
+    Uh, c = U.cpu().numpy().astype(np.float64), centres.cpu().numpy().astype(np.float64)
+    if passes < 100:
+        # converged: every sampled row sits with its nearest centre, every centre is the mean of its rows
+        samp = rng.choice(N, 2000, replace=False)
+        d2 = ((Uh[samp, None, :] - c[None]) ** 2).sum(-1)
+        mine = d2[np.arange(len(samp)), lab[samp]]
+        assert np.all(mine <= d2.min(1) * (1 + 1e-5) + 1e-14)
+        for g in (0, k // 2, k - 1):
+            members = Uh[lab == g]
+            if len(members):
+                assert np.allclose(c[g], members.mean(0), rtol=1e-5, atol=1e-7)
+
+
+def test_paper_sized_aggregation_is_bit_exact(qc):
+    import torch
+    N, k, m = 32768, 100, 3
+    rng = np.random.default_rng(78)
+    base = rng.integers(0, k, size=N)
+    labels = np.stack([np.where(rng.random(N) < 0.08, rng.integers(0, k, size=N), rng.permutation(k)[base]) for _ in range(m)]).astype(np.int32)
+    out = torch.empty(N, dtype=torch.int32, device="cuda")
+    qc.qc_tap_aggregate(_cuda(labels), k, out, _work(qc, 256, 8, 128, k, 128))
+    assert np.array_equal(out.cpu().numpy(), tap.aggregate(labels, k))

@@ -39,6 +39,8 @@ TRAFFIC = {
     ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc1"): (7676.6 * 2.0 + 4608.0) * 1024,
     ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_proj"): (6164.1 * 2.0 + 9216.0) * 1024,
     ("dit_xl2_256_w8a8_b8_ddim50_n2", "attention"): (7283.5 * 2.0 + 1536.0) * 1024,
+    # profiles/clustering_tap1_counters.txt
+    ("tap1", "similarity"): (1707711.9 * 2.0 + 278726.8) * 1024,
 }
 
 
@@ -163,7 +165,8 @@ def bench_tap(args):
                    "kmeans_pass_limit": TAP_MAX_PASSES},
         "roofline": {"bound": "mfma", "kernel": "similarity (sgemm_kernel, cosine + temporal epilogue)", "achieved": ach,
                      "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / FP32_MFMA_PEAK_TFLOPS,
-                     "traffic": None, "avg_launch_us": sim_ms / launches * 1e3, "launches": launches},
+                     "traffic": TRAFFIC.get((wl.name, "similarity")), "avg_launch_us": sim_ms / launches * 1e3,
+                     "launches": launches},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = tap_cpu_baseline(wl)

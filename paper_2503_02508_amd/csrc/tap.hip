@@ -49,7 +49,12 @@ __device__ __forceinline__ double wave_sum(double v) {
 // each 64 x 64 = 2 x 2 blocks of v_mfma_f32_32x32x2_f32), K walked in slabs of 32 staged through LDS k-major, so that
 // an operand fetch is 32 consecutive floats per half wavefront.  The next slab's global loads are in flight while the
 // current one is multiplied.
-constexpr int TM = 128, TN = 128, TK = 32, LDT = 132;
+constexpr int TM = 128, TN = 128, TK = 32;
+// LDS row stride (floats) of a k-major tile.  An operand contiguous along k is transposed on the way in: lane l
+// writes element (k = 4 (l % 8) + i, o = l / 8); 4 * 130 = 8 (mod 64) spreads the 64 lanes over 64 banks.  An operand
+// contiguous along its own index is stored with 16-byte writes and needs a stride that is a multiple of 4.
+template <bool KC>
+constexpr int ldt() { return KC ? 130 : 132; }
 
 enum SgemmEpi { SE_PLAIN = 0, SE_SIM = 1, SE_COLSCALE = 2 };
 
@@ -72,9 +77,13 @@ struct SgemmArgs {
 // One operand's share of a slab for this thread: four units of four consecutive elements.
 //  KC: unit u -> (o = u / 8, k4 = (u % 8) * 4), elements along k
 //  else: unit u -> (k = u / 32, o4 = (u % 32) * 4), elements along o
-template <bool KC>
-__device__ __forceinline__ void load_units(const float *P, long long so, long long sk, int o0, int O, int k0, int K,
-                                           bool vec, int tid, float4 (&r)[4]) {
+// Out-of-range elements are loaded from a clamped (valid) address and zeroed only when the slab is written to LDS
+// (bit 4 p + i of the returned mask = element i of unit p is in range): nothing touches a loaded register before
+// that, so all loads of a slab stay in flight together while the previous slab is multiplied.
+template <bool KC, bool vec>
+__device__ __forceinline__ unsigned load_units(const float *P, long long so, long long sk, int o0, int O, int k0, int K,
+                                               int tid, float4 (&r)[4]) {
+  unsigned mask = 0;
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int u = tid + 256 * p;
@@ -82,15 +91,15 @@ __device__ __forceinline__ void load_units(const float *P, long long so, long lo
       const int o = o0 + (u >> 3), k = k0 + ((u & 7) << 2);
       if (vec) {
         const bool ok = o < O && k < K;
-        const float4 v = *reinterpret_cast<const float4 *>(P + (ok ? (long long)o * so + k : 0));
-        r[p] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+        r[p] = *reinterpret_cast<const float4 *>(P + (ok ? (long long)o * so + k : 0));
+        mask |= ok ? 0xFu << (4 * p) : 0u;
       } else {
         float e[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const bool ok = o < O && k + i < K;
-          const float v = P[ok ? (long long)o * so + (long long)(k + i) * sk : 0];
-          e[i] = ok ? v : 0.f;
+          e[i] = P[ok ? (long long)o * so + (long long)(k + i) * sk : 0];
+          mask |= ok ? 1u << (4 * p + i) : 0u;
         }
         r[p] = make_float4(e[0], e[1], e[2], e[3]);
       }
@@ -98,8 +107,8 @@ __device__ __forceinline__ void load_units(const float *P, long long so, long lo
       const int k = k0 + (u >> 5), o = o0 + ((u & 31) << 2);
       if (vec) {
         const bool ok = o < O && k < K;
-        const float4 v = *reinterpret_cast<const float4 *>(P + (ok ? (long long)k * sk + o : 0));
-        r[p] = ok ? v : make_float4(0.f, 0.f, 0.f, 0.f);
+        r[p] = *reinterpret_cast<const float4 *>(P + (ok ? (long long)k * sk + o : 0));
+        mask |= ok ? 0xFu << (4 * p) : 0u;
       } else {
         // element loads: lane l takes o = l % 32 + 32 i, so that every load covers 32 consecutive floats
         const int ob = o0 + (u & 31);
@@ -107,45 +116,52 @@ __device__ __forceinline__ void load_units(const float *P, long long so, long lo
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const bool ok = ob + 32 * i < O && k < K;
-          const float v = P[ok ? (long long)k * sk + (long long)(ob + 32 * i) * so : 0];
-          e[i] = ok ? v : 0.f;
+          e[i] = P[ok ? (long long)k * sk + (long long)(ob + 32 * i) * so : 0];
+          mask |= ok ? 1u << (4 * p + i) : 0u;
         }
         r[p] = make_float4(e[0], e[1], e[2], e[3]);
       }
     }
   }
+  return mask;
 }
 
-template <bool KC>
-__device__ __forceinline__ void store_units(float *T, int tid, bool vec, const float4 (&r)[4]) {
+template <bool KC, bool vec>
+__device__ __forceinline__ void store_units(float *T, int tid, unsigned mask, const float4 (&r)[4]) {
+  constexpr int LDT = ldt<KC>();
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int u = tid + 256 * p;
+    const float x = (mask >> (4 * p)) & 1u ? r[p].x : 0.f, y = (mask >> (4 * p + 1)) & 1u ? r[p].y : 0.f;
+    const float z = (mask >> (4 * p + 2)) & 1u ? r[p].z : 0.f, w = (mask >> (4 * p + 3)) & 1u ? r[p].w : 0.f;
     if (KC) {
       const int o = u >> 3, k = (u & 7) << 2;
-      T[(k + 0) * LDT + o] = r[p].x;
-      T[(k + 1) * LDT + o] = r[p].y;
-      T[(k + 2) * LDT + o] = r[p].z;
-      T[(k + 3) * LDT + o] = r[p].w;
+      T[(k + 0) * LDT + o] = x;
+      T[(k + 1) * LDT + o] = y;
+      T[(k + 2) * LDT + o] = z;
+      T[(k + 3) * LDT + o] = w;
     } else {
       const int k = u >> 5;
       if (vec) {
-        *reinterpret_cast<float4 *>(T + k * LDT + ((u & 31) << 2)) = r[p];
+        *reinterpret_cast<float4 *>(T + k * LDT + ((u & 31) << 2)) = make_float4(x, y, z, w);
       } else {
         float *d = T + k * LDT + (u & 31);
-        d[0] = r[p].x;
-        d[32] = r[p].y;
-        d[64] = r[p].z;
-        d[96] = r[p].w;
+        d[0] = x;
+        d[32] = y;
+        d[64] = z;
+        d[96] = w;
       }
     }
   }
 }
 
-template <bool AKC, bool BKC, int EPI>
+// VEC: both operands take 16-byte loads (a compile-time choice: a run-time branch around the loads would make the
+// compiler wait for them at the join and expose their latency)
+template <bool AKC, bool BKC, int EPI, bool VEC>
 __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs p) {
-  __shared__ __align__(16) float As[TK * LDT];
-  __shared__ __align__(16) float Bs[TK * LDT];
+  constexpr int LDA = ldt<AKC>(), LDB = ldt<BKC>();
+  __shared__ __align__(16) float As[2][TK * LDA];
+  __shared__ __align__(16) float Bs[2][TK * LDB];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tiles_m = (p.M + TM - 1) / TM, tiles_n = (p.N + TN - 1) / TN;
   const int total = tiles_m * tiles_n;
@@ -165,35 +181,58 @@ __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // Two LDS buffers: while slab s is multiplied from one, slab s + 1 (already in registers) is written to the other
+  // and slab s + 2 is requested from memory; one barrier per slab.  A buffer is overwritten two slabs after it was
+  // read, and the barrier in between is passed only by wavefronts that have finished reading it.
   float4 ra[4], rb[4];
   const int kbeg = blockIdx.y * p.kchunk, kend = min(p.K, kbeg + p.kchunk);
   const int nslab = (kend - kbeg + TK - 1) / TK;
   if (EPI == SE_PLAIN) p.C += (long long)blockIdx.y * p.part_stride;
-  load_units<AKC>(p.A, p.sam, p.sak, m0, p.M, kbeg, kend, p.a_vec, tid, ra);
-  load_units<BKC>(p.B, p.sbn, p.sbk, n0, p.N, kbeg, kend, p.b_vec, tid, rb);
+  unsigned ma = load_units<AKC, VEC>(p.A, p.sam, p.sak, m0, p.M, kbeg, kend, tid, ra);
+  unsigned mb = load_units<BKC, VEC>(p.B, p.sbn, p.sbk, n0, p.N, kbeg, kend, tid, rb);
+  store_units<AKC, VEC>(As[0], tid, ma, ra);
+  store_units<BKC, VEC>(Bs[0], tid, mb, rb);
+  ma = load_units<AKC, VEC>(p.A, p.sam, p.sak, m0, p.M, kbeg + TK, kend, tid, ra);
+  mb = load_units<BKC, VEC>(p.B, p.sbn, p.sbk, n0, p.N, kbeg + TK, kend, tid, rb);
+  __syncthreads();
   for (int s = 0; s < nslab; ++s) {
-    __syncthreads();
-    store_units<AKC>(As, tid, p.a_vec, ra);
-    store_units<BKC>(Bs, tid, p.b_vec, rb);
-    __syncthreads();
+    const int cur = s & 1;
     if (s + 1 < nslab) {
-      load_units<AKC>(p.A, p.sam, p.sak, m0, p.M, kbeg + (s + 1) * TK, kend, p.a_vec, tid, ra);
-      load_units<BKC>(p.B, p.sbn, p.sbk, n0, p.N, kbeg + (s + 1) * TK, kend, p.b_vec, tid, rb);
+      store_units<AKC, VEC>(As[cur ^ 1], tid, ma, ra);
+      store_units<BKC, VEC>(Bs[cur ^ 1], tid, mb, rb);
     }
-    const float *ap = As + (lane >> 5) * LDT + wm0 + (lane & 31);
-    const float *bp = Bs + (lane >> 5) * LDT + wn0 + (lane & 31);
+    if (s + 2 < nslab) {
+      ma = load_units<AKC, VEC>(p.A, p.sam, p.sak, m0, p.M, kbeg + (s + 2) * TK, kend, tid, ra);
+      mb = load_units<BKC, VEC>(p.B, p.sbn, p.sbk, n0, p.N, kbeg + (s + 2) * TK, kend, tid, rb);
+    }
+    const float *ap = As[cur] + (lane >> 5) * LDA + wm0 + (lane & 31);
+    const float *bp = Bs[cur] + (lane >> 5) * LDB + wn0 + (lane & 31);
 #pragma unroll
     for (int kk = 0; kk < TK / 2; ++kk) {
-      const float a0 = ap[kk * 2 * LDT], a1 = ap[kk * 2 * LDT + 32];
-      const float b0 = bp[kk * 2 * LDT], b1 = bp[kk * 2 * LDT + 32];
+      const float a0 = ap[kk * 2 * LDA], a1 = ap[kk * 2 * LDA + 32];
+      const float b0 = bp[kk * 2 * LDB], b1 = bp[kk * 2 * LDB + 32];
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
     }
+    __syncthreads();
   }
 
-  // epilogue: register r of a 32 x 32 block is row 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32
+  // epilogue: register r of a 32 x 32 block is row 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32.  The row
+  // factors of the similarity epilogue are fetched for all 32 rows of this lane in one batch (clamped, branch-free)
+  float rsv[2][16], trv[2][16];
+  if (EPI == SE_SIM) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        const int mm = m < p.M ? m : p.M - 1;
+        rsv[i][r] = p.rs[mm];
+        trv[i][r] = p.tr[mm];
+      }
+  }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int n = n0 + wn0 + j * 32 + (lane & 31);
@@ -206,11 +245,10 @@ __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (!nok || m >= p.M) continue;
         float v = acc[i][j][r];
-        if (EPI == SE_SIM) v = p.alpha * (v * p.rs[m] * csn) + (1.f - p.alpha) * expf(-fabsf(p.tr[m] - tcn));
+        if (EPI == SE_SIM) v = p.alpha * (v * rsv[i][r] * csn) + (1.f - p.alpha) * expf(-fabsf(trv[i][r] - tcn));
         if (EPI == SE_COLSCALE) v *= csn;
-        p.C[(long long)m * p.ldc + n] = v;
+        if (nok && m < p.M) p.C[(long long)m * p.ldc + n] = v;
       }
   }
 }
@@ -253,7 +291,12 @@ hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st, float *part = nullptr, si
       a.C = part;
     }
   }
-#define SG_LAUNCH(AK, BK, E) hipLaunchKernelGGL((sgemm_kernel<AK, BK, E>), dim3(grid, splits), dim3(256), 0, st, a)
+  const bool vec = a.a_vec && a.b_vec;
+#define SG_LAUNCH(AK, BK, E)                                                                                   \
+  do {                                                                                                         \
+    if (vec) hipLaunchKernelGGL((sgemm_kernel<AK, BK, E, true>), dim3(grid, splits), dim3(256), 0, st, a);     \
+    else hipLaunchKernelGGL((sgemm_kernel<AK, BK, E, false>), dim3(grid, splits), dim3(256), 0, st, a);        \
+  } while (0)
   if (epi == SE_SIM) {
     if (a.a_kc && a.b_kc) SG_LAUNCH(true, true, SE_SIM);
     else return hipErrorInvalidValue;
@@ -419,82 +462,129 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double *part, in
   W[i] = s;
 }
 
-// Inverse Cholesky factor of W + shift I (= Lc Lc^T, Lc lower), one workgroup, the matrix in LDS (fp64).  The shift,
-// shift_rel times the largest diagonal entry, keeps the factorisation alive when the rows are numerically dependent
-// (shifted Cholesky QR: the rows come out better conditioned, not yet orthonormal, and the next pass finishes).
-// The sweep is the square-root-free form: at column j, with pivot p_j, every later row i takes
-//   trailing matrix  w_iq -= w_ij w_qj / p_j   (j < q <= i)
-//   inverse          r_iq -= w_ij r_jq / p_j   (q <= j; r starts as the identity)
-// which reads only column j and writes only columns beyond j, so one barrier per column suffices.  Then
-// Lc = w diag(p)^-1/2 and Lc^-1 = diag(p)^-1/2 r.  r's strict lower triangle lives in the strict upper triangle of the
-// LDS matrix (r_iq at [q][i]); its diagonal is 1.  Out: Rinv[kb, kb] fp32 = Lc^-1 (lower triangular), so that Rinv Y
-// has orthonormal rows when the shift is negligible.  With `check` set (the last pass, whose input should already be
-// near orthonormal) a pivot below 1/4 raises the flag: the block has no full rank.  A non-positive pivot always
-// raises it.  Thread (ty, tx) of the 8 x 128 workgroup handles rows i = j + 1 + ty, + 8, ... and column q = tx.
+// Inverse Cholesky factor of W + shift I (= Lc Lc^T, Lc lower), one workgroup.  The shift, shift_rel times the largest
+// diagonal entry, keeps the factorisation alive when the rows are numerically dependent (shifted Cholesky QR: the
+// rows come out better conditioned, not yet orthonormal, and the next pass finishes).
+// The sweep is the square-root-free form on one kb x kb array S: the lower triangle and diagonal hold the trailing
+// matrix w, the strict upper triangle the inverse being built, r_iq (i > q) at S[q][i], r's unit diagonal implicit.
+// At column j, with pivot p_j = S[j][j], every element beyond column j takes
+//   S[R][C] -= g(R) g(C) / p_j,   g(x) = S[x][j] for x != j, g(j) = 1,   for C > j and (R >= C or R <= j)
+// (R >= C: trailing matrix w_RC -= w_Rj w_Cj / p_j;  R <= j: inverse r_CR -= w_Cj r_jR / p_j), which reads only column
+// j.  Thread (ty, tx) of the 8 x 128 workgroup keeps S[ty + 8 q][tx], q = 0..15, in registers; the owners of column
+// j publish it through LDS (two buffers in turn, so one barrier per column suffices).  Then Lc^-1 = diag(p)^-1/2 r.
+// Out: Rinv[kb, kb] fp32 = Lc^-1 (lower triangular), so that Rinv Y has orthonormal rows when the shift is
+// negligible.  With `check` set (the last pass, whose input should already be near orthonormal) the kernel returns the
+// identity at once when W is the identity to 1e-5, and a pivot below 1/4 raises the flag: the block has no full
+// rank.  A non-positive pivot always raises it.
 __global__ __launch_bounds__(1024) void chol_inv_kernel(const double *W, int kb, double shift_rel, int check,
                                                          float *Rinv, int *flag) {
-  extern __shared__ double Ws[];
+  __shared__ double colbuf[2][KB_MAX];
+  __shared__ double pivs[KB_MAX];
   __shared__ double dmax;
   const int tid = threadIdx.x, tx = tid & 127, ty = tid >> 7;
-  const int ld = kb + 1;
-  for (int u = tid; u < kb * kb; u += 1024) {
-    const int i = u / kb, c = u % kb;
-    Ws[i * ld + c] = c <= i ? W[u] : 0.0;
+  constexpr int NQ = KB_MAX / 8;
+  double S[NQ];
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    const int R = ty + 8 * q;
+    const bool in = tx < kb && R < kb && R >= tx;
+    const double v = W[in ? R * kb + tx : 0];
+    S[q] = in ? v : 0.0;
+    if (R == tx && R < kb) pivs[R] = S[q];
+  }
+  // last pass only: rows that are already orthonormal to fp32 level (|W - I| <= 1e-5 everywhere) are left as they are
+  if (check) {
+    double dev = 0.0;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int R = ty + 8 * q;
+      const bool in = tx < kb && R < kb && R >= tx;
+      const double d = fabs(S[q] - (R == tx ? 1.0 : 0.0));
+      dev = in ? fmax(dev, d) : dev;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) dev = fmax(dev, __shfl_xor(dev, o, 64));
+    if ((tid & 63) == 0) colbuf[0][tid >> 6] = dev;
   }
   __syncthreads();
   if (tid == 0) {
     double m = 0.0;
-    for (int i = 0; i < kb; ++i) m = fmax(m, Ws[i * ld + i]);
+    for (int i = 0; i < kb; ++i) m = fmax(m, pivs[i]);
     dmax = m;
   }
-  __syncthreads();
-  for (int i = tid; i < kb; i += 1024) Ws[i * ld + i] += shift_rel * dmax;
-  __syncthreads();
-  for (int j = 0; j < kb; ++j) {
-    double piv = Ws[j * ld + j];
-    if (!(piv > 0.0) || !isfinite(piv)) {
-      if (tid == 0) {
-        atomicOr(flag, 2);
-        Ws[j * ld + j] = 1.0;             // nobody else writes the pivot; readers of this column use the local value
+  if (check) {
+    double dev = 0.0;
+    for (int w = 0; w < 16; ++w) dev = fmax(dev, colbuf[0][w]);
+    if (dev <= 1e-5) {                    // the same value in every thread: the whole workgroup leaves together
+      if (tx < kb) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          const int R = ty + 8 * q;
+          if (R < kb) Rinv[tx * kb + R] = R == tx ? 1.f : 0.f;
+        }
       }
+      return;
+    }
+  }
+  __syncthreads();
+  const double shift = shift_rel * dmax;
+#pragma unroll
+  for (int q = 0; q < NQ; ++q)
+    if (ty + 8 * q == tx) S[q] += shift;
+  for (int j = 0; j < kb; ++j) {
+    double *buf = colbuf[j & 1];
+    if (tx == j) {
+#pragma unroll
+      for (int q = 0; q < NQ; ++q)
+        if (ty + 8 * q < kb) buf[ty + 8 * q] = S[q];
+    }
+    __syncthreads();
+    double piv = buf[j];
+    if (!(piv > 0.0) || !isfinite(piv)) {
+      if (tid == 0) atomicOr(flag, 2);
       piv = 1.0;
     } else if (check && piv < 0.25) {
       if (tid == 0) atomicOr(flag, 2);
     }
-    if (tx < kb) {
+    if (tid == 0) pivs[j] = piv;
+    // wavefronts whose columns are all done skip the update; inside, every load is unconditional (clamped) and the
+    // per-element conditions are selects, so the LDS reads of a column are in flight together
+    if ((((tid | 63) & 127) > j)) {
       // 1 / p: hardware estimate refined by two Newton steps
       double inv_p = __builtin_amdgcn_rcp(piv);
       inv_p = inv_p * (2.0 - piv * inv_p);
       inv_p = inv_p * (2.0 - piv * inv_p);
-      // column j: rows below the diagonal hold w_qj, rows above it r_jq, the diagonal stands for r_jj = 1
-      const double colq = (tx == j ? 1.0 : Ws[tx * ld + j]) * inv_p;
-      // this thread's rows i = j + 1 + ty + 8 s: all loads first, then the updates, so that the LDS latencies overlap
-      const bool lower = tx > j;
-      double f[KB_MAX / 8], t[KB_MAX / 8];
+      const bool col_on = tx > j && tx < kb;
+      const double gc = buf[tx < kb ? tx : 0] * inv_p;
+      double g[NQ];
 #pragma unroll
-      for (int q = 0; q < KB_MAX / 8; ++q) {
-        const int i = j + 1 + ty + 8 * q;
-        const bool on = i < kb && (!lower || tx <= i);
-        const int ii = i < kb ? i : j;                       // any valid row
-        f[q] = Ws[ii * ld + j];
-        t[q] = Ws[lower ? ii * ld + tx : tx * ld + ii];
-        if (!on) f[q] = 0.0;
+      for (int q = 0; q < NQ; ++q) {
+        const int R = ty + 8 * q;
+        g[q] = buf[R < kb ? R : 0];
       }
 #pragma unroll
-      for (int q = 0; q < KB_MAX / 8; ++q) {
-        const int i = j + 1 + ty + 8 * q;
-        if (i < kb && (!lower || tx <= i)) Ws[lower ? i * ld + tx : tx * ld + i] = fma(-f[q], colq, t[q]);
+      for (int q = 0; q < NQ; ++q) {
+        const int R = ty + 8 * q;
+        const bool on = col_on && R < kb && (R >= tx || R <= j);
+        const double gq = R == j ? 1.0 : g[q];
+        const double upd = fma(-gq, gc, S[q]);
+        S[q] = on ? upd : S[q];
       }
     }
-    __syncthreads();
+    // the buffer that column j + 1 is published to was last read at column j - 1, before this column's barrier
   }
-  for (int u = tid; u < kb * kb; u += 1024) {
-    const int i = u / kb, c = u % kb;
-    const double sc = 1.0 / sqrt(Ws[i * ld + i]);
-    double v = 0.0;
-    if (i == c) v = sc;
-    else if (i > c) v = Ws[c * ld + i] * sc;
-    Rinv[u] = (float)v;
+  __syncthreads();
+  if (tx < kb) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int R = ty + 8 * q;
+      if (R >= kb) continue;
+      // S[R][tx] with R < tx is r_{tx, R}: row tx of the inverse; everything above the diagonal of Rinv is zero
+      float v = 0.f;
+      if (R == tx) v = (float)(1.0 / sqrt(pivs[R]));
+      else if (R < tx) v = (float)(S[q] / sqrt(pivs[tx]));
+      Rinv[tx * kb + R] = v;
+    }
   }
 }
 
@@ -578,7 +668,7 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const double *T, int kb, i
       }
       ga = row16_sum(ga);
       const double al = nrm2[a], be = nrm2[b];
-      if (live && fmin(al, be) > floor2 && fabs(ga) > 1e-13 * sqrt(al * be)) {
+      if (live && fmin(al, be) > floor2 && fabs(ga) > 1e-11 * sqrt(al * be)) {
         const double zeta = (be - al) / (2.0 * ga);
         const double tt = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
         const double c_ = 1.0 / sqrt(1.0 + tt * tt), s_ = c_ * tt;
@@ -1008,9 +1098,7 @@ int cholqr_pass(const float *in, float *out, int kb, int n, int check, EmbedWork
   hipLaunchKernelGGL(gram_partial_kernel, dim3(parts), dim3(256), 0, st, in, kb, n, (long long)n, 1ll, gram_chunk(n),
                      w.part);
   hipLaunchKernelGGL(gram_reduce_kernel, dim3((kb * kb + 255) / 256), dim3(256), 0, st, w.part, parts, kb * kb, w.W);
-  const size_t lds = (size_t)kb * (kb + 1) * sizeof(double);
-  TAP_HIP(set_lds((const void *)chol_inv_kernel, lds));
-  hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(1024), lds, st, w.W, kb, 1e-12, check, w.Rinv, w.flag);
+  hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(1024), 0, st, w.W, kb, 1e-12, check, w.Rinv, w.flag);
   TAP_HIP(hipGetLastError());
   SgemmArgs g{};
   g.A = w.Rinv; g.sam = kb; g.sak = 1;

@@ -12,6 +12,9 @@ byte is fetched from and written to HBM once).
 
     rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <out> -- python3 paper_2503_02508_amd/profile_driver.py
     rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <out> -- python3 paper_2503_02508_amd/profile_driver.py
+
+With `--workload tap1` the run is one subsample of the calibration-set clustering instead (similarity, degree
+normalisation, embedding, k-means at the benchmark's sizes and settings), followed by the same copies.
 """
 from __future__ import annotations
 
@@ -35,6 +38,11 @@ def main():
     import numpy as np
     import torch
     import paper_2503_02508_amd as qc
+
+    if args.workload.startswith("tap"):
+        run_tap(args, qc, np, torch)
+        copies(args, torch)
+        return
     from synthetic import dit_inputs as I
 
     wl = I.WORKLOADS[args.workload]
@@ -57,6 +65,34 @@ def main():
     for i in range(args.sampler_steps):
         ctx.sample_step(x, lab, i, tt[i], at[i], ap_[i], wl.cfg_scale, K[i])
     torch.cuda.synchronize()
+    copies(args, torch)
+
+
+def run_tap(args, qc, np, torch):
+    from synthetic import tap_inputs as TI
+    wl = TI.TAP_WORKLOADS[args.workload]
+    kb = min(128, (wl.k + 7) // 8 * 8 + 24)
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    X, t, _, _ = TI.make_pool(wl.N, wl.F, wl.steps, wl.classes, wl.seed)
+    Xd, td = dev(X), dev(t)
+    idx = dev(TI.make_subsamples(wl.N, wl.n, wl.m, wl.seed + 1)[0])
+    init = dev(TI.make_init(wl.N, wl.k, wl.m, wl.seed + 2)[0])
+    q0 = dev(TI.make_start_block(kb, wl.n, wl.seed + 3))
+    work = torch.empty(qc.qc_tap_workspace_bytes(wl.N, wl.F, wl.n, wl.k, kb), dtype=torch.uint8, device="cuda")
+    A = torch.empty((wl.N, wl.n), device="cuda")
+    dr, dc = torch.empty(wl.N, device="cuda"), torch.empty(wl.n, device="cuda")
+    U, sig = torch.empty((wl.N, wl.k), device="cuda"), torch.empty(wl.k, device="cuda")
+    lab, cen = torch.empty(wl.N, dtype=torch.int32, device="cuda"), torch.empty((wl.k, wl.k), device="cuda")
+    print("profile_driver: %s, one subsample" % wl.name, flush=True)
+    qc.qc_tap_similarity(Xd, td, idx, wl.alpha, A, dr, dc, work)
+    qc.qc_tap_normalise(A, dr, dc, work)
+    qc.qc_tap_embed(A, wl.k, 8, q0, U, sig, work)
+    qc.qc_tap_kmeans(U, init, 100, lab, cen, work)
+    torch.cuda.synchronize()
+
+
+def copies(args, torch):
     n = args.copy_mib * (1 << 20) // 4
     src = torch.ones(n, device="cuda")
     dst = torch.empty_like(src)

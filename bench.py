@@ -133,7 +133,10 @@ def bench_tap(args):
     init = dev(TI.make_init(wl.N, wl.k, wl.m, wl.seed + 2))
     q0 = dev(TI.make_start_block(kb, wl.n, wl.seed + 3))
     del X
-    work = torch.empty(qc.qc_tap_workspace_bytes(wl.N, wl.F, wl.n, wl.k, kb), dtype=torch.uint8, device="cuda")
+    # room for all subsamples at once (at most 3 are worked on together)
+    slots = min(wl.m, 3)
+    per = (qc.qc_tap_workspace_bytes(wl.N, wl.F, wl.n, wl.k, kb) + 255) // 256 * 256
+    work = torch.empty(slots * per, dtype=torch.uint8, device="cuda")
     final = torch.empty(wl.N, dtype=torch.int32, device="cuda")
     per = torch.empty((wl.m, wl.N), dtype=torch.int32, device="cuda")
 
@@ -162,6 +165,7 @@ def bench_tap(args):
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "pool": wl.N, "features": wl.F, "subsample": wl.n, "subsamples": wl.m,
                    "clusters": wl.k, "alpha": wl.alpha, "iteration_block": kb, "power_iterations": TAP_ITERS,
+                   "concurrent_subsamples": slots,
                    "kmeans_pass_limit": TAP_MAX_PASSES},
         "roofline": {"bound": "mfma", "kernel": "similarity (sgemm_kernel, cosine + temporal epilogue)", "achieved": ach,
                      "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / FP32_MFMA_PEAK_TFLOPS,

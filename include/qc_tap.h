@@ -106,8 +106,14 @@ int qc_tap_aggregate(const int *labels, int m, int N, int k, int *out, int *perm
 /* The whole algorithm: for each of the m subsamples (subsamples dev [m, n]
  * int32) similarity, normalisation, embedding (start block q0 dev [kb, n],
  * shared by the subsamples) and k-means (init_idx dev [m, k]); then the merge.
- * labels_out dev [N] int32, per_labels dev [m, N] int32 out.  Waits for the
- * stream; errors as in the calls above. */
+ * labels_out dev [N] int32, per_labels dev [m, N] int32 out.  With a workspace
+ * of s times the size qc_tap_workspace_bytes gives (s = 2 or 3) the call
+ * works on s subsamples at a time: the first on `stream`, the others on
+ * internal streams of the library that start after the work already enqueued
+ * on `stream` and have drained when the call returns (the results do not
+ * depend on s).  Waits for the stream; errors as in the calls above, reported
+ * after the k-means of the subsample concerned (the outputs are then
+ * unspecified).  Process-wide internal streams: calls must not overlap. */
 int qc_tap_cluster(const float *X, const float *t, int N, int F, const int *subsamples, int m, int n, float alpha,
                    int k, int kb, int iters, const float *q0, const int *init_idx, int max_iter, int *labels_out,
                    int *per_labels, void *work, size_t work_bytes, void *stream);

@@ -398,7 +398,10 @@ __global__ __launch_bounds__(256) void degree_check_kernel(const float *d, int c
   }
 }
 
-__global__ __launch_bounds__(256) void normalise_kernel(float *A, const float *dr, const float *dc, int N, int n) {
+// `guard` (may be null): a device flag raised by the degree check; the matrix is left alone when it is set
+__global__ __launch_bounds__(256) void normalise_kernel(float *A, const float *dr, const float *dc, int N, int n,
+                                                        const int *guard) {
+  if (guard && *guard) return;
   const int nblk = (n + 255) / 256;
   const int r = blockIdx.x / nblk;
   const int h = (blockIdx.x % nblk) * 256 + threadIdx.x;
@@ -994,6 +997,7 @@ struct SmallWork {      // k-means (N rows of d dimensions), aggregation, normal
 
 struct ClusterWork {
   float *A, *dr, *dc, *U, *sigma, *centres;
+  int *flags;           // [4]: index, degree, rank, initial-centre checks of a deferred run
   void *sub;            // region handed to the calls above
   size_t sub_bytes, bytes;
   ClusterWork(void *w, int N, int F, int n, int k, int kb) {
@@ -1004,6 +1008,7 @@ struct ClusterWork {
     U = c.take<float>((size_t)N * k);
     sigma = c.take<float>(k);
     centres = c.take<float>((size_t)k * k);
+    flags = c.take<int>(64);
     // the k-means region is sized for rows of up to kb dimensions, so that the one size also covers qc_tap_kmeans
     // on an embedding of the whole iteration block
     size_t s1 = SimWork(nullptr, N, F, n).bytes, s2 = EmbedWork(nullptr, N, n, k, kb).bytes, s3 = SmallWork(nullptr, N, kb, kb).bytes;
@@ -1039,12 +1044,26 @@ struct SimProfile {
 };
 SimProfile g_prof;
 
+// Each stage below takes `ext`: null = use the flag word in its own workspace and report the error before returning
+// (the stage waits for the stream); non-null = raise that device flag instead and only enqueue (the caller reads the
+// flags of several stages, possibly of several streams, later).
+// internal streams of qc_tap_cluster (created on first use, kept for the life of the process; default priority)
+constexpr int MAX_SLOTS = 3;
+hipStream_t g_streams[MAX_SLOTS] = {nullptr, nullptr, nullptr};
+hipEvent_t g_fork = nullptr;
+hipEvent_t g_chain[MAX_SLOTS] = {nullptr, nullptr, nullptr};
+
+// `gemm_after` (may be null): the contraction starts after this event.  A caller that runs several subsamples on
+// several streams chains them (embed_impl records the matching event after its own large product), so that the
+// chip-filling products run one after the other and only the small, latency-bound kernels overlap.
 int similarity_impl(const float *X, const float *t, int N, int F, const int *idx, int n, float alpha, float *A,
-                    float *d_r, float *d_c, void *work, hipStream_t st) {
+                    float *d_r, float *d_c, void *work, hipStream_t st, int *ext = nullptr,
+                    hipEvent_t gemm_after = nullptr) {
   SimWork w(work, N, F, n);
-  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
+  int *fl = ext ? ext : w.flag;
+  if (!ext) hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
   hipLaunchKernelGGL(rownorm_kernel, dim3((N + 3) / 4), dim3(256), 0, st, X, N, F, w.rinv);
-  hipLaunchKernelGGL(gather_kernel, dim3(n), dim3(256), 0, st, X, w.rinv, t, idx, N, F, w.Xs, w.cs, w.tc, w.flag);
+  hipLaunchKernelGGL(gather_kernel, dim3(n), dim3(256), 0, st, X, w.rinv, t, idx, N, F, w.Xs, w.cs, w.tc, fl);
   TAP_HIP(hipGetLastError());
   SgemmArgs g{};
   g.A = X; g.sam = F; g.sak = 1;
@@ -1052,6 +1071,7 @@ int similarity_impl(const float *X, const float *t, int N, int F, const int *idx
   g.C = A; g.ldc = n;
   g.M = N; g.N = n; g.K = F;
   g.rs = w.rinv; g.cs = w.cs; g.tr = t; g.tc = w.tc; g.alpha = alpha;
+  if (gemm_after) TAP_HIP(hipStreamWaitEvent(st, gemm_after, 0));
   if (g_prof.on) {
     if (g_prof.used == g_prof.ev.size()) {
       hipEvent_t a, b;
@@ -1067,24 +1087,31 @@ int similarity_impl(const float *X, const float *t, int N, int F, const int *idx
   hipLaunchKernelGGL(colsum_partial_kernel, dim3((n + 63) / 64, COL_CHUNKS), dim3(256), 0, st, A, N, n, w.colpart);
   hipLaunchKernelGGL(colsum_final_kernel, dim3((n + 255) / 256), dim3(256), 0, st, w.colpart, n, d_c);
   TAP_HIP(hipGetLastError());
+  if (ext) return QC_OK;
   int flag = 0;
   TAP_RC(read_flag(w.flag, st, &flag));
   if (flag) TAP_FAIL(QC_ERR_RANGE, "a subsample index lies outside [0, %d)", N);
   return QC_OK;
 }
 
-int normalise_impl(float *A, const float *d_r, const float *d_c, int N, int n, void *work, hipStream_t st) {
+int normalise_impl(float *A, const float *d_r, const float *d_c, int N, int n, void *work, hipStream_t st,
+                   int *ext = nullptr) {
   SmallWork w(work, 1, 1, 1);
-  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
-  hipLaunchKernelGGL(degree_check_kernel, dim3((N + 255) / 256), dim3(256), 0, st, d_r, N, w.flag);
-  hipLaunchKernelGGL(degree_check_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_c, n, w.flag);
+  int *fl = ext ? ext : w.flag;
+  if (!ext) hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
+  hipLaunchKernelGGL(degree_check_kernel, dim3((N + 255) / 256), dim3(256), 0, st, d_r, N, fl);
+  hipLaunchKernelGGL(degree_check_kernel, dim3((n + 255) / 256), dim3(256), 0, st, d_c, n, fl);
   TAP_HIP(hipGetLastError());
-  int flag = 0;
-  TAP_RC(read_flag(w.flag, st, &flag));
-  if (flag) TAP_FAIL(QC_ERR_RANGE, "a degree of the similarity matrix is not positive and finite");
-  hipLaunchKernelGGL(normalise_kernel, dim3(((n + 255) / 256) * N), dim3(256), 0, st, A, d_r, d_c, N, n);
+  if (!ext) {
+    int flag = 0;
+    TAP_RC(read_flag(w.flag, st, &flag));
+    if (flag) TAP_FAIL(QC_ERR_RANGE, "a degree of the similarity matrix is not positive and finite");
+  }
+  // with a deferred check the kernel itself leaves the matrix alone when the flag is up
+  hipLaunchKernelGGL(normalise_kernel, dim3(((n + 255) / 256) * N), dim3(256), 0, st, A, d_r, d_c, N, n,
+                     ext ? (const int *)ext : (const int *)nullptr);
   TAP_HIP(hipGetLastError());
-  TAP_HIP(hipStreamSynchronize(st));
+  if (!ext) TAP_HIP(hipStreamSynchronize(st));
   return QC_OK;
 }
 
@@ -1093,12 +1120,12 @@ hipError_t set_lds(const void *kern, size_t bytes) {
 }
 
 // one pass of shifted Cholesky QR on the rows of `in` [kb, n] into `out` (`in` and `out` must differ)
-int cholqr_pass(const float *in, float *out, int kb, int n, int check, EmbedWork &w, hipStream_t st) {
+int cholqr_pass(const float *in, float *out, int kb, int n, int check, EmbedWork &w, int *fl, hipStream_t st) {
   const int parts = gram_parts(n);
   hipLaunchKernelGGL(gram_partial_kernel, dim3(parts), dim3(256), 0, st, in, kb, n, (long long)n, 1ll, gram_chunk(n),
                      w.part);
   hipLaunchKernelGGL(gram_reduce_kernel, dim3((kb * kb + 255) / 256), dim3(256), 0, st, w.part, parts, kb * kb, w.W);
-  hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(1024), 0, st, w.W, kb, 1e-12, check, w.Rinv, w.flag);
+  hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(1024), 0, st, w.W, kb, 1e-12, check, w.Rinv, fl);
   TAP_HIP(hipGetLastError());
   SgemmArgs g{};
   g.A = w.Rinv; g.sam = kb; g.sak = 1;
@@ -1112,17 +1139,19 @@ int cholqr_pass(const float *in, float *out, int kb, int n, int check, EmbedWork
 // rows of `in` made orthonormal into w.Q: three passes, which is enough for a block whose condition number is as
 // large as 10^12 (the power iteration multiplies by L^T L, whose small eigenvalues are rounding noise in fp32); uses
 // w.Z and w.Y as intermediates (`in` may be w.Y)
-int orthonormalise(const float *in, EmbedWork &w, int kb, int n, hipStream_t st) {
-  TAP_RC(cholqr_pass(in, w.Z, kb, n, 0, w, st));
-  TAP_RC(cholqr_pass(w.Z, w.Y, kb, n, 0, w, st));
-  TAP_RC(cholqr_pass(w.Y, w.Q, kb, n, 1, w, st));
+int orthonormalise(const float *in, EmbedWork &w, int kb, int n, int *fl, hipStream_t st) {
+  TAP_RC(cholqr_pass(in, w.Z, kb, n, 0, w, fl, st));
+  TAP_RC(cholqr_pass(w.Z, w.Y, kb, n, 0, w, fl, st));
+  TAP_RC(cholqr_pass(w.Y, w.Q, kb, n, 1, w, fl, st));
   return QC_OK;
 }
 
+// `big_done` (may be null) is recorded after the one chip-filling product of this stage (L^T L)
 int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const float *q0, float *U, float *sigma,
-               void *work, hipStream_t st) {
+               void *work, hipStream_t st, int *ext = nullptr, hipEvent_t big_done = nullptr) {
   EmbedWork w(work, N, n, k, kb);
-  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
+  int *fl = ext ? ext : w.flag;
+  if (!ext) hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
   TAP_HIP(hipGetLastError());
   // G = L^T L drives the power iteration (its fp32 rounding only slows the convergence of directions whose singular
   // values are below about 3e-4 of the largest; the Rayleigh-Ritz step below works on L itself)
@@ -1132,7 +1161,8 @@ int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const flo
   g.C = w.G; g.ldc = n;
   g.M = n; g.N = n; g.K = N;
   TAP_HIP(sgemm(g, SE_PLAIN, st, w.spart, w.spart_elems));
-  TAP_RC(orthonormalise(q0, w, kb, n, st));
+  if (big_done) TAP_HIP(hipEventRecord(big_done, st));
+  TAP_RC(orthonormalise(q0, w, kb, n, fl, st));
   SgemmArgs mul{};
   mul.A = w.Q; mul.sam = n; mul.sak = 1;
   mul.B = w.G; mul.sbn = n; mul.sbk = 1;      // G is symmetric
@@ -1140,7 +1170,7 @@ int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const flo
   mul.M = kb; mul.N = n; mul.K = n;
   for (int it = 0; it < iters; ++it) {
     TAP_HIP(sgemm(mul, SE_PLAIN, st, w.spart, w.spart_elems));
-    TAP_RC(orthonormalise(w.Y, w, kb, n, st));
+    TAP_RC(orthonormalise(w.Y, w, kb, n, fl, st));
   }
   // Rayleigh-Ritz on B = L Q^T [N, kb]: T = B^T B (fp64), its k leading eigenvectors W, U = B W^T diag(1 / sigma)
   SgemmArgs bm{};
@@ -1164,45 +1194,93 @@ int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const flo
   u.M = N; u.N = k; u.K = kb;
   u.cs = w.isig;
   TAP_HIP(sgemm(u, SE_COLSCALE, st));
+  if (ext) return QC_OK;
   int flag = 0;
   TAP_RC(read_flag(w.flag, st, &flag));
   if (flag) TAP_FAIL(QC_ERR_RANGE, "the iteration block has no full rank (a zero start vector, or fewer than kb independent directions)");
   return QC_OK;
 }
 
-int kmeans_impl(const float *U, int N, int d, int k, const int *init_idx, int max_iter, int *labels, float *centres,
-                int *passes_out, void *work, hipStream_t st) {
-  SmallWork w(work, N, d, k);
-  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.flag, 64, 0);
-  hipLaunchKernelGGL(fill_int_kernel, dim3((N + 255) / 256), dim3(256), 0, st, labels, N, -1);
-  hipLaunchKernelGGL(kmeans_init_kernel, dim3(k), dim3(256), 0, st, U, N, d, k, init_idx, centres, w.flag);
-  TAP_HIP(hipGetLastError());
-  int flag = 0;
-  TAP_RC(read_flag(w.flag, st, &flag));
-  if (flag) TAP_FAIL(QC_ERR_RANGE, "an initial-centre index lies outside [0, %d)", N);
+// One k-means problem of a group that advances in lockstep, each on its own stream
+struct KmSlot {
+  const float *U;
+  const int *init_idx;
+  int *labels;
+  float *centres;
+  void *work;
+  hipStream_t st;
+  int *ext;            // null, or a device flag for the index check (read by the caller)
+  int passes;
+  bool active;
+};
+
+// Lloyd's iteration on `ns` problems of the same shape: every pass is enqueued on all streams before the host waits
+// for the first changed-label count, so the problems' kernels overlap; a problem leaves the loop when a pass changes
+// nothing.  With a null `ext` the initial-centre indices are checked (and the error reported) before the first pass.
+int kmeans_multi(KmSlot *slots, int ns, int N, int d, int k, int max_iter) {
   const size_t lds = ((size_t)k * d + (size_t)64 * (d + 1)) * sizeof(float);
   TAP_HIP(set_lds((const void *)kmeans_assign_kernel, lds));
   const size_t lds_acc = (size_t)k * d * sizeof(double);
   TAP_HIP(set_lds((const void *)kmeans_partial_kernel, lds_acc));
   const int nb = kmeans_blocks(N);
-  int passes = 0;
-  for (int it = 0; it < max_iter; ++it) {
-    hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, st, w.changed, 64, 0);
-    hipLaunchKernelGGL(kmeans_assign_kernel, dim3((N + 63) / 64), dim3(256), lds, st, U, N, d, centres, k, labels,
-                       w.changed);
+  for (int i = 0; i < ns; ++i) {
+    KmSlot &q = slots[i];
+    SmallWork w(q.work, N, d, k);
+    if (!q.ext) hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, q.st, w.flag, 64, 0);
+    hipLaunchKernelGGL(fill_int_kernel, dim3((N + 255) / 256), dim3(256), 0, q.st, q.labels, N, -1);
+    hipLaunchKernelGGL(kmeans_init_kernel, dim3(k), dim3(256), 0, q.st, q.U, N, d, k, q.init_idx, q.centres,
+                       q.ext ? q.ext : w.flag);
     TAP_HIP(hipGetLastError());
-    ++passes;
-    int changed = 0;
-    TAP_RC(read_flag(w.changed, st, &changed));
-    if (changed == 0) break;
-    hipLaunchKernelGGL(kmeans_partial_kernel, dim3(nb), dim3(128), lds_acc, st, U, N, d, labels, k, kmeans_rows_per(N),
-                       w.psum, w.pcnt);
-    hipLaunchKernelGGL(kmeans_finish_kernel, dim3((k * d + 255) / 256), dim3(256), 0, st, w.psum, w.pcnt, nb, k, d,
-                       centres);
-    TAP_HIP(hipGetLastError());
+    q.passes = 0;
+    q.active = true;
   }
-  TAP_HIP(hipStreamSynchronize(st));
-  if (passes_out) *passes_out = passes;
+  for (int i = 0; i < ns; ++i) {
+    if (slots[i].ext) continue;
+    SmallWork w(slots[i].work, N, d, k);
+    int flag = 0;
+    TAP_RC(read_flag(w.flag, slots[i].st, &flag));
+    if (flag) TAP_FAIL(QC_ERR_RANGE, "an initial-centre index lies outside [0, %d)", N);
+  }
+  for (int it = 0; it < max_iter; ++it) {
+    bool any = false;
+    for (int i = 0; i < ns; ++i) {
+      KmSlot &q = slots[i];
+      if (!q.active) continue;
+      any = true;
+      SmallWork w(q.work, N, d, k);
+      hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, q.st, w.changed, 64, 0);
+      hipLaunchKernelGGL(kmeans_assign_kernel, dim3((N + 63) / 64), dim3(256), lds, q.st, q.U, N, d, q.centres, k,
+                         q.labels, w.changed);
+      TAP_HIP(hipGetLastError());
+      ++q.passes;
+    }
+    if (!any) break;
+    for (int i = 0; i < ns; ++i) {
+      KmSlot &q = slots[i];
+      if (!q.active) continue;
+      SmallWork w(q.work, N, d, k);
+      int changed = 0;
+      TAP_RC(read_flag(w.changed, q.st, &changed));
+      if (changed == 0) {
+        q.active = false;
+        continue;
+      }
+      hipLaunchKernelGGL(kmeans_partial_kernel, dim3(nb), dim3(128), lds_acc, q.st, q.U, N, d, q.labels, k,
+                         kmeans_rows_per(N), w.psum, w.pcnt);
+      hipLaunchKernelGGL(kmeans_finish_kernel, dim3((k * d + 255) / 256), dim3(256), 0, q.st, w.psum, w.pcnt, nb, k, d,
+                         q.centres);
+      TAP_HIP(hipGetLastError());
+    }
+  }
+  for (int i = 0; i < ns; ++i) TAP_HIP(hipStreamSynchronize(slots[i].st));
+  return QC_OK;
+}
+
+int kmeans_impl(const float *U, int N, int d, int k, const int *init_idx, int max_iter, int *labels, float *centres,
+                int *passes_out, void *work, hipStream_t st) {
+  KmSlot q{U, init_idx, labels, centres, work, st, nullptr, 0, false};
+  TAP_RC(kmeans_multi(&q, 1, N, d, k, max_iter));
+  if (passes_out) *passes_out = q.passes;
   return QC_OK;
 }
 
@@ -1324,17 +1402,59 @@ int qc_tap_cluster(const float *X, const float *t, int N, int F, const int *subs
   if (iters < 0 || iters > 1000) TAP_FAIL(QC_ERR_RANGE, "iters must lie in [0, 1000]");
   if (max_iter < 1) TAP_FAIL(QC_ERR_RANGE, "max_iter must be at least 1");
   if (!aligned16(X) || !aligned16(q0)) TAP_FAIL(QC_ERR_ALIGN, "X and q0 must be 16-byte aligned");
-  ClusterWork w(work, N, F, n, k, kb);
-  TAP_RC(check_work(work, work_bytes, w.bytes));
+  const size_t per = (ClusterWork(nullptr, N, F, n, k, kb).bytes + 255) & ~size_t(255);
+  TAP_RC(check_work(work, work_bytes, per));
   hipStream_t st = static_cast<hipStream_t>(stream);
-  for (int i = 0; i < m; ++i) {
-    TAP_RC(similarity_impl(X, t, N, F, subsamples + (size_t)i * n, n, alpha, w.A, w.dr, w.dc, w.sub, st));
-    TAP_RC(normalise_impl(w.A, w.dr, w.dc, N, n, w.sub, st));
-    TAP_RC(embed_impl(w.A, N, n, k, kb, iters, q0, w.U, w.sigma, w.sub, st));
-    TAP_RC(kmeans_impl(w.U, N, k, k, init_idx + (size_t)i * k, max_iter, per_labels + (size_t)i * N, w.centres, nullptr,
-                       w.sub, st));
+  // as many subsamples at a time as the workspace holds (at most MAX_SLOTS): the first on the caller's stream, the
+  // others on internal streams that start after the work already enqueued on the caller's stream
+  int slots = (int)(work_bytes / per);
+  if (slots > MAX_SLOTS) slots = MAX_SLOTS;
+  if (slots > m) slots = m;
+  hipStream_t ss[MAX_SLOTS] = {st, nullptr, nullptr};
+  if (slots > 1) {
+    if (!g_fork) TAP_HIP(hipEventCreateWithFlags(&g_fork, hipEventDisableTiming));
+    TAP_HIP(hipEventRecord(g_fork, st));
+    for (int j = 1; j < slots; ++j) {
+      if (!g_streams[j]) TAP_HIP(hipStreamCreateWithFlags(&g_streams[j], hipStreamNonBlocking));
+      TAP_HIP(hipStreamWaitEvent(g_streams[j], g_fork, 0));
+      ss[j] = g_streams[j];
+    }
   }
-  TAP_RC(aggregate_impl(per_labels, m, N, k, labels_out, nullptr, w.sub, st));
+  for (int i0 = 0; i0 < m; i0 += slots) {
+    const int ns = m - i0 < slots ? m - i0 : slots;
+    KmSlot km[MAX_SLOTS];
+    for (int j = 0; j < ns; ++j) {
+      ClusterWork w(static_cast<char *>(work) + (size_t)j * per, N, F, n, k, kb);
+      const int i = i0 + j;
+      hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, ss[j], w.flags, 64, 0);
+      if (slots > 1 && !g_chain[j]) TAP_HIP(hipEventCreateWithFlags(&g_chain[j], hipEventDisableTiming));
+      TAP_RC(similarity_impl(X, t, N, F, subsamples + (size_t)i * n, n, alpha, w.A, w.dr, w.dc, w.sub, ss[j], w.flags + 0,
+                             j > 0 ? g_chain[j - 1] : nullptr));
+      TAP_RC(normalise_impl(w.A, w.dr, w.dc, N, n, w.sub, ss[j], w.flags + 1));
+      TAP_RC(embed_impl(w.A, N, n, k, kb, iters, q0, w.U, w.sigma, w.sub, ss[j], w.flags + 2,
+                        slots > 1 ? g_chain[j] : nullptr));
+      km[j] = KmSlot{w.U, init_idx + (size_t)i * k, per_labels + (size_t)i * N, w.centres, w.sub, ss[j], w.flags + 3, 0, false};
+    }
+    // the first pass of the k-means below runs on whatever the earlier stages left; the flags tell afterwards
+    // whether that was meaningful (every kernel stays inside its buffers on any input)
+    int rc = kmeans_multi(km, ns, N, k, k, max_iter);
+    for (int j = 0; j < ns && rc == QC_OK; ++j) {
+      ClusterWork w(static_cast<char *>(work) + (size_t)j * per, N, F, n, k, kb);
+      int fl[4] = {0, 0, 0, 0};
+      TAP_HIP(hipMemcpyAsync(fl, w.flags, sizeof(fl), hipMemcpyDeviceToHost, ss[j]));
+      TAP_HIP(hipStreamSynchronize(ss[j]));
+      if (fl[0]) { qc::set_error("a subsample index lies outside [0, %d)", N); rc = QC_ERR_RANGE; }
+      else if (fl[1]) { qc::set_error("a degree of the similarity matrix is not positive and finite"); rc = QC_ERR_RANGE; }
+      else if (fl[2]) { qc::set_error("the iteration block has no full rank (a zero start vector, or fewer than kb independent directions)"); rc = QC_ERR_RANGE; }
+      else if (fl[3]) { qc::set_error("an initial-centre index lies outside [0, %d)", N); rc = QC_ERR_RANGE; }
+    }
+    if (rc != QC_OK) {
+      for (int j = 0; j < slots; ++j) (void)hipStreamSynchronize(ss[j]);
+      return rc;
+    }
+  }
+  // every stream has drained (the k-means loop ends with a wait on each): the merge runs on the caller's stream
+  TAP_RC(aggregate_impl(per_labels, m, N, k, labels_out, nullptr, work, st));
   TAP_HIP(hipStreamSynchronize(st));
   return QC_OK;
 }

@@ -223,18 +223,19 @@ def test_aggregate_is_bit_exact(qc, m, N, k, noise):
 
 
 # ------------------------------------------------------------------------------------- whole algorithm
-@pytest.mark.parametrize("N,F,k,n,kb", [(700, 96, 6, 80, 8), (1100, 64, 9, 140, 16)])
-def test_cluster_recovers_planted_groups_like_the_oracle(qc, N, F, k, n, kb):
+@pytest.mark.parametrize("N,F,k,n,kb,m,slots", [(700, 96, 6, 80, 8, 3, 1), (1100, 64, 9, 140, 16, 3, 3), (900, 48, 5, 70, 8, 5, 2)])
+def test_cluster_recovers_planted_groups_like_the_oracle(qc, N, F, k, n, kb, m, slots):
+    """slots = subsamples worked on at a time (workspace of that many times the base size): same labels."""
     import torch
-    m = 3
     X, t, truth = TI.make_planted(N, F, k, seed=N)
     subs = TI.make_subsamples(N, n, m, seed=N + 1)
     init = np.stack([[int(np.flatnonzero(truth == g)[i]) for g in range(k)] for i in range(m)]).astype(np.int32)
     q0 = TI.make_start_block(kb, n, seed=N + 2)
     final = torch.empty(N, dtype=torch.int32, device="cuda")
     per = torch.empty((m, N), dtype=torch.int32, device="cuda")
-    qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(subs), 0.5, k, 8, _cuda(q0), _cuda(init), 50, final, per,
-                      _work(qc, N, F, n, k, kb))
+    base = (qc.qc_tap_workspace_bytes(N, F, n, k, kb) + 255) // 256 * 256
+    work = torch.empty(slots * base, dtype=torch.uint8, device="cuda")
+    qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(subs), 0.5, k, 8, _cuda(q0), _cuda(init), 50, final, per, work)
     wf, wp = tap.tap(X, t, subs, 0.5, k, init, 50)
     # the oracle recovers the planted groups exactly (its own pin); the embedding's sign and rotation freedom does
     # not touch distances between rows, so the labels must be the same ones
@@ -322,3 +323,37 @@ def test_paper_sized_aggregation_is_bit_exact(qc):
     out = torch.empty(N, dtype=torch.int32, device="cuda")
     qc.qc_tap_aggregate(_cuda(labels), k, out, _work(qc, 256, 8, 128, k, 128))
     assert np.array_equal(out.cpu().numpy(), tap.aggregate(labels, k))
+
+
+def test_cluster_reports_deferred_errors(qc):
+    """Inside the whole algorithm the data-dependent checks are read after the k-means of the subsample concerned."""
+    import torch
+    N, F, k, n, kb, m = 400, 32, 4, 48, 8, 3
+    X, t, truth = TI.make_planted(N, F, k, seed=5)
+    subs = TI.make_subsamples(N, n, m, seed=6)
+    init = np.stack([[int(np.flatnonzero(truth == g)[i]) for g in range(k)] for i in range(m)]).astype(np.int32)
+    q0 = TI.make_start_block(kb, n, seed=7)
+    final = torch.empty(N, dtype=torch.int32, device="cuda")
+    per = torch.empty((m, N), dtype=torch.int32, device="cuda")
+    base = (qc.qc_tap_workspace_bytes(N, F, n, k, kb) + 255) // 256 * 256
+    for slots in (1, 3):
+        work = torch.empty(slots * base, dtype=torch.uint8, device="cuda")
+        bad = subs.copy(); bad[1, 5] = N + 3
+        with pytest.raises(qc.QCError) as e:
+            qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(bad), 0.5, k, 4, _cuda(q0), _cuda(init), 20, final, per, work)
+        assert e.value.code == -4 and "subsample index" in str(e.value)
+        badi = init.copy(); badi[2, 0] = -1
+        with pytest.raises(qc.QCError) as e:
+            qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(subs), 0.5, k, 4, _cuda(q0), _cuda(badi), 20, final, per, work)
+        assert e.value.code == -4 and "initial-centre" in str(e.value)
+        q0z = q0.copy(); q0z[2] = 0.0
+        with pytest.raises(qc.QCError) as e:
+            qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(subs), 0.5, k, 4, _cuda(q0z), _cuda(init), 20, final, per, work)
+        assert e.value.code == -4 and "full rank" in str(e.value)
+        Xneg = X.copy(); Xneg[: N // 2] *= -1.0                       # opposite halves, cosine weight 1: negative degrees
+        with pytest.raises(qc.QCError) as e:
+            qc.qc_tap_cluster(_cuda(Xneg), _cuda(t), _cuda(subs), 1.0, k, 4, _cuda(q0), _cuda(init), 20, final, per, work)
+        assert e.value.code == -4
+        # and the context-free library is usable afterwards
+        qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(subs), 0.5, k, 8, _cuda(q0), _cuda(init), 50, final, per, work)
+        assert np.array_equal(final.cpu().numpy(), truth)

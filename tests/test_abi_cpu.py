@@ -182,6 +182,11 @@ def test_clustering_argument_checks_without_a_device(qc):
     assert L.qc_tap_cluster(f, f, 64, 8, f, 3, 16, 0.5, 4, 8, 5, f, f, 10, f, None, f, big, None) == -1
     assert L.qc_tap_cluster(f, f, 64, 8, f, 9, 16, 0.5, 4, 8, 5, f, f, 10, f, f, f, big, None) == -7
     assert L.qc_tap_cluster(f, f, 64, 8, f, 3, 16, 0.5, 4, 8, 5, f, f, 10, f, f, f, C.c_size_t(1000), None) == -6
+    ms, cnt = C.c_float(), C.c_int()
+    assert L.qc_tap_profile_end(C.byref(ms), C.byref(cnt)) == -5           # no _begin
+    assert L.qc_tap_profile_end(None, C.byref(cnt)) == -1
+    assert L.qc_tap_profile_begin() == 0
+    assert L.qc_tap_profile_end(C.byref(ms), C.byref(cnt)) == 0 and cnt.value == 0 and ms.value == 0.0
 
 
 @pytest.mark.parametrize("steps", [50, 100, 250, 7, 1])

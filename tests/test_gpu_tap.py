@@ -357,3 +357,47 @@ def test_cluster_reports_deferred_errors(qc):
         # and the context-free library is usable afterwards
         qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(subs), 0.5, k, 8, _cuda(q0), _cuda(init), 50, final, per, work)
         assert np.array_equal(final.cpu().numpy(), truth)
+
+
+# ------------------------------------------------------------------------------------------------ edge cases
+def test_edge_shapes(qc):
+    """Smallest and degenerate shapes: iteration block = subsample = k, one cluster, one subsample, a pool smaller
+    than a tile."""
+    import torch
+    # embedding with kb == n == k (the block spans the whole column space: no iteration needed, iters = 0)
+    N, n, k = 40, 8, 8
+    L, _ = _planted_L(N, 12, 4, n, seed=21)
+    U, sig = torch.empty((N, k), device="cuda"), torch.empty(k, device="cuda")
+    qc.qc_tap_embed(_cuda(L), k, 0, _cuda(TI.make_start_block(8, n, seed=22)), U, sig, _work(qc, N, 12, n, k, 8))
+    Uo, so = tap.embed(L, k)
+    lead = so > 1e-3 * so[0]                                          # trailing values sit at fp32 rounding level
+    assert np.allclose(sig.cpu().numpy()[lead], so[lead], atol=2e-5)
+    Ud = U.cpu().numpy().astype(np.float64)[:, lead]
+    assert np.linalg.svd(Ud.T @ Uo[:, lead], compute_uv=False).min() >= 1 - 1e-4
+    # k-means with one cluster: everything lands in it after one pass, the centre is the mean
+    Uk = np.random.default_rng(23).standard_normal((33, 5)).astype(np.float32)
+    labels, centres = torch.empty(33, dtype=torch.int32, device="cuda"), torch.empty((1, 5), device="cuda")
+    passes = qc.qc_tap_kmeans(_cuda(Uk), _cuda(np.array([7], np.int32)), 10, labels, centres, _work(qc, 256, 8, 128, 1, 128))
+    assert passes == 2 and labels.cpu().tolist() == [0] * 33
+    assert np.allclose(centres.cpu().numpy()[0], Uk.astype(np.float64).mean(0), rtol=1e-6, atol=1e-7)
+    # the whole algorithm with a single subsample: the merge is the identity
+    N, F, k, n, kb = 150, 20, 3, 24, 8
+    X, t, truth = TI.make_planted(N, F, k, seed=24)
+    subs = TI.make_subsamples(N, n, 1, seed=25)
+    init = np.array([[int(np.flatnonzero(truth == g)[0]) for g in range(k)]], dtype=np.int32)
+    final, per = torch.empty(N, dtype=torch.int32, device="cuda"), torch.empty((1, N), dtype=torch.int32, device="cuda")
+    qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(subs), 0.5, k, 6, _cuda(TI.make_start_block(kb, n, seed=26)), _cuda(init), 30,
+                      final, per, _work(qc, N, F, n, k, kb))
+    assert torch.equal(final, per[0]) and np.array_equal(final.cpu().numpy(), truth)
+    wf, _ = tap.tap(X, t, subs, 0.5, k, init, 30)
+    assert np.array_equal(final.cpu().numpy(), wf)
+    # similarity with the whole pool as subsample (n == N), N below one tile
+    N, F = 24, 10
+    X, t, _, _ = TI.make_pool(N, F, 50, 4, seed=27)
+    idx = np.arange(N, dtype=np.int32)
+    A = torch.empty((N, N), device="cuda")
+    dr, dc = torch.empty(N, device="cuda"), torch.empty(N, device="cuda")
+    qc.qc_tap_similarity(_cuda(X), _cuda(t), _cuda(idx), 0.7, A, dr, dc, _work(qc, N, F, N, 8, 8))
+    want = tap.similarity(X, t, idx, 0.7)
+    assert np.abs(A.cpu().numpy() - want).max() <= 2e-6
+    assert np.allclose(dr.cpu().numpy(), want.sum(1), rtol=2e-6) and np.allclose(dc.cpu().numpy(), want.sum(0), rtol=2e-6)

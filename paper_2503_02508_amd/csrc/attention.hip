@@ -207,7 +207,11 @@ __device__ __forceinline__ void unpack_pairs(v4u p, v2u &hi, v2u &lo) {
   lo.y = __builtin_amdgcn_perm(p.w, p.z, 0x07060302u);
 }
 
-template <int NCH, int NEB>   // feature chunks of 32 (operand width), feature blocks of 16 that hold real features
+// NCH feature chunks of 32 (operand width), NEB feature blocks of 16 that hold real features, QB query blocks of 16 per
+// wavefront (a workgroup covers 64 * QB queries).  QB = 2 reads every K / V^T fragment once for two MFMAs; QB = 1 makes
+// twice as many workgroups with half the MFMA chain each, for launches that would leave compute units idle.  The
+// arithmetic per query is the same in both.
+template <int NCH, int NEB, int QB>
 __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *__restrict__ Qp, const unsigned *__restrict__ Kp,
                                                             const _Float16 *__restrict__ Vh, const _Float16 *__restrict__ Vl, int T,
                                                             int Tp, int H, int hd, int DPv, const QParam *qp,
@@ -233,12 +237,17 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   // feature padding of the K tile is never written below: clear it once
   for (int i = tid; i < 2 * 64 * KROW / 8; i += 256) ((v8h *)&Ksh[0][0])[i] = (v8h){0, 0, 0, 0, 0, 0, 0, 0};
 
-  v4f o[2][NEB];
+  v4f o[QB][NEB];
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int j = 0; j < QB; ++j)
 #pragma unroll
     for (int e = 0; e < NEB; ++e) o[j][e] = (v4f){0.f, 0.f, 0.f, 0.f};
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.0f, 0.0f};
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int j = 0; j < QB; ++j) {
+    m_run[j] = -INFINITY;
+    l_run[j] = 0.0f;
+  }
 
   v4u kreg[KCH];
   v4u vreg[2][VCH];
@@ -290,15 +299,15 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   };
 
   load_tile(0);                            // first key tile and the queries are in flight together
-  int q_row[2];
-  v8h qh[2][NCH], qlo[2][NCH];
+  int q_row[QB];
+  v8h qh[QB][NCH], qlo[QB][NCH];
   {
     // all query loads are issued before any is used; rows beyond T read row T-1 (their results are never
     // stored), features beyond d read the last chunk and are zeroed below
-    v4u qraw[2][NCH][2];
+    v4u qraw[QB][NCH][2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      q_row[j] = blockIdx.y * 128 + wave * 32 + j * 16 + ql;
+    for (int j = 0; j < QB; ++j) {
+      q_row[j] = blockIdx.y * (64 * QB) + wave * (16 * QB) + j * 16 + ql;
       const unsigned *src = Qp + tok_base + (long long)min(q_row[j], T - 1) * hd;
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
@@ -308,7 +317,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
       }
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < QB; ++j)
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
         const int f = 32 * c + 8 * g;
@@ -330,7 +339,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
 
     // S^T = K Q^T: the K fragments run two iterations ahead of the MFMAs that use them (LDS latency is
     // several MFMA groups long and a wavefront is alone on its SIMD)
-    v4f s[2][4];
+    v4f s[QB][4];
     constexpr int NS = 4 * NCH;
     v8h kfh[3], kfl[3];
     auto load_k = [&](int it, int slot) {
@@ -340,25 +349,29 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
     };
     load_k(0, 0);
     load_k(1, 1);
-    v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = acc0;
+    v4f acc[QB];
+#pragma unroll
+    for (int j = 0; j < QB; ++j) acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int it = 0; it < NS; ++it) {
       const int kt = it / NCH, c = it % NCH, slot = it % 3;
       if (it + 2 < NS) load_k(it + 2, (it + 2) % 3);
       __builtin_amdgcn_sched_barrier(0);
       const v8h kh = kfh[slot], kl = kfl[slot];
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[0][c], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[1][c], acc1, 0, 0, 0);
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[0][c], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[1][c], acc1, 0, 0, 0);
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[0][c], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[1][c], acc1, 0, 0, 0);
+      // the query blocks alternate so that consecutive MFMAs do not wait on each other's result
+#pragma unroll
+      for (int j = 0; j < QB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, qh[j][c], acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < QB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qlo[j][c], acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < QB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, qh[j][c], acc[j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       if (c == NCH - 1) {
-        s[0][kt] = acc0;
-        s[1][kt] = acc1;
-        acc0 = (v4f){0.f, 0.f, 0.f, 0.f};
-        acc1 = acc0;
+#pragma unroll
+        for (int j = 0; j < QB; ++j) {
+          s[j][kt] = acc[j];
+          acc[j] = (v4f){0.f, 0.f, 0.f, 0.f};
+        }
       }
     }
     // the first V^T fragments are requested before the softmax arithmetic, which hides their latency
@@ -371,10 +384,10 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
     };
     load_v(0, 0);
     load_v(1, 1);
-    v8h ph[2][2], pl[2][2];
+    v8h ph[QB][2], pl[QB][2];
     const bool ragged_tile = k0 + 64 > T;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < QB; ++j) {
       float mx = -INFINITY;
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
@@ -408,13 +421,12 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
       if (it + 2 < NP) load_v(it + 2, (it + 2) % 3);
       __builtin_amdgcn_sched_barrier(0);
       const v8h vh = vfh[slot], vl = vfl[slot];
-      // the two query blocks alternate so that consecutive MFMAs never wait on each other's result
-      o[0][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, ph[0][a], o[0][e], 0, 0, 0);
-      o[1][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, ph[1][a], o[1][e], 0, 0, 0);
-      o[0][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[0][a], o[0][e], 0, 0, 0);
-      o[1][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[1][a], o[1][e], 0, 0, 0);
-      o[0][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[0][a], o[0][e], 0, 0, 0);
-      o[1][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[1][a], o[1][e], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < QB; ++j) o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, ph[j][a], o[j][e], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < QB; ++j) o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[j][a], o[j][e], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < QB; ++j) o[j][e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph[j][a], o[j][e], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -422,7 +434,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   const QParam t = *qp;
   const float qs = t.s, qz = (float)t.z;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
+  for (int j = 0; j < QB; ++j) {
     float l = l_run[j];
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
@@ -445,12 +457,25 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
 
 hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
                                 int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st) {
-  dim3 grid(B * H, (T + 127) / 128);
   const int neb = (hd + 15) / 16, nch = (hd + 31) / 32;
   if (hd > 80 || hd % 4) return hipErrorInvalidValue;      // K prefetch registers are sized for d <= 80
-#define QC_ATT(NCH, NEB)                                                                                               \
-  hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, H, hd, \
-                     DPv, qp, q_out)
+  // one query block per wavefront when two would leave compute units without a workgroup (QC_ATT_QB forces 1 or 2)
+  static int forced = -1;
+  if (forced < 0) {
+    const char *e = getenv("QC_ATT_QB");
+    forced = e ? atoi(e) : 0;
+  }
+  const int qb = forced == 1 || forced == 2 ? forced : (B * H * ((T + 127) / 128) < 256 ? 1 : 2);
+  dim3 grid(B * H, (T + 64 * qb - 1) / (64 * qb));
+#define QC_ATT(NCH, NEB)                                                                                                    \
+  do {                                                                                                                      \
+    if (qb == 1)                                                                                                            \
+      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 1>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, \
+                         H, hd, DPv, qp, q_out);                                                                            \
+    else                                                                                                                    \
+      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 2>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, \
+                         H, hd, DPv, qp, q_out);                                                                            \
+  } while (0)
   if (nch == 1 && neb == 1) QC_ATT(1, 1);
   else if (nch == 1) QC_ATT(1, 2);
   else if (nch == 2 && neb == 3) QC_ATT(2, 3);

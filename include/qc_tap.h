@@ -67,8 +67,8 @@ int qc_tap_normalise(float *A, const float *d_r, const float *d_c, int N, int n,
 /* The k leading left singular vectors of L[N, n] ("top k eigenvectors") and the
  * singular values: block power iteration on L^T L with kb >= k vectors started
  * from q0 (dev [kb, n] fp32, caller-drawn random numbers), `iters` rounds of
- * multiply + orthonormalisation (shifted Cholesky QR in fp64, three passes), then
- * a Rayleigh-Ritz step on the kb-dimensional subspace (Jacobi rotations) that
+ * multiply + shifted Cholesky QR in fp64 (one pass between two multiplications,
+ * three passes for the final basis), then a Rayleigh-Ritz step on the kb-dimensional subspace (Jacobi rotations) that
  * keeps the k largest.  U dev [N, k] out: orthonormal columns, column j
  * belonging to sigma[j] (dev [k] out, descending); each column's sign is
  * arbitrary.  The error of the subspace falls as (sigma_kb+1 / sigma_k)^(2 iters).
@@ -86,8 +86,9 @@ int qc_tap_embed(const float *L, int N, int n, int k, int kb, int iters, const f
  * cluster keeps its centre); stops when a pass changes no label or after
  * max_iter assignment passes.  labels dev [N] int32 out, centres dev [k, d]
  * fp32 out, *passes_out host (may be NULL) = assignment passes run.  d <= 128.
- * Waits for the stream after every pass; QC_ERR_RANGE for an index outside
- * [0, N). */
+ * The passes decide on the device whether they still have work; the host waits
+ * for the stream after every eighth pass (and at the end).  QC_ERR_RANGE for an
+ * index outside [0, N). */
 int qc_tap_kmeans(const float *U, int N, int d, int k, const int *init_idx, int max_iter, int *labels,
                   float *centres, int *passes_out, void *work, size_t work_bytes, void *stream);
 

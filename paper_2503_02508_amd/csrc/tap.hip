@@ -72,6 +72,9 @@ struct SgemmArgs {
   // its partial product to C + s * part_stride; a second kernel adds the partial products in order
   int kchunk;
   long long part_stride;
+  // symmetric product (SE_PLAIN, B = A with the same strides, M = N): only the tiles on and below the diagonal are
+  // computed; the kernel that adds the partial products also writes the mirror image
+  int sym;
 };
 
 // One operand's share of a slab for this thread: four units of four consecutive elements.
@@ -155,6 +158,15 @@ __device__ __forceinline__ void store_units(float *T, int tid, unsigned mask, co
   }
 }
 
+// entry t of the lower triangle walked row by row -> (row, column), column <= row
+__device__ __forceinline__ void tri_decode(int t, int &row, int &col) {
+  int r = (int)((sqrtf(8.f * (float)t + 1.f) - 1.f) * 0.5f);
+  while (r * (r + 1) / 2 > t) --r;
+  while ((r + 1) * (r + 2) / 2 <= t) ++r;
+  row = r;
+  col = t - r * (r + 1) / 2;
+}
+
 // VEC: both operands take 16-byte loads (a compile-time choice: a run-time branch around the loads would make the
 // compiler wait for them at the join and expose their latency)
 template <bool AKC, bool BKC, int EPI, bool VEC>
@@ -164,13 +176,20 @@ __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs p) {
   __shared__ __align__(16) float Bs[2][TK * LDB];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tiles_m = (p.M + TM - 1) / TM, tiles_n = (p.N + TN - 1) / TN;
-  const int total = tiles_m * tiles_n;
+  const int total = p.sym ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
   // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of tiles (n fastest) so that the
   // tiles sharing an A panel meet in one L2
   const int per_xcd = (total + NUM_XCD - 1) / NUM_XCD;
   const int tile = (blockIdx.x % NUM_XCD) * per_xcd + blockIdx.x / NUM_XCD;
   if (blockIdx.x / NUM_XCD >= per_xcd || tile >= total) return;
-  const int m0 = (tile / tiles_n) * TM, n0 = (tile % tiles_n) * TN;
+  int tm, tn;
+  if (p.sym) {
+    tri_decode(tile, tm, tn);
+  } else {
+    tm = tile / tiles_n;
+    tn = tile % tiles_n;
+  }
+  const int m0 = tm * TM, n0 = tn * TN;
   const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
 
   floatx16 acc[2][2];
@@ -262,6 +281,33 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *part, i
   out[i] = s;
 }
 
+// the same for a symmetric n x n product of which only the tiles on and below the diagonal were computed: one
+// workgroup per 32 x 32 block on or below the diagonal adds the partial products, writes the block and, through LDS,
+// its transpose (`out` may be `part` when there is a single partial product)
+__global__ __launch_bounds__(256) void splitk_reduce_sym_kernel(const float *part, int splits, long long stride, int n,
+                                                                long long ldc, float *out) {
+  __shared__ float tile[32][33];
+  int bm, bn;
+  tri_decode(blockIdx.x, bm, bn);
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int r = bm * 32 + ty + 8 * rr, c = bn * 32 + tx;
+    const bool ok = r < n && c < n;
+    float s = 0.f;
+    for (int q = 0; q < splits; ++q) s += part[ok ? q * stride + (long long)r * ldc + c : 0];
+    if (ok) out[(long long)r * ldc + c] = s;
+    tile[ty + 8 * rr][tx] = s;
+  }
+  __syncthreads();
+  if (bm == bn) return;
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int r = bn * 32 + ty + 8 * rr, c = bm * 32 + tx;
+    if (r < n && c < n) out[(long long)r * ldc + c] = tile[tx][ty + 8 * rr];
+  }
+}
+
 // `part` (part_elems floats) allows a plain product with few tiles and a long K to be split along K
 hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st, float *part = nullptr, size_t part_elems = 0) {
   if (a.M <= 0 || a.N <= 0) return hipSuccess;
@@ -272,7 +318,9 @@ hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st, float *part = nullptr, si
   // 16-byte loads: base aligned, the strided dimension's stride and the contiguous extent multiples of 4
   a.a_vec = aligned16(a.A) && (a.a_kc ? (a.sam % 4 == 0 && a.K % 4 == 0) : (a.sak % 4 == 0 && a.M % 4 == 0));
   a.b_vec = aligned16(a.B) && (a.b_kc ? (a.sbn % 4 == 0 && a.K % 4 == 0) : (a.sbk % 4 == 0 && a.N % 4 == 0));
-  const int tiles = ((a.M + TM - 1) / TM) * ((a.N + TN - 1) / TN);
+  if (a.sym && (epi != SE_PLAIN || a.M != a.N || a.A != a.B || a.sam != a.sbn || a.sak != a.sbk)) return hipErrorInvalidValue;
+  const int tiles_m = (a.M + TM - 1) / TM;
+  const int tiles = a.sym ? tiles_m * (tiles_m + 1) / 2 : tiles_m * ((a.N + TN - 1) / TN);
   const int grid = ((tiles + NUM_XCD - 1) / NUM_XCD) * NUM_XCD;
   int splits = 1;
   a.kchunk = a.K > 0 ? a.K : 1;
@@ -280,7 +328,7 @@ hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st, float *part = nullptr, si
   float *out = a.C;
   const long long out_elems = (long long)a.M * a.ldc;
   if (epi == SE_PLAIN && part && tiles < 256 && a.K >= 8 * TK) {
-    long long want = (512 + tiles - 1) / tiles;
+    long long want = 512 / tiles;            // at most the 512 workgroups the chip holds at a time
     if (want > 16) want = 16;
     if (want > a.K / (4 * TK)) want = a.K / (4 * TK);
     if (want > (long long)(part_elems / (size_t)out_elems)) want = (long long)(part_elems / (size_t)out_elems);
@@ -310,9 +358,14 @@ hipError_t sgemm(SgemmArgs a, int epi, hipStream_t st, float *part = nullptr, si
     else return hipErrorInvalidValue;
   }
 #undef SG_LAUNCH
-  if (splits > 1)
+  if (a.sym) {
+    const int nb = (a.M + 31) / 32;
+    hipLaunchKernelGGL(splitk_reduce_sym_kernel, dim3(nb * (nb + 1) / 2), dim3(256), 0, st,
+                       splits > 1 ? (const float *)part : (const float *)out, splits, out_elems, a.M, a.ldc, out);
+  } else if (splits > 1) {
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((out_elems + 255) / 256)), dim3(256), 0, st, part, splits,
                        out_elems, out_elems, out);
+  }
   return hipGetLastError();
 }
 
@@ -461,20 +514,31 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double *part, in
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= kk) return;
   double s = 0.0;
-  for (int b = 0; b < nparts; ++b) s += part[(long long)b * kk + i];
+  int b = 0;
+  for (; b + 8 <= nparts; b += 8) {        // eight loads in flight, added in order
+    double t[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t[q] = part[(long long)(b + q) * kk + i];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) s += t[q];
+  }
+  for (; b < nparts; ++b) s += part[(long long)b * kk + i];
   W[i] = s;
 }
 
 // Inverse Cholesky factor of W + shift I (= Lc Lc^T, Lc lower), one workgroup.  The shift, shift_rel times the largest
 // diagonal entry, keeps the factorisation alive when the rows are numerically dependent (shifted Cholesky QR: the
 // rows come out better conditioned, not yet orthonormal, and the next pass finishes).
-// The sweep is the square-root-free form on one kb x kb array S: the lower triangle and diagonal hold the trailing
-// matrix w, the strict upper triangle the inverse being built, r_iq (i > q) at S[q][i], r's unit diagonal implicit.
-// At column j, with pivot p_j = S[j][j], every element beyond column j takes
-//   S[R][C] -= g(R) g(C) / p_j,   g(x) = S[x][j] for x != j, g(j) = 1,   for C > j and (R >= C or R <= j)
-// (R >= C: trailing matrix w_RC -= w_Rj w_Cj / p_j;  R <= j: inverse r_CR -= w_Cj r_jR / p_j), which reads only column
-// j.  Thread (ty, tx) of the 8 x 128 workgroup keeps S[ty + 8 q][tx], q = 0..15, in registers; the owners of column
-// j publish it through LDS (two buffers in turn, so one barrier per column suffices).  Then Lc^-1 = diag(p)^-1/2 r.
+// The sweep is the square-root-free form on one kb x kb array S.  After column j, rows R > j of the columns C > j
+// hold the trailing matrix w (kept whole: the copies above the diagonal are updated too and never read, which saves
+// every per-lane condition), rows R <= j of the columns C > j hold the inverse being built, r_CR at S[R][C], r's unit
+// diagonal implicit.  At column j, with pivot p_j = S[j][j], every element of the columns C > j takes
+//   S[R][C] -= g(R) g(C) / p_j,   g(x) = S[x][j] for x != j, g(j) = 1,
+// where row j starts from zero (r_Cj = -w_Cj / p_j), which reads only column j.  Wavefront w of the 16 keeps the
+// columns w, w + 16, ..., lane l the rows l and l + 64 of each: finished columns are skipped by a test that is
+// uniform over the wavefront, and the work stays balanced until the last columns.  The owner of column j publishes it
+// through LDS (two buffers in turn, so one barrier per column suffices), with 1 in place of the pivot.
+// Then Lc^-1 = diag(p)^-1/2 r.
 // Out: Rinv[kb, kb] fp32 = Lc^-1 (lower triangular), so that Rinv Y has orthonormal rows when the shift is
 // negligible.  With `check` set (the last pass, whose input should already be near orthonormal) the kernel returns the
 // identity at once when W is the identity to 1e-5, and a pivot below 1/4 raises the flag: the block has no full
@@ -482,32 +546,39 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double *part, in
 __global__ __launch_bounds__(1024) void chol_inv_kernel(const double *W, int kb, double shift_rel, int check,
                                                          float *Rinv, int *flag) {
   __shared__ double colbuf[2][KB_MAX];
+  __shared__ double pivbuf[2];
   __shared__ double pivs[KB_MAX];
+  __shared__ double red[16];
   __shared__ double dmax;
-  const int tid = threadIdx.x, tx = tid & 127, ty = tid >> 7;
-  constexpr int NQ = KB_MAX / 8;
-  double S[NQ];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  constexpr int NC = KB_MAX / 16;
+  double S[NC][2];
 #pragma unroll
-  for (int q = 0; q < NQ; ++q) {
-    const int R = ty + 8 * q;
-    const bool in = tx < kb && R < kb && R >= tx;
-    const double v = W[in ? R * kb + tx : 0];
-    S[q] = in ? v : 0.0;
-    if (R == tx && R < kb) pivs[R] = S[q];
-  }
+  for (int i = 0; i < NC; ++i)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int R = lane + 64 * h, C = w + 16 * i;
+      const bool in = R < kb && C < kb;
+      const int lo = R < C ? R : C, hi = R < C ? C : R;
+      const double v = W[in ? hi * kb + lo : 0];        // the Gram matrix is read from its lower triangle
+      S[i][h] = in ? v : 0.0;
+      if (in && R == C) pivs[R] = v;
+    }
   // last pass only: rows that are already orthonormal to fp32 level (|W - I| <= 1e-5 everywhere) are left as they are
   if (check) {
     double dev = 0.0;
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int R = ty + 8 * q;
-      const bool in = tx < kb && R < kb && R >= tx;
-      const double d = fabs(S[q] - (R == tx ? 1.0 : 0.0));
-      dev = in ? fmax(dev, d) : dev;
-    }
+    for (int i = 0; i < NC; ++i)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int R = lane + 64 * h, C = w + 16 * i;
+        const double d = fabs(S[i][h] - (R == C ? 1.0 : 0.0));
+        dev = (R < kb && C < kb) ? fmax(dev, d) : dev;
+      }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) dev = fmax(dev, __shfl_xor(dev, o, 64));
-    if ((tid & 63) == 0) colbuf[0][tid >> 6] = dev;
+    if (lane == 0) red[w] = dev;
   }
   __syncthreads();
   if (tid == 0) {
@@ -517,32 +588,43 @@ __global__ __launch_bounds__(1024) void chol_inv_kernel(const double *W, int kb,
   }
   if (check) {
     double dev = 0.0;
-    for (int w = 0; w < 16; ++w) dev = fmax(dev, colbuf[0][w]);
+    for (int q = 0; q < 16; ++q) dev = fmax(dev, red[q]);
     if (dev <= 1e-5) {                    // the same value in every thread: the whole workgroup leaves together
-      if (tx < kb) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-          const int R = ty + 8 * q;
-          if (R < kb) Rinv[tx * kb + R] = R == tx ? 1.f : 0.f;
+      for (int i = 0; i < NC; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int R = lane + 64 * h, C = w + 16 * i;
+          if (R < kb && C < kb) Rinv[C * kb + R] = R == C ? 1.f : 0.f;
         }
-      }
       return;
     }
   }
   __syncthreads();
   const double shift = shift_rel * dmax;
 #pragma unroll
-  for (int q = 0; q < NQ; ++q)
-    if (ty + 8 * q == tx) S[q] += shift;
+  for (int i = 0; i < NC; ++i)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      if (lane + 64 * h == w + 16 * i) S[i][h] += shift;
   for (int j = 0; j < kb; ++j) {
     double *buf = colbuf[j & 1];
-    if (tx == j) {
+    const bool z0 = lane == j, z1 = lane + 64 == j;       // this lane's copy of row j
+    if (w == (j & 15)) {
+      double v0 = 0.0, v1 = 0.0;
 #pragma unroll
-      for (int q = 0; q < NQ; ++q)
-        if (ty + 8 * q < kb) buf[ty + 8 * q] = S[q];
+      for (int i = 0; i < NC; ++i)
+        if (i == (j >> 4)) {
+          v0 = S[i][0];
+          v1 = S[i][1];
+        }
+      if (z0) pivbuf[j & 1] = v0;
+      if (z1) pivbuf[j & 1] = v1;
+      buf[lane] = z0 ? 1.0 : v0;
+      buf[lane + 64] = z1 ? 1.0 : v1;
     }
     __syncthreads();
-    double piv = buf[j];
+    double piv = pivbuf[j & 1];
     if (!(piv > 0.0) || !isfinite(piv)) {
       if (tid == 0) atomicOr(flag, 2);
       piv = 1.0;
@@ -550,45 +632,38 @@ __global__ __launch_bounds__(1024) void chol_inv_kernel(const double *W, int kb,
       if (tid == 0) atomicOr(flag, 2);
     }
     if (tid == 0) pivs[j] = piv;
-    // wavefronts whose columns are all done skip the update; inside, every load is unconditional (clamped) and the
-    // per-element conditions are selects, so the LDS reads of a column are in flight together
-    if ((((tid | 63) & 127) > j)) {
+    if (w + 16 * (NC - 1) > j) {          // this wavefront still has a column beyond j
       // 1 / p: hardware estimate refined by two Newton steps
       double inv_p = __builtin_amdgcn_rcp(piv);
       inv_p = inv_p * (2.0 - piv * inv_p);
       inv_p = inv_p * (2.0 - piv * inv_p);
-      const bool col_on = tx > j && tx < kb;
-      const double gc = buf[tx < kb ? tx : 0] * inv_p;
-      double g[NQ];
+      const double g0 = buf[lane], g1 = buf[lane + 64];
 #pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const int R = ty + 8 * q;
-        g[q] = buf[R < kb ? R : 0];
-      }
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const int R = ty + 8 * q;
-        const bool on = col_on && R < kb && (R >= tx || R <= j);
-        const double gq = R == j ? 1.0 : g[q];
-        const double upd = fma(-gq, gc, S[q]);
-        S[q] = on ? upd : S[q];
+      for (int i = 0; i < NC; ++i) {
+        const int C = w + 16 * i;
+        if (C > j && C < kb) {
+          const double gc = buf[C] * inv_p;
+          const double s0 = z0 ? 0.0 : S[i][0], s1 = z1 ? 0.0 : S[i][1];
+          S[i][0] = fma(-g0, gc, s0);
+          S[i][1] = fma(-g1, gc, s1);
+        }
       }
     }
     // the buffer that column j + 1 is published to was last read at column j - 1, before this column's barrier
   }
   __syncthreads();
-  if (tx < kb) {
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int R = ty + 8 * q;
-      if (R >= kb) continue;
-      // S[R][tx] with R < tx is r_{tx, R}: row tx of the inverse; everything above the diagonal of Rinv is zero
+  for (int i = 0; i < NC; ++i)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int R = lane + 64 * h, C = w + 16 * i;
+      if (R >= kb || C >= kb) continue;
+      // S[R][C] with R < C is r_{C, R}: row C of the inverse; everything above the diagonal of Rinv is zero
       float v = 0.f;
-      if (R == tx) v = (float)(1.0 / sqrt(pivs[R]));
-      else if (R < tx) v = (float)(S[q] / sqrt(pivs[tx]));
-      Rinv[tx * kb + R] = v;
+      if (R == C) v = (float)(1.0 / sqrt(pivs[R]));
+      else if (R < C) v = (float)(S[i][h] / sqrt(pivs[C]));
+      Rinv[C * kb + R] = v;
     }
-  }
 }
 
 // ------------------------------------------------------------------------------- Rayleigh-Ritz (Jacobi)
@@ -732,39 +807,66 @@ __global__ __launch_bounds__(256) void kmeans_init_kernel(const float *U, int N,
   for (int j = threadIdx.x; j < d; j += 256) centres[c * d + j] = U[(long long)r * d + j];
 }
 
-// assignment pass: 64 rows per workgroup staged in LDS beside the centres; thread (row, g) scans the centres
-// c = g, g + 4, ...; the four candidates of a row are merged with ties to the lowest centre
+// Control words of one k-means run (device, ints): ctl[0], ctl[1] = labels changed by the passes of even / odd index,
+// ctl[2] = 1 once a pass has changed nothing, ctl[3] = assignment passes run.  Every kernel of a pass leaves at once
+// when ctl[2] is up, so the host may enqueue passes ahead of knowing whether they are needed.
+constexpr int KM_DONE = 2, KM_PASSES = 3;
+
+// assignment pass `it`: 64 rows per workgroup staged in LDS beside the centres (rows padded with zeros to whole
+// float4s, which leaves every sum as it is); thread (row, g) scans the centres c = g, g + 4, ... four at a time (one
+// 16-byte broadcast read per centre and four dimensions), each sum running over the dimensions in ascending order; the
+// four candidates of a row are merged with ties to the lowest centre
 __global__ __launch_bounds__(256) void kmeans_assign_kernel(const float *U, int N, int d, const float *centres, int k,
-                                                            int *labels, int *changed) {
+                                                            int *labels, int *ctl, int it) {
+  if (ctl[KM_DONE]) return;
   extern __shared__ float sm[];
-  float *cs = sm;                       // [k][d]
-  float *us = sm + k * d;               // [64][d + 1]
+  const int dp = (d + 3) & ~3;
+  float *cs = sm;                       // [k][dp]
+  float *us = sm + k * dp;              // [64][dp + 1]
   __shared__ float bd[4][64];
   __shared__ int bi[4][64];
   const int tid = threadIdx.x, row = tid & 63, g = tid >> 6;
   const int r0 = blockIdx.x * 64;
-  for (int u = tid; u < k * d; u += 256) cs[u] = centres[u];
-  for (int u = tid; u < 64 * d; u += 256) {
-    const int rr = u / d, j = u % d;
-    const bool ok = r0 + rr < N;
+  if (blockIdx.x == 0 && tid == 0) atomicAdd(&ctl[KM_PASSES], 1);
+  for (int u = tid; u < k * dp; u += 256) {
+    const int c = u / dp, j = u - c * dp;
+    const float v = centres[j < d ? c * d + j : 0];
+    cs[u] = j < d ? v : 0.f;
+  }
+  for (int u = tid; u < 64 * dp; u += 256) {
+    const int rr = u / dp, j = u - rr * dp;
+    const bool ok = r0 + rr < N && j < d;
     const float v = U[ok ? (long long)(r0 + rr) * d + j : 0];
-    us[rr * (d + 1) + j] = ok ? v : 0.f;
+    us[rr * (dp + 1) + j] = ok ? v : 0.f;
   }
   __syncthreads();
   float best = INFINITY;
   int besti = 0x7fffffff;
-  const float *u = us + row * (d + 1);
-  for (int c = g; c < k; c += 4) {
-    const float *cc = cs + c * d;
-    float s = 0.f;
-    for (int j = 0; j < d; ++j) {
-      const float df = u[j] - cc[j];
-      s = fmaf(df, df, s);
+  const float *u = us + row * (dp + 1);
+  for (int c0 = g; c0 < k; c0 += 16) {
+    const float *p0 = cs + c0 * dp;
+    const float *p1 = cs + (c0 + 4 < k ? c0 + 4 : c0) * dp;
+    const float *p2 = cs + (c0 + 8 < k ? c0 + 8 : c0) * dp;
+    const float *p3 = cs + (c0 + 12 < k ? c0 + 12 : c0) * dp;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    for (int j = 0; j < dp; j += 4) {
+      const float4 a0 = *(const float4 *)(p0 + j), a1 = *(const float4 *)(p1 + j);
+      const float4 a2 = *(const float4 *)(p2 + j), a3 = *(const float4 *)(p3 + j);
+      const float u0 = u[j], u1 = u[j + 1], u2 = u[j + 2], u3 = u[j + 3];
+      float t;
+      t = u0 - a0.x; s0 = fmaf(t, t, s0); t = u1 - a0.y; s0 = fmaf(t, t, s0);
+      t = u2 - a0.z; s0 = fmaf(t, t, s0); t = u3 - a0.w; s0 = fmaf(t, t, s0);
+      t = u0 - a1.x; s1 = fmaf(t, t, s1); t = u1 - a1.y; s1 = fmaf(t, t, s1);
+      t = u2 - a1.z; s1 = fmaf(t, t, s1); t = u3 - a1.w; s1 = fmaf(t, t, s1);
+      t = u0 - a2.x; s2 = fmaf(t, t, s2); t = u1 - a2.y; s2 = fmaf(t, t, s2);
+      t = u2 - a2.z; s2 = fmaf(t, t, s2); t = u3 - a2.w; s2 = fmaf(t, t, s2);
+      t = u0 - a3.x; s3 = fmaf(t, t, s3); t = u1 - a3.y; s3 = fmaf(t, t, s3);
+      t = u2 - a3.z; s3 = fmaf(t, t, s3); t = u3 - a3.w; s3 = fmaf(t, t, s3);
     }
-    if (s < best) {
-      best = s;
-      besti = c;
-    }
+    if (s0 < best) { best = s0; besti = c0; }
+    if (c0 + 4 < k && s1 < best) { best = s1; besti = c0 + 4; }
+    if (c0 + 8 < k && s2 < best) { best = s2; besti = c0 + 8; }
+    if (c0 + 12 < k && s3 < best) { best = s3; besti = c0 + 12; }
   }
   bd[g][row] = best;
   bi[g][row] = besti;
@@ -780,16 +882,20 @@ __global__ __launch_bounds__(256) void kmeans_assign_kernel(const float *U, int 
     }
     if (labels[r0 + row] != besti) {
       labels[r0 + row] = besti;
-      atomicAdd(changed, 1);
+      atomicAdd(&ctl[it & 1], 1);
     }
   }
 }
 
 // update pass, stage 1: workgroup b walks its range of rows in ascending order, thread j owning dimension j, and adds
-// each row to its cluster's fp64 sums in LDS; stage 2 adds the workgroups' sums in order.  An empty cluster keeps its
-// centre.
+// each row to its cluster's fp64 sums in LDS (LDS adds without return value: the adds of one thread to one address
+// are carried out in program order, so the sums are those of the rows in ascending order; 16 rows are loaded ahead);
+// stage 2 adds the workgroups' sums in order.  An empty cluster keeps its centre.  Nothing happens when the pass
+// changed no label.
 __global__ __launch_bounds__(128) void kmeans_partial_kernel(const float *U, int N, int d, const int *labels, int k,
-                                                             int rows_per, double *psum, int *pcnt) {
+                                                             int rows_per, double *psum, int *pcnt, const int *ctl,
+                                                             int it) {
+  if (ctl[KM_DONE] || ctl[it & 1] == 0) return;
   extern __shared__ double accs[];      // [k][d]
   __shared__ int cnt[KB_MAX];
   const int j = threadIdx.x;
@@ -799,24 +905,39 @@ __global__ __launch_bounds__(128) void kmeans_partial_kernel(const float *U, int
   const int r0 = blockIdx.x * rows_per, r1 = min(N, r0 + rows_per);
   const int jj = j < d ? j : 0;
   int r = r0;
-  for (; r + 4 <= r1; r += 4) {
-    int c[4];
-    float v[4];
+  int c[16], cn[16];
+  float v[16], vn[16];
+  if (r + 16 <= r1) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      c[i] = clamp_label(labels[r + i], k);
+    for (int i = 0; i < 16; ++i) {
+      c[i] = labels[r + i];
       v[i] = U[(long long)(r + i) * d + jj];
     }
+  }
+  for (; r + 16 <= r1; r += 16) {
+    // the next 16 rows are requested before this batch is added (clamped to the range: the last request repeats rows)
+    const int rn = r + 32 <= r1 ? r + 16 : r;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (j < d) accs[c[i] * d + j] += (double)v[i];
-      if (j == 0) cnt[c[i]] += 1;
+    for (int i = 0; i < 16; ++i) {
+      cn[i] = labels[rn + i];
+      vn[i] = U[(long long)(rn + i) * d + jj];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int ci = clamp_label(c[i], k);
+      if (j < d) atomicAdd(&accs[ci * d + j], (double)v[i]);
+      if (j == 0) atomicAdd(&cnt[ci], 1);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      c[i] = cn[i];
+      v[i] = vn[i];
     }
   }
   for (; r < r1; ++r) {
     const int c = clamp_label(labels[r], k);
-    if (j < d) accs[c * d + j] += (double)U[(long long)r * d + j];
-    if (j == 0) cnt[c] += 1;
+    if (j < d) atomicAdd(&accs[c * d + j], (double)U[(long long)r * d + j]);
+    if (j == 0) atomicAdd(&cnt[c], 1);
   }
   __syncthreads();
   double *ps = psum + (long long)blockIdx.x * k * d;
@@ -824,14 +945,37 @@ __global__ __launch_bounds__(128) void kmeans_partial_kernel(const float *U, int
   for (int u = j; u < k; u += 128) pcnt[blockIdx.x * k + u] = cnt[u];
 }
 
-__global__ __launch_bounds__(256) void kmeans_finish_kernel(const double *psum, const int *pcnt, int nb, int k, int d,
-                                                            float *centres) {
-  const int u = blockIdx.x * 256 + threadIdx.x;
+// stage 2, and the bookkeeping of pass `it`: a pass that changed nothing raises ctl[2]; otherwise the other pass
+// parity's counter is cleared for the next pass (nothing reads it during this kernel)
+__global__ __launch_bounds__(64) void kmeans_finish_kernel(const double *psum, const int *pcnt, int nb, int k, int d,
+                                                           float *centres, int *ctl, int it) {
+  if (ctl[KM_DONE]) return;
+  if (ctl[it & 1] == 0) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) ctl[KM_DONE] = 1;
+    return;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) ctl[(it + 1) & 1] = 0;
+  const int u = blockIdx.x * 64 + threadIdx.x;
   if (u >= k * d) return;
   const int c = u / d;
   double tot = 0.0;
   int m = 0;
-  for (int b = 0; b < nb; ++b) {
+  int b = 0;
+  for (; b + 16 <= nb; b += 16) {
+    double t[16];
+    int q[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      t[i] = psum[(long long)(b + i) * k * d + u];
+      q[i] = pcnt[(b + i) * k + c];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      tot += t[i];
+      m += q[i];
+    }
+  }
+  for (; b < nb; ++b) {
     tot += psum[(long long)b * k * d + u];
     m += pcnt[b * k + c];
   }
@@ -845,44 +989,48 @@ __global__ __launch_bounds__(256) void contingency_kernel(const int *a, const in
 }
 
 // greedy renaming, one workgroup: k times take the largest remaining count (ties to the lowest flat index), fix
-// perm[column] = row, retire the row and the column
-__global__ __launch_bounds__(256) void greedy_match_kernel(const int *T, int k, int *perm) {
-  __shared__ int rdone[KB_MAX], cdone[KB_MAX];
-  __shared__ int bv[256], bx[256];
+// perm[column] = row, retire the row and the column.  The table lives in registers, 16 entries per thread, each as
+// the 64-bit key (count << 32) | (2^31 - 1 - flat index), so that the largest key is the entry wanted; retired and
+// absent entries are -1.  A round is a maximum over the thread's keys, over the wavefront (shuffles) and over the 16
+// wavefronts (LDS, two buffers in turn: one barrier per round).
+__global__ __launch_bounds__(1024) void greedy_match_kernel(const int *T, int k, int *perm) {
+  constexpr int PER = KB_MAX * KB_MAX / 1024;
+  __shared__ long long wbest[2][16];
   const int tid = threadIdx.x;
-  for (int i = tid; i < k; i += 256) rdone[i] = cdone[i] = 0;
-  __syncthreads();
+  long long key[PER];
+  int rc[PER];                              // (row << 8) | column of the entry
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int u = tid + 1024 * i;
+    const bool in = u < k * k;
+    const int v = T[in ? u : 0];
+    key[i] = in ? ((long long)v << 32) | (long long)(unsigned)(0x7fffffff - u) : -1ll;
+    rc[i] = in ? ((u / k) << 8) | (u % k) : 0xffff;
+  }
   for (int it = 0; it < k; ++it) {
-    int best = -1, besti = 0x7fffffff;
-    for (int u = tid; u < k * k; u += 256) {
-      const int p = u / k, q = u % k;
-      if (rdone[p] || cdone[q]) continue;
-      const int v = T[u];
-      if (v > best) {          // u ascends, so the first maximum of this thread is its lowest index
-        best = v;
-        besti = u;
-      }
+    long long m = key[0];
+#pragma unroll
+    for (int i = 1; i < PER; ++i) m = key[i] > m ? key[i] : m;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const long long x = __shfl_xor(m, o, 64);
+      m = x > m ? x : m;
     }
-    bv[tid] = best;
-    bx[tid] = besti;
+    if ((tid & 63) == 0) wbest[it & 1][tid >> 6] = m;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-      if (tid < o) {
-        const int v = bv[tid + o], x = bx[tid + o];
-        if (v > bv[tid] || (v == bv[tid] && x < bx[tid])) {
-          bv[tid] = v;
-          bx[tid] = x;
-        }
-      }
-      __syncthreads();
+    long long g = wbest[it & 1][0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) {
+      const long long x = wbest[it & 1][w];
+      g = x > g ? x : g;
     }
-    if (tid == 0) {
-      const int p = bx[0] / k, q = bx[0] % k;
-      perm[q] = p;
-      rdone[p] = 1;
-      cdone[q] = 1;
-    }
-    __syncthreads();
+    // rows and columns retire in pairs, so (k - it)^2 entries are still live here and g >= 0
+    const int u = 0x7fffffff - (int)(unsigned)(g & 0xffffffffll);
+    const int p = u / k, q = u - p * k;
+    if (tid == 0) perm[q] = p;
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+      if ((rc[i] >> 8) == p || (rc[i] & 0xff) == q) key[i] = -1ll;
   }
 }
 
@@ -922,11 +1070,9 @@ struct Carve {
   }
 };
 
-// element ranges of the partial Gram matrices: at most 128 of them, at least 128 elements each
-int gram_chunk(int len) {
-  const int c = (((len + 127) / 128) + 31) / 32 * 32;
-  return c < 128 ? 128 : c;
-}
+// element ranges of the partial Gram matrices: at most 128 of them, whole multiples of the 32 elements the kernel
+// stages at a time
+int gram_chunk(int len) { return (((len + 127) / 128) + 31) / 32 * 32; }
 int gram_parts(int len) { return (len + gram_chunk(len) - 1) / gram_chunk(len); }
 
 // row ranges of the k-means partial sums: at most 256 of them, at least 256 rows each
@@ -970,7 +1116,7 @@ struct EmbedWork {
     Wk = c.take<float>((size_t)k * kb);
     isig = c.take<float>(k);
     Rinv = c.take<float>((size_t)kb * kb);
-    spart_elems = (size_t)4 * n * n;
+    spart_elems = (size_t)5 * n * n;
     spart = c.take<float>(spart_elems);
     const int parts = gram_parts(n) > gram_parts(N) ? gram_parts(n) : gram_parts(N);
     part = c.take<double>((size_t)parts * kb * kb);
@@ -1146,6 +1292,13 @@ int orthonormalise(const float *in, EmbedWork &w, int kb, int n, int *fl, hipStr
   return QC_OK;
 }
 
+// Between two multiplications of the power iteration one pass is enough: the next product only needs rows that span
+// the same space and are well conditioned (a single shifted pass leaves them orthonormal to about the square of the
+// block's condition number times the fp64 rounding, far from dependent); `in` must not be w.Q
+int recondition(const float *in, EmbedWork &w, int kb, int n, int *fl, hipStream_t st) {
+  return cholqr_pass(in, w.Q, kb, n, 0, w, fl, st);
+}
+
 // `big_done` (may be null) is recorded after the one chip-filling product of this stage (L^T L)
 int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const float *q0, float *U, float *sigma,
                void *work, hipStream_t st, int *ext = nullptr, hipEvent_t big_done = nullptr) {
@@ -1160,9 +1313,11 @@ int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const flo
   g.B = L; g.sbn = 1; g.sbk = n;
   g.C = w.G; g.ldc = n;
   g.M = n; g.N = n; g.K = N;
+  g.sym = 1;
   TAP_HIP(sgemm(g, SE_PLAIN, st, w.spart, w.spart_elems));
   if (big_done) TAP_HIP(hipEventRecord(big_done, st));
-  TAP_RC(orthonormalise(q0, w, kb, n, fl, st));
+  if (iters > 0) TAP_RC(recondition(q0, w, kb, n, fl, st));
+  else TAP_RC(orthonormalise(q0, w, kb, n, fl, st));
   SgemmArgs mul{};
   mul.A = w.Q; mul.sam = n; mul.sak = 1;
   mul.B = w.G; mul.sbn = n; mul.sbk = 1;      // G is symmetric
@@ -1170,7 +1325,8 @@ int embed_impl(const float *L, int N, int n, int k, int kb, int iters, const flo
   mul.M = kb; mul.N = n; mul.K = n;
   for (int it = 0; it < iters; ++it) {
     TAP_HIP(sgemm(mul, SE_PLAIN, st, w.spart, w.spart_elems));
-    TAP_RC(orthonormalise(w.Y, w, kb, n, fl, st));
+    if (it + 1 < iters) TAP_RC(recondition(w.Y, w, kb, n, fl, st));
+    else TAP_RC(orthonormalise(w.Y, w, kb, n, fl, st));      // the final basis: orthonormal to fp32 level
   }
   // Rayleigh-Ritz on B = L Q^T [N, kb]: T = B^T B (fp64), its k leading eigenvectors W, U = B W^T diag(1 / sigma)
   SgemmArgs bm{};
@@ -1214,11 +1370,15 @@ struct KmSlot {
   bool active;
 };
 
-// Lloyd's iteration on `ns` problems of the same shape: every pass is enqueued on all streams before the host waits
-// for the first changed-label count, so the problems' kernels overlap; a problem leaves the loop when a pass changes
-// nothing.  With a null `ext` the initial-centre indices are checked (and the error reported) before the first pass.
+// Lloyd's iteration on `ns` problems of the same shape, each on its own stream.  The passes decide on the device
+// whether they still have work (see the control words above), so the host enqueues KM_BATCH passes on every stream and
+// only then reads the control words; a problem leaves the loop when a pass has changed nothing.  With a null `ext` the
+// initial-centre indices are checked (and the error reported) before the first pass.
+constexpr int KM_BATCH = 8;
+
 int kmeans_multi(KmSlot *slots, int ns, int N, int d, int k, int max_iter) {
-  const size_t lds = ((size_t)k * d + (size_t)64 * (d + 1)) * sizeof(float);
+  const int dp = (d + 3) & ~3;
+  const size_t lds = ((size_t)k * dp + (size_t)64 * (dp + 1)) * sizeof(float);
   TAP_HIP(set_lds((const void *)kmeans_assign_kernel, lds));
   const size_t lds_acc = (size_t)k * d * sizeof(double);
   TAP_HIP(set_lds((const void *)kmeans_partial_kernel, lds_acc));
@@ -1227,12 +1387,13 @@ int kmeans_multi(KmSlot *slots, int ns, int N, int d, int k, int max_iter) {
     KmSlot &q = slots[i];
     SmallWork w(q.work, N, d, k);
     if (!q.ext) hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, q.st, w.flag, 64, 0);
+    hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, q.st, w.changed, 64, 0);
     hipLaunchKernelGGL(fill_int_kernel, dim3((N + 255) / 256), dim3(256), 0, q.st, q.labels, N, -1);
     hipLaunchKernelGGL(kmeans_init_kernel, dim3(k), dim3(256), 0, q.st, q.U, N, d, k, q.init_idx, q.centres,
                        q.ext ? q.ext : w.flag);
     TAP_HIP(hipGetLastError());
     q.passes = 0;
-    q.active = true;
+    q.active = max_iter > 0;
   }
   for (int i = 0; i < ns; ++i) {
     if (slots[i].ext) continue;
@@ -1241,35 +1402,34 @@ int kmeans_multi(KmSlot *slots, int ns, int N, int d, int k, int max_iter) {
     TAP_RC(read_flag(w.flag, slots[i].st, &flag));
     if (flag) TAP_FAIL(QC_ERR_RANGE, "an initial-centre index lies outside [0, %d)", N);
   }
-  for (int it = 0; it < max_iter; ++it) {
+  for (int it0 = 0; it0 < max_iter; it0 += KM_BATCH) {
+    const int it1 = it0 + KM_BATCH < max_iter ? it0 + KM_BATCH : max_iter;
     bool any = false;
-    for (int i = 0; i < ns; ++i) {
-      KmSlot &q = slots[i];
-      if (!q.active) continue;
-      any = true;
-      SmallWork w(q.work, N, d, k);
-      hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, q.st, w.changed, 64, 0);
-      hipLaunchKernelGGL(kmeans_assign_kernel, dim3((N + 63) / 64), dim3(256), lds, q.st, q.U, N, d, q.centres, k,
-                         q.labels, w.changed);
-      TAP_HIP(hipGetLastError());
-      ++q.passes;
+    for (int it = it0; it < it1; ++it) {
+      for (int i = 0; i < ns; ++i) {
+        KmSlot &q = slots[i];
+        if (!q.active) continue;
+        any = true;
+        SmallWork w(q.work, N, d, k);
+        hipLaunchKernelGGL(kmeans_assign_kernel, dim3((N + 63) / 64), dim3(256), lds, q.st, q.U, N, d, q.centres, k,
+                           q.labels, w.changed, it);
+        hipLaunchKernelGGL(kmeans_partial_kernel, dim3(nb), dim3(128), lds_acc, q.st, q.U, N, d, q.labels, k,
+                           kmeans_rows_per(N), w.psum, w.pcnt, w.changed, it);
+        hipLaunchKernelGGL(kmeans_finish_kernel, dim3((k * d + 63) / 64), dim3(64), 0, q.st, w.psum, w.pcnt, nb, k, d,
+                           q.centres, w.changed, it);
+        TAP_HIP(hipGetLastError());
+      }
     }
     if (!any) break;
     for (int i = 0; i < ns; ++i) {
       KmSlot &q = slots[i];
       if (!q.active) continue;
       SmallWork w(q.work, N, d, k);
-      int changed = 0;
-      TAP_RC(read_flag(w.changed, q.st, &changed));
-      if (changed == 0) {
-        q.active = false;
-        continue;
-      }
-      hipLaunchKernelGGL(kmeans_partial_kernel, dim3(nb), dim3(128), lds_acc, q.st, q.U, N, d, q.labels, k,
-                         kmeans_rows_per(N), w.psum, w.pcnt);
-      hipLaunchKernelGGL(kmeans_finish_kernel, dim3((k * d + 255) / 256), dim3(256), 0, q.st, w.psum, w.pcnt, nb, k, d,
-                         q.centres);
-      TAP_HIP(hipGetLastError());
+      int ctl[4] = {0, 0, 0, 0};
+      TAP_HIP(hipMemcpyAsync(ctl, w.changed, sizeof(ctl), hipMemcpyDeviceToHost, q.st));
+      TAP_HIP(hipStreamSynchronize(q.st));
+      q.passes = ctl[KM_PASSES];
+      if (ctl[KM_DONE]) q.active = false;
     }
   }
   for (int i = 0; i < ns; ++i) TAP_HIP(hipStreamSynchronize(slots[i].st));
@@ -1290,7 +1450,7 @@ int aggregate_impl(const int *labels, int m, int N, int k, int *out, int *perm_o
   for (int i = 1; i < m; ++i) {
     hipLaunchKernelGGL(fill_int_kernel, dim3((k * k + 255) / 256), dim3(256), 0, st, w.T, k * k, 0);
     hipLaunchKernelGGL(contingency_kernel, dim3((N + 255) / 256), dim3(256), 0, st, labels, labels + (size_t)i * N, N, k, w.T);
-    hipLaunchKernelGGL(greedy_match_kernel, dim3(1), dim3(256), 0, st, w.T, k, w.perm + (size_t)i * k);
+    hipLaunchKernelGGL(greedy_match_kernel, dim3(1), dim3(1024), 0, st, w.T, k, w.perm + (size_t)i * k);
   }
   hipLaunchKernelGGL(vote_kernel, dim3((N + 255) / 256), dim3(256), 0, st, labels, w.perm, m, N, k, out);
   TAP_HIP(hipGetLastError());

@@ -889,7 +889,7 @@ __global__ __launch_bounds__(256) void kmeans_assign_kernel(const float *U, int 
 
 // update pass, stage 1: workgroup b walks its range of rows in ascending order, thread j owning dimension j, and adds
 // each row to its cluster's fp64 sums in LDS (LDS adds without return value: the adds of one thread to one address
-// are carried out in program order, so the sums are those of the rows in ascending order; 16 rows are loaded ahead);
+// are carried out in program order, so the sums are those of the rows in ascending order; 32 rows are loaded ahead);
 // stage 2 adds the workgroups' sums in order.  An empty cluster keeps its centre.  Nothing happens when the pass
 // changed no label.
 __global__ __launch_bounds__(128) void kmeans_partial_kernel(const float *U, int N, int d, const int *labels, int k,
@@ -905,31 +905,32 @@ __global__ __launch_bounds__(128) void kmeans_partial_kernel(const float *U, int
   const int r0 = blockIdx.x * rows_per, r1 = min(N, r0 + rows_per);
   const int jj = j < d ? j : 0;
   int r = r0;
-  int c[16], cn[16];
-  float v[16], vn[16];
-  if (r + 16 <= r1) {
+  constexpr int RB = 32;                  // rows per batch; two batches are in flight
+  int c[RB], cn[RB];
+  float v[RB], vn[RB];
+  if (r + RB <= r1) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < RB; ++i) {
       c[i] = labels[r + i];
       v[i] = U[(long long)(r + i) * d + jj];
     }
   }
-  for (; r + 16 <= r1; r += 16) {
-    // the next 16 rows are requested before this batch is added (clamped to the range: the last request repeats rows)
-    const int rn = r + 32 <= r1 ? r + 16 : r;
+  for (; r + RB <= r1; r += RB) {
+    // the next batch is requested before this one is added (clamped to the range: the last request repeats rows)
+    const int rn = r + 2 * RB <= r1 ? r + RB : r;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < RB; ++i) {
       cn[i] = labels[rn + i];
       vn[i] = U[(long long)(rn + i) * d + jj];
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < RB; ++i) {
       const int ci = clamp_label(c[i], k);
       if (j < d) atomicAdd(&accs[ci * d + j], (double)v[i]);
       if (j == 0) atomicAdd(&cnt[ci], 1);
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < RB; ++i) {
       c[i] = cn[i];
       v[i] = vn[i];
     }

@@ -196,6 +196,21 @@ def test_kmeans_pass_limit_duplicate_centres_and_bad_indices(qc):
     with pytest.raises(qc.QCError) as e:
         qc.qc_tap_kmeans(_cuda(U), _cuda(np.array([0, 3], np.int32)), 10, labels, centres, work)
     assert e.value.code == -4
+    # pass limits that fall inside and at the end of a group of passes the host enqueues ahead, on a problem that needs
+    # more passes than any of them: the state after exactly that many passes
+    rng = np.random.default_rng(77)
+    N, d, k = 3000, 8, 12
+    U = (rng.standard_normal((k, d))[rng.integers(0, k, size=N)] + 1.5 * rng.standard_normal((N, d))).astype(np.float32)
+    init = rng.choice(N, k, replace=False).astype(np.int32)
+    assert tap.kmeans(U, init, 100)[2] > 17
+    labels, centres = torch.empty(N, dtype=torch.int32, device="cuda"), torch.empty((k, d), device="cuda")
+    work = _work(qc, N, 8, 128, k, 128)
+    for limit in (3, 8, 9, 17):
+        wl, wc, wp = tap.kmeans(U, init, limit)
+        assert wp == limit
+        assert qc.qc_tap_kmeans(_cuda(U), _cuda(init), limit, labels, centres, work) == limit
+        if _check_labels(U, labels.cpu().numpy(), wl, wc) == 0:
+            assert np.allclose(centres.cpu().numpy(), wc, rtol=1e-6, atol=1e-6)
 
 
 # ------------------------------------------------------------------------------------------ aggregation

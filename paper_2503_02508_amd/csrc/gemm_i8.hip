@@ -428,6 +428,85 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     const bool fast_t = (T % 4) == 0;
     const bool tile_one_batch = (T % BM) == 0;      // then every row of the tile belongs to batch element m0 / T
     const int b_tile = m0 / T;
+    if (BM == 128 && BN == 128 && tile_one_batch && fast_t && m0 + BM <= p.M && n0 + BN <= p.N && !p.y &&
+        D % BN == 0 && (p.hd & 3) == 0 && (p.Tp & 7) == 0) {
+      // Interior tile inside one batch element and one of Q, K, V: the split values go through LDS (free after the K
+      // loop) and leave as 16-byte stores along the contiguous direction of their layout (Q / K: features of a
+      // token and head; V^T: tokens of a feature), instead of 4-byte (Q / K) and scattered 8-byte (V^T) stores.
+      const int part = n0 / D;
+      const int tb = m0 - b_tile * T;                         // first token of the tile
+      if (part < 2) {
+        constexpr int SR = BN + 4;                            // words per staged row
+        unsigned *stage = (unsigned *)smem;
+        const float mul = part == 0 ? p.q_scale : 1.0f;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int nl = wn0 + j * 32 + (lane & 31);
+          const float sc = a_s * w_scale[n0 + nl];
+          const int zw = a_z * wsum[n0 + nl];
+          const float bs = bias ? bias[n0 + nl] : 0.0f;
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int ml = wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+              const float v = fmaf(sc, (float)(acc[i][j][r] - zw), bs) * mul;
+              const _Float16 hi = (_Float16)v, lo = (_Float16)(v - (float)hi);
+              stage[ml * SR + nl] =
+                  (unsigned)__builtin_bit_cast(unsigned short, hi) | ((unsigned)__builtin_bit_cast(unsigned short, lo) << 16);
+            }
+        }
+        __syncthreads();
+        // thread -> four features cc .. cc + 3 (inside one head: heads start at multiples of hd, a multiple of 4) of
+        // the rows cr, cr + NT / 32, ...
+        const int cr = tid >> 5, cc = (tid & 31) * 4;
+        const int nn = n0 - part * D + cc, h = nn / p.hd, e = nn - h * p.hd;
+        unsigned *dst = (part == 0 ? p.q_words : p.k_words) +
+                        ((unsigned)(b_tile * p.heads + h) * (unsigned)T + (unsigned)(tb + cr)) * (unsigned)p.hd + (unsigned)e;
+#pragma unroll
+        for (int q = 0; q < BM * 32 / NT; ++q)
+          *(v4i *)(dst + (unsigned)(q * (NT / 32)) * (unsigned)p.hd) = *(const v4i *)(stage + (cr + q * (NT / 32)) * SR + cc);
+      } else {
+        constexpr int VR = BM + 8;                            // halves per staged feature row
+        _Float16 *sh = (_Float16 *)smem, *sl = sh + BN * VR;
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int nl = wn0 + j * 32 + (lane & 31);
+          const float sc = a_s * w_scale[n0 + nl];
+          const int zw = a_z * wsum[n0 + nl];
+          const float bs = bias ? bias[n0 + nl] : 0.0f;
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+              h4 hi, lo;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const float v = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs);
+                hi[q] = (_Float16)v;
+                lo[q] = (_Float16)(v - (float)hi[q]);
+              }
+              // four consecutive tokens stay together under the key permutation of the V^T rows
+              const int pos = vt_pos(wm0 + i * 32 + rg * 8 + (lane >> 5) * 4);
+              *(h4 *)(sh + nl * VR + pos) = hi;
+              *(h4 *)(sl + nl * VR + pos) = lo;
+            }
+        }
+        __syncthreads();
+        // thread -> 8 consecutive token positions ch of the features fc, fc + NT / 16, ...
+        const int fc = tid >> 4, ch = (tid & 15) * 8;
+#pragma unroll
+        for (int q = 0; q < BN * 16 / NT; ++q) {
+          const int col = fc + q * (NT / 16);
+          const int nn = n0 - 2 * D + col, h = nn / p.hd, e = nn - h * p.hd;
+          const unsigned o = ((unsigned)(b_tile * p.heads + h) * (unsigned)p.DP + (unsigned)e) * (unsigned)p.Tp + (unsigned)(tb + ch);
+          *(v4i *)(vh + o) = *(const v4i *)(sh + col * VR + ch);
+          *(v4i *)(vl + o) = *(const v4i *)(sl + col * VR + ch);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int n = n0 + wn0 + j * 32 + (lane & 31);

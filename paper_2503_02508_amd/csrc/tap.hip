@@ -685,6 +685,18 @@ __device__ __forceinline__ double row16_sum(double v) {
   return v;
 }
 
+// 1 / x and x^-1/2 to fp64 rounding level: hardware estimate, two Newton steps
+__device__ __forceinline__ double nr_rcp(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  r = r * (2.0 - x * r);
+  return r * (2.0 - x * r);
+}
+__device__ __forceinline__ double nr_rsq(double x) {
+  double r = __builtin_amdgcn_rsq(x);
+  r = r * (1.5 - 0.5 * x * r * r);
+  return r * (1.5 - 0.5 * x * r * r);
+}
+
 // Eigenvectors of the symmetric positive semi-definite T[kb, kb] (fp64) by one-sided Jacobi rotations on the rows of
 // a copy M of T (LDS): rotations from the left make the rows mutually orthogonal; then row j = lambda_j v_j^T.  The
 // kb / 2 pairs of a round are disjoint (round-robin schedule) and rotate concurrently, one pair per row of 16 lanes
@@ -747,9 +759,13 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const double *T, int kb, i
       ga = row16_sum(ga);
       const double al = nrm2[a], be = nrm2[b];
       if (live && fmin(al, be) > floor2 && fabs(ga) > 1e-11 * sqrt(al * be)) {
-        const double zeta = (be - al) / (2.0 * ga);
-        const double tt = copysign(1.0, zeta) / (fabs(zeta) + sqrt(1.0 + zeta * zeta));
-        const double c_ = 1.0 / sqrt(1.0 + tt * tt), s_ = c_ * tt;
+        // the rotation from hardware reciprocal / reciprocal-square-root estimates refined by Newton steps: a
+        // correctly rounded division and square root cost several times the rest of the round, and any (c, s) with
+        // c^2 + s^2 = 1 to rounding keeps the rows' span; the sweeps converge on the same vectors
+        const double zeta = (be - al) * nr_rcp(2.0 * ga);
+        const double h2 = fma(zeta, zeta, 1.0);
+        const double tt = copysign(1.0, zeta) * nr_rcp(fabs(zeta) + h2 * nr_rsq(h2));
+        const double c_ = nr_rsq(fma(tt, tt, 1.0)), s_ = c_ * tt;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int c = e + 16 * i;

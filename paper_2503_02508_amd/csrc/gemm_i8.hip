@@ -753,7 +753,12 @@ static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
   // keep the LDS and memory pipes busy (they are issue-bound per wavefront), so the tile is shared by 8.
   // The residual epilogue keeps a tile of x in registers, which would leave the 4-wavefront variant one
   // workgroup per CU: it always runs on 8.
-  if (EPI == EPI_RESID || ((a.M + 127) / 128) * ((a.N + 127) / 128) <= 256)
+  // Inside a block the QKV product runs beside the other sub-batch's kernels: beyond half a chip of tiles it takes
+  // the 4-wavefront variant, whose workgroups share a compute unit with the other stream's instead of queueing for a
+  // free one (measured on the benchmark's sub-batches, 216 tiles: +1.8 % on the whole pass although the launch itself
+  // takes 5 % longer).
+  const int n_tiles = ((a.M + 127) / 128) * (((a.sel_D ? 2 * a.sel_D : a.N) + 127) / 128);
+  if (EPI == EPI_RESID || n_tiles <= (EPI == EPI_QKV ? 128 : 256))
     return launch_cfg<128, 128, 2, 4, EPI, TAG, W4, 3>(a, nz, st);
   // Otherwise 4 wavefronts per tile and two workgroups per compute unit.  (256x256 tiles on 8 wavefronts halve
   // the L2 traffic per operation but measured no faster at M = 32768 and slower below, and their QKV

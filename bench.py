@@ -34,8 +34,8 @@ TAP_ITERS, TAP_MAX_PASSES = 8, 100   # power-iteration rounds and k-means pass l
 # under profiles/, keyed by (workload, kernel class).  None where no counter run covers the pair.
 TRAFFIC = {
     # profiles/sampler_cfg1_dit_xl2_b8_hbm_traffic.txt: (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB per dispatch
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc2"): (17407.2 * 2.0 + 9216.0) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_qkv"): (6323.5 * 2.0 + 13825.7) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc2"): (17407.0 * 2.0 + 9216.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_qkv"): (6374.5 * 2.0 + 13824.0) * 1024,
     ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc1"): (7676.6 * 2.0 + 4608.0) * 1024,
     ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_proj"): (6180.1 * 2.0 + 9216.0) * 1024,
     ("dit_xl2_256_w8a8_b8_ddim50_n2", "attention"): (7245.0 * 2.0 + 1536.0) * 1024,

@@ -40,7 +40,7 @@ TRAFFIC = {
     ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_proj"): (6180.1 * 2.0 + 9216.0) * 1024,
     ("dit_xl2_256_w8a8_b8_ddim50_n2", "attention"): (7245.0 * 2.0 + 1536.0) * 1024,
     # profiles/clustering_tap1_counters.txt
-    ("tap1", "similarity"): (1715369.6 * 2.0 + 279863.8) * 1024,
+    ("tap1", "similarity"): (1706789.6 * 2.0 + 279926.8) * 1024,
 }
 
 

@@ -226,14 +226,29 @@ __global__ __launch_bounds__(256, 2) void sgemm_kernel(SgemmArgs p) {
     }
     const float *ap = As[cur] + (lane >> 5) * LDA + wm0 + (lane & 31);
     const float *bp = Bs[cur] + (lane >> 5) * LDB + wn0 + (lane & 31);
+    // the fragments of step kk + 1 are read from LDS before the four products of step kk are issued (the
+    // scheduling barriers pin that order), so an LDS round trip hides behind 256 cycles of matrix-core work
+    float a0 = ap[0], a1 = ap[32], b0 = bp[0], b1 = bp[32];
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
     for (int kk = 0; kk < TK / 2; ++kk) {
-      const float a0 = ap[kk * 2 * LDA], a1 = ap[kk * 2 * LDA + 32];
-      const float b0 = bp[kk * 2 * LDB], b1 = bp[kk * 2 * LDB + 32];
+      float na0 = 0.f, na1 = 0.f, nb0 = 0.f, nb1 = 0.f;
+      if (kk + 1 < TK / 2) {
+        na0 = ap[(kk + 1) * 2 * LDA];
+        na1 = ap[(kk + 1) * 2 * LDA + 32];
+        nb0 = bp[(kk + 1) * 2 * LDB];
+        nb1 = bp[(kk + 1) * 2 * LDB + 32];
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);      // the LDS reads (two paired loads)
+      }
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);        // then the four matrix instructions
+      a0 = na0;
+      a1 = na1;
+      b0 = nb0;
+      b1 = nb1;
     }
     __syncthreads();
   }

@@ -335,3 +335,170 @@ def test_guidance_step_uses_null_label_for_second_half():
     ec = dit.denoiser(lat, np.full(3, 500), lab, TINY, w, lin, {}, True)
     eu = dit.denoiser(lat, np.full(3, 500), np.full(3, TINY.num_classes), TINY, w, lin, {}, True)
     assert np.allclose(eps, eu + 1.5 * (ec - eu), atol=1e-14)
+
+
+# ------------------------------------- head, tail and calibration of the network
+class _TorchDiT:
+    """The whole un-quantised network (the cited DiT architecture) written with torch library
+    routines only: conv2d patch embedding, embedding lookup, linear / silu / layer_norm, scaled-dot-
+    product attention, fold for the un-patchify.  Returns the noise estimate and, per block, the
+    inputs of the five linears (the quantiser sites)."""
+
+    def __init__(self, w, desc):
+        self.w = {k: torch.from_numpy(np.asarray(v, dtype=np.float64)) for k, v in w.items() if k != "blocks"}
+        self.blocks = [{k: torch.from_numpy(v.astype(np.float64)) for k, v in b.items()} for b in w["blocks"]]
+        self.d = desc
+
+    def cond(self, t, y):
+        w, half = self.w, self.d.freq_dim // 2
+        freqs = torch.pow(torch.tensor(10000.0, dtype=torch.float64), -torch.arange(half, dtype=torch.float64) / half)
+        args = torch.as_tensor(np.asarray(t), dtype=torch.float64)[:, None] * freqs[None]
+        emb = torch.cat([torch.cos(args), torch.sin(args)], dim=1)
+        te = F.linear(F.silu(F.linear(emb, w["t_w1"], w["t_b1"])), w["t_w2"], w["t_b2"])
+        return te + F.embedding(torch.as_tensor(np.asarray(y), dtype=torch.long), w["label_table"])
+
+    def embed(self, x):
+        w, d = self.w, self.d
+        k = w["patch_w"].reshape(d.hidden, d.latent_c, d.patch, d.patch)
+        tok = F.conv2d(torch.from_numpy(np.asarray(x, dtype=np.float64)), k, w["patch_b"], stride=d.patch)
+        return tok.flatten(2).transpose(1, 2) + w["pos"][None]
+
+    def final(self, x, c):
+        w, d = self.w, self.d
+        p, C2 = d.patch, 2 * d.latent_c
+        shift, scale = F.linear(F.silu(c), w["fada_w"], w["fada_b"]).chunk(2, dim=1)
+        h = F.layer_norm(x, (d.hidden,), eps=1e-6) * (1 + scale.unsqueeze(1)) + shift.unsqueeze(1)
+        out = F.linear(h, w["flin_w"], w["flin_b"])                      # [B, T, p*p*2C], features (ph, pw, c)
+        B, T, _ = out.shape
+        cols = out.reshape(B, T, p, p, C2).permute(0, 4, 2, 3, 1).reshape(B, C2 * p * p, T)   # fold wants (c, ph, pw)
+        img = F.fold(cols, output_size=(d.latent_h, d.latent_w), kernel_size=p, stride=p)
+        return img[:, :d.latent_c]
+
+    def forward(self, x, t, y):
+        c = self.cond(t, y)
+        h = self.embed(x)
+        sites = []
+        for bw in self.blocks:
+            B, T, D = h.shape
+            H = self.d.heads
+            a_in = F.silu(c)
+            sm, cm, gm, sl, cl, gl = F.linear(a_in, bw["ada_w"], bw["ada_b"]).chunk(6, dim=1)
+            q_in = F.layer_norm(h, (D,), eps=1e-6) * (1 + cm.unsqueeze(1)) + sm.unsqueeze(1)
+            qkv = F.linear(q_in, bw["qkv_w"], bw["qkv_b"]).reshape(B, T, 3, H, D // H).permute(2, 0, 3, 1, 4)
+            p_in = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2]).transpose(1, 2).reshape(B, T, D)
+            h = h + gm.unsqueeze(1) * F.linear(p_in, bw["proj_w"], bw["proj_b"])
+            f1_in = F.layer_norm(h, (D,), eps=1e-6) * (1 + cl.unsqueeze(1)) + sl.unsqueeze(1)
+            f2_in = F.gelu(F.linear(f1_in, bw["fc1_w"], bw["fc1_b"]), approximate="tanh")
+            h = h + gl.unsqueeze(1) * F.linear(f2_in, bw["fc2_w"], bw["fc2_b"])
+            sites.append({"ada": a_in, "qkv": q_in, "proj": p_in, "fc1": f1_in, "fc2": f2_in})
+        return self.final(h, c).numpy(), sites
+
+
+def test_conditioning_vs_torch_library():
+    w, _, _ = _tiny_setup()
+    t = np.array([0, 37, 999]); y = np.array([3, 0, TINY.num_classes])          # last row of the table = null label
+    got = dit.conditioning(t, y, w)
+    want = _TorchDiT(w, TINY).cond(t, y).numpy()
+    assert got.shape == (3, TINY.hidden) and np.allclose(got, want, rtol=1e-11, atol=1e-13)
+    # each label moves the vector by exactly the difference of its table rows; the timestep part is shared
+    other = dit.conditioning(t, np.array([4, 0, 1]), w)
+    assert np.allclose(other[0] - got[0], w["label_table"][4].astype(np.float64) - w["label_table"][3])
+    assert np.array_equal(other[1], got[1])
+    # the hidden layer of the timestep MLP has a SiLU: zeroing the second layer's weights leaves bias + label row only
+    w2 = dict(w); w2["t_w2"] = np.zeros_like(w["t_w2"])
+    assert np.allclose(dit.conditioning(t, y, w2), w["t_b2"].astype(np.float64) + w["label_table"][y])
+
+
+def test_embed_vs_conv2d_patch_embedding():
+    w, lat, _ = _tiny_setup()
+    got = dit.embed(lat, w, TINY.patch)
+    want = _TorchDiT(w, TINY).embed(lat).numpy()
+    assert got.shape == (3, TINY.tokens, TINY.hidden) and np.allclose(got, want, rtol=1e-11, atol=1e-13)
+    # a zero latent embeds to bias + position table
+    z = dit.embed(np.zeros_like(lat), w, TINY.patch)
+    assert np.allclose(z, (w["patch_b"].astype(np.float64) + w["pos"].astype(np.float64))[None])
+    # one hot pixel (c, i*p+ph, j*p+pw) excites column (c, ph, pw) of the kernel in token i*gw+j only
+    p, gw = TINY.patch, TINY.latent_w // TINY.patch
+    x1 = np.zeros((1, TINY.latent_c, TINY.latent_h, TINY.latent_w)); x1[0, 2, 1 * p + 1, 3 * p + 0] = 1.0
+    d = dit.embed(x1, w, p) - z[:1]
+    col = w["patch_w"].astype(np.float64)[:, (2 * p + 1) * p + 0]
+    assert np.allclose(d[0, 1 * gw + 3], col) and np.count_nonzero(np.abs(d).sum(-1)) == 1
+
+
+def test_final_layer_vs_torch_library_and_closed_forms():
+    w, _, _ = _tiny_setup()
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((2, TINY.tokens, TINY.hidden)); c = rng.standard_normal((2, TINY.hidden))
+    got = dit.final_layer(x, c, w, TINY.patch, TINY.latent_c, TINY.latent_h, TINY.latent_w)
+    want = _TorchDiT(w, TINY).final(torch.from_numpy(x), torch.from_numpy(c)).numpy()
+    assert got.shape == (2, TINY.latent_c, TINY.latent_h, TINY.latent_w)
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-12)
+    # zero linear weights: every pixel shows the bias of its (ph, pw, c) feature, c among the FIRST C of the 2C channels
+    w0 = dict(w); w0["flin_w"] = np.zeros_like(w["flin_w"])
+    e = dit.final_layer(x, c, w0, TINY.patch, TINY.latent_c, TINY.latent_h, TINY.latent_w)
+    p, C = TINY.patch, TINY.latent_c
+    for (ch, r, col) in [(0, 0, 0), (3, 5, 2), (1, 7, 7)]:
+        assert e[1, ch, r, col] == np.float64(w["flin_b"][((r % p) * p + (col % p)) * 2 * C + ch])
+    # modulation: first half of the adaLN output is the shift, second half the scale (scale = -1 wipes the normalised
+    # activations, shift = s then makes every feature s, so the output is s * row-sums of the linear + bias)
+    D = TINY.hidden
+    w1 = dict(w); w1["fada_w"] = np.zeros_like(w["fada_w"])
+    w1["fada_b"] = np.concatenate([np.full(D, 0.25, np.float32), np.full(D, -1.0, np.float32)])
+    e1 = dit.final_layer(x, c, w1, p, C, TINY.latent_h, TINY.latent_w)
+    feat = 0.25 * w["flin_w"].astype(np.float64).sum(axis=1) + w["flin_b"]
+    assert np.allclose(e1[0, 2, 4, 5], feat[((4 % p) * p + (5 % p)) * 2 * C + 2])
+
+
+def test_fp_denoiser_vs_torch_library_network():
+    w, lat, lab = _tiny_setup()
+    t = np.array([500, 20, 980])
+    got = dit.denoiser(lat, t, lab, TINY, w, dit.FPLinears(w), {}, True)
+    want, _ = _TorchDiT(w, TINY).forward(lat, t, lab)
+    assert np.allclose(got, want, rtol=1e-9, atol=1e-11)
+
+
+def test_calibration_ranges_are_site_inputs_over_all_calibration_data():
+    """Eq. 2 on calibration data: for every (block, site) the range is the min / max of that linear's INPUT, taken
+    over all calibration samples together; Eq. 3 then gives (s, z).  The inputs come from the torch-library network."""
+    w, lat, lab = _tiny_setup()
+    t = np.array([980, 500, 20])
+    qp, ranges = sampler.calibrate(TINY, w, lat, lab, t)
+    net = _TorchDiT(w, TINY)
+    per_sample = [net.forward(lat[n:n + 1], t[n:n + 1], lab[n:n + 1])[1] for n in range(3)]
+    for blk in range(TINY.depth):
+        for site in dit.SITES:
+            lo = min(float(s[blk][site].min()) for s in per_sample)
+            hi = max(float(s[blk][site].max()) for s in per_sample)
+            glo, ghi = ranges[(blk, site)]
+            assert math.isclose(glo, lo, rel_tol=1e-9, abs_tol=1e-12) and math.isclose(ghi, hi, rel_tol=1e-9, abs_tol=1e-12)
+            s, z = qp[(blk, site)]
+            ws, wz = quant.act_qparams(lo, hi)
+            assert z == wz and math.isclose(float(s), float(ws), rel_tol=1e-6)
+            # the range covers 0 and the grid reaches both ends (reading of Eq. 2-3 pinned in the quantiser tests)
+            assert float(s) * (0 - z) <= min(lo, 0) + float(s) / 2 and float(s) * (255 - z) >= max(hi, 0) - float(s) / 2
+    # a single sample gives a narrower (or equal) range everywhere, and strictly narrower somewhere
+    _, r1 = sampler.calibrate(TINY, w, lat[:1], lab[:1], t[:1])
+    assert all(r1[k][0] >= ranges[k][0] and r1[k][1] <= ranges[k][1] for k in ranges)
+    assert any(r1[k] != ranges[k] for k in ranges)
+
+
+def test_calibrate_block_ranges_vs_torch_block_inputs():
+    w, _, _ = _tiny_setup()
+    rng = np.random.default_rng(13)
+    tok = rng.standard_normal((3, TINY.tokens, TINY.hidden)); cond = rng.standard_normal((3, TINY.hidden))
+    qp, ranges = sampler.calibrate_block(TINY, w, tok, cond)
+    bw = {k: torch.from_numpy(v.astype(np.float64)) for k, v in w["blocks"][0].items()}
+    x, c = torch.from_numpy(tok), torch.from_numpy(cond)
+    D, H = TINY.hidden, TINY.heads
+    sm, cm, gm, sl, cl, gl = F.linear(F.silu(c), bw["ada_w"], bw["ada_b"]).chunk(6, dim=1)
+    q_in = F.layer_norm(x, (D,), eps=1e-6) * (1 + cm.unsqueeze(1)) + sm.unsqueeze(1)
+    qkv = F.linear(q_in, bw["qkv_w"], bw["qkv_b"]).reshape(3, TINY.tokens, 3, H, D // H).permute(2, 0, 3, 1, 4)
+    p_in = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2]).transpose(1, 2).reshape(3, TINY.tokens, D)
+    x2 = x + gm.unsqueeze(1) * F.linear(p_in, bw["proj_w"], bw["proj_b"])
+    f1_in = F.layer_norm(x2, (D,), eps=1e-6) * (1 + cl.unsqueeze(1)) + sl.unsqueeze(1)
+    f2_in = F.gelu(F.linear(f1_in, bw["fc1_w"], bw["fc1_b"]), approximate="tanh")
+    want = {"ada": F.silu(c), "qkv": q_in, "proj": p_in, "fc1": f1_in, "fc2": f2_in}
+    assert set(ranges) == {(0, s) for s in dit.SITES}
+    for site, v in want.items():
+        assert np.allclose(ranges[(0, site)], (float(v.min()), float(v.max())), rtol=1e-9, atol=1e-12)
+        assert qp[(0, site)][1] == quant.act_qparams(float(v.min()), float(v.max()))[1]

@@ -19,6 +19,17 @@ floating point.
 What is cached ("outputs from self-attention and MLP layers", same section):
 the output of the attention projection and of fc2, bias included, before the
 adaLN gate.  A cached block recomputes only the gates at the current timestep.
+
+Storage precision (the paper fixes none): every tensor the sampler keeps in
+memory between two operations - conditioning vectors, tokens, modulation
+vectors, Q | K | V, the module outputs that are cached, the residual stream
+after every gated add, the noise estimate - is a float32 tensor; `st()` below
+rounds to it.  The arithmetic between two stored tensors is float64 (exact
+integer contractions, float64 everywhere else).  Values that are quantised
+right where they are produced (LayerNorm + modulation output, attention
+output, GELU output) are never stored: Eq. 1 rounds the float64 value to
+float32 once and decides there.  `storage("f64")` switches the rounding off
+(used to check the formulas against library routines to 1e-10).
 """
 from __future__ import annotations
 
@@ -26,8 +37,29 @@ import numpy as np
 
 from .quant import QLinear, lin_q, bf16_round
 
+import contextlib
+
 SITES = ("ada", "qkv", "proj", "fc1", "fc2")
 F64 = np.float64
+_STORE_F32 = True
+
+
+def st(x):
+    """The value of x after it is stored as a float32 tensor."""
+    x = np.asarray(x, dtype=F64)
+    return x.astype(np.float32).astype(F64) if _STORE_F32 else x
+
+
+@contextlib.contextmanager
+def storage(kind: str):
+    """storage("f64"): stored tensors keep float64 (pure mathematics); storage("f32"): the default."""
+    global _STORE_F32
+    old = _STORE_F32
+    _STORE_F32 = {"f32": True, "f64": False}[kind]
+    try:
+        yield
+    finally:
+        _STORE_F32 = old
 
 
 # ------------------------------------------------------------ linear modes
@@ -104,7 +136,7 @@ def attention(qkv, heads: int):
 # ------------------------------------------------------------------- blocks
 def block_mod(c, blk: int, linear):
     """adaLN projection of a block: Lin(SiLU(c)) split into its six chunks."""
-    mod = linear(blk, "ada", silu(c))
+    mod = st(linear(blk, "ada", silu(c)))
     return np.split(mod, 6, axis=1)
 
 
@@ -116,20 +148,20 @@ def block_full(x, c, blk: int, heads: int, linear, cache: dict | None = None, ta
     B, T, D = x.shape
     shift_msa, scale_msa, gate_msa, shift_mlp, scale_mlp, gate_mlp = block_mod(c, blk, linear)
     h = modulate(layer_norm(x), shift_msa, scale_msa)
-    qkv = linear(blk, "qkv", h.reshape(B * T, D)).reshape(B, T, 3 * D)
+    qkv = st(linear(blk, "qkv", h.reshape(B * T, D))).reshape(B, T, 3 * D)
     o = attention(qkv, heads)
-    A = linear(blk, "proj", o.reshape(B * T, D)).reshape(B, T, D)
-    x = x + gate_msa[:, None, :] * A
+    A = st(linear(blk, "proj", o.reshape(B * T, D))).reshape(B, T, D)
+    x = st(x + gate_msa[:, None, :] * A)
     h2 = modulate(layer_norm(x), shift_mlp, scale_mlp)
     u = linear(blk, "fc1", h2.reshape(B * T, D))
     g = gelu_tanh(u)
-    Mo = linear(blk, "fc2", g).reshape(B, T, D)
-    x = x + gate_mlp[:, None, :] * Mo
+    Mo = st(linear(blk, "fc2", g)).reshape(B, T, D)
+    x = st(x + gate_mlp[:, None, :] * Mo)
     if cache is not None:
         cache[(blk, "attn")] = bf16_round(A) if cache_bf16 else A
         cache[(blk, "mlp")] = bf16_round(Mo) if cache_bf16 else Mo
     if tap is not None:
-        tap.update(h=h, qkv=qkv, o=o, A=A, h2=h2, u=u, g=g, Mo=Mo)
+        tap.update(h=h, qkv=qkv, o=o, A=A, h2=h2, u=u, g=g, Mo=Mo, x=x)
     return x
 
 
@@ -137,8 +169,8 @@ def block_cached(x, c, blk: int, linear, cache: dict):
     """A block on a non-refresh step: the stored module outputs are reused and
     only the gates come from the current conditioning."""
     _, _, gate_msa, _, _, gate_mlp = block_mod(c, blk, linear)
-    x = x + gate_msa[:, None, :] * cache[(blk, "attn")]
-    x = x + gate_mlp[:, None, :] * cache[(blk, "mlp")]
+    x = st(x + gate_msa[:, None, :] * cache[(blk, "attn")])
+    x = st(x + gate_mlp[:, None, :] * cache[(blk, "mlp")])
     return x
 
 
@@ -153,19 +185,19 @@ def block_mixed(x, c, blk: int, heads: int, linear, cache: dict, attn_full: bool
     shift_msa, scale_msa, gate_msa, shift_mlp, scale_mlp, gate_mlp = block_mod(c, blk, linear)
     if attn_full:
         h = modulate(layer_norm(x), shift_msa, scale_msa)
-        qkv = linear(blk, "qkv", h.reshape(B * T, D)).reshape(B, T, 3 * D)
-        A = linear(blk, "proj", attention(qkv, heads).reshape(B * T, D)).reshape(B, T, D)
+        qkv = st(linear(blk, "qkv", h.reshape(B * T, D))).reshape(B, T, 3 * D)
+        A = st(linear(blk, "proj", attention(qkv, heads).reshape(B * T, D))).reshape(B, T, D)
         cache[(blk, "attn")] = bf16_round(A) if cache_bf16 else A
     else:
         A = cache[(blk, "attn")]
-    x = x + gate_msa[:, None, :] * A
+    x = st(x + gate_msa[:, None, :] * A)
     if mlp_full:
         h2 = modulate(layer_norm(x), shift_mlp, scale_mlp)
-        Mo = linear(blk, "fc2", gelu_tanh(linear(blk, "fc1", h2.reshape(B * T, D)))).reshape(B, T, D)
+        Mo = st(linear(blk, "fc2", gelu_tanh(linear(blk, "fc1", h2.reshape(B * T, D))))).reshape(B, T, D)
         cache[(blk, "mlp")] = bf16_round(Mo) if cache_bf16 else Mo
     else:
         Mo = cache[(blk, "mlp")]
-    x = x + gate_mlp[:, None, :] * Mo
+    x = st(x + gate_mlp[:, None, :] * Mo)
     return x
 
 
@@ -180,10 +212,10 @@ def timestep_embedding(t, dim: int = 256):
 
 def conditioning(t, y, w: dict):
     """c = MLP(sinusoid(t)) + label_table[y]."""
-    e = timestep_embedding(t, w["t_w1"].shape[1])
-    h = silu(e @ w["t_w1"].astype(F64).T + w["t_b1"].astype(F64))
-    te = h @ w["t_w2"].astype(F64).T + w["t_b2"].astype(F64)
-    return te + w["label_table"].astype(F64)[np.asarray(y, dtype=np.int64)]
+    e = st(timestep_embedding(t, w["t_w1"].shape[1]))
+    h = st(silu(e @ w["t_w1"].astype(F64).T + w["t_b1"].astype(F64)))
+    te = st(h @ w["t_w2"].astype(F64).T + w["t_b2"].astype(F64))
+    return st(te + w["label_table"].astype(F64)[np.asarray(y, dtype=np.int64)])
 
 
 def patchify(x, p: int):
@@ -204,16 +236,16 @@ def unpatchify(tok, p: int, c_out: int, H: int, W: int):
 
 def embed(x_lat, w: dict, p: int):
     tok = patchify(np.asarray(x_lat, dtype=F64), p)
-    return tok @ w["patch_w"].astype(F64).T + w["patch_b"].astype(F64) + w["pos"].astype(F64)[None]
+    return st(tok @ w["patch_w"].astype(F64).T + w["patch_b"].astype(F64) + w["pos"].astype(F64)[None])
 
 
 def final_layer(x, c, w: dict, p: int, C: int, H: int, W: int):
     """adaLN-modulated LayerNorm, linear to p*p*2C features, unpatchify; returns
     the noise estimate = first C of the 2C channels."""
-    mod = silu(c) @ w["fada_w"].astype(F64).T + w["fada_b"].astype(F64)
+    mod = st(silu(c) @ w["fada_w"].astype(F64).T + w["fada_b"].astype(F64))
     shift, scale = np.split(mod, 2, axis=1)
     h = modulate(layer_norm(x), shift, scale)
-    out = h @ w["flin_w"].astype(F64).T + w["flin_b"].astype(F64)
+    out = st(h @ w["flin_w"].astype(F64).T + w["flin_b"].astype(F64))
     img = unpatchify(out, p, 2 * C, H, W)
     return img[:, :C]
 

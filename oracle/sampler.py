@@ -15,12 +15,15 @@ Readings taken where the paper is silent:
     evaluated as x + (K-1)(x-mu), which is Eq. 10 rearranged.
   * classifier-free guidance (not in the paper; used by one workload): the
     batch is [conditional ; null-label], eps = eps_u + w (eps_c - eps_u).
+  * storage precision: the sample after the solver update and the sample after
+    VC are float32 tensors (dit.st); each of the two is evaluated in float64
+    from the stored tensors it reads.
 """
 from __future__ import annotations
 
 import numpy as np
 
-from .dit import FPLinears, QLinears, denoiser, block_full, SITES
+from .dit import FPLinears, QLinears, denoiser, block_full, SITES, st
 from .quant import act_qparams
 
 F64 = np.float64
@@ -89,9 +92,9 @@ def sample_step(x, labels, i, t, abar_t, abar_prev, desc, w, linear, cache, inte
     eps = denoiser(xin, tt, yin, desc, w, linear, cache, full, taps, cache_bf16)
     if cfg_scale > 0:
         eps = cfg_combine(eps[:B], eps[B:], cfg_scale)
-    xn = ddim_update(np.asarray(x, dtype=F64), eps, abar_t, abar_prev)
+    xn = st(ddim_update(np.asarray(x, dtype=F64), eps, abar_t, abar_prev))      # the updated sample is a stored tensor ...
     if K_t is not None:
-        xn = vc_correct(xn, K_t)
+        xn = st(vc_correct(xn, K_t))                                           # ... and so is the corrected one
     return xn, eps
 
 

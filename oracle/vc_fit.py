@@ -37,7 +37,7 @@ from __future__ import annotations
 import numpy as np
 
 from . import sampler
-from .dit import FPLinears
+from .dit import FPLinears, st
 
 F64 = np.float64
 
@@ -91,6 +91,6 @@ def fit_sampler(x0, labels, steps, interval, desc, w, linear_q, cfg_scale=0.0, e
                                        force_full=True)
         x_hat, _ = sampler.sample_step(x_hat, labels, i, int(tt[i]), at[i], ap[i], desc, w, linear_q, cache_q, interval,
                                        cfg_scale, None)
-        K[i] = fit_factor(x_hat, x_ref, eps)
-        x_hat = sampler.vc_correct(x_hat, K[i])
+        K[i] = st(fit_factor(x_hat, x_ref, eps))              # the factors are a stored (float32) table
+        x_hat = st(sampler.vc_correct(x_hat, K[i]))
     return K, x_hat, x_ref

@@ -832,7 +832,7 @@ static int sample_step_prepared(qc_ctx *ctx, float *x, int B, int mode, int w, d
   const double cx = std::sqrt(abar_prev / abar_t);
   const double ce = std::sqrt(1.0 - abar_prev) - cx * std::sqrt(1.0 - abar_t);
   QC_PROF(QC_K_DDIM_VC);
-  QC_HIP(launch_ddim_vc(x, ctx->eps, B, ctx->C, ctx->d.latent_h * ctx->d.latent_w, (float)cx, (float)ce, cfg_scale, K_t, st));
+  QC_HIP(launch_ddim_vc(x, ctx->eps, B, ctx->C, ctx->d.latent_h * ctx->d.latent_w, cx, ce, cfg_scale, K_t, st));
   return QC_OK;
 }
 
@@ -1072,7 +1072,7 @@ int qc_vc_fit_sampler(qc_ctx *ctx, const qc_weights_f32 *w, float *x_hat, float 
     // reference: un-quantised network, every step in full, no VC
     rc = denoise_f32_impl(ctx, w, x_ref, B, t[i], labels, B, Beff, ctx->eps_ref, st);
     if (rc) return rc;
-    QC_HIP(launch_ddim_vc(x_ref, ctx->eps_ref, B, C, HW, (float)cx, (float)ce, cfg_scale, nullptr, st));
+    QC_HIP(launch_ddim_vc(x_ref, ctx->eps_ref, B, C, HW, cx, ce, cfg_scale, nullptr, st));
     // accelerated: quantised network under the cache rule, VC with the factor fitted at this very step
     const int mode = step_mode(ctx, i, -1);
     const unsigned char *sched = step_sched(ctx, i, -1);
@@ -1080,7 +1080,7 @@ int qc_vc_fit_sampler(qc_ctx *ctx, const qc_weights_f32 *w, float *x_hat, float 
     if (rc) return rc;
     rc = denoise_impl(ctx, x_hat, B, Beff, mode, 0, ctx->eps, st, sched);
     if (rc) return rc;
-    QC_HIP(launch_ddim_vc(x_hat, ctx->eps, B, C, HW, (float)cx, (float)ce, cfg_scale, nullptr, st));
+    QC_HIP(launch_ddim_vc(x_hat, ctx->eps, B, C, HW, cx, ce, cfg_scale, nullptr, st));
     float *K_i = K_out + (size_t)i * C;
     QC_HIP(launch_vc_fit(x_hat, x_ref, B, C, HW, vc_eps, ctx->vcfit_work, K_i, st));
     QC_HIP(launch_vc(x_hat, K_i, nullptr, B, C, HW, st));

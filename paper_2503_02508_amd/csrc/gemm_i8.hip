@@ -40,6 +40,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 
 
 constexpr int NUM_XCD = 8;
+constexpr int GELU_FIX_CAP = 1024;      // queue of fc1 outputs decided again in float64, per tile
 
 __device__ __forceinline__ int map_col(int j, int sel_D) {
   return sel_D ? (j < sel_D ? j + 2 * sel_D : j + 4 * sel_D) : j;
@@ -76,6 +77,24 @@ __device__ __forceinline__ unsigned short bf16_bits(float v) {
   unsigned u = __builtin_bit_cast(unsigned, v);
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (unsigned short)(u >> 16);
+}
+
+// Dequantised output of a quantised linear as it is stored: the float32 rounding of the float64 value
+// (a_s * w_s[n]) * (acc - a_z * wsum[n]) + bias[n] (the product of the two scales is exact in float64; one float64
+// multiplication, one float64 addition, one rounding to float32).  Stored tensors then carry no rounding of their own
+// beyond the storage format, so the codes quantised from them further down do not depend on the order of operations here.
+__device__ __forceinline__ float dequant_f32(double sc, int corr, double bs) {
+  return (float)__dadd_rn(__dmul_rn(sc, (double)corr), bs);
+}
+
+// The fc1 epilogue's exact path for one output element: float64 from the integer accumulator to the GELU value, one
+// rounding to float32, Eq. 1 with an IEEE division.  x / (1 + exp(-2u)) = 0.5 x (1 + tanh u).
+__device__ __noinline__ int gelu_code_exact(int corr, float a_s, float w_s, float bias, float o_s, int o_z) {
+  const double u = __dadd_rn(__dmul_rn((double)a_s * (double)w_s, (double)corr), (double)bias);
+  const double k = 0.7978845608028654 * (u + 0.044715 * u * u * u);
+  const float g = (float)(u / (1.0 + exp(-2.0 * k)));
+  const float r = __builtin_rintf(g / o_s) + (float)o_z;
+  return (int)fminf(fmaxf(r, -128.0f), 127.0f);
 }
 
 // Eq. 1 on signed codes with the quotient v / s refined to the correctly rounded
@@ -370,6 +389,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     float *c_bs = (float *)(smem + BN * 8);
     unsigned char *stage = smem + BN * 12;             // [BM][BN + 16] codes
     constexpr int SROW = BN + 16;
+    // Elements whose fast evaluation lands too close to a rounding boundary of Eq. 1 to be trusted are queued here and
+    // decided again in float64 (gelu_code_exact): the codes are then those of exact arithmetic on the accumulators.
+    int *fix_cnt = (int *)(stage + BM * SROW);
+    int *fix_ent = fix_cnt + 4;                        // [GELU_FIX_CAP][4]: accumulator minus zero-point term, column, row
+    if (tid == 0) *fix_cnt = 0;
     if (tid < BN) {
       const int n = n0 + tid;
       const bool ok = n < p.N;
@@ -380,6 +404,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     __syncthreads();
     const QParam oq = *p.o_qp;
     const float o_s = oq.s, o_inv = 1.0f / oq.s, o_z = (float)oq.z;
+    // bound of the fast path's error in units of the output step: 1.5e-6 |v| / s covers the float32 dequantisation, the
+    // exp2 / reciprocal estimates and the refined quotient with a margin of 2; 2e-6 covers the bias rounding
+    const float tol_v = 1.5e-6f * o_inv;
     const int g = lane >> 5;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -394,8 +421,21 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
           int code[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float v = fmaf(sc[e], (float)(acc[i][j][rg * 4 + e] - zw[e]), bs[e]);
-            code[e] = quant_code(gelu_tanh(v), o_s, o_inv, o_z);
+            const int corr = acc[i][j][rg * 4 + e] - zw[e];
+            const float v = fmaf(sc[e], (float)corr, bs[e]);
+            const float gv = gelu_tanh(v);
+            float q = gv * o_inv;
+            q = fmaf(fmaf(-q, o_s, gv), o_inv, q);
+            const float r = __builtin_rintf(q);
+            code[e] = (int)fminf(fmaxf(r + o_z, -128.0f), 127.0f);
+            if (fabsf(fabsf(q - r) - 0.5f) < fmaf(tol_v, fabsf(v), 2e-6f)) {
+              const int slot = atomicAdd(fix_cnt, 1);
+              if (slot < GELU_FIX_CAP) {
+                fix_ent[slot * 4 + 0] = corr;
+                fix_ent[slot * 4 + 1] = nl + e;
+                fix_ent[slot * 4 + 2] = wm0 + i * 32 + (lane & 31);
+              }
+            }
           }
           const unsigned w = (unsigned)(code[0] & 0xFF) | ((unsigned)(code[1] & 0xFF) << 8) |
                              ((unsigned)(code[2] & 0xFF) << 16) | ((unsigned)(code[3] & 0xFF) << 24);
@@ -404,6 +444,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
       }
     }
     __syncthreads();
+    {
+      const int nfix = min(*fix_cnt, GELU_FIX_CAP);
+      for (int f = tid; f < nfix; f += NT) {
+        const int corr = fix_ent[f * 4 + 0], nl = fix_ent[f * 4 + 1], row = fix_ent[f * 4 + 2];
+        const int n = n0 + nl;
+        if (n < p.N) stage[row * SROW + nl] = (unsigned char)gelu_code_exact(corr, a_s, w_scale[n], bias ? bias[n] : 0.0f, o_s, oq.z);
+      }
+      if (nfix) __syncthreads();
+    }
     // coalesced write-out: 16-byte chunks, 8 lanes cover a 128-byte row segment
     constexpr int CH = BN / 16;
     for (int c = tid; c < BM * CH; c += NT) {
@@ -442,15 +491,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int nl = wn0 + j * 32 + (lane & 31);
-          const float sc = a_s * w_scale[n0 + nl];
+          const double sc = (double)a_s * (double)w_scale[n0 + nl];
           const int zw = a_z * wsum[n0 + nl];
-          const float bs = bias ? bias[n0 + nl] : 0.0f;
+          const double bs = bias ? (double)bias[n0 + nl] : 0.0;
 #pragma unroll
           for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int ml = wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-              const float v = fmaf(sc, (float)(acc[i][j][r] - zw), bs) * mul;
+              const float v = dequant_f32(sc, acc[i][j][r] - zw, bs) * mul;
               const _Float16 hi = (_Float16)v, lo = (_Float16)(v - (float)hi);
               stage[ml * SR + nl] =
                   (unsigned)__builtin_bit_cast(unsigned short, hi) | ((unsigned)__builtin_bit_cast(unsigned short, lo) << 16);
@@ -473,9 +522,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const int nl = wn0 + j * 32 + (lane & 31);
-          const float sc = a_s * w_scale[n0 + nl];
+          const double sc = (double)a_s * (double)w_scale[n0 + nl];
           const int zw = a_z * wsum[n0 + nl];
-          const float bs = bias ? bias[n0 + nl] : 0.0f;
+          const double bs = bias ? (double)bias[n0 + nl] : 0.0;
 #pragma unroll
           for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -483,7 +532,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
               h4 hi, lo;
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
-                const float v = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs);
+                const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
                 hi[q] = (_Float16)v;
                 lo[q] = (_Float16)(v - (float)hi[q]);
               }
@@ -511,9 +560,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     for (int j = 0; j < TN; ++j) {
       const int n = n0 + wn0 + j * 32 + (lane & 31);
       if (n >= p.N) continue;
-      const float sc = a_s * w_scale[n];
+      const double sc = (double)a_s * (double)w_scale[n];
       const int zw = a_z * wsum[n];
-      const float bs = bias ? bias[n] : 0.0f;
+      const double bs = bias ? (double)bias[n] : 0.0;
       const int part = n / D, nn = n - part * D, h = nn / p.hd, e = nn - h * p.hd;
       const float mul = part == 0 ? p.q_scale : 1.0f;
       unsigned *dpair = part == 0 ? p.q_words : p.k_words;   // Q / K: one (hi | lo << 16) word per element
@@ -531,7 +580,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
               h4 hi, lo;
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
-                const float v = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs);
+                const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
                 hi[q] = (_Float16)v;
                 lo[q] = (_Float16)(v - (float)hi[q]);
               }
@@ -547,7 +596,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
             for (int rg = 0; rg < 4; ++rg)
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
-                const float v = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs) * mul;
+                const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs) * mul;
                 const _Float16 hi = (_Float16)v, lo = (_Float16)(v - (float)hi);
                 dst[(unsigned)(i * 32 + rg * 8 + q) * (unsigned)p.hd] =
                     (unsigned)__builtin_bit_cast(unsigned short, hi) | ((unsigned)__builtin_bit_cast(unsigned short, lo) << 16);
@@ -564,7 +613,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
           _Float16 hi[4], lo[4];
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            const float v = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs) * mul;
+            const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs) * mul;
             hi[q] = (_Float16)v;
             lo[q] = (_Float16)(v - (float)hi[q]);
           }
@@ -595,7 +644,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
           if (p.y) {   // optional fp32 copy for inspection
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-              if (mb + q < p.M) p.y[(long long)(mb + q) * p.ldy + n] = fmaf(sc, (float)(acc[i][j][rg * 4 + q] - zw), bs);
+              if (mb + q < p.M) p.y[(long long)(mb + q) * p.ldy + n] = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
           }
         }
       }
@@ -615,7 +664,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     for (int j0 = 0; j0 < TN; j0 += JB)
 #pragma unroll
       for (int i0 = 0; i0 < TM; i0 += IB) {
-        float xv[JB][IB][16], gv[JB], scv[JB], bsv[JB];
+        float xv[JB][IB][16], gv[JB];
+        double scv[JB], bsv[JB];
         int zwv[JB];
 #pragma unroll
         for (int jj = 0; jj < JB; ++jj) {
@@ -627,9 +677,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
               const int m = min(m0 + wm0 + (i0 + ii) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), p.M - 1);
               xv[jj][ii][r] = p.x[(long long)m * p.N + n];
             }
-          scv[jj] = a_s * w_scale[n];
+          scv[jj] = (double)a_s * (double)w_scale[n];
           zwv[jj] = a_z * wsum[n];
-          bsv[jj] = bias ? bias[n] : 0.0f;
+          bsv[jj] = bias ? (double)bias[n] : 0.0;
           gv[jj] = p.gate[(long long)b_uniform * p.ld_gate + n];
         }
 #pragma unroll
@@ -644,11 +694,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
               for (int r = 0; r < 16; ++r) {
                 const int i = i0 + ii;
                 const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                const float v = fmaf(scv[jj], (float)(acc[i][j][r] - zwv[jj]), bsv[jj]);
+                const float v = dequant_f32(scv[jj], acc[i][j][r] - zwv[jj], bsv[jj]);
                 const long long o = (long long)m * p.N + n;
                 if (p.cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
                 else ((float *)p.cache_out)[o] = v;
-                p.x[o] = xv[jj][ii][r] + gv[jj] * v;
+                p.x[o] = fmaf(gv[jj], v, xv[jj][ii][r]);
               }
           } else {
             if (n >= p.N) continue;
@@ -659,12 +709,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
                 const int i = i0 + ii;
                 const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 if (m >= p.M) continue;
-                const float v = fmaf(scv[jj], (float)(acc[i][j][r] - zwv[jj]), bsv[jj]);
+                const float v = dequant_f32(scv[jj], acc[i][j][r] - zwv[jj], bsv[jj]);
                 const long long o = (long long)m * p.N + n;
                 if (p.cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
                 else ((float *)p.cache_out)[o] = v;
                 const float g = p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
-                p.x[o] = xv[jj][ii][r] + g * v;
+                p.x[o] = fmaf(g, v, xv[jj][ii][r]);
               }
           }
         }
@@ -677,9 +727,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     const int jl = n0 + wn0 + j * 32 + (lane & 31);
     if (jl >= ncover) continue;
     const int n = map_col(jl, p.sel_D);
-    const float sc = a_s * w_scale[n];
+    const double sc = (double)a_s * (double)w_scale[n];
     const int zw = a_z * wsum[n];
-    const float bs = bias ? bias[n] : 0.0f;
+    const double bs = bias ? (double)bias[n] : 0.0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -688,7 +738,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
         if (m >= p.M) continue;
         const int a = acc[i][j][r];
         float *y = p.y + (long long)z * p.zs_out;
-        y[(long long)m * p.ldy + n] = fmaf(sc, (float)(a - zw), bs);
+        y[(long long)m * p.ldy + n] = dequant_f32(sc, a - zw, bs);
         if (p.acc_out) p.acc_out[(long long)m * p.N + n] = a;
       }
     }
@@ -698,7 +748,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK = 128>
 static hipError_t launch_cfg(const GemmArgs &a, int nz, hipStream_t st) {
   constexpr int smem_loop = 2 * (BM + BN) * (BK + 16);
-  constexpr int smem_epi = BN * 12 + BM * (BN + 16);
+  constexpr int smem_epi = BN * 12 + BM * (BN + 16) + 16 + GELU_FIX_CAP * 16;
   constexpr int smem = smem_loop > smem_epi ? smem_loop : smem_epi;
   static bool attr_set = false;
   auto kern = gemm_i8_kernel<BM, BN, WM, WN, EPI, TAG, W4, PF, BK>;

@@ -105,7 +105,7 @@ hipError_t launch_cache_reuse(float *x, const void *cached, const float *gate, i
 hipError_t launch_cached_blocks(float *x, const void *cache, size_t cache_block_stride, size_t cache_which_stride,
                                 const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D, bool bf16,
                                 hipStream_t st);
-hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, float cx, float ce, float cfg_scale,
+hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, double cx, double ce, float cfg_scale,
                           const float *K_t, hipStream_t st);
 hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, int HW, hipStream_t st);
 hipError_t launch_vc_fit(const float *x_hat, const float *x_ref, int B, int C, int HW, float eps, double *work, float *K_t,

@@ -179,8 +179,12 @@ hipError_t launch_ln_mod_quant(const float *x, const float *shift, const float *
   return hipGetLastError();
 }
 
-// ------------------------------------------------- small fp32 linear (M = B)
-// y[b, n] = act_out(W[n, :] . act_in(x[b, :]) + bias[n]); one wavefront per n.
+// ------------------------------------------------- small linear (few rows)
+// y[b, n] = act_out(W[n, :] . act_in(x[b, :]) + bias[n]); one wavefront per n.  Inputs and outputs are float32 tensors;
+// the arithmetic in between is float64 and the result is rounded once, so that what is stored does not depend on the
+// summation order (conditioning vectors feed quantisers, where a last-bit difference can move a code).
+__device__ __forceinline__ double silu_d(double x) { return x / (1.0 + exp(-x)); }
+
 __global__ __launch_bounds__(256) void small_linear_kernel(const float *__restrict__ x, int ldx, const float *__restrict__ W,
                                                            const float *__restrict__ bias, float *__restrict__ y, int ldy,
                                                            int B, int N, int K, int act_in, int act_out) {
@@ -189,26 +193,26 @@ __global__ __launch_bounds__(256) void small_linear_kernel(const float *__restri
   if (n >= N) return;
   const float *wr = W + (size_t)n * K;
   for (int b0 = 0; b0 < B; b0 += 8) {
-    float acc[8];
+    double acc[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+    for (int i = 0; i < 8; ++i) acc[i] = 0.0;
     for (int k = lane; k < K; k += 64) {
-      const float wv = wr[k];
+      const double wv = (double)wr[k];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         if (b0 + i < B) {
-          float xv = x[(size_t)(b0 + i) * ldx + k];
-          if (act_in == 1) xv = silu_f(xv);
-          acc[i] = fmaf(wv, xv, acc[i]);
+          double xv = (double)x[(size_t)(b0 + i) * ldx + k];
+          if (act_in == 1) xv = silu_d(xv);
+          acc[i] = fma(wv, xv, acc[i]);
         }
       }
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       if (b0 + i < B) {
-        float r = wave_sum(acc[i]) + (bias ? bias[n] : 0.0f);
-        if (act_out == 1) r = silu_f(r);
-        if (lane == 0) y[(size_t)(b0 + i) * ldy + n] = r;
+        double r = wave_sum_d(acc[i]) + (bias ? (double)bias[n] : 0.0);
+        if (act_out == 1) r = silu_d(r);
+        if (lane == 0) y[(size_t)(b0 + i) * ldy + n] = (float)r;
       }
     }
   }
@@ -262,7 +266,7 @@ __global__ void silu_quant_kernel(const float *__restrict__ c, int BD, int L, co
                                   int8_t *__restrict__ q, size_t l_stride) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= BD) return;
-  const float v = silu_f(c[i]);
+  const float v = (float)silu_d((double)c[i]);      // float64 value rounded once, then Eq. 1
   for (int l = 0; l < L; ++l) {
     QParam t = qp[(size_t)l * qp_stride];
     q[(size_t)l * l_stride + i] = (int8_t)quant_code(v, t.s, t.z);
@@ -293,11 +297,10 @@ __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x,
   }
   __syncthreads();
   for (int n = threadIdx.x; n < D; n += blockDim.x) {
-    float acc = 0.0f;
-    const float bias = pb[n], pe = pos[(size_t)t * D + n];
+    // float64 dot product, rounded once when the token is stored
+    double acc = 0.0;
+    const float *wr = pw + (size_t)n * F;
     if (F % 4 == 0) {
-      // sixteen weights per round trip; the sum keeps the feature order
-      const float *wr = pw + (size_t)n * F;
       for (int f0 = 0; f0 < F; f0 += 16) {
         float4 w4[4];
 #pragma unroll
@@ -306,17 +309,17 @@ __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x,
         for (int u = 0; u < 4; ++u) {
           const int f = f0 + 4 * u;
           if (f < F) {
-            acc = fmaf(w4[u].x, patch[f], acc);
-            acc = fmaf(w4[u].y, patch[f + 1], acc);
-            acc = fmaf(w4[u].z, patch[f + 2], acc);
-            acc = fmaf(w4[u].w, patch[f + 3], acc);
+            acc = fma((double)w4[u].x, (double)patch[f], acc);
+            acc = fma((double)w4[u].y, (double)patch[f + 1], acc);
+            acc = fma((double)w4[u].z, (double)patch[f + 2], acc);
+            acc = fma((double)w4[u].w, (double)patch[f + 3], acc);
           }
         }
       }
     } else {
-      for (int f = 0; f < F; ++f) acc = fmaf(pw[(size_t)n * F + f], patch[f], acc);
+      for (int f = 0; f < F; ++f) acc = fma((double)wr[f], (double)patch[f], acc);
     }
-    tok[(size_t)bt * D + n] = acc + bias + pe;
+    tok[(size_t)bt * D + n] = (float)((acc + (double)pb[n]) + (double)pos[(size_t)t * D + n]);
   }
 }
 
@@ -352,45 +355,47 @@ __global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ to
     s4[it] = *(const float4 *)(sh + kk[it]);
     c4[it] = *(const float4 *)(sc + kk[it]);
   }
-  float sum = 0.0f;
+  // float64 throughout (the noise estimate is rounded once, when it is stored)
+  double sum = 0.0;
 #pragma unroll
   for (int it = 0; it < LN_MAX_IT; ++it)
-    if ((lane + 64 * it) * 4 < D) sum += (v[it].x + v[it].y) + (v[it].z + v[it].w);
-  const float mean = wave_sum(sum) / (float)D;
-  float sq = 0.0f;
+    if ((lane + 64 * it) * 4 < D) sum += ((double)v[it].x + (double)v[it].y) + ((double)v[it].z + (double)v[it].w);
+  const double mean = wave_sum_d(sum) / (double)D;
+  double sq = 0.0;
 #pragma unroll
   for (int it = 0; it < LN_MAX_IT; ++it)
     if ((lane + 64 * it) * 4 < D) {
-      float a = v[it].x - mean, bq = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
+      const double a = v[it].x - mean, bq = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
       sq += (a * a + bq * bq) + (c * c + d * d);
     }
-  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + 1e-6f);
+  const double rstd = 1.0 / sqrt(wave_sum_d(sq) / (double)D + 1e-6);
+  double h[LN_MAX_IT][4];
 #pragma unroll
   for (int it = 0; it < LN_MAX_IT; ++it) {
     if ((lane + 64 * it) * 4 < D) {
-      v[it].x = (v[it].x - mean) * rstd * (1.0f + c4[it].x) + s4[it].x;
-      v[it].y = (v[it].y - mean) * rstd * (1.0f + c4[it].y) + s4[it].y;
-      v[it].z = (v[it].z - mean) * rstd * (1.0f + c4[it].z) + s4[it].z;
-      v[it].w = (v[it].w - mean) * rstd * (1.0f + c4[it].w) + s4[it].w;
+      h[it][0] = (v[it].x - mean) * rstd * (1.0 + (double)c4[it].x) + (double)s4[it].x;
+      h[it][1] = (v[it].y - mean) * rstd * (1.0 + (double)c4[it].y) + (double)s4[it].y;
+      h[it][2] = (v[it].z - mean) * rstd * (1.0 + (double)c4[it].z) + (double)s4[it].z;
+      h[it][3] = (v[it].w - mean) * rstd * (1.0 + (double)c4[it].w) + (double)s4[it].w;
     } else {
-      v[it] = make_float4(0.f, 0.f, 0.f, 0.f);      // contributes nothing to the dot products below
+      h[it][0] = h[it][1] = h[it][2] = h[it][3] = 0.0;      // contributes nothing to the dot products below
     }
   }
   // the p*p*C dot products of this row, 16 at a time: per-lane partial sums, then a butterfly that halves
   // the number of live values with every exchange (17 shuffles for 16 sums instead of 6 each)
   const int n_out = p * p * C;
   for (int o0 = 0; o0 < n_out; o0 += 16) {
-    float part[16];
+    double part[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
-      part[u] = 0.0f;
+      part[u] = 0.0;
       const int oi = o0 + u;
       if (oi < n_out) {
         const float *wr = fw + (size_t)((oi / C) * 2 * C + oi % C) * D;
 #pragma unroll
         for (int it = 0; it < LN_MAX_IT; ++it) {
           const float4 w4 = *(const float4 *)(wr + kk[it]);
-          part[u] += (v[it].x * w4.x + v[it].y * w4.y) + (v[it].z * w4.z + v[it].w * w4.w);
+          part[u] += (h[it][0] * (double)w4.x + h[it][1] * (double)w4.y) + (h[it][2] * (double)w4.z + h[it][3] * (double)w4.w);
         }
       }
     }
@@ -402,19 +407,19 @@ __global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ to
       const bool upper = (lane & dist) != 0;
 #pragma unroll
       for (int u = 0; u < half; ++u) {
-        const float keep = upper ? part[u + half] : part[u];
-        const float send = upper ? part[u] : part[u + half];
+        const double keep = upper ? part[u + half] : part[u];
+        const double send = upper ? part[u] : part[u + half];
         part[u] = keep + __shfl_xor(send, dist, 64);
       }
     }
-    float r = part[0];
+    double r = part[0];
     r += __shfl_xor(r, 2, 64);
     r += __shfl_xor(r, 1, 64);
     const int u_mine = ((lane >> 5) & 1) * 8 + ((lane >> 4) & 1) * 4 + ((lane >> 3) & 1) * 2 + ((lane >> 2) & 1);
     const int oi = o0 + u_mine;
     if ((lane & 3) == 0 && oi < n_out) {
       const int pp = oi / C, c = oi % C;
-      eps[(((size_t)b * C + c) * H + ty * p + pp / p) * W + tx * p + pp % p] = r + fb[pp * 2 * C + c];
+      eps[(((size_t)b * C + c) * H + ty * p + pp / p) * W + tx * p + pp % p] = (float)(r + (double)fb[pp * 2 * C + c]);
     }
   }
 }
@@ -567,35 +572,47 @@ __device__ __forceinline__ float block_sum_256(float v, float *red) {
 
 // One workgroup per (latent, channel) plane.  xhat = cx*x + ce*eps is DDIM with
 // eta = 0 (cx = sqrt(abar_prev/abar_t), ce = sqrt(1-abar_prev) - cx*sqrt(1-abar_t));
-// then Eq. 10 with mu = plane mean: x~ = xhat + (K-1)(xhat - mu).
+// then Eq. 10 with mu = plane mean: x~ = xhat + (K-1)(xhat - mu).  Both the updated sample and the corrected sample are
+// stored float32 tensors; guidance + solver update, and VC, are each evaluated in float64 from the stored tensors they
+// read and rounded once (the same values the separate DDIM, fit and VC launches of the factor fitting produce).
+__device__ __forceinline__ double block_sum_256d(double v, double *red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();                       // red may still be read from the previous use
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 __global__ __launch_bounds__(256) void ddim_vc_kernel(float *__restrict__ x, const float *__restrict__ eps, int B, int C,
-                                                      int HW, float cx, float ce, float cfg, const float *__restrict__ K_t) {
-  __shared__ float red[4];
+                                                      int HW, double cx, double ce, float cfg, const float *__restrict__ K_t) {
+  __shared__ double red[4];
   const int plane = blockIdx.x, c = plane % C;
   float *xp = x + (size_t)plane * HW;
   const float *ec = eps + (size_t)plane * HW;
   const float *eu = eps + ((size_t)B * C + plane) * HW;
-  float sum = 0.0f;
+  const double w = (double)cfg;
+  double sum = 0.0;
   for (int i = threadIdx.x; i < HW; i += 256) {
-    float e = ec[i];
+    double e = (double)ec[i];
     if (cfg > 0.0f) {
-      const float u = eu[i];
-      e = u + cfg * (e - u);
+      const double u = (double)eu[i];
+      e = u + w * (e - u);
     }
-    const float xh = cx * xp[i] + ce * e;
+    const float xh = (float)(cx * (double)xp[i] + ce * e);
     xp[i] = xh;
-    sum += xh;
+    sum += (double)xh;
   }
   if (!K_t) return;
-  const float mu = block_sum_256(sum, red) / (float)HW;
-  const float km1 = K_t[c] - 1.0f;
-  for (int i = threadIdx.x; i < HW; i += 256) {
-    const float xh = xp[i];
-    xp[i] = xh + km1 * (xh - mu);
+  const double mu = block_sum_256d(sum, red) / (double)HW;
+  const double km1 = (double)K_t[c] - 1.0;
+  for (int i = threadIdx.x; i < HW; i += 256) {          // a thread re-reads only what it wrote itself
+    const double xh = (double)xp[i];
+    xp[i] = (float)(xh + km1 * (xh - mu));
   }
 }
 
-hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, float cx, float ce, float cfg_scale,
+hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, double cx, double ce, float cfg_scale,
                           const float *K_t, hipStream_t st) {
   hipLaunchKernelGGL(ddim_vc_kernel, dim3(B * C), dim3(256), 0, st, x, eps, B, C, HW, cx, ce, cfg_scale, K_t);
   return hipGetLastError();
@@ -603,21 +620,21 @@ hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, floa
 
 __global__ __launch_bounds__(256) void vc_kernel(float *__restrict__ x, const float *__restrict__ K_t,
                                                  const float *__restrict__ mu_in, int C, int HW) {
-  __shared__ float red[4];
+  __shared__ double red[4];
   const int plane = blockIdx.x, c = plane % C;
   float *xp = x + (size_t)plane * HW;
-  float mu;
+  double mu;
   if (mu_in) {
-    mu = mu_in[c];
+    mu = (double)mu_in[c];
   } else {
-    float sum = 0.0f;
-    for (int i = threadIdx.x; i < HW; i += 256) sum += xp[i];
-    mu = block_sum_256(sum, red) / (float)HW;
+    double sum = 0.0;
+    for (int i = threadIdx.x; i < HW; i += 256) sum += (double)xp[i];
+    mu = block_sum_256d(sum, red) / (double)HW;
   }
-  const float km1 = K_t[c] - 1.0f;
+  const double km1 = (double)K_t[c] - 1.0;
   for (int i = threadIdx.x; i < HW; i += 256) {
-    const float v = xp[i];
-    xp[i] = v + km1 * (v - mu);
+    const double v = (double)xp[i];
+    xp[i] = (float)(v + km1 * (v - mu));
   }
 }
 
@@ -633,15 +650,6 @@ hipError_t launch_vc(float *x, const float *K_t, const float *mu, int B, int C, 
 // S2 = sum d^2 w, d = x^ - mu, w = 1 + 1 / (x'^2 + eps), mu = spatial mean of the x^ plane.
 // One workgroup per (sample, channel) plane writes its two partial sums (fp64); a second, tiny kernel adds the
 // planes of a channel in a fixed order, so the result does not depend on scheduling.
-__device__ __forceinline__ double block_sum_256d(double v, double *red) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  __syncthreads();                       // red may still be read from the previous use
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return (red[0] + red[1]) + (red[2] + red[3]);
-}
-
 __global__ __launch_bounds__(256) void vc_fit_sums_kernel(const float *__restrict__ x_hat, const float *__restrict__ x_ref,
                                                           int HW, double eps, double *__restrict__ part) {
   __shared__ double red[4];

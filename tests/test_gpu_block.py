@@ -25,13 +25,15 @@ WIDEST = I.ModelDesc(depth=1, hidden=2048, heads=32, mlp_dim=2304, patch=1, late
                      num_classes=5)
 HEAD80 = I.ModelDesc(depth=1, hidden=320, heads=4, mlp_dim=640, patch=2, latent_c=4, latent_h=12, latent_w=10,
                      num_classes=5)
-MAX_FLIP_FRACTION = 1e-2
-# Module outputs inside a block (the cached tensors) sit behind one or two more
-# quantisers than the block input; a flipped code upstream shifts a whole row of
-# the next linear's output and flips more codes there, so their error is a
-# multiple of the block output's.  They get a looser bar; the block output, the
-# noise estimate and the latents get the task's bar.
-INNER_MAX_ABS, INNER_REL_RMS = 5e-2, 5e-3
+# Every stored tensor is the float32 rounding of an exactly evaluated value and every quantiser but the attention
+# kernel's decides as the oracle does (tests/test_gpu_quantisers.py), so codes differ only where an attention output
+# sits within the kernel's fp16-pair / fp32 error of a rounding boundary (a few 1e-6 of them) and in what such a code
+# then moves downstream: one such code shifts a row of the projection output, the LayerNorm codes of that row follow
+# and with them a row of fc1 / fc2 outputs.  The block output, the noise estimate and the samples are held to the task's
+# bar; the module outputs inside the network (the cached tensors), where such a row is not diluted by the residual
+# stream, are held to 3e-2 / 2.5e-3 (measured worst case 1.7e-2 / 1.2e-3, bit-equal where no attention code differs).
+MAX_FLIP_FRACTION = 1e-3
+INNER_MAX_ABS, INNER_REL_RMS = 3e-2, 2.5e-3
 
 
 def _cuda(a, dtype=None):
@@ -288,7 +290,7 @@ def test_sampler_free_running_whole_loop_via_qc_sample():
     got = xd.cpu().numpy()
     ma, rr = max_abs(got, want), rel_rms(got, want)
     print("free-running tiny: max-abs %.2e rel-RMS %.2e (|x| rms %.2f)" % (ma, rr, np.sqrt(np.mean(want ** 2))))
-    assert rr <= 1e-3
+    assert rr <= 1e-3 and ma <= 1e-2
     ctx.close()
 
 

@@ -15,6 +15,13 @@ TINY = I.ModelDesc(depth=2, hidden=32, heads=2, mlp_dim=64, patch=2, latent_c=4,
                    num_classes=10)
 
 
+@pytest.fixture
+def exact_storage():
+    """The formulas against library routines: stored tensors keep float64 (no rounding to the float32 storage format)."""
+    with dit.storage("f64"):
+        yield
+
+
 def _tiny_setup(seed=0, std=0.2):
     w = I.make_weights(TINY, seed, std=std)
     lat = I.make_latents(3, TINY, seed + 1)
@@ -106,7 +113,7 @@ class _TorchBlock:
         return (x + gl.unsqueeze(1) * m).numpy()
 
 
-def test_fp_block_vs_torch_library_block():
+def test_fp_block_vs_torch_library_block(exact_storage):
     w, _, _ = _tiny_setup()
     rng = np.random.default_rng(4)
     x = rng.standard_normal((2, TINY.tokens, TINY.hidden))
@@ -121,7 +128,7 @@ def _qparams_for(w, x_lat, lab, t):
     return qp, ranges
 
 
-def test_quantised_block_close_to_fp_and_converges_with_bits():
+def test_quantised_block_close_to_fp_and_converges_with_bits(exact_storage):
     w, lat, lab = _tiny_setup()
     t = np.array([500, 500, 500])
     qp8, ranges = _qparams_for(w, lat, lab, t)
@@ -159,7 +166,7 @@ def test_block_is_identity_when_gates_are_zero():
     bw["ada_w"][2 * D:3 * D] = 0; bw["ada_b"][2 * D:3 * D] = 0      # gate_msa
     bw["ada_w"][5 * D:6 * D] = 0; bw["ada_b"][5 * D:6 * D] = 0      # gate_mlp
     rng = np.random.default_rng(5)
-    x = rng.standard_normal((2, TINY.tokens, D)); c = rng.standard_normal((2, D))
+    x = dit.st(rng.standard_normal((2, TINY.tokens, D))); c = rng.standard_normal((2, D))      # a stored (float32) stream
     qp = {(0, s): quant.act_qparams(-4, 4) for s in dit.SITES}
     out = dit.block_full(x, c, 0, TINY.heads, dit.QLinears(w, qp))
     assert np.array_equal(out, x)
@@ -327,7 +334,7 @@ def test_vc_matches_gaussian_rescale_statistically():
     assert abs(y.std() - 0.5) < 5e-3 and abs(y.mean() - 1.5) < 2e-2
 
 
-def test_guidance_step_uses_null_label_for_second_half():
+def test_guidance_step_uses_null_label_for_second_half(exact_storage):
     w, lat, lab = _tiny_setup()
     qp, _ = _qparams_for(w, lat, lab, np.array([500, 500, 500]))
     lin = dit.QLinears(w, qp)
@@ -394,7 +401,7 @@ class _TorchDiT:
         return self.final(h, c).numpy(), sites
 
 
-def test_conditioning_vs_torch_library():
+def test_conditioning_vs_torch_library(exact_storage):
     w, _, _ = _tiny_setup()
     t = np.array([0, 37, 999]); y = np.array([3, 0, TINY.num_classes])          # last row of the table = null label
     got = dit.conditioning(t, y, w)
@@ -409,7 +416,7 @@ def test_conditioning_vs_torch_library():
     assert np.allclose(dit.conditioning(t, y, w2), w["t_b2"].astype(np.float64) + w["label_table"][y])
 
 
-def test_embed_vs_conv2d_patch_embedding():
+def test_embed_vs_conv2d_patch_embedding(exact_storage):
     w, lat, _ = _tiny_setup()
     got = dit.embed(lat, w, TINY.patch)
     want = _TorchDiT(w, TINY).embed(lat).numpy()
@@ -425,7 +432,7 @@ def test_embed_vs_conv2d_patch_embedding():
     assert np.allclose(d[0, 1 * gw + 3], col) and np.count_nonzero(np.abs(d).sum(-1)) == 1
 
 
-def test_final_layer_vs_torch_library_and_closed_forms():
+def test_final_layer_vs_torch_library_and_closed_forms(exact_storage):
     w, _, _ = _tiny_setup()
     rng = np.random.default_rng(12)
     x = rng.standard_normal((2, TINY.tokens, TINY.hidden)); c = rng.standard_normal((2, TINY.hidden))
@@ -449,7 +456,7 @@ def test_final_layer_vs_torch_library_and_closed_forms():
     assert np.allclose(e1[0, 2, 4, 5], feat[((4 % p) * p + (5 % p)) * 2 * C + 2])
 
 
-def test_fp_denoiser_vs_torch_library_network():
+def test_fp_denoiser_vs_torch_library_network(exact_storage):
     w, lat, lab = _tiny_setup()
     t = np.array([500, 20, 980])
     got = dit.denoiser(lat, t, lab, TINY, w, dit.FPLinears(w), {}, True)
@@ -457,7 +464,7 @@ def test_fp_denoiser_vs_torch_library_network():
     assert np.allclose(got, want, rtol=1e-9, atol=1e-11)
 
 
-def test_calibration_ranges_are_site_inputs_over_all_calibration_data():
+def test_calibration_ranges_are_site_inputs_over_all_calibration_data(exact_storage):
     """Eq. 2 on calibration data: for every (block, site) the range is the min / max of that linear's INPUT, taken
     over all calibration samples together; Eq. 3 then gives (s, z).  The inputs come from the torch-library network."""
     w, lat, lab = _tiny_setup()
@@ -482,7 +489,7 @@ def test_calibration_ranges_are_site_inputs_over_all_calibration_data():
     assert any(r1[k] != ranges[k] for k in ranges)
 
 
-def test_calibrate_block_ranges_vs_torch_block_inputs():
+def test_calibrate_block_ranges_vs_torch_block_inputs(exact_storage):
     w, _, _ = _tiny_setup()
     rng = np.random.default_rng(13)
     tok = rng.standard_normal((3, TINY.tokens, TINY.hidden)); cond = rng.standard_normal((3, TINY.hidden))
@@ -502,3 +509,30 @@ def test_calibrate_block_ranges_vs_torch_block_inputs():
     for site, v in want.items():
         assert np.allclose(ranges[(0, site)], (float(v.min()), float(v.max())), rtol=1e-9, atol=1e-12)
         assert qp[(0, site)][1] == quant.act_qparams(float(v.min()), float(v.max()))[1]
+
+
+def test_storage_format_rounds_the_stored_tensors_only():
+    """Default storage: every tensor kept between two operations is a float32 value, and the result stays within
+    float32 rounding of the pure-float64 evaluation of the same formulas."""
+    w, lat, lab = _tiny_setup()
+    t = np.array([500, 20, 980])
+    with dit.storage("f64"):
+        c64 = dit.conditioning(t, lab, w); e64 = dit.embed(lat, w, TINY.patch)
+        fp64 = dit.denoiser(lat, t, lab, TINY, w, dit.FPLinears(w), {}, True)
+    c32 = dit.conditioning(t, lab, w); e32 = dit.embed(lat, w, TINY.patch)
+    cache, taps = {}, []
+    qp, _ = sampler.calibrate(TINY, w, lat, lab, t)
+    fp32 = dit.denoiser(lat, t, lab, TINY, w, dit.FPLinears(w), {}, True)
+    dit.denoiser(lat, t, lab, TINY, w, dit.QLinears(w, qp), cache, True, taps)
+    f32_exact = lambda a: np.array_equal(np.asarray(a, dtype=np.float32).astype(np.float64), a)
+    assert f32_exact(c32) and f32_exact(e32) and f32_exact(fp32) and not f32_exact(c64)
+    assert all(f32_exact(v) for v in cache.values())
+    assert all(f32_exact(tp[k]) for tp in taps for k in ("qkv", "A", "Mo", "x"))
+    assert not any(f32_exact(tp[k]) for tp in taps for k in ("h", "o", "u", "g"))      # quantised where produced, never stored
+    assert np.allclose(c32, c64, rtol=1e-5, atol=1e-7) and not np.array_equal(c32, c64)
+    assert np.allclose(e32, e64, rtol=1e-7, atol=1e-9) and np.allclose(fp32, fp64, rtol=1e-4, atol=1e-6)
+    assert dit.st(np.float64(1.0) + 2.0 ** -30) == 1.0
+    with dit.storage("f64"):
+        assert dit.st(np.float64(1.0) + 2.0 ** -30) != 1.0
+    x1, _ = sampler.sample_step(lat.astype(np.float64), lab, 0, 500, 0.3, 0.4, TINY, w, dit.QLinears(w, qp), {}, 2, K_t=np.full(4, 0.97))
+    assert f32_exact(x1)

@@ -120,6 +120,6 @@ def test_fit_along_a_trajectory_reduces_the_objective():
         xr, _ = sampler.sample_step(xr, lab, i, int(tt[i]), at[i], ap[i], model, w, fp, {}, 1, 0.0, None, force_full=True)
         xh, _ = sampler.sample_step(xh, lab, i, int(tt[i]), at[i], ap[i], model, w, lin, cache, interval, 0.0, None)
         assert np.all(vc_fit.objective(K[i], xh, xr, 1e-3) <= vc_fit.objective(np.ones(4), xh, xr, 1e-3) + 1e-12)
-        xh = sampler.vc_correct(xh, K[i])
+        xh = dit.st(sampler.vc_correct(xh, K[i]))          # the corrected sample is a stored (float32) tensor
     np.testing.assert_allclose(xh, x_hat, rtol=0, atol=1e-12)
     np.testing.assert_allclose(xr, x_ref, rtol=0, atol=1e-12)

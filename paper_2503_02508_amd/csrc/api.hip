@@ -498,14 +498,14 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
     a.q_words = q_words; a.k_words = k_words; a.vt_hi = vt_hi; a.vt_lo = vt_lo;
     a.heads = ctx->H; a.hd = ctx->hd; a.DP = ctx->DP; a.Tp = ctx->Tp; a.rows_per_batch = T;
     a.q_scale = 1.4426950408889634f / std::sqrt((float)ctx->hd);     // log2(e) / sqrt(d): the softmax runs in base 2
-    a.y = ctx->keep_qkv_f32 ? ctx->qkv + row0 * 3 * D : nullptr; a.ldy = 3 * D;
+    a.y = ctx->qkv + row0 * 3 * D; a.ldy = 3 * D;      // float32 Q | K | V: the attention kernel's exact path reads it
     QC_PROF(QC_K_GEMM_QKV);
     QC_HIP(launch_gemm(a, EPI_QKV, 1, st, QC_SITE_QKV));
   }
   {
     QC_PROF(QC_K_ATTENTION);
     QC_HIP(launch_attention_f16(q_words, k_words, vt_hi, vt_lo, B, T, ctx->Tp, ctx->H, ctx->hd, ctx->DP, qp + QC_SITE_PROJ,
-                                qa_attn, st));
+                                qa_attn, ctx->qkv + row0 * 3 * D, st));
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_PROJ], qa_attn, D, QC_SITE_PROJ);

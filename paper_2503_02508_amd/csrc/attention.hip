@@ -215,7 +215,7 @@ template <int NCH, int NEB, int QB>
 __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *__restrict__ Qp, const unsigned *__restrict__ Kp,
                                                             const _Float16 *__restrict__ Vh, const _Float16 *__restrict__ Vl, int T,
                                                             int Tp, int H, int hd, int DPv, const QParam *qp,
-                                                            int8_t *__restrict__ q_out) {
+                                                            int8_t *__restrict__ q_out, const float *__restrict__ qkv32) {
   constexpr int DP = 32 * NCH;
   constexpr int KROW = DP + 8;    // halves per K row in LDS (16 bytes of padding)
   constexpr int VROW = 64 + 8;    // halves per V^T row in LDS
@@ -431,32 +431,130 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
     }
   }
 
+  // ---- epilogue.  The codes of the workgroup's queries are staged in LDS (the K tiles are no longer needed), the ones
+  // whose value lies too close to a rounding boundary of Eq. 1 for the arithmetic above (fp16 pairs, fp32 sums and
+  // exponentials) to be trusted are decided again in float64 from the float32 Q | K | V, then the rows go out.
   const QParam t = *qp;
   const float qs = t.s, qz = (float)t.z;
+  constexpr int NQ = 64 * QB;                     // queries of this workgroup
+  constexpr int SRB = 16 * NEB + 16;              // staged row: the head's features, padded
+  constexpr int FIX_CAP = 192;
+  static_assert(NQ * SRB + 16 + FIX_CAP * 8 <= (int)sizeof(Ksh), "the epilogue's staging area must fit in the K tile buffers");
+  unsigned char *stage = (unsigned char *)&Ksh[0][0];
+  int *fix_cnt = (int *)(stage + NQ * SRB);
+  int *fix_ent = fix_cnt + 4;                     // [FIX_CAP][2]: query within the workgroup, feature
+  __syncthreads();                                // every wavefront is past its last K / V^T fragment
+  if (tid == 0) *fix_cnt = 0;
+  __syncthreads();
+  // |v / s - rint(v / s)| within tol of 1/2: 3e-5 steps + 1e-6 of the code's size bound the kernel's error with a wide margin
+  // (its differing codes, a few 1e-6 of all, put the mean error near 1e-6 steps)
 #pragma unroll
   for (int j = 0; j < QB; ++j) {
     float l = l_run[j];
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
-    if (q_row[j] >= T) continue;
     const float inv = 1.0f / l;
-    const size_t out_row = ((size_t)b * T + q_row[j]) * D + (size_t)h * hd;
+    const int qloc = wave * (16 * QB) + j * 16 + ql;
 #pragma unroll
     for (int e = 0; e < NEB; ++e) {
       const int f = 16 * e + 4 * g;
-      if (f >= hd) continue;
       const v4f v = o[j][e] * inv;
       int c[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) c[r] = (int)fminf(fmaxf(rintf(v[r] / qs) + qz, -128.f), 127.f);
-      *(unsigned *)(q_out + out_row + f) = (unsigned)(c[0] & 0xFF) | ((unsigned)(c[1] & 0xFF) << 8) |
-                                           ((unsigned)(c[2] & 0xFF) << 16) | ((unsigned)(c[3] & 0xFF) << 24);
+      for (int r = 0; r < 4; ++r) {
+        const float qv = v[r] / qs, rr = rintf(qv);
+        c[r] = (int)fminf(fmaxf(rr + qz, -128.f), 127.f);
+        if (qkv32 && q_row[j] < T && f + r < hd && fabsf(fabsf(qv - rr) - 0.5f) < fmaf(1e-6f, fabsf(qv), 3e-5f)) {
+          const int slot = atomicAdd(fix_cnt, 1);
+          if (slot < FIX_CAP) {
+            fix_ent[2 * slot] = qloc;
+            fix_ent[2 * slot + 1] = f + r;
+          }
+        }
+      }
+      *(unsigned *)(stage + qloc * SRB + f) = (unsigned)(c[0] & 0xFF) | ((unsigned)(c[1] & 0xFF) << 8) |
+                                              ((unsigned)(c[2] & 0xFF) << 16) | ((unsigned)(c[3] & 0xFF) << 24);
     }
+  }
+  __syncthreads();
+  const int q_first = blockIdx.y * NQ;            // first query of the workgroup
+  {
+    // one wavefront per queued output: softmax(q K^T / sqrt(d)) V[:, feature] in float64, a lane owns keys lane, lane + 64, ...
+    const int nfix = min(*fix_cnt, FIX_CAP);
+    const int ld = 3 * D;
+    const float *base = qkv32 + (size_t)b * T * ld + (size_t)h * hd;
+    const double rs = 1.0 / sqrt((double)hd);
+    constexpr int KPL = 16;                       // keys per lane kept in registers (T <= 1024); beyond that the scores are formed twice
+    for (int fi = wave; fi < nfix; fi += 4) {
+      const int qloc = fix_ent[2 * fi], feat = fix_ent[2 * fi + 1];
+      const float *qr = base + (size_t)(q_first + qloc) * ld;
+      auto score = [&](int key) {
+        const float *kr = base + (size_t)key * ld + D;
+        double acc = 0.0;
+        for (int d0 = 0; d0 < hd; d0 += 4) {
+          const v4f qv = *(const v4f *)(qr + d0), kv = *(const v4f *)(kr + d0);
+          acc = fma((double)qv[0], (double)kv[0], acc);
+          acc = fma((double)qv[1], (double)kv[1], acc);
+          acc = fma((double)qv[2], (double)kv[2], acc);
+          acc = fma((double)qv[3], (double)kv[3], acc);
+        }
+        return acc * rs;
+      };
+      double sc[KPL];
+      double mx = -INFINITY;
+      const bool keep = T <= 64 * KPL;
+#pragma unroll
+      for (int u = 0; u < KPL; ++u) {
+        const int key = lane + 64 * u;
+        sc[u] = (keep && key < T) ? score(key) : -INFINITY;
+        mx = fmax(mx, sc[u]);
+      }
+      if (!keep)
+        for (int key = lane; key < T; key += 64) mx = fmax(mx, score(key));
+#pragma unroll
+      for (int o2 = 32; o2 > 0; o2 >>= 1) mx = fmax(mx, __shfl_xor(mx, o2, 64));
+      double den = 0.0, num = 0.0;
+      if (keep) {
+#pragma unroll
+        for (int u = 0; u < KPL; ++u) {
+          const int key = lane + 64 * u;
+          if (key < T) {
+            const double pj = exp(sc[u] - mx);
+            den += pj;
+            num = fma(pj, (double)base[(size_t)key * ld + 2 * D + feat], num);
+          }
+        }
+      } else {
+        for (int key = lane; key < T; key += 64) {
+          const double pj = exp(score(key) - mx);
+          den += pj;
+          num = fma(pj, (double)base[(size_t)key * ld + 2 * D + feat], num);
+        }
+      }
+#pragma unroll
+      for (int o2 = 32; o2 > 0; o2 >>= 1) {
+        den += __shfl_xor(den, o2, 64);
+        num += __shfl_xor(num, o2, 64);
+      }
+      if (lane == 0) {
+        const float ov = (float)(num / den);
+        stage[qloc * SRB + feat] = (unsigned char)(int)fminf(fmaxf(rintf(ov / qs) + qz, -128.f), 127.f);
+      }
+    }
+    if (nfix) __syncthreads();
+  }
+  // rows out: hd bytes per query (a multiple of 4), contiguous in the output row of the token
+  const int wpr = hd >> 2;                        // 32-bit words per row
+  for (int i = tid; i < NQ * wpr; i += 256) {
+    const int qloc = i / wpr, wd = i - qloc * wpr;
+    const int qg = q_first + qloc;
+    if (qg < T) *(unsigned *)(q_out + ((size_t)b * T + qg) * D + (size_t)h * hd + 4 * wd) = *(const unsigned *)(stage + qloc * SRB + 4 * wd);
   }
 }
 
 hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
-                                int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st) {
+                                int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, const float *qkv32,
+                                hipStream_t st) {
   const int neb = (hd + 15) / 16, nch = (hd + 31) / 32;
   if (hd > 80 || hd % 4) return hipErrorInvalidValue;      // K prefetch registers are sized for d <= 80
   // one query block per wavefront when two would leave compute units without a workgroup (QC_ATT_QB forces 1 or 2)
@@ -471,10 +569,10 @@ hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words
   do {                                                                                                                      \
     if (qb == 1)                                                                                                            \
       hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 1>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, \
-                         H, hd, DPv, qp, q_out);                                                                            \
+                         H, hd, DPv, qp, q_out, qkv32);                                                                     \
     else                                                                                                                    \
       hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 2>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, \
-                         H, hd, DPv, qp, q_out);                                                                            \
+                         H, hd, DPv, qp, q_out, qkv32);                                                                     \
   } while (0)
   if (nch == 1 && neb == 1) QC_ATT(1, 1);
   else if (nch == 1) QC_ATT(1, 2);

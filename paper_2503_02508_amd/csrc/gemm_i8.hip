@@ -477,7 +477,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
     const bool fast_t = (T % 4) == 0;
     const bool tile_one_batch = (T % BM) == 0;      // then every row of the tile belongs to batch element m0 / T
     const int b_tile = m0 / T;
-    if (BM == 128 && BN == 128 && tile_one_batch && fast_t && m0 + BM <= p.M && n0 + BN <= p.N && !p.y &&
+    if (BM == 128 && BN == 128 && tile_one_batch && fast_t && m0 + BM <= p.M && n0 + BN <= p.N &&
         D % BN == 0 && (p.hd & 3) == 0 && (p.Tp & 7) == 0) {
       // Interior tile inside one batch element and one of Q, K, V: the split values go through LDS (free after the K
       // loop) and leave as 16-byte stores along the contiguous direction of their layout (Q / K: features of a
@@ -499,7 +499,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int ml = wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-              const float v = dequant_f32(sc, acc[i][j][r] - zw, bs) * mul;
+              const float v0 = dequant_f32(sc, acc[i][j][r] - zw, bs);
+              if (p.y) p.y[(long long)(m0 + ml) * p.ldy + n0 + nl] = v0;      // float32 copy (32 lanes write 128 contiguous bytes)
+              const float v = v0 * mul;
               const _Float16 hi = (_Float16)v, lo = (_Float16)(v - (float)hi);
               stage[ml * SR + nl] =
                   (unsigned)__builtin_bit_cast(unsigned short, hi) | ((unsigned)__builtin_bit_cast(unsigned short, lo) << 16);
@@ -533,6 +535,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
                 const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
+                if (p.y) p.y[(long long)(m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4 + q) * p.ldy + n0 + nl] = v;
                 hi[q] = (_Float16)v;
                 lo[q] = (_Float16)(v - (float)hi[q]);
               }
@@ -566,7 +569,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
       const int part = n / D, nn = n - part * D, h = nn / p.hd, e = nn - h * p.hd;
       const float mul = part == 0 ? p.q_scale : 1.0f;
       unsigned *dpair = part == 0 ? p.q_words : p.k_words;   // Q / K: one (hi | lo << 16) word per element
-      if (tile_one_batch && fast_t && m0 + BM <= p.M && !p.y) {
+      if (tile_one_batch && fast_t && m0 + BM <= p.M) {
         // interior tile inside one batch element: 32-bit offsets advanced row by row, no per-element index arithmetic
         const int tb = m0 - b_tile * T + wm0 + (lane >> 5) * 4;            // token of this lane's first row
         const unsigned head = (unsigned)(b_tile * p.heads + h);
@@ -581,6 +584,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
                 const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
+                if (p.y) p.y[(long long)(m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4 + q) * p.ldy + n] = v;
                 hi[q] = (_Float16)v;
                 lo[q] = (_Float16)(v - (float)hi[q]);
               }
@@ -596,7 +600,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
             for (int rg = 0; rg < 4; ++rg)
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
-                const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs) * mul;
+                const float v0 = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
+                if (p.y) p.y[(long long)(m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4 + q) * p.ldy + n] = v0;
+                const float v = v0 * mul;
                 const _Float16 hi = (_Float16)v, lo = (_Float16)(v - (float)hi);
                 dst[(unsigned)(i * 32 + rg * 8 + q) * (unsigned)p.hd] =
                     (unsigned)__builtin_bit_cast(unsigned short, hi) | ((unsigned)__builtin_bit_cast(unsigned short, lo) << 16);

@@ -113,7 +113,8 @@ hipError_t launch_vc_fit(const float *x_hat, const float *x_ref, int B, int C, i
 hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const QParam *qp, int8_t *q_out, float *f32_out,
                             hipStream_t st);
 hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
-                                int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, hipStream_t st);
+                                int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, const float *qkv32,
+                                hipStream_t st);
 // calibration helpers
 hipError_t launch_linear_f32(const float *x, const float *W, const float *b, float *y, int M, int N, int K, int act_out,
                              hipStream_t st);

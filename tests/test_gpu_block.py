@@ -2,10 +2,8 @@
 against the CPU oracle, through the C ABI, on identical seeded inputs.
 
 Floating-point outputs: max-abs <= 1e-2 and relative RMS <= 1e-3 (the bar of
-the task).  The integer codes inside a block follow floating-point values that
-the device computes in fp32 and the oracle in fp64, so a code can land on the
-other side of a rounding boundary; the tests bound how often (and require that
-a differing code differs by exactly one step)."""
+the task), also for the tensors inside a block.  The integer codes inside a
+block are the oracle's (at most 1e-6 of them may differ, by one step)."""
 import numpy as np
 import pytest
 
@@ -25,15 +23,13 @@ WIDEST = I.ModelDesc(depth=1, hidden=2048, heads=32, mlp_dim=2304, patch=1, late
                      num_classes=5)
 HEAD80 = I.ModelDesc(depth=1, hidden=320, heads=4, mlp_dim=640, patch=2, latent_c=4, latent_h=12, latent_w=10,
                      num_classes=5)
-# Every stored tensor is the float32 rounding of an exactly evaluated value and every quantiser but the attention
-# kernel's decides as the oracle does (tests/test_gpu_quantisers.py), so codes differ only where an attention output
-# sits within the kernel's fp16-pair / fp32 error of a rounding boundary (a few 1e-6 of them) and in what such a code
-# then moves downstream: one such code shifts a row of the projection output, the LayerNorm codes of that row follow
-# and with them a row of fc1 / fc2 outputs.  The block output, the noise estimate and the samples are held to the task's
-# bar; the module outputs inside the network (the cached tensors), where such a row is not diluted by the residual
-# stream, are held to 3e-2 / 2.5e-3 (measured worst case 1.7e-2 / 1.2e-3, bit-equal where no attention code differs).
-MAX_FLIP_FRACTION = 1e-3
-INNER_MAX_ABS, INNER_REL_RMS = 3e-2, 2.5e-3
+# Every stored tensor is the float32 rounding of an exactly evaluated value and every quantiser decides as the oracle
+# does (each fused quantiser is checked alone in tests/test_gpu_quantisers.py; the fc1 epilogue and the attention kernel
+# decide again in float64 where their fast arithmetic lands too close to a rounding boundary), so the device's tensors
+# and codes are the oracle's bit for bit apart from double-rounding ties.  The tensors inside a block (the cached module
+# outputs, Q | K | V) are held to the same bar as the block output, and the codes may differ in at most 1e-6 of the cases.
+MAX_FLIP_FRACTION = 1e-6
+INNER_MAX_ABS, INNER_REL_RMS = 1e-2, 1e-3
 
 
 def _cuda(a, dtype=None):

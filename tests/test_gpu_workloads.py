@@ -23,15 +23,10 @@ from qc_testlib import make_pair, oracle_calibration, rel_rms, max_abs
 
 pytestmark = pytest.mark.gpu
 
-# The task's bar (max-abs 1e-2, relative RMS 1e-3) is asserted on every sample and, up to a depth of 8 blocks, on the
-# residual stream and the noise estimate.  At the full depth of 28 blocks those two carry a stated, measured miss in
-# relative RMS (1.3e-3 and 1.5e-3 measured; max-abs stays inside 1e-2): the network with random-init weights amplifies
-# a single differing code (each quantiser turns a difference d into about sqrt(d * step)), the attention kernel's
-# fp16-pair arithmetic differs from exact arithmetic in a few 1e-6 of its codes (tests/test_gpu_quantisers.py; every
-# other kernel gives the oracle's codes and bit-equal stored tensors), and 28 x 256 x 1152 attention outputs per latent
-# make one such code certain; after it the latent's activations settle at the distance two exact evaluations that
-# differ in one code have.  The samples, which the noise estimate enters with a small solver coefficient, keep the bar.
-DEEP_REL_RMS = 2.5e-3
+# The task's bar (max-abs 1e-2, relative RMS 1e-3) is asserted on every sample, on the residual stream after the last
+# block and on the noise estimate, at every depth.  (Measured: bit-equal to the oracle, final latents of the 50-step
+# loop included - every stored tensor is the float32 rounding of an exactly evaluated value and every quantiser decides
+# as the oracle does.)
 
 
 def _run(wl, depth, n_steps, sub, check_stream=False):
@@ -66,13 +61,13 @@ def _run(wl, depth, n_steps, sub, check_stream=False):
                 tok_dev = ctx.workspace("tokens", (Beff, model.tokens, model.hidden), torch.float32).cpu().numpy()[rows]
                 s_abs, s_rel = max_abs(tok_dev, taps[-1]["x"]), rel_rms(tok_dev, taps[-1]["x"])
                 print("   residual stream after block %d: max-abs %.2e rel-RMS %.2e" % (model.depth - 1, s_abs, s_rel))
-                assert s_abs <= 1e-2 and s_rel <= (DEEP_REL_RMS if model.depth > 8 else 1e-3)
+                assert s_abs <= 1e-2 and s_rel <= 1e-3
             if wl.cfg_scale <= 0:
                 shape = (Beff, model.latent_c, model.latent_h, model.latent_w)
                 eps_dev = ctx.workspace("eps", shape, torch.float32).cpu().numpy()[sub]
                 e_abs, e_rel = max_abs(eps_dev, eps_or), rel_rms(eps_dev, eps_or)
                 print("   eps step 0: max-abs %.2e rel-RMS %.2e" % (e_abs, e_rel))
-                assert e_abs <= 1e-2 and e_rel <= (DEEP_REL_RMS if model.depth > 8 else 1e-3)
+                assert e_abs <= 1e-2 and e_rel <= 1e-3
         torch.cuda.synchronize()
         got = xd.cpu().numpy()[sub]
         errs.append((max_abs(got, x_or), rel_rms(got, x_or)))
@@ -117,9 +112,7 @@ def test_cfg1_whole_loop_final_latents():
     print("cfg1 final latents after %d steps: max-abs %.2e rel-RMS %.2e (|x| rms %.2f, max %.2f)" % (
         wl.steps, ma, rr, np.sqrt(np.mean(want ** 2)), np.abs(want).max()))
     assert np.isfinite(got).all()
-    # the sample has grown to |x| ~ 10^2 (random-init weights: the noise estimate does not cancel it): max-abs is held to
-    # the bar's 1e-2 relative to a unit-scale sample, i.e. 1e-2 * rms(x) here
-    assert rr <= 1e-3 and ma <= 1e-2 * max(1.0, float(np.sqrt(np.mean(want ** 2))))
+    assert rr <= 1e-3 and ma <= 1e-2
 
 
 @pytest.mark.parametrize("key,sub", [("cfg2", [17]), ("cfg3", [5]), ("cfg4", [9])])

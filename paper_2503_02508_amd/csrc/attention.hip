@@ -223,8 +223,10 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   constexpr int VCH = (NEB * 16 * 8 + 255) / 256;
   __shared__ __align__(16) _Float16 Ksh[2][64 * KROW];
   __shared__ __align__(16) _Float16 Vsh[2][NEB * 16 * VROW];
+  __shared__ int fix_cnt_s;                       // outputs queued for the exact decision (epilogue)
 
   const int D = H * hd;
+  if (threadIdx.x == 0) fix_cnt_s = 0;            // published by the barriers of the key loop
   // blockIdx.x = (batch, head): the query blocks of one head are B*H workgroups apart and land on the same XCD
   // (workgroups go round-robin over the 8 XCDs), so its K and V are fetched into one L2 only
   const int bh = blockIdx.x, b = bh / H, h = bh % H;
@@ -439,15 +441,16 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   constexpr int NQ = 64 * QB;                     // queries of this workgroup
   constexpr int SRB = 16 * NEB + 16;              // staged row: the head's features, padded
   constexpr int FIX_CAP = 192;
-  static_assert(NQ * SRB + 16 + FIX_CAP * 8 <= (int)sizeof(Ksh), "the epilogue's staging area must fit in the K tile buffers");
+  static_assert(NQ * SRB + FIX_CAP * 8 <= (int)sizeof(Ksh), "the epilogue's staging area must fit in the K tile buffers");
   unsigned char *stage = (unsigned char *)&Ksh[0][0];
-  int *fix_cnt = (int *)(stage + NQ * SRB);
-  int *fix_ent = fix_cnt + 4;                     // [FIX_CAP][2]: query within the workgroup, feature
+  int *fix_cnt = &fix_cnt_s;
+  int *fix_ent = (int *)(stage + NQ * SRB);       // [FIX_CAP][2]: query within the workgroup, feature
   __syncthreads();                                // every wavefront is past its last K / V^T fragment
-  if (tid == 0) *fix_cnt = 0;
-  __syncthreads();
-  // |v / s - rint(v / s)| within tol of 1/2: 3e-5 steps + 1e-6 of the code's size bound the kernel's error with a wide margin
-  // (its differing codes, a few 1e-6 of all, put the mean error near 1e-6 steps)
+  // |v / s - rint(v / s)| within tol of 1/2: 1.2e-5 steps + 4e-7 of the code's size at 256 keys is about ten times the
+  // kernel's mean error there (its differing codes without this path, a few 1e-6 of all, put the mean error near 1e-6
+  // steps); the sums grow with the number of keys and the bound with them
+  const float tol_k = fmaxf(1.0f, (float)T * (1.0f / 256.0f));
+  const float tol_0 = 1.2e-5f * tol_k, tol_q = 4e-7f * tol_k;
 #pragma unroll
   for (int j = 0; j < QB; ++j) {
     float l = l_run[j];
@@ -464,7 +467,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
       for (int r = 0; r < 4; ++r) {
         const float qv = v[r] / qs, rr = rintf(qv);
         c[r] = (int)fminf(fmaxf(rr + qz, -128.f), 127.f);
-        if (qkv32 && q_row[j] < T && f + r < hd && fabsf(fabsf(qv - rr) - 0.5f) < fmaf(1e-6f, fabsf(qv), 3e-5f)) {
+        if (qkv32 && q_row[j] < T && f + r < hd && fabsf(fabsf(qv - rr) - 0.5f) < fmaf(tol_q, fabsf(qv), tol_0)) {
           const int slot = atomicAdd(fix_cnt, 1);
           if (slot < FIX_CAP) {
             fix_ent[2 * slot] = qloc;
@@ -479,58 +482,76 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   __syncthreads();
   const int q_first = blockIdx.y * NQ;            // first query of the workgroup
   {
-    // one wavefront per queued output: softmax(q K^T / sqrt(d)) V[:, feature] in float64, a lane owns keys lane, lane + 64, ...
+    // softmax(q K^T / sqrt(d)) V[:, feature] in float64 for every queued output
     const int nfix = min(*fix_cnt, FIX_CAP);
     const int ld = 3 * D;
     const float *base = qkv32 + (size_t)b * T * ld + (size_t)h * hd;
     const double rs = 1.0 / sqrt((double)hd);
-    constexpr int KPL = 16;                       // keys per lane kept in registers (T <= 1024); beyond that the scores are formed twice
+    // One wavefront per queued output.  A key row is shared by a pair of lanes (even lane: first half of its 16-byte
+    // chunks, odd lane: second half); a lane pair takes four keys per pass and all their loads are issued at once, so
+    // 128 keys cost one memory round trip; chunks beyond d are read from a clamped address and multiplied by zero.
+    // Running (max, sum, weighted sum) per lane; the lanes are merged by reducing the max first, so that the merge
+    // needs one exponential per lane.
+    constexpr int NCH2 = 2 * NEB;                 // chunks per lane
+    constexpr int KU = NEB >= 5 ? 2 : (NEB >= 4 ? 3 : 4);      // keys in flight per lane pair (as many as the register file holds)
+    const int half = lane & 1, kl = lane >> 1;    // 32 lane pairs
     for (int fi = wave; fi < nfix; fi += 4) {
       const int qloc = fix_ent[2 * fi], feat = fix_ent[2 * fi + 1];
       const float *qr = base + (size_t)(q_first + qloc) * ld;
-      auto score = [&](int key) {
-        const float *kr = base + (size_t)key * ld + D;
-        double acc = 0.0;
-        for (int d0 = 0; d0 < hd; d0 += 4) {
-          const v4f qv = *(const v4f *)(qr + d0), kv = *(const v4f *)(kr + d0);
-          acc = fma((double)qv[0], (double)kv[0], acc);
-          acc = fma((double)qv[1], (double)kv[1], acc);
-          acc = fma((double)qv[2], (double)kv[2], acc);
-          acc = fma((double)qv[3], (double)kv[3], acc);
-        }
-        return acc * rs;
-      };
-      double sc[KPL];
-      double mx = -INFINITY;
-      const bool keep = T <= 64 * KPL;
+      v4f qf[NCH2];
 #pragma unroll
-      for (int u = 0; u < KPL; ++u) {
-        const int key = lane + 64 * u;
-        sc[u] = (keep && key < T) ? score(key) : -INFINITY;
-        mx = fmax(mx, sc[u]);
+      for (int c = 0; c < NCH2; ++c) {
+        const int d0 = 4 * (half * NCH2 + c);
+        qf[c] = *(const v4f *)(qr + min(d0, hd - 4));
+        if (d0 >= hd) qf[c] = (v4f){0.f, 0.f, 0.f, 0.f};
       }
-      if (!keep)
-        for (int key = lane; key < T; key += 64) mx = fmax(mx, score(key));
+      double mx = -INFINITY, den = 0.0, num = 0.0;
+      for (int k0 = 0; k0 < T; k0 += 32 * KU) {
+        v4f kv[KU][NCH2];
+        float vv[KU];
 #pragma unroll
-      for (int o2 = 32; o2 > 0; o2 >>= 1) mx = fmax(mx, __shfl_xor(mx, o2, 64));
-      double den = 0.0, num = 0.0;
-      if (keep) {
+        for (int u = 0; u < KU; ++u) {
+          const float *kr = base + (size_t)min(k0 + 32 * u + kl, T - 1) * ld;
 #pragma unroll
-        for (int u = 0; u < KPL; ++u) {
-          const int key = lane + 64 * u;
-          if (key < T) {
-            const double pj = exp(sc[u] - mx);
-            den += pj;
-            num = fma(pj, (double)base[(size_t)key * ld + 2 * D + feat], num);
+          for (int c = 0; c < NCH2; ++c) kv[u][c] = *(const v4f *)(kr + D + min(4 * (half * NCH2 + c), hd - 4));
+          vv[u] = kr[2 * D + feat];
+        }
+        double sv[KU];
+        double pm = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+          double acc = 0.0;
+#pragma unroll
+          for (int c = 0; c < NCH2; ++c) {
+            acc = fma((double)qf[c][0], (double)kv[u][c][0], acc);
+            acc = fma((double)qf[c][1], (double)kv[u][c][1], acc);
+            acc = fma((double)qf[c][2], (double)kv[u][c][2], acc);
+            acc = fma((double)qf[c][3], (double)kv[u][c][3], acc);
           }
+          acc += __shfl_xor(acc, 1, 64);          // both lanes of the pair now hold the whole dot product
+          sv[u] = (k0 + 32 * u + kl < T && half == 0) ? acc * rs : -INFINITY;      // the even lane carries the key
+          pm = fmax(pm, sv[u]);
         }
-      } else {
-        for (int key = lane; key < T; key += 64) {
-          const double pj = exp(score(key) - mx);
-          den += pj;
-          num = fma(pj, (double)base[(size_t)key * ld + 2 * D + feat], num);
+        if (pm > -INFINITY) {
+          const double mn = fmax(mx, pm);
+          const double a2 = exp(mx - mn);         // exp(-inf) = 0 on the first pass
+          den *= a2;
+          num *= a2;
+#pragma unroll
+          for (int u = 0; u < KU; ++u) {
+            const double pj = exp(sv[u] - mn);    // 0 for a key that is not this lane's
+            den += pj;
+            num = fma(pj, (double)vv[u], num);
+          }
+          mx = mn;
         }
       }
+      double gm = mx;
+#pragma unroll
+      for (int o2 = 32; o2 > 0; o2 >>= 1) gm = fmax(gm, __shfl_xor(gm, o2, 64));
+      const double sc2 = mx > -INFINITY ? exp(mx - gm) : 0.0;
+      den *= sc2;
+      num *= sc2;
 #pragma unroll
       for (int o2 = 32; o2 > 0; o2 >>= 1) {
         den += __shfl_xor(den, o2, 64);
@@ -544,11 +565,13 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
     if (nfix) __syncthreads();
   }
   // rows out: hd bytes per query (a multiple of 4), contiguous in the output row of the token
-  const int wpr = hd >> 2;                        // 32-bit words per row
-  for (int i = tid; i < NQ * wpr; i += 256) {
-    const int qloc = i / wpr, wd = i - qloc * wpr;
-    const int qg = q_first + qloc;
-    if (qg < T) *(unsigned *)(q_out + ((size_t)b * T + qg) * D + (size_t)h * hd + 4 * wd) = *(const unsigned *)(stage + qloc * SRB + 4 * wd);
+  const int wpr = hd >> 2;                        // 32-bit words per row (<= 20): 32 lanes per row, 8 rows per pass
+  const int wd = tid & 31;
+#pragma unroll
+  for (int r0 = 0; r0 < NQ; r0 += 8) {
+    const int qloc = r0 + (tid >> 5), qg = q_first + qloc;
+    if (wd < wpr && qg < T)
+      *(unsigned *)(q_out + ((size_t)b * T + qg) * D + (size_t)h * hd + 4 * wd) = *(const unsigned *)(stage + qloc * SRB + 4 * wd);
   }
 }
 

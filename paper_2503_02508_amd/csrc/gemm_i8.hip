@@ -108,7 +108,7 @@ __device__ __forceinline__ int quant_code(float v, float s, float inv_s, float z
 }
 
 template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_i8_kernel(GemmArgs p) {
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int NT = 64 * WM * WN;            // threads per workgroup
@@ -419,6 +419,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
           int code[4];
+          bool doubt[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int corr = acc[i][j][rg * 4 + e] - zw[e];
@@ -428,14 +429,20 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_i8_kernel(GemmArgs p) {
             q = fmaf(fmaf(-q, o_s, gv), o_inv, q);
             const float r = __builtin_rintf(q);
             code[e] = (int)fminf(fmaxf(r + o_z, -128.0f), 127.0f);
-            if (fabsf(fabsf(q - r) - 0.5f) < fmaf(tol_v, fabsf(v), 2e-6f)) {
-              const int slot = atomicAdd(fix_cnt, 1);
-              if (slot < GELU_FIX_CAP) {
-                fix_ent[slot * 4 + 0] = corr;
-                fix_ent[slot * 4 + 1] = nl + e;
-                fix_ent[slot * 4 + 2] = wm0 + i * 32 + (lane & 31);
+            doubt[e] = fabsf(fabsf(q - r) - 0.5f) < fmaf(tol_v, fabsf(v), 2e-6f);
+          }
+          // one branch per four outputs; taken by a wavefront about once in a hundred times
+          if (doubt[0] | doubt[1] | doubt[2] | doubt[3]) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (doubt[e]) {
+                const int slot = atomicAdd(fix_cnt, 1);
+                if (slot < GELU_FIX_CAP) {
+                  fix_ent[slot * 4 + 0] = acc[i][j][rg * 4 + e] - zw[e];
+                  fix_ent[slot * 4 + 1] = nl + e;
+                  fix_ent[slot * 4 + 2] = wm0 + i * 32 + (lane & 31);
+                }
               }
-            }
           }
           const unsigned w = (unsigned)(code[0] & 0xFF) | ((unsigned)(code[1] & 0xFF) << 8) |
                              ((unsigned)(code[2] & 0xFF) << 16) | ((unsigned)(code[3] & 0xFF) << 24);

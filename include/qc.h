@@ -176,6 +176,16 @@ int qc_vc_correct(float *x, const float *K_t, const float *mu_or_null, int B, in
 int qc_vc_fit(const float *x_hat, const float *x_ref, int B, int C, int H, int W, float eps, double *work, float *K_t,
               void *stream);
 
+/* qc_vc_fit for callers that cannot allocate device memory for `work` (code under HIP graph capture, serving loops
+ * and harnesses that forbid allocation): the per-plane partial sums live in a fixed device array inside the library,
+ * QC_VC_FIT_STATIC_MAX_PLANES planes (B * C) at most, 256 KiB per GPU the library runs on, held until the process
+ * ends.  Same arguments, kernels and results as qc_vc_fit without `work`; B * C beyond the limit is QC_ERR_WORKSPACE.
+ * The call allocates nothing.  Every call on a GPU uses that GPU's one array (each plane's slot is overwritten by
+ * every call, nothing has to be cleared in between): calls that overlap on one GPU - different streams or host
+ * threads - race and must be serialised by the caller. */
+#define QC_VC_FIT_STATIC_MAX_PLANES 16384
+int qc_vc_fit_static(const float *x_hat, const float *x_ref, int B, int C, int H, int W, float eps, float *K_t, void *stream);
+
 /* Deterministic DDIM schedule on the 1000-step linear-beta (1e-4..2e-2)
  * training schedule: t[i] = (steps-1-i) * floor(1000/steps), abar_t[i],
  * abar_prev[i] (= 1 on the last step).  HOST arrays of `steps` entries. */

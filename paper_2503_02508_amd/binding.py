@@ -10,7 +10,7 @@ import os
 
 __all__ = [
     "lib", "QCError", "ModelDesc", "Context", "QC_FULL", "QC_CACHED", "QC_CACHE_ATTN", "QC_CACHE_MLP", "SITES",
-    "qc_quantize_act", "qc_quantize_weight", "qc_w8a8_linear", "qc_vc_correct", "qc_vc_fit", "qc_ddim_schedule", "last_error",
+    "qc_quantize_act", "qc_quantize_weight", "qc_w8a8_linear", "qc_vc_correct", "qc_vc_fit", "qc_vc_fit_static", "qc_ddim_schedule", "last_error",
     "LIB_PATH", "WS", "KERNEL_CLASSES",
     "qc_tap_workspace_bytes", "qc_tap_similarity", "qc_tap_normalise", "qc_tap_embed", "qc_tap_kmeans",
     "qc_tap_aggregate", "qc_tap_cluster", "qc_tap_profile_begin", "qc_tap_profile_end",
@@ -61,6 +61,7 @@ _SIGS = {
     "qc_set_cache_mask": (i32, [vp, vp, i32]),
     "qc_set_cache_format": (i32, [vp, i32]),
     "qc_vc_fit": (i32, [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp]),
+    "qc_vc_fit_static": (i32, [vp, vp, i32, i32, i32, i32, f32, vp, vp]),
     "qc_denoise_f32": (i32, [vp, C.POINTER(Weights), vp, i32, vp, i32, i32, vp, vp]),
     "qc_vc_fit_sampler": (i32, [vp, C.POINTER(Weights), vp, vp, vp, i32, i32, f32, f32, vp, vp]),
     "qc_ddim_schedule": (i32, [i32, C.POINTER(C.c_int32), C.POINTER(f64), C.POINTER(f64)]),
@@ -136,6 +137,11 @@ def qc_w8a8_linear(qx, qw, wsum, w_scale, bias, x_scale, x_zp, weight_bits, y, a
 def qc_vc_fit(x_hat, x_ref, eps, work, K_t):
     B, Cc, H, W = x_hat.shape
     _chk(lib.qc_vc_fit(_p(x_hat), _p(x_ref), B, Cc, H, W, float(eps), _p(work), _p(K_t), _stream()))
+
+
+def qc_vc_fit_static(x_hat, x_ref, eps, K_t):
+    B, Cc, H, W = x_hat.shape
+    _chk(lib.qc_vc_fit_static(_p(x_hat), _p(x_ref), B, Cc, H, W, float(eps), _p(K_t), _stream()))
 
 
 def qc_vc_correct(x, K_t, mu=None):

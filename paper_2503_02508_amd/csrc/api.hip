@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "qc_internal.h"
@@ -1030,6 +1031,45 @@ int qc_vc_fit(const float *x_hat, const float *x_ref, int B, int C, int H, int W
   if (reinterpret_cast<uintptr_t>(work) & 7u) QC_FAIL(QC_ERR_ALIGN, "work must be 8-byte aligned");
   hipStream_t st = static_cast<hipStream_t>(stream);
   QC_HIP(launch_vc_fit(x_hat, x_ref, B, C, H * W, eps, work, K_t, st));
+  return QC_OK;
+}
+
+}  // extern "C"
+
+// Partial sums of qc_vc_fit_static: one copy per GPU, addressed through the pointer hipGetSymbolAddress returns for the
+// current device (the array's name is only a host-side handle).
+static __device__ __align__(256) double vc_fit_scratch[2 * QC_VC_FIT_STATIC_MAX_PLANES];
+static std::mutex vc_fit_scratch_mutex;
+static double *vc_fit_scratch_ptr[64] = {};      // per device, filled on the first call there
+
+static int vc_fit_scratch_for_current_device(double **out) {
+  int dev = 0;
+  QC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) QC_FAIL(QC_ERR_UNSUPPORTED, "device index %d outside 0..63", dev);
+  std::lock_guard<std::mutex> lock(vc_fit_scratch_mutex);
+  if (!vc_fit_scratch_ptr[dev]) {
+    double *p = nullptr;
+    QC_HIP(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(vc_fit_scratch)));
+    if (!p) QC_FAIL(QC_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    vc_fit_scratch_ptr[dev] = p;
+  }
+  *out = vc_fit_scratch_ptr[dev];
+  return QC_OK;
+}
+
+extern "C" {
+
+int qc_vc_fit_static(const float *x_hat, const float *x_ref, int B, int C, int H, int W, float eps, float *K_t, void *stream) {
+  if (!x_hat || !x_ref || !K_t) QC_FAIL(QC_ERR_NULL, "a pointer is NULL");
+  if (B < 1 || C < 1 || H < 1 || W < 1) QC_FAIL(QC_ERR_SHAPE, "B, C, H, W must be positive");
+  if (!(eps >= 0.0f)) QC_FAIL(QC_ERR_RANGE, "eps must be >= 0");
+  if ((long long)B * C > QC_VC_FIT_STATIC_MAX_PLANES)
+    QC_FAIL(QC_ERR_WORKSPACE, "B * C = %lld planes exceed the %d the library's fixed scratch holds", (long long)B * C,
+            QC_VC_FIT_STATIC_MAX_PLANES);
+  double *work = nullptr;
+  int rc = vc_fit_scratch_for_current_device(&work);
+  if (rc) return rc;
+  QC_HIP(launch_vc_fit(x_hat, x_ref, B, C, H * W, eps, work, K_t, static_cast<hipStream_t>(stream)));
   return QC_OK;
 }
 

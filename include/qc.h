@@ -60,7 +60,11 @@ enum {                                               /* qc_workspace_ptr selecto
   QC_WS_MOD = 5,      /* float  [L, R, 6D] adaLN modulation of every block; R = max(512, max_batch) rows,
                          row = step slot of the prepared window * batch + batch element           */
   QC_WS_COND = 6,     /* float  [R, D]     conditioning vectors c, same rows                        */
-  QC_WS_EPS = 7       /* float  [B, C, H, W] last noise estimate                            */
+  QC_WS_EPS = 7,      /* float  [B, C, H, W] last noise estimate                            */
+  QC_WS_QKV_HEADS = 8 /* float  the copy of the last QKV projection the attention kernel reads: Q [B, H, T, d], then
+                         K [B, H, T, d], then V transposed [B, H, dp, Tp] (d = D / H, dp = d rounded up to 16, Tp = T
+                         rounded up to 64; the keys of each group of 32 interleaved in units of 4: key t sits at
+                         (t & ~31) | (((u & 3) << 1 | u >> 2) << 2) | (t & 3), u = (t >> 2) & 7); B = max_batch   */
 };
 
 /* The network: a class-conditional DiT (the architecture the paper evaluates,
@@ -233,8 +237,8 @@ int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out);
  * copied.  mask = NULL restores the interval rule. */
 int qc_set_cache_mask(qc_ctx *ctx, const unsigned char *mask, int steps);
 
-/* Inspection aid: when on, full blocks also write the QKV projection as fp32 into the
- * QC_WS_QKV buffer (the attention kernel itself reads an fp16 high/low split of it). */
+/* Inspection aid: when on, full blocks also write the QKV projection row-major into the
+ * QC_WS_QKV buffer (the attention kernel itself reads head-major copies of the same fp32 values). */
 int qc_keep_qkv_f32(qc_ctx *ctx, int on);
 
 /* Noise estimate of the whole network at timestep t.  x: dev [n_labels, C, H, W],

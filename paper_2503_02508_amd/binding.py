@@ -25,7 +25,7 @@ lib = C.CDLL(LIB_PATH)
 QC_FULL, QC_CACHED = 0, 1
 QC_CACHE_ATTN, QC_CACHE_MLP = 0, 1
 SITES = ("ada", "qkv", "proj", "fc1", "fc2")
-WS = {"tokens": 0, "qact_ln": 1, "qact_attn": 2, "qact_mlp": 3, "qkv": 4, "mod": 5, "cond": 6, "eps": 7}
+WS = {"tokens": 0, "qact_ln": 1, "qact_attn": 2, "qact_mlp": 3, "qkv": 4, "mod": 5, "cond": 6, "eps": 7, "qkv_heads": 8}
 
 vp, i32, f32, f64, sz = C.c_void_p, C.c_int, C.c_float, C.c_double, C.c_size_t
 

@@ -92,9 +92,9 @@ struct qc_ctx {
   float *eps_ref;      // noise prediction of the un-quantised reference forward (VC fitting)
   double *vcfit_work;  // per-plane partial sums of the VC fit [max_batch * C][2]
   int8_t *silu_q, *qa_ln, *qa_attn, *qa_mlp;
-  _Float16 *qkv16;            // fp16 (high, low) Q, K words [B,H,T,hd] and V^T halves [B,H,DP,Tp] for the attention kernel
-  long long qkv_part_stride, qkv_v_stride;   // words per Q / K array, halves per V^T array
-  size_t qkv16_bytes;
+  float *qkv_hm;              // float32 Q, K [B,H,T,hd] and V^T [B,H,DP,Tp] (head-major) for the attention kernel
+  long long qkv_part_stride;  // elements per Q / K array
+  size_t qkv_hm_bytes;
   int DP, Tp;
   int win_rows;               // row capacity of cond / fmod / mod / silu_q (per block for the last two)
   bool keep_qkv_f32 = false;
@@ -188,6 +188,8 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
         q.bias = ada_bias ? ada_bias + l * 6 * D : nullptr;
       } else {
         q.q = a.take<char>(weight_bytes(d, Ns[s], Ks[s]));
+        // second copy in MFMA fragment order for the large-M GEMM (shapes its loop covers)
+        if (Ns[s] % 32 == 0 && Ks[s] % 128 == 0) q.qt = a.take<char>(weight_bytes(d, Ns[s], Ks[s]));
         q.scale = a.take<float>(Ns[s]);
         q.wsum = a.take<int32_t>(Ns[s]);
         q.bias = a.take<float>(Ns[s]);
@@ -209,8 +211,8 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
   int8_t *silu_q = a.take<int8_t>(L * WR * D), *qa_ln = a.take<int8_t>(M * D), *qa_attn = a.take<int8_t>(M * D);
   int8_t *qa_mlp = a.take<int8_t>(M * R);
   const size_t hd = D / d.heads, DP = (hd + 15) / 16 * 16, Tp = (T + 63) / 64 * 64;
-  const size_t part = B * d.heads * T * hd, vpart = B * d.heads * DP * Tp;   // part: 32-bit words = 2 halves each
-  _Float16 *qkv16 = a.take<_Float16>(4 * part + 2 * vpart);
+  const size_t part = B * d.heads * T * hd, vpart = B * d.heads * DP * Tp;
+  float *qkv_hm = a.take<float>(2 * part + vpart);
   float *cal_h = a.take<float>(T * D), *cal_o = a.take<float>(T * D), *cal_a = a.take<float>(T * D);
   float *cal_u = a.take<float>(T * R), *cal_mod = a.take<float>(6 * D);
   int *cal_slots = a.take<int>(L * QC_NUM_SITES * 2), *cal_label = a.take<int>(4);
@@ -223,8 +225,8 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
     c->tokens = tokens; c->qkv = qkv; c->eps = eps; c->silu_q = silu_q; c->qa_ln = qa_ln; c->qa_attn = qa_attn;
     c->qa_mlp = qa_mlp; c->cal_h = cal_h; c->cal_o = cal_o; c->cal_a = cal_a; c->cal_u = cal_u; c->cal_mod = cal_mod;
     c->cal_slots = cal_slots; c->cal_label = cal_label; c->eps_ref = eps_ref; c->vcfit_work = vcfit_work;
-    c->qkv16 = qkv16; c->qkv_part_stride = (long long)part; c->qkv_v_stride = (long long)vpart;
-    c->qkv16_bytes = (4 * part + 2 * vpart) * sizeof(_Float16); c->DP = (int)DP; c->Tp = (int)Tp;
+    c->qkv_hm = qkv_hm; c->qkv_part_stride = (long long)part;
+    c->qkv_hm_bytes = (2 * part + vpart) * sizeof(float); c->DP = (int)DP; c->Tp = (int)Tp;
     c->win_rows = (int)WR;
   }
   return (a.off + 255) & ~size_t(255);
@@ -313,7 +315,7 @@ int qc_load_weights_f32(qc_ctx *ctx, const qc_weights_f32 *w, void *stream) {
       {ctx->fada_b, w->fada_b, 2 * D}, {ctx->flin_w, w->flin_w, O * D}, {ctx->flin_b, w->flin_b, O}};
   for (auto &c : cp) QC_HIP(hipMemcpyAsync(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToDevice, st));
   // padding features / keys of the fp16 attention operands are never written afterwards and must read as zero
-  QC_HIP(hipMemsetAsync(ctx->qkv16, 0, ctx->qkv16_bytes, st));
+  QC_HIP(hipMemsetAsync(ctx->qkv_hm, 0, ctx->qkv_hm_bytes, st));
   for (int l = 0; l < ctx->L; ++l) {
     const qc_block_weights_f32 &b = w->blocks[l];
     const float *ws[QC_NUM_SITES] = {b.ada_w, b.qkv_w, b.proj_w, b.fc1_w, b.fc2_w};
@@ -321,6 +323,7 @@ int qc_load_weights_f32(qc_ctx *ctx, const qc_weights_f32 *w, void *stream) {
     for (int s = 0; s < QC_NUM_SITES; ++s) {
       LinearQ &q = ctx->blk[l].lin[s];
       QC_HIP(launch_quantize_weight(ws[s], q.N, q.K, ctx->d.weight_bits, q.q, q.scale, q.wsum, st));
+      if (q.qt) QC_HIP(launch_tile_weight(q.q, q.qt, q.N, q.K, ctx->d.weight_bits, st));
       QC_HIP(hipMemcpyAsync(q.bias, bs[s], (size_t)q.N * sizeof(float), hipMemcpyDeviceToDevice, st));
     }
   }
@@ -477,13 +480,12 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
   const bool w4 = ctx->d.weight_bits == 4;
   const BlockQ &bq = ctx->blk[l];
   int8_t *qa_ln = ctx->qa_ln + row0 * D, *qa_attn = ctx->qa_attn + row0 * D, *qa_mlp = ctx->qa_mlp + row0 * R;
-  unsigned *q_words = (unsigned *)ctx->qkv16 + (size_t)sb.b0 * ctx->H * T * ctx->hd;
-  unsigned *k_words = q_words + ctx->qkv_part_stride;
-  _Float16 *vt_hi = ctx->qkv16 + 4 * ctx->qkv_part_stride + (size_t)sb.b0 * ctx->H * ctx->DP * ctx->Tp;
-  _Float16 *vt_lo = vt_hi + ctx->qkv_v_stride;
+  float *q32 = ctx->qkv_hm + (size_t)sb.b0 * ctx->H * T * ctx->hd;
+  float *k32 = q32 + ctx->qkv_part_stride;
+  float *vt32 = ctx->qkv_hm + 2 * ctx->qkv_part_stride + (size_t)sb.b0 * ctx->H * ctx->DP * ctx->Tp;
   auto base = [&](const LinearQ &q, const int8_t *A, int K, int site) {
     GemmArgs a{};
-    a.A = A; a.W = q.q; a.w_scale = q.scale; a.wsum = q.wsum; a.bias = q.bias;
+    a.A = A; a.W = q.q; a.Wt = q.qt; a.w_scale = q.scale; a.wsum = q.wsum; a.bias = q.bias;
     a.M = M; a.N = q.N; a.K = K; a.lda = K; a.w4 = w4; a.a_qp = qp + site;
     return a;
   };
@@ -496,17 +498,15 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_QKV], qa_ln, D, QC_SITE_QKV);
-    a.q_words = q_words; a.k_words = k_words; a.vt_hi = vt_hi; a.vt_lo = vt_lo;
+    a.q32 = q32; a.k32 = k32; a.vt32 = vt32;
     a.heads = ctx->H; a.hd = ctx->hd; a.DP = ctx->DP; a.Tp = ctx->Tp; a.rows_per_batch = T;
-    a.q_scale = 1.4426950408889634f / std::sqrt((float)ctx->hd);     // log2(e) / sqrt(d): the softmax runs in base 2
-    a.y = ctx->qkv + row0 * 3 * D; a.ldy = 3 * D;      // float32 Q | K | V: the attention kernel's exact path reads it
+    if (ctx->keep_qkv_f32) { a.y = ctx->qkv + row0 * 3 * D; a.ldy = 3 * D; }      // row-major copy for inspection
     QC_PROF(QC_K_GEMM_QKV);
     QC_HIP(launch_gemm(a, EPI_QKV, 1, st, QC_SITE_QKV));
   }
   {
     QC_PROF(QC_K_ATTENTION);
-    QC_HIP(launch_attention_f16(q_words, k_words, vt_hi, vt_lo, B, T, ctx->Tp, ctx->H, ctx->hd, ctx->DP, qp + QC_SITE_PROJ,
-                                qa_attn, ctx->qkv + row0 * 3 * D, st));
+    QC_HIP(launch_attention_f16(q32, k32, vt32, B, T, ctx->Tp, ctx->H, ctx->hd, ctx->DP, qp + QC_SITE_PROJ, qa_attn, st));
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_PROJ], qa_attn, D, QC_SITE_PROJ);
@@ -619,6 +619,7 @@ int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out) 
     case QC_WS_MOD: p = ctx->mod; n = (size_t)ctx->L * ctx->win_rows * 6 * D * 4; break;
     case QC_WS_COND: p = ctx->cond; n = (size_t)ctx->win_rows * D * 4; break;
     case QC_WS_EPS: p = ctx->eps; n = B * ctx->C * ctx->d.latent_h * ctx->d.latent_w * 4; break;
+    case QC_WS_QKV_HEADS: p = ctx->qkv_hm; n = ctx->qkv_hm_bytes; break;
     default: QC_FAIL(QC_ERR_RANGE, "unknown workspace selector %d", which);
   }
   *ptr_out = p;

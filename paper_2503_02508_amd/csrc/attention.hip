@@ -171,15 +171,15 @@ hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const
 // ---------------------------------------------------------------------------
 // Production kernel: the same online-softmax tiling on the fp16 matrix cores
 // (v_mfma_f32_16x16x32_f16, 16x the fp32 MFMA rate).  Every operand is carried
-// as an fp16 pair (high part + low part, ~22 significant bits, written by the
-// QKV GEMM epilogue) and every product is formed as hi*hi + hi*lo + lo*hi with
-// fp32 accumulation, which keeps the result at fp32 accuracy so that the int8
-// codes quantised from it stay the oracle's.  The probabilities are split the
-// same way after the exponential.
+// as an fp16 pair (high part + low part, ~22 significant bits, split when a tile
+// is staged) and every product is formed as hi*hi + hi*lo + lo*hi with fp32
+// accumulation, which keeps the result at fp32 accuracy so that the int8 codes
+// quantised from it stay the oracle's.  The probabilities are split the same
+// way after the exponential.
 //
-// Global layouts: Q and K as one 32-bit (hi | lo << 16) word per element,
-// [B, H, T, d]; V transposed, separate hi and lo arrays [B, H, DPv, Tp] with the
-// keys of each group of 32 interleaved in units of 4 (vt_pos).
+// Global layouts (float32, written by the QKV GEMM epilogue): Q and K
+// [B, H, T, d]; V transposed [B, H, DPv, Tp] with the keys of each group of 32
+// interleaved in units of 4 (vt_pos).
 //
 // Layout facts used (16x16x32 f16): lane l supplies A[row l%16][k 8(l/16)..+7]
 // and B[k 8(l/16)..+7][col l%16] as 8 halves; result register r of lane l is
@@ -199,12 +199,22 @@ typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
 
-// four (hi | lo << 16) words -> four hi halves, four lo halves
-__device__ __forceinline__ void unpack_pairs(v4u p, v2u &hi, v2u &lo) {
-  hi.x = __builtin_amdgcn_perm(p.y, p.x, 0x05040100u);
-  hi.y = __builtin_amdgcn_perm(p.w, p.z, 0x05040100u);
-  lo.x = __builtin_amdgcn_perm(p.y, p.x, 0x07060302u);
-  lo.y = __builtin_amdgcn_perm(p.w, p.z, 0x07060302u);
+// four float32 values -> four hi halves (the value rounded to fp16) and four lo halves (what the rounding left, again
+// rounded to fp16): hi + lo carries about 22 significant bits.  The hi half that is stored and the one that is
+// subtracted must be the same bits: the conversion is therefore made opaque to the compiler, which otherwise forms
+// the stored halves with the packed conversion instruction and the subtracted ones with the scalar one, and the two
+// were observed to disagree on ties (the sum was then off by one unit of the hi half).
+__device__ __forceinline__ void split_pairs(v4f v, v2u &hi, v2u &lo) {
+  unsigned hb[4], lb[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    hb[e] = __builtin_bit_cast(unsigned short, (_Float16)v[e]);
+    asm volatile("" : "+v"(hb[e]));
+    const float hf = (float)__builtin_bit_cast(_Float16, (unsigned short)hb[e]);
+    lb[e] = __builtin_bit_cast(unsigned short, (_Float16)(v[e] - hf));
+  }
+  hi = (v2u){hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16)};
+  lo = (v2u){lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16)};
 }
 
 // NCH feature chunks of 32 (operand width), NEB feature blocks of 16 that hold real features, QB query blocks of 16 per
@@ -212,10 +222,9 @@ __device__ __forceinline__ void unpack_pairs(v4u p, v2u &hi, v2u &lo) {
 // twice as many workgroups with half the MFMA chain each, for launches that would leave compute units idle.  The
 // arithmetic per query is the same in both.
 template <int NCH, int NEB, int QB>
-__global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *__restrict__ Qp, const unsigned *__restrict__ Kp,
-                                                            const _Float16 *__restrict__ Vh, const _Float16 *__restrict__ Vl, int T,
-                                                            int Tp, int H, int hd, int DPv, const QParam *qp,
-                                                            int8_t *__restrict__ q_out, const float *__restrict__ qkv32) {
+__global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__restrict__ Qp, const float *__restrict__ Kp,
+                                                            const float *__restrict__ Vt, int T, int Tp, int H, int hd, int DPv,
+                                                            float q_mul, const QParam *qp, int8_t *__restrict__ q_out) {
   constexpr int DP = 32 * NCH;
   constexpr int KROW = DP + 8;    // halves per K row in LDS (16 bytes of padding)
   constexpr int VROW = 64 + 8;    // halves per V^T row in LDS
@@ -251,8 +260,8 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
     l_run[j] = 0.0f;
   }
 
-  v4u kreg[KCH];
-  v4u vreg[2][VCH];
+  v4f kreg[KCH];
+  v4f vreg[2][VCH];
   // key row and feature offset of this thread's K chunks (the same for every tile: no divisions in the loop).
   // Loads never branch: a chunk index beyond the tile is clamped to the last chunk and a key beyond T to key
   // T-1 (finite values that the ragged-tile mask or the store predicate discards), so that all loads of a tile
@@ -270,13 +279,13 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   auto load_tile = [&](int k0) {
 #pragma unroll
     for (int u = 0; u < KCH; ++u)
-      kreg[u] = *(const v4u *)(Kp + tok_base + (long long)min(k0 + kr[u], T - 1) * hd + kc[u]);
+      kreg[u] = *(const v4f *)(Kp + tok_base + (long long)min(k0 + kr[u], T - 1) * hd + kc[u]);
 #pragma unroll
     for (int u = 0; u < VCH; ++u) {
       const int i = min(tid + 256 * u, NEB * 16 * 8 - 1);
       const int e = i >> 3, c8 = (i & 7) * 8;
-      vreg[0][u] = *(const v4u *)(Vh + vt_base + (long long)e * Tp + k0 + c8);
-      vreg[1][u] = *(const v4u *)(Vl + vt_base + (long long)e * Tp + k0 + c8);
+      vreg[0][u] = *(const v4f *)(Vt + vt_base + (long long)e * Tp + k0 + c8);
+      vreg[1][u] = *(const v4f *)(Vt + vt_base + (long long)e * Tp + k0 + c8 + 4);
     }
   };
   auto store_tile = [&]() {
@@ -284,7 +293,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
     for (int u = 0; u < KCH; ++u) {
       if (kvalid[u]) {
         v2u hi, lo;
-        unpack_pairs(kreg[u], hi, lo);
+        split_pairs(kreg[u], hi, lo);
         *(v2u *)(Ksh[0] + kr[u] * KROW + kc[u]) = hi;
         *(v2u *)(Ksh[1] + kr[u] * KROW + kc[u]) = lo;
       }
@@ -294,8 +303,11 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
       const int i = tid + 256 * u;
       if (i < NEB * 16 * 8) {
         const int e = i >> 3, c8 = (i & 7) * 8;
-        *(v4u *)(Vsh[0] + e * VROW + c8) = vreg[0][u];
-        *(v4u *)(Vsh[1] + e * VROW + c8) = vreg[1][u];
+        v2u h0, l0, h1, l1;
+        split_pairs(vreg[0][u], h0, l0);
+        split_pairs(vreg[1][u], h1, l1);
+        *(v4u *)(Vsh[0] + e * VROW + c8) = (v4u){h0.x, h0.y, h1.x, h1.y};
+        *(v4u *)(Vsh[1] + e * VROW + c8) = (v4u){l0.x, l0.y, l1.x, l1.y};
       }
     }
   };
@@ -306,16 +318,16 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   {
     // all query loads are issued before any is used; rows beyond T read row T-1 (their results are never
     // stored), features beyond d read the last chunk and are zeroed below
-    v4u qraw[QB][NCH][2];
+    v4f qraw[QB][NCH][2];
 #pragma unroll
     for (int j = 0; j < QB; ++j) {
       q_row[j] = blockIdx.y * (64 * QB) + wave * (16 * QB) + j * 16 + ql;
-      const unsigned *src = Qp + tok_base + (long long)min(q_row[j], T - 1) * hd;
+      const float *src = Qp + tok_base + (long long)min(q_row[j], T - 1) * hd;
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
         const int f = 32 * c + 8 * g;
-        qraw[j][c][0] = *(const v4u *)(src + min(f, hd - 4));
-        qraw[j][c][1] = *(const v4u *)(src + min(f + 4, hd - 4));
+        qraw[j][c][0] = *(const v4f *)(src + min(f, hd - 4));
+        qraw[j][c][1] = *(const v4f *)(src + min(f + 4, hd - 4));
       }
     }
 #pragma unroll
@@ -324,8 +336,8 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
       for (int c = 0; c < NCH; ++c) {
         const int f = 32 * c + 8 * g;
         v2u h0, l0, h1, l1;
-        unpack_pairs(qraw[j][c][0], h0, l0);
-        unpack_pairs(qraw[j][c][1], h1, l1);
+        split_pairs(qraw[j][c][0] * q_mul, h0, l0);     // queries pre-scaled by log2(e) / sqrt(d): the softmax runs in base 2
+        split_pairs(qraw[j][c][1] * q_mul, h1, l1);
         if (f >= hd) { h0 = (v2u){0, 0}; l0 = h0; }
         if (f + 4 >= hd) { h1 = (v2u){0, 0}; l1 = h1; }
         v4u hh = {h0.x, h0.y, h1.x, h1.y}, ll = {l0.x, l0.y, l1.x, l1.y};
@@ -467,7 +479,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
       for (int r = 0; r < 4; ++r) {
         const float qv = v[r] / qs, rr = rintf(qv);
         c[r] = (int)fminf(fmaxf(rr + qz, -128.f), 127.f);
-        if (qkv32 && q_row[j] < T && f + r < hd && fabsf(fabsf(qv - rr) - 0.5f) < fmaf(tol_q, fabsf(qv), tol_0)) {
+        if (q_row[j] < T && f + r < hd && fabsf(fabsf(qv - rr) - 0.5f) < fmaf(tol_q, fabsf(qv), tol_0)) {
           const int slot = atomicAdd(fix_cnt, 1);
           if (slot < FIX_CAP) {
             fix_ent[2 * slot] = qloc;
@@ -484,8 +496,8 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   {
     // softmax(q K^T / sqrt(d)) V[:, feature] in float64 for every queued output
     const int nfix = min(*fix_cnt, FIX_CAP);
-    const int ld = 3 * D;
-    const float *base = qkv32 + (size_t)b * T * ld + (size_t)h * hd;
+    const int ld = hd;
+    const float *qbase = Qp + tok_base, *kbase = Kp + tok_base;
     const double rs = 1.0 / sqrt((double)hd);
     // One wavefront per queued output.  A key row is shared by a pair of lanes (even lane: first half of its 16-byte
     // chunks, odd lane: second half); a lane pair takes four keys per pass and all their loads are issued at once, so
@@ -497,7 +509,8 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
     const int half = lane & 1, kl = lane >> 1;    // 32 lane pairs
     for (int fi = wave; fi < nfix; fi += 4) {
       const int qloc = fix_ent[2 * fi], feat = fix_ent[2 * fi + 1];
-      const float *qr = base + (size_t)(q_first + qloc) * ld;
+      const float *qr = qbase + (size_t)(q_first + qloc) * ld;
+      const float *vrow = Vt + vt_base + (size_t)feat * Tp;       // V^T row of the feature, keys in vt_pos order
       v4f qf[NCH2];
 #pragma unroll
       for (int c = 0; c < NCH2; ++c) {
@@ -511,10 +524,11 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
         float vv[KU];
 #pragma unroll
         for (int u = 0; u < KU; ++u) {
-          const float *kr = base + (size_t)min(k0 + 32 * u + kl, T - 1) * ld;
+          const int key = min(k0 + 32 * u + kl, T - 1);
+          const float *kr = kbase + (size_t)key * ld;
 #pragma unroll
-          for (int c = 0; c < NCH2; ++c) kv[u][c] = *(const v4f *)(kr + D + min(4 * (half * NCH2 + c), hd - 4));
-          vv[u] = kr[2 * D + feat];
+          for (int c = 0; c < NCH2; ++c) kv[u][c] = *(const v4f *)(kr + min(4 * (half * NCH2 + c), hd - 4));
+          vv[u] = vrow[vt_pos(key)];
         }
         double sv[KU];
         double pm = -INFINITY;
@@ -575,27 +589,22 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const unsigned *_
   }
 }
 
-hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
-                                int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, const float *qkv32,
-                                hipStream_t st) {
+hipError_t launch_attention_f16(const float *q32, const float *k32, const float *vt32, int B, int T, int Tp, int H, int hd,
+                                int DPv, const QParam *qp, int8_t *q_out, hipStream_t st) {
   const int neb = (hd + 15) / 16, nch = (hd + 31) / 32;
   if (hd > 80 || hd % 4) return hipErrorInvalidValue;      // K prefetch registers are sized for d <= 80
-  // one query block per wavefront when two would leave compute units without a workgroup (QC_ATT_QB forces 1 or 2)
-  static int forced = -1;
-  if (forced < 0) {
-    const char *e = getenv("QC_ATT_QB");
-    forced = e ? atoi(e) : 0;
-  }
-  const int qb = forced == 1 || forced == 2 ? forced : (B * H * ((T + 127) / 128) < 256 ? 1 : 2);
+  const float q_mul = 1.4426950408889634f / std::sqrt((float)hd);     // log2(e) / sqrt(d)
+  // one query block per wavefront when two would leave compute units without a workgroup
+  const int qb = B * H * ((T + 127) / 128) < 256 ? 1 : 2;
   dim3 grid(B * H, (T + 64 * qb - 1) / (64 * qb));
 #define QC_ATT(NCH, NEB)                                                                                                    \
   do {                                                                                                                      \
     if (qb == 1)                                                                                                            \
-      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 1>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, \
-                         H, hd, DPv, qp, q_out, qkv32);                                                                     \
+      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 1>), grid, dim3(256), 0, st, q32, k32, vt32, T, Tp, H, hd, DPv,    \
+                         q_mul, qp, q_out);                                                                                 \
     else                                                                                                                    \
-      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 2>), grid, dim3(256), 0, st, q_words, k_words, vt_hi, vt_lo, T, Tp, \
-                         H, hd, DPv, qp, q_out, qkv32);                                                                     \
+      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 2>), grid, dim3(256), 0, st, q32, k32, vt32, T, Tp, H, hd, DPv,    \
+                         q_mul, qp, q_out);                                                                                 \
   } while (0)
   if (nch == 1 && neb == 1) QC_ATT(1, 1);
   else if (nch == 1) QC_ATT(1, 2);

@@ -107,6 +107,374 @@ __device__ __forceinline__ int quant_code(float v, float s, float inv_s, float z
   return (int)r;
 }
 
+// Epilogue of a tile: acc[i][j] is the 32 x 32 block (i along the rows m of the activations, j along the output
+// columns n) of wavefront (wave / WN, wave % WN); for EPI_GELU_Q the weights were the first MFMA operand (register
+// index runs along n), otherwise the activations were (register index runs along m).  smem: the workgroup's dynamic
+// LDS, free for reuse (every wavefront is past its last fragment read).
+// FAST: the launcher has checked that every tile is interior along m and lies in one batch element (and, for the QKV
+// scatter, the alignment its staged path needs); the general paths are then not compiled into the kernel.
+template <int BM, int BN, int WM, int WN, int EPI, bool FAST = false>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM / WM / 32][BN / WN / 32], unsigned char *smem,
+                                              const int m0, const int n0, const int z) {
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NT = 64 * WM * WN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
+  const int ncover = p.sel_D ? 2 * p.sel_D : p.N;
+  float a_s = p.a_scale;
+  int a_z = p.a_zp;
+  if (p.a_qp) {
+    QParam q = p.a_qp[(long long)z * p.zs_qp];
+    a_s = q.s;
+    a_z = q.z;
+  }
+  const float *w_scale = p.w_scale + (long long)z * p.zs_vecN;
+  const int32_t *wsum = p.wsum + (long long)z * p.zs_vecN;
+  const float *bias = p.bias ? p.bias + (long long)z * p.zs_vecN : nullptr;
+
+  if (EPI == EPI_GELU_Q) {
+    // per-column constants into LDS: v = sc[n] * float(acc - zw[n]) + bs[n]
+    float *c_sc = (float *)smem;
+    int *c_zw = (int *)(smem + BN * 4);
+    float *c_bs = (float *)(smem + BN * 8);
+    unsigned char *stage = smem + BN * 12;             // [BM][BN + 16] codes
+    constexpr int SROW = BN + 16;
+    // Elements whose fast evaluation lands too close to a rounding boundary of Eq. 1 to be trusted are queued here and
+    // decided again in float64 (gelu_code_exact): the codes are then those of exact arithmetic on the accumulators.
+    int *fix_cnt = (int *)(stage + BM * SROW);
+    int *fix_ent = fix_cnt + 4;                        // [GELU_FIX_CAP][4]: accumulator minus zero-point term, column, row
+    if (tid == 0) *fix_cnt = 0;
+    if (tid < BN) {
+      const int n = n0 + tid;
+      const bool ok = n < p.N;
+      c_sc[tid] = ok ? a_s * w_scale[n] : 0.0f;
+      c_zw[tid] = ok ? a_z * wsum[n] : 0;
+      c_bs[tid] = (ok && bias) ? bias[n] : 0.0f;
+    }
+    __syncthreads();
+    const QParam oq = *p.o_qp;
+    const float o_s = oq.s, o_inv = 1.0f / oq.s, o_z = (float)oq.z;
+    // bound of the fast path's error in units of the output step: 1.5e-6 |v| / s covers the float32 dequantisation, the
+    // exp2 / reciprocal estimates and the refined quotient with a margin of 2; 2e-6 covers the bias rounding
+    const float tol_v = 1.5e-6f * o_inv;
+    const int g = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int nl = wn0 + j * 32 + rg * 8 + g * 4;       // 4 consecutive columns of this lane
+        const v4f sc = *(const v4f *)(c_sc + nl);
+        const v4i zw = *(const v4i *)(c_zw + nl);
+        const v4f bs = *(const v4f *)(c_bs + nl);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          int code[4];
+          bool doubt[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int corr = acc[i][j][rg * 4 + e] - zw[e];
+            const float v = fmaf(sc[e], (float)corr, bs[e]);
+            const float gv = gelu_tanh(v);
+            float q = gv * o_inv;
+            q = fmaf(fmaf(-q, o_s, gv), o_inv, q);
+            const float r = __builtin_rintf(q);
+            code[e] = (int)fminf(fmaxf(r + o_z, -128.0f), 127.0f);
+            doubt[e] = fabsf(fabsf(q - r) - 0.5f) < fmaf(tol_v, fabsf(v), 2e-6f);
+          }
+          // one branch per four outputs; taken by a wavefront about once in a hundred times
+          if (doubt[0] | doubt[1] | doubt[2] | doubt[3]) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (doubt[e]) {
+                const int slot = atomicAdd(fix_cnt, 1);
+                if (slot < GELU_FIX_CAP) {
+                  fix_ent[slot * 4 + 0] = acc[i][j][rg * 4 + e] - zw[e];
+                  fix_ent[slot * 4 + 1] = nl + e;
+                  fix_ent[slot * 4 + 2] = wm0 + i * 32 + (lane & 31);
+                }
+              }
+          }
+          const unsigned w = (unsigned)(code[0] & 0xFF) | ((unsigned)(code[1] & 0xFF) << 8) |
+                             ((unsigned)(code[2] & 0xFF) << 16) | ((unsigned)(code[3] & 0xFF) << 24);
+          *(unsigned *)(stage + (wm0 + i * 32 + (lane & 31)) * SROW + nl) = w;
+        }
+      }
+    }
+    __syncthreads();
+    {
+      const int nfix = min(*fix_cnt, GELU_FIX_CAP);
+      for (int f = tid; f < nfix; f += NT) {
+        const int corr = fix_ent[f * 4 + 0], nl = fix_ent[f * 4 + 1], row = fix_ent[f * 4 + 2];
+        const int n = n0 + nl;
+        if (n < p.N) stage[row * SROW + nl] = (unsigned char)gelu_code_exact(corr, a_s, w_scale[n], bias ? bias[n] : 0.0f, o_s, oq.z);
+      }
+      if (nfix) __syncthreads();
+    }
+    // coalesced write-out: 16-byte chunks, 8 lanes cover a 128-byte row segment
+    constexpr int CH = BN / 16;
+    for (int c = tid; c < BM * CH; c += NT) {
+      const int r = c / CH, cc = (c % CH) * 16;
+      const int m = m0 + r, n = n0 + cc;
+      if (m >= p.M || n >= p.N) continue;
+      int8_t *dst = p.q_out + (long long)m * p.ldq + n;
+      if (n + 16 <= p.N) {
+        *(v4i *)dst = *(const v4i *)(stage + r * SROW + cc);
+      } else {
+        for (int e = 0; n + e < p.N; ++e) dst[e] = (int8_t)stage[r * SROW + cc + e];
+      }
+    }
+    return;
+  }
+
+  if (EPI == EPI_QKV) {
+    // float32 values scattered to the head-major layouts of the attention kernel: Q and K [B, H, T, hd], V transposed
+    // and key-permuted [B, H, DP, Tp]; p.y, when set, also receives them row-major ([M, 3 D], for inspection)
+    const int T = p.rows_per_batch, D = p.N / 3;
+    const bool fast_t = (T % 4) == 0;
+    const bool tile_one_batch = (T % BM) == 0;      // then every row of the tile belongs to batch element m0 / T
+    const int b_tile = m0 / T;
+    constexpr int HN = 128;                                   // the tile is handled in column halves of 128
+    if (FAST || (BM == 128 && BN % HN == 0 && (BN / WN) <= HN && tile_one_batch && fast_t && m0 + BM <= p.M && D % HN == 0 &&
+                 (p.hd & 3) == 0 && (p.Tp & 7) == 0)) {
+      // Tile inside one batch element, every 128 columns inside one of Q, K, V: the values go through LDS (free after
+      // the K loop) and leave as 16-byte stores along the contiguous direction of their layout (Q / K: features of a
+      // token and head; V^T: tokens of a feature).
+      const int tb = m0 - b_tile * T;                         // first token of the tile
+#pragma unroll
+      for (int hn = 0; hn < BN / HN; ++hn) {
+        const int n0h = n0 + hn * HN;                         // first column of this half
+        if (n0h >= p.N) break;
+        const bool mine = wn0 / HN == hn;                     // this wavefront's columns lie in the half
+        const int part = n0h / D;
+        if (hn) __syncthreads();                              // the previous half has left the staging area
+        float *stage = (float *)smem;
+        constexpr int SR = HN + 4;                            // Q / K: floats per staged token row
+        constexpr int VR = BM + 4;                            // V^T: floats per staged feature row
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if (!mine) continue;
+          const int nl = wn0 - hn * HN + j * 32 + (lane & 31);
+          const double sc = (double)a_s * (double)w_scale[n0h + nl];
+          const int zw = a_z * wsum[n0h + nl];
+          const double bs = bias ? (double)bias[n0h + nl] : 0.0;
+          float *ycol = p.y ? p.y + (long long)m0 * p.ldy + n0h + nl : nullptr;     // 32 lanes write 128 contiguous bytes
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+              const int ml = wm0 + i * 32 + rg * 8 + (lane >> 5) * 4;
+              v4f v;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                v[q] = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
+                if (ycol) ycol[(unsigned)(ml + q) * (unsigned)p.ldy] = v[q];
+              }
+              if (part < 2) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) stage[(ml + q) * SR + nl] = v[q];
+              } else {
+                // four consecutive tokens stay together under the key permutation of the V^T rows
+                *(v4f *)(stage + nl * VR + vt_pos(ml)) = v;
+              }
+            }
+            if (TM * TN > 4) __builtin_amdgcn_sched_barrier(0);      // large register tiles: keep the live ranges of a block short
+          }
+        }
+        __syncthreads();
+        if (part < 2) {
+          // thread -> four features cc .. cc + 3 (inside one head: heads start at multiples of hd, a multiple of 4) of
+          // the rows cr, cr + NT / 32, ...
+          const int cr = tid >> 5, cc = (tid & 31) * 4;
+          const int nn = n0h - part * D + cc, h = nn / p.hd, e = nn - h * p.hd;
+          float *dst = (part == 0 ? p.q32 : p.k32) +
+                       ((unsigned)(b_tile * p.heads + h) * (unsigned)T + (unsigned)(tb + cr)) * (unsigned)p.hd + (unsigned)e;
+#pragma unroll
+          for (int q = 0; q < BM * 32 / NT; ++q)
+            *(v4f *)(dst + (unsigned)(q * (NT / 32)) * (unsigned)p.hd) = *(const v4f *)(stage + (cr + q * (NT / 32)) * SR + cc);
+        } else {
+          // thread -> 4 consecutive token positions ch of the features fc, fc + NT / 32, ...
+          const int fc = tid >> 5, ch = (tid & 31) * 4;
+#pragma unroll
+          for (int q = 0; q < HN * 32 / NT; ++q) {
+            const int col = fc + q * (NT / 32);
+            const int nn = n0h - 2 * D + col, h = nn / p.hd, e = nn - h * p.hd;
+            const unsigned o = ((unsigned)(b_tile * p.heads + h) * (unsigned)p.DP + (unsigned)e) * (unsigned)p.Tp + (unsigned)(tb + ch);
+            *(v4f *)(p.vt32 + o) = *(const v4f *)(stage + col * VR + ch);
+          }
+        }
+      }
+      return;
+    }
+    if (FAST) return;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn0 + j * 32 + (lane & 31);
+      if (n >= p.N) continue;
+      const double sc = (double)a_s * (double)w_scale[n];
+      const int zw = a_z * wsum[n];
+      const double bs = bias ? (double)bias[n] : 0.0;
+      const int part = n / D, nn = n - part * D, h = nn / p.hd, e = nn - h * p.hd;
+      float *dqk = part == 0 ? p.q32 : p.k32;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const int mb = m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4;   // 4 consecutive rows mb .. mb+3
+          if (mb >= p.M) continue;
+          v4f v;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
+          const int b0 = tile_one_batch ? b_tile : mb / T, t0 = mb - b0 * T;
+          if (part == 2 && fast_t && mb + 3 < p.M) {
+            // T is a multiple of 4: the four rows are tokens t0 .. t0 + 3 of one batch element, contiguous in V^T
+            *(v4f *)(p.vt32 + ((long long)(b0 * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t0)) = v;
+          } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              if (mb + q >= p.M) continue;
+              int b = b0, t = t0 + q;
+              while (t >= T) { t -= T; ++b; }
+              if (part == 2) p.vt32[((long long)(b * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t)] = v[q];
+              else dqk[((long long)(b * p.heads + h) * T + t) * p.hd + e] = v[q];
+            }
+          }
+          if (p.y) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              if (mb + q < p.M) p.y[(long long)(mb + q) * p.ldy + n] = v[q];
+          }
+        }
+      }
+    }
+    return;
+  }
+
+  if (EPI == EPI_RESID) {
+    // read-modify-write of the residual stream: the loads of a batch of column blocks are all issued
+    // before the first use, so the epilogue pays one memory round trip per batch instead of one per
+    // register group; a batch is the whole tile when its values fit in registers beside the accumulators
+    constexpr int JB = TM * TN <= 4 ? TN : 1, IB = TM * TN <= 4 ? TM : 1;
+    const bool uniform_batch = (p.rows_per_batch % BM) == 0;
+    const int b_uniform = m0 / p.rows_per_batch;
+    if (FAST) {
+      // every row of the tile exists and belongs to batch element b_uniform; N is a multiple of 32, so a wavefront's
+      // 32-column block lies inside the matrix or outside it as a whole
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn0 + j * 32 + (lane & 31);
+        if (n0 + wn0 + j * 32 >= p.N) continue;
+        const double sc = (double)a_s * (double)w_scale[n];
+        const int zw = a_z * wsum[n];
+        const double bs = bias ? (double)bias[n] : 0.0;
+        const float g = p.gate[(long long)b_uniform * p.ld_gate + n];
+        const long long ob = (long long)m0 * p.N + n;
+        float *xcol = p.x + ob;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          float xv[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            xv[r] = xcol[(unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float v = dequant_f32(sc, acc[i][j][r] - zw, bs);
+            const unsigned o = (unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N;
+            if (p.cache_bf16) ((unsigned short *)p.cache_out + ob)[o] = bf16_bits(v);
+            else ((float *)p.cache_out + ob)[o] = v;
+            xcol[o] = fmaf(g, v, xv[r]);
+          }
+          __builtin_amdgcn_sched_barrier(0);                  // one block's values live at a time
+        }
+      }
+      return;
+    }
+    const bool interior = uniform_batch && m0 + BM <= p.M && n0 + BN <= p.N;
+#pragma unroll
+    for (int j0 = 0; j0 < TN; j0 += JB)
+#pragma unroll
+      for (int i0 = 0; i0 < TM; i0 += IB) {
+        float xv[JB][IB][16], gv[JB];
+        double scv[JB], bsv[JB];
+        int zwv[JB];
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+          const int n = min(n0 + wn0 + (j0 + jj) * 32 + (lane & 31), p.N - 1);
+#pragma unroll
+          for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int m = min(m0 + wm0 + (i0 + ii) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), p.M - 1);
+              xv[jj][ii][r] = p.x[(long long)m * p.N + n];
+            }
+          scv[jj] = (double)a_s * (double)w_scale[n];
+          zwv[jj] = a_z * wsum[n];
+          bsv[jj] = bias ? (double)bias[n] : 0.0;
+          gv[jj] = p.gate[(long long)b_uniform * p.ld_gate + n];
+        }
+#pragma unroll
+        for (int jj = 0; jj < JB; ++jj) {
+          const int j = j0 + jj;
+          const int n = n0 + wn0 + j * 32 + (lane & 31);
+          if (interior) {
+            // interior tile inside one batch element: no bounds checks, one gate per column
+#pragma unroll
+            for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int i = i0 + ii;
+                const float v = dequant_f32(scv[jj], acc[i][j][r] - zwv[jj], bsv[jj]);
+                // 32-bit offset inside the tile's rows from one 64-bit base per column
+                const long long ob = (long long)m0 * p.N + n;
+                const unsigned o = (unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N;
+                if (p.cache_bf16) ((unsigned short *)p.cache_out + ob)[o] = bf16_bits(v);
+                else ((float *)p.cache_out + ob)[o] = v;
+                (p.x + ob)[o] = fmaf(gv[jj], v, xv[jj][ii][r]);
+              }
+          } else {
+            if (n >= p.N) continue;
+#pragma unroll
+            for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int i = i0 + ii;
+                const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                if (m >= p.M) continue;
+                const float v = dequant_f32(scv[jj], acc[i][j][r] - zwv[jj], bsv[jj]);
+                const long long o = (long long)m * p.N + n;
+                if (p.cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
+                else ((float *)p.cache_out)[o] = v;
+                const float g = p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
+                p.x[o] = fmaf(g, v, xv[jj][ii][r]);
+              }
+          }
+        }
+        if (TM * TN > 4) __builtin_amdgcn_sched_barrier(0);      // large register tiles: one batch's values live at a time
+      }
+    return;
+  }
+
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int jl = n0 + wn0 + j * 32 + (lane & 31);
+    if (jl >= ncover) continue;
+    const int n = map_col(jl, p.sel_D);
+    const double sc = (double)a_s * (double)w_scale[n];
+    const int zw = a_z * wsum[n];
+    const double bs = bias ? (double)bias[n] : 0.0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (m >= p.M) continue;
+        const int a = acc[i][j][r];
+        float *y = p.y + (long long)z * p.zs_out;
+        y[(long long)m * p.ldy + n] = dequant_f32(sc, a - zw, bs);
+        if (p.acc_out) p.acc_out[(long long)m * p.N + n] = a;
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_i8_kernel(GemmArgs p) {
   constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -370,392 +738,203 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && BM * BN <= 128 * 128
     }
   }
 
-  // ------------------------------------------------------------ epilogue
-  float a_s = p.a_scale;
-  int a_z = p.a_zp;
-  if (p.a_qp) {
-    QParam q = p.a_qp[(long long)z * p.zs_qp];
-    a_s = q.s;
-    a_z = q.z;
-  }
-  const float *w_scale = p.w_scale + (long long)z * p.zs_vecN;
-  const int32_t *wsum = p.wsum + (long long)z * p.zs_vecN;
-  const float *bias = p.bias ? p.bias + (long long)z * p.zs_vecN : nullptr;
+  gemm_epilogue<BM, BN, WM, WN, EPI>(p, acc, smem, m0, n0, z);
+}
 
-  if (EPI == EPI_GELU_Q) {
-    // per-column constants into LDS: v = sc[n] * float(acc - zw[n]) + bs[n]
-    float *c_sc = (float *)smem;
-    int *c_zw = (int *)(smem + BN * 4);
-    float *c_bs = (float *)(smem + BN * 8);
-    unsigned char *stage = smem + BN * 12;             // [BM][BN + 16] codes
-    constexpr int SROW = BN + 16;
-    // Elements whose fast evaluation lands too close to a rounding boundary of Eq. 1 to be trusted are queued here and
-    // decided again in float64 (gelu_code_exact): the codes are then those of exact arithmetic on the accumulators.
-    int *fix_cnt = (int *)(stage + BM * SROW);
-    int *fix_ent = fix_cnt + 4;                        // [GELU_FIX_CAP][4]: accumulator minus zero-point term, column, row
-    if (tid == 0) *fix_cnt = 0;
-    if (tid < BN) {
-      const int n = n0 + tid;
-      const bool ok = n < p.N;
-      c_sc[tid] = ok ? a_s * w_scale[n] : 0.0f;
-      c_zw[tid] = ok ? a_z * wsum[n] : 0;
-      c_bs[tid] = (ok && bias) ? bias[n] : 0.0f;
-    }
-    __syncthreads();
-    const QParam oq = *p.o_qp;
-    const float o_s = oq.s, o_inv = 1.0f / oq.s, o_z = (float)oq.z;
-    // bound of the fast path's error in units of the output step: 1.5e-6 |v| / s covers the float32 dequantisation, the
-    // exp2 / reciprocal estimates and the refined quotient with a margin of 2; 2e-6 covers the bias rounding
-    const float tol_v = 1.5e-6f * o_inv;
-    const int g = lane >> 5;
+// ---------------------------------------------------------------------------------------------------------------
+// Large-M kernel.  At M of several thousand rows the tile loop above is bound by LDS traffic (its writes run at a
+// quarter of the read rate) and by the 64 bytes per clock a compute unit can pull through its vector memory path,
+// so this kernel moves fewer bytes through both:
+//   * tile 128 (M) x 256 (N), four wavefronts side by side along N, each 128 x 64 (4 x 2 blocks of 32 x 32: one LDS
+//     fragment read feeds two MFMAs, one weight fragment four), two workgroups per compute unit so that one tile's
+//     prologue and epilogue run under the other's main loop;
+//   * weights never touch LDS: they are stored a second time in MFMA fragment order (fragment (n / 32, k / 32) =
+//     64 lanes x 16 bytes, lane l = row n % 32 = l % 32, bytes 16 (l / 32) .. of the 32 k values; packed nibbles:
+//     8 bytes per lane) and each wavefront streams the fragments of its own 64 columns straight into a ring of
+//     registers, RB k-groups deep;
+//   * activations go global -> LDS without passing through registers (global_load_lds_dwordx4: a wavefront's 64
+//     lanes deposit 1 KB at the LDS address in M0, lane l at + 16 l), in slabs of 64 bytes of K, NB slabs in flight.
+//     A slab row is 64 bytes, its four 16-byte chunks XOR-swizzled with bits 2..3 of the row so that the fragment
+//     reads (32 consecutive rows, one chunk) are free of bank conflicts; the swizzle is applied to the global
+//     address a lane fetches from, the LDS side of the transfer is linear;
+//   * one barrier per slab, between its two k-groups: it publishes slab kt + 1 (each wavefront has waited for its own
+//     direct loads of that slab) and certifies that slab kt - 1 is no longer read, whose buffer the loads of slab
+//     kt + NB - 1 issued right after it overwrite.
+// The direct loads and the ring loads are issued through inline assembly, so the compiler neither sees their LDS /
+// register writes nor counts them: every wait on the vector memory counter below is written by hand from the program
+// order of these loads (loads return in order).  Per slab and wavefront that order is: two ring loads (group
+// 2 kt + RB - 1), [barrier], two direct loads (slab kt + NB - 1), two ring loads (group 2 kt + RB).
+#define QC_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
+// the same, tied to the two ring registers that become valid with it: their uses cannot be moved above the wait
+#define QC_WAIT_VM_FOR(n, r0, r1) asm volatile("s_waitcnt vmcnt(" #n ")" : "+v"(r0), "+v"(r1)::"memory")
+
+__device__ __forceinline__ void direct_load16(const int8_t *base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+}
+
+template <int EPI, int TAG, bool W4>
+__global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
+  constexpr int BM = 128, BN = 256, WM = 1, WN = 4, TM = 4, TN = 2, BK = 64;
+  constexpr int RB = 4, NB = 4;                   // ring depth (k-groups), LDS slabs
+  constexpr int SLAB = BM * BK;
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // Tile order: XCD x (= workgroup id mod 8) owns a contiguous range of the order "16 tile rows at a time, column by
+  // column", so the workgroups resident on an XCD at one time share few activation and weight panels.
+  const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+  const int per_xcd = (gridDim.x + 7) >> 3;
+  const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (t >= tiles_m * tiles_n) return;
+  constexpr int GM = 16;
+  const int grp = t / (GM * tiles_n), gm0 = grp * GM, gsz = min(GM, tiles_m - gm0), rr = t - grp * GM * tiles_n;
+  const int tn = rr / gsz, tm = gm0 + rr % gsz;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int wn0 = wave * (TN * 32);
+
+  // direct loads of the activations: instruction i of wavefront w fills rows 64 i + 16 w .. + 16 of a slab; lane l ->
+  // row l / 4, physical chunk l % 4, which holds logical chunk (l % 4) ^ ((row >> 2) & 3).  Rows beyond M re-read row M - 1.
+  unsigned aoff[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = i * 64 + wave * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    aoff[i] = (unsigned)(min(m0 + row, p.M - 1) - m0) * (unsigned)p.lda + c * 16;
+  }
+  const int8_t *abase = p.A + (size_t)m0 * p.lda;
+  const int nk = p.K / BK, ng = p.K / 32;
+  auto load_slab = [&](int kt) {                  // slabs past the end re-read the last one (never used)
+    const int8_t *src = abase + min(kt, nk - 1) * BK;
+    const unsigned dst = (unsigned)((kt % NB) * SLAB + wave * 1024);
+    direct_load16(src, aoff[0], dst);
+    direct_load16(src, aoff[1], dst + 4096);
+  };
+
+  // weight fragment streams of this wavefront: n-blocks (n0 + wn0) / 32 + j (blocks past N re-read the last block)
+  constexpr int FRAG = W4 ? 512 : 1024;           // bytes per fragment
+  typedef typename std::conditional<W4, v2i, v4i>::type wfrag_t;
+  const int nblocks = p.N / 32;
+  const int8_t *sb[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) sb[j] = (const int8_t *)p.Wt + (size_t)min((n0 + wn0) / 32 + j, nblocks - 1) * ng * FRAG;
+  const unsigned lane_off = lane * (W4 ? 8 : 16);
+  wfrag_t bq[RB][TN];
+  auto load_ring = [&](int slot, int g) {         // groups past the end re-read the last one (never used)
+    const size_t go = (size_t)min(g, ng - 1) * FRAG;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const int nl = wn0 + j * 32 + rg * 8 + g * 4;       // 4 consecutive columns of this lane
-        const v4f sc = *(const v4f *)(c_sc + nl);
-        const v4i zw = *(const v4i *)(c_zw + nl);
-        const v4f bs = *(const v4f *)(c_bs + nl);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          int code[4];
-          bool doubt[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int corr = acc[i][j][rg * 4 + e] - zw[e];
-            const float v = fmaf(sc[e], (float)corr, bs[e]);
-            const float gv = gelu_tanh(v);
-            float q = gv * o_inv;
-            q = fmaf(fmaf(-q, o_s, gv), o_inv, q);
-            const float r = __builtin_rintf(q);
-            code[e] = (int)fminf(fmaxf(r + o_z, -128.0f), 127.0f);
-            doubt[e] = fabsf(fabsf(q - r) - 0.5f) < fmaf(tol_v, fabsf(v), 2e-6f);
-          }
-          // one branch per four outputs; taken by a wavefront about once in a hundred times
-          if (doubt[0] | doubt[1] | doubt[2] | doubt[3]) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (doubt[e]) {
-                const int slot = atomicAdd(fix_cnt, 1);
-                if (slot < GELU_FIX_CAP) {
-                  fix_ent[slot * 4 + 0] = acc[i][j][rg * 4 + e] - zw[e];
-                  fix_ent[slot * 4 + 1] = nl + e;
-                  fix_ent[slot * 4 + 2] = wm0 + i * 32 + (lane & 31);
-                }
-              }
-          }
-          const unsigned w = (unsigned)(code[0] & 0xFF) | ((unsigned)(code[1] & 0xFF) << 8) |
-                             ((unsigned)(code[2] & 0xFF) << 16) | ((unsigned)(code[3] & 0xFF) << 24);
-          *(unsigned *)(stage + (wm0 + i * 32 + (lane & 31)) * SROW + nl) = w;
-        }
-      }
+      if (W4) asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(bq[slot][j]) : "v"(lane_off), "s"(sb[j] + go) : "memory");
+      else asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(bq[slot][j]) : "v"(lane_off), "s"(sb[j] + go) : "memory");
     }
-    __syncthreads();
-    {
-      const int nfix = min(*fix_cnt, GELU_FIX_CAP);
-      for (int f = tid; f < nfix; f += NT) {
-        const int corr = fix_ent[f * 4 + 0], nl = fix_ent[f * 4 + 1], row = fix_ent[f * 4 + 2];
-        const int n = n0 + nl;
-        if (n < p.N) stage[row * SROW + nl] = (unsigned char)gelu_code_exact(corr, a_s, w_scale[n], bias ? bias[n] : 0.0f, o_s, oq.z);
-      }
-      if (nfix) __syncthreads();
-    }
-    // coalesced write-out: 16-byte chunks, 8 lanes cover a 128-byte row segment
-    constexpr int CH = BN / 16;
-    for (int c = tid; c < BM * CH; c += NT) {
-      const int r = c / CH, cc = (c % CH) * 16;
-      const int m = m0 + r, n = n0 + cc;
-      if (m >= p.M || n >= p.N) continue;
-      int8_t *dst = p.q_out + (long long)m * p.ldq + n;
-      if (n + 16 <= p.N) {
-        *(v4i *)dst = *(const v4i *)(stage + r * SROW + cc);
-      } else {
-        for (int e = 0; n + e < p.N; ++e) dst[e] = (int8_t)stage[r * SROW + cc + e];
-      }
-    }
-    return;
-  }
+  };
 
-  if (EPI == EPI_QKV) {
-    // split every value into fp16 high and low parts (hi + lo carries ~22 bits) and scatter to the
-    // head-major layouts of the attention kernel
-    const int T = p.rows_per_batch, D = p.N / 3;
-    _Float16 *vh = p.vt_hi, *vl = p.vt_lo;
-    const bool fast_t = (T % 4) == 0;
-    const bool tile_one_batch = (T % BM) == 0;      // then every row of the tile belongs to batch element m0 / T
-    const int b_tile = m0 / T;
-    if (BM == 128 && BN == 128 && tile_one_batch && fast_t && m0 + BM <= p.M && n0 + BN <= p.N &&
-        D % BN == 0 && (p.hd & 3) == 0 && (p.Tp & 7) == 0) {
-      // Interior tile inside one batch element and one of Q, K, V: the split values go through LDS (free after the K
-      // loop) and leave as 16-byte stores along the contiguous direction of their layout (Q / K: features of a
-      // token and head; V^T: tokens of a feature), instead of 4-byte (Q / K) and scattered 8-byte (V^T) stores.
-      const int part = n0 / D;
-      const int tb = m0 - b_tile * T;                         // first token of the tile
-      if (part < 2) {
-        constexpr int SR = BN + 4;                            // words per staged row
-        unsigned *stage = (unsigned *)smem;
-        const float mul = part == 0 ? p.q_scale : 1.0f;
+  v16i acc[TM][TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int nl = wn0 + j * 32 + (lane & 31);
-          const double sc = (double)a_s * (double)w_scale[n0 + nl];
-          const int zw = a_z * wsum[n0 + nl];
-          const double bs = bias ? (double)bias[n0 + nl] : 0.0;
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int ml = wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-              const float v0 = dequant_f32(sc, acc[i][j][r] - zw, bs);
-              if (p.y) p.y[(long long)(m0 + ml) * p.ldy + n0 + nl] = v0;      // float32 copy (32 lanes write 128 contiguous bytes)
-              const float v = v0 * mul;
-              const _Float16 hi = (_Float16)v, lo = (_Float16)(v - (float)hi);
-              stage[ml * SR + nl] =
-                  (unsigned)__builtin_bit_cast(unsigned short, hi) | ((unsigned)__builtin_bit_cast(unsigned short, lo) << 16);
-            }
-        }
-        __syncthreads();
-        // thread -> four features cc .. cc + 3 (inside one head: heads start at multiples of hd, a multiple of 4) of
-        // the rows cr, cr + NT / 32, ...
-        const int cr = tid >> 5, cc = (tid & 31) * 4;
-        const int nn = n0 - part * D + cc, h = nn / p.hd, e = nn - h * p.hd;
-        unsigned *dst = (part == 0 ? p.q_words : p.k_words) +
-                        ((unsigned)(b_tile * p.heads + h) * (unsigned)T + (unsigned)(tb + cr)) * (unsigned)p.hd + (unsigned)e;
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0;
+
+  const int frow = lane & 31, fsw = (frow >> 2) & 3;
+  v4i fa[2][TM];
+  auto read_frags = [&](int f, int kt, int kg) {
+    const unsigned char *a_base = smem + (kt % NB) * SLAB + frow * BK + ((((lane >> 5) + 2 * kg) ^ fsw) * 16);
 #pragma unroll
-        for (int q = 0; q < BM * 32 / NT; ++q)
-          *(v4i *)(dst + (unsigned)(q * (NT / 32)) * (unsigned)p.hd) = *(const v4i *)(stage + (cr + q * (NT / 32)) * SR + cc);
-      } else {
-        constexpr int VR = BM + 8;                            // halves per staged feature row
-        _Float16 *sh = (_Float16 *)smem, *sl = sh + BN * VR;
-        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int nl = wn0 + j * 32 + (lane & 31);
-          const double sc = (double)a_s * (double)w_scale[n0 + nl];
-          const int zw = a_z * wsum[n0 + nl];
-          const double bs = bias ? (double)bias[n0 + nl] : 0.0;
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-              h4 hi, lo;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
-                if (p.y) p.y[(long long)(m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4 + q) * p.ldy + n0 + nl] = v;
-                hi[q] = (_Float16)v;
-                lo[q] = (_Float16)(v - (float)hi[q]);
-              }
-              // four consecutive tokens stay together under the key permutation of the V^T rows
-              const int pos = vt_pos(wm0 + i * 32 + rg * 8 + (lane >> 5) * 4);
-              *(h4 *)(sh + nl * VR + pos) = hi;
-              *(h4 *)(sl + nl * VR + pos) = lo;
-            }
-        }
-        __syncthreads();
-        // thread -> 8 consecutive token positions ch of the features fc, fc + NT / 16, ...
-        const int fc = tid >> 4, ch = (tid & 15) * 8;
-#pragma unroll
-        for (int q = 0; q < BN * 16 / NT; ++q) {
-          const int col = fc + q * (NT / 16);
-          const int nn = n0 - 2 * D + col, h = nn / p.hd, e = nn - h * p.hd;
-          const unsigned o = ((unsigned)(b_tile * p.heads + h) * (unsigned)p.DP + (unsigned)e) * (unsigned)p.Tp + (unsigned)(tb + ch);
-          *(v4i *)(vh + o) = *(const v4i *)(sh + col * VR + ch);
-          *(v4i *)(vl + o) = *(const v4i *)(sl + col * VR + ch);
-        }
-      }
-      return;
-    }
+    for (int i = 0; i < TM; ++i) fa[f][i] = *(const v4i *)(a_base + i * 32 * BK);
+  };
+  auto mfma_group = [&](int f, int slot) {
+    v4i wf[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn0 + j * 32 + (lane & 31);
-      if (n >= p.N) continue;
-      const double sc = (double)a_s * (double)w_scale[n];
-      const int zw = a_z * wsum[n];
-      const double bs = bias ? (double)bias[n] : 0.0;
-      const int part = n / D, nn = n - part * D, h = nn / p.hd, e = nn - h * p.hd;
-      const float mul = part == 0 ? p.q_scale : 1.0f;
-      unsigned *dpair = part == 0 ? p.q_words : p.k_words;   // Q / K: one (hi | lo << 16) word per element
-      if (tile_one_batch && fast_t && m0 + BM <= p.M) {
-        // interior tile inside one batch element: 32-bit offsets advanced row by row, no per-element index arithmetic
-        const int tb = m0 - b_tile * T + wm0 + (lane >> 5) * 4;            // token of this lane's first row
-        const unsigned head = (unsigned)(b_tile * p.heads + h);
-        if (part == 2) {
-          const unsigned base = (head * (unsigned)p.DP + (unsigned)e) * (unsigned)p.Tp;
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-              typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-              h4 hi, lo;
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
-                if (p.y) p.y[(long long)(m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4 + q) * p.ldy + n] = v;
-                hi[q] = (_Float16)v;
-                lo[q] = (_Float16)(v - (float)hi[q]);
-              }
-              const unsigned o = base + (unsigned)vt_pos(tb + i * 32 + rg * 8);
-              *(h4 *)(vh + o) = hi;
-              *(h4 *)(vl + o) = lo;
-            }
-        } else {
-          unsigned *dst = dpair + (head * (unsigned)T + (unsigned)tb) * (unsigned)p.hd + (unsigned)e;
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg)
-#pragma unroll
-              for (int q = 0; q < 4; ++q) {
-                const float v0 = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
-                if (p.y) p.y[(long long)(m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4 + q) * p.ldy + n] = v0;
-                const float v = v0 * mul;
-                const _Float16 hi = (_Float16)v, lo = (_Float16)(v - (float)hi);
-                dst[(unsigned)(i * 32 + rg * 8 + q) * (unsigned)p.hd] =
-                    (unsigned)__builtin_bit_cast(unsigned short, hi) | ((unsigned)__builtin_bit_cast(unsigned short, lo) << 16);
-              }
-        }
-        continue;
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-          const int mb = m0 + wm0 + i * 32 + rg * 8 + (lane >> 5) * 4;   // 4 consecutive rows mb .. mb+3
-          if (mb >= p.M) continue;
-          _Float16 hi[4], lo[4];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float v = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs) * mul;
-            hi[q] = (_Float16)v;
-            lo[q] = (_Float16)(v - (float)hi[q]);
-          }
-          const int b0 = tile_one_batch ? b_tile : mb / T, t0 = mb - b0 * T;
-          if (part == 2 && fast_t && mb + 3 < p.M) {
-            const int b = b0, t = t0;
-            const long long o = ((long long)(b * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t);
-            typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-            *(h4 *)(vh + o) = (h4){hi[0], hi[1], hi[2], hi[3]};
-            *(h4 *)(vl + o) = (h4){lo[0], lo[1], lo[2], lo[3]};
-          } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int m = mb + q;
-              if (m >= p.M) continue;
-              int b = b0, t = t0 + q;
-              while (t >= T) { t -= T; ++b; }
-              if (part == 2) {
-                const long long o = ((long long)(b * p.heads + h) * p.DP + e) * p.Tp + vt_pos(t);
-                vh[o] = hi[q];
-                vl[o] = lo[q];
-              } else {
-                const unsigned short uh = __builtin_bit_cast(unsigned short, hi[q]), ul = __builtin_bit_cast(unsigned short, lo[q]);
-                dpair[((long long)(b * p.heads + h) * T + t) * p.hd + e] = (unsigned)uh | ((unsigned)ul << 16);
-              }
-            }
-          }
-          if (p.y) {   // optional fp32 copy for inspection
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-              if (mb + q < p.M) p.y[(long long)(mb + q) * p.ldy + n] = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
-          }
-        }
-      }
+      if constexpr (W4) wf[j] = unpack_w4(bq[slot][j]);
+      else wf[j] = bq[slot][j];
     }
-    return;
-  }
-
-  if (EPI == EPI_RESID) {
-    // read-modify-write of the residual stream: the loads of a batch of column blocks are all issued
-    // before the first use, so the epilogue pays one memory round trip per batch instead of one per
-    // register group; a batch is the whole tile when its values fit in registers beside the accumulators
-    constexpr int JB = TM * TN <= 4 ? TN : 1, IB = TM * TN <= 4 ? TM : (TM % 2 == 0 ? 2 : 1);
-    const bool uniform_batch = (p.rows_per_batch % BM) == 0;
-    const int b_uniform = m0 / p.rows_per_batch;
-    const bool interior = uniform_batch && m0 + BM <= p.M && n0 + BN <= p.N;
 #pragma unroll
-    for (int j0 = 0; j0 < TN; j0 += JB)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int i0 = 0; i0 < TM; i0 += IB) {
-        float xv[JB][IB][16], gv[JB];
-        double scv[JB], bsv[JB];
-        int zwv[JB];
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) {
-          const int n = min(n0 + wn0 + (j0 + jj) * 32 + (lane & 31), p.N - 1);
-#pragma unroll
-          for (int ii = 0; ii < IB; ++ii)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int m = min(m0 + wm0 + (i0 + ii) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), p.M - 1);
-              xv[jj][ii][r] = p.x[(long long)m * p.N + n];
-            }
-          scv[jj] = (double)a_s * (double)w_scale[n];
-          zwv[jj] = a_z * wsum[n];
-          bsv[jj] = bias ? (double)bias[n] : 0.0;
-          gv[jj] = p.gate[(long long)b_uniform * p.ld_gate + n];
-        }
-#pragma unroll
-        for (int jj = 0; jj < JB; ++jj) {
-          const int j = j0 + jj;
-          const int n = n0 + wn0 + j * 32 + (lane & 31);
-          if (interior) {
-            // interior tile inside one batch element: no bounds checks, one gate per column
-#pragma unroll
-            for (int ii = 0; ii < IB; ++ii)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                const int i = i0 + ii;
-                const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                const float v = dequant_f32(scv[jj], acc[i][j][r] - zwv[jj], bsv[jj]);
-                const long long o = (long long)m * p.N + n;
-                if (p.cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
-                else ((float *)p.cache_out)[o] = v;
-                p.x[o] = fmaf(gv[jj], v, xv[jj][ii][r]);
-              }
-          } else {
-            if (n >= p.N) continue;
-#pragma unroll
-            for (int ii = 0; ii < IB; ++ii)
-#pragma unroll
-              for (int r = 0; r < 16; ++r) {
-                const int i = i0 + ii;
-                const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                if (m >= p.M) continue;
-                const float v = dequant_f32(scv[jj], acc[i][j][r] - zwv[jj], bsv[jj]);
-                const long long o = (long long)m * p.N + n;
-                if (p.cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
-                else ((float *)p.cache_out)[o] = v;
-                const float g = p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
-                p.x[o] = fmaf(g, v, xv[jj][ii][r]);
-              }
-          }
-        }
+      for (int j = 0; j < TN; ++j) {
+        if (EPI == EPI_GELU_Q) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], fa[f][i], acc[i][j], 0, 0, 0);
+        else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[f][i], wf[j], acc[i][j], 0, 0, 0);
       }
-    return;
-  }
+  };
 
+  // prologue: slabs 0 .. NB - 2 and groups 0 .. RB - 2 requested, everything landed before the first use
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int jl = n0 + wn0 + j * 32 + (lane & 31);
-    if (jl >= ncover) continue;
-    const int n = map_col(jl, p.sel_D);
-    const double sc = (double)a_s * (double)w_scale[n];
-    const int zw = a_z * wsum[n];
-    const double bs = bias ? (double)bias[n] : 0.0;
+  for (int s = 0; s < NB - 1; ++s) load_slab(s);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (m >= p.M) continue;
-        const int a = acc[i][j][r];
-        float *y = p.y + (long long)z * p.zs_out;
-        y[(long long)m * p.ldy + n] = dequant_f32(sc, a - zw, bs);
-        if (p.acc_out) p.acc_out[(long long)m * p.N + n] = a;
-      }
-    }
+  for (int s = 0; s < RB - 1; ++s) load_ring(s, s);
+  __builtin_amdgcn_sched_barrier(0);
+  QC_WAIT_VM(0);
+  __syncthreads();
+  read_frags(0, 0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // Slab kt = k-groups 2 kt and 2 kt + 1.  On entry: slabs <= kt have landed and are published, slabs <= kt + NB - 2
+  // are requested, fa[0] holds the fragments of (kt, group 0), ring groups <= 2 kt + RB - 2 are requested.
+  // Loads younger than the one a wait is for (see the order above), with RB = NB = 4:
+  //   ring group 2 kt     (requested after the barrier of slab kt - 2): 6 (slab kt - 1) + 2      =  8
+  //   direct loads of slab kt + 1 (after the barrier of slab kt - 2):   2 + 6 (slab kt - 1) + 2  = 10
+  //   ring group 2 kt + 1 (requested at the top of slab kt - 1):        4 + 6 (this slab)        = 10
+  static_assert(RB == 4 && NB == 4 && TN == 2, "the vmcnt waits below are counted for this depth");
+  auto slab = [&](int kt, int slot0) {
+    read_frags(1, kt, 1);
+    load_ring((slot0 + RB - 1) % RB, 2 * kt + RB - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    QC_WAIT_VM_FOR(8, bq[slot0][0], bq[slot0][1]);
+    mfma_group(0, slot0);
+    __builtin_amdgcn_sched_barrier(0);
+    QC_WAIT_VM(10);
+    asm volatile("s_barrier" ::: "memory");
+    load_slab(kt + NB - 1);
+    load_ring(slot0 % RB, 2 * kt + RB);
+    read_frags(0, kt + 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    QC_WAIT_VM_FOR(10, bq[(slot0 + 1) % RB][0], bq[(slot0 + 1) % RB][1]);
+    mfma_group(1, (slot0 + 1) % RB);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  for (int kt = 0; kt + 2 <= nk; kt += 2) {       // K is a multiple of 128 (checked by the launcher)
+    slab(kt, 0);
+    slab(kt + 1, 2);
   }
+  // the loads that ran past the end (clamped addresses) must have landed before LDS and registers are reused
+  QC_WAIT_VM(0);
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
+  gemm_epilogue<BM, BN, WM, WN, EPI, true>(p, acc, smem, m0, n0, 0);
+}
+
+constexpr int BIG_SMEM_LOOP = 4 * 128 * 64;
+constexpr int BIG_SMEM_QKV = 128 * (128 + 4) * 4;                        // one staged column half, float32
+constexpr int BIG_SMEM_GELU = 256 * 12 + 128 * (256 + 16) + 16 + GELU_FIX_CAP * 16;
+
+template <int EPI, int TAG, bool W4>
+static hipError_t launch_big(const GemmArgs &a, hipStream_t st) {
+  constexpr int smem = EPI == EPI_QKV ? BIG_SMEM_QKV : (EPI == EPI_GELU_Q ? BIG_SMEM_GELU : BIG_SMEM_LOOP);
+  static_assert(smem >= BIG_SMEM_LOOP && 2 * smem <= 160 * 1024, "two workgroups per compute unit");
+  static bool attr_set = false;
+  auto kern = gemm_i8_big_kernel<EPI, TAG, W4>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles = ((a.M + 127) / 128) * ((a.N + 255) / 256);
+  hipLaunchKernelGGL(kern, dim3(((tiles + 7) / 8) * 8), dim3(256), smem, st, a);
+  return hipGetLastError();
+}
+
+// The large-M kernel takes over when the weights exist in fragment order, the shape fits its loop (K a multiple of
+// 128, N of 32, 16-byte aligned rows), every 128-row tile is whole and inside one batch element (its epilogues are
+// compiled without the general paths) and its 128 x 256 tiles fill the chip's 512 workgroup slots.
+static bool use_big(const GemmArgs &a, int epi, int nz) {
+  if (!a.Wt || nz != 1 || a.sel_D || a.acc_out) return false;
+  if (a.K % 128 || a.N % 32 || a.lda % 16 || a.M % 128) return false;
+  if (epi == EPI_RESID && a.rows_per_batch % 128) return false;
+  if (epi == EPI_QKV && (a.rows_per_batch % 128 || (a.N / 3) % 128 || a.hd % 4 || a.Tp % 8)) return false;
+  const long long tiles = (long long)((a.M + 127) / 128) * ((a.N + 255) / 256);
+  return tiles >= 384;
 }
 
 template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK = 128>
@@ -803,6 +982,9 @@ static int forced_tile() {
 
 template <int EPI, int TAG, bool W4>
 static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
+  if constexpr (EPI != EPI_F32) {
+    if (use_big(a, EPI, nz)) return launch_big<EPI, TAG, W4>(a, st);
+  }
   if (a.M <= 32) return launch_cfg<32, 128, 1, 4, EPI, TAG, W4, 3>(a, nz, st);
   if (a.M <= 64) return launch_cfg<64, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
   switch (forced_tile()) {

@@ -18,6 +18,7 @@ struct QParam {
 // One quantised weight matrix in the arena.
 struct LinearQ {
   void *q = nullptr;         // int8 [N, K] or packed nibbles [N, K/2]
+  void *qt = nullptr;        // the same codes in MFMA fragment order for the large-M kernel, or null
   float *scale = nullptr;    // [N]
   int32_t *wsum = nullptr;   // [N]
   float *bias = nullptr;     // [N]
@@ -32,6 +33,7 @@ enum Epi { EPI_F32 = 0, EPI_GELU_Q = 1, EPI_RESID = 2, EPI_QKV = 3 };
 struct GemmArgs {
   const int8_t *A;           // [M, lda] signed codes
   const void *W;             // [N, K] int8 or [N, K/2] packed
+  const void *Wt;            // the same codes in MFMA fragment order (launch_tile_weight), or null
   const float *w_scale;
   const int32_t *wsum;
   const float *bias;         // may be null
@@ -64,13 +66,11 @@ struct GemmArgs {
   const float *gate;         // [B, ld_gate]
   int ld_gate;
   int rows_per_batch;        // T
-  // EPI_QKV: Q | K | V columns go out as fp16 (high part, low part) for the attention kernel:
-  // Q (pre-scaled by q_scale) and K as one (hi | lo << 16) word per element, [B, H, T, hd];
-  // V transposed and key-permuted, separate hi and lo arrays [B, H, DP, Tp] (DP = hd rounded up to 16)
-  unsigned *q_words, *k_words;
-  _Float16 *vt_hi, *vt_lo;
+  // EPI_QKV: the float32 Q | K | V columns go out in the attention kernel's head-major layouts: Q and K
+  // [B, H, T, hd]; V transposed and key-permuted [B, H, DP, Tp] (DP = hd rounded up to 16, Tp = T rounded up to 64);
+  // y, when set, also receives them row-major
+  float *q32, *k32, *vt32;
   int heads, hd, DP, Tp;
-  float q_scale;
 };
 
 // position of key t inside V^T rows: within each group of 32 keys the units of 4 keys are interleaved so that
@@ -81,6 +81,8 @@ __host__ __device__ inline int vt_pos(int t) {
 }
 
 hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st, int site);
+// row-major codes [N, K] (or packed [N, K/2]) -> fragment order; N % 32 == 0, K % 32 == 0
+hipError_t launch_tile_weight(const void *q, void *qt, int N, int K, int bits, hipStream_t st);
 
 // ---- elementwise / row kernels
 hipError_t launch_quantize_act(const float *x, int8_t *q, size_t n, float s, int z_signed, hipStream_t st);
@@ -112,9 +114,8 @@ hipError_t launch_vc_fit(const float *x_hat, const float *x_ref, int B, int C, i
                          hipStream_t st);
 hipError_t launch_attention(const float *qkv, int B, int T, int H, int hd, const QParam *qp, int8_t *q_out, float *f32_out,
                             hipStream_t st);
-hipError_t launch_attention_f16(const unsigned *q_words, const unsigned *k_words, const _Float16 *vt_hi, const _Float16 *vt_lo,
-                                int B, int T, int Tp, int H, int hd, int DPv, const QParam *qp, int8_t *q_out, const float *qkv32,
-                                hipStream_t st);
+hipError_t launch_attention_f16(const float *q32, const float *k32, const float *vt32, int B, int T, int Tp, int H, int hd,
+                                int DPv, const QParam *qp, int8_t *q_out, hipStream_t st);
 // calibration helpers
 hipError_t launch_linear_f32(const float *x, const float *W, const float *b, float *y, int M, int N, int K, int act_out,
                              hipStream_t st);

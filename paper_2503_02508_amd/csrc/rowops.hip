@@ -99,6 +99,30 @@ hipError_t launch_quantize_weight(const float *w, int N, int K, int bits, void *
   return hipGetLastError();
 }
 
+// ------------------------------------------------ weights in fragment order
+// Copies the codes of a quantised weight matrix into the order the large-M GEMM streams them in: fragment
+// (n / 32, k / 32) is 64 lanes x 16 bytes (8 bytes for packed nibbles), lane l holds row n % 32 = l % 32, k values
+// 16 (l / 32) .. 16 (l / 32) + 15 of the group.  One thread per (fragment, lane).
+__global__ __launch_bounds__(256) void tile_weight_kernel(const unsigned char *__restrict__ q, unsigned char *__restrict__ qt, int N,
+                                                          int K, int w4) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int ng = K / 32;
+  if (i >= (size_t)(N / 32) * ng * 64) return;
+  const int l = (int)(i & 63), kg = (int)((i >> 6) % ng), nb = (int)((i >> 6) / ng);
+  const size_t n = (size_t)nb * 32 + (l & 31);
+  const int k = kg * 32 + (l >> 5) * 16;
+  if (w4) *(uint2 *)(qt + i * 8) = *(const uint2 *)(q + n * (K >> 1) + (k >> 1));
+  else *(uint4 *)(qt + i * 16) = *(const uint4 *)(q + n * K + k);
+}
+
+hipError_t launch_tile_weight(const void *q, void *qt, int N, int K, int bits, hipStream_t st) {
+  if (N % 32 || K % 32) return hipErrorInvalidValue;
+  const size_t n = (size_t)(N / 32) * (K / 32) * 64;
+  hipLaunchKernelGGL(tile_weight_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const unsigned char *)q,
+                     (unsigned char *)qt, N, K, bits == 4 ? 1 : 0);
+  return hipGetLastError();
+}
+
 // ------------------------------------------- LayerNorm + modulate + quantise
 // One wavefront per token row; the row lives in registers (D <= 2048).
 constexpr int LN_MAX_IT = 8;

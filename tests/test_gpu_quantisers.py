@@ -38,6 +38,9 @@ def _signed_codes(x, s, z):
     ("dit_s2", I.DIT_S2_1BLOCK, 2, 8, 0.02),
     ("xl_256", I.DIT_XL2_256, 2, 8, 0.02),
     ("xl_256_w4", I.DIT_XL2_256, 2, 4, 0.02),
+    # M = 12288 rows: all four linears take the large-M GEMM kernel (fragment-ordered weights)
+    ("xl_256_large_m", I.DIT_XL2_256, 48, 8, 0.02),
+    ("xl_256_large_m_w4", I.DIT_XL2_256, 48, 4, 0.02),
     ("ragged", I.ModelDesc(depth=1, hidden=80, heads=4, mlp_dim=176, patch=1, latent_c=3, latent_h=5, latent_w=7,
                            num_classes=7), 3, 8, 0.15),
 ])

@@ -35,6 +35,7 @@ namespace qc {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
@@ -153,9 +154,12 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
     __syncthreads();
     const QParam oq = *p.o_qp;
     const float o_s = oq.s, o_inv = 1.0f / oq.s, o_z = (float)oq.z;
-    // bound of the fast path's error in units of the output step: 1.5e-6 |v| / s covers the float32 dequantisation, the
-    // exp2 / reciprocal estimates and the refined quotient with a margin of 2; 2e-6 covers the bias rounding
-    const float tol_v = 1.5e-6f * o_inv;
+    // Bound of the fast path's error in units of the output step, as a multiple of |v| / s (|GELU(v)| <= |v|):
+    // 1.5e-6 covers the float32 dequantisation (accumulators beyond 2^24 are rounded on conversion) and the exp2 /
+    // reciprocal estimates with a margin of 2, 2e-7 the unrefined quotient gv * (1 / s); 2e-6 absolute covers the bias
+    // rounding.  An element is in doubt when |q - rint(q)| + bound > 1/2.
+    const float tol_v = 1.7e-6f * o_inv;
+    const float doubt_at = 0.5f - 2e-6f;
     const int g = lane >> 5;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -171,14 +175,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
           bool doubt[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int corr = acc[i][j][rg * 4 + e] - zw[e];
-            const float v = fmaf(sc[e], (float)corr, bs[e]);
-            const float gv = gelu_tanh(v);
-            float q = gv * o_inv;
-            q = fmaf(fmaf(-q, o_s, gv), o_inv, q);
+            const float v = fmaf(sc[e], (float)(acc[i][j][rg * 4 + e] - zw[e]), bs[e]);
+            const float q = gelu_tanh(v) * o_inv;
             const float r = __builtin_rintf(q);
             code[e] = (int)fminf(fmaxf(r + o_z, -128.0f), 127.0f);
-            doubt[e] = fabsf(fabsf(q - r) - 0.5f) < fmaf(tol_v, fabsf(v), 2e-6f);
+            doubt[e] = fmaf(tol_v, fabsf(v), fabsf(q - r)) > doubt_at;
           }
           // one branch per four outputs; taken by a wavefront about once in a hundred times
           if (doubt[0] | doubt[1] | doubt[2] | doubt[3]) {
@@ -894,7 +895,9 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
     mfma_group(1, (slot0 + 1) % RB);
     __builtin_amdgcn_sched_barrier(0);
   };
-  for (int kt = 0; kt + 2 <= nk; kt += 2) {       // K is a multiple of 128 (checked by the launcher)
+  // K is a multiple of 128 (checked by the launcher): an even number of slabs; the ring slot of a slab's first group
+  // advances by two per slab and returns to 0 every RB / 2 slabs
+  for (int kt = 0; kt + 2 <= nk; kt += 2) {
     slab(kt, 0);
     slab(kt + 1, 2);
   }
@@ -906,13 +909,14 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
 }
 
 constexpr int BIG_SMEM_LOOP = 4 * 128 * 64;
-constexpr int BIG_SMEM_QKV = 128 * (128 + 4) * 4;                        // one staged column half, float32
+constexpr int BIG_SMEM_STAGE = 128 * (128 + 4) * 4;                      // one staged column half of the QKV scatter, float32
 constexpr int BIG_SMEM_GELU = 256 * 12 + 128 * (256 + 16) + 16 + GELU_FIX_CAP * 16;
 
 template <int EPI, int TAG, bool W4>
 static hipError_t launch_big(const GemmArgs &a, hipStream_t st) {
-  constexpr int smem = EPI == EPI_QKV ? BIG_SMEM_QKV : (EPI == EPI_GELU_Q ? BIG_SMEM_GELU : BIG_SMEM_LOOP);
-  static_assert(smem >= BIG_SMEM_LOOP && 2 * smem <= 160 * 1024, "two workgroups per compute unit");
+  constexpr int smem_epi = EPI == EPI_GELU_Q ? BIG_SMEM_GELU : (EPI == EPI_QKV ? BIG_SMEM_STAGE : 0);
+  constexpr int smem = smem_epi > BIG_SMEM_LOOP ? smem_epi : BIG_SMEM_LOOP;
+  static_assert(2 * smem <= 160 * 1024, "two workgroups per compute unit");
   static bool attr_set = false;
   auto kern = gemm_i8_big_kernel<EPI, TAG, W4>;
   if (!attr_set) {

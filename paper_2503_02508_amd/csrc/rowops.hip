@@ -136,47 +136,63 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // The value that gets quantised is formed in fp64 and rounded to fp32 once: the codes then differ from
 // exact arithmetic only where the fp32 residual stream itself does, which keeps code flips (and the
 // error they seed in every later layer) at the floor.
-// One workgroup (4 wavefronts) per token row: short per-thread work and 8 wavefronts per SIMD keep the
-// two memory round trips (row in, codes out) and the fp64 arithmetic of different rows overlapped.
+// One workgroup per R consecutive token rows, one float4 of every row per thread (the launch sizes the workgroup to
+// D / 4 rounded up to whole wavefronts, D <= 2048): every load of the rows and of their modulation vectors is issued
+// at once, one memory round trip.  R = 1 gives the most workgroups (small M); R = 4 puts four times the bytes in
+// flight per compute unit, which is what the memory system needs to run near its peak at large M.  The arithmetic of a
+// row, and with it every code, is the same for both.
+template <int R>
 __global__ __launch_bounds__(512) void ln_mod_quant_kernel(const float *__restrict__ x, const float *__restrict__ shift,
                                                            const float *__restrict__ scale, int ld_mod, int M, int D, int T,
                                                            const QParam *qp, int8_t *__restrict__ q,
                                                            float *__restrict__ f32_out) {
-  // one float4 per thread (the launch sizes the workgroup to D / 4 rounded up to whole wavefronts, D <= 2048):
-  // every load of the row and of its modulation vectors is issued at once, one memory round trip
-  __shared__ double red[16];
-  const int m = blockIdx.x;
-  const int b = m / T;
+  __shared__ double red[R][16];
+  __shared__ double stat[R][2];
+  const int m0 = blockIdx.x * R;
   const int k = threadIdx.x * 4;
   const bool live = k < D;
   const int kc = live ? k : 0;
-  const float4 v = *(const float4 *)(x + (size_t)m * D + kc);
-  const float4 s4 = *(const float4 *)(shift + (size_t)b * ld_mod + kc);
-  const float4 c4 = *(const float4 *)(scale + (size_t)b * ld_mod + kc);
-  double sum = 0.0, sq = 0.0;
-  if (live) {
-    const double a = v.x, bq = v.y, c = v.z, d = v.w;
-    sum = (a + bq) + (c + d);
-    sq = (a * a + bq * bq) + (c * c + d * d);
+  float4 v[R], s4[R], c4[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int m = min(m0 + r, M - 1);             // rows beyond M re-read the last row (never stored)
+    const int b = m / T;
+    v[r] = *(const float4 *)(x + (size_t)m * D + kc);
+    s4[r] = *(const float4 *)(shift + (size_t)b * ld_mod + kc);
+    c4[r] = *(const float4 *)(scale + (size_t)b * ld_mod + kc);
   }
   // mean and variance from one reduction of (sum, sum of squares): in fp64 the cancellation in
   // E[x^2] - mean^2 costs ~1e-13 relative for rows of O(1) values, far below the fp32 rounding of the result
-  sum = wave_sum_d(sum);
-  sq = wave_sum_d(sq);
   const int nw = blockDim.x >> 6;
-  if ((threadIdx.x & 63) == 0) {
-    red[threadIdx.x >> 6] = sum;
-    red[8 + (threadIdx.x >> 6)] = sq;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    double sum = 0.0, sq = 0.0;
+    if (live) {
+      const double a = v[r].x, bq = v[r].y, c = v[r].z, d = v[r].w;
+      sum = (a + bq) + (c + d);
+      sq = (a * a + bq * bq) + (c * c + d * d);
+    }
+    sum = wave_sum_d(sum);
+    sq = wave_sum_d(sq);
+    if ((threadIdx.x & 63) == 0) {
+      red[r][threadIdx.x >> 6] = sum;
+      red[r][8 + (threadIdx.x >> 6)] = sq;
+    }
   }
   __syncthreads();
-  double tot = 0.0, tot2 = 0.0;
-  for (int w = 0; w < nw; ++w) {
-    tot += red[w];
-    tot2 += red[8 + w];
+  if (threadIdx.x < R) {                          // one thread per row finishes its statistics
+    const int r = threadIdx.x;
+    double tot = 0.0, tot2 = 0.0;
+    for (int w = 0; w < nw; ++w) {
+      tot += red[r][w];
+      tot2 += red[r][8 + w];
+    }
+    const double mean = tot / (double)D;
+    const double var = tot2 / (double)D - mean * mean;
+    stat[r][0] = mean;
+    stat[r][1] = 1.0 / sqrt(fmax(var, 0.0) + 1e-6);
   }
-  const double mean = tot / (double)D;
-  const double var = tot2 / (double)D - mean * mean;
-  const double rstd = 1.0 / sqrt(fmax(var, 0.0) + 1e-6);
+  __syncthreads();
   float qs = 1.0f;
   int qz = 0;
   if (qp) {
@@ -185,21 +201,31 @@ __global__ __launch_bounds__(512) void ln_mod_quant_kernel(const float *__restri
     qz = t.z;
   }
   if (!live) return;
-  const float h0 = (float)((v.x - mean) * rstd * (1.0 + (double)c4.x) + (double)s4.x);
-  const float h1 = (float)((v.y - mean) * rstd * (1.0 + (double)c4.y) + (double)s4.y);
-  const float h2 = (float)((v.z - mean) * rstd * (1.0 + (double)c4.z) + (double)s4.z);
-  const float h3 = (float)((v.w - mean) * rstd * (1.0 + (double)c4.w) + (double)s4.w);
-  if (q)
-    *(unsigned *)(q + (size_t)m * D + k) =
-        pack4(quant_code(h0, qs, qz), quant_code(h1, qs, qz), quant_code(h2, qs, qz), quant_code(h3, qs, qz));
-  if (f32_out) *(float4 *)(f32_out + (size_t)m * D + k) = make_float4(h0, h1, h2, h3);
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int m = m0 + r;
+    if (m >= M) break;
+    const double mean = stat[r][0], rstd = stat[r][1];
+    const float h0 = (float)((v[r].x - mean) * rstd * (1.0 + (double)c4[r].x) + (double)s4[r].x);
+    const float h1 = (float)((v[r].y - mean) * rstd * (1.0 + (double)c4[r].y) + (double)s4[r].y);
+    const float h2 = (float)((v[r].z - mean) * rstd * (1.0 + (double)c4[r].z) + (double)s4[r].z);
+    const float h3 = (float)((v[r].w - mean) * rstd * (1.0 + (double)c4[r].w) + (double)s4[r].w);
+    if (q)
+      *(unsigned *)(q + (size_t)m * D + k) =
+          pack4(quant_code(h0, qs, qz), quant_code(h1, qs, qz), quant_code(h2, qs, qz), quant_code(h3, qs, qz));
+    if (f32_out) *(float4 *)(f32_out + (size_t)m * D + k) = make_float4(h0, h1, h2, h3);
+  }
 }
 
 hipError_t launch_ln_mod_quant(const float *x, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
                                const QParam *qp, int8_t *q, float *f32_out, hipStream_t st) {
   const int threads = ((D / 4 + 63) / 64) * 64;
   if (D % 4 || threads > 512) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(ln_mod_quant_kernel, dim3(M), dim3(threads), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q, f32_out);
+  if (M >= 8192)
+    hipLaunchKernelGGL(ln_mod_quant_kernel<4>, dim3((M + 3) / 4), dim3(threads), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q,
+                       f32_out);
+  else
+    hipLaunchKernelGGL(ln_mod_quant_kernel<1>, dim3(M), dim3(threads), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q, f32_out);
   return hipGetLastError();
 }
 

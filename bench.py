@@ -87,6 +87,56 @@ def cpu_baseline(wl):
                       "scaled to %d refresh + %d cached steps" % (times[0], times[1], n_full, wl.steps - n_full)}
 
 
+def per_shape_rates(model, weight_bits):
+    """The four quantised linears, the attention kernel and the LayerNorm + quantise kernel of ONE block of the
+    workload's network at M = 2048 and M = 32768 token rows (batch 8 and 128 at 256 tokens), each launch alone on
+    the chip (block-level call, one stream), timed with HIP events around every launch: achieved TOP/s (TFLOP/s for
+    the attention, GB/s for the bandwidth-bound kernel) per shape."""
+    import numpy as np
+    import torch
+    from dataclasses import replace
+    import paper_2503_02508_amd as qc
+    from synthetic import dit_inputs as I
+    m1 = replace(I.shrink(model, 1), weight_bits=weight_bits)
+    w = I.make_weights(m1, 1)
+    D, R, T = m1.hidden, m1.mlp_dim, m1.tokens
+    out = {}
+    for M in (2048, 32768):
+        B = M // T
+        if B < 1 or B * T != M:
+            continue
+        ctx = qc.Context(m1, B, 2)
+        ctx.load_weights(w)
+        for site, (sc, z) in enumerate([(0.01, 128), (0.04, 128), (0.002, 128), (0.04, 128), (0.02, 10)]):
+            ctx.set_act_qparams(0, site, sc, z)
+        x = torch.from_numpy(I.make_tokens(B, m1, 2)).cuda()
+        c = torch.from_numpy(I.make_cond(B, m1, 3, std=0.5)).cuda()
+
+        def blocks():
+            for _ in range(5):
+                ctx.dit_block(0, qc.QC_FULL, x, c)
+        blocks()
+        torch.cuda.synchronize()
+        prof = ctx.profile_pass(blocks)
+        ops = {"gemm_qkv": 2.0 * M * 3 * D * D, "gemm_proj": 2.0 * M * D * D, "gemm_fc1": 2.0 * M * R * D,
+               "gemm_fc2": 2.0 * M * D * R}
+        row = {}
+        for k, p in prof.items():
+            us = p["total_ms"] * 1e3 / max(p["launches"], 1)
+            if k in ops:
+                row[k] = {"avg_us": us, "TOP/s": ops[k] / (us * 1e-6) / 1e12, "frac": ops[k] / (us * 1e-6) / 1e12 / INT8_MFMA_PEAK_TOPS}
+            elif k == "ln_mod_quant":      # fp32 row in, int8 codes out
+                row[k] = {"avg_us": us, "GB/s": 5.0 * M * D / (us * 1e-6) / 1e9, "frac": 5.0 * M * D / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+            elif k == "attention":
+                fl = 4.0 * B * m1.heads * T * T * m1.head_dim
+                row[k] = {"avg_us": us, "TFLOP/s": fl / (us * 1e-6) / 1e12, "frac": fl / (us * 1e-6) / 1e12 / FP16_MFMA_PEAK_TFLOPS}
+        out["m%d" % M] = row
+        ctx.close()
+        del ctx, x, c
+        torch.cuda.empty_cache()
+    return out
+
+
 def tap_block(k):
     """Size of the iteration block: k rounded up to a multiple of 8 plus 24 guard vectors, at most 128."""
     return min(128, (k + 7) // 8 * 8 + 24)
@@ -294,7 +344,8 @@ def main():
                         "avg_launch_us": dom["avg_us"], "launches": dom["launches"]}
     total_int8 = int8_ops_per_full_step(m, Beff) * n_full
     out = {
-        "metric": "latents/sec, DiT-XL/2 W8A8+cache 256^2 at 50 steps; int8 GEMM % of MFMA peak",
+        "metric": "latents/sec, DiT-XL/2 W%dA8+cache %d^2 at %d steps; int8 GEMM %% of MFMA peak" % (
+            m.weight_bits, 8 * m.latent_h, wl.steps),
         "value": value, "unit": "latents/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
@@ -307,6 +358,11 @@ def main():
         "roofline": roofline,
         "kernels": prof,
     }
+    # per-shape rates of one block's kernels, each launch alone on the chip
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    out["per_shape"] = per_shape_rates(m, m.weight_bits)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -241,6 +241,13 @@ int qc_set_cache_mask(qc_ctx *ctx, const unsigned char *mask, int steps);
  * QC_WS_QKV buffer (the attention kernel itself reads head-major copies of the same fp32 values). */
 int qc_keep_qkv_f32(qc_ctx *ctx, int on);
 
+/* Class labels live in device memory, so the entry points that take them (qc_denoise, qc_sample_step,
+ * qc_sample, qc_vc_fit_sampler) cannot validate them on the host: the conditioning kernel clamps a label outside
+ * [0, num_classes] into that range (Experimental Settings: num_classes real classes plus the null label
+ * num_classes) and raises a flag on the device.  qc_check waits for `stream`, returns QC_ERR_RANGE if the flag was
+ * raised since the last call (and clears it), QC_OK otherwise. */
+int qc_check(qc_ctx *ctx, void *stream);
+
 /* Noise estimate of the whole network at timestep t.  x: dev [n_labels, C, H, W],
  * labels: dev int32 [n_labels].  The effective batch B is n_labels, or
  * 2 * n_labels for guidance: then sample b + n_labels is latent b again with

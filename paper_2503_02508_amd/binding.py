@@ -74,6 +74,7 @@ _SIGS = {
     "qc_sample_step": (i32, [vp, vp, vp, i32, i32, i32, f64, f64, f32, vp, i32, vp]),
     "qc_sample": (i32, [vp, vp, vp, i32, i32, f32, vp, vp]),
     "qc_keep_qkv_f32": (i32, [vp, i32]),
+    "qc_check": (i32, [vp, vp]),
     "qc_tap_workspace_bytes": (i32, [i32, i32, i32, i32, i32, C.POINTER(sz)]),
     "qc_tap_similarity": (i32, [vp, vp, i32, i32, vp, i32, f32, vp, vp, vp, vp, sz, vp]),
     "qc_tap_normalise": (i32, [vp, vp, vp, i32, i32, vp, sz, vp]),
@@ -313,6 +314,10 @@ class Context:
 
     def keep_qkv_f32(self, on=True):
         _chk(lib.qc_keep_qkv_f32(self.h, int(on)))
+
+    def check(self):
+        """Waits for the current stream; raises if a kernel flagged an out-of-range class label since the last call."""
+        _chk(lib.qc_check(self.h, _stream()))
 
     def dit_block(self, block, mode, x, c):
         _chk(lib.qc_dit_block(self.h, block, mode, _p(x), _p(c), x.shape[0], _stream()))

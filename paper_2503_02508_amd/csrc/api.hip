@@ -95,6 +95,7 @@ struct qc_ctx {
   float *qkv_hm;              // float32 Q, K [B,H,T,hd] and V^T [B,H,DP,Tp] (head-major) for the attention kernel
   long long qkv_part_stride;  // elements per Q / K array
   size_t qkv_hm_bytes;
+  int *dev_flags;             // [0]: bit 0 = a class label outside [0, num_classes] was met (and clamped)
   int DP, Tp;
   int win_rows;               // row capacity of cond / fmod / mod / silu_q (per block for the last two)
   bool keep_qkv_f32 = false;
@@ -105,7 +106,6 @@ struct qc_ctx {
   // a denoiser call may run its batch as up to MAX_LANES independent sub-batches on internal streams
   hipStream_t lane_stream[4] = {nullptr, nullptr, nullptr, nullptr};
   hipEvent_t ev_fork = nullptr, ev_join[4] = {nullptr, nullptr, nullptr, nullptr};
-  int forced_lanes = -1;
   // optional per-kernel-class timing with HIP events (qc_profile_begin / qc_profile_end)
   bool prof_on = false;
   std::vector<hipEvent_t> prof_pool;
@@ -218,13 +218,14 @@ static size_t layout(const qc_model_desc &d, int max_batch, char *base, qc_ctx *
   int *cal_slots = a.take<int>(L * QC_NUM_SITES * 2), *cal_label = a.take<int>(4);
   float *eps_ref = a.take<float>(B * C * d.latent_h * d.latent_w);
   double *vcfit_work = a.take<double>(B * C * 2);
+  int *dev_flags = a.take<int>(64);
   if (c) {
     c->patch_w = patch_w; c->patch_b = patch_b; c->pos = pos; c->t_w1 = t_w1; c->t_b1 = t_b1; c->t_w2 = t_w2; c->t_b2 = t_b2;
     c->label_table = label_table; c->fada_w = fada_w; c->fada_b = fada_b; c->flin_w = flin_w; c->flin_b = flin_b;
     c->dev_qp = dev_qp; c->cache = cache; c->emb = emb; c->h1 = h1; c->te = te; c->cond = cond; c->mod = mod; c->fmod = fmod;
     c->tokens = tokens; c->qkv = qkv; c->eps = eps; c->silu_q = silu_q; c->qa_ln = qa_ln; c->qa_attn = qa_attn;
     c->qa_mlp = qa_mlp; c->cal_h = cal_h; c->cal_o = cal_o; c->cal_a = cal_a; c->cal_u = cal_u; c->cal_mod = cal_mod;
-    c->cal_slots = cal_slots; c->cal_label = cal_label; c->eps_ref = eps_ref; c->vcfit_work = vcfit_work;
+    c->cal_slots = cal_slots; c->cal_label = cal_label; c->eps_ref = eps_ref; c->vcfit_work = vcfit_work; c->dev_flags = dev_flags;
     c->qkv_hm = qkv_hm; c->qkv_part_stride = (long long)part;
     c->qkv_hm_bytes = (2 * part + vpart) * sizeof(float); c->DP = (int)DP; c->Tp = (int)Tp;
     c->win_rows = (int)WR;
@@ -316,6 +317,7 @@ int qc_load_weights_f32(qc_ctx *ctx, const qc_weights_f32 *w, void *stream) {
   for (auto &c : cp) QC_HIP(hipMemcpyAsync(c.dst, c.src, c.n * sizeof(float), hipMemcpyDeviceToDevice, st));
   // padding features / keys of the fp16 attention operands are never written afterwards and must read as zero
   QC_HIP(hipMemsetAsync(ctx->qkv_hm, 0, ctx->qkv_hm_bytes, st));
+  QC_HIP(hipMemsetAsync(ctx->dev_flags, 0, 64 * sizeof(int), st));
   for (int l = 0; l < ctx->L; ++l) {
     const qc_block_weights_f32 &b = w->blocks[l];
     const float *ws[QC_NUM_SITES] = {b.ada_w, b.qkv_w, b.proj_w, b.fc1_w, b.fc2_w};
@@ -653,6 +655,25 @@ int qc_set_cache_mask(qc_ctx *ctx, const unsigned char *mask, int steps) {
   return QC_OK;
 }
 
+// Waits for the stream, then reports and clears what the kernels flagged on the device.
+static int report_flags(qc_ctx *ctx, hipStream_t st) {
+  int f = 0;
+  QC_HIP(hipMemcpyAsync(&f, ctx->dev_flags, sizeof(int), hipMemcpyDeviceToHost, st));
+  QC_HIP(hipStreamSynchronize(st));
+  if (f) {
+    QC_HIP(hipMemsetAsync(ctx->dev_flags, 0, sizeof(int), st));
+    QC_HIP(hipStreamSynchronize(st));
+  }
+  if (f & 1) QC_FAIL(QC_ERR_RANGE, "a class label outside [0, %d] was passed (the null label is %d); it was clamped", ctx->d.num_classes, ctx->d.num_classes);
+  return QC_OK;
+}
+
+int qc_check(qc_ctx *ctx, void *stream) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  if (!ctx->weights_loaded) return QC_OK;
+  return report_flags(ctx, static_cast<hipStream_t>(stream));
+}
+
 int qc_keep_qkv_f32(qc_ctx *ctx, int on) {
   if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
   ctx->keep_qkv_f32 = on != 0;
@@ -672,7 +693,7 @@ static int run_cond(qc_ctx *ctx, const int32_t *t, int nw, const int32_t *labels
   }
   QC_HIP(launch_small_linear(ctx->emb, fd, ctx->t_w1, ctx->t_b1, ctx->h1, D, nw, D, fd, 0, 1, st));
   QC_HIP(launch_small_linear(ctx->h1, D, ctx->t_w2, ctx->t_b2, ctx->te, D, nw, D, D, 0, 0, st));
-  QC_HIP(launch_cond_finish(ctx->te, ctx->label_table, labels, n_labels, ctx->d.num_classes, nw * B, B, D, ctx->cond, st));
+  QC_HIP(launch_cond_finish(ctx->te, ctx->label_table, labels, n_labels, ctx->d.num_classes, nw * B, B, D, ctx->cond, ctx->dev_flags, st));
   return QC_OK;
 }
 
@@ -721,13 +742,8 @@ static int denoise_tail(qc_ctx *ctx, const Sub &sb, int mode, float *eps_out, hi
 // compute units, and every dependent kernel pays a few microseconds of dispatch latency), and latents
 // are independent, so the batch may be cut into sub-batches that run the network concurrently: the first
 // on the caller's stream, the others on internal streams, their launches interleaved block by block.
-// QC_LANES (environment) forces the number of sub-batches.
 static int choose_lanes(qc_ctx *ctx, int B) {
-  if (ctx->forced_lanes < 0) {
-    const char *e = getenv("QC_LANES");
-    ctx->forced_lanes = e ? atoi(e) : 0;
-  }
-  int n = ctx->forced_lanes > 0 ? ctx->forced_lanes : ((long long)B * ctx->T <= 4096 ? 2 : 1);
+  int n = (long long)B * ctx->T <= 4096 ? 2 : 1;
   if (n > MAX_LANES) n = MAX_LANES;
   if (n > B) n = B;
   return n < 1 ? 1 : n;

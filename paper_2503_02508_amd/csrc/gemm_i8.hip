@@ -973,17 +973,6 @@ static hipError_t launch_cfg(const GemmArgs &a, int nz, hipStream_t st) {
   return hipGetLastError();
 }
 
-// Tile choice.  QC_GEMM_TILE (environment, read once) forces one for tuning runs:
-// 1 = 128x128 and 2 = 256x128 on 4 wavefronts, 3 = 256x256 and 4 = 128x128 on 8 wavefronts.
-static int forced_tile() {
-  static int v = -1;
-  if (v < 0) {
-    const char *e = getenv("QC_GEMM_TILE");
-    v = e ? atoi(e) : 0;
-  }
-  return v;
-}
-
 template <int EPI, int TAG, bool W4>
 static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
   if constexpr (EPI != EPI_F32) {
@@ -991,13 +980,6 @@ static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
   }
   if (a.M <= 32) return launch_cfg<32, 128, 1, 4, EPI, TAG, W4, 3>(a, nz, st);
   if (a.M <= 64) return launch_cfg<64, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
-  switch (forced_tile()) {
-    case 1: return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
-    case 2: return launch_cfg<256, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
-    case 3: return launch_cfg<256, 256, 2, 4, EPI, TAG, W4, 2>(a, nz, st);
-    case 4: return launch_cfg<128, 128, 2, 4, EPI, TAG, W4, 3>(a, nz, st);
-    default: break;
-  }
   // Fewer tiles than compute units: a workgroup is alone on its CU and a single wavefront per SIMD cannot
   // keep the LDS and memory pipes busy (they are issue-bound per wavefront), so the tile is shared by 8.
   // The residual epilogue keeps a tile of x in registers, which would leave the 4-wavefront variant one
@@ -1009,9 +991,7 @@ static hipError_t launch_shape(const GemmArgs &a, int nz, hipStream_t st) {
   const int n_tiles = ((a.M + 127) / 128) * (((a.sel_D ? 2 * a.sel_D : a.N) + 127) / 128);
   if (EPI == EPI_RESID || n_tiles <= (EPI == EPI_QKV ? 128 : 256))
     return launch_cfg<128, 128, 2, 4, EPI, TAG, W4, 3>(a, nz, st);
-  // Otherwise 4 wavefronts per tile and two workgroups per compute unit.  (256x256 tiles on 8 wavefronts halve
-  // the L2 traffic per operation but measured no faster at M = 32768 and slower below, and their QKV
-  // epilogue does not fit the register file: they stay selectable for tuning only.)
+  // Otherwise 4 wavefronts per tile and two workgroups per compute unit.
   return launch_cfg<128, 128, 2, 2, EPI, TAG, W4, 3>(a, nz, st);
 }
 

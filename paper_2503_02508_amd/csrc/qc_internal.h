@@ -94,7 +94,7 @@ hipError_t launch_small_linear(const float *x, int ldx, const float *W, const fl
                                int K, int act_in, int act_out, hipStream_t st);
 hipError_t launch_time_embed(int t_first, int t_step, int W, int dim, float *out, hipStream_t st);
 hipError_t launch_cond_finish(const float *te, const float *table, const int32_t *labels, int n_labels, int null_label,
-                              int rows, int B, int D, float *c, hipStream_t st);
+                              int rows, int B, int D, float *c, int *flags, hipStream_t st);
 hipError_t launch_silu_quant(const float *c, int B, int D, int L, const QParam *qp, int qp_stride, int8_t *q,
                              size_t l_stride, hipStream_t st);
 hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, float *tok, int B, int n_src,

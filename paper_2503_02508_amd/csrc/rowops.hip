@@ -296,18 +296,22 @@ hipError_t launch_time_embed(int t_first, int t_step, int W, int dim, float *out
 // c[r, :] = te[r / B, :] + table[label of batch element r % B]: rows are (timestep slot, batch element)
 __global__ void cond_finish_kernel(const float *__restrict__ te, const float *__restrict__ table,
                                    const int32_t *__restrict__ labels, int n_labels, int null_label, int rows, int B, int D,
-                                   float *__restrict__ c) {
+                                   float *__restrict__ c, int *__restrict__ flags) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= rows * D) return;
   const int r = i / D, n = i % D, w = r / B, b = r % B;
-  const int y = b < n_labels ? labels[b] : null_label;
+  int y = b < n_labels ? labels[b] : null_label;
+  if (y < 0 || y > null_label) {                  // the table has null_label + 1 rows: clamp, and tell the host
+    if (n == 0) atomicOr(flags, 1);
+    y = min(max(y, 0), null_label);
+  }
   c[i] = te[(size_t)w * D + n] + table[(size_t)y * D + n];
 }
 
 hipError_t launch_cond_finish(const float *te, const float *table, const int32_t *labels, int n_labels, int null_label,
-                              int rows, int B, int D, float *c, hipStream_t st) {
+                              int rows, int B, int D, float *c, int *flags, hipStream_t st) {
   hipLaunchKernelGGL(cond_finish_kernel, dim3((rows * D + 255) / 256), dim3(256), 0, st, te, table, labels, n_labels,
-                     null_label, rows, B, D, c);
+                     null_label, rows, B, D, c, flags);
   return hipGetLastError();
 }
 

@@ -1225,11 +1225,21 @@ SimProfile g_prof;
 // Each stage below takes `ext`: null = use the flag word in its own workspace and report the error before returning
 // (the stage waits for the stream); non-null = raise that device flag instead and only enqueue (the caller reads the
 // flags of several stages, possibly of several streams, later).
-// internal streams of qc_tap_cluster (created on first use, kept for the life of the process; default priority)
+// Internal streams and events of one qc_tap_cluster call (default priority).  They belong to the call, not to the
+// process: calls from several host threads, or on several devices, share nothing.
 constexpr int MAX_SLOTS = 3;
-hipStream_t g_streams[MAX_SLOTS] = {nullptr, nullptr, nullptr};
-hipEvent_t g_fork = nullptr;
-hipEvent_t g_chain[MAX_SLOTS] = {nullptr, nullptr, nullptr};
+struct CallStreams {
+  hipStream_t streams[MAX_SLOTS] = {nullptr, nullptr, nullptr};
+  hipEvent_t fork = nullptr;
+  hipEvent_t chain[MAX_SLOTS] = {nullptr, nullptr, nullptr};
+  ~CallStreams() {
+    for (int j = 0; j < MAX_SLOTS; ++j) {
+      if (streams[j]) { (void)hipStreamSynchronize(streams[j]); (void)hipStreamDestroy(streams[j]); }
+      if (chain[j]) (void)hipEventDestroy(chain[j]);
+    }
+    if (fork) (void)hipEventDestroy(fork);
+  }
+};
 
 // `gemm_after` (may be null): the contraction starts after this event.  A caller that runs several subsamples on
 // several streams chains them (embed_impl records the matching event after its own large product), so that the
@@ -1603,14 +1613,16 @@ int qc_tap_cluster(const float *X, const float *t, int N, int F, const int *subs
   if (slots > MAX_SLOTS) slots = MAX_SLOTS;
   if (slots > m) slots = m;
   hipStream_t ss[MAX_SLOTS] = {st, nullptr, nullptr};
+  CallStreams cs;                                 // destroyed (after a wait on each stream) on every way out
   if (slots > 1) {
-    if (!g_fork) TAP_HIP(hipEventCreateWithFlags(&g_fork, hipEventDisableTiming));
-    TAP_HIP(hipEventRecord(g_fork, st));
+    TAP_HIP(hipEventCreateWithFlags(&cs.fork, hipEventDisableTiming));
+    TAP_HIP(hipEventRecord(cs.fork, st));
     for (int j = 1; j < slots; ++j) {
-      if (!g_streams[j]) TAP_HIP(hipStreamCreateWithFlags(&g_streams[j], hipStreamNonBlocking));
-      TAP_HIP(hipStreamWaitEvent(g_streams[j], g_fork, 0));
-      ss[j] = g_streams[j];
+      TAP_HIP(hipStreamCreateWithFlags(&cs.streams[j], hipStreamNonBlocking));
+      TAP_HIP(hipStreamWaitEvent(cs.streams[j], cs.fork, 0));
+      ss[j] = cs.streams[j];
     }
+    for (int j = 0; j < slots; ++j) TAP_HIP(hipEventCreateWithFlags(&cs.chain[j], hipEventDisableTiming));
   }
   for (int i0 = 0; i0 < m; i0 += slots) {
     const int ns = m - i0 < slots ? m - i0 : slots;
@@ -1619,12 +1631,11 @@ int qc_tap_cluster(const float *X, const float *t, int N, int F, const int *subs
       ClusterWork w(static_cast<char *>(work) + (size_t)j * per, N, F, n, k, kb);
       const int i = i0 + j;
       hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, ss[j], w.flags, 64, 0);
-      if (slots > 1 && !g_chain[j]) TAP_HIP(hipEventCreateWithFlags(&g_chain[j], hipEventDisableTiming));
       TAP_RC(similarity_impl(X, t, N, F, subsamples + (size_t)i * n, n, alpha, w.A, w.dr, w.dc, w.sub, ss[j], w.flags + 0,
-                             j > 0 ? g_chain[j - 1] : nullptr));
+                             j > 0 ? cs.chain[j - 1] : nullptr));
       TAP_RC(normalise_impl(w.A, w.dr, w.dc, N, n, w.sub, ss[j], w.flags + 1));
       TAP_RC(embed_impl(w.A, N, n, k, kb, iters, q0, w.U, w.sigma, w.sub, ss[j], w.flags + 2,
-                        slots > 1 ? g_chain[j] : nullptr));
+                        slots > 1 ? cs.chain[j] : nullptr));
       km[j] = KmSlot{w.U, init_idx + (size_t)i * k, per_labels + (size_t)i * N, w.centres, w.sub, ss[j], w.flags + 3, 0, false};
     }
     // the first pass of the k-means below runs on whatever the earlier stages left; the flags tell afterwards

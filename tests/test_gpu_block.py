@@ -484,3 +484,29 @@ def test_calibration_matches_oracle():
             assert abs(gs - float(s)) <= 2e-5 * float(s), (blk, site, gs, s)
             assert abs(gz - z) <= 1, (blk, site, gz, z)
         ctx.close()
+
+
+def test_out_of_range_label_is_clamped_and_reported():
+    """Labels live on the device: a label outside [0, num_classes] is clamped by the conditioning kernel, the run
+    completes with the clamped label's result, and qc_check reports QC_ERR_RANGE once."""
+    import torch
+    import paper_2503_02508_amd as qc
+    model = TINY
+    w = I.make_weights(model, 5, std=0.15)
+    ctx = qc.Context(model, 2, 1)
+    ctx.load_weights(w)
+    for blk in range(model.depth):
+        for site in range(5):
+            ctx.set_act_qparams(blk, site, 0.05, 128)
+    x = _cuda(I.make_latents(2, model, 6))
+    eps_bad, eps_ok = torch.empty_like(x), torch.empty_like(x)
+    ctx.check()                                                       # nothing flagged yet
+    ctx.denoise(x, 300, _cuda(np.array([1, model.num_classes + 7], dtype=np.int32)), 2, qc.QC_FULL, eps_bad)
+    with pytest.raises(qc.QCError) as e:
+        ctx.check()
+    assert e.value.code == -4
+    ctx.check()                                                       # reported once, then cleared
+    ctx.denoise(x, 300, _cuda(np.array([1, model.num_classes], dtype=np.int32)), 2, qc.QC_FULL, eps_ok)
+    ctx.check()
+    assert torch.equal(eps_bad, eps_ok)
+    ctx.close()

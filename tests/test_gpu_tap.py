@@ -259,6 +259,42 @@ def test_cluster_recovers_planted_groups_like_the_oracle(qc, N, F, k, n, kb, m, 
     assert np.array_equal(final.cpu().numpy(), truth)                # centre g starts inside planted group g
 
 
+def test_cluster_on_a_pool_without_planted_groups_gives_the_oracles_labels(qc):
+    """The small workload's pool (diffusion-like samples of 16 classes at 50 noise levels, no planted groups: the
+    singular values fall off smoothly after the third): with 100 rounds of the block iteration the embedding spans
+    the oracle's subspace to 1 - cos <= 1e-6, and the whole algorithm (three subsamples, k-means, alignment, vote)
+    returns the oracle's labels, per subsample and final, at the benchmark's 8 rounds and at 100."""
+    import torch
+    wl = TI.TAP_WORKLOADS["tap0"]
+    kb = 32
+    N, F, n, k, m = wl.N, wl.F, wl.n, wl.k, wl.m
+    X, t, _, _ = TI.make_pool(N, F, wl.steps, wl.classes, wl.seed)
+    subs = TI.make_subsamples(N, n, m, wl.seed + 1)
+    init = TI.make_init(N, k, m, wl.seed + 2)
+    q0 = TI.make_start_block(kb, n, wl.seed + 3)
+    wf, wp = tap.tap(X, t, subs, wl.alpha, k, init, 100)
+    assert len(np.unique(wf)) == k                                    # every cluster is used: not a degenerate pool
+    work = _work(qc, N, F, n, k, kb)
+    # subspace of the first subsample's embedding
+    A = torch.empty((N, n), device="cuda")
+    dr, dc = torch.empty(N, device="cuda"), torch.empty(n, device="cuda")
+    qc.qc_tap_similarity(_cuda(X), _cuda(t), _cuda(subs[0]), wl.alpha, A, dr, dc, work)
+    qc.qc_tap_normalise(A, dr, dc, work)
+    U, sig = torch.empty((N, k), device="cuda"), torch.empty(k, device="cuda")
+    qc.qc_tap_embed(A, k, 100, _cuda(q0), U, sig, work)
+    Uo, so = tap.embed(tap.normalised(tap.similarity(X, t, subs[0], wl.alpha)), k + 1)
+    assert so[k - 1] / so[k] > 1.01                                   # the k-th and (k+1)-th values are distinct
+    cosines = np.linalg.svd(U.cpu().numpy().astype(np.float64).T @ Uo[:, :k], compute_uv=False)
+    assert cosines.min() >= 1 - 1e-6, cosines
+    assert np.allclose(sig.cpu().numpy(), so[:k], atol=2e-6)
+    for iters in (8, 100):
+        final = torch.empty(N, dtype=torch.int32, device="cuda")
+        per = torch.empty((m, N), dtype=torch.int32, device="cuda")
+        qc.qc_tap_cluster(_cuda(X), _cuda(t), _cuda(subs), wl.alpha, k, iters, _cuda(q0), _cuda(init), 100, final, per, work)
+        assert np.array_equal(per.cpu().numpy(), wp), iters
+        assert np.array_equal(final.cpu().numpy(), wf), iters
+
+
 # ------------------------------------------------------- the paper's sizes, in the configuration bench.py times
 def test_paper_sized_pool_sampled_outputs_and_properties(qc):
     """N = 32768 samples of 4096 features, subsamples of N / 20, 100 clusters, iteration block 128, 8 power
@@ -302,12 +338,23 @@ def test_paper_sized_pool_sampled_outputs_and_properties(qc):
     # the leading left singular vector of the normalised matrix is sqrt(d_r) up to scale
     u1 = torch.sqrt(dr.double() / dr.double().sum())
     assert abs(abs(float(u1 @ Ud[:, 0])) - 1.0) <= 1e-6
-    # singular pairs: L L^T u_j = sigma_j^2 u_j for the leading, well separated ones
+    # Convergence criterion of the block iteration, for ALL k pairs at the iteration count bench.py times (8 rounds
+    # with a block of 128): || L L^T u_j - sigma_j^2 u_j || <= 2e-6 sigma_1^2 (measured: 6e-7 for the leading pair, whose
+    # residual is fp32 rounding of entries of size 1, and below 2e-7 for all others), and every sigma_j within 5e-5 of
+    # the singular values a library routine (float64 SVD of the device's own normalised matrix) returns; the trailing
+    # values of this pool lie 1e-6 apart, so single vectors are not pinned there, the invariant subspace is.
     Ld = A.double()
-    for j in range(5):
-        res = Ld @ (Ld.T @ Ud[:, j]) - s[j] ** 2 * Ud[:, j]
-        assert float(res.norm()) <= 1e-5 * s[0] ** 2, (j, float(res.norm()))
-    del Ld
+    res = (Ld @ (Ld.T @ Ud) - Ud * torch.from_numpy(s ** 2).cuda()[None]).norm(dim=0).cpu().numpy()
+    assert res.shape == (k,) and res.max() <= 2e-6 * s[0] ** 2, (int(res.argmax()), float(res.max()))
+    sv = torch.linalg.svdvals(Ld).cpu().numpy()
+    assert np.abs(s - sv[:k]).max() <= 5e-5, float(np.abs(s - sv[:k]).max())
+    # 32 rounds bring every sigma_j to the library's within fp32 rounding
+    U32, sig32 = torch.empty((N, k), device="cuda"), torch.empty(k, device="cuda")
+    qc.qc_tap_embed(A, k, 32, _cuda(TI.make_start_block(kb, n, wl.seed + 3)), U32, sig32, work)
+    assert np.abs(sig32.cpu().numpy().astype(np.float64) - sv[:k]).max() <= 5e-7
+    res32 = (Ld @ (Ld.T @ U32.double()) - U32.double() * (sig32.double() ** 2)[None]).norm(dim=0)
+    assert float(res32.max()) <= 2e-6
+    del Ld, U32
 
     labels = torch.empty(N, dtype=torch.int32, device="cuda")
     centres = torch.empty((k, k), device="cuda")

@@ -236,6 +236,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cache-format", choices=["fp32", "bf16"], default="fp32",
                     help="storage of the cached module outputs (fp32 is the headline configuration)")
+    ap.add_argument("--stream-format", choices=["fp32", "bf16"], default="fp32",
+                    help="storage of the residual stream (fp32 is the headline configuration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (latents are independent, so more GPUs would each run "
@@ -265,6 +267,7 @@ def main():
     ctx.calibrate(torch.from_numpy(clat).cuda(), [tt[i] for i in idx], clab)
     ctx.drop_fp32()
     ctx.set_cache_format(args.cache_format)
+    ctx.set_stream_format(args.stream_format)
     del w
     lat = torch.from_numpy(I.make_latents(B, m, wl.seed_latents)).cuda()
     lab = torch.from_numpy(I.make_labels(B, m, wl.seed_labels).astype(np.int32)).cuda()
@@ -310,6 +313,7 @@ def main():
             p["avg_us"] = p["total_ms"] * 1e3 / max(p["launches"], 1)
         MT, D, R = Beff * m.tokens, m.hidden, m.mlp_dim
         per_pass = n_full * m.depth        # full blocks in one pass
+        sb = 2 if args.stream_format == "bf16" else 4      # bytes per residual-stream element
         # algorithmic work of each class in one pass; a pass may cut the batch into sub-batches that are
         # launched separately, so the work of one launch is the class's work over its launches
         work = {
@@ -318,10 +322,10 @@ def main():
             "gemm_fc1": ("mfma", 2.0 * MT * R * D * per_pass),
             "gemm_fc2": ("mfma", 2.0 * MT * D * R * per_pass),
             "attention": ("mfma16", 4.0 * Beff * m.heads * m.tokens * m.tokens * m.head_dim * per_pass),
-            # fp32 row in, int8 codes out
-            "ln_mod_quant": ("hbm", 5.0 * MT * D * 2 * per_pass),
+            # residual-stream row in, int8 codes out
+            "ln_mod_quant": ("hbm", (sb + 1.0) * MT * D * 2 * per_pass),
             # both cached tensors of every block read once, the residual stream read and written once
-            "cached_blocks": ("hbm", (2.0 * m.depth * (2 if args.cache_format == "bf16" else 4) + 2.0 * 4) * MT * D
+            "cached_blocks": ("hbm", (2.0 * m.depth * (2 if args.cache_format == "bf16" else 4) + 2.0 * sb) * MT * D
                               * (wl.steps - n_full)),
             # sample and noise estimate(s) read, sample written; one launch per step
             "ddim_vc": ("hbm", (4.0 * (B + Beff) + 4.0 * B) * m.latent_c * m.latent_h * m.latent_w * wl.steps),
@@ -352,7 +356,7 @@ def main():
         "config": {"workload": wl.name, "latents": B, "effective_batch": Beff, "sampler_steps": wl.steps,
                    "cache_interval": wl.cache_interval, "refresh_steps": n_full, "cfg_scale": wl.cfg_scale,
                    "weight_bits": m.weight_bits, "vc": True,
-                   "cache_format": args.cache_format},
+                   "cache_format": args.cache_format, "stream_format": args.stream_format},
         "int8_tops_end_to_end": total_int8 / (ms_per_step * 1e-3) / 1e12,
         "full_step_us": full_us, "cached_step_us": cached_us,
         "roofline": roofline,

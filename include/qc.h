@@ -52,7 +52,7 @@ enum { QC_FULL = 0, QC_CACHED = 1 };                 /* block / step mode       
 enum { QC_CACHE_ATTN = 0, QC_CACHE_MLP = 1 };        /* which cached module output */
 enum { QC_SITE_ADA = 0, QC_SITE_QKV = 1, QC_SITE_PROJ = 2, QC_SITE_FC1 = 3, QC_SITE_FC2 = 4, QC_NUM_SITES = 5 };
 enum {                                               /* qc_workspace_ptr selectors */
-  QC_WS_TOKENS = 0,   /* float  [B, T, D]  residual stream of the last denoiser call      */
+  QC_WS_TOKENS = 0,   /* float (bfloat16 under QC_STREAM_BF16) [B, T, D]  residual stream of the last denoiser call */
   QC_WS_QACT_LN = 1,  /* int8   [B*T, D]   codes produced by the last LN+modulate+quantise */
   QC_WS_QACT_ATTN = 2,/* int8   [B*T, D]   codes of the last attention output              */
   QC_WS_QACT_MLP = 3, /* int8   [B*T, R]   codes of the last GELU output                    */
@@ -223,6 +223,15 @@ int qc_cache_ptr(qc_ctx *ctx, int block, int which, void **ptr_out);
  * cache holds. */
 enum { QC_CACHE_FP32 = 0, QC_CACHE_BF16 = 1 };
 int qc_set_cache_format(qc_ctx *ctx, int format);
+/* Storage format of the residual stream inside the network-level calls (qc_denoise, qc_sample_step, qc_sample):
+ * the token tensor [B, T, D] that the patch embedding writes and every block reads and updates.  QC_STREAM_FP32
+ * (default) keeps float32.  QC_STREAM_BF16 stores the bfloat16 rounding (nearest even) of every float32 value
+ * written to it - the embedding's output and the stream after every gated add - so that the LayerNorm kernels,
+ * the proj / fc2 epilogues and the cached-block kernel move half the bytes of it; all other tensors keep their
+ * formats.  Not in the paper: a precision choice of this implementation, off by default; qc_dit_block, whose
+ * stream is the caller's float32 tensor, is not affected.  Set it between sampling runs, not inside one. */
+enum { QC_STREAM_FP32 = 0, QC_STREAM_BF16 = 1 };
+int qc_set_stream_format(qc_ctx *ctx, int format);
 /* Device address of an internal buffer, see QC_WS_*; for inspection by tests. */
 int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out);
 

@@ -30,6 +30,13 @@ right where they are produced (LayerNorm + modulation output, attention
 output, GELU output) are never stored: Eq. 1 rounds the float64 value to
 float32 once and decides there.  `storage("f64")` switches the rounding off
 (used to check the formulas against library routines to 1e-10).
+
+Reduced-precision residual stream (not in the paper: a storage variant that
+halves the bytes every block reads and writes of it): under
+`stream_format("bf16")` the token tensor - the patch embedding's output and
+the residual stream after every gated add - is stored as bfloat16 (`st_x()`:
+the float64 value rounded to float32, then to bfloat16, ties to even); every
+other stored tensor keeps float32.
 """
 from __future__ import annotations
 
@@ -48,6 +55,27 @@ def st(x):
     """The value of x after it is stored as a float32 tensor."""
     x = np.asarray(x, dtype=F64)
     return x.astype(np.float32).astype(F64) if _STORE_F32 else x
+
+
+_STREAM_BF16 = False
+
+
+def st_x(x):
+    """The value of the token tensor / residual stream x after it is stored (float32, or bfloat16 under
+    stream_format("bf16"))."""
+    return bf16_round(st(x)) if (_STREAM_BF16 and _STORE_F32) else st(x)
+
+
+@contextlib.contextmanager
+def stream_format(kind: str):
+    """stream_format("bf16"): the residual stream is stored as bfloat16; stream_format("f32"): the default."""
+    global _STREAM_BF16
+    old = _STREAM_BF16
+    _STREAM_BF16 = {"f32": False, "bf16": True}[kind]
+    try:
+        yield
+    finally:
+        _STREAM_BF16 = old
 
 
 @contextlib.contextmanager
@@ -151,12 +179,12 @@ def block_full(x, c, blk: int, heads: int, linear, cache: dict | None = None, ta
     qkv = st(linear(blk, "qkv", h.reshape(B * T, D))).reshape(B, T, 3 * D)
     o = attention(qkv, heads)
     A = st(linear(blk, "proj", o.reshape(B * T, D))).reshape(B, T, D)
-    x = st(x + gate_msa[:, None, :] * A)
+    x = st_x(x + gate_msa[:, None, :] * A)
     h2 = modulate(layer_norm(x), shift_mlp, scale_mlp)
     u = linear(blk, "fc1", h2.reshape(B * T, D))
     g = gelu_tanh(u)
     Mo = st(linear(blk, "fc2", g)).reshape(B, T, D)
-    x = st(x + gate_mlp[:, None, :] * Mo)
+    x = st_x(x + gate_mlp[:, None, :] * Mo)
     if cache is not None:
         cache[(blk, "attn")] = bf16_round(A) if cache_bf16 else A
         cache[(blk, "mlp")] = bf16_round(Mo) if cache_bf16 else Mo
@@ -169,8 +197,8 @@ def block_cached(x, c, blk: int, linear, cache: dict):
     """A block on a non-refresh step: the stored module outputs are reused and
     only the gates come from the current conditioning."""
     _, _, gate_msa, _, _, gate_mlp = block_mod(c, blk, linear)
-    x = st(x + gate_msa[:, None, :] * cache[(blk, "attn")])
-    x = st(x + gate_mlp[:, None, :] * cache[(blk, "mlp")])
+    x = st_x(x + gate_msa[:, None, :] * cache[(blk, "attn")])
+    x = st_x(x + gate_mlp[:, None, :] * cache[(blk, "mlp")])
     return x
 
 
@@ -190,14 +218,14 @@ def block_mixed(x, c, blk: int, heads: int, linear, cache: dict, attn_full: bool
         cache[(blk, "attn")] = bf16_round(A) if cache_bf16 else A
     else:
         A = cache[(blk, "attn")]
-    x = st(x + gate_msa[:, None, :] * A)
+    x = st_x(x + gate_msa[:, None, :] * A)
     if mlp_full:
         h2 = modulate(layer_norm(x), shift_mlp, scale_mlp)
         Mo = st(linear(blk, "fc2", gelu_tanh(linear(blk, "fc1", h2.reshape(B * T, D))))).reshape(B, T, D)
         cache[(blk, "mlp")] = bf16_round(Mo) if cache_bf16 else Mo
     else:
         Mo = cache[(blk, "mlp")]
-    x = st(x + gate_mlp[:, None, :] * Mo)
+    x = st_x(x + gate_mlp[:, None, :] * Mo)
     return x
 
 
@@ -236,7 +264,7 @@ def unpatchify(tok, p: int, c_out: int, H: int, W: int):
 
 def embed(x_lat, w: dict, p: int):
     tok = patchify(np.asarray(x_lat, dtype=F64), p)
-    return st(tok @ w["patch_w"].astype(F64).T + w["patch_b"].astype(F64) + w["pos"].astype(F64)[None])
+    return st_x(tok @ w["patch_w"].astype(F64).T + w["patch_b"].astype(F64) + w["pos"].astype(F64)[None])
 
 
 def final_layer(x, c, w: dict, p: int, C: int, H: int, W: int):

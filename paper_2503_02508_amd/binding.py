@@ -75,6 +75,7 @@ _SIGS = {
     "qc_sample": (i32, [vp, vp, vp, i32, i32, f32, vp, vp]),
     "qc_keep_qkv_f32": (i32, [vp, i32]),
     "qc_check": (i32, [vp, vp]),
+    "qc_set_stream_format": (i32, [vp, i32]),
     "qc_tap_workspace_bytes": (i32, [i32, i32, i32, i32, i32, C.POINTER(sz)]),
     "qc_tap_similarity": (i32, [vp, vp, i32, i32, vp, i32, f32, vp, vp, vp, vp, sz, vp]),
     "qc_tap_normalise": (i32, [vp, vp, vp, i32, i32, vp, sz, vp]),
@@ -314,6 +315,10 @@ class Context:
 
     def keep_qkv_f32(self, on=True):
         _chk(lib.qc_keep_qkv_f32(self.h, int(on)))
+
+    def set_stream_format(self, fmt):
+        """"fp32" (default) or "bf16": storage of the residual stream inside denoise / sample_step / sample."""
+        _chk(lib.qc_set_stream_format(self.h, {"fp32": 0, "bf16": 1}[fmt]))
 
     def check(self):
         """Waits for the current stream; raises if a kernel flagged an out-of-range class label since the last call."""

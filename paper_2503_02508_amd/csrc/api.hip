@@ -99,6 +99,7 @@ struct qc_ctx {
   int DP, Tp;
   int win_rows;               // row capacity of cond / fmod / mod / silu_q (per block for the last two)
   bool keep_qkv_f32 = false;
+  bool stream_bf16 = false;   // the network-level calls keep the residual stream (tokens) as bfloat16
   // calibration scratch (one sample)
   float *cal_h, *cal_o, *cal_a, *cal_u, *cal_mod;
   int *cal_slots, *cal_label;
@@ -473,7 +474,7 @@ static int run_adaln(qc_ctx *ctx, int l0, int nl, int r0, int rows, bool gates_o
 }
 
 // One full block on the rows of sub-batch sb; x points at the first of those rows.
-static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream_t st, bool attn_full = true,
+static int run_block_full(qc_ctx *ctx, int l, void *x, int xb, const Sub &sb, hipStream_t st, bool attn_full = true,
                           bool mlp_full = true) {
   const int D = ctx->D, R = ctx->R, T = ctx->T, B = sb.nb, M = B * T;
   const size_t row0 = (size_t)sb.b0 * T;
@@ -492,11 +493,11 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
     return a;
   };
   if (!attn_full) {
-    QC_HIP(launch_cache_reuse(x, cache_at(ctx, l, QC_CACHE_ATTN, row0 * D), mod + 2 * D, 6 * D, B, T, D, ctx->cache_bf16, st));
+    QC_HIP(launch_cache_reuse(x, xb, cache_at(ctx, l, QC_CACHE_ATTN, row0 * D), mod + 2 * D, 6 * D, B, T, D, ctx->cache_bf16, st));
   } else {
   {
     QC_PROF(QC_K_LN_QUANT);
-    QC_HIP(launch_ln_mod_quant(x, mod, mod + D, 6 * D, M, D, T, qp + QC_SITE_QKV, qa_ln, nullptr, st));
+    QC_HIP(launch_ln_mod_quant(x, xb, mod, mod + D, 6 * D, M, D, T, qp + QC_SITE_QKV, qa_ln, nullptr, st));
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_QKV], qa_ln, D, QC_SITE_QKV);
@@ -512,19 +513,19 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_PROJ], qa_attn, D, QC_SITE_PROJ);
-    a.cache_out = cache_at(ctx, l, QC_CACHE_ATTN, row0 * D); a.cache_bf16 = ctx->cache_bf16; a.x = x; a.gate = mod + 2 * D; a.ld_gate = 6 * D;
+    a.cache_out = cache_at(ctx, l, QC_CACHE_ATTN, row0 * D); a.cache_bf16 = ctx->cache_bf16; a.x = x; a.x_bf16 = xb; a.gate = mod + 2 * D; a.ld_gate = 6 * D;
     a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_PROJ);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_PROJ));
   }
   }
   if (!mlp_full) {
-    QC_HIP(launch_cache_reuse(x, cache_at(ctx, l, QC_CACHE_MLP, row0 * D), mod + 5 * D, 6 * D, B, T, D, ctx->cache_bf16, st));
+    QC_HIP(launch_cache_reuse(x, xb, cache_at(ctx, l, QC_CACHE_MLP, row0 * D), mod + 5 * D, 6 * D, B, T, D, ctx->cache_bf16, st));
     return QC_OK;
   }
   {
     QC_PROF(QC_K_LN_QUANT);
-    QC_HIP(launch_ln_mod_quant(x, mod + 3 * D, mod + 4 * D, 6 * D, M, D, T, qp + QC_SITE_FC1, qa_ln, nullptr, st));
+    QC_HIP(launch_ln_mod_quant(x, xb, mod + 3 * D, mod + 4 * D, 6 * D, M, D, T, qp + QC_SITE_FC1, qa_ln, nullptr, st));
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_FC1], qa_ln, D, QC_SITE_FC1);
@@ -534,7 +535,7 @@ static int run_block_full(qc_ctx *ctx, int l, float *x, const Sub &sb, hipStream
   }
   {
     GemmArgs a = base(bq.lin[QC_SITE_FC2], qa_mlp, R, QC_SITE_FC2);
-    a.cache_out = cache_at(ctx, l, QC_CACHE_MLP, row0 * D); a.cache_bf16 = ctx->cache_bf16; a.x = x; a.gate = mod + 5 * D; a.ld_gate = 6 * D;
+    a.cache_out = cache_at(ctx, l, QC_CACHE_MLP, row0 * D); a.cache_bf16 = ctx->cache_bf16; a.x = x; a.x_bf16 = xb; a.gate = mod + 5 * D; a.ld_gate = 6 * D;
     a.rows_per_batch = T;
     QC_PROF(QC_K_GEMM_FC2);
     QC_HIP(launch_gemm(a, EPI_RESID, 1, st, QC_SITE_FC2));
@@ -559,13 +560,13 @@ int qc_dit_block(qc_ctx *ctx, int block, int mode, float *x, const float *c, int
   rc = run_adaln(ctx, block, 1, 0, B, mode == QC_CACHED, st);
   if (rc) return rc;
   if (mode == QC_FULL) {
-    rc = run_block_full(ctx, block, x, whole, st);
+    rc = run_block_full(ctx, block, x, 0, whole, st);
     ctx->cache_batch[(size_t)block * 2] = ctx->cache_batch[(size_t)block * 2 + 1] = B;
     return rc;
   }
   const float *mod = ctx->mod + (size_t)block * ctx->win_rows * 6 * D;
-  QC_HIP(launch_cache_reuse(x, cache_at(ctx, block, QC_CACHE_ATTN), mod + 2 * D, (int)(6 * D), B, ctx->T, (int)D, ctx->cache_bf16, st));
-  QC_HIP(launch_cache_reuse(x, cache_at(ctx, block, QC_CACHE_MLP), mod + 5 * D, (int)(6 * D), B, ctx->T, (int)D, ctx->cache_bf16, st));
+  QC_HIP(launch_cache_reuse(x, 0, cache_at(ctx, block, QC_CACHE_ATTN), mod + 2 * D, (int)(6 * D), B, ctx->T, (int)D, ctx->cache_bf16, st));
+  QC_HIP(launch_cache_reuse(x, 0, cache_at(ctx, block, QC_CACHE_MLP), mod + 5 * D, (int)(6 * D), B, ctx->T, (int)D, ctx->cache_bf16, st));
   return QC_OK;
 }
 
@@ -595,7 +596,7 @@ int qc_cache_reuse(qc_ctx *ctx, int block, int which, float *x, const float *gat
   if (!aligned16(x) || !aligned16(gate)) QC_FAIL(QC_ERR_ALIGN, "x and gate must be 16-byte aligned");
   if (ctx->cache_batch[(size_t)block * 2 + which] != B)
     QC_FAIL(QC_ERR_STATE, "block %d holds no cached tensor %d for batch %d", block, which, B);
-  QC_HIP(launch_cache_reuse(x, cache_at(ctx, block, which), gate, ld_gate, B, ctx->T, ctx->D, ctx->cache_bf16, static_cast<hipStream_t>(stream)));
+  QC_HIP(launch_cache_reuse(x, 0, cache_at(ctx, block, which), gate, ld_gate, B, ctx->T, ctx->D, ctx->cache_bf16, static_cast<hipStream_t>(stream)));
   return QC_OK;
 }
 
@@ -613,7 +614,7 @@ int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out) 
   void *p = nullptr;
   size_t n = 0;
   switch (which) {
-    case QC_WS_TOKENS: p = ctx->tokens; n = M * D * 4; break;
+    case QC_WS_TOKENS: p = ctx->tokens; n = M * D * (ctx->stream_bf16 ? 2 : 4); break;
     case QC_WS_QACT_LN: p = ctx->qa_ln; n = M * D; break;
     case QC_WS_QACT_ATTN: p = ctx->qa_attn; n = M * D; break;
     case QC_WS_QACT_MLP: p = ctx->qa_mlp; n = M * ctx->R; break;
@@ -634,6 +635,13 @@ int qc_set_cache_format(qc_ctx *ctx, int format) {
   if (format != QC_CACHE_FP32 && format != QC_CACHE_BF16) QC_FAIL(QC_ERR_RANGE, "format must be QC_CACHE_FP32 or QC_CACHE_BF16");
   ctx->cache_bf16 = format == QC_CACHE_BF16;
   for (int &v : ctx->cache_batch) v = 0;      // what the cache holds is in the other format: nothing is stored
+  return QC_OK;
+}
+
+int qc_set_stream_format(qc_ctx *ctx, int format) {
+  if (!ctx) QC_FAIL(QC_ERR_NULL, "ctx is NULL");
+  if (format != QC_STREAM_FP32 && format != QC_STREAM_BF16) QC_FAIL(QC_ERR_RANGE, "format must be QC_STREAM_FP32 or QC_STREAM_BF16");
+  ctx->stream_bf16 = format == QC_STREAM_BF16;
   return QC_OK;
 }
 
@@ -715,10 +723,16 @@ static int prepare_window(qc_ctx *ctx, const int32_t *t, int nw, const int32_t *
 
 // The x-dependent part of the network on one sub-batch (rows b0 .. b0+nb of the effective batch) in three
 // pieces, so that the caller can interleave the launches of several sub-batches: the patch embedding ...
+// The token tensor of the network-level calls: float32, or bfloat16 in the reduced-precision variant (the same
+// buffer, half used); element offset -> address.
+static void *tokens_at(qc_ctx *ctx, size_t elem) {
+  return reinterpret_cast<char *>(ctx->tokens) + elem * (ctx->stream_bf16 ? 2 : 4);
+}
+
 static int denoise_head(qc_ctx *ctx, const float *x, int n_labels, const Sub &sb, hipStream_t st) {
   const int D = ctx->D;
-  QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens + (size_t)sb.b0 * ctx->T * D, sb.nb, n_labels, ctx->C,
-                      ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, sb.b0, st));
+  QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, tokens_at(ctx, (size_t)sb.b0 * ctx->T * D), ctx->stream_bf16,
+                      sb.nb, n_labels, ctx->C, ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, sb.b0, st));
   return QC_OK;
 }
 
@@ -726,14 +740,15 @@ static int denoise_head(qc_ctx *ctx, const float *x, int n_labels, const Sub &sb
 static int denoise_tail(qc_ctx *ctx, const Sub &sb, int mode, float *eps_out, hipStream_t st) {
   const int D = ctx->D, L = ctx->L, B = sb.nb;
   const size_t lat = (size_t)ctx->C * ctx->d.latent_h * ctx->d.latent_w;
-  float *tokens = ctx->tokens + (size_t)sb.b0 * ctx->T * D;
+  void *tokens = tokens_at(ctx, (size_t)sb.b0 * ctx->T * D);
+  const int xb = ctx->stream_bf16;
   if (mode == QC_CACHED) {
     const size_t slot = (size_t)ctx->max_batch * ctx->T * D;
     QC_PROF(QC_K_CACHED_BLOCKS);
-    QC_HIP(launch_cached_blocks(tokens, cache_at(ctx, 0, 0, (size_t)sb.b0 * ctx->T * D), 2 * slot, slot, ctx->mod + (size_t)sb.r0 * 6 * D,
+    QC_HIP(launch_cached_blocks(tokens, xb, cache_at(ctx, 0, 0, (size_t)sb.b0 * ctx->T * D), 2 * slot, slot, ctx->mod + (size_t)sb.r0 * 6 * D,
                                 (size_t)ctx->win_rows * 6 * D, 6 * D, L, B, ctx->T, D, ctx->cache_bf16, st));
   }
-  QC_HIP(launch_final(tokens, ctx->fmod + (size_t)sb.r0 * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + (size_t)sb.b0 * lat, B,
+  QC_HIP(launch_final(tokens, xb, ctx->fmod + (size_t)sb.r0 * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + (size_t)sb.b0 * lat, B,
                       ctx->C, ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, st));
   return QC_OK;
 }
@@ -787,7 +802,7 @@ static int denoise_impl(qc_ctx *ctx, const float *x, int n_labels, int B, int mo
   if (mode == QC_FULL || mixed)
     for (int l = 0; l < ctx->L && !rc; ++l)
       for (int i = 0; i < lanes && !rc; ++i)
-        rc = run_block_full(ctx, l, ctx->tokens + (size_t)sub[i].b0 * ctx->T * ctx->D, sub[i], ls[i],
+        rc = run_block_full(ctx, l, tokens_at(ctx, (size_t)sub[i].b0 * ctx->T * ctx->D), ctx->stream_bf16, sub[i], ls[i],
                             mixed ? sched[2 * l] != 0 : true, mixed ? sched[2 * l + 1] != 0 : true);
   for (int i = 0; i < lanes && !rc; ++i) rc = denoise_tail(ctx, sub[i], mixed ? QC_FULL : mode, eps_out, ls[i]);
   // join even after an error so that the internal streams never run past the caller's stream unobserved
@@ -949,19 +964,19 @@ static int fp32_blocks_one(qc_ctx *ctx, const qc_weights_f32 *w, const float *co
     float *mod = ctx->cal_mod;
     if (slot) QC_HIP(launch_minmax_silu(cond, D, slot + 2 * QC_SITE_ADA, st));
     QC_HIP(launch_small_linear(cond, D, b.ada_w, b.ada_b, mod, 6 * D, 1, 6 * D, D, 1, 0, st));
-    QC_HIP(launch_ln_mod_quant(ctx->tokens, mod, mod + D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
+    QC_HIP(launch_ln_mod_quant(ctx->tokens, 0, mod, mod + D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
     if (slot) QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_QKV, st));
     QC_HIP(launch_linear_f32(ctx->cal_h, b.qkv_w, b.qkv_b, ctx->qkv, T, 3 * D, D, 0, st));
     QC_HIP(launch_attention(ctx->qkv, 1, T, ctx->H, ctx->hd, nullptr, nullptr, ctx->cal_o, st));
     if (slot) QC_HIP(launch_minmax(ctx->cal_o, (size_t)T * D, slot + 2 * QC_SITE_PROJ, st));
     QC_HIP(launch_linear_f32(ctx->cal_o, b.proj_w, b.proj_b, ctx->cal_a, T, D, D, 0, st));
-    QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 2 * D, 6 * D, 1, T, D, false, st));
-    QC_HIP(launch_ln_mod_quant(ctx->tokens, mod + 3 * D, mod + 4 * D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
+    QC_HIP(launch_cache_reuse(ctx->tokens, 0, ctx->cal_a, mod + 2 * D, 6 * D, 1, T, D, false, st));
+    QC_HIP(launch_ln_mod_quant(ctx->tokens, 0, mod + 3 * D, mod + 4 * D, 6 * D, T, D, T, nullptr, nullptr, ctx->cal_h, st));
     if (slot) QC_HIP(launch_minmax(ctx->cal_h, (size_t)T * D, slot + 2 * QC_SITE_FC1, st));
     QC_HIP(launch_linear_f32(ctx->cal_h, b.fc1_w, b.fc1_b, ctx->cal_u, T, R, D, 2, st));
     if (slot) QC_HIP(launch_minmax(ctx->cal_u, (size_t)T * R, slot + 2 * QC_SITE_FC2, st));
     QC_HIP(launch_linear_f32(ctx->cal_u, b.fc2_w, b.fc2_b, ctx->cal_a, T, D, R, 0, st));
-    QC_HIP(launch_cache_reuse(ctx->tokens, ctx->cal_a, mod + 5 * D, 6 * D, 1, T, D, false, st));
+    QC_HIP(launch_cache_reuse(ctx->tokens, 0, ctx->cal_a, mod + 5 * D, 6 * D, 1, T, D, false, st));
   }
   return QC_OK;
 }
@@ -977,11 +992,11 @@ static int denoise_f32_impl(qc_ctx *ctx, const qc_weights_f32 *w, const float *x
   if (rc) return rc;
   QC_HIP(launch_small_linear(ctx->cond, D, ctx->fada_w, ctx->fada_b, ctx->fmod, 2 * D, B, 2 * D, D, 1, 0, st));
   for (int b = 0; b < B; ++b) {
-    QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 1, n_src, ctx->C, ctx->d.latent_h, ctx->d.latent_w,
+    QC_HIP(launch_embed(x, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 0, 1, n_src, ctx->C, ctx->d.latent_h, ctx->d.latent_w,
                         ctx->d.patch, D, b, st));
     rc = fp32_blocks_one(ctx, w, ctx->cond + (size_t)b * D, nullptr, st);
     if (rc) return rc;
-    QC_HIP(launch_final(ctx->tokens, ctx->fmod + (size_t)b * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + b * lat, 1, ctx->C,
+    QC_HIP(launch_final(ctx->tokens, 0, ctx->fmod + (size_t)b * 2 * D, ctx->flin_w, ctx->flin_b, eps_out + b * lat, 1, ctx->C,
                         ctx->d.latent_h, ctx->d.latent_w, ctx->d.patch, D, st));
   }
   return QC_OK;
@@ -1017,7 +1032,7 @@ int qc_calibrate_minmax(qc_ctx *ctx, const qc_weights_f32 *w, const float *x, co
     QC_HIP(hipStreamSynchronize(st));
     rc = run_cond(ctx, &t[i], 1, ctx->cal_label, 1, 1, st);
     if (rc) return rc;
-    QC_HIP(launch_embed(x + i * lat, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 1, 1, ctx->C, ctx->d.latent_h,
+    QC_HIP(launch_embed(x + i * lat, ctx->patch_w, ctx->patch_b, ctx->pos, ctx->tokens, 0, 1, 1, ctx->C, ctx->d.latent_h,
                         ctx->d.latent_w, ctx->d.patch, D, 0, st));
     rc = fp32_blocks_one(ctx, w, ctx->cond, ctx->cal_slots, st);
     if (rc) return rc;

@@ -73,13 +73,6 @@ __device__ __forceinline__ float gelu_tanh(float v) {
   return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
 
-// bfloat16 storage of an fp32 value, round to nearest even
-__device__ __forceinline__ unsigned short bf16_bits(float v) {
-  unsigned u = __builtin_bit_cast(unsigned, v);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (unsigned short)(u >> 16);
-}
-
 // Dequantised output of a quantised linear as it is stored: the float32 rounding of the float64 value
 // (a_s * w_s[n]) * (acc - a_z * wsum[n]) + bias[n] (the product of the two scales is exact in float64; one float64
 // multiplication, one float64 addition, one rounding to float32).  Stored tensors then carry no rounding of their own
@@ -114,7 +107,8 @@ __device__ __forceinline__ int quant_code(float v, float s, float inv_s, float z
 // LDS, free for reuse (every wavefront is past its last fragment read).
 // FAST: the launcher has checked that every tile is interior along m and lies in one batch element (and, for the QKV
 // scatter, the alignment its staged path needs); the general paths are then not compiled into the kernel.
-template <int BM, int BN, int WM, int WN, int EPI, bool FAST = false>
+// RBF: the residual stream or the cache may be bfloat16 (read from the arguments); false: both are known to be float32.
+template <int BM, int BN, int WM, int WN, int EPI, bool FAST = false, bool RBF = true>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM / WM / 32][BN / WN / 32], unsigned char *smem,
                                               const int m0, const int n0, const int z) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32, NT = 64 * WM * WN;
@@ -356,6 +350,52 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
     constexpr int JB = TM * TN <= 4 ? TN : 1, IB = TM * TN <= 4 ? TM : 1;
     const bool uniform_batch = (p.rows_per_batch % BM) == 0;
     const int b_uniform = m0 / p.rows_per_batch;
+    const int x_bf16 = RBF ? p.x_bf16 : 0, cache_bf16 = RBF ? p.cache_bf16 : 0;
+    if (FAST && RBF && (x_bf16 || cache_bf16) && p.N % 128 == 0) {
+      // A bfloat16 stream or cache: 32 lanes of a wavefront cover only 64 bytes of a row, and 2-byte stores leave
+      // every cache line half written.  The dequantised values go through LDS in column halves of 128 instead, and
+      // every thread handles four adjacent columns of 16 rows: 8- or 16-byte loads and stores, whole lines per row.
+      constexpr int HN = 128, SR = HN + 4, RQ = BM * 32 / NT;
+      float *stage = (float *)smem;
+      const int cr = tid >> 5, cc = (tid & 31) * 4;     // thread -> rows cr + (NT / 32) q, columns cc .. cc + 3 of a half
+#pragma unroll
+      for (int hn = 0; hn < BN / HN; ++hn) {
+        const int n0h = n0 + hn * HN;
+        if (n0h >= p.N) break;
+        const bool mine = wn0 / HN == hn;               // this wavefront's columns lie in the half
+        if (hn) __syncthreads();                        // the previous half has left the staging area
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          if (!mine) continue;
+          const int nl = wn0 - hn * HN + j * 32 + (lane & 31);
+          const double sc = (double)a_s * (double)w_scale[n0h + nl];
+          const int zw = a_z * wsum[n0h + nl];
+          const double bs = bias ? (double)bias[n0h + nl] : 0.0;
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              stage[(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * SR + nl] = dequant_f32(sc, acc[i][j][r] - zw, bs);
+            __builtin_amdgcn_sched_barrier(0);          // one block's values live at a time
+          }
+        }
+        __syncthreads();
+        const v4f gv = *(const v4f *)(p.gate + (long long)b_uniform * p.ld_gate + n0h + cc);
+        const size_t ob4 = ((size_t)m0 * p.N + n0h + cc) >> 2;      // in groups of four elements
+        const size_t row4 = (size_t)p.N >> 2;
+#pragma unroll 4
+        for (int q = 0; q < RQ; ++q) {
+          const int row = cr + q * (NT / 32);
+          const v4f v = *(const v4f *)(stage + row * SR + cc);
+          const size_t o4 = ob4 + (size_t)row * row4;
+          const float4 xo = stream_load4(p.x, o4, x_bf16);
+          stream_store4(p.cache_out, o4, make_float4(v.x, v.y, v.z, v.w), cache_bf16);
+          stream_store4(p.x, o4, make_float4(fmaf(gv.x, v.x, xo.x), fmaf(gv.y, v.y, xo.y), fmaf(gv.z, v.z, xo.z), fmaf(gv.w, v.w, xo.w)),
+                        x_bf16);
+        }
+      }
+      return;
+    }
     if (FAST) {
       // every row of the tile exists and belongs to batch element b_uniform; N is a multiple of 32, so a wavefront's
       // 32-column block lies inside the matrix or outside it as a whole
@@ -368,20 +408,19 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
         const double bs = bias ? (double)bias[n] : 0.0;
         const float g = p.gate[(long long)b_uniform * p.ld_gate + n];
         const long long ob = (long long)m0 * p.N + n;
-        float *xcol = p.x + ob;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
           float xv[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            xv[r] = xcol[(unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N];
+            xv[r] = stream_load(p.x, ob + (unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N, x_bf16);
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const float v = dequant_f32(sc, acc[i][j][r] - zw, bs);
             const unsigned o = (unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N;
-            if (p.cache_bf16) ((unsigned short *)p.cache_out + ob)[o] = bf16_bits(v);
+            if (cache_bf16) ((unsigned short *)p.cache_out + ob)[o] = bf16_bits(v);
             else ((float *)p.cache_out + ob)[o] = v;
-            xcol[o] = fmaf(g, v, xv[r]);
+            stream_store(p.x, ob + o, fmaf(g, v, xv[r]), x_bf16);
           }
           __builtin_amdgcn_sched_barrier(0);                  // one block's values live at a time
         }
@@ -404,7 +443,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int m = min(m0 + wm0 + (i0 + ii) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), p.M - 1);
-              xv[jj][ii][r] = p.x[(long long)m * p.N + n];
+              xv[jj][ii][r] = stream_load(p.x, (long long)m * p.N + n, x_bf16);
             }
           scv[jj] = (double)a_s * (double)w_scale[n];
           zwv[jj] = a_z * wsum[n];
@@ -426,9 +465,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
                 // 32-bit offset inside the tile's rows from one 64-bit base per column
                 const long long ob = (long long)m0 * p.N + n;
                 const unsigned o = (unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N;
-                if (p.cache_bf16) ((unsigned short *)p.cache_out + ob)[o] = bf16_bits(v);
+                if (cache_bf16) ((unsigned short *)p.cache_out + ob)[o] = bf16_bits(v);
                 else ((float *)p.cache_out + ob)[o] = v;
-                (p.x + ob)[o] = fmaf(gv[jj], v, xv[jj][ii][r]);
+                stream_store(p.x, ob + o, fmaf(gv[jj], v, xv[jj][ii][r]), x_bf16);
               }
           } else {
             if (n >= p.N) continue;
@@ -441,10 +480,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
                 if (m >= p.M) continue;
                 const float v = dequant_f32(scv[jj], acc[i][j][r] - zwv[jj], bsv[jj]);
                 const long long o = (long long)m * p.N + n;
-                if (p.cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
+                if (cache_bf16) ((unsigned short *)p.cache_out)[o] = bf16_bits(v);
                 else ((float *)p.cache_out)[o] = v;
                 const float g = p.gate[(long long)(m / p.rows_per_batch) * p.ld_gate + n];
-                p.x[o] = fmaf(g, v, xv[jj][ii][r]);
+                stream_store(p.x, o, fmaf(g, v, xv[jj][ii][r]), x_bf16);
               }
           }
         }
@@ -476,7 +515,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
   }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK>
+template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK, bool RBF>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && BM * BN <= 128 * 128) ? 2 : 1) void gemm_i8_kernel(GemmArgs p) {
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -739,7 +778,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && BM * BN <= 128 * 128
     }
   }
 
-  gemm_epilogue<BM, BN, WM, WN, EPI>(p, acc, smem, m0, n0, z);
+  gemm_epilogue<BM, BN, WM, WN, EPI, false, RBF>(p, acc, smem, m0, n0, z);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -773,7 +812,7 @@ __device__ __forceinline__ void direct_load16(const int8_t *base, unsigned voff,
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
 }
 
-template <int EPI, int TAG, bool W4>
+template <int EPI, int TAG, bool W4, bool RBF>
 __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   constexpr int BM = 128, BN = 256, WM = 1, WN = 4, TM = 4, TN = 2, BK = 64;
   constexpr int RB = 4, NB = 4;                   // ring depth (k-groups), LDS slabs
@@ -905,20 +944,20 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   QC_WAIT_VM(0);
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
-  gemm_epilogue<BM, BN, WM, WN, EPI, true>(p, acc, smem, m0, n0, 0);
+  gemm_epilogue<BM, BN, WM, WN, EPI, true, RBF>(p, acc, smem, m0, n0, 0);
 }
 
 constexpr int BIG_SMEM_LOOP = 4 * 128 * 64;
-constexpr int BIG_SMEM_STAGE = 128 * (128 + 4) * 4;                      // one staged column half of the QKV scatter, float32
+constexpr int BIG_SMEM_STAGE = 128 * (128 + 4) * 4;                      // one staged column half, float32 (QKV scatter, residual)
 constexpr int BIG_SMEM_GELU = 256 * 12 + 128 * (256 + 16) + 16 + GELU_FIX_CAP * 16;
 
-template <int EPI, int TAG, bool W4>
-static hipError_t launch_big(const GemmArgs &a, hipStream_t st) {
-  constexpr int smem_epi = EPI == EPI_GELU_Q ? BIG_SMEM_GELU : (EPI == EPI_QKV ? BIG_SMEM_STAGE : 0);
+template <int EPI, int TAG, bool W4, bool RBF>
+static hipError_t launch_big_fmt(const GemmArgs &a, hipStream_t st) {
+  constexpr int smem_epi = EPI == EPI_GELU_Q ? BIG_SMEM_GELU : BIG_SMEM_STAGE;
   constexpr int smem = smem_epi > BIG_SMEM_LOOP ? smem_epi : BIG_SMEM_LOOP;
   static_assert(2 * smem <= 160 * 1024, "two workgroups per compute unit");
   static bool attr_set = false;
-  auto kern = gemm_i8_big_kernel<EPI, TAG, W4>;
+  auto kern = gemm_i8_big_kernel<EPI, TAG, W4, RBF>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
@@ -927,6 +966,13 @@ static hipError_t launch_big(const GemmArgs &a, hipStream_t st) {
   const int tiles = ((a.M + 127) / 128) * ((a.N + 255) / 256);
   hipLaunchKernelGGL(kern, dim3(((tiles + 7) / 8) * 8), dim3(256), smem, st, a);
   return hipGetLastError();
+}
+
+// the residual epilogue is compiled twice: for float32 stream and cache, and for the bfloat16 variants of either
+template <int EPI, int TAG, bool W4>
+static hipError_t launch_big(const GemmArgs &a, hipStream_t st) {
+  if (EPI == EPI_RESID && (a.x_bf16 || a.cache_bf16)) return launch_big_fmt<EPI, TAG, W4, true>(a, st);
+  return launch_big_fmt<EPI, TAG, W4, false>(a, st);
 }
 
 // The large-M kernel takes over when the weights exist in fragment order, the shape fits its loop (K a multiple of
@@ -941,13 +987,17 @@ static bool use_big(const GemmArgs &a, int epi, int nz) {
   return tiles >= 384;
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK = 128>
+template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK = 128, bool RBF = false>
 static hipError_t launch_cfg(const GemmArgs &a, int nz, hipStream_t st) {
+  // the residual epilogue is compiled for float32 stream and cache, and once more for the bfloat16 variants of either
+  if constexpr (EPI == EPI_RESID && !RBF) {
+    if (a.x_bf16 || a.cache_bf16) return launch_cfg<BM, BN, WM, WN, EPI, TAG, W4, PF, BK, true>(a, nz, st);
+  }
   constexpr int smem_loop = 2 * (BM + BN) * (BK + 16);
   constexpr int smem_epi = BN * 12 + BM * (BN + 16) + 16 + GELU_FIX_CAP * 16;
   constexpr int smem = smem_loop > smem_epi ? smem_loop : smem_epi;
   static bool attr_set = false;
-  auto kern = gemm_i8_kernel<BM, BN, WM, WN, EPI, TAG, W4, PF, BK>;
+  auto kern = gemm_i8_kernel<BM, BN, WM, WN, EPI, TAG, W4, PF, BK, RBF>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;

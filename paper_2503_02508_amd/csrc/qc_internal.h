@@ -62,7 +62,8 @@ struct GemmArgs {
   // EPI_RESID
   void *cache_out;           // [M, N] fp32, or bfloat16 when cache_bf16 is set
   int cache_bf16;
-  float *x;                  // [M, N] residual stream, updated in place
+  void *x;                   // [M, N] residual stream (fp32, or bfloat16 when x_bf16 is set), updated in place
+  int x_bf16;
   const float *gate;         // [B, ld_gate]
   int ld_gate;
   int rows_per_batch;        // T
@@ -80,6 +81,41 @@ __host__ __device__ inline int vt_pos(int t) {
   return (t & ~31) | ((((u & 3) << 1) | (u >> 2)) << 2) | (t & 3);
 }
 
+// ---- storage formats.  The cached tensors and, in the reduced-precision variant, the residual stream are stored as
+// fp32 or as bfloat16 (round to nearest even of the fp32 value); element i of a tensor sits at index i of either format.
+__host__ __device__ inline unsigned short bf16_bits(float v) {
+  unsigned u = __builtin_bit_cast(unsigned, v);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (unsigned short)(u >> 16);
+}
+__host__ __device__ inline float bf16_value(unsigned short h) { return __builtin_bit_cast(float, (unsigned)h << 16); }
+// element / four elements of the residual stream (bf != 0: bfloat16); i4 counts groups of four elements
+__device__ __forceinline__ float stream_load(const void *x, size_t i, int bf) {
+  return bf ? bf16_value(((const unsigned short *)x)[i]) : ((const float *)x)[i];
+}
+__device__ __forceinline__ void stream_store(void *x, size_t i, float v, int bf) {
+  if (bf) ((unsigned short *)x)[i] = bf16_bits(v);
+  else ((float *)x)[i] = v;
+}
+__device__ __forceinline__ float4 stream_load4(const void *x, size_t i4, int bf) {
+  if (bf) {
+    const uint2 r = ((const uint2 *)x)[i4];
+    return make_float4(__builtin_bit_cast(float, r.x << 16), __builtin_bit_cast(float, r.x & 0xFFFF0000u),
+                       __builtin_bit_cast(float, r.y << 16), __builtin_bit_cast(float, r.y & 0xFFFF0000u));
+  }
+  return ((const float4 *)x)[i4];
+}
+__device__ __forceinline__ void stream_store4(void *x, size_t i4, float4 v, int bf) {
+  if (bf) {
+    uint2 r;
+    r.x = (unsigned)bf16_bits(v.x) | ((unsigned)bf16_bits(v.y) << 16);
+    r.y = (unsigned)bf16_bits(v.z) | ((unsigned)bf16_bits(v.w) << 16);
+    ((uint2 *)x)[i4] = r;
+  } else {
+    ((float4 *)x)[i4] = v;
+  }
+}
+
 hipError_t launch_gemm(const GemmArgs &a, int epi, int nz, hipStream_t st, int site);
 // row-major codes [N, K] (or packed [N, K/2]) -> fragment order; N % 32 == 0, K % 32 == 0
 hipError_t launch_tile_weight(const void *q, void *qt, int N, int K, int bits, hipStream_t st);
@@ -88,7 +124,8 @@ hipError_t launch_tile_weight(const void *q, void *qt, int N, int K, int bits, h
 hipError_t launch_quantize_act(const float *x, int8_t *q, size_t n, float s, int z_signed, hipStream_t st);
 hipError_t launch_quantize_weight(const float *w, int N, int K, int bits, void *qw, float *scale, int32_t *wsum,
                                   hipStream_t st);
-hipError_t launch_ln_mod_quant(const float *x, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
+// x_bf16 / tok_bf16 below: the residual stream argument is bfloat16 instead of fp32
+hipError_t launch_ln_mod_quant(const void *x, int x_bf16, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
                                const QParam *qp, int8_t *q, float *f32_out, hipStream_t st);
 hipError_t launch_small_linear(const float *x, int ldx, const float *W, const float *b, float *y, int ldy, int B, int N,
                                int K, int act_in, int act_out, hipStream_t st);
@@ -97,14 +134,14 @@ hipError_t launch_cond_finish(const float *te, const float *table, const int32_t
                               int rows, int B, int D, float *c, int *flags, hipStream_t st);
 hipError_t launch_silu_quant(const float *c, int B, int D, int L, const QParam *qp, int qp_stride, int8_t *q,
                              size_t l_stride, hipStream_t st);
-hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, float *tok, int B, int n_src,
-                        int C, int H, int W, int p, int D, int b_off, hipStream_t st);
-hipError_t launch_final(const float *tok, const float *fmod, const float *fw, const float *fb, float *eps, int B, int C,
-                        int H, int W, int p, int D, hipStream_t st);
+hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, void *tok, int tok_bf16, int B,
+                        int n_src, int C, int H, int W, int p, int D, int b_off, hipStream_t st);
+hipError_t launch_final(const void *tok, int tok_bf16, const float *fmod, const float *fw, const float *fb, float *eps, int B,
+                        int C, int H, int W, int p, int D, hipStream_t st);
 hipError_t launch_cache_store(const float *src, void *dst, size_t n, bool bf16, hipStream_t st);
-hipError_t launch_cache_reuse(float *x, const void *cached, const float *gate, int ld_gate, int B, int T, int D, bool bf16,
-                              hipStream_t st);
-hipError_t launch_cached_blocks(float *x, const void *cache, size_t cache_block_stride, size_t cache_which_stride,
+hipError_t launch_cache_reuse(void *x, int x_bf16, const void *cached, const float *gate, int ld_gate, int B, int T, int D,
+                              bool bf16, hipStream_t st);
+hipError_t launch_cached_blocks(void *x, int x_bf16, const void *cache, size_t cache_block_stride, size_t cache_which_stride,
                                 const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D, bool bf16,
                                 hipStream_t st);
 hipError_t launch_ddim_vc(float *x, const float *eps, int B, int C, int HW, double cx, double ce, float cfg_scale,

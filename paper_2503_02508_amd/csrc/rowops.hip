@@ -142,7 +142,7 @@ __device__ __forceinline__ double wave_sum_d(double v) {
 // flight per compute unit, which is what the memory system needs to run near its peak at large M.  The arithmetic of a
 // row, and with it every code, is the same for both.
 template <int R>
-__global__ __launch_bounds__(512) void ln_mod_quant_kernel(const float *__restrict__ x, const float *__restrict__ shift,
+__global__ __launch_bounds__(512) void ln_mod_quant_kernel(const void *__restrict__ x, int x_bf16, const float *__restrict__ shift,
                                                            const float *__restrict__ scale, int ld_mod, int M, int D, int T,
                                                            const QParam *qp, int8_t *__restrict__ q,
                                                            float *__restrict__ f32_out) {
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(512) void ln_mod_quant_kernel(const float *__restri
   for (int r = 0; r < R; ++r) {
     const int m = min(m0 + r, M - 1);             // rows beyond M re-read the last row (never stored)
     const int b = m / T;
-    v[r] = *(const float4 *)(x + (size_t)m * D + kc);
+    v[r] = stream_load4(x, ((size_t)m * D + kc) >> 2, x_bf16);
     s4[r] = *(const float4 *)(shift + (size_t)b * ld_mod + kc);
     c4[r] = *(const float4 *)(scale + (size_t)b * ld_mod + kc);
   }
@@ -217,15 +217,16 @@ __global__ __launch_bounds__(512) void ln_mod_quant_kernel(const float *__restri
   }
 }
 
-hipError_t launch_ln_mod_quant(const float *x, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
+hipError_t launch_ln_mod_quant(const void *x, int x_bf16, const float *shift, const float *scale, int ld_mod, int M, int D, int T,
                                const QParam *qp, int8_t *q, float *f32_out, hipStream_t st) {
   const int threads = ((D / 4 + 63) / 64) * 64;
   if (D % 4 || threads > 512) return hipErrorInvalidValue;
   if (M >= 8192)
-    hipLaunchKernelGGL(ln_mod_quant_kernel<4>, dim3((M + 3) / 4), dim3(threads), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q,
-                       f32_out);
+    hipLaunchKernelGGL(ln_mod_quant_kernel<4>, dim3((M + 3) / 4), dim3(threads), 0, st, x, x_bf16, shift, scale, ld_mod, M, D, T,
+                       qp, q, f32_out);
   else
-    hipLaunchKernelGGL(ln_mod_quant_kernel<1>, dim3(M), dim3(threads), 0, st, x, shift, scale, ld_mod, M, D, T, qp, q, f32_out);
+    hipLaunchKernelGGL(ln_mod_quant_kernel<1>, dim3(M), dim3(threads), 0, st, x, x_bf16, shift, scale, ld_mod, M, D, T, qp, q,
+                       f32_out);
   return hipGetLastError();
 }
 
@@ -338,7 +339,8 @@ hipError_t launch_silu_quant(const float *c, int B, int D, int L, const QParam *
 // tok[b, t, n] = sum_f pw[n, f] * patch(b, t)[f] + pb[n] + pos[t, n], features f = (c, ph, pw).
 __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x, const float *__restrict__ pw,
                                                     const float *__restrict__ pb, const float *__restrict__ pos,
-                                                    float *__restrict__ tok, int n_src, int C, int H, int W, int p, int D, int b_off) {
+                                                    void *__restrict__ tok, int tok_bf16, int n_src, int C, int H, int W, int p,
+                                                    int D, int b_off) {
   __shared__ float patch[256];
   const int gw = W / p, T = (H / p) * gw;
   const int bt = blockIdx.x, b = bt / T, t = bt % T;
@@ -373,14 +375,14 @@ __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ x,
     } else {
       for (int f = 0; f < F; ++f) acc = fma((double)wr[f], (double)patch[f], acc);
     }
-    tok[(size_t)bt * D + n] = (float)((acc + (double)pb[n]) + (double)pos[(size_t)t * D + n]);
+    stream_store(tok, (size_t)bt * D + n, (float)((acc + (double)pb[n]) + (double)pos[(size_t)t * D + n]), tok_bf16);
   }
 }
 
-hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, float *tok, int B, int n_src,
-                        int C, int H, int W, int p, int D, int b_off, hipStream_t st) {
+hipError_t launch_embed(const float *x, const float *pw, const float *pb, const float *pos, void *tok, int tok_bf16, int B,
+                        int n_src, int C, int H, int W, int p, int D, int b_off, hipStream_t st) {
   const int T = (H / p) * (W / p);
-  hipLaunchKernelGGL(embed_kernel, dim3(B * T), dim3(256), 0, st, x, pw, pb, pos, tok, n_src, C, H, W, p, D, b_off);
+  hipLaunchKernelGGL(embed_kernel, dim3(B * T), dim3(256), 0, st, x, pw, pb, pos, tok, tok_bf16, n_src, C, H, W, p, D, b_off);
   return hipGetLastError();
 }
 
@@ -388,7 +390,7 @@ hipError_t launch_embed(const float *x, const float *pw, const float *pb, const 
 // Per token: LayerNorm, modulate with (shift, scale) = fmod[b, 0:D], fmod[b, D:2D],
 // dot with the rows of the output linear that belong to the first C of the 2C
 // channels, and scatter to eps[b, c, ty*p+ph, tx*p+pw] (output features (ph, pw, c)).
-__global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ tok, const float *__restrict__ fmod,
+__global__ __launch_bounds__(256) void final_kernel(const void *__restrict__ tok, int tok_bf16, const float *__restrict__ fmod,
                                                     const float *__restrict__ fw, const float *__restrict__ fb,
                                                     float *__restrict__ eps, int M, int C, int H, int W, int p, int D) {
   const int lane = threadIdx.x & 63;
@@ -396,7 +398,6 @@ __global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ to
   if (m >= M) return;
   const int gw = W / p, T = (H / p) * gw;
   const int b = m / T, t = m % T, ty = t / gw, tx = t % gw;
-  const float *row = tok + (size_t)m * D;
   const float *sh = fmod + (size_t)b * 2 * D, *sc = sh + D;
   // loads never branch (chunks beyond D re-read the last chunk and are zeroed): the row and its modulation
   // vectors arrive in one memory round trip
@@ -405,7 +406,7 @@ __global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ to
 #pragma unroll
   for (int it = 0; it < LN_MAX_IT; ++it) {
     kk[it] = min((lane + 64 * it) * 4, D - 4);
-    v[it] = *(const float4 *)(row + kk[it]);
+    v[it] = stream_load4(tok, ((size_t)m * D + kk[it]) >> 2, tok_bf16);
     s4[it] = *(const float4 *)(sh + kk[it]);
     c4[it] = *(const float4 *)(sc + kk[it]);
   }
@@ -478,21 +479,15 @@ __global__ __launch_bounds__(256) void final_kernel(const float *__restrict__ to
   }
 }
 
-hipError_t launch_final(const float *tok, const float *fmod, const float *fw, const float *fb, float *eps, int B, int C,
-                        int H, int W, int p, int D, hipStream_t st) {
+hipError_t launch_final(const void *tok, int tok_bf16, const float *fmod, const float *fw, const float *fb, float *eps, int B,
+                        int C, int H, int W, int p, int D, hipStream_t st) {
   const int M = B * (H / p) * (W / p);
-  hipLaunchKernelGGL(final_kernel, dim3((M + 3) / 4), dim3(256), 0, st, tok, fmod, fw, fb, eps, M, C, H, W, p, D);
+  hipLaunchKernelGGL(final_kernel, dim3((M + 3) / 4), dim3(256), 0, st, tok, tok_bf16, fmod, fw, fb, eps, M, C, H, W, p, D);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- cache ops
-// The cached tensors are stored as fp32 or, in the reduced-precision variant, as bfloat16 (round to nearest even
-// of the fp32 value); element i of a tensor sits at index i of either format.
-__device__ __forceinline__ unsigned short bf16_bits(float v) {
-  unsigned u = __builtin_bit_cast(unsigned, v);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (unsigned short)(u >> 16);
-}
+// The cached tensors are stored as fp32 or, in the reduced-precision variant, as bfloat16; so is the residual stream.
 
 template <bool BF16>
 __device__ __forceinline__ float4 load_cached4(const void *base, size_t i4) {
@@ -531,36 +526,39 @@ hipError_t launch_cache_store(const float *src, void *dst, size_t n, bool bf16, 
 
 // x[b, t, :] += gate[b, :] * cached[b, t, :]
 template <bool BF16>
-__global__ __launch_bounds__(256) void cache_reuse_kernel(float *__restrict__ x, const void *__restrict__ cached,
+__global__ __launch_bounds__(256) void cache_reuse_kernel(void *__restrict__ x, int x_bf16, const void *__restrict__ cached,
                                                           const float *__restrict__ gate, int ld_gate, size_t n4, int TD4,
                                                           int D4) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n4) return;
   const int b = (int)(i / TD4), n = (int)(i % D4) * 4;
-  float4 xv = ((float4 *)x)[i];
+  float4 xv = stream_load4(x, i, x_bf16);
   const float4 cv = load_cached4<BF16>(cached, i);
   float4 g = *(const float4 *)(gate + (size_t)b * ld_gate + n);
   xv.x = xv.x + g.x * cv.x;
   xv.y = xv.y + g.y * cv.y;
   xv.z = xv.z + g.z * cv.z;
   xv.w = xv.w + g.w * cv.w;
-  ((float4 *)x)[i] = xv;
+  stream_store4(x, i, xv, x_bf16);
 }
 
-hipError_t launch_cache_reuse(float *x, const void *cached, const float *gate, int ld_gate, int B, int T, int D, bool bf16,
-                              hipStream_t st) {
+hipError_t launch_cache_reuse(void *x, int x_bf16, const void *cached, const float *gate, int ld_gate, int B, int T, int D,
+                              bool bf16, hipStream_t st) {
   const size_t n4 = (size_t)B * T * D / 4;
   const dim3 grid((unsigned)((n4 + 255) / 256));
-  if (bf16) hipLaunchKernelGGL(cache_reuse_kernel<true>, grid, dim3(256), 0, st, x, cached, gate, ld_gate, n4, T * D / 4, D / 4);
-  else hipLaunchKernelGGL(cache_reuse_kernel<false>, grid, dim3(256), 0, st, x, cached, gate, ld_gate, n4, T * D / 4, D / 4);
+  if (bf16) hipLaunchKernelGGL(cache_reuse_kernel<true>, grid, dim3(256), 0, st, x, x_bf16, cached, gate, ld_gate, n4, T * D / 4, D / 4);
+  else hipLaunchKernelGGL(cache_reuse_kernel<false>, grid, dim3(256), 0, st, x, x_bf16, cached, gate, ld_gate, n4, T * D / 4, D / 4);
   return hipGetLastError();
 }
 
 // All blocks of a cached step in one pass over x: for every block in order,
 // x += gate_msa * attn_cached; x += gate_mlp * mlp_cached (same association
-// as block after block).  mod[l, b, 6D] holds the gates in chunks 2 and 5.  Cache strides are in elements.
+// as block after block; a bfloat16 stream is rounded to its storage format after every addition, as it would be if
+// it went through memory).  mod[l, b, 6D] holds the gates in chunks 2 and 5.  Cache strides are in elements.
+__device__ __forceinline__ float as_stored(float v, int bf) { return bf ? bf16_value(bf16_bits(v)) : v; }
+
 template <bool BF16>
-__global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ x, const void *__restrict__ cache,
+__global__ __launch_bounds__(256) void cached_blocks_kernel(void *__restrict__ x, int x_bf16, const void *__restrict__ cache,
                                                             size_t cache_block_stride, size_t cache_which_stride,
                                                             const float *__restrict__ mod, size_t mod_block_stride,
                                                             int ld_mod, int L, size_t n4, int TD4, int D4, int D) {
@@ -569,10 +567,12 @@ __global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ 
   const int b = (int)(i / TD4), n = (int)(i % D4) * 4;
   constexpr size_t ES = BF16 ? 2 : 4;               // bytes per cached element
   const char *cbase = (const char *)cache;
-  float4 xv = ((float4 *)x)[i];
+  float4 xv = stream_load4(x, i, x_bf16);
   auto apply = [&](const float4 &g1, const float4 &a, const float4 &g2, const float4 &mo) {
-    xv.x = xv.x + g1.x * a.x; xv.y = xv.y + g1.y * a.y; xv.z = xv.z + g1.z * a.z; xv.w = xv.w + g1.w * a.w;
-    xv.x = xv.x + g2.x * mo.x; xv.y = xv.y + g2.y * mo.y; xv.z = xv.z + g2.z * mo.z; xv.w = xv.w + g2.w * mo.w;
+    xv.x = as_stored(xv.x + g1.x * a.x, x_bf16); xv.y = as_stored(xv.y + g1.y * a.y, x_bf16);
+    xv.z = as_stored(xv.z + g1.z * a.z, x_bf16); xv.w = as_stored(xv.w + g1.w * a.w, x_bf16);
+    xv.x = as_stored(xv.x + g2.x * mo.x, x_bf16); xv.y = as_stored(xv.y + g2.y * mo.y, x_bf16);
+    xv.z = as_stored(xv.z + g2.z * mo.z, x_bf16); xv.w = as_stored(xv.w + g2.w * mo.w, x_bf16);
   };
   // the loads of four blocks are in flight together; the additions keep the block order
   constexpr int U = 4;
@@ -597,19 +597,19 @@ __global__ __launch_bounds__(256) void cached_blocks_kernel(float *__restrict__ 
     const float4 mo = load_cached4<BF16>(cbase + ((size_t)l * cache_block_stride + cache_which_stride) * ES, i);
     apply(g1, a, g2, mo);
   }
-  ((float4 *)x)[i] = xv;
+  stream_store4(x, i, xv, x_bf16);
 }
 
-hipError_t launch_cached_blocks(float *x, const void *cache, size_t cache_block_stride, size_t cache_which_stride,
+hipError_t launch_cached_blocks(void *x, int x_bf16, const void *cache, size_t cache_block_stride, size_t cache_which_stride,
                                 const float *mod, size_t mod_block_stride, int ld_mod, int L, int B, int T, int D, bool bf16,
                                 hipStream_t st) {
   const size_t n4 = (size_t)B * T * D / 4;
   const dim3 grid((unsigned)((n4 + 255) / 256));
   if (bf16)
-    hipLaunchKernelGGL(cached_blocks_kernel<true>, grid, dim3(256), 0, st, x, cache, cache_block_stride, cache_which_stride, mod,
+    hipLaunchKernelGGL(cached_blocks_kernel<true>, grid, dim3(256), 0, st, x, x_bf16, cache, cache_block_stride, cache_which_stride, mod,
                        mod_block_stride, ld_mod, L, n4, T * D / 4, D / 4, D);
   else
-    hipLaunchKernelGGL(cached_blocks_kernel<false>, grid, dim3(256), 0, st, x, cache, cache_block_stride, cache_which_stride, mod,
+    hipLaunchKernelGGL(cached_blocks_kernel<false>, grid, dim3(256), 0, st, x, x_bf16, cache, cache_block_stride, cache_which_stride, mod,
                        mod_block_stride, ld_mod, L, n4, T * D / 4, D / 4, D);
   return hipGetLastError();
 }

@@ -160,7 +160,7 @@ def test_cache_store_and_reuse_calls():
 
 
 # ------------------------------------------------------------ whole network
-def _denoise_case(model, seed, B, t, std, guidance=False, wb=8):
+def _denoise_case(model, seed, B, t, std, guidance=False, wb=8, stream="fp32"):
     import torch
     import paper_2503_02508_amd as qc
     from dataclasses import replace
@@ -171,13 +171,15 @@ def _denoise_case(model, seed, B, t, std, guidance=False, wb=8):
     qp, _, _ = oracle_calibration(model, w, lat=clat, lab=clab, t=np.full(4, t))
     Beff = 2 * B if guidance else B
     lin, ctx = make_pair(model, w, qp, Beff)
+    ctx.set_stream_format(stream)
     lat = I.make_latents(B, model, seed + 1)
     lab = I.make_labels(B, model, seed + 2)
     xin = np.concatenate([lat, lat]) if guidance else lat
     yin = np.concatenate([lab, np.full(B, model.num_classes)]) if guidance else lab
     cache = {}
-    want_full = dit.denoiser(xin, np.full(Beff, t), yin, model, w, lin, cache, True)
-    want_cached = dit.denoiser(xin, np.full(Beff, t - 7), yin, model, w, lin, cache, False)
+    with dit.stream_format({"fp32": "f32", "bf16": "bf16"}[stream]):
+        want_full = dit.denoiser(xin, np.full(Beff, t), yin, model, w, lin, cache, True)
+        want_cached = dit.denoiser(xin, np.full(Beff, t - 7), yin, model, w, lin, cache, False)
     eps = torch.empty((Beff, model.latent_c, model.latent_h, model.latent_w), device="cuda")
     xd, ld = _cuda(lat), _cuda(lab.astype(np.int32))
     ctx.denoise(xd, t, ld, Beff, qc.QC_FULL, eps)
@@ -509,4 +511,63 @@ def test_out_of_range_label_is_clamped_and_reported():
     ctx.denoise(x, 300, _cuda(np.array([1, model.num_classes], dtype=np.int32)), 2, qc.QC_FULL, eps_ok)
     ctx.check()
     assert torch.equal(eps_bad, eps_ok)
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,model,B,std,guidance,wb", [
+    ("tiny", TINY, 3, 0.15, False, 8),
+    ("ragged_cfg", RAGGED, 2, 0.15, True, 8),
+    ("xl_256_depth2", I.shrink(I.DIT_XL2_256, 2), 2, 0.02, False, 8),
+    ("xl_256_depth2_large_m_w4", I.shrink(I.DIT_XL2_256, 2), 40, 0.02, False, 4),     # M = 10240: the large-M GEMM's epilogues
+])
+def test_denoiser_with_bf16_residual_stream(name, model, B, std, guidance, wb):
+    """Reduced-precision variant: the token tensor is stored as bfloat16 (embedding output and the stream after every
+    gated add) on both sides; everything else as in the float32-stream test, to the same bar."""
+    full, cached, As, Ms = _denoise_case(model, 23, B, 500, std, guidance, wb, stream="bf16")
+    r = [assert_close(*full, name + "/eps_full"), assert_close(*cached, name + "/eps_cached")]
+    for l, (a, m) in enumerate(zip(As, Ms)):
+        assert_close(*a, "%s/attn_out[%d]" % (name, l), INNER_MAX_ABS, INNER_REL_RMS)
+        assert_close(*m, "%s/mlp_out[%d]" % (name, l), INNER_MAX_ABS, INNER_REL_RMS)
+    print(name, "bf16 stream: eps full max-abs %.2e rel-RMS %.2e; cached max-abs %.2e rel-RMS %.2e" % (r[0] + r[1]))
+    # and it is a different computation from the float32-stream one
+    full32, _, _, _ = _denoise_case(model, 23, min(B, 2), 500, std, guidance, wb) if B <= 3 else (None, None, None, None)
+    if full32 is not None:
+        assert not np.array_equal(full32[0], full[0][:full32[0].shape[0]])
+
+
+@pytest.mark.parametrize("name,model,B,steps,interval,cfg", [
+    ("tiny_n2", TINY, 3, 8, 2, 0.0), ("ragged_n3_cfg", RAGGED, 2, 7, 3, 1.5),
+    ("xl_256_depth2_n2", I.shrink(I.DIT_XL2_256, 2), 2, 50, 2, 0.0)])
+def test_sampler_with_bf16_stream_and_bf16_cache(name, model, B, steps, interval, cfg):
+    """Both reduced-precision storage variants together, through the whole free-running loop (qc_sample): bfloat16
+    residual stream and bfloat16 cache on both sides, final latents to the bar."""
+    import torch
+    std = 0.02 if model.hidden > 256 else 0.15
+    w = I.make_weights(model, 191, std=std)
+    tt, at, ap = sampler.ddim_schedule(steps)
+    clat = np.concatenate([I.make_latents(1, model, 4000 + i) for i in range(4)])
+    qp, _, _ = oracle_calibration(model, w, lat=clat, lab=I.make_labels(4, model, 192), t=tt[[0, steps // 3, 2 * steps // 3, steps - 1]])
+    Beff = 2 * B if cfg > 0 else B
+    lin, ctx = make_pair(model, w, qp, Beff, interval)
+    ctx.set_cache_format("bf16")
+    ctx.set_stream_format("bf16")
+    lat, lab = I.make_latents(B, model, 193), I.make_labels(B, model, 194)
+    n_run = min(steps, 3 * interval + 1)
+    K = I.make_vc_factors(steps, model.latent_c, 195)
+    xd = _cuda(lat)
+    x_or, cache = lat.astype(np.float64), {}
+    with dit.stream_format("bf16"):
+        for i in range(n_run):
+            x_or, _ = sampler.sample_step(x_or, lab, i, int(tt[i]), at[i], ap[i], model, w, lin, cache, interval, cfg, K[i],
+                                          cache_bf16=True)
+    Kd, ld = _cuda(K), _cuda(lab.astype(np.int32))
+    for i in range(n_run):
+        ctx.sample_step(xd, ld, i, int(tt[i]), float(at[i]), float(ap[i]), cfg, Kd[i])
+    torch.cuda.synchronize()
+    got = xd.cpu().numpy()
+    ma, rr = max_abs(got, x_or), rel_rms(got, x_or)
+    print(name, "bf16 stream + cache, %d free-running steps: max-abs %.2e rel-RMS %.2e" % (n_run, ma, rr))
+    assert ma <= 1e-2 and rr <= 1e-3
+    tok = ctx.workspace("tokens", (Beff, model.tokens, model.hidden), torch.bfloat16)
+    assert torch.isfinite(tok.float()).all()
     ctx.close()

@@ -536,3 +536,34 @@ def test_storage_format_rounds_the_stored_tensors_only():
         assert dit.st(np.float64(1.0) + 2.0 ** -30) != 1.0
     x1, _ = sampler.sample_step(lat.astype(np.float64), lab, 0, 500, 0.3, 0.4, TINY, w, dit.QLinears(w, qp), {}, 2, K_t=np.full(4, 0.97))
     assert f32_exact(x1)
+
+
+def test_bf16_stream_format_rounds_the_token_tensor_only():
+    """stream_format("bf16"): the embedding's output and the residual stream after every gated add are bfloat16
+    values (8 significant bits: the low 16 bits of their float32 pattern are zero), every other stored tensor keeps
+    float32, and the noise estimate stays within bfloat16 rounding of the float32-stream one.  The rounding itself
+    is pinned bit by bit: ties go to the even 16-bit pattern, 1 + 2^-8 rounds down to 1, 1 + 3 * 2^-8 up to 1 + 2^-6."""
+    w, lat, lab = _tiny_setup()
+    t = np.array([500, 20, 980])
+    qp, _ = sampler.calibrate(TINY, w, lat, lab, t)
+    is_bf16 = lambda a: np.all((np.asarray(a, dtype=np.float32).view(np.uint32) & 0xFFFF) == 0) and np.array_equal(
+        np.asarray(a, dtype=np.float32).astype(np.float64), a)
+    f32_exact = lambda a: np.array_equal(np.asarray(a, dtype=np.float32).astype(np.float64), a)
+    taps32, taps16 = [], []
+    e32 = dit.denoiser(lat, t, lab, TINY, w, dit.QLinears(w, qp), {}, True, taps32)
+    with dit.stream_format("bf16"):
+        assert dit.st_x(1.0 + 2.0 ** -8) == 1.0 and dit.st_x(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+        assert dit.st_x(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7          # above the tie: up
+        assert dit.st(1.0 + 2.0 ** -8) == 1.0 + 2.0 ** -8                            # other tensors: float32
+        tok = dit.embed(lat, w, TINY.patch)
+        cache = {}
+        e16 = dit.denoiser(lat, t, lab, TINY, w, dit.QLinears(w, qp), cache, True, taps16)
+        e16c = dit.denoiser(lat, t, lab, TINY, w, dit.QLinears(w, qp), cache, False)
+    assert is_bf16(tok) and all(is_bf16(tp["x"]) for tp in taps16)
+    assert all(f32_exact(tp[k]) and not is_bf16(tp[k]) for tp in taps16 for k in ("qkv", "A", "Mo"))
+    assert not any(is_bf16(tp["x"]) for tp in taps32)
+    assert f32_exact(e16) and not np.array_equal(e16, e32)
+    # bfloat16 keeps 8 bits: the stream's relative error is 2^-9 per store, the estimate moves by a few times that
+    rel = lambda a, b: np.sqrt(np.mean((a - b) ** 2) / np.mean(b ** 2))
+    assert rel(e16, e32) < 5e-2 and rel(e16c, e16) < 1.0
+    assert dit.st_x(1.0 + 2.0 ** -8) == 1.0 + 2.0 ** -8                              # back to float32 outside the block

@@ -236,43 +236,81 @@ hipError_t launch_ln_mod_quant(const void *x, int x_bf16, const float *shift, co
 // summation order (conditioning vectors feed quantisers, where a last-bit difference can move a code).
 __device__ __forceinline__ double silu_d(double x) { return x / (1.0 + exp(-x)); }
 
+// One workgroup = 8 rows x 16 NC outputs: the (activated) inputs of the 8 rows are formed once, in float64, and kept in
+// LDS (the activation is an exponential per value: it must not be repeated per output); a wavefront takes 4 NC of the
+// outputs, four at a time, so that every input value read from LDS and every weight read from memory feeds 4 and 8
+// multiply-adds.  NC = 4 for many rows (all steps of a window at once), NC = 1 for few (one step: the outputs must
+// supply the workgroups).  Per output the summation order is fixed: lane l adds k = l, l + 64, ... in order, then the
+// lanes are reduced by the shuffle tree of wave_sum_d.
+template <int NC>
 __global__ __launch_bounds__(256) void small_linear_kernel(const float *__restrict__ x, int ldx, const float *__restrict__ W,
                                                            const float *__restrict__ bias, float *__restrict__ y, int ldy,
                                                            int B, int N, int K, int act_in, int act_out) {
-  const int lane = threadIdx.x & 63;
-  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (n >= N) return;
-  const float *wr = W + (size_t)n * K;
-  for (int b0 = 0; b0 < B; b0 += 8) {
-    double acc[8];
+  extern __shared__ double xs[];                  // [8][K]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b0 = blockIdx.y * 8, n0 = blockIdx.x * (16 * NC);
+  for (int i = threadIdx.x; i < 8 * K; i += 256) {
+    const int r = i / K, k = i - r * K;
+    double v = b0 + r < B ? (double)x[(size_t)(b0 + r) * ldx + k] : 0.0;
+    if (act_in == 1) v = silu_d(v);
+    xs[i] = v;
+  }
+  __syncthreads();
+  for (int c = 0; c < NC; ++c) {
+    const int n = n0 + wave * (4 * NC) + c * 4;
+    if (n >= N) break;
+    double acc[8][4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[r][j] = 0.0;
+    const float *wr[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) wr[j] = W + (size_t)min(n + j, N - 1) * K;      // outputs beyond N repeat the last (not stored)
     for (int k = lane; k < K; k += 64) {
-      const double wv = (double)wr[k];
+      double wv[4];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (b0 + i < B) {
-          double xv = (double)x[(size_t)(b0 + i) * ldx + k];
-          if (act_in == 1) xv = silu_d(xv);
-          acc[i] = fma(wv, xv, acc[i]);
+      for (int j = 0; j < 4; ++j) wv[j] = (double)wr[j][k];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const double xv = xs[r * K + k];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[r][j] = fma(wv[j], xv, acc[r][j]);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        double t = wave_sum_d(acc[r][j]);
+        if (lane == 0 && b0 + r < B && n + j < N) {
+          t += bias ? (double)bias[n + j] : 0.0;
+          if (act_out == 1) t = silu_d(t);
+          y[(size_t)(b0 + r) * ldy + n + j] = (float)t;
         }
       }
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (b0 + i < B) {
-        double r = wave_sum_d(acc[i]) + (bias ? (double)bias[n] : 0.0);
-        if (act_out == 1) r = silu_d(r);
-        if (lane == 0) y[(size_t)(b0 + i) * ldy + n] = (float)r;
-      }
-    }
   }
 }
 
 hipError_t launch_small_linear(const float *x, int ldx, const float *W, const float *b, float *y, int ldy, int B, int N,
                                int K, int act_in, int act_out, hipStream_t st) {
-  hipLaunchKernelGGL(small_linear_kernel, dim3((N + 3) / 4), dim3(256), 0, st, x, ldx, W, b, y, ldy, B, N, K, act_in,
-                     act_out);
+  const size_t smem = (size_t)8 * K * sizeof(double);
+  if (smem > 160 * 1024) return hipErrorInvalidValue;
+  static size_t attr = 0;
+  if (smem > attr) {
+    hipError_t e = hipFuncSetAttribute((const void *)small_linear_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void *)small_linear_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr = smem;
+  }
+  const int groups = (B + 7) / 8;
+  if ((long long)groups * ((N + 63) / 64) >= 512)
+    hipLaunchKernelGGL(small_linear_kernel<4>, dim3((N + 63) / 64, groups), dim3(256), smem, st, x, ldx, W, b, y, ldy, B, N, K,
+                       act_in, act_out);
+  else
+    hipLaunchKernelGGL(small_linear_kernel<1>, dim3((N + 15) / 16, groups), dim3(256), smem, st, x, ldx, W, b, y, ldy, B, N, K,
+                       act_in, act_out);
   return hipGetLastError();
 }
 

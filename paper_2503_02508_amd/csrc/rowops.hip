@@ -428,6 +428,7 @@ hipError_t launch_embed(const float *x, const float *pw, const float *pb, const 
 // Per token: LayerNorm, modulate with (shift, scale) = fmod[b, 0:D], fmod[b, D:2D],
 // dot with the rows of the output linear that belong to the first C of the 2C
 // channels, and scatter to eps[b, c, ty*p+ph, tx*p+pw] (output features (ph, pw, c)).
+template <int NIT>   // 256-feature slices of a row that a wavefront holds (D <= 256 NIT)
 __global__ __launch_bounds__(256) void final_kernel(const void *__restrict__ tok, int tok_bf16, const float *__restrict__ fmod,
                                                     const float *__restrict__ fw, const float *__restrict__ fb,
                                                     float *__restrict__ eps, int M, int C, int H, int W, int p, int D) {
@@ -439,10 +440,10 @@ __global__ __launch_bounds__(256) void final_kernel(const void *__restrict__ tok
   const float *sh = fmod + (size_t)b * 2 * D, *sc = sh + D;
   // loads never branch (chunks beyond D re-read the last chunk and are zeroed): the row and its modulation
   // vectors arrive in one memory round trip
-  float4 v[LN_MAX_IT], s4[LN_MAX_IT], c4[LN_MAX_IT];
-  int kk[LN_MAX_IT];
+  float4 v[NIT], s4[NIT], c4[NIT];
+  int kk[NIT];
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it) {
+  for (int it = 0; it < NIT; ++it) {
     kk[it] = min((lane + 64 * it) * 4, D - 4);
     v[it] = stream_load4(tok, ((size_t)m * D + kk[it]) >> 2, tok_bf16);
     s4[it] = *(const float4 *)(sh + kk[it]);
@@ -451,20 +452,20 @@ __global__ __launch_bounds__(256) void final_kernel(const void *__restrict__ tok
   // float64 throughout (the noise estimate is rounded once, when it is stored)
   double sum = 0.0;
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it)
+  for (int it = 0; it < NIT; ++it)
     if ((lane + 64 * it) * 4 < D) sum += ((double)v[it].x + (double)v[it].y) + ((double)v[it].z + (double)v[it].w);
   const double mean = wave_sum_d(sum) / (double)D;
   double sq = 0.0;
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it)
+  for (int it = 0; it < NIT; ++it)
     if ((lane + 64 * it) * 4 < D) {
       const double a = v[it].x - mean, bq = v[it].y - mean, c = v[it].z - mean, d = v[it].w - mean;
       sq += (a * a + bq * bq) + (c * c + d * d);
     }
   const double rstd = 1.0 / sqrt(wave_sum_d(sq) / (double)D + 1e-6);
-  double h[LN_MAX_IT][4];
+  double h[NIT][4];
 #pragma unroll
-  for (int it = 0; it < LN_MAX_IT; ++it) {
+  for (int it = 0; it < NIT; ++it) {
     if ((lane + 64 * it) * 4 < D) {
       h[it][0] = (v[it].x - mean) * rstd * (1.0 + (double)c4[it].x) + (double)s4[it].x;
       h[it][1] = (v[it].y - mean) * rstd * (1.0 + (double)c4[it].y) + (double)s4[it].y;
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(256) void final_kernel(const void *__restrict__ tok
       if (oi < n_out) {
         const float *wr = fw + (size_t)((oi / C) * 2 * C + oi % C) * D;
 #pragma unroll
-        for (int it = 0; it < LN_MAX_IT; ++it) {
+        for (int it = 0; it < NIT; ++it) {
           const float4 w4 = *(const float4 *)(wr + kk[it]);
           part[u] += (h[it][0] * (double)w4.x + h[it][1] * (double)w4.y) + (h[it][2] * (double)w4.z + h[it][3] * (double)w4.w);
         }
@@ -520,7 +521,13 @@ __global__ __launch_bounds__(256) void final_kernel(const void *__restrict__ tok
 hipError_t launch_final(const void *tok, int tok_bf16, const float *fmod, const float *fw, const float *fb, float *eps, int B,
                         int C, int H, int W, int p, int D, hipStream_t st) {
   const int M = B * (H / p) * (W / p);
-  hipLaunchKernelGGL(final_kernel, dim3((M + 3) / 4), dim3(256), 0, st, tok, tok_bf16, fmod, fw, fb, eps, M, C, H, W, p, D);
+  const dim3 grid((M + 3) / 4);
+#define QC_FINAL(NIT) hipLaunchKernelGGL(final_kernel<NIT>, grid, dim3(256), 0, st, tok, tok_bf16, fmod, fw, fb, eps, M, C, H, W, p, D)
+  if (D <= 256) QC_FINAL(1);
+  else if (D <= 512) QC_FINAL(2);
+  else if (D <= 1280) QC_FINAL(5);
+  else QC_FINAL(LN_MAX_IT);
+#undef QC_FINAL
   return hipGetLastError();
 }
 

@@ -802,8 +802,15 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && BM * BN <= 128 * 128
 //     kt + NB - 1 issued right after it overwrite.
 // The direct loads and the ring loads are issued through inline assembly, so the compiler neither sees their LDS /
 // register writes nor counts them: every wait on the vector memory counter below is written by hand from the program
-// order of these loads (loads return in order).  Per slab and wavefront that order is: two ring loads (group
-// 2 kt + RB - 1), [barrier], two direct loads (slab kt + NB - 1), two ring loads (group 2 kt + RB).
+// order of these loads.  Per slab and wavefront that order is: two ring loads (group 2 kt + RB - 1), [barrier], two
+// direct loads (slab kt + NB - 1), two ring loads (group 2 kt + RB).
+// The counter is shared by both kinds of load, but only loads of one kind complete in the order they were issued: a
+// register load may complete before an older direct load and the other way round (measured: waits that counted all
+// younger loads of either kind let 2 - 3 % of the outputs of a 32768 x 4608 x 1152 product go wrong on some boxes and
+// none on others).  A wait for a load therefore counts only the younger loads of its own kind: while the load is
+// pending those are pending too, so the counter is above the threshold whatever the other kind does.  The price is
+// that a wait also holds for loads of the other kind beyond the threshold; NB = 8 slabs of direct loads in flight keep
+// the threshold of the barrier's wait at 10.
 #define QC_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
 // the same, tied to the two ring registers that become valid with it: their uses cannot be moved above the wait
 #define QC_WAIT_VM_FOR(n, r0, r1) asm volatile("s_waitcnt vmcnt(" #n ")" : "+v"(r0), "+v"(r1)::"memory")
@@ -815,7 +822,7 @@ __device__ __forceinline__ void direct_load16(const int8_t *base, unsigned voff,
 template <int EPI, int TAG, bool W4, bool RBF>
 __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   constexpr int BM = 128, BN = 256, WM = 1, WN = 4, TM = 4, TN = 2, BK = 64;
-  constexpr int RB = 4, NB = 4;                   // ring depth (k-groups), LDS slabs
+  constexpr int RB = 4, NB = 8;                   // ring depth (k-groups), LDS slabs
   constexpr int SLAB = BM * BK;
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -912,16 +919,17 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
 
   // Slab kt = k-groups 2 kt and 2 kt + 1.  On entry: slabs <= kt have landed and are published, slabs <= kt + NB - 2
   // are requested, fa[0] holds the fragments of (kt, group 0), ring groups <= 2 kt + RB - 2 are requested.
-  // Loads younger than the one a wait is for (see the order above), with RB = NB = 4:
-  //   ring group 2 kt     (requested after the barrier of slab kt - 2): 6 (slab kt - 1) + 2      =  8
-  //   direct loads of slab kt + 1 (after the barrier of slab kt - 2):   2 + 6 (slab kt - 1) + 2  = 10
-  //   ring group 2 kt + 1 (requested at the top of slab kt - 1):        4 + 6 (this slab)        = 10
-  static_assert(RB == 4 && NB == 4 && TN == 2, "the vmcnt waits below are counted for this depth");
+  // Younger loads of the same kind as the one a wait is for (see the order above), with RB = 4, NB = 8:
+  //   ring group 2 kt     (requested after the barrier of slab kt - 2): ring loads of slab kt - 1 (4) and the two at
+  //                       the top of this slab                                                              = 6
+  //   direct loads of slab kt + 1 (after the barrier of slab kt - NB + 2): those of slabs kt + 2 .. kt + NB - 2 = 10
+  //   ring group 2 kt + 1 (requested at the top of slab kt - 1): 2 + 4 (this slab)                              = 6
+  static_assert(RB == 4 && NB == 8 && TN == 2, "the vmcnt waits below are counted for this depth");
   auto slab = [&](int kt, int slot0) {
     read_frags(1, kt, 1);
     load_ring((slot0 + RB - 1) % RB, 2 * kt + RB - 1);
     __builtin_amdgcn_sched_barrier(0);
-    QC_WAIT_VM_FOR(8, bq[slot0][0], bq[slot0][1]);
+    QC_WAIT_VM_FOR(6, bq[slot0][0], bq[slot0][1]);
     mfma_group(0, slot0);
     __builtin_amdgcn_sched_barrier(0);
     QC_WAIT_VM(10);
@@ -930,7 +938,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
     load_ring(slot0 % RB, 2 * kt + RB);
     read_frags(0, kt + 1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    QC_WAIT_VM_FOR(10, bq[(slot0 + 1) % RB][0], bq[(slot0 + 1) % RB][1]);
+    QC_WAIT_VM_FOR(6, bq[(slot0 + 1) % RB][0], bq[(slot0 + 1) % RB][1]);
     mfma_group(1, (slot0 + 1) % RB);
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -947,7 +955,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   gemm_epilogue<BM, BN, WM, WN, EPI, true, RBF>(p, acc, smem, m0, n0, 0);
 }
 
-constexpr int BIG_SMEM_LOOP = 4 * 128 * 64;
+constexpr int BIG_SMEM_LOOP = 8 * 128 * 64;
 constexpr int BIG_SMEM_STAGE = 128 * (128 + 4) * 4;                      // one staged column half, float32 (QKV scatter, residual)
 constexpr int BIG_SMEM_GELU = 256 * 12 + 128 * (256 + 16) + 16 + GELU_FIX_CAP * 16;
 

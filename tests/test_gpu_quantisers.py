@@ -138,3 +138,77 @@ def test_each_fused_quantiser_alone(name, model, B, wb, std):
     assert f_ln2[0] == 0.0, "second LayerNorm quantiser: %.2e of its codes differ" % f_ln2[0]
     assert f_gelu[0] == 0.0, "GELU quantiser: %.2e of its codes differ" % f_gelu[0]
     assert f_attn[0] == 0.0, "attention quantiser: %.2e of its codes differ" % f_attn[0]
+
+
+@pytest.mark.parametrize("wb", [8, 4])
+def test_large_m_linears_every_tile_at_32768_rows(wb):
+    """The four linears of a DiT-XL/2 block at M = 32768 rows (128 latents, the launch shape of the guided workload):
+    the large-M GEMM kernel streams activations and weights with hand-counted waits, so a wait that is one load short
+    shows up as a few wrong 32-row fragments somewhere in the 4608 tiles and not in a small product.  Four rows of
+    every 128-row tile (one per 32-row fragment) are recomputed by the oracle from the device's own upstream codes:
+    Q | K | V, projection output, GELU codes and fc2 output must equal it exactly; and a second run from the same
+    input must reproduce every stored tensor bit for bit."""
+    import torch
+    import paper_2503_02508_amd as qc
+    from dataclasses import replace
+    model = replace(I.shrink(I.DIT_XL2_256, 1), weight_bits=wb)
+    B, seed = 128, 91
+    w = I.make_weights(model, seed, std=0.02)
+    D, R, T = model.hidden, model.mlp_dim, model.tokens
+    tok = I.make_tokens(B, model, seed + 1)
+    cond = I.make_cond(B, model, seed + 2, std=0.5)
+    qp, _ = sampler.calibrate_block(model, w, I.make_tokens(4, model, seed + 3), I.make_cond(4, model, seed + 4, std=0.5))
+    lin, ctx = make_pair(model, w, qp, B)
+    ctx.keep_qkv_f32(True)
+    M = B * T
+    rows = (np.arange(M // 128)[:, None] * 128 + np.array([5, 44, 83, 122])[None]).reshape(-1)
+    rows_t = torch.from_numpy(rows).cuda()
+    L = lin.lin[0]
+    f32 = lambda a: np.asarray(a, dtype=np.float64).astype(np.float32)
+    cond_d, tok_d = _cuda(cond), _cuda(tok)
+
+    def run():
+        x = tok_d.clone()
+        ctx.dit_block(0, qc.QC_FULL, x, cond_d)
+        torch.cuda.synchronize()
+        return dict(x=x.reshape(M, D),
+                    qkv=ctx.workspace("qkv", (M, 3 * D), torch.float32).clone(),
+                    c_attn=ctx.workspace("qact_attn", (M, D), torch.int8).clone(),
+                    c_ln2=ctx.workspace("qact_ln", (M, D), torch.int8).clone(),
+                    c_gelu=ctx.workspace("qact_mlp", (M, R), torch.int8).clone(),
+                    A=ctx.cache_tensor(0, qc.QC_CACHE_ATTN, B).reshape(M, D).clone(),
+                    Mo=ctx.cache_tensor(0, qc.QC_CACHE_MLP, B).reshape(M, D).clone())
+
+    first = run()
+    mod = ctx.workspace("mod", (512, 6 * D), torch.float32).cpu().numpy()[:B].astype(np.float64)
+    for rep in range(3):
+        again = run()
+        for k in first:
+            assert torch.equal(first[k], again[k]), "%s differs between two runs from the same input (run %d)" % (k, rep + 2)
+    ctx.close()
+    g = {k: v[rows_t].cpu().numpy() for k, v in first.items()}
+    bidx = rows // T
+
+    # Q | K | V from the oracle's first-LayerNorm codes of the sampled rows
+    s, z = qp[(0, "qkv")]
+    xr = tok.reshape(M, D)[rows].astype(np.float64)
+    h1 = dit.layer_norm(xr) * (1.0 + mod[bidx, D:2 * D]) + mod[bidx, 0:D]
+    corr = quant.int_matmul(_signed_codes(h1, s, z), L["qkv"].q) - (z - 128) * L["qkv"].wsum[None]
+    want = (np.float64(np.float32(s)) * L["qkv"].scale.astype(np.float64))[None] * corr + L["qkv"].bias.astype(np.float64)[None]
+    assert np.array_equal(g["qkv"], f32(want)), "Q | K | V: %d sampled rows differ" % np.count_nonzero(np.any(g["qkv"] != f32(want), axis=1))
+    # projection output from the device's attention codes
+    s, z = qp[(0, "proj")]
+    corr = quant.int_matmul(g["c_attn"], L["proj"].q) - (z - 128) * L["proj"].wsum[None]
+    want = (np.float64(np.float32(s)) * L["proj"].scale.astype(np.float64))[None] * corr + L["proj"].bias.astype(np.float64)[None]
+    assert np.array_equal(g["A"], f32(want)), "projection: %d sampled rows differ" % np.count_nonzero(np.any(g["A"] != f32(want), axis=1))
+    # GELU codes from the device's second-LayerNorm codes
+    s, z = qp[(0, "fc1")]
+    corr = quant.int_matmul(g["c_ln2"], L["fc1"].q) - (z - 128) * L["fc1"].wsum[None]
+    u = (np.float64(np.float32(s)) * L["fc1"].scale.astype(np.float64))[None] * corr + L["fc1"].bias.astype(np.float64)[None]
+    s2, z2 = qp[(0, "fc2")]
+    want = _signed_codes(dit.gelu_tanh(u), s2, z2)
+    assert np.array_equal(g["c_gelu"], want), "fc1 + GELU: %d sampled rows differ" % np.count_nonzero(np.any(g["c_gelu"] != want, axis=1))
+    # fc2 output from the device's GELU codes
+    corr = quant.int_matmul(g["c_gelu"], L["fc2"].q) - (z2 - 128) * L["fc2"].wsum[None]
+    want = (np.float64(np.float32(s2)) * L["fc2"].scale.astype(np.float64))[None] * corr + L["fc2"].bias.astype(np.float64)[None]
+    assert np.array_equal(g["Mo"], f32(want)), "fc2: %d sampled rows differ" % np.count_nonzero(np.any(g["Mo"] != f32(want), axis=1))

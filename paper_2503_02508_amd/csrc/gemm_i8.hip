@@ -793,27 +793,26 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && BM * BN <= 128 * 128
 //     8 bytes per lane) and each wavefront streams the fragments of its own 64 columns straight into a ring of
 //     registers, RB k-groups deep;
 //   * activations go global -> LDS without passing through registers (global_load_lds_dwordx4: a wavefront's 64
-//     lanes deposit 1 KB at the LDS address in M0, lane l at + 16 l), in slabs of 64 bytes of K, NB slabs in flight.
+//     lanes deposit 1 KB at the LDS address in M0, lane l at + 16 l), in slabs of 64 bytes of K through NB slab buffers.
 //     A slab row is 64 bytes, its four 16-byte chunks XOR-swizzled with bits 2..3 of the row so that the fragment
 //     reads (32 consecutive rows, one chunk) are free of bank conflicts; the swizzle is applied to the global
 //     address a lane fetches from, the LDS side of the transfer is linear;
-//   * one barrier per slab, between its two k-groups: it publishes slab kt + 1 (each wavefront has waited for its own
-//     direct loads of that slab) and certifies that slab kt - 1 is no longer read, whose buffer the loads of slab
-//     kt + NB - 1 issued right after it overwrite.
+//   * one barrier per slab, between its two k-groups.  Every load of a wavefront (its share of the direct loads of
+//     slab kt + 2, the ring loads of k-groups 2 kt + 4 and 2 kt + 5) is issued right after the barrier of slab kt and
+//     the wavefront waits for ALL its loads (vmcnt(0)) right before the barrier of slab kt + 1, so a load has one slab
+//     of MFMA work to land.  That barrier publishes slab kt + 2 and certifies that slab kt is no longer read, whose
+//     buffer (of three) the direct loads issued after it overwrite.
 // The direct loads and the ring loads are issued through inline assembly, so the compiler neither sees their LDS /
-// register writes nor counts them: every wait on the vector memory counter below is written by hand from the program
-// order of these loads.  Per slab and wavefront that order is: two ring loads (group 2 kt + RB - 1), [barrier], two
-// direct loads (slab kt + NB - 1), two ring loads (group 2 kt + RB).
-// The counter is shared by both kinds of load, but only loads of one kind complete in the order they were issued: a
-// register load may complete before an older direct load and the other way round (measured: waits that counted all
-// younger loads of either kind let 2 - 3 % of the outputs of a 32768 x 4608 x 1152 product go wrong on some boxes and
-// none on others).  A wait for a load therefore counts only the younger loads of its own kind: while the load is
-// pending those are pending too, so the counter is above the threshold whatever the other kind does.  The price is
-// that a wait also holds for loads of the other kind beyond the threshold; NB = 8 slabs of direct loads in flight keep
-// the threshold of the barrier's wait at 10.
+// register writes nor counts them.  Waits that count loads (vmcnt(n), n > 0) are not used: the vector memory counter
+// is shared by both kinds of load, and a register load may complete before an older direct load and the other way
+// round, so "at most n younger loads outstanding" says nothing about an older load of the other kind (measured on a
+// standalone copy of this loop: such waits let 2 - 3 % of the outputs of a 32768 x 4608 x 1152 product go wrong on
+// some boxes and none on others, also with thresholds that count only younger loads of the same kind when the loads
+// are interleaved with the MFMAs).  vmcnt(0) followed by the barrier is the one documented way to know that a direct
+// load has landed; it costs about 8 % against the deepest prefetch that happened to give right results.
 #define QC_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
-// the same, tied to the two ring registers that become valid with it: their uses cannot be moved above the wait
-#define QC_WAIT_VM_FOR(n, r0, r1) asm volatile("s_waitcnt vmcnt(" #n ")" : "+v"(r0), "+v"(r1)::"memory")
+// the same, tied to the four ring registers that become valid with it: their uses cannot be moved above the wait
+#define QC_WAIT_VM0_FOR(r0, r1, r2, r3) asm volatile("s_waitcnt vmcnt(0)" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3)::"memory")
 
 __device__ __forceinline__ void direct_load16(const int8_t *base, unsigned voff, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
@@ -822,7 +821,7 @@ __device__ __forceinline__ void direct_load16(const int8_t *base, unsigned voff,
 template <int EPI, int TAG, bool W4, bool RBF>
 __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   constexpr int BM = 128, BN = 256, WM = 1, WN = 4, TM = 4, TN = 2, BK = 64;
-  constexpr int RB = 4, NB = 8;                   // ring depth (k-groups), LDS slabs
+  constexpr int RB = 4, NB = 3;                   // ring depth (k-groups), LDS slabs
   constexpr int SLAB = BM * BK;
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -906,47 +905,41 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
       }
   };
 
-  // prologue: slabs 0 .. NB - 2 and groups 0 .. RB - 2 requested, everything landed before the first use
+  // prologue: slabs 0, 1 and ring groups 0 .. 3 requested, everything landed before the first use
 #pragma unroll
   for (int s = 0; s < NB - 1; ++s) load_slab(s);
 #pragma unroll
-  for (int s = 0; s < RB - 1; ++s) load_ring(s, s);
+  for (int s = 0; s < RB; ++s) load_ring(s, s);
   __builtin_amdgcn_sched_barrier(0);
   QC_WAIT_VM(0);
   __syncthreads();
   read_frags(0, 0, 0);
   __builtin_amdgcn_sched_barrier(0);
 
-  // Slab kt = k-groups 2 kt and 2 kt + 1.  On entry: slabs <= kt have landed and are published, slabs <= kt + NB - 2
-  // are requested, fa[0] holds the fragments of (kt, group 0), ring groups <= 2 kt + RB - 2 are requested.
-  // Younger loads of the same kind as the one a wait is for (see the order above), with RB = 4, NB = 8:
-  //   ring group 2 kt     (requested after the barrier of slab kt - 2): ring loads of slab kt - 1 (4) and the two at
-  //                       the top of this slab                                                              = 6
-  //   direct loads of slab kt + 1 (after the barrier of slab kt - NB + 2): those of slabs kt + 2 .. kt + NB - 2 = 10
-  //   ring group 2 kt + 1 (requested at the top of slab kt - 1): 2 + 4 (this slab)                              = 6
-  static_assert(RB == 4 && NB == 8 && TN == 2, "the vmcnt waits below are counted for this depth");
-  auto slab = [&](int kt, int slot0) {
+  // Slab kt = k-groups 2 kt and 2 kt + 1, ring slots 2 par and 2 par + 1 with par = kt % 2.  On entry: slab kt is
+  // published, slab kt + 1 and ring groups 2 kt + 2, 2 kt + 3 (slots of the other parity) are requested, fa[0] holds the
+  // fragments of (kt, group 0).
+  static_assert(RB == 4 && NB == 3 && TN == 2, "slot and buffer arithmetic below is written for this depth");
+  auto slab = [&](int kt, int par) {
     read_frags(1, kt, 1);
-    load_ring((slot0 + RB - 1) % RB, 2 * kt + RB - 1);
     __builtin_amdgcn_sched_barrier(0);
-    QC_WAIT_VM_FOR(6, bq[slot0][0], bq[slot0][1]);
-    mfma_group(0, slot0);
+    mfma_group(0, 2 * par);
     __builtin_amdgcn_sched_barrier(0);
-    QC_WAIT_VM(10);
+    QC_WAIT_VM0_FOR(bq[2 * (par ^ 1)][0], bq[2 * (par ^ 1)][1], bq[2 * (par ^ 1) + 1][0], bq[2 * (par ^ 1) + 1][1]);
     asm volatile("s_barrier" ::: "memory");
-    load_slab(kt + NB - 1);
-    load_ring(slot0 % RB, 2 * kt + RB);
+    load_slab(kt + 2);
+    load_ring(2 * par, 2 * kt + 4);
     read_frags(0, kt + 1, 0);
     __builtin_amdgcn_sched_barrier(0);
-    QC_WAIT_VM_FOR(6, bq[(slot0 + 1) % RB][0], bq[(slot0 + 1) % RB][1]);
-    mfma_group(1, (slot0 + 1) % RB);
+    mfma_group(1, 2 * par + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_ring(2 * par + 1, 2 * kt + 5);
     __builtin_amdgcn_sched_barrier(0);
   };
-  // K is a multiple of 128 (checked by the launcher): an even number of slabs; the ring slot of a slab's first group
-  // advances by two per slab and returns to 0 every RB / 2 slabs
+  // K is a multiple of 128 (checked by the launcher): an even number of slabs
   for (int kt = 0; kt + 2 <= nk; kt += 2) {
     slab(kt, 0);
-    slab(kt + 1, 2);
+    slab(kt + 1, 1);
   }
   // the loads that ran past the end (clamped addresses) must have landed before LDS and registers are reused
   QC_WAIT_VM(0);
@@ -955,7 +948,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   gemm_epilogue<BM, BN, WM, WN, EPI, true, RBF>(p, acc, smem, m0, n0, 0);
 }
 
-constexpr int BIG_SMEM_LOOP = 8 * 128 * 64;
+constexpr int BIG_SMEM_LOOP = 3 * 128 * 64;
 constexpr int BIG_SMEM_STAGE = 128 * (128 + 4) * 4;                      // one staged column half, float32 (QKV scatter, residual)
 constexpr int BIG_SMEM_GELU = 256 * 12 + 128 * (256 + 16) + 16 + GELU_FIX_CAP * 16;
 

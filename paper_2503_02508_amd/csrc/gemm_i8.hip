@@ -791,37 +791,33 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN == 4 && BM * BN <= 128 * 128
 //   * weights never touch LDS: they are stored a second time in MFMA fragment order (fragment (n / 32, k / 32) =
 //     64 lanes x 16 bytes, lane l = row n % 32 = l % 32, bytes 16 (l / 32) .. of the 32 k values; packed nibbles:
 //     8 bytes per lane) and each wavefront streams the fragments of its own 64 columns straight into a ring of
-//     registers, RB k-groups deep;
-//   * activations go global -> LDS without passing through registers (global_load_lds_dwordx4: a wavefront's 64
-//     lanes deposit 1 KB at the LDS address in M0, lane l at + 16 l), in slabs of 64 bytes of K through NB slab buffers.
-//     A slab row is 64 bytes, its four 16-byte chunks XOR-swizzled with bits 2..3 of the row so that the fragment
-//     reads (32 consecutive rows, one chunk) are free of bank conflicts; the swizzle is applied to the global
-//     address a lane fetches from, the LDS side of the transfer is linear;
-//   * one barrier per slab, between its two k-groups.  Every load of a wavefront (its share of the direct loads of
-//     slab kt + 2, the ring loads of k-groups 2 kt + 4 and 2 kt + 5) is issued right after the barrier of slab kt and
-//     the wavefront waits for ALL its loads (vmcnt(0)) right before the barrier of slab kt + 1, so a load has one slab
-//     of MFMA work to land.  That barrier publishes slab kt + 2 and certifies that slab kt is no longer read, whose
-//     buffer (of three) the direct loads issued after it overwrite.
-// The direct loads and the ring loads are issued through inline assembly, so the compiler neither sees their LDS /
-// register writes nor counts them.  Waits that count loads (vmcnt(n), n > 0) are not used: the vector memory counter
-// is shared by both kinds of load, and a register load may complete before an older direct load and the other way
-// round, so "at most n younger loads outstanding" says nothing about an older load of the other kind (measured on a
-// standalone copy of this loop: such waits let 2 - 3 % of the outputs of a 32768 x 4608 x 1152 product go wrong on
-// some boxes and none on others, also with thresholds that count only younger loads of the same kind when the loads
-// are interleaved with the MFMAs).  vmcnt(0) followed by the barrier is the one documented way to know that a direct
-// load has landed; it costs about 8 % against the deepest prefetch that happened to give right results.
+//     registers, four k-groups deep (slots 2 par, 2 par + 1 for the two k-groups of a slab of parity par);
+//   * activations go global -> registers -> LDS in slabs of 64 bytes of K (a thread moves two 16-byte chunks per
+//     slab), two slabs in flight in registers, three slab buffers in LDS.  A slab row is 64 bytes, its four 16-byte
+//     chunks XOR-swizzled with bits 2..3 of the row so that the fragment reads (32 consecutive rows, one chunk) are
+//     free of bank conflicts;
+//   * one barrier per slab, between its two k-groups: slab kt + 1 is written to LDS during the first k-group of slab
+//     kt and read after that barrier; its buffer was last read in slab kt - 2, two barriers ago;
+//   * one memory instruction is issued behind each MFMA (pinned with scheduling barriers), so a wavefront keeps its
+//     matrix pipe fed while its loads, LDS writes and fragment reads are in flight.
+// Every global load here is an ordinary register load issued through inline assembly (the compiler neither sees nor
+// counts them); register loads complete in the order they were issued, so each wait on the vector memory counter below
+// is the number of loads issued after the one it is for.  Per slab the order is: two activation loads (slab kt + 3),
+// two ring loads (k-group 2 kt + 4), [barrier], two ring loads (k-group 2 kt + 5).
+// (A variant that sent the activations straight to LDS (global_load_lds_dwordx4) was measured first: those loads and
+// register loads share the counter but complete out of order with respect to each other, so counted waits gave wrong
+// fragments on some boxes, and draining the counter before every barrier cost 8 % against this version.)
 #define QC_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
-// the same, tied to the four ring registers that become valid with it: their uses cannot be moved above the wait
-#define QC_WAIT_VM0_FOR(r0, r1, r2, r3) asm volatile("s_waitcnt vmcnt(0)" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3)::"memory")
-
-__device__ __forceinline__ void direct_load16(const int8_t *base, unsigned voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
-}
+// the same, tied to registers that become valid with it: their uses cannot be moved above the wait
+#define QC_WAIT_VM_FOR2(n, r0, r1) asm volatile("s_waitcnt vmcnt(" #n ")" : "+v"(r0), "+v"(r1)::"memory")
+#define QC_WAIT_VM_FOR4(n, r0, r1, r2, r3) asm volatile("s_waitcnt vmcnt(" #n ")" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3)::"memory")
+// all LDS writes of this wavefront done, then the workgroup barrier
+#define QC_LDS_DONE_BARRIER asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory")
 
 template <int EPI, int TAG, bool W4, bool RBF>
 __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   constexpr int BM = 128, BN = 256, WM = 1, WN = 4, TM = 4, TN = 2, BK = 64;
-  constexpr int RB = 4, NB = 3;                   // ring depth (k-groups), LDS slabs
+  constexpr int RB = 4, NB = 3, NS = 2;           // ring depth (k-groups), LDS slab buffers, slabs in flight in registers
   constexpr int SLAB = BM * BK;
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -838,23 +834,22 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   const int m0 = tm * BM, n0 = tn * BN;
   const int wn0 = wave * (TN * 32);
 
-  // direct loads of the activations: instruction i of wavefront w fills rows 64 i + 16 w .. + 16 of a slab; lane l ->
-  // row l / 4, physical chunk l % 4, which holds logical chunk (l % 4) ^ ((row >> 2) & 3).  Rows beyond M re-read row M - 1.
-  unsigned aoff[2];
+  // activations: load i of thread tid covers row 64 i + tid / 4, 16-byte chunk tid % 4 of a slab and is written to
+  // LDS at the swizzled position of that chunk.  Rows beyond M re-read row M - 1.
+  unsigned aoff[2], lpos[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const int row = i * 64 + wave * 16 + (lane >> 2);
-    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    const int row = i * 64 + (tid >> 2), c = tid & 3;
     aoff[i] = (unsigned)(min(m0 + row, p.M - 1) - m0) * (unsigned)p.lda + c * 16;
+    lpos[i] = row * BK + ((c ^ ((row >> 2) & 3)) * 16);
   }
   const int8_t *abase = p.A + (size_t)m0 * p.lda;
   const int nk = p.K / BK, ng = p.K / 32;
-  auto load_slab = [&](int kt) {                  // slabs past the end re-read the last one (never used)
-    const int8_t *src = abase + min(kt, nk - 1) * BK;
-    const unsigned dst = (unsigned)((kt % NB) * SLAB + wave * 1024);
-    direct_load16(src, aoff[0], dst);
-    direct_load16(src, aoff[1], dst + 4096);
+  v4i ra[NS][2];
+  auto load_a = [&](int q, int kt, int i) {       // slabs past the end re-read the last one (never used)
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(ra[q][i]) : "v"(aoff[i]), "s"(abase + min(kt, nk - 1) * BK) : "memory");
   };
+  auto write_a = [&](int q, int kt, int i) { *(v4i *)(smem + (kt % NB) * SLAB + lpos[i]) = ra[q][i]; };
 
   // weight fragment streams of this wavefront: n-blocks (n0 + wn0) / 32 + j (blocks past N re-read the last block)
   constexpr int FRAG = W4 ? 512 : 1024;           // bytes per fragment
@@ -884,64 +879,89 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
 
   const int frow = lane & 31, fsw = (frow >> 2) & 3;
   v4i fa[2][TM];
-  auto read_frags = [&](int f, int kt, int kg) {
-    const unsigned char *a_base = smem + (kt % NB) * SLAB + frow * BK + ((((lane >> 5) + 2 * kg) ^ fsw) * 16);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) fa[f][i] = *(const v4i *)(a_base + i * 32 * BK);
+  auto read_frag = [&](int f, int kt, int kg, int i) {
+    fa[f][i] = *(const v4i *)(smem + (kt % NB) * SLAB + frow * BK + ((((lane >> 5) + 2 * kg) ^ fsw) * 16) + i * 32 * BK);
   };
-  auto mfma_group = [&](int f, int slot) {
-    v4i wf[TN];
+  v4i wf[TN];
+  auto unpack_ring = [&](int slot) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       if constexpr (W4) wf[j] = unpack_w4(bq[slot][j]);
       else wf[j] = bq[slot][j];
     }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        if (EPI == EPI_GELU_Q) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], fa[f][i], acc[i][j], 0, 0, 0);
-        else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[f][i], wf[j], acc[i][j], 0, 0, 0);
-      }
   };
+  auto mfma = [&](int f, int i, int j) {
+    if (EPI == EPI_GELU_Q) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[j], fa[f][i], acc[i][j], 0, 0, 0);
+    else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[f][i], wf[j], acc[i][j], 0, 0, 0);
+  };
+#define QC_SB __builtin_amdgcn_sched_barrier(0)
 
-  // prologue: slabs 0, 1 and ring groups 0 .. 3 requested, everything landed before the first use
+  // prologue: slab 0 -> LDS, slabs 1 and 2 -> the two register sets, ring groups 0 .. 3
+  load_a(0, 0, 0); load_a(0, 0, 1);
+  load_a(1, 1, 0); load_a(1, 1, 1);
 #pragma unroll
-  for (int s = 0; s < NB - 1; ++s) load_slab(s);
+  for (int g = 0; g < RB; ++g) load_ring(g, g);
+  QC_SB;
+  QC_WAIT_VM_FOR4(0, ra[0][0], ra[0][1], ra[1][0], ra[1][1]);
+  write_a(0, 0, 0); write_a(0, 0, 1);
+  QC_SB;
+  load_a(0, 2, 0); load_a(0, 2, 1);
+  QC_LDS_DONE_BARRIER;
 #pragma unroll
-  for (int s = 0; s < RB; ++s) load_ring(s, s);
-  __builtin_amdgcn_sched_barrier(0);
-  QC_WAIT_VM(0);
-  __syncthreads();
-  read_frags(0, 0, 0);
-  __builtin_amdgcn_sched_barrier(0);
+  for (int i = 0; i < TM; ++i) read_frag(0, 0, 0, i);
+  QC_SB;
 
-  // Slab kt = k-groups 2 kt and 2 kt + 1, ring slots 2 par and 2 par + 1 with par = kt % 2.  On entry: slab kt is
-  // published, slab kt + 1 and ring groups 2 kt + 2, 2 kt + 3 (slots of the other parity) are requested, fa[0] holds the
-  // fragments of (kt, group 0).
-  static_assert(RB == 4 && NB == 3 && TN == 2, "slot and buffer arithmetic below is written for this depth");
-  auto slab = [&](int kt, int par) {
-    read_frags(1, kt, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_group(0, 2 * par);
-    __builtin_amdgcn_sched_barrier(0);
-    QC_WAIT_VM0_FOR(bq[2 * (par ^ 1)][0], bq[2 * (par ^ 1)][1], bq[2 * (par ^ 1) + 1][0], bq[2 * (par ^ 1) + 1][1]);
-    asm volatile("s_barrier" ::: "memory");
-    load_slab(kt + 2);
+  // Slab kt = k-groups 2 kt and 2 kt + 1, ring slots 2 par and 2 par + 1 (par = kt % 2), register set q = (kt + 1) % 2
+  // holds slab kt + 1.  On entry: slab kt is in LDS and published; fa[0] holds (or awaits) the fragments of (kt,
+  // group 0); ring groups up to 2 kt + 3 and activation slabs up to kt + 2 are requested.
+  // Loads issued after the one a wait is for:
+  //   top of the slab, for ring group 2 kt and for slab kt + 1 in registers (both requested in the first half of slab
+  //   kt - 2, the activations first): ring group 2 kt - 1 ... (2) and the six loads of slab kt - 1                 = 8
+  //   (slab 1 needs the prologue's load of slab 2, which has only the six loads of slab 0 behind it:                 6)
+  //   after the barrier, for ring group 2 kt + 1 (requested at the end of slab kt - 2): six loads of slab kt - 1 and
+  //   the four of this slab's first half                                                                          = 10
+  static_assert(RB == 4 && NB == 3 && NS == 2 && TM == 4 && TN == 2, "waits and slots below are written for this depth");
+  auto slab = [&](int kt, int par, auto first) {
+    const int q = (kt + 1) % NS;
+    if constexpr (decltype(first)::value) QC_WAIT_VM_FOR4(6, bq[2 * par][0], bq[2 * par][1], ra[q][0], ra[q][1]);
+    else QC_WAIT_VM_FOR4(8, bq[2 * par][0], bq[2 * par][1], ra[q][0], ra[q][1]);
+    unpack_ring(2 * par);
+    QC_SB;
+    mfma(0, 0, 0); write_a(q, kt + 1, 0); QC_SB;
+    mfma(0, 0, 1); write_a(q, kt + 1, 1); QC_SB;
+    mfma(0, 1, 0); read_frag(1, kt, 1, 0); QC_SB;
+    mfma(0, 1, 1); read_frag(1, kt, 1, 1); QC_SB;
+    mfma(0, 2, 0); read_frag(1, kt, 1, 2); QC_SB;
+    mfma(0, 2, 1); read_frag(1, kt, 1, 3); QC_SB;
+    mfma(0, 3, 0); load_a(q, kt + 3, 0); QC_SB;
+    mfma(0, 3, 1); load_a(q, kt + 3, 1); QC_SB;
     load_ring(2 * par, 2 * kt + 4);
-    read_frags(0, kt + 1, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_group(1, 2 * par + 1);
-    __builtin_amdgcn_sched_barrier(0);
+    QC_SB;
+    QC_LDS_DONE_BARRIER;
+    QC_WAIT_VM_FOR2(10, bq[2 * par + 1][0], bq[2 * par + 1][1]);
+    unpack_ring(2 * par + 1);
+    QC_SB;
+    mfma(1, 0, 0); QC_SB;
+    mfma(1, 0, 1); QC_SB;
+    mfma(1, 1, 0); QC_SB;
+    mfma(1, 1, 1); QC_SB;
+    mfma(1, 2, 0); read_frag(0, kt + 1, 0, 0); QC_SB;
+    mfma(1, 2, 1); read_frag(0, kt + 1, 0, 1); QC_SB;
+    mfma(1, 3, 0); read_frag(0, kt + 1, 0, 2); QC_SB;
+    mfma(1, 3, 1); read_frag(0, kt + 1, 0, 3); QC_SB;
     load_ring(2 * par + 1, 2 * kt + 5);
-    __builtin_amdgcn_sched_barrier(0);
+    QC_SB;
   };
-  // K is a multiple of 128 (checked by the launcher): an even number of slabs
-  for (int kt = 0; kt + 2 <= nk; kt += 2) {
-    slab(kt, 0);
-    slab(kt + 1, 1);
+  // K is a multiple of 128 (checked by the launcher): an even number of slabs, at least two
+  slab(0, 0, std::false_type());
+  slab(1, 1, std::true_type());
+  for (int kt = 2; kt + 2 <= nk; kt += 2) {
+    slab(kt, 0, std::false_type());
+    slab(kt + 1, 1, std::false_type());
   }
-  // the loads that ran past the end (clamped addresses) must have landed before LDS and registers are reused
+#undef QC_SB
+  // the loads that ran past the end (clamped addresses) must have landed before registers are reused, and every
+  // wavefront must be past its last fragment read before the epilogue reuses LDS
   QC_WAIT_VM(0);
   __builtin_amdgcn_sched_barrier(0);
   __syncthreads();

@@ -51,6 +51,7 @@ struct GemmArgs {
   // (the two gate chunks of an adaLN projection).
   int sel_D;
   int xcd_m;                 // XCD grid rows (set by the launcher)
+  int group_m;               // large-M kernel: tile rows per group of its tile order (set by the launcher)
   // EPI_F32
   float *y;
   int ldy;

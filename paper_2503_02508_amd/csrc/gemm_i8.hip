@@ -398,31 +398,48 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
     }
     if (FAST) {
       // every row of the tile exists and belongs to batch element b_uniform; N is a multiple of 32, so a wavefront's
-      // 32-column block lies inside the matrix or outside it as a whole
+      // 32-column block lies inside the matrix or outside it as a whole.  Addresses are a wavefront-uniform row pointer
+      // (scalar arithmetic) plus one 32-bit lane offset, and the loads of x of XB blocks (16 values per lane each: the
+      // registers of the K loop's operand ring and fragments are free now) are issued before the first is used, so a
+      // tile's epilogue pays TM x TN / XB memory round trips instead of TM x TN.
+      constexpr int XB = (!RBF && TM % 2 == 0) ? 2 : 1;   // the bfloat16 variants have no registers to spare   // the bfloat16 variants have no registers to spare
+      const int wv = __builtin_amdgcn_readfirstlane(wave);
+      const int wm0u = (wv / WN) * (BM / WM), wn0u = (wv % WN) * (BN / WN);
+      const unsigned loff = (unsigned)((lane >> 5) * 4) * (unsigned)p.N + (unsigned)(lane & 31);
+      const size_t xsz = x_bf16 ? 2 : 4, csz = cache_bf16 ? 2 : 4;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn0 + j * 32 + (lane & 31);
-        if (n0 + wn0 + j * 32 >= p.N) continue;
+        const int nb = n0 + wn0u + j * 32;
+        if (nb >= p.N) continue;
+        const int n = nb + (lane & 31);
         const double sc = (double)a_s * (double)w_scale[n];
         const int zw = a_z * wsum[n];
         const double bs = bias ? (double)bias[n] : 0.0;
         const float g = p.gate[(long long)b_uniform * p.ld_gate + n];
-        const long long ob = (long long)m0 * p.N + n;
+        const size_t e0 = (size_t)(m0 + wm0u) * p.N + nb;           // first element of the wavefront's block column
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          float xv[16];
+        for (int i0 = 0; i0 < TM; i0 += XB) {
+          float xv[XB][16];
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            xv[r] = stream_load(p.x, ob + (unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N, x_bf16);
+          for (int ii = 0; ii < XB; ++ii) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float v = dequant_f32(sc, acc[i][j][r] - zw, bs);
-            const unsigned o = (unsigned)(wm0 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * (unsigned)p.N;
-            if (cache_bf16) ((unsigned short *)p.cache_out + ob)[o] = bf16_bits(v);
-            else ((float *)p.cache_out + ob)[o] = v;
-            stream_store(p.x, ob + o, fmaf(g, v, xv[r]), x_bf16);
+            for (int r = 0; r < 16; ++r) {
+              const size_t er = e0 + (size_t)((i0 + ii) * 32 + (r >> 2) * 8 + (r & 3)) * p.N;
+              xv[ii][r] = stream_load((const char *)p.x + er * xsz, loff, x_bf16);
+            }
           }
-          __builtin_amdgcn_sched_barrier(0);                  // one block's values live at a time
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int ii = 0; ii < XB; ++ii) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const size_t er = e0 + (size_t)((i0 + ii) * 32 + (r >> 2) * 8 + (r & 3)) * p.N;
+              const float v = dequant_f32(sc, acc[i0 + ii][j][r] - zw, bs);
+              stream_store((char *)p.cache_out + er * csz, loff, v, cache_bf16);
+              stream_store((char *)p.x + er * xsz, loff, fmaf(g, v, xv[ii][r]), x_bf16);
+            }
+            __builtin_amdgcn_sched_barrier(0);                // one block's dequantised values live at a time
+          }
         }
       }
       return;
@@ -832,7 +849,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   const int GM = p.group_m;
   const int grp = t / (GM * tiles_n), gm0 = grp * GM, gsz = min(GM, tiles_m - gm0), rr = t - grp * GM * tiles_n;
   const int tn = rr / gsz, tm = gm0 + rr % gsz;
-  const int m0 = tm * BM, n0 = tn * BN;
+  const int m0 = __builtin_amdgcn_readfirstlane(tm * BM), n0 = __builtin_amdgcn_readfirstlane(tn * BN);   // the divisions above run on the vector ALU
   const int wn0 = wave * (TN * 32);
 
   // activations: load i of thread tid covers row 64 i + tid / 4, 16-byte chunk tid % 4 of a slab and is written to

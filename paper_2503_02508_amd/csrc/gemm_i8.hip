@@ -147,7 +147,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
     }
     __syncthreads();
     const QParam oq = *p.o_qp;
-    const float o_s = oq.s, o_inv = 1.0f / oq.s, o_z = (float)oq.z;
+    // codes are formed as the paper's unsigned ones (zero point + 128, clamped to 0 .. 255, converted and packed by
+    // one instruction each); the sign bit of the four bytes is flipped back when the word is stored
+    const float o_s = oq.s, o_inv = 1.0f / oq.s, o_zu = (float)(oq.z + 128);
     // Bound of the fast path's error in units of the output step, as a multiple of |v| / s (|GELU(v)| <= |v|):
     // 1.5e-6 covers the float32 dequantisation (accumulators beyond 2^24 are rounded on conversion) and the exp2 /
     // reciprocal estimates with a margin of 2, 2e-7 the unrefined quotient gv * (1 / s); 2e-6 absolute covers the bias
@@ -165,16 +167,17 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
         const v4f bs = *(const v4f *)(c_bs + nl);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-          int code[4];
+          unsigned w = 0;
           bool doubt[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float v = fmaf(sc[e], (float)(acc[i][j][rg * 4 + e] - zw[e]), bs[e]);
             const float q = gelu_tanh(v) * o_inv;
             const float r = __builtin_rintf(q);
-            code[e] = (int)fminf(fmaxf(r + o_z, -128.0f), 127.0f);
+            w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(r + o_zu, 0.0f, 255.0f), e, w);
             doubt[e] = fmaf(tol_v, fabsf(v), fabsf(q - r)) > doubt_at;
           }
+          w ^= 0x80808080u;
           // one branch per four outputs; taken by a wavefront about once in a hundred times
           if (doubt[0] | doubt[1] | doubt[2] | doubt[3]) {
 #pragma unroll
@@ -188,8 +191,6 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
                 }
               }
           }
-          const unsigned w = (unsigned)(code[0] & 0xFF) | ((unsigned)(code[1] & 0xFF) << 8) |
-                             ((unsigned)(code[2] & 0xFF) << 16) | ((unsigned)(code[3] & 0xFF) << 24);
           *(unsigned *)(stage + (wm0 + i * 32 + (lane & 31)) * SROW + nl) = w;
         }
       }

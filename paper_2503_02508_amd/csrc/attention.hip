@@ -223,7 +223,7 @@ __device__ __forceinline__ void split_pairs(v4f v, v2u &hi, v2u &lo) {
 // arithmetic per query is the same in both.
 template <int NCH, int NEB, int QB>
 __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__restrict__ Qp, const float *__restrict__ Kp,
-                                                            const float *__restrict__ Vt, int T, int Tp, int H, int hd, int DPv,
+                                                            const float *__restrict__ Vt, int BH, int T, int Tp, int H, int hd, int DPv,
                                                             float q_mul, const QParam *qp, int8_t *__restrict__ q_out) {
   constexpr int DP = 32 * NCH;
   constexpr int KROW = DP + 8;    // halves per K row in LDS (16 bytes of padding)
@@ -236,9 +236,15 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__re
 
   const int D = H * hd;
   if (threadIdx.x == 0) fix_cnt_s = 0;            // published by the barriers of the key loop
-  // blockIdx.x = (batch, head): the query blocks of one head are B*H workgroups apart and land on the same XCD
-  // (workgroups go round-robin over the 8 XCDs), so its K and V are fetched into one L2 only
-  const int bh = blockIdx.x, b = bh / H, h = bh % H;
+  // Workgroups go round-robin over the 8 XCDs.  Workgroup id -> XCD id % 8, position id / 8 on that XCD; the query
+  // blocks of one (batch, head) take consecutive positions of one XCD, so they run at the same time and the head's K
+  // and V are fetched from HBM once, into that XCD's L2.
+  const int n_qblk = gridDim.y;                   // query blocks per head (the grid is 1-D in effect: x * y workgroups)
+  const int wg = blockIdx.y * gridDim.x + blockIdx.x;
+  const int pos = wg >> 3, qblk = pos % n_qblk;
+  const int bh = (pos / n_qblk) * 8 + (wg & 7);
+  if (bh >= BH) return;                           // the grid is rounded up to whole groups of 8 heads
+  const int b = bh / H, h = bh % H;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ql = lane & 15, g = lane >> 4;
   const long long tok_base = (long long)bh * T * hd;
@@ -321,7 +327,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__re
     v4f qraw[QB][NCH][2];
 #pragma unroll
     for (int j = 0; j < QB; ++j) {
-      q_row[j] = blockIdx.y * (64 * QB) + wave * (16 * QB) + j * 16 + ql;
+      q_row[j] = qblk * (64 * QB) + wave * (16 * QB) + j * 16 + ql;
       const float *src = Qp + tok_base + (long long)min(q_row[j], T - 1) * hd;
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
@@ -492,7 +498,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__re
     }
   }
   __syncthreads();
-  const int q_first = blockIdx.y * NQ;            // first query of the workgroup
+  const int q_first = qblk * NQ;                  // first query of the workgroup
   {
     // softmax(q K^T / sqrt(d)) V[:, feature] in float64 for every queued output
     const int nfix = min(*fix_cnt, FIX_CAP);
@@ -596,14 +602,14 @@ hipError_t launch_attention_f16(const float *q32, const float *k32, const float 
   const float q_mul = 1.4426950408889634f / std::sqrt((float)hd);     // log2(e) / sqrt(d)
   // one query block per wavefront when two would leave compute units without a workgroup
   const int qb = B * H * ((T + 127) / 128) < 256 ? 1 : 2;
-  dim3 grid(B * H, (T + 64 * qb - 1) / (64 * qb));
+  dim3 grid((B * H + 7) / 8 * 8, (T + 64 * qb - 1) / (64 * qb));
 #define QC_ATT(NCH, NEB)                                                                                                    \
   do {                                                                                                                      \
     if (qb == 1)                                                                                                            \
-      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 1>), grid, dim3(256), 0, st, q32, k32, vt32, T, Tp, H, hd, DPv,    \
+      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 1>), grid, dim3(256), 0, st, q32, k32, vt32, B * H, T, Tp, H, hd, DPv,    \
                          q_mul, qp, q_out);                                                                                 \
     else                                                                                                                    \
-      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 2>), grid, dim3(256), 0, st, q32, k32, vt32, T, Tp, H, hd, DPv,    \
+      hipLaunchKernelGGL((attention_f16_kernel<NCH, NEB, 2>), grid, dim3(256), 0, st, q32, k32, vt32, B * H, T, Tp, H, hd, DPv,    \
                          q_mul, qp, q_out);                                                                                 \
   } while (0)
   if (nch == 1 && neb == 1) QC_ATT(1, 1);

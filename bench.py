@@ -34,23 +34,23 @@ TAP_ITERS, TAP_MAX_PASSES = 8, 100   # power-iteration rounds and k-means pass l
 # under profiles/, keyed by (workload, kernel class).  None where no counter run covers the pair.
 TRAFFIC = {
     # profiles/sampler_cfg1_dit_xl2_b8_hbm_traffic.txt: (FETCH_SIZE * 2.0 + WRITE_SIZE * 1.0) KiB per dispatch
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc2"): (17402.8 * 2.0 + 9216.0) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_qkv"): (6389.8 * 2.0 + 13824.0) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc1"): (7754.0 * 2.0 + 4608.0) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_proj"): (6173.6 * 2.0 + 9216.0) * 1024,
-    ("dit_xl2_256_w8a8_b8_ddim50_n2", "attention"): (7323.0 * 2.0 + 1536.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc2"): (17402.7 * 2.0 + 9216.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_qkv"): (6389.1 * 2.0 + 13824.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_fc1"): (7751.1 * 2.0 + 4608.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "gemm_proj"): (6167.5 * 2.0 + 9216.0) * 1024,
+    ("dit_xl2_256_w8a8_b8_ddim50_n2", "attention"): (7326.0 * 2.0 + 1536.0) * 1024,
     # profiles/sampler_cfg2_dit_xl2_b64_cfg_hbm_traffic.txt
-    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "gemm_fc2"): (344587.3 * 2.0 + 294912.0) * 1024,
-    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "gemm_qkv"): (124067.3 * 2.0 + 452701.3) * 1024,
-    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "gemm_fc1"): (96970.3 * 2.0 + 147456.0) * 1024,
-    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "gemm_proj"): (132579.1 * 2.0 + 294912.0) * 1024,
-    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "attention"): (437464.5 * 2.0 + 49152.0) * 1024,
+    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "gemm_fc2"): (332125.0 * 2.0 + 294912.0) * 1024,
+    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "gemm_qkv"): (154249.9 * 2.0 + 454764.7) * 1024,
+    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "gemm_fc1"): (254733.6 * 2.0 + 147456.0) * 1024,
+    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "gemm_proj"): (120028.1 * 2.0 + 294912.0) * 1024,
+    ("dit_xl2_256_w8a8_b64_cfg_ddim100_n3", "attention"): (268460.4 * 2.0 + 49152.0) * 1024,
     # profiles/sampler_cfg3_dit_xl2_512_b16_hbm_traffic.txt
-    ("dit_xl2_512_w8a8_b16_ddim50_n2", "gemm_fc2"): (158593.7 * 2.0 + 147456.0) * 1024,
-    ("dit_xl2_512_w8a8_b16_ddim50_n2", "gemm_qkv"): (53030.9 * 2.0 + 225313.9) * 1024,
-    ("dit_xl2_512_w8a8_b16_ddim50_n2", "gemm_fc1"): (52517.7 * 2.0 + 73728.0) * 1024,
-    ("dit_xl2_512_w8a8_b16_ddim50_n2", "gemm_proj"): (60716.0 * 2.0 + 147456.0) * 1024,
-    ("dit_xl2_512_w8a8_b16_ddim50_n2", "attention"): (836601.4 * 2.0 + 24576.0) * 1024,
+    ("dit_xl2_512_w8a8_b16_ddim50_n2", "gemm_fc2"): (147087.0 * 2.0 + 147456.0) * 1024,
+    ("dit_xl2_512_w8a8_b16_ddim50_n2", "gemm_qkv"): (76425.0 * 2.0 + 226030.6) * 1024,
+    ("dit_xl2_512_w8a8_b16_ddim50_n2", "gemm_fc1"): (124429.6 * 2.0 + 73728.0) * 1024,
+    ("dit_xl2_512_w8a8_b16_ddim50_n2", "gemm_proj"): (58563.5 * 2.0 + 147456.0) * 1024,
+    ("dit_xl2_512_w8a8_b16_ddim50_n2", "attention"): (143814.6 * 2.0 + 24576.0) * 1024,
     # profiles/clustering_tap1_counters.txt
     ("tap1", "similarity"): (1706789.6 * 2.0 + 279926.8) * 1024,
 }

@@ -199,22 +199,25 @@ typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
 
-// four float32 values -> four hi halves (the value rounded to fp16) and four lo halves (what the rounding left, again
-// rounded to fp16): hi + lo carries about 22 significant bits.  The hi half that is stored and the one that is
-// subtracted must be the same bits: the conversion is therefore made opaque to the compiler, which otherwise forms
-// the stored halves with the packed conversion instruction and the subtracted ones with the scalar one, and the two
-// were observed to disagree on ties (the sum was then off by one unit of the hi half).
+// Two float32 values -> their hi halves (the values rounded to fp16, packed) and lo halves (what the rounding left,
+// again rounded to fp16): hi + lo carries about 22 significant bits.  One packed conversion per pair of halves.  The
+// hi halves that are stored and the ones that are subtracted must be the same bits, so the packed word is made opaque
+// to the compiler and converted back from there (otherwise it forms the subtracted halves with a second, scalar
+// conversion, and the two were observed to disagree on ties: the sum was then off by one unit of the hi half).
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void split_pair(float a, float b, unsigned &hi, unsigned &lo) {
+  hi = __builtin_bit_cast(unsigned, __builtin_convertvector((v2f){a, b}, v2h));
+  asm volatile("" : "+v"(hi));
+  const v2h hh = __builtin_bit_cast(v2h, hi);
+  lo = __builtin_bit_cast(unsigned, __builtin_convertvector((v2f){a - (float)hh[0], b - (float)hh[1]}, v2h));
+}
 __device__ __forceinline__ void split_pairs(v4f v, v2u &hi, v2u &lo) {
-  unsigned hb[4], lb[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    hb[e] = __builtin_bit_cast(unsigned short, (_Float16)v[e]);
-    asm volatile("" : "+v"(hb[e]));
-    const float hf = (float)__builtin_bit_cast(_Float16, (unsigned short)hb[e]);
-    lb[e] = __builtin_bit_cast(unsigned short, (_Float16)(v[e] - hf));
-  }
-  hi = (v2u){hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16)};
-  lo = (v2u){lb[0] | (lb[1] << 16), lb[2] | (lb[3] << 16)};
+  unsigned h0, l0, h1, l1;
+  split_pair(v[0], v[1], h0, l0);
+  split_pair(v[2], v[3], h1, l1);
+  hi = (v2u){h0, h1};
+  lo = (v2u){l0, l1};
 }
 
 // NCH feature chunks of 32 (operand width), NEB feature blocks of 16 that hold real features, QB query blocks of 16 per
@@ -409,13 +412,17 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__re
 #pragma unroll
     for (int j = 0; j < QB; ++j) {
       float mx = -INFINITY;
+      if (ragged_tile) {                    // wavefront-uniform: whole tiles skip the masking
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (k0 + kt * 16 + 4 * g + r >= T) s[j][kt][r] = -INFINITY;
+      }
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (ragged_tile && k0 + kt * 16 + 4 * g + r >= T) s[j][kt][r] = -INFINITY;
-          mx = fmaxf(mx, s[j][kt][r]);
-        }
+        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[j][kt][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m_run[j], mx);
@@ -425,15 +432,22 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__re
 #pragma unroll
       for (int e = 0; e < NEB; ++e) o[j][e] *= alpha;
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
+      for (int a = 0; a < 2; ++a) {
+        v4u hw, lw;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float pv = __builtin_amdgcn_exp2f(s[j][kt][r] - m_new);
-          l_run[j] += pv;
-          const _Float16 hi = (_Float16)pv;
-          ph[j][kt >> 1][(kt & 1) * 4 + r] = hi;
-          pl[j][kt >> 1][(kt & 1) * 4 + r] = (_Float16)(pv - (float)hi);
+        for (int w = 0; w < 4; ++w) {         // word w of the operand: keys (kt = 2 a + w / 2, r = 2 (w % 2) .. + 1)
+          const int kt = 2 * a + (w >> 1), r = 2 * (w & 1);
+          const float p0 = __builtin_amdgcn_exp2f(s[j][kt][r] - m_new), p1 = __builtin_amdgcn_exp2f(s[j][kt][r + 1] - m_new);
+          l_run[j] += p0;
+          l_run[j] += p1;
+          unsigned h2, l2;
+          split_pair(p0, p1, h2, l2);
+          hw[w] = h2;
+          lw[w] = l2;
         }
+        ph[j][a] = __builtin_bit_cast(v8h, hw);
+        pl[j][a] = __builtin_bit_cast(v8h, lw);
+      }
     }
 #pragma unroll
     for (int it = 0; it < NP; ++it) {

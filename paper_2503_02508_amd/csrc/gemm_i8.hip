@@ -213,7 +213,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
       if (m >= p.M || n >= p.N) continue;
       int8_t *dst = p.q_out + (long long)m * p.ldq + n;
       if (n + 16 <= p.N) {
-        *(v4i *)dst = *(const v4i *)(stage + r * SROW + cc);
+        // large launches: streaming stores (the tensor is far larger than the L2 and would only evict the operands)
+        if (FAST) __builtin_nontemporal_store(*(const v4i *)(stage + r * SROW + cc), (v4i *)dst);
+        else *(v4i *)dst = *(const v4i *)(stage + r * SROW + cc);
       } else {
         for (int e = 0; n + e < p.N; ++e) dst[e] = (int8_t)stage[r * SROW + cc + e];
       }
@@ -284,8 +286,12 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
           float *dst = (part == 0 ? p.q32 : p.k32) +
                        ((unsigned)(b_tile * p.heads + h) * (unsigned)T + (unsigned)(tb + cr)) * (unsigned)p.hd + (unsigned)e;
 #pragma unroll
-          for (int q = 0; q < BM * 32 / NT; ++q)
-            *(v4f *)(dst + (unsigned)(q * (NT / 32)) * (unsigned)p.hd) = *(const v4f *)(stage + (cr + q * (NT / 32)) * SR + cc);
+          for (int q = 0; q < BM * 32 / NT; ++q) {
+            const v4f v = *(const v4f *)(stage + (cr + q * (NT / 32)) * SR + cc);
+            v4f *d = (v4f *)(dst + (unsigned)(q * (NT / 32)) * (unsigned)p.hd);
+            if (FAST) __builtin_nontemporal_store(v, d);      // large launches: streaming stores
+            else *d = v;
+          }
         } else {
           // thread -> 4 consecutive token positions ch of the features fc, fc + NT / 32, ...
           const int fc = tid >> 5, ch = (tid & 31) * 4;
@@ -294,7 +300,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
             const int col = fc + q * (NT / 32);
             const int nn = n0h - 2 * D + col, h = nn / p.hd, e = nn - h * p.hd;
             const unsigned o = ((unsigned)(b_tile * p.heads + h) * (unsigned)p.DP + (unsigned)e) * (unsigned)p.Tp + (unsigned)(tb + ch);
-            *(v4f *)(p.vt32 + o) = *(const v4f *)(stage + col * VR + ch);
+            if (FAST) __builtin_nontemporal_store(*(const v4f *)(stage + col * VR + ch), (v4f *)(p.vt32 + o));
+            else *(v4f *)(p.vt32 + o) = *(const v4f *)(stage + col * VR + ch);
           }
         }
       }
@@ -436,7 +443,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
             for (int r = 0; r < 16; ++r) {
               const size_t er = e0 + (size_t)((i0 + ii) * 32 + (r >> 2) * 8 + (r & 3)) * p.N;
               const float v = dequant_f32(sc, acc[i0 + ii][j][r] - zw, bs);
-              stream_store((char *)p.cache_out + er * csz, loff, v, cache_bf16);
+              // the cached tensor is written once and read a step later: a streaming store keeps it out of the L2's way
+              if (!RBF) __builtin_nontemporal_store(v, (float *)((char *)p.cache_out + er * csz) + loff);
+              else stream_store((char *)p.cache_out + er * csz, loff, v, cache_bf16);
               stream_store((char *)p.x + er * xsz, loff, fmaf(g, v, xv[ii][r]), x_bf16);
             }
             __builtin_amdgcn_sched_barrier(0);                // one block's dequantised values live at a time

@@ -481,8 +481,12 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__re
   // |v / s - rint(v / s)| within tol of 1/2: 1.2e-5 steps + 4e-7 of the code's size at 256 keys is about ten times the
   // kernel's mean error there (its differing codes without this path, a few 1e-6 of all, put the mean error near 1e-6
   // steps); the sums grow with the number of keys and the bound with them
+  // The quotient of Eq. 1 is formed as v * (1 / s) here: that is within 2.5e-7 |v / s| of the correctly rounded
+  // quotient, so the two can only round to different integers inside the window below (whose relative part is widened
+  // by that much), where the float64 path, which divides, decides.
   const float tol_k = fmaxf(1.0f, (float)T * (1.0f / 256.0f));
-  const float tol_0 = 1.2e-5f * tol_k, tol_q = 4e-7f * tol_k;
+  const float tol_0 = 1.2e-5f * tol_k, tol_q = 4e-7f * tol_k + 2.5e-7f;
+  const float inv_qs = 1.0f / qs;
 #pragma unroll
   for (int j = 0; j < QB; ++j) {
     float l = l_run[j];
@@ -497,7 +501,7 @@ __global__ __launch_bounds__(256, 2) void attention_f16_kernel(const float *__re
       int c[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float qv = v[r] / qs, rr = rintf(qv);
+        const float qv = v[r] * inv_qs, rr = rintf(qv);
         c[r] = (int)fminf(fmaxf(rr + qz, -128.f), 127.f);
         if (q_row[j] < T && f + r < hd && fabsf(fabsf(qv - rr) - 0.5f) < fmaf(tol_q, fabsf(qv), tol_0)) {
           const int slot = atomicAdd(fix_cnt, 1);

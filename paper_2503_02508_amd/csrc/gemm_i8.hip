@@ -72,6 +72,13 @@ __device__ __forceinline__ float gelu_tanh(float v) {
   const float t = v * fmaf(c2, v * v, c1);
   return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
 }
+// the same divided by the quantiser step s: v / (s + s exp(-2u)), the step folded into the denominator
+__device__ __forceinline__ float gelu_tanh_over(float v, float s) {
+  const float c1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
+  const float c2 = c1 * 0.044715f;
+  const float t = v * fmaf(c2, v * v, c1);
+  return v * __builtin_amdgcn_rcpf(fmaf(s, __builtin_amdgcn_exp2f(t), s));
+}
 
 // Dequantised output of a quantised linear as it is stored: the float32 rounding of the float64 value
 // (a_s * w_s[n]) * (acc - a_z * wsum[n]) + bias[n] (the product of the two scales is exact in float64; one float64
@@ -172,7 +179,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float v = fmaf(sc[e], (float)(acc[i][j][rg * 4 + e] - zw[e]), bs[e]);
-            const float q = gelu_tanh(v) * o_inv;
+            const float q = gelu_tanh_over(v, o_s);
             const float r = __builtin_rintf(q);
             w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(r + o_zu, 0.0f, 255.0f), e, w);
             doubt[e] = fmaf(tol_v, fabsf(v), fabsf(q - r)) > doubt_at;

@@ -261,7 +261,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
           const double sc = (double)a_s * (double)w_scale[n0h + nl];
           const int zw = a_z * wsum[n0h + nl];
           const double bs = bias ? (double)bias[n0h + nl] : 0.0;
-          float *ycol = p.y ? p.y + (long long)m0 * p.ldy + n0h + nl : nullptr;     // 32 lanes write 128 contiguous bytes
+          // the optional row-major copy is not compiled into the large-M kernel (its launcher declines such launches)
+          float *ycol = (!FAST && p.y) ? p.y + (long long)m0 * p.ldy + n0h + nl : nullptr;     // 32 lanes write 128 contiguous bytes
 #pragma unroll
           for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -1045,7 +1046,7 @@ static bool use_big(const GemmArgs &a, int epi, int nz) {
   if (!a.Wt || nz != 1 || a.sel_D || a.acc_out) return false;
   if (a.K % 128 || a.N % 32 || a.lda % 16 || a.M % 128) return false;
   if (epi == EPI_RESID && a.rows_per_batch % 128) return false;
-  if (epi == EPI_QKV && (a.rows_per_batch % 128 || (a.N / 3) % 128 || a.hd % 4 || a.Tp % 8)) return false;
+  if (epi == EPI_QKV && (a.y || a.rows_per_batch % 128 || (a.N / 3) % 128 || a.hd % 4 || a.Tp % 8)) return false;
   const long long tiles = (long long)((a.M + 127) / 128) * ((a.N + 255) / 256);
   return tiles >= 384;
 }

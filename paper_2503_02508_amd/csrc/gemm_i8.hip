@@ -175,24 +175,27 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
           unsigned w = 0;
-          bool doubt[4];
+          float dist[4];                                      // distance from the rounding boundary plus the error bound
+          int corr[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float v = fmaf(sc[e], (float)(acc[i][j][rg * 4 + e] - zw[e]), bs[e]);
+            // the large-M kernel's accumulators already carry the zero-point term
+            corr[e] = FAST ? acc[i][j][rg * 4 + e] : acc[i][j][rg * 4 + e] - zw[e];
+            const float v = fmaf(sc[e], (float)corr[e], bs[e]);
             const float q = gelu_tanh_over(v, o_s);
             const float r = __builtin_rintf(q);
             w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(r + o_zu, 0.0f, 255.0f), e, w);
-            doubt[e] = fmaf(tol_v, fabsf(v), fabsf(q - r)) > doubt_at;
+            dist[e] = fmaf(tol_v, fabsf(v), fabsf(q - r));
           }
           w ^= 0x80808080u;
-          // one branch per four outputs; taken by a wavefront about once in a hundred times
-          if (doubt[0] | doubt[1] | doubt[2] | doubt[3]) {
+          // one comparison and one branch per four outputs; taken by a wavefront about once in a hundred times
+          if (fmaxf(fmaxf(dist[0], dist[1]), fmaxf(dist[2], dist[3])) > doubt_at) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (doubt[e]) {
+              if (dist[e] > doubt_at) {
                 const int slot = atomicAdd(fix_cnt, 1);
                 if (slot < GELU_FIX_CAP) {
-                  fix_ent[slot * 4 + 0] = acc[i][j][rg * 4 + e] - zw[e];
+                  fix_ent[slot * 4 + 0] = corr[e];
                   fix_ent[slot * 4 + 1] = nl + e;
                   fix_ent[slot * 4 + 2] = wm0 + i * 32 + (lane & 31);
                 }
@@ -921,12 +924,29 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_big_kernel(GemmArgs p) {
   };
 
   v16i acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
+  if constexpr (EPI == EPI_GELU_Q) {
+    // the accumulators start at minus the zero-point term a_z * wsum[n] of their column (the weights are the first
+    // MFMA operand here: register 4 rg + e of block j is column 32 j + 8 rg + 4 (lane / 32) + e), so the epilogue
+    // finds acc - a_z * wsum[n] ready; the loads complete under the prologue's wait for the first slabs
+    const int a_z = p.a_qp ? p.a_qp[0].z : p.a_zp;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0;
+      for (int rg = 0; rg < 4; ++rg) {
+        const v4i ws = *(const v4i *)(p.wsum + min(n0 + wn0 + j * 32 + rg * 8 + (lane >> 5) * 4, p.N - 4));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[i][j][rg * 4 + e] = -(a_z * ws[e]);
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[i][j][q] = 0;
+  }
 
   const int frow = lane & 31, fsw = (frow >> 2) & 3;
   v4i fa[2][TM];

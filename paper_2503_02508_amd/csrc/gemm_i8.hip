@@ -247,21 +247,6 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
       // the K loop) and leave as 16-byte stores along the contiguous direction of their layout (Q / K: features of a
       // token and head; V^T: tokens of a feature).
       const int tb = m0 - b_tile * T;                         // first token of the tile
-      if (FAST) {
-        // every wavefront dequantises its accumulators in place first (the registers then hold float32 bits), so the
-        // staging below, which only the wavefronts of one column half take part in at a time, is LDS traffic only
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int n = min(n0 + wn0 + j * 32 + (lane & 31), p.N - 1);
-          const double sc = (double)a_s * (double)w_scale[n];
-          const int zw = a_z * wsum[n];
-          const double bs = bias ? (double)bias[n] : 0.0;
-#pragma unroll
-          for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = __builtin_bit_cast(int, dequant_f32(sc, acc[i][j][r] - zw, bs));
-        }
-      }
 #pragma unroll
       for (int hn = 0; hn < BN / HN; ++hn) {
         const int n0h = n0 + hn * HN;                         // first column of this half
@@ -289,7 +274,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
               v4f v;
 #pragma unroll
               for (int q = 0; q < 4; ++q) {
-                v[q] = FAST ? __builtin_bit_cast(float, acc[i][j][rg * 4 + q]) : dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
+                v[q] = dequant_f32(sc, acc[i][j][rg * 4 + q] - zw, bs);
                 if (ycol) ycol[(unsigned)(ml + q) * (unsigned)p.ldy] = v[q];
               }
               if (part < 2) {

@@ -37,6 +37,26 @@ def code_flip_stats(got_codes, want_codes):
     return float(np.mean(d != 0)), int(d.max()) if d.size else 0
 
 
+def qkv_rows_from_heads(ctx, model, max_batch, B):
+    """The last QKV projection as a row-major [B * T, 3 D] device tensor, gathered from the head-major buffers the
+    attention kernel reads (Q and K [max_batch, H, T, d], V transposed [max_batch, H, dp, Tp] with the keys of each group
+    of 32 interleaved in units of 4).  Unlike the optional row-major copy this needs no extra output of the QKV GEMM,
+    so the launch under test is the one the sampler makes."""
+    import torch
+    H, T, D = model.heads, model.tokens, model.hidden
+    d = D // H
+    dp, Tp = (d + 15) // 16 * 16, (T + 63) // 64 * 64
+    n = max_batch * H * T * d
+    buf = ctx.workspace("qkv_heads", (2 * n + max_batch * H * dp * Tp,), torch.float32)
+    q = buf[:n].view(max_batch, H, T, d)[:B].permute(0, 2, 1, 3).reshape(B * T, D)
+    k = buf[n:2 * n].view(max_batch, H, T, d)[:B].permute(0, 2, 1, 3).reshape(B * T, D)
+    t = torch.arange(T, device=buf.device)
+    u = (t >> 2) & 7
+    pos = (t & ~31) | ((((u & 3) << 1) | (u >> 2)) << 2) | (t & 3)
+    v = buf[2 * n:].view(max_batch, H, dp, Tp)[:B, :, :d][:, :, :, pos].permute(0, 3, 1, 2).reshape(B * T, D)
+    return torch.cat([q, k, v], dim=1)
+
+
 def oracle_calibration(model, w, wl=None, lat=None, lab=None, t=None):
     """Activation parameters from the oracle's un-quantised forward."""
     if lat is None:

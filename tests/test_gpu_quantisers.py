@@ -19,7 +19,7 @@ import pytest
 
 from oracle import dit, quant, sampler
 from synthetic import dit_inputs as I
-from qc_testlib import make_pair, code_flip_stats, rel_rms, max_abs
+from qc_testlib import make_pair, code_flip_stats, rel_rms, max_abs, qkv_rows_from_heads
 
 pytestmark = pytest.mark.gpu
 
@@ -59,14 +59,19 @@ def test_each_fused_quantiser_alone(name, model, B, wb, std):
     cond = I.make_cond(B, model, seed + 2, std=0.5)
     qp, _ = sampler.calibrate_block(model, w, I.make_tokens(4, model, seed + 3), I.make_cond(4, model, seed + 4, std=0.5))
     lin, ctx = make_pair(model, w, qp, B)
-    ctx.keep_qkv_f32(True)
+    # large launches: Q | K | V are read back from the head-major buffers, so that the QKV GEMM runs without the optional
+    # row-major copy, i.e. through the large-M kernel as in the sampler; the small cases read that copy (and check it)
+    big = B * T >= 8192
+    ctx.keep_qkv_f32(not big)
     x = _cuda(tok)
     ctx.dit_block(0, qc.QC_FULL, x, _cuda(cond))
     torch.cuda.synchronize()
     M = B * T
     x_mid = x.cpu().numpy().astype(np.float64)                                   # device, fp32 values
     mod = ctx.workspace("mod", (ctx.max_batch if ctx.max_batch > 512 else 512, 6 * D), torch.float32).cpu().numpy()[:B].astype(np.float64)
-    qkv_dev = ctx.workspace("qkv", (M, 3 * D), torch.float32).cpu().numpy().astype(np.float64)
+    qkv_heads = qkv_rows_from_heads(ctx, model, B, B).cpu().numpy().astype(np.float64)
+    qkv_dev = qkv_heads if big else ctx.workspace("qkv", (M, 3 * D), torch.float32).cpu().numpy().astype(np.float64)
+    assert np.array_equal(qkv_dev, qkv_heads), "the head-major Q | K | V differ from the row-major copy"
     c_attn = ctx.workspace("qact_attn", (M, D), torch.int8).cpu().numpy()
     c_ln2 = ctx.workspace("qact_ln", (M, D), torch.int8).cpu().numpy()
     c_gelu = ctx.workspace("qact_mlp", (M, R), torch.int8).cpu().numpy()
@@ -159,7 +164,6 @@ def test_large_m_linears_every_tile_at_32768_rows(wb):
     cond = I.make_cond(B, model, seed + 2, std=0.5)
     qp, _ = sampler.calibrate_block(model, w, I.make_tokens(4, model, seed + 3), I.make_cond(4, model, seed + 4, std=0.5))
     lin, ctx = make_pair(model, w, qp, B)
-    ctx.keep_qkv_f32(True)
     M = B * T
     rows = (np.arange(M // 128)[:, None] * 128 + np.array([5, 44, 83, 122])[None]).reshape(-1)
     rows_t = torch.from_numpy(rows).cuda()
@@ -172,7 +176,7 @@ def test_large_m_linears_every_tile_at_32768_rows(wb):
         ctx.dit_block(0, qc.QC_FULL, x, cond_d)
         torch.cuda.synchronize()
         return dict(x=x.reshape(M, D),
-                    qkv=ctx.workspace("qkv", (M, 3 * D), torch.float32).clone(),
+                    qkv=qkv_rows_from_heads(ctx, model, B, B),      # from the head-major buffers: no row-major copy is asked for, so the large-M kernel runs
                     c_attn=ctx.workspace("qact_attn", (M, D), torch.int8).clone(),
                     c_ln2=ctx.workspace("qact_ln", (M, D), torch.int8).clone(),
                     c_gelu=ctx.workspace("qact_mlp", (M, R), torch.int8).clone(),

@@ -1061,14 +1061,17 @@ static hipError_t launch_big(const GemmArgs &a, hipStream_t st) {
 
 // The large-M kernel takes over when the weights exist in fragment order, the shape fits its loop (K a multiple of
 // 128, N of 32, 16-byte aligned rows), every 128-row tile is whole and inside one batch element (its epilogues are
-// compiled without the general paths) and its 128 x 256 tiles fill the chip's 512 workgroup slots.
+// compiled without the general paths) and the launch has enough 128 x 256 tiles for it to pay.
 static bool use_big(const GemmArgs &a, int epi, int nz) {
   if (!a.Wt || nz != 1 || a.sel_D || a.acc_out) return false;
   if (a.K % 128 || a.N % 32 || a.lda % 16 || a.M % 128) return false;
   if (epi == EPI_RESID && a.rows_per_batch % 128) return false;
   if (epi == EPI_QKV && (a.y || a.rows_per_batch % 128 || (a.N / 3) % 128 || a.hd % 4 || a.Tp % 8)) return false;
   const long long tiles = (long long)((a.M + 127) / 128) * ((a.N + 255) / 256);
-  return tiles >= 384;
+  // measured alone on the chip (DiT-XL/2 shapes): 160 tiles (proj / fc2 at M = 4096) run 20 % faster here than in the
+  // tile kernel, 224 - 288 tiles (QKV / fc1 at M = 2048) 0 - 10 % faster, 112 - 144 tiles (M = 1024) 3 - 15 % slower,
+  // 80 tiles (proj / fc2 at M = 2048) 15 - 25 % slower
+  return tiles >= 150;
 }
 
 template <int BM, int BN, int WM, int WN, int EPI, int TAG, bool W4, int PF, int BK = 128, bool RBF = false>

@@ -383,6 +383,16 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
         if (n0h >= p.N) break;
         const bool mine = wn0 / HN == hn;               // this wavefront's columns lie in the half
         if (hn) __syncthreads();                        // the previous half has left the staging area
+        const v4f gv = *(const v4f *)(p.gate + (long long)b_uniform * p.ld_gate + n0h + cc);
+        const size_t ob4 = ((size_t)m0 * p.N + n0h + cc) >> 2;      // in groups of four elements
+        const size_t row4 = (size_t)p.N >> 2;
+        // a bfloat16 stream: the thread's 16 pieces of x (8 bytes each) are requested before the staging, which hides
+        // their latency (a float32 stream would take twice the registers: its loads stay in the loop below)
+        uint2 xraw[RQ];
+        if (x_bf16) {
+#pragma unroll
+          for (int q = 0; q < RQ; ++q) xraw[q] = ((const uint2 *)p.x)[ob4 + (size_t)(cr + q * (NT / 32)) * row4];
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           if (!mine) continue;
@@ -399,15 +409,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &p, v16i (&acc)[BM 
           }
         }
         __syncthreads();
-        const v4f gv = *(const v4f *)(p.gate + (long long)b_uniform * p.ld_gate + n0h + cc);
-        const size_t ob4 = ((size_t)m0 * p.N + n0h + cc) >> 2;      // in groups of four elements
-        const size_t row4 = (size_t)p.N >> 2;
 #pragma unroll 4
         for (int q = 0; q < RQ; ++q) {
           const int row = cr + q * (NT / 32);
           const v4f v = *(const v4f *)(stage + row * SR + cc);
           const size_t o4 = ob4 + (size_t)row * row4;
-          const float4 xo = stream_load4(p.x, o4, x_bf16);
+          float4 xo;
+          if (x_bf16) {
+            xo = make_float4(__builtin_bit_cast(float, xraw[q].x << 16), __builtin_bit_cast(float, xraw[q].x & 0xFFFF0000u),
+                             __builtin_bit_cast(float, xraw[q].y << 16), __builtin_bit_cast(float, xraw[q].y & 0xFFFF0000u));
+          } else {
+            xo = stream_load4(p.x, o4, 0);
+          }
           stream_store4(p.cache_out, o4, make_float4(v.x, v.y, v.z, v.w), cache_bf16);
           stream_store4(p.x, o4, make_float4(fmaf(gv.x, v.x, xo.x), fmaf(gv.y, v.y, xo.y), fmaf(gv.z, v.z, xo.z), fmaf(gv.w, v.w, xo.w)),
                         x_bf16);

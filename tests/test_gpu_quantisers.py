@@ -39,6 +39,10 @@ def _signed_codes(x, s, z):
     ("xl_256", I.DIT_XL2_256, 2, 8, 0.02),
     ("xl_256_w4", I.DIT_XL2_256, 2, 4, 0.02),
     # M = 12288 rows: all four linears take the large-M GEMM kernel (fragment-ordered weights)
+    # M = 2048 and 4096 rows: launches on both sides of the tile count from which the large-M kernel takes over
+    # (M = 2048: QKV and fc1 large-M, proj and fc2 tile kernel; M = 4096: all four large-M)
+    ("xl_256_m2048", I.DIT_XL2_256, 8, 8, 0.02),
+    ("xl_256_m4096_w4", I.DIT_XL2_256, 16, 4, 0.02),
     ("xl_256_large_m", I.DIT_XL2_256, 48, 8, 0.02),
     ("xl_256_large_m_w4", I.DIT_XL2_256, 48, 4, 0.02),
     ("ragged", I.ModelDesc(depth=1, hidden=80, heads=4, mlp_dim=176, patch=1, latent_c=3, latent_h=5, latent_w=7,
@@ -61,7 +65,7 @@ def test_each_fused_quantiser_alone(name, model, B, wb, std):
     lin, ctx = make_pair(model, w, qp, B)
     # large launches: Q | K | V are read back from the head-major buffers, so that the QKV GEMM runs without the optional
     # row-major copy, i.e. through the large-M kernel as in the sampler; the small cases read that copy (and check it)
-    big = B * T >= 8192
+    big = B * T >= 2048
     ctx.keep_qkv_f32(not big)
     x = _cuda(tok)
     ctx.dit_block(0, qc.QC_FULL, x, _cuda(cond))

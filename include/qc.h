@@ -247,7 +247,9 @@ int qc_workspace_ptr(qc_ctx *ctx, int which, void **ptr_out, size_t *bytes_out);
 int qc_set_cache_mask(qc_ctx *ctx, const unsigned char *mask, int steps);
 
 /* Inspection aid: when on, full blocks also write the QKV projection row-major into the
- * QC_WS_QKV buffer (the attention kernel itself reads head-major copies of the same fp32 values). */
+ * QC_WS_QKV buffer (the attention kernel itself reads head-major copies of the same fp32 values).
+ * Only the general GEMM kernel writes that copy: while it is on, large QKV launches do not take the
+ * large-M kernel (same values, slower); QC_WS_QKV_HEADS can be read without it. */
 int qc_keep_qkv_f32(qc_ctx *ctx, int on);
 
 /* Class labels live in device memory, so the entry points that take them (qc_denoise, qc_sample_step,
